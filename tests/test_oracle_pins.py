@@ -1,0 +1,454 @@
+"""Pins for the CPU oracle: it is checked against what the paper and the mathematics fix,
+never against itself and never against the HIP path.  CPU only.
+
+Each test names the passage it pins and the kind of mistake it would catch.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2310_01777_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_qkv(B, H, T, d, seed, std=1.0):
+    g = np.random.default_rng(seed)
+    return [g.standard_normal((B, H, T, d)) * std for _ in range(3)]
+
+
+# ----------------------------------------------------------------------------------------------
+# integer helpers -- Sec. 3.1 "Linear Sparse Attention Mask Generation", App. A.5.3
+# ----------------------------------------------------------------------------------------------
+
+def test_k_hat_formula_golden():
+    with open(os.path.join(GOLDEN, "k_hat_cases.txt")) as f:
+        rows = [ln.split("#")[0].split() for ln in f if ln.split("#")[0].strip()]
+    assert len(rows) >= 8
+    for k, K, T, want in rows:
+        assert oracle.k_hat_from_k(int(k), int(K), int(T)) == int(want), (k, K, T)
+
+
+def test_round8_matches_library_bf16_cast():
+    """The reduced-precision rounding point is bf16 round-to-nearest-even (library cast)."""
+    g = np.random.default_rng(0)
+    x = np.concatenate([g.standard_normal(4000) * 10.0 ** g.integers(-20, 20, 4000),
+                        [1.00390625, 1.01171875, 3.0, 255.5, 256.5, 0.0, -1.00390625]])
+    x = x.astype(np.float32)  # representable inputs so the library sees the same number
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    got = np.array([oracle.round8(float(v)) for v in x])
+    assert np.array_equal(got, want)
+
+
+# ----------------------------------------------------------------------------------------------
+# a5 expansion
+# ----------------------------------------------------------------------------------------------
+
+def _onehot_rows(p, selected_cols):
+    """A_hat whose row t puts descending mass on selected_cols[t] (so they are the top-k^)."""
+    A = np.zeros((p.B, p.H, p.T, p.K))
+    for t, cols in enumerate(selected_cols):
+        for rank, c in enumerate(cols):
+            A[..., t, c] = 1.0 - 0.01 * rank
+    return A
+
+
+def test_expansion_hand_enumerated_T8_K4():
+    """T=8, K=4: column c covers keys {2c, 2c+1}.  Hand-written expected lists."""
+    p = oracle.Params(B=1, H=1, T=8, d=4, m=4, K=4, k_hat=2, k_budget=0, causal=False)
+    chosen = [[0, 3], [1, 2], [3, 0], [2, 1], [0, 1], [2, 3], [1, 3], [0, 2]]
+    sel, idx, cnt = oracle.topk_mask(p, _onehot_rows(p, chosen))
+    want_idx = [[0, 1, 6, 7], [2, 3, 4, 5], [0, 1, 6, 7], [2, 3, 4, 5],
+                [0, 1, 2, 3], [4, 5, 6, 7], [2, 3, 6, 7], [0, 1, 4, 5]]
+    assert idx[0, 0].tolist() == want_idx
+    assert cnt[0, 0].tolist() == [4] * 8
+    assert sel[0, 0].tolist() == [sorted(c) for c in chosen]
+
+    # causal: keys j > t are dropped; columns past the diagonal are never candidates
+    pc = oracle.Params(B=1, H=1, T=8, d=4, m=4, K=4, k_hat=2, k_budget=0, causal=True)
+    A = np.tile(np.array([0.1, 0.2, 0.3, 0.4]), (1, 1, 8, 1))  # later columns score higher
+    sel, idx, cnt = oracle.topk_mask(pc, A)
+    want = [
+        ([0, -1], [0, -1, -1, -1], 1),       # t=0: only column 0, only key 0
+        ([0, -1], [0, 1, -1, -1], 2),        # t=1
+        ([0, 1], [0, 1, 2, -1], 3),          # t=2: columns 0,1; key 3 is in the future
+        ([0, 1], [0, 1, 2, 3], 4),
+        ([1, 2], [2, 3, 4, -1], 3),          # t=4: candidates 0..2, best two are 1,2
+        ([1, 2], [2, 3, 4, 5], 4),
+        ([2, 3], [4, 5, 6, -1], 3),
+        ([2, 3], [4, 5, 6, 7], 4),
+    ]
+    for t, (s, i, c) in enumerate(want):
+        assert sel[0, 0, t].tolist() == s, t
+        assert idx[0, 0, t].tolist() == i, t
+        assert cnt[0, 0, t] == c, t
+
+
+@pytest.mark.parametrize("T,K", [(64, 8), (60, 7), (37, 5), (16, 16), (128, 3)])
+def test_expansion_equals_library_nearest_resize(T, K):
+    """k_budget=0: M* is the nearest-neighbour resize of the T x K mask to T x T (library op)."""
+    g = np.random.default_rng(T * 100 + K)
+    k_hat = max(1, K // 2)
+    p = oracle.Params(B=1, H=2, T=T, d=4, m=4, K=K, k_hat=k_hat, k_budget=0, causal=False)
+    A = g.random((1, 2, T, K))
+    sel, idx, cnt = oracle.topk_mask(p, A)
+    for h in range(2):
+        Mhat = np.zeros((T, K), dtype=np.float32)
+        for t in range(T):
+            Mhat[t, sel[0, h, t][sel[0, h, t] >= 0]] = 1.0
+        # resize the key axis K -> T, query axis untouched.  torch 'nearest' maps dst -> floor(dst*K/T)
+        # in float; use the exact integer gather for widths where float rounding could matter.
+        src = (np.arange(T) * K) // T
+        Mstar_lib = torch.nn.functional.interpolate(
+            torch.from_numpy(Mhat)[None, None], size=(T, T), mode="nearest")[0, 0].numpy()
+        Mstar_int = Mhat[:, src]
+        if T % K == 0:
+            assert np.array_equal(Mstar_lib, Mstar_int)
+        got = np.zeros((T, T), dtype=np.float32)
+        for t in range(T):
+            js = idx[0, h, t, :cnt[0, h, t]]
+            assert np.all(np.diff(js) > 0)           # ascending, unique
+            got[t, js] = 1.0
+            assert np.all(idx[0, h, t, cnt[0, h, t]:] == -1)
+        assert np.array_equal(got, Mstar_int)
+
+
+def test_replication_cap_k_star():
+    """k^ = 1 with budget k emits k* = min(k, ceil(T/K)) evenly spaced keys (App. A.5.3)."""
+    T, K = 1024, 8       # width 128
+    for k in (1, 5, 16, 128, 500):
+        p = oracle.Params(B=1, H=1, T=T, d=4, m=4, K=K, k_hat=1, k_budget=k, causal=False)
+        A = np.zeros((1, 1, T, K)); A[..., 3] = 1.0
+        _, idx, cnt = oracle.topk_mask(p, A)
+        kstar = min(k, -(-T // K))
+        assert np.all(cnt == kstar)
+        js = idx[0, 0, 17, :kstar]
+        assert js[0] == 3 * 128 and js[-1] < 4 * 128
+        gaps = np.diff(js)
+        if kstar > 1:
+            assert gaps.max() - gaps.min() <= 1          # uniform spacing
+            assert gaps.min() >= 128 // kstar              # spread over the whole block,
+            assert js[-1] >= 4 * 128 - -(-128 // kstar)    # not the first k* keys of it
+        assert oracle.row_stride(p) == kstar
+        if k == 5:   # hand-evaluated: 384 + floor(i * 128 / 5)
+            assert js.tolist() == [384, 409, 435, 460, 486]
+
+
+def test_nnz_is_linear_in_T():
+    """Sum of cnt ~ T * k for fixed k (App. A.5.3: constant number of non-zeros T*k)."""
+    K, k = 16, 32
+    tot = []
+    for T in (256, 512, 1024):
+        kh = oracle.k_hat_from_k(k, K, T)
+        p = oracle.Params(B=1, H=1, T=T, d=4, m=4, K=K, k_hat=kh, k_budget=k, causal=False)
+        A = np.random.default_rng(T).random((1, 1, T, K))
+        _, _, cnt = oracle.topk_mask(p, A)
+        assert cnt.max() <= oracle.row_stride(p) <= k
+        tot.append(cnt.sum() / T)
+    assert max(tot) <= k and min(tot) >= k / 2
+
+
+# ----------------------------------------------------------------------------------------------
+# a4 selection
+# ----------------------------------------------------------------------------------------------
+
+def test_topk_equals_full_sort_and_tie_rule():
+    g = np.random.default_rng(5)
+    T, K, kh = 96, 24, 7
+    for causal in (False, True):
+        p = oracle.Params(B=1, H=3, T=T, d=4, m=4, K=K, k_hat=kh, causal=causal)
+        A = g.random((1, 3, T, K))
+        A[0, 1] = np.round(A[0, 1] * 4) / 4           # plant many exact duplicates
+        A[0, 2, :, :] = 0.5                            # all equal: lowest columns must win
+        sel, _, _ = oracle.topk_mask(p, A)
+        for h in range(3):
+            for t in range(T):
+                ncand = (t * K) // T + 1 if causal else K
+                n = min(kh, ncand)
+                # stable sort by descending value => lower column first among equals
+                order = np.argsort(-A[0, h, t, :ncand], kind="stable")[:n]
+                assert sel[0, h, t, :n].tolist() == sorted(order.tolist()), (causal, h, t)
+                assert np.all(sel[0, h, t, n:] == -1)
+                chosen = set(order.tolist())
+                rest = [A[0, h, t, c] for c in range(ncand) if c not in chosen]
+                if rest:
+                    assert min(A[0, h, t, c] for c in chosen) >= max(rest)
+
+
+# ----------------------------------------------------------------------------------------------
+# a6 sparse attention: reduces to dense softmax attention when every key is kept
+# ----------------------------------------------------------------------------------------------
+
+def _dense_attention(Q, K, V, scale, causal, seq_len=None):
+    """Textbook softmax attention with library softmax, fp64."""
+    Q, K, V = (torch.from_numpy(np.asarray(x, dtype=np.float64)) for x in (Q, K, V))
+    B, H, T, d = Q.shape
+    S = scale * Q @ K.transpose(-1, -2)
+    keep = torch.ones(B, 1, T, T, dtype=torch.bool)
+    if causal:
+        keep &= torch.tril(torch.ones(T, T, dtype=torch.bool))
+    if seq_len is not None:
+        ar = torch.arange(T)
+        valid = ar[None, :] < torch.as_tensor(seq_len)[:, None]
+        keep &= valid[:, None, None, :]
+    S = S.masked_fill(~keep, float("-inf"))
+    O = torch.softmax(S, -1) @ V
+    if seq_len is not None:
+        O = O * valid[:, None, :, None]
+    return O.numpy()
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("T,K", [(48, 12), (50, 7), (32, 32)])
+def test_full_selection_is_dense_attention(causal, T, K):
+    """k^ = K and no budget: the listed keys are all admissible keys, so the output is exact
+    (causal / padded) softmax attention.  Also covers K = T (one key per column)."""
+    B, H, d, m = 2, 2, 8, 16
+    Q, Kk, V = _rand_qkv(B, H, T, d, seed=T + K)
+    W = synth.gaussian_orthogonal(m, d, 0).numpy()
+    seq_len = np.array([T, T - 5], dtype=np.int32)
+    p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=K, k_hat=K, k_budget=0, causal=causal, scale=0.3)
+    out = oracle.forward(p, Q, Kk, V, W, seq_len=seq_len)
+    want = _dense_attention(Q, Kk, V, 0.3, causal, seq_len)
+    np.testing.assert_allclose(out["O"], want, rtol=1e-12, atol=1e-13)
+    # the list itself: every admissible key, ascending
+    for b in range(B):
+        for t in range(T):
+            n = 0 if t >= seq_len[b] else (min(t, seq_len[b] - 1) + 1 if causal else seq_len[b])
+            assert out["cnt"][b, 0, t] == n
+            assert out["idx"][b, 0, t, :n].tolist() == list(range(n))
+
+
+def test_sparse_softmax_rows_sum_to_one():
+    """With V = 1 the output is the row sum of the sparse probabilities, which must be 1
+    (Sec. 3.1.1: after sigma each row of A* sums to 1)."""
+    B, H, T, d, m, K = 1, 2, 64, 8, 16, 16
+    Q, Kk, _ = _rand_qkv(B, H, T, d, seed=3)
+    V = np.ones((B, H, T, d))
+    W = synth.gaussian_orthogonal(m, d, 0).numpy()
+    p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=K, k_hat=3, causal=True, scale=0.35)
+    out = oracle.forward(p, Q, Kk, V, W)
+    np.testing.assert_allclose(out["O"], 1.0, rtol=0, atol=1e-13)
+
+
+def test_sparse_attention_brute_force_dense_mask():
+    """Tiny T: build the dense T x T mask from idx, run masked dense softmax (excluded keys get
+    -inf, not logit 0) with library ops, compare."""
+    B, H, T, d, m, K, kh = 1, 2, 16, 4, 8, 4, 2
+    Q, Kk, V = _rand_qkv(B, H, T, d, seed=11)
+    W = synth.gaussian_orthogonal(m, d, 0).numpy()
+    for causal in (False, True):
+        p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=K, k_hat=kh, causal=causal, scale=0.5)
+        out = oracle.forward(p, Q, Kk, V, W)
+        M = np.zeros((B, H, T, T), dtype=bool)
+        for h in range(H):
+            for t in range(T):
+                M[0, h, t, out["idx"][0, h, t, :out["cnt"][0, h, t]]] = True
+        S = 0.5 * torch.from_numpy(Q) @ torch.from_numpy(Kk).transpose(-1, -2)
+        S = S.masked_fill(~torch.from_numpy(M), float("-inf"))
+        want = (torch.softmax(S, -1) @ torch.from_numpy(V)).numpy()
+        np.testing.assert_allclose(out["O"], want, rtol=1e-12, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------------------------
+# a1-a3 estimate
+# ----------------------------------------------------------------------------------------------
+
+def _exact_bucketed_softmax(Q, K, scale, Kc, causal, seq_len=None):
+    """Bucket sums of the exact softmax matrix: softmax(scale QK^T) @ V_I with V_I the one-hot
+    T x Kc nearest-neighbour stretch of the identity (built with the library resize when Kc | T)."""
+    Q, K = torch.from_numpy(np.asarray(Q, np.float64)), torch.from_numpy(np.asarray(K, np.float64))
+    B, H, T, d = Q.shape
+    S = scale * Q @ K.transpose(-1, -2)
+    keep = torch.ones(B, 1, T, T, dtype=torch.bool)
+    if causal:
+        keep &= torch.tril(torch.ones(T, T, dtype=torch.bool))
+    if seq_len is not None:
+        valid = torch.arange(T)[None, :] < torch.as_tensor(seq_len)[:, None]
+        keep &= valid[:, None, None, :]
+    A = torch.softmax(S.masked_fill(~keep, float("-inf")), -1)
+    if T % Kc == 0:
+        VI = torch.nn.functional.interpolate(torch.eye(Kc, dtype=torch.float64)[None, None],
+                                             size=(T, Kc), mode="nearest")[0, 0]
+    else:
+        VI = torch.zeros(T, Kc, dtype=torch.float64)
+        VI[torch.arange(T), (torch.arange(T) * Kc) // T] = 1.0
+    return (A @ VI).numpy()
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_estimate_converges_to_exact_softmax_buckets(causal):
+    """As m grows the estimate tends to the bucket sums of exact softmax(scale QK^T), error
+    ~ m^-1/2 (unbiased positive random features).  A dropped norm term on the key side, a wrong
+    sign, a transposed projection or a wrong bucket map all break the limit."""
+    B, H, T, d, Kc = 1, 2, 32, 8, 8
+    Q, K, _ = _rand_qkv(B, H, T, d, seed=21, std=0.4)
+    exact = _exact_bucketed_softmax(Q, K, 0.5, Kc, causal)
+    errs = []
+    for m in (256, 4096, 65536):
+        W = np.random.default_rng(m).standard_normal((m, d))
+        p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=Kc, k_hat=2, causal=causal, scale=0.5)
+        A = oracle.estimate(p, Q, K, W)
+        np.testing.assert_allclose(A.sum(-1), 1.0, atol=1e-12)
+        assert A.min() >= 0.0
+        errs.append(np.abs(A - exact).max())
+    # dropping the key-side norm term moves the limit by ~0.04 here, far outside this bound
+    assert errs[2] < 0.006, errs
+    assert errs[2] < errs[0] / 3, errs        # 256x more features: ~16x smaller error expected
+
+
+def test_estimate_K_equals_T_is_softmax_matrix():
+    """K = T: V_I is the identity and the estimate approximates the attention matrix itself."""
+    B, H, T, d, m = 1, 1, 16, 6, 65536
+    Q, K, _ = _rand_qkv(B, H, T, d, seed=33, std=0.4)
+    W = np.random.default_rng(1).standard_normal((m, d))
+    p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=T, k_hat=2, causal=True, scale=0.6)
+    A = oracle.estimate(p, Q, K, W)
+    exact = _exact_bucketed_softmax(Q, K, 0.6, T, True)
+    assert np.abs(A - exact).max() < 0.01
+    assert np.all(np.triu(A[0, 0], 1) == 0.0)            # causal zeros above the diagonal
+
+
+@pytest.mark.parametrize("T,K", [(24, 6), (23, 5)])
+def test_estimate_closed_form_zero_inputs(T, K):
+    """Q = K = 0: every feature is 1, so A_hat[t,c] = (#admissible keys in column c) / (#admissible
+    keys).  Catches bucket-boundary and causal off-by-one mistakes exactly."""
+    B, H, d, m = 2, 1, 4, 8
+    Z = np.zeros((B, H, T, d))
+    W = np.random.default_rng(2).standard_normal((m, d))
+    seq_len = np.array([T, T - 4], dtype=np.int32)
+    for causal in (False, True):
+        p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=K, k_hat=1, causal=causal)
+        A = oracle.estimate(p, Z, Z, W, seq_len=seq_len)
+        for b in range(B):
+            for t in range(T):
+                if t >= seq_len[b]:
+                    assert np.all(A[b, 0, t] == 0.0)
+                    continue
+                jmax = min(t, seq_len[b] - 1) if causal else seq_len[b] - 1
+                counts = np.bincount((np.arange(jmax + 1) * K) // T, minlength=K)
+                np.testing.assert_allclose(A[b, 0, t], counts / counts.sum(), atol=1e-14)
+
+
+def test_estimate_literal_favor_with_stretched_identity():
+    """The paper's literal form phi(Q) (phi(K)^T V_I), V_I = library nearest-neighbour resize of
+    I_K, evaluated with matmuls through the T x T kernel matrix (a different association than
+    the oracle's bucket sums)."""
+    B, H, T, d, m, Kc = 1, 2, 24, 6, 32, 6
+    Q, K, _ = _rand_qkv(B, H, T, d, seed=8, std=0.8)
+    W = synth.gaussian_orthogonal(m, d, 3).numpy().astype(np.float64)
+    scale = 0.4
+    VI = torch.nn.functional.interpolate(torch.eye(Kc, dtype=torch.float64)[None, None],
+                                         size=(T, Kc), mode="nearest")[0, 0].numpy()
+    for causal in (False, True):
+        p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=Kc, k_hat=2, causal=causal, scale=scale)
+        A = oracle.estimate(p, Q, K, W)
+        for h in range(H):
+            x, y = np.sqrt(scale) * Q[0, h], np.sqrt(scale) * K[0, h]
+            fq = np.exp(x @ W.T - 0.5 * (x * x).sum(-1, keepdims=True))
+            fk = np.exp(y @ W.T - 0.5 * (y * y).sum(-1, keepdims=True))
+            G = fq @ fk.T                                  # T x T kernel estimate
+            if causal:
+                G = np.tril(G)
+            raw = G @ VI
+            np.testing.assert_allclose(A[0, h], raw / raw.sum(-1, keepdims=True), rtol=1e-11)
+
+
+def test_selection_invariant_to_row_scaling_of_queries_features():
+    """A positive per-row factor on phi(Q) (e.g. any stabiliser) cancels in the normaliser:
+    scaling q_t changes |x|^2 but A_hat rows still sum to one and the oracle's power-of-two row
+    shift leaves results unchanged when W x is unchanged.  Checked via two equivalent inputs:
+    adding to q a vector orthogonal to every w_i changes only |x|^2."""
+    B, H, T, d, m, Kc = 1, 1, 20, 8, 4, 5
+    Q, K, _ = _rand_qkv(B, H, T, d, seed=4, std=0.7)
+    W = np.random.default_rng(9).standard_normal((m, d))
+    # vector in the null space of W (m < d)
+    _, _, vt = np.linalg.svd(W)
+    nvec = vt[-1]
+    Q2 = Q + 3.0 * nvec
+    p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=Kc, k_hat=2, causal=True, scale=0.5)
+    A1, A2 = oracle.estimate(p, Q, K, W), oracle.estimate(p, Q2, K, W)
+    np.testing.assert_allclose(A1, A2, rtol=1e-9, atol=1e-15)
+
+
+# ----------------------------------------------------------------------------------------------
+# whole path: causality and padding invariances, row subsets
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("round8", [False, True])
+def test_causality_bit_exact(round8):
+    """Causal mode: changing Q, K, V at positions > t0 leaves rows <= t0 bit-identical."""
+    B, H, T, d, m, Kc, kh = 1, 2, 40, 8, 16, 8, 3
+    Q, K, V = _rand_qkv(B, H, T, d, seed=6)
+    W = synth.gaussian_orthogonal(m, d, 0).numpy()
+    p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=Kc, k_hat=kh, causal=True, scale=0.35,
+                      round8=round8)
+    a = oracle.forward(p, Q, K, V, W)
+    t0 = 22
+    g = np.random.default_rng(0)
+    Q2, K2, V2 = Q.copy(), K.copy(), V.copy()
+    for X in (Q2, K2, V2):
+        X[:, :, t0 + 1:] = g.standard_normal(X[:, :, t0 + 1:].shape) * 3
+    b = oracle.forward(p, Q2, K2, V2, W)
+    for key in ("O", "A_hat", "sel", "idx", "cnt"):
+        assert np.array_equal(a[key][:, :, :t0 + 1], b[key][:, :, :t0 + 1]), key
+    assert not np.array_equal(a["O"][:, :, t0 + 1:], b["O"][:, :, t0 + 1:])
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_padding_invariance(causal):
+    """Positions >= seq_len[b] are inert: overwriting them changes nothing; padded rows are zero
+    with cnt = 0; seq_len = T equals the unpadded run."""
+    B, H, T, d, m, Kc, kh = 2, 2, 36, 8, 16, 6, 2
+    Q, K, V = _rand_qkv(B, H, T, d, seed=7)
+    W = synth.gaussian_orthogonal(m, d, 0).numpy()
+    p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=Kc, k_hat=kh, causal=causal, scale=0.35)
+    seq_len = np.array([T, 25], dtype=np.int32)
+    a = oracle.forward(p, Q, K, V, W, seq_len=seq_len)
+    Q2, K2, V2 = Q.copy(), K.copy(), V.copy()
+    for X in (Q2, K2, V2):
+        X[1, :, 25:] = 99.0
+    b = oracle.forward(p, Q2, K2, V2, W, seq_len=seq_len)
+    for key in ("O", "A_hat", "sel", "idx", "cnt"):
+        assert np.array_equal(a[key], b[key]), key
+    assert np.all(a["O"][1, :, 25:] == 0) and np.all(a["cnt"][1, :, 25:] == 0)
+    assert np.all(a["A_hat"][1, :, 25:] == 0) and np.all(a["idx"][1, :, :25] < 25)
+    full = oracle.forward(p, Q, K, V, W, seq_len=np.array([T, T], dtype=np.int32))
+    none = oracle.forward(p, Q, K, V, W)
+    for key in ("O", "A_hat", "sel", "idx", "cnt"):
+        assert np.array_equal(full[key], none[key]), key
+
+
+def test_row_subset_matches_full_run():
+    """The sampled-rows entry (used for full-size checks) returns exactly the full run's rows."""
+    B, H, T, d, m, Kc, kh = 1, 2, 64, 8, 16, 8, 3
+    Q, K, V = _rand_qkv(B, H, T, d, seed=12)
+    W = synth.gaussian_orthogonal(m, d, 0).numpy()
+    p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=Kc, k_hat=kh, causal=True, scale=0.35, round8=True)
+    full = oracle.forward(p, Q, K, V, W)
+    rows = np.array([0, 1, 7, 8, 31, 63], dtype=np.int32)
+    sub = oracle.forward(p, Q, K, V, W, rows=rows)
+    for key in ("O", "A_hat", "sel", "idx", "cnt"):
+        assert np.array_equal(full[key][:, :, rows], sub[key]), key
+
+
+def test_forward_stage_composition_and_threads():
+    """forward == estimate -> topk_mask -> sparse_attn, for any thread count and head range."""
+    wl = synth.Workload("tiny", 2, 3, 64, 16, 32, 8, 3, 0, True, "bf16", 4)
+    x = synth.make_inputs(wl)
+    Q, K, V, W = (x[k].to(torch.float64).numpy() for k in "QKVW")
+    p = oracle.Params(B=2, H=3, T=64, d=16, m=32, K=8, k_hat=3, causal=True, scale=0.25, round8=True)
+    A = oracle.estimate(p, Q, K, W)
+    sel, idx, cnt = oracle.topk_mask(p, A)
+    O = oracle.sparse_attn(p, Q, K, V, idx, cnt)
+    for nt in (1, 3):
+        f = oracle.forward(p, Q, K, V, W, n_threads=nt)
+        assert f["threads"] == nt
+        assert np.array_equal(f["O"], O) and np.array_equal(f["idx"], idx)
+        assert np.array_equal(f["A_hat"], A) and np.array_equal(f["sel"], sel)
+    part = oracle.forward(p, Q, K, V, W, heads=(2, 4))
+    assert np.array_equal(part["O"].reshape(6, 64, 16)[2:4], O.reshape(6, 64, 16)[2:4])
+    assert np.all(part["O"].reshape(6, 64, 16)[:2] == 0)
