@@ -1,0 +1,151 @@
+#!/usr/bin/env python3
+"""Benchmark of the SEA attention forward pass on one MI355X.
+
+A step is one sea_forward call (feature maps, key-side state, estimate contraction, per-row
+top-k^ + mask expansion, sparse attention) over one batch of synthetic Q, K, V already resident
+in HBM.  Prints ONE JSON line: tokens/s per attention layer, the roofline figure of the dominant
+kernel (sparse attention, timed with HIP events on the launch stream inside the timed region),
+and the CPU oracle timed on this machine's host cores on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2",
+                    help="c1..c5 or c4_T<len>; c2 is the configuration the metric is quoted on")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU-work budget of the oracle sample")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, x, budget_s):
+    """Oracle forward on a bounded sample of heads, all host threads; tokens/s scaled to the layer."""
+    import numpy as np
+    import torch
+    import oracle
+
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
+    f64 = lambda t: t.to(torch.float64).numpy()
+    nheads = wl.B * wl.H
+    p = oracle.Params(B=wl.B, H=wl.H, T=wl.T, d=wl.d, m=wl.m, K=wl.K, k_hat=wl.k_hat,
+                      k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale, round8=wl.dtype == "bf16")
+    Q, K, V, W = f64(x["Q"]), f64(x["K"]), f64(x["V"]), f64(x["W"])
+    sl = None if x["seq_len"] is None else x["seq_len"].numpy()
+    t0 = time.perf_counter()
+    oracle.forward(p, Q, K, V, W, seq_len=sl, heads=(0, 1), n_threads=1, want_aux=False)
+    one = time.perf_counter() - t0
+    n = int(max(1, min(nheads, budget_s / max(one, 1e-6))))
+    n = max(min(nheads, cores), (n // cores) * cores) if n >= cores else n
+    n = min(n, nheads)
+    t0 = time.perf_counter()
+    out = oracle.forward(p, Q, K, V, W, seq_len=sl, heads=(0, n), n_threads=cores, want_aux=False)
+    wall = time.perf_counter() - t0
+    tokens = wl.B * wl.T * (n / nheads)
+    return {"value": tokens / wall, "unit": "tokens/s", "cores": int(out["threads"]), "kind": "oracle",
+            "sample": f"first {n} of {nheads} heads of {wl.name} (full T={wl.T}), fp64 C oracle, "
+                      f"{wall:.2f} s wall; one head on one thread {one:.2f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (heads are independent; see DESIGN.md for how "
+              "the path would shard); rerun with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2310_01777_amd import binding as sea
+    from paper_2310_01777_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    wl = synth.get_workload(args.workload)
+    x = synth.make_inputs(wl)
+    d = {k: x[k].to(dev) for k in "QKVW"}
+    sl = None if x["seq_len"] is None else x["seq_len"].to(dev)
+    p = sea.SeaParams(B=wl.B, H=wl.H, T=wl.T, d=wl.d, m=wl.m, K=wl.K, k_hat=wl.k_hat,
+                      k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale, dtype=wl.dtype, seq_len=sl)
+    ws = sea.alloc_workspace(p, dev)
+    O = torch.empty_like(d["Q"])
+    L = sea.sea_row_stride(p)
+
+    # one untimed call with cnt kept, to count the (query, key) pairs the sparse stage processes
+    cnt = torch.empty(wl.B, wl.H, wl.T, dtype=torch.int32, device=dev)
+    sea.sea_forward(p, d["Q"], d["K"], d["V"], d["W"], O, None, None, None, cnt, ws)
+    torch.cuda.synchronize()
+    pairs = int(cnt.sum().item())
+    active_rows = int((cnt > 0).sum().item())
+    del cnt
+
+    step = lambda: sea.sea_forward(p, d["Q"], d["K"], d["V"], d["W"], O, None, None, None, None, ws)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    sea.sea_profile_enable(True)
+    sea.sea_profile_collect()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    stages = sea.sea_profile_collect()
+    sea.sea_profile_enable(False)
+
+    tokens = wl.B * wl.T
+    ms_per_step = elapsed / args.steps * 1e3
+    value = tokens * args.steps / elapsed
+
+    # roofline of the dominant kernel: sparse attention, bound by gathered bytes.
+    # algorithmic bytes per (query, key) pair: one K row + one V row + one int32 index;
+    # per query row: q in, o out.
+    es = 2 if wl.dtype == "bf16" else 4
+    nrows = wl.B * wl.H * wl.T
+    sparse_ms, sparse_n = stages["sparse"]
+    sparse_avg_ms = sparse_ms / max(sparse_n, 1)
+    algo_bytes = pairs * (2 * wl.d * es + 4) + nrows * (2 * wl.d * es + 4)
+    achieved = algo_bytes / (sparse_avg_ms * 1e-3) / 1e9 if sparse_avg_ms > 0 else 0.0
+    roofline = {"kernel": "sparse_attn", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                "avg_kernel_ms": sparse_avg_ms, "algorithmic_bytes": algo_bytes, "pairs": pairs}
+    # estimator: issued matrix-core flops (two projections + contraction, dense count)
+    est_ms = sum(stages[k][0] for k in ("features", "state", "contract")) / max(stages["contract"][1], 1)
+    est_flops = wl.B * wl.H * (4.0 * wl.T * wl.d * wl.m + 2.0 * wl.T * wl.m * wl.K)
+    est = {"ms": est_ms, "dense_flops": est_flops,
+           "tflops": est_flops / (est_ms * 1e-3) / 1e12 if est_ms > 0 else 0.0,
+           "frac_of_bf16_mfma_peak": (est_flops / (est_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS)
+           if est_ms > 0 and wl.dtype == "bf16" else None}
+
+    out = {
+        "metric": "SEA attn fwd tokens/s per layer + % HBM/MFMA roofline, T=1k..32k",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: B={wl.B} H={wl.H} T={wl.T} d={wl.d} m={wl.m} K={wl.K} "
+                               f"k_hat={wl.k_hat} k_budget={wl.k_budget} causal={int(wl.causal)} "
+                               f"pad_frac={wl.pad_frac} clustered Q/K ({wl.centroids} centroids), seed {wl.seed}",
+                   "row_stride": L, "mean_keys_per_active_row": pairs / max(active_rows, 1)},
+        "roofline": roofline,
+        "stage_ms": {k: (v[0] / max(v[1], 1)) for k, v in stages.items() if v[1] > 0},
+        "estimator": est,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, x, args.cpu_seconds)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

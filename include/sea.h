@@ -1,0 +1,164 @@
+/*
+ * sea.h -- C ABI of the SEA attention forward pass for AMD MI355X (gfx950).
+ *
+ * SEA (arXiv 2310.01777, Sec. 3.1) runs attention in two phases: (1) a
+ * kernel-based (FAVOR+ random-feature) estimate A_hat of the attention matrix,
+ * compressed to a fixed width K; (2) a per-query top-k^ selection on A_hat, its
+ * nearest-neighbour expansion into a sparse T x T mask, and softmax attention
+ * restricted to the selected keys.  Cost and memory are linear in T.
+ *
+ * Conventions shared by every entry point
+ *   - Every pointer argument except `const sea_params*` and those marked "host"
+ *     is DEVICE memory owned by the caller.  The library never allocates or
+ *     frees device memory and never synchronises: it only enqueues kernels on
+ *     the given stream (a hipStream_t passed as void*, NULL = default stream)
+ *     and returns.
+ *   - Tensors are dense row-major: Q, K, V, O are [B][H][T][d]; W is [m][d];
+ *     A_hat is [B][H][T][K] float; sel is [B][H][T][k_hat] int32; idx is
+ *     [B][H][T][L] int32 with L = sea_row_stride(); cnt is [B][H][T] int32.
+ *     Q, K, V, W, O hold `dtype` elements (float or bfloat16).
+ *   - Output buffers are fully overwritten: unused sel/idx slots are -1, rows at
+ *     or beyond seq_len[b] get O = 0, A_hat = 0, cnt = 0.
+ *   - Return value: SEA_OK (0) or a negative sea_status.  No exceptions, no
+ *     aborts.  After SEA_EHIP, sea_last_hip_error() gives the hipError_t value.
+ *   - Calls are reentrant across streams; two calls that share a workspace or an
+ *     output buffer must be ordered by the caller.
+ */
+#ifndef SEA_H_
+#define SEA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SEA_F32 = 0, SEA_BF16 = 1 } sea_dtype;
+
+typedef enum {
+  SEA_OK = 0,
+  SEA_EINVAL = -1,     /* NULL pointer, non-positive size, K > T, k_hat > K, ...          */
+  SEA_ENOTSUP = -2,    /* valid but not implemented: d != 64, K > 1024, m % 32 != 0, ...  */
+  SEA_EWORKSPACE = -3, /* workspace NULL or smaller than sea_workspace_bytes()             */
+  SEA_EHIP = -4        /* a HIP call failed; see sea_last_hip_error()                      */
+} sea_status;
+
+/*
+ * Problem statement (Sec. 3 "Preliminaries", Sec. 3.1):
+ *   Q, K, V in R^{T x d} per head, optional batch B and head H dimensions;
+ *   K = width of the compressed matrix; k^ = entries selected per query row in
+ *   the compressed space; k = the paper's sparsity budget in the full space.
+ */
+typedef struct {
+  int32_t B, H, T, d;  /* d must be 64                                                     */
+  int32_t m;           /* number of random features = rows of W; multiple of 32, <= 1024   */
+  int32_t K;           /* compressed width, 1 <= K <= min(T, 1024)                          */
+  int32_t k_hat;       /* 1 <= k_hat <= K                                                   */
+  int32_t k_budget;    /* the paper's k: at most max(1, floor(k_budget / k_hat)) keys are
+                          emitted per selected column, evenly spaced (App. A.5.3 "limit the
+                          pixel replications, space them uniformly"); 0 = whole columns     */
+  int32_t causal;      /* 0: every key < seq_len is admissible; 1: only keys j <= t         */
+  float scale;         /* logits = scale * q.k.  The paper writes softmax(QK^T) with no
+                          factor; pass d^-1/2 for the usual scaled attention                */
+  sea_dtype dtype;     /* element type of Q, K, V, W, O                                     */
+  const int32_t* seq_len; /* device [B] or NULL.  Right padding: keys and query rows at
+                          positions >= seq_len[b] are inactive                              */
+} sea_params;
+
+/* k^ = max(1, round(k K / T)), halves rounded up (Sec. 3.1 "Linear Sparse Attention Mask
+ * Generation").  Pure host arithmetic. */
+int32_t sea_k_hat(int32_t k, int32_t K, int32_t T);
+
+/* L, the row stride of idx: k_hat * r with r = ceil(T/K) keys per selected column, or
+ * min(ceil(T/K), max(1, k_budget / k_hat)) when k_budget > 0.  Host arithmetic; returns a
+ * negative sea_status on invalid parameters. */
+int32_t sea_row_stride(const sea_params* p);
+
+/* Bytes of device scratch sea_estimate / sea_forward need for these parameters (0 on invalid
+ * parameters).  The workspace must be 256-byte aligned; its contents are undefined afterwards. */
+size_t sea_workspace_bytes(const sea_params* p);
+
+/*
+ * Phase (1), Sec. 3 "Performer (FAVOR+)" and Sec. 3.1 "Attention Matrix Estimation".
+ *   phi(x)[i] = exp(w_i.x - |x|^2/2) with x = sqrt(scale) q (keys alike), w_i = row i of W;
+ *   V_I = the T x K one-hot matrix with V_I[j][floor(j K / T)] = 1 (nearest-neighbour stretch
+ *   of the identity); A_hat = rownorm( phi(Q) (phi(K)^T V_I) ), where a causal row t only
+ *   sums keys j <= t.  Rows sum to 1; columns holding no admissible key are 0.
+ * dtype = SEA_BF16: phi(Q) and the key-side state phi(K)^T V_I (for a causal row also the
+ * prefix state of its own column) are rounded to bfloat16 and contracted on the matrix
+ * cores with fp32 accumulation.  dtype = SEA_F32: all products accumulate in fp64.
+ * The feature exponent is not stabilised on the key side: log2(e) * |w_i|^2 / 2 must stay
+ * below the fp32 exponent range (true for any Gaussian W with d = 64).
+ */
+int sea_estimate(const sea_params* p, const void* Q, const void* K, const void* W,
+                 float* A_hat, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Phase (2a, 2b), Sec. 3.1 "Grouped Top-k^ Selection" (per-query grouping) and "Linear Sparse
+ * Attention Mask Generation" / App. A.5.3 (sparse nearest-neighbour interpolation).
+ *   For each active row: among the columns that hold an admissible key, take the
+ *   min(k_hat, #columns) largest A_hat entries (equal values: lower column first); sel lists
+ *   them ascending.  Column c covers keys [ceil(cT/K), ceil((c+1)T/K)), width w; a selected
+ *   column emits keys start + floor(i w / r), i < r; keys j > t (causal) or j >= seq_len are
+ *   dropped.  idx lists the emitted keys ascending, cnt their number.
+ * sel may be NULL.
+ */
+int sea_topk_mask(const sea_params* p, const float* A_hat, int32_t* sel, int32_t* idx,
+                  int32_t* cnt, void* hip_stream);
+
+/*
+ * Phase (2c), Sec. 3.1.1 "Sparse Attention Mechanism": rho (QK^T only at listed positions),
+ * sigma (softmax over the listed positions of each row), C = A* V.
+ *   O[t] = sum_j softmax_j(scale * q_t.k_j) v_j over j in idx[t][0..cnt[t]).
+ * Rows with cnt = 0 give zeros.  Entries outside [0, T) are ignored.  `row_stride` is the
+ * stride L of idx (any L >= max cnt).  Logits and softmax run in fp32 (bf16) or with fp64
+ * dot products (f32); O is rounded once to `dtype`.  No T x T intermediate exists.
+ */
+int sea_sparse_attn(const sea_params* p, const void* Q, const void* K, const void* V,
+                    const int32_t* idx, const int32_t* cnt, int32_t row_stride, void* O,
+                    void* hip_stream);
+
+/*
+ * The whole forward pass (Fig. "model structure", phases 1 and 2 back to back) on one stream.
+ * A_hat_opt, sel_opt, idx_opt, cnt_opt may each be NULL when the caller does not want that
+ * intermediate; results are identical either way.
+ */
+int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V, const void* W,
+                void* O, float* A_hat_opt, int32_t* sel_opt, int32_t* idx_opt, int32_t* cnt_opt,
+                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Quadratic attention A = softmax(scale QK^T), C = AV (Sec. 3 "Preliminaries"), causal and/or
+ * right-padded like the sparse path, computed tile by tile with no T x T buffer.  This is the
+ * baseline the sparse path is reported against, not part of SEA.
+ */
+int sea_dense_attn(const sea_params* p, const void* Q, const void* K, const void* V, void* O,
+                   void* hip_stream);
+
+/*
+ * Per-stage timing for benchmarks.  While enabled, each kernel launch made by the library is
+ * bracketed by HIP events recorded on the launch stream.  sea_profile_collect() synchronises
+ * those events, adds the elapsed milliseconds and launch counts per stage into the two host
+ * arrays of length SEA_STAGE_COUNT, and forgets them.  Process-wide, not thread-safe.
+ */
+typedef enum {
+  SEA_STAGE_FEATURES = 0, /* a1: feature maps phi(Q), phi(K)                              */
+  SEA_STAGE_STATE = 1,    /* a2: key-side bucket sums and prefixes                         */
+  SEA_STAGE_CONTRACT = 2, /* a3: phi(Q) x state, normalisation                             */
+  SEA_STAGE_TOPK_MASK = 3,/* a4 + a5                                                       */
+  SEA_STAGE_SPARSE = 4,   /* a6                                                            */
+  SEA_STAGE_DENSE = 5,    /* dense baseline                                                */
+  SEA_STAGE_COUNT = 6
+} sea_stage;
+int sea_profile_enable(int on);
+int sea_profile_collect(double* host_ms /*[SEA_STAGE_COUNT]*/, int64_t* host_launches /*[SEA_STAGE_COUNT]*/);
+
+const char* sea_strerror(int status);
+int sea_last_hip_error(void);
+const char* sea_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEA_H_ */

@@ -1,0 +1,239 @@
+"""ctypes binding of libsea_hip.so: same names as the C ABI in include/sea.h.
+
+Argument marshalling only -- every step of the path runs in the HIP kernels.  Tensors are
+torch CUDA (ROCm) tensors used purely as device memory; the HIP stream is torch's current
+stream unless one is given.  If the shared library is missing the import of this module
+fails loudly; there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsea_hip.so")
+
+SEA_F32, SEA_BF16 = 0, 1
+SEA_OK, SEA_EINVAL, SEA_ENOTSUP, SEA_EWORKSPACE, SEA_EHIP = 0, -1, -2, -3, -4
+STAGES = ("features", "state", "contract", "topk_mask", "sparse", "dense")
+
+
+class SeaParamsC(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("T", ctypes.c_int32),
+                ("d", ctypes.c_int32), ("m", ctypes.c_int32), ("K", ctypes.c_int32),
+                ("k_hat", ctypes.c_int32), ("k_budget", ctypes.c_int32),
+                ("causal", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("dtype", ctypes.c_int32), ("seq_len", ctypes.c_void_p)]
+
+
+class SeaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib.sea_strerror(status).decode()
+        if status == SEA_EHIP:
+            msg += f" [hipError {_lib.sea_last_hip_error()}]"
+        super().__init__(f"{where}: {msg} ({status})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(hipcc --offload-arch=gfx950).  There is no CPU fallback.")
+    lib = ctypes.CDLL(LIB_PATH)
+    P = ctypes.POINTER(SeaParamsC)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    lib.sea_k_hat.restype, lib.sea_k_hat.argtypes = i32, [i32, i32, i32]
+    lib.sea_row_stride.restype, lib.sea_row_stride.argtypes = i32, [P]
+    lib.sea_workspace_bytes.restype, lib.sea_workspace_bytes.argtypes = sz, [P]
+    lib.sea_estimate.restype, lib.sea_estimate.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, sz, vp]
+    lib.sea_topk_mask.restype, lib.sea_topk_mask.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp]
+    lib.sea_sparse_attn.restype, lib.sea_sparse_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.sea_forward.restype, lib.sea_forward.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.sea_dense_attn.restype, lib.sea_dense_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp]
+    lib.sea_profile_enable.restype, lib.sea_profile_enable.argtypes = ctypes.c_int, [ctypes.c_int]
+    lib.sea_profile_collect.restype = ctypes.c_int
+    lib.sea_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.sea_strerror.restype, lib.sea_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
+    lib.sea_last_hip_error.restype, lib.sea_last_hip_error.argtypes = ctypes.c_int, []
+    lib.sea_version.restype, lib.sea_version.argtypes = ctypes.c_char_p, []
+    return lib
+
+
+_lib = _load()
+
+
+@dataclass
+class SeaParams:
+    """Mirror of ``sea_params``.  ``dtype`` is 'f32' or 'bf16'; ``seq_len`` a CUDA int32 [B] tensor or None."""
+    B: int
+    H: int
+    T: int
+    d: int
+    m: int
+    K: int
+    k_hat: int
+    k_budget: int = 0
+    causal: bool = True
+    scale: float = 0.125
+    dtype: str = "bf16"
+    seq_len: Optional[torch.Tensor] = None
+
+    def c(self) -> SeaParamsC:
+        sl = None
+        if self.seq_len is not None:
+            t = self.seq_len
+            assert t.is_cuda and t.dtype == torch.int32 and t.is_contiguous() and t.numel() == self.B
+            sl = t.data_ptr()
+        return SeaParamsC(self.B, self.H, self.T, self.d, self.m, self.K, self.k_hat, self.k_budget,
+                          int(self.causal), float(self.scale), SEA_BF16 if self.dtype == "bf16" else SEA_F32,
+                          sl)
+
+    @property
+    def torch_dtype(self) -> torch.dtype:
+        return torch.bfloat16 if self.dtype == "bf16" else torch.float32
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None, numel=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name}: expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name}: expected dtype {dtype}, got {t.dtype}")
+    if numel is not None and t.numel() < numel:
+        raise ValueError(f"{name}: needs {numel} elements, has {t.numel()}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _check(rc: int, where: str):
+    if rc != SEA_OK:
+        raise SeaError(rc, where)
+
+
+def sea_k_hat(k: int, K: int, T: int) -> int:
+    return int(_lib.sea_k_hat(k, K, T))
+
+
+def sea_row_stride(p: SeaParams) -> int:
+    cp = p.c()
+    L = int(_lib.sea_row_stride(ctypes.byref(cp)))
+    if L < 0:
+        raise SeaError(L, "sea_row_stride")
+    return L
+
+
+def sea_workspace_bytes(p: SeaParams) -> int:
+    cp = p.c()
+    return int(_lib.sea_workspace_bytes(ctypes.byref(cp)))
+
+
+def sea_estimate(p: SeaParams, Q, K, W, A_hat, workspace, stream=None):
+    n = p.B * p.H * p.T
+    cp = p.c()
+    _check(_lib.sea_estimate(ctypes.byref(cp), _ptr(Q, p.torch_dtype, n * p.d, "Q"),
+                             _ptr(K, p.torch_dtype, n * p.d, "K"),
+                             _ptr(W, p.torch_dtype, p.m * p.d, "W"),
+                             _ptr(A_hat, torch.float32, n * p.K, "A_hat"),
+                             _ptr(workspace, None, None, "workspace"),
+                             workspace.numel() * workspace.element_size(), _stream(stream)),
+           "sea_estimate")
+
+
+def sea_topk_mask(p: SeaParams, A_hat, sel, idx, cnt, stream=None):
+    n = p.B * p.H * p.T
+    L = sea_row_stride(p)
+    cp = p.c()
+    _check(_lib.sea_topk_mask(ctypes.byref(cp), _ptr(A_hat, torch.float32, n * p.K, "A_hat"),
+                              _ptr(sel, torch.int32, n * p.k_hat, "sel"),
+                              _ptr(idx, torch.int32, n * L, "idx"),
+                              _ptr(cnt, torch.int32, n, "cnt"), _stream(stream)),
+           "sea_topk_mask")
+
+
+def sea_sparse_attn(p: SeaParams, Q, K, V, idx, cnt, row_stride, O, stream=None):
+    n = p.B * p.H * p.T
+    cp = p.c()
+    _check(_lib.sea_sparse_attn(ctypes.byref(cp), _ptr(Q, p.torch_dtype, n * p.d, "Q"),
+                                _ptr(K, p.torch_dtype, n * p.d, "K"),
+                                _ptr(V, p.torch_dtype, n * p.d, "V"),
+                                _ptr(idx, torch.int32, n * row_stride, "idx"),
+                                _ptr(cnt, torch.int32, n, "cnt"), int(row_stride),
+                                _ptr(O, p.torch_dtype, n * p.d, "O"), _stream(stream)),
+           "sea_sparse_attn")
+
+
+def sea_forward(p: SeaParams, Q, K, V, W, O, A_hat=None, sel=None, idx=None, cnt=None,
+                workspace=None, stream=None):
+    n = p.B * p.H * p.T
+    L = sea_row_stride(p)
+    cp = p.c()
+    _check(_lib.sea_forward(ctypes.byref(cp), _ptr(Q, p.torch_dtype, n * p.d, "Q"),
+                            _ptr(K, p.torch_dtype, n * p.d, "K"),
+                            _ptr(V, p.torch_dtype, n * p.d, "V"),
+                            _ptr(W, p.torch_dtype, p.m * p.d, "W"),
+                            _ptr(O, p.torch_dtype, n * p.d, "O"),
+                            _ptr(A_hat, torch.float32, n * p.K, "A_hat"),
+                            _ptr(sel, torch.int32, n * p.k_hat, "sel"),
+                            _ptr(idx, torch.int32, n * L, "idx"),
+                            _ptr(cnt, torch.int32, n, "cnt"),
+                            _ptr(workspace, None, None, "workspace"),
+                            workspace.numel() * workspace.element_size(), _stream(stream)),
+           "sea_forward")
+
+
+def sea_dense_attn(p: SeaParams, Q, K, V, O, stream=None):
+    n = p.B * p.H * p.T
+    cp = p.c()
+    _check(_lib.sea_dense_attn(ctypes.byref(cp), _ptr(Q, p.torch_dtype, n * p.d, "Q"),
+                               _ptr(K, p.torch_dtype, n * p.d, "K"),
+                               _ptr(V, p.torch_dtype, n * p.d, "V"),
+                               _ptr(O, p.torch_dtype, n * p.d, "O"), _stream(stream)),
+           "sea_dense_attn")
+
+
+def sea_profile_enable(on: bool):
+    _check(_lib.sea_profile_enable(int(bool(on))), "sea_profile_enable")
+
+
+def sea_profile_collect():
+    """{stage: (milliseconds, launches)} accumulated since the last collect."""
+    ms = (ctypes.c_double * len(STAGES))()
+    cnt = (ctypes.c_int64 * len(STAGES))()
+    _check(_lib.sea_profile_collect(ms, cnt), "sea_profile_collect")
+    return {name: (ms[i], cnt[i]) for i, name in enumerate(STAGES)}
+
+
+def sea_version() -> str:
+    return _lib.sea_version().decode()
+
+
+# ---- conveniences that only allocate device memory ----
+
+def alloc_workspace(p: SeaParams, device="cuda") -> torch.Tensor:
+    nbytes = sea_workspace_bytes(p)
+    if nbytes == 0:
+        raise SeaError(SEA_EINVAL, "sea_workspace_bytes")
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)   # torch allocations are 512-B aligned
+
+
+def alloc_outputs(p: SeaParams, device="cuda", aux=True):
+    n = (p.B, p.H, p.T)
+    out = dict(O=torch.empty(*n, p.d, dtype=p.torch_dtype, device=device))
+    if aux:
+        L = sea_row_stride(p)
+        out.update(A_hat=torch.empty(*n, p.K, dtype=torch.float32, device=device),
+                   sel=torch.empty(*n, p.k_hat, dtype=torch.int32, device=device),
+                   idx=torch.empty(*n, L, dtype=torch.int32, device=device),
+                   cnt=torch.empty(*n, dtype=torch.int32, device=device))
+    return out

@@ -1,0 +1,286 @@
+// C ABI of libsea_hip.so: argument checks, parameter marshalling and stage dispatch.
+// Every computation runs in the HIP kernels of the sibling translation units.
+#include <limits.h>
+
+#include <vector>
+
+#include "sea_internal.h"
+
+namespace sea {
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int fail_hip(hipError_t e) {
+  g_last_hip_error = static_cast<int>(e);
+  return SEA_EHIP;
+}
+
+// ---- profiling state (process-wide) ----
+struct Span {
+  sea_stage stage;
+  hipEvent_t a, b;
+};
+bool g_profile = false;
+std::vector<Span> g_spans;
+std::vector<hipEvent_t> g_free_events;
+
+hipEvent_t take_event() {
+  if (!g_free_events.empty()) {
+    hipEvent_t e = g_free_events.back();
+    g_free_events.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+int check_common(const sea_params* p) {
+  if (!p) return SEA_EINVAL;
+  if (p->B <= 0 || p->H <= 0 || p->T <= 0 || p->d <= 0) return SEA_EINVAL;
+  if (p->dtype != SEA_F32 && p->dtype != SEA_BF16) return SEA_EINVAL;
+  if (static_cast<int64_t>(p->B) * p->H > INT32_MAX) return SEA_EINVAL;
+  if (!(p->scale > 0.f) || !(p->scale < 1e30f)) return SEA_EINVAL;
+  if (p->d != kHeadDim) return SEA_ENOTSUP;
+  if (static_cast<int64_t>(p->B) * p->H * p->T > (int64_t(1) << 40)) return SEA_ENOTSUP;
+  return SEA_OK;
+}
+
+int check_mask_params(const sea_params* p) {
+  if (p->K <= 0 || p->K > p->T) return SEA_EINVAL;
+  if (p->k_hat <= 0 || p->k_hat > p->K) return SEA_EINVAL;
+  if (p->k_budget < 0) return SEA_EINVAL;
+  if (p->K > 1024) return SEA_ENOTSUP;
+  return SEA_OK;
+}
+
+int check_estimate_params(const sea_params* p) {
+  if (p->m <= 0) return SEA_EINVAL;
+  if (p->m % 32 != 0 || p->m > 1024) return SEA_ENOTSUP;
+  return SEA_OK;
+}
+
+int32_t rep_cap_of(const sea_params* p) {
+  if (p->k_budget <= 0) return INT32_MAX;
+  const int32_t cap = p->k_budget / p->k_hat;
+  return cap < 1 ? 1 : cap;
+}
+
+int32_t row_stride_of(const sea_params* p) {
+  const int32_t wmax = (p->T + p->K - 1) / p->K;
+  const int32_t cap = rep_cap_of(p);
+  const int64_t L = static_cast<int64_t>(p->k_hat) * (wmax < cap ? wmax : cap);
+  return L > INT32_MAX ? -1 : static_cast<int32_t>(L);
+}
+
+Shape make_shape(const sea_params* p, bool with_mask) {
+  Shape s{};
+  s.N = p->B * p->H;
+  s.H = p->H;
+  s.T = p->T;
+  s.m = p->m;
+  s.K = p->K;
+  s.k_hat = p->k_hat;
+  s.causal = p->causal ? 1 : 0;
+  s.scale = p->scale;
+  s.seq_len = p->seq_len;
+  if (with_mask) {
+    s.rep_cap = rep_cap_of(p);
+    s.L = row_stride_of(p);
+  }
+  return s;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
+
+size_t estimate_ws(const sea_params* p) {
+  const Shape s = make_shape(p, false);
+  return align256(p->dtype == SEA_BF16 ? estimate_bf16_workspace(s) : estimate_f64_workspace(s));
+}
+
+}  // namespace
+
+void stage_begin(sea_stage stage, hipStream_t st) {
+  if (!g_profile) return;
+  Span sp{stage, take_event(), take_event()};
+  if (!sp.a || !sp.b) return;
+  (void)hipEventRecord(sp.a, st);
+  g_spans.push_back(sp);
+}
+
+void stage_end(sea_stage stage, hipStream_t st) {
+  if (!g_profile || g_spans.empty()) return;
+  Span& sp = g_spans.back();
+  if (sp.stage == stage) (void)hipEventRecord(sp.b, st);
+}
+
+}  // namespace sea
+
+using namespace sea;
+
+extern "C" {
+
+int32_t sea_k_hat(int32_t k, int32_t K, int32_t T) {
+  if (k <= 0 || K <= 0 || T <= 0) return SEA_EINVAL;
+  const int64_t num = static_cast<int64_t>(k) * K;
+  const int64_t r = (2 * num + T) / (2 * static_cast<int64_t>(T));
+  return r < 1 ? 1 : static_cast<int32_t>(r > INT32_MAX ? INT32_MAX : r);
+}
+
+int32_t sea_row_stride(const sea_params* p) {
+  int rc = check_common(p);
+  if (rc == SEA_OK) rc = check_mask_params(p);
+  if (rc != SEA_OK) return rc;
+  const int32_t L = row_stride_of(p);
+  return L < 0 ? SEA_ENOTSUP : L;
+}
+
+size_t sea_workspace_bytes(const sea_params* p) {
+  if (check_common(p) != SEA_OK || check_mask_params(p) != SEA_OK ||
+      check_estimate_params(p) != SEA_OK || row_stride_of(p) < 0)
+    return 0;
+  // estimator scratch, then A_hat, idx, cnt for sea_forward when the caller keeps none of them
+  const size_t rows = static_cast<size_t>(p->B) * p->H * p->T;
+  size_t bytes = estimate_ws(p);
+  bytes += align256(rows * p->K * sizeof(float));
+  bytes += align256(rows * static_cast<size_t>(row_stride_of(p)) * sizeof(int32_t));
+  bytes += align256(rows * sizeof(int32_t));
+  return bytes;
+}
+
+int sea_estimate(const sea_params* p, const void* Q, const void* K, const void* W, float* A_hat,
+                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_common(p);
+  if (rc == SEA_OK) rc = check_mask_params(p);
+  if (rc == SEA_OK) rc = check_estimate_params(p);
+  if (rc != SEA_OK) return rc;
+  if (!Q || !K || !W || !A_hat) return SEA_EINVAL;
+  if (!workspace || workspace_bytes < estimate_ws(p)) return SEA_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SEA_EWORKSPACE;
+  const Shape s = make_shape(p, true);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  hipError_t e;
+  if (p->dtype == SEA_BF16)
+    e = launch_estimate_bf16(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                             static_cast<const uint16_t*>(W), A_hat, workspace, st);
+  else
+    e = launch_estimate_f64(s, static_cast<const float*>(Q), static_cast<const float*>(K),
+                            static_cast<const float*>(W), A_hat, workspace, st);
+  return e == hipSuccess ? SEA_OK : fail_hip(e);
+}
+
+int sea_topk_mask(const sea_params* p, const float* A_hat, int32_t* sel, int32_t* idx,
+                  int32_t* cnt, void* hip_stream) {
+  int rc = check_common(p);
+  if (rc == SEA_OK) rc = check_mask_params(p);
+  if (rc != SEA_OK) return rc;
+  if (!A_hat || !idx || !cnt) return SEA_EINVAL;
+  if (row_stride_of(p) < 0) return SEA_ENOTSUP;
+  const Shape s = make_shape(p, true);
+  const hipError_t e = launch_topk_mask(s, A_hat, sel, idx, cnt, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SEA_OK : fail_hip(e);
+}
+
+int sea_sparse_attn(const sea_params* p, const void* Q, const void* K, const void* V,
+                    const int32_t* idx, const int32_t* cnt, int32_t row_stride, void* O,
+                    void* hip_stream) {
+  const int rc = check_common(p);
+  if (rc != SEA_OK) return rc;
+  if (!Q || !K || !V || !idx || !cnt || !O || row_stride <= 0) return SEA_EINVAL;
+  const Shape s = make_shape(p, false);
+  const hipError_t e = launch_sparse_attn(s, p->dtype, Q, K, V, idx, cnt, row_stride, O,
+                                          static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SEA_OK : fail_hip(e);
+}
+
+int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V, const void* W,
+                void* O, float* A_hat_opt, int32_t* sel_opt, int32_t* idx_opt, int32_t* cnt_opt,
+                void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_common(p);
+  if (rc == SEA_OK) rc = check_mask_params(p);
+  if (rc == SEA_OK) rc = check_estimate_params(p);
+  if (rc != SEA_OK) return rc;
+  if (!Q || !K || !V || !W || !O) return SEA_EINVAL;
+  if (row_stride_of(p) < 0) return SEA_ENOTSUP;
+  if (!workspace || workspace_bytes < sea_workspace_bytes(p)) return SEA_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SEA_EWORKSPACE;
+  const Shape s = make_shape(p, true);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const size_t rows = static_cast<size_t>(s.N) * s.T;
+  char* w = static_cast<char*>(workspace);
+  void* est_ws = w;
+  w += estimate_ws(p);
+  float* A_hat = A_hat_opt ? A_hat_opt : reinterpret_cast<float*>(w);
+  w += align256(rows * s.K * sizeof(float));
+  int32_t* idx = idx_opt ? idx_opt : reinterpret_cast<int32_t*>(w);
+  w += align256(rows * static_cast<size_t>(s.L) * sizeof(int32_t));
+  int32_t* cnt = cnt_opt ? cnt_opt : reinterpret_cast<int32_t*>(w);
+
+  hipError_t e;
+  if (p->dtype == SEA_BF16)
+    e = launch_estimate_bf16(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                             static_cast<const uint16_t*>(W), A_hat, est_ws, st);
+  else
+    e = launch_estimate_f64(s, static_cast<const float*>(Q), static_cast<const float*>(K),
+                            static_cast<const float*>(W), A_hat, est_ws, st);
+  if (e != hipSuccess) return fail_hip(e);
+  e = launch_topk_mask(s, A_hat, sel_opt, idx, cnt, st);
+  if (e != hipSuccess) return fail_hip(e);
+  e = launch_sparse_attn(s, p->dtype, Q, K, V, idx, cnt, s.L, O, st);
+  return e == hipSuccess ? SEA_OK : fail_hip(e);
+}
+
+int sea_dense_attn(const sea_params* p, const void* Q, const void* K, const void* V, void* O,
+                   void* hip_stream) {
+  const int rc = check_common(p);
+  if (rc != SEA_OK) return rc;
+  if (!Q || !K || !V || !O) return SEA_EINVAL;
+  const Shape s = make_shape(p, false);
+  const hipError_t e =
+      launch_dense_attn(s, p->dtype, Q, K, V, O, static_cast<hipStream_t>(hip_stream));
+  if (e == hipErrorNotSupported) return SEA_ENOTSUP;
+  return e == hipSuccess ? SEA_OK : fail_hip(e);
+}
+
+int sea_profile_enable(int on) {
+  g_profile = on != 0;
+  return SEA_OK;
+}
+
+int sea_profile_collect(double* host_ms, int64_t* host_launches) {
+  if (!host_ms || !host_launches) return SEA_EINVAL;
+  int rc = SEA_OK;
+  for (Span& sp : g_spans) {
+    float ms = 0.f;
+    hipError_t e = hipEventSynchronize(sp.b);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, sp.a, sp.b);
+    if (e == hipSuccess && sp.stage >= 0 && sp.stage < SEA_STAGE_COUNT) {
+      host_ms[sp.stage] += ms;
+      host_launches[sp.stage] += 1;
+    } else if (e != hipSuccess) {
+      rc = fail_hip(e);
+    }
+    g_free_events.push_back(sp.a);
+    g_free_events.push_back(sp.b);
+  }
+  g_spans.clear();
+  return rc;
+}
+
+const char* sea_strerror(int status) {
+  switch (status) {
+    case SEA_OK: return "ok";
+    case SEA_EINVAL: return "invalid argument (NULL pointer, size out of range, K > T or k_hat > K)";
+    case SEA_ENOTSUP: return "not supported (d != 64, K > 1024, or m not a multiple of 32 up to 1024)";
+    case SEA_EWORKSPACE: return "workspace missing, misaligned or smaller than sea_workspace_bytes()";
+    case SEA_EHIP: return "a HIP runtime call failed (see sea_last_hip_error)";
+    default: return "unknown status";
+  }
+}
+
+int sea_last_hip_error(void) { return g_last_hip_error; }
+
+const char* sea_version(void) { return "sea-hip 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,99 @@
+// Internal declarations shared by the HIP translation units of libsea_hip.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "sea.h"
+
+namespace sea {
+
+constexpr int kWave = 64;
+constexpr int kHeadDim = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+
+// Shape block handed to kernels by value.
+struct Shape {
+  int32_t N;  // B * H heads
+  int32_t H;
+  int32_t T;
+  int32_t m;
+  int32_t K;
+  int32_t k_hat;
+  int32_t rep_cap;  // max keys per selected column (>= 1), INT32_MAX-like when uncapped
+  int32_t L;        // row stride of idx
+  int32_t causal;
+  float scale;
+  const int32_t* seq_len;  // device [B] or nullptr
+};
+
+// ---- launchers (each enqueues on `st` and returns the launch error, if any) ----
+hipError_t launch_estimate_f64(const Shape& s, const float* Q, const float* K, const float* W,
+                               float* A_hat, void* ws, hipStream_t st);
+size_t estimate_f64_workspace(const Shape& s);
+
+hipError_t launch_estimate_bf16(const Shape& s, const uint16_t* Q, const uint16_t* K,
+                                const uint16_t* W, float* A_hat, void* ws, hipStream_t st);
+size_t estimate_bf16_workspace(const Shape& s);
+
+hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, int32_t* idx,
+                            int32_t* cnt, hipStream_t st);
+
+hipError_t launch_sparse_attn(const Shape& s, sea_dtype dt, const void* Q, const void* K,
+                              const void* V, const int32_t* idx, const int32_t* cnt, int32_t L,
+                              void* O, hipStream_t st);
+
+hipError_t launch_dense_attn(const Shape& s, sea_dtype dt, const void* Q, const void* K,
+                             const void* V, void* O, hipStream_t st);
+
+// ---- per-stage event timing (see sea_profile_enable) ----
+void stage_begin(sea_stage stage, hipStream_t st);
+void stage_end(sea_stage stage, hipStream_t st);
+struct StageScope {
+  sea_stage stage;
+  hipStream_t st;
+  StageScope(sea_stage s, hipStream_t t) : stage(s), st(t) { stage_begin(s, t); }
+  ~StageScope() { stage_end(stage, st); }
+};
+
+// ---- device helpers ----
+#if defined(__HIPCC__)
+
+// Workgroup ids are dealt round-robin to the 8 XCDs.  Remap so that each XCD gets one
+// contiguous range of logical tiles: rows of one head then share that XCD's L2.
+__device__ __forceinline__ uint32_t xcd_contiguous(uint32_t bid, uint32_t nblocks) {
+  constexpr uint32_t X = 8;
+  const uint32_t per = nblocks / X, rem = nblocks % X;
+  if (bid >= per * X) return bid;  // ragged tail stays in place
+  (void)rem;
+  const uint32_t xcd = bid % X, slot = bid / X;
+  return xcd * per + slot;
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) {
+  return __uint_as_float(static_cast<uint32_t>(h) << 16);
+}
+__device__ __forceinline__ float bf16lo_to_f32(uint32_t pair) { return __uint_as_float(pair << 16); }
+__device__ __forceinline__ float bf16hi_to_f32(uint32_t pair) {
+  return __uint_as_float(pair & 0xffff0000u);
+}
+// round-to-nearest-even, finite inputs
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return static_cast<uint16_t>(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+}
+
+// first key of column c: ceil(c T / K); column of key j: floor(j K / T)
+__device__ __forceinline__ int32_t block_start(int32_t c, int32_t T, int32_t K) {
+  return static_cast<int32_t>((static_cast<int64_t>(c) * T + K - 1) / K);
+}
+__device__ __forceinline__ int32_t bucket_of(int32_t j, int32_t T, int32_t K) {
+  return static_cast<int32_t>((static_cast<int64_t>(j) * K) / T);
+}
+
+#endif  // __HIPCC__
+
+}  // namespace sea

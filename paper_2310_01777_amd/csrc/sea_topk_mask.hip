@@ -1,0 +1,172 @@
+// Per-query top-k^ selection on the compressed estimate and its expansion to key positions
+// (Sec. 3.1 "Grouped Top-k^ Selection", per-query grouping; "Linear Sparse Attention Mask
+// Generation" and App. A.5.3 for the nearest-neighbour expansion with a replication cap).
+//
+// One wavefront owns one query row.  The K <= 1024 scores of the row sit in registers,
+// SLOTS = ceil(K / 64) per lane (column = slot * 64 + lane).  The k^-th largest score is
+// found exactly by a bitwise search on order-preserving integer keys, using wave ballots and
+// population counts only; ties at the threshold go to the lower column.  Selected columns
+// are compacted in ascending order with ballot prefix counts, then expanded.
+#include "sea_internal.h"
+
+namespace sea {
+namespace {
+
+constexpr int kWavesPerBlock = 4;
+
+__device__ __forceinline__ uint32_t ordered_key(float a) {
+  a += 0.0f;  // -0 -> +0
+  uint32_t u = __float_as_uint(a);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ int popc64(uint64_t x) { return __popcll(x); }
+__device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
+  return __popcll(mask & ((1ull << lane) - 1ull));
+}
+
+template <int SLOTS>
+__global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
+    Shape s, const float* __restrict__ A_hat, int32_t* __restrict__ sel, int32_t* __restrict__ idx,
+    int32_t* __restrict__ cnt) {
+  __shared__ int32_t sh_sel[kWavesPerBlock][SLOTS * kWave];
+  __shared__ int32_t sh_off[kWavesPerBlock][SLOTS * kWave + 1];
+  const int wid = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int64_t row = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wid;
+  const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
+  if (row >= nrows) return;  // whole wave leaves; no block-wide barrier is used below
+  const int32_t t = static_cast<int32_t>(row % s.T);
+  const int32_t b = static_cast<int32_t>((row / s.T) / s.H);
+  const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
+  int32_t* irow = idx + row * s.L;
+  int32_t* srow = sel ? sel + row * s.k_hat : nullptr;
+
+  if (t >= len) {  // inactive row
+    for (int32_t x = lane; x < s.L; x += kWave) irow[x] = -1;
+    if (srow)
+      for (int32_t x = lane; x < s.k_hat; x += kWave) srow[x] = -1;
+    if (lane == 0) cnt[row] = 0;
+    return;
+  }
+  const int32_t jmax = (s.causal && t < len - 1) ? t : len - 1;  // last admissible key
+  const int32_t ncand = bucket_of(jmax, s.T, s.K) + 1;           // candidate columns 0..ncand-1
+  const int32_t n = min(s.k_hat, ncand);
+
+  uint32_t key[SLOTS];
+#pragma unroll
+  for (int q = 0; q < SLOTS; ++q) {
+    const int32_t c = q * kWave + lane;
+    key[q] = (c < ncand) ? ordered_key(A_hat[row * s.K + c]) : 0u;  // c < ncand <= K
+  }
+  // largest tau with #{key >= tau} >= n  ==  the n-th largest key
+  uint32_t tau = 0;
+#pragma unroll 1
+  for (int bit = 31; bit >= 0; --bit) {
+    const uint32_t trial = tau | (1u << bit);
+    int c_ge = 0;
+#pragma unroll
+    for (int q = 0; q < SLOTS; ++q) c_ge += popc64(__ballot(key[q] >= trial));
+    if (c_ge >= n) tau = trial;
+  }
+  int c_gt = 0;
+#pragma unroll
+  for (int q = 0; q < SLOTS; ++q) c_gt += popc64(__ballot(key[q] > tau));
+  int need_eq = n - c_gt;  // how many of the entries equal to tau are taken, lowest columns first
+
+  // compaction in ascending column order (slot-major, then lane)
+  int n_sel = 0;
+#pragma unroll
+  for (int q = 0; q < SLOTS; ++q) {
+    const uint64_t eq = __ballot(key[q] == tau);
+    const bool take_eq = (key[q] == tau) && (lanes_below(eq, lane) < need_eq);
+    const bool take = (key[q] > tau) || take_eq;
+    const uint64_t tk = __ballot(take);
+    if (take) sh_sel[wid][n_sel + lanes_below(tk, lane)] = q * kWave + lane;
+    n_sel += popc64(tk);
+    need_eq -= min(need_eq, popc64(eq));
+  }
+  // n_sel == n by construction
+  __builtin_amdgcn_wave_barrier();
+  if (srow)
+    for (int32_t x = lane; x < s.k_hat; x += kWave) srow[x] = (x < n_sel) ? sh_sel[wid][x] : -1;
+
+  // expansion: selected column c emits r keys start + floor(i w / r), i < r
+  const bool uniform = (s.T % s.K) == 0;
+  int32_t total;
+  if (uniform) {
+    const int32_t w = s.T / s.K;
+    const int32_t r = min(w, s.rep_cap);
+    total = n_sel * r;
+    int32_t kept = 0;
+    for (int32_t x0 = 0; x0 < s.L; x0 += kWave) {
+      const int32_t x = x0 + lane;
+      int32_t j = -1;
+      if (x < total) {
+        const int32_t si = x / r, i = x - si * r;
+        const int32_t c = sh_sel[wid][si];
+        j = c * w + static_cast<int32_t>((static_cast<int64_t>(i) * w) / r);
+        if (j > jmax) j = -1;
+      }
+      if (x < s.L) irow[x] = j;
+      kept += popc64(__ballot(j >= 0));
+    }
+    total = kept;  // dropped keys are a suffix: only the last selected column can overrun jmax
+  } else {
+    // ragged columns: per-selection offsets by a serial prefix in lane 0 (n_sel <= K)
+    if (lane == 0) {
+      int32_t acc = 0;
+      for (int32_t si = 0; si < n_sel; ++si) {
+        sh_off[wid][si] = acc;
+        const int32_t c = sh_sel[wid][si];
+        const int32_t w = block_start(c + 1, s.T, s.K) - block_start(c, s.T, s.K);
+        acc += min(w, s.rep_cap);
+      }
+      sh_off[wid][n_sel] = acc;
+    }
+    __builtin_amdgcn_wave_barrier();
+    for (int32_t x = lane; x < s.L; x += kWave) irow[x] = -1;
+    __builtin_amdgcn_wave_barrier();
+    int32_t kept = 0;
+    for (int32_t si = 0; si < n_sel; ++si) {
+      const int32_t c = sh_sel[wid][si];
+      const int32_t s0 = block_start(c, s.T, s.K);
+      const int32_t w = block_start(c + 1, s.T, s.K) - s0;
+      const int32_t r = min(w, s.rep_cap);
+      const int32_t off = sh_off[wid][si];
+      for (int32_t i = lane; i < r; i += kWave) {
+        const int32_t j = s0 + static_cast<int32_t>((static_cast<int64_t>(i) * w) / r);
+        if (j <= jmax && off + i < s.L) irow[off + i] = j;
+      }
+      // count kept keys of this column (uniform value across the wave)
+      int32_t lo = 0, hi = r;  // first i with s0 + floor(i w / r) > jmax
+      while (lo < hi) {
+        const int32_t mid = (lo + hi) >> 1;
+        if (s0 + static_cast<int32_t>((static_cast<int64_t>(mid) * w) / r) > jmax) hi = mid;
+        else lo = mid + 1;
+      }
+      kept += lo;
+    }
+    total = kept;
+  }
+  if (lane == 0) cnt[row] = total;
+}
+
+}  // namespace
+
+hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, int32_t* idx,
+                            int32_t* cnt, hipStream_t st) {
+  const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
+  const uint32_t grid = static_cast<uint32_t>((nrows + kWavesPerBlock - 1) / kWavesPerBlock);
+  const dim3 block(kWavesPerBlock * kWave);
+  const int slots = (s.K + kWave - 1) / kWave;
+  StageScope scope(SEA_STAGE_TOPK_MASK, st);
+  if (slots <= 1) hipLaunchKernelGGL(topk_mask_kernel<1>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt);
+  else if (slots <= 2) hipLaunchKernelGGL(topk_mask_kernel<2>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt);
+  else if (slots <= 4) hipLaunchKernelGGL(topk_mask_kernel<4>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt);
+  else if (slots <= 8) hipLaunchKernelGGL(topk_mask_kernel<8>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt);
+  else hipLaunchKernelGGL(topk_mask_kernel<16>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt);
+  return hipGetLastError();
+}
+
+}  // namespace sea

@@ -1,0 +1,286 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Integer work (selection, expansion) must be bit-exact; floating point within
+the contract's relative tolerances (1e-5 fp32, 2e-2 bf16)."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2310_01777_amd import synth
+from tests.util import (GAP, TOL, assert_close, candidate_counts, oracle_params, selection_gaps,
+                        to_np64)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sea():
+    from paper_2310_01777_amd import binding
+    return binding
+
+
+def _wl(name, B, H, T, m, K, k_hat, k_budget=0, causal=True, dtype="bf16", centroids=4,
+        pad_frac=0.0, seed=1234):
+    return synth.Workload(name, B, H, T, 64, m, K, k_hat, k_budget, causal, dtype, centroids,
+                          pad_frac, seed)
+
+
+def _params(sea, wl, seq_len_dev=None):
+    return sea.SeaParams(B=wl.B, H=wl.H, T=wl.T, d=wl.d, m=wl.m, K=wl.K, k_hat=wl.k_hat,
+                         k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale, dtype=wl.dtype,
+                         seq_len=seq_len_dev)
+
+
+def _dev(x):
+    return {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in x.items()}
+
+
+def _gpu_forward(sea, wl, x):
+    xd = _dev(x)
+    p = _params(sea, wl, xd["seq_len"])
+    out = sea.alloc_outputs(p)
+    ws = sea.alloc_workspace(p)
+    print(f"[case] {wl.name} B{wl.B} H{wl.H} T{wl.T} m{wl.m} K{wl.K} kh{wl.k_hat} kb{wl.k_budget} "
+          f"causal{int(wl.causal)} {wl.dtype}", flush=True)
+    sea.sea_forward(p, xd["Q"], xd["K"], xd["V"], xd["W"], out["O"], out["A_hat"], out["sel"],
+                    out["idx"], out["cnt"], ws)
+    torch.cuda.synchronize()
+    return p, xd, {k: v.cpu() for k, v in out.items()}
+
+
+def _oracle_forward(wl, x, rows=None):
+    p = oracle_params(wl)
+    sl = None if x["seq_len"] is None else x["seq_len"].numpy()
+    return p, oracle.forward(p, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), to_np64(x["W"]),
+                             seq_len=sl, rows=rows)
+
+
+SMALL_CASES = [
+    # spans several 64-row tiles and a ragged tail; uniform and ragged column widths
+    _wl("f32_causal", 1, 3, 200, 64, 25, 6, dtype="f32"),
+    _wl("f32_bidir_pad", 2, 2, 192, 32, 16, 5, causal=False, dtype="f32", pad_frac=0.3),
+    _wl("f32_ragged_cols", 1, 2, 150, 64, 13, 4, dtype="f32"),
+    _wl("f32_budget", 1, 2, 256, 32, 8, 2, k_budget=10, dtype="f32"),
+    _wl("bf16_causal", 2, 3, 320, 128, 40, 9),
+    _wl("bf16_tail", 1, 2, 203, 64, 29, 7),
+    _wl("bf16_bidir_pad", 3, 2, 256, 128, 32, 8, causal=False, pad_frac=0.3),
+    _wl("bf16_ragged_cols", 1, 2, 300, 96, 17, 5),
+    _wl("bf16_budget", 1, 2, 512, 64, 16, 4, k_budget=24),
+    _wl("bf16_wideK", 1, 1, 640, 64, 320, 40),
+    _wl("bf16_K_eq_T", 1, 2, 96, 32, 96, 11),
+]
+
+
+@pytest.mark.parametrize("wl", SMALL_CASES, ids=lambda w: w.name)
+def test_forward_matches_oracle(sea, wl):
+    x = synth.make_inputs(wl)
+    p, xd, g = _gpu_forward(sea, wl, x)
+    po, o = _oracle_forward(wl, x)
+    sl = None if x["seq_len"] is None else x["seq_len"].numpy()
+    tol = TOL[wl.dtype]
+
+    # a1-a3: estimate
+    A_g = g["A_hat"].numpy().astype(np.float64)
+    assert_close(A_g, o["A_hat"], tol, "A_hat")
+    np.testing.assert_allclose(A_g.sum(-1)[o["cnt"] > 0], 1.0, atol=1e-5)
+
+    # a4-a5 stage-wise: the oracle's selection applied to the GPU's own A_hat is bit-identical
+    sel_s, idx_s, cnt_s = oracle.topk_mask(po, A_g, seq_len=sl)
+    assert np.array_equal(g["sel"].numpy(), sel_s)
+    assert np.array_equal(g["idx"].numpy(), idx_s)
+    assert np.array_equal(g["cnt"].numpy(), cnt_s)
+
+    # a6 stage-wise: oracle sparse attention over the GPU's lists
+    O_s = oracle.sparse_attn(po, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), idx_s, cnt_s)
+    assert_close(to_np64(g["O"]), O_s, tol, "O (stage)")
+
+    # end to end: identical index sets except at near-ties of the oracle's scores
+    same = (g["sel"].numpy() == o["sel"]).all(-1)
+    ncand = candidate_counts(wl.B, wl.H, wl.T, wl.K, wl.causal, sl)
+    gaps = selection_gaps(o["A_hat"], o["sel"], ncand)
+    bad = ~same & ~(gaps < GAP[wl.dtype])
+    assert not bad.any(), f"{bad.sum()} rows differ with gap >= {GAP[wl.dtype]:g}: min gap {gaps[~same].max()}"
+    assert (~same).mean() <= 0.02, f"{(~same).sum()} of {same.size} rows differ"
+    assert np.array_equal(g["idx"].numpy()[same], o["idx"][same])
+    assert np.array_equal(g["cnt"].numpy()[same], o["cnt"][same])
+    Og, Oo = to_np64(g["O"]).copy(), o["O"].copy()
+    Og[~same] = 0.0
+    Oo[~same] = 0.0
+    assert_close(Og, Oo, tol, "O (end to end)")
+    print(f"    rows differing at near-ties: {(~same).sum()} / {same.size}", flush=True)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("causal", [False, True])
+def test_full_selection_reduces_to_dense_attention(sea, dtype, causal):
+    """k^ = K, no budget: O must equal textbook softmax attention (library softmax, fp64)."""
+    wl = _wl("dense_limit", 2, 2, 160, 32, 20, 20, causal=causal, dtype=dtype, pad_frac=0.2)
+    x = synth.make_inputs(wl)
+    _, _, g = _gpu_forward(sea, wl, x)
+    Q, K, V = (x[k].to(torch.float64) for k in "QKV")
+    S = wl.scale * Q @ K.transpose(-1, -2)
+    T = wl.T
+    valid = torch.arange(T)[None, :] < x["seq_len"][:, None]
+    keep = valid[:, None, None, :].expand(wl.B, 1, T, T).clone()
+    if causal:
+        keep &= torch.tril(torch.ones(T, T, dtype=torch.bool))
+    want = torch.softmax(S.masked_fill(~keep, float("-inf")), -1) @ V
+    want = (want * valid[:, None, :, None]).numpy()
+    assert_close(to_np64(g["O"]), want, TOL[dtype], "O vs dense")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_topk_mask_exact_on_planted_ties(sea, dtype):
+    """Selection and expansion are integer work: bit-exact, including planted duplicates."""
+    g = torch.Generator().manual_seed(5)
+    for (T, K, kh, kb, causal) in [(128, 32, 7, 0, True), (130, 24, 24, 0, False),
+                                   (256, 256, 5, 0, True), (1024, 8, 1, 50, False),
+                                   (777, 100, 33, 70, True), (64, 1, 1, 0, True)]:
+        B, H = 2, 2
+        A = torch.rand(B, H, T, K, generator=g)
+        A[0, 1] = torch.round(A[0, 1] * 4) / 4
+        A[1, 0] = 0.25
+        A[1, 1, :, ::3] = 0.0
+        seq_len = torch.tensor([T, max(1, T - 37)], dtype=torch.int32)
+        wl = _wl("topk", B, H, T, 32, K, kh, k_budget=kb, causal=causal, dtype=dtype)
+        p = _params(sea, wl, seq_len.cuda())
+        L = sea.sea_row_stride(p)
+        sel = torch.empty(B, H, T, kh, dtype=torch.int32, device="cuda")
+        idx = torch.empty(B, H, T, L, dtype=torch.int32, device="cuda")
+        cnt = torch.empty(B, H, T, dtype=torch.int32, device="cuda")
+        print(f"[case] topk T{T} K{K} kh{kh} kb{kb} causal{int(causal)}", flush=True)
+        sea.sea_topk_mask(p, A.cuda(), sel, idx, cnt)
+        torch.cuda.synchronize()
+        po = oracle_params(wl)
+        assert L == oracle.row_stride(po)
+        s_o, i_o, c_o = oracle.topk_mask(po, A.numpy(), seq_len=seq_len.numpy())
+        assert np.array_equal(sel.cpu().numpy(), s_o)
+        assert np.array_equal(idx.cpu().numpy(), i_o)
+        assert np.array_equal(cnt.cpu().numpy(), c_o)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sparse_attn_arbitrary_lists(sea, dtype):
+    """The sparse kernel takes any per-row list: ragged counts, empty rows, repeated keys,
+    unsorted order, and ignores entries outside [0, T)."""
+    B, H, T, L = 2, 3, 150, 70
+    wl = _wl("lists", B, H, T, 32, 10, 3, dtype=dtype)
+    x = synth.make_inputs(wl)
+    g = torch.Generator().manual_seed(9)
+    idx = torch.randint(0, T, (B, H, T, L), generator=g, dtype=torch.int32)
+    cnt = torch.randint(0, L + 1, (B, H, T), generator=g, dtype=torch.int32)
+    cnt[0, 0, :5] = 0
+    cnt[1, 2, 7] = L
+    idx[0, 1, :, 3] = -1          # ignored entries
+    idx[0, 2, :, 5] = T + 4
+    xd = _dev(x)
+    p = _params(sea, wl)
+    O = torch.empty(B, H, T, 64, dtype=p.torch_dtype, device="cuda")
+    sea.sea_sparse_attn(p, xd["Q"], xd["K"], xd["V"], idx.cuda(), cnt.cuda(), L, O)
+    torch.cuda.synchronize()
+    # oracle on the cleaned lists (invalid entries removed)
+    idx_np, cnt_np = idx.numpy().copy(), cnt.numpy().copy()
+    for r in np.ndindex(B, H, T):
+        row = idx_np[r][:cnt_np[r]]
+        keep = row[(row >= 0) & (row < T)]
+        idx_np[r] = -1
+        idx_np[r][:len(keep)] = keep
+        cnt_np[r] = len(keep)
+    po = oracle_params(wl)
+    want = oracle.sparse_attn(po, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), idx_np, cnt_np)
+    assert_close(to_np64(O), want, TOL[dtype], "O lists")
+    assert (O[0, 0, :5] == 0).all()
+
+
+def test_causality_and_determinism_on_gpu(sea):
+    """Rows <= t0 do not change when later positions change; two runs are bit-identical."""
+    wl = _wl("causality", 1, 2, 256, 64, 32, 6)
+    x = synth.make_inputs(wl)
+    _, _, a = _gpu_forward(sea, wl, x)
+    _, _, a2 = _gpu_forward(sea, wl, x)
+    for k in a:
+        assert torch.equal(a[k], a2[k]), k
+    t0 = 137
+    y = {k: (v.clone() if isinstance(v, torch.Tensor) else v) for k, v in x.items()}
+    gen = torch.Generator().manual_seed(3)
+    for k in "QKV":
+        y[k][:, :, t0 + 1:] = (torch.randn(y[k][:, :, t0 + 1:].shape, generator=gen) * 2).to(y[k].dtype)
+    _, _, b = _gpu_forward(sea, wl, y)
+    for k in a:
+        assert torch.equal(a[k][:, :, :t0 + 1], b[k][:, :, :t0 + 1]), k
+
+
+def test_padding_rows_and_zero_length(sea):
+    """seq_len = 0 for a batch element: every output of it is inert; other elements unaffected."""
+    wl = _wl("pad0", 2, 2, 128, 32, 16, 4, causal=False)
+    x = synth.make_inputs(wl)
+    x["seq_len"] = torch.tensor([0, 100], dtype=torch.int32)
+    _, _, g = _gpu_forward(sea, wl, x)
+    assert (g["O"][0] == 0).all() and (g["cnt"][0] == 0).all() and (g["A_hat"][0] == 0).all()
+    assert (g["idx"][0] == -1).all() and (g["sel"][0] == -1).all()
+    assert (g["O"][1, :, 100:] == 0).all() and (g["cnt"][1, :, 100:] == 0).all()
+    _, o = _oracle_forward(wl, x)
+    assert_close(to_np64(g["O"]), o["O"], TOL["bf16"], "O padded")
+
+
+def test_optional_outputs_do_not_change_results(sea):
+    wl = _wl("noaux", 1, 2, 192, 64, 24, 5)
+    x = synth.make_inputs(wl)
+    p, xd, g = _gpu_forward(sea, wl, x)
+    O2 = torch.empty_like(xd["Q"])
+    ws = sea.alloc_workspace(p)
+    sea.sea_forward(p, xd["Q"], xd["K"], xd["V"], xd["W"], O2, None, None, None, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(O2.cpu(), g["O"])
+
+
+# ---- full-size configurations, in the launch configuration bench.py times, on sampled rows ----
+
+FULL = ["c1", "c2", "c5", "c4_T8192"]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_sampled_rows(sea, name):
+    wl = synth.get_workload(name)
+    x = synth.make_inputs(wl)
+    p, xd, g = _gpu_forward(sea, wl, x)
+    rng = np.random.default_rng(0)
+    rows = np.unique(np.concatenate([[0, 1, wl.T // wl.K - 1, wl.T // wl.K, wl.T - 1],
+                                     rng.integers(0, wl.T, 40)])).astype(np.int32)
+    heads = sorted(set([0, wl.B * wl.H - 1] + rng.integers(0, wl.B * wl.H, 3).tolist()))
+    tol = TOL[wl.dtype]
+    n_diff = n_rows = 0
+    for bh in heads:
+        b, h = divmod(bh, wl.H)
+        one = replace(wl, B=1, H=1)
+        xs = {k: x[k][b:b + 1, h:h + 1] for k in "QKV"}
+        xs["W"] = x["W"]
+        xs["seq_len"] = None if x["seq_len"] is None else x["seq_len"][b:b + 1]
+        po, o = _oracle_forward(one, xs, rows=rows)
+        sl = None if xs["seq_len"] is None else xs["seq_len"].numpy()
+        A_g = g["A_hat"][b, h][rows].numpy().astype(np.float64)[None, None]
+        assert_close(A_g, o["A_hat"], tol, f"A_hat head {bh}")
+        sel_s, idx_s, cnt_s = oracle.topk_mask(po, A_g, seq_len=sl, rows=rows)
+        assert np.array_equal(g["sel"][b, h][rows].numpy()[None, None], sel_s)
+        assert np.array_equal(g["idx"][b, h][rows].numpy()[None, None], idx_s)
+        assert np.array_equal(g["cnt"][b, h][rows].numpy()[None, None], cnt_s)
+        O_s = oracle.sparse_attn(po, to_np64(xs["Q"]), to_np64(xs["K"]), to_np64(xs["V"]), idx_s, cnt_s,
+                                 rows=rows)
+        assert_close(to_np64(g["O"][b, h][rows])[None, None], O_s, tol, f"O head {bh}")
+        same = (sel_s == o["sel"]).all(-1)
+        ncand = candidate_counts(1, 1, wl.T, wl.K, wl.causal, sl, rows)
+        gaps = selection_gaps(o["A_hat"], o["sel"], ncand)
+        bad = ~same & ~(gaps < GAP[wl.dtype])
+        assert not bad.any(), f"head {bh}: rows {rows[bad[0, 0]]} differ, gaps {gaps[bad]}"
+        n_diff += int((~same).sum())
+        n_rows += same.size
+    # properties that hold at any size, over the whole output
+    cnt = g["cnt"].numpy()
+    L = sea.sea_row_stride(p)
+    assert cnt.max() <= L and cnt.min() >= 0
+    idx = g["idx"].numpy()
+    assert ((idx >= 0).sum(-1) == cnt).all()
+    assert np.isfinite(to_np64(g["O"])).all()
+    print(f"    sampled rows differing at near-ties: {n_diff} / {n_rows}", flush=True)
