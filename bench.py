@@ -30,6 +30,9 @@ def parse():
                     help="c1..c5 or c4_T<len>; c2 is the configuration the metric is quoted on")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU-work budget of the oracle sample")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
+                    help="only run a plain device copy of this many MiB three times (calibrates the "
+                         "FETCH_SIZE / WRITE_SIZE counters of rocprofv3 --pmc) and exit")
     return ap.parse_args()
 
 
@@ -73,6 +76,14 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
+    if args.copy_probe > 0:
+        src = torch.ones(args.copy_probe << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes": args.copy_probe << 20, "copies": 3}))
+        return
     wl = synth.get_workload(args.workload)
     x = synth.make_inputs(wl)
     d = {k: x[k].to(dev) for k in "QKVW"}
