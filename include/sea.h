@@ -131,10 +131,12 @@ int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V
 /*
  * Quadratic attention A = softmax(scale QK^T), C = AV (Sec. 3 "Preliminaries"), causal and/or
  * right-padded like the sparse path, computed tile by tile with no T x T buffer.  This is the
- * baseline the sparse path is reported against, not part of SEA.
+ * baseline the sparse path is reported against, not part of SEA.  bf16 only (SEA_ENOTSUP for
+ * fp32); needs sea_dense_workspace_bytes() of 256-byte aligned scratch (a transposed copy of V).
  */
+size_t sea_dense_workspace_bytes(const sea_params* p);
 int sea_dense_attn(const sea_params* p, const void* Q, const void* K, const void* V, void* O,
-                   void* hip_stream);
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Per-stage timing for benchmarks.  While enabled, each kernel launch made by the library is

@@ -54,7 +54,8 @@ def _load() -> ctypes.CDLL:
     lib.sea_topk_mask.restype, lib.sea_topk_mask.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp]
     lib.sea_sparse_attn.restype, lib.sea_sparse_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.sea_forward.restype, lib.sea_forward.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
-    lib.sea_dense_attn.restype, lib.sea_dense_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp]
+    lib.sea_dense_workspace_bytes.restype, lib.sea_dense_workspace_bytes.argtypes = sz, [P]
+    lib.sea_dense_attn.restype, lib.sea_dense_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, sz, vp]
     lib.sea_profile_enable.restype, lib.sea_profile_enable.argtypes = ctypes.c_int, [ctypes.c_int]
     lib.sea_profile_collect.restype = ctypes.c_int
     lib.sea_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
@@ -192,13 +193,20 @@ def sea_forward(p: SeaParams, Q, K, V, W, O, A_hat=None, sel=None, idx=None, cnt
            "sea_forward")
 
 
-def sea_dense_attn(p: SeaParams, Q, K, V, O, stream=None):
+def sea_dense_workspace_bytes(p: SeaParams) -> int:
+    cp = p.c()
+    return int(_lib.sea_dense_workspace_bytes(ctypes.byref(cp)))
+
+
+def sea_dense_attn(p: SeaParams, Q, K, V, O, workspace, stream=None):
     n = p.B * p.H * p.T
     cp = p.c()
     _check(_lib.sea_dense_attn(ctypes.byref(cp), _ptr(Q, p.torch_dtype, n * p.d, "Q"),
                                _ptr(K, p.torch_dtype, n * p.d, "K"),
                                _ptr(V, p.torch_dtype, n * p.d, "V"),
-                               _ptr(O, p.torch_dtype, n * p.d, "O"), _stream(stream)),
+                               _ptr(O, p.torch_dtype, n * p.d, "O"),
+                               _ptr(workspace, None, None, "workspace"),
+                               workspace.numel() * workspace.element_size(), _stream(stream)),
            "sea_dense_attn")
 
 

@@ -140,12 +140,19 @@ size_t sea_workspace_bytes(const sea_params* p) {
   if (check_common(p) != SEA_OK || check_mask_params(p) != SEA_OK ||
       check_estimate_params(p) != SEA_OK || row_stride_of(p) < 0)
     return 0;
-  // estimator scratch, then A_hat, idx, cnt for sea_forward when the caller keeps none of them
+  // estimator scratch and A_hat, then either the tiled path's mask bits + compact K / V^T or
+  // the row-list path's idx + cnt (for when the caller keeps none of them)
   const size_t rows = static_cast<size_t>(p->B) * p->H * p->T;
+  const Shape s = make_shape(p, true);
   size_t bytes = estimate_ws(p);
   bytes += align256(rows * p->K * sizeof(float));
-  bytes += align256(rows * static_cast<size_t>(row_stride_of(p)) * sizeof(int32_t));
-  bytes += align256(rows * sizeof(int32_t));
+  if (tile_attn_supported(s, p->dtype, nullptr)) {
+    bytes += align256(rows * ((p->K + 31) / 32) * sizeof(uint32_t));
+    bytes += align256(tile_attn_workspace(s));
+  } else {
+    bytes += align256(rows * static_cast<size_t>(row_stride_of(p)) * sizeof(int32_t));
+    bytes += align256(rows * sizeof(int32_t));
+  }
   return bytes;
 }
 
@@ -178,7 +185,8 @@ int sea_topk_mask(const sea_params* p, const float* A_hat, int32_t* sel, int32_t
   if (!A_hat || !idx || !cnt) return SEA_EINVAL;
   if (row_stride_of(p) < 0) return SEA_ENOTSUP;
   const Shape s = make_shape(p, true);
-  const hipError_t e = launch_topk_mask(s, A_hat, sel, idx, cnt, static_cast<hipStream_t>(hip_stream));
+  const hipError_t e =
+      launch_topk_mask(s, A_hat, sel, idx, cnt, nullptr, static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? SEA_OK : fail_hip(e);
 }
 
@@ -213,9 +221,7 @@ int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V
   w += estimate_ws(p);
   float* A_hat = A_hat_opt ? A_hat_opt : reinterpret_cast<float*>(w);
   w += align256(rows * s.K * sizeof(float));
-  int32_t* idx = idx_opt ? idx_opt : reinterpret_cast<int32_t*>(w);
-  w += align256(rows * static_cast<size_t>(s.L) * sizeof(int32_t));
-  int32_t* cnt = cnt_opt ? cnt_opt : reinterpret_cast<int32_t*>(w);
+  const bool tiled = tile_attn_supported(s, p->dtype, nullptr);
 
   hipError_t e;
   if (p->dtype == SEA_BF16)
@@ -225,20 +231,43 @@ int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V
     e = launch_estimate_f64(s, static_cast<const float*>(Q), static_cast<const float*>(K),
                             static_cast<const float*>(W), A_hat, est_ws, st);
   if (e != hipSuccess) return fail_hip(e);
-  e = launch_topk_mask(s, A_hat, sel_opt, idx, cnt, st);
+  if (tiled) {
+    // column-structured mask: selection as bits, attention on 32-row tiles; the row lists are
+    // written only if the caller asked for them
+    uint32_t* mbits = reinterpret_cast<uint32_t*>(w);
+    w += align256(rows * ((s.K + 31) / 32) * sizeof(uint32_t));
+    e = launch_topk_mask(s, A_hat, sel_opt, idx_opt, cnt_opt, mbits, st);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_tile_attn(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                         static_cast<const uint16_t*>(V), mbits, static_cast<uint16_t*>(O), w, st);
+    return e == hipSuccess ? SEA_OK : fail_hip(e);
+  }
+  int32_t* idx = idx_opt ? idx_opt : reinterpret_cast<int32_t*>(w);
+  w += align256(rows * static_cast<size_t>(s.L) * sizeof(int32_t));
+  int32_t* cnt = cnt_opt ? cnt_opt : reinterpret_cast<int32_t*>(w);
+  e = launch_topk_mask(s, A_hat, sel_opt, idx, cnt, nullptr, st);
   if (e != hipSuccess) return fail_hip(e);
   e = launch_sparse_attn(s, p->dtype, Q, K, V, idx, cnt, s.L, O, st);
   return e == hipSuccess ? SEA_OK : fail_hip(e);
 }
 
+size_t sea_dense_workspace_bytes(const sea_params* p) {
+  if (check_common(p) != SEA_OK || p->dtype != SEA_BF16) return 0;
+  return dense_attn_workspace(make_shape(p, false));
+}
+
 int sea_dense_attn(const sea_params* p, const void* Q, const void* K, const void* V, void* O,
-                   void* hip_stream) {
+                   void* workspace, size_t workspace_bytes, void* hip_stream) {
   const int rc = check_common(p);
   if (rc != SEA_OK) return rc;
   if (!Q || !K || !V || !O) return SEA_EINVAL;
+  if (p->dtype != SEA_BF16) return SEA_ENOTSUP;
   const Shape s = make_shape(p, false);
+  if (!workspace || workspace_bytes < dense_attn_workspace(s) ||
+      reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+    return SEA_EWORKSPACE;
   const hipError_t e =
-      launch_dense_attn(s, p->dtype, Q, K, V, O, static_cast<hipStream_t>(hip_stream));
+      launch_dense_attn(s, p->dtype, Q, K, V, O, workspace, static_cast<hipStream_t>(hip_stream));
   if (e == hipErrorNotSupported) return SEA_ENOTSUP;
   return e == hipSuccess ? SEA_OK : fail_hip(e);
 }

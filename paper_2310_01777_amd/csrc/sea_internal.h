@@ -35,15 +35,23 @@ hipError_t launch_estimate_bf16(const Shape& s, const uint16_t* Q, const uint16_
                                 const uint16_t* W, float* A_hat, void* ws, hipStream_t st);
 size_t estimate_bf16_workspace(const Shape& s);
 
+// sel, idx, cnt, mbits may each be nullptr; mbits is [N][T][ceil(K/32)] selected-column bits
 hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, int32_t* idx,
-                            int32_t* cnt, hipStream_t st);
+                            int32_t* cnt, uint32_t* mbits, hipStream_t st);
+
+// Tiled MFMA attention over the column-structured mask (bf16, K | T, power-of-two keys per column)
+bool tile_attn_supported(const Shape& s, sea_dtype dt, int32_t* rlog_out);
+size_t tile_attn_workspace(const Shape& s);
+hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
+                            const uint32_t* mbits, uint16_t* O, void* ws, hipStream_t st);
+size_t dense_attn_workspace(const Shape& s);
 
 hipError_t launch_sparse_attn(const Shape& s, sea_dtype dt, const void* Q, const void* K,
                               const void* V, const int32_t* idx, const int32_t* cnt, int32_t L,
                               void* O, hipStream_t st);
 
 hipError_t launch_dense_attn(const Shape& s, sea_dtype dt, const void* Q, const void* K,
-                             const void* V, void* O, hipStream_t st);
+                             const void* V, void* O, void* ws, hipStream_t st);
 
 // ---- per-stage event timing (see sea_profile_enable) ----
 void stage_begin(sea_stage stage, hipStream_t st);

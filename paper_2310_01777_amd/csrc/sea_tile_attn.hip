@@ -1,0 +1,399 @@
+// Tiled attention on the CDNA4 matrix cores, used for (a) the sparse attention stage of
+// sea_forward when the mask has column structure (Sec. 3.1.1 rho, sigma, A* V with the mask of
+// Sec. 3.1 "Linear Sparse Attention Mask Generation") and (b) the dense baseline
+// softmax(QK^T)V (Sec. 3 "Preliminaries").
+//
+// Why tiles: every query row that selects compressed column c attends to the same r keys of
+// that column, so the keys any row of a head can use form one fixed "compact" list of U = K r
+// keys (all T keys when whole columns are emitted).  A wavefront takes 32 consecutive query
+// rows and walks that list in chunks of 32 keys; a chunk no row of the tile selected is
+// skipped, otherwise S^T = K_chunk Q_tile^T and O^T += V_chunk^T P^T run as
+// v_mfma_f32_32x32x16_bf16 with per-(row, column) mask bits applied to S in registers.  K/V
+// rows are thus read once per 32 query rows instead of once per row, and no T x T or T x L
+// buffer exists.  The softmax is the streaming form; each lane owns one query (the MFMA
+// output column), so row maxima and sums need a single cross-lane exchange.
+//
+// Operand layouts (32x32x16 bf16): A lane l = row l%32, contraction elems 8(l/32)..+7;
+// B lane l = col l%32, same elems; C reg i = row 8(i/4) + 4(l/32) + i%4, col l%32.
+// P leaves the first product in C layout (lane = query, regs = keys) and is fed back as the B
+// operand of the second product; its register order fixes which key each contraction slot
+// means, and the V^T fragments are fetched in that same order from a transposed copy of V.
+#include "sea_internal.h"
+
+namespace sea {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+struct TileArgs {
+  const uint16_t* Q;    // [N][T][64]
+  const uint16_t* Kc;   // [N][U][64] compact keys (== K when whole columns are emitted)
+  const uint16_t* Vct;  // [N][Upad / 64][64][64] transposed compact values in 64-key tiles, zero padded
+  const uint32_t* mbits;  // [N][T][KW] selected-column bits, nullptr for dense
+  uint16_t* O;          // [N][T][64]
+  const int32_t* seq_len;
+  int32_t N, H, T;
+  int32_t U, Upad;      // compact keys per head, padded to a multiple of 32
+  int32_t KW;           // mask words per row
+  int32_t rlog;         // log2(keys per column r)
+  int32_t w;            // column width in keys
+  int32_t causal;
+  float c;              // scale * log2(e)
+};
+
+// combine a value with the one held by the same lane of the other 32-lane half of the wave
+__device__ __forceinline__ float half_max(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// position in the sequence of compact key u
+__device__ __forceinline__ int32_t pos_of(int32_t u, int32_t rlog, int32_t w) {
+  const int32_t col = u >> rlog, i = u & ((1 << rlog) - 1);
+  return col * w + ((i * w) >> rlog);
+}
+
+// number of compact keys with position <= jmax (positions ascend with u)
+__device__ __forceinline__ int32_t compact_count(int32_t jmax, int32_t rlog, int32_t w) {
+  if (jmax < 0) return 0;
+  const int32_t col = jmax / w, delta = jmax - col * w;
+  const int32_t r = 1 << rlog;
+  const int32_t inside = min(r, ((delta + 1) * r + w - 1) / w);
+  return col * r + inside;
+}
+
+constexpr int kChunk = 64;   // keys staged in LDS per step (two 32-key MFMA sub-chunks)
+constexpr int kKRow = 72;    // halfwords per staged K row: 128 B + 16 B pad, conflict-free b128 reads
+constexpr int kVRow = 68;    // halfwords per staged V^T row: 128 B + 8 B pad, conflict-free b64 reads
+
+// Block = 4 waves = 128 consecutive query rows of one head (32 per wave).  The block walks the
+// compact key list in steps of 64 keys; each step's K rows and V^T tile are fetched once with
+// full-line 128-bit loads, parked in LDS (double buffered, one barrier per step) and read by
+// all four waves as MFMA fragments.
+// RLOG = log2(keys per column) for 1..16 keys per column, 5 for 32 or more (then a 32-key
+// sub-chunk lies inside one column and the actual shift is a.rlog).
+template <int RLOG, bool DENSE>
+__global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[2][kChunk * kKRow];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[2][kHeadDim * kVRow];
+  const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+  const int ql = lane & 31, g = lane >> 5;
+  const uint32_t wgs = (a.T + 127) / 128;  // blocks per head
+  const uint32_t lb = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int64_t head = lb / wgs;
+  // heavy (late, causal) blocks first within a head
+  const int32_t wg_tile = static_cast<int32_t>(wgs - 1 - lb % wgs);
+  const int32_t q0 = wg_tile * 128 + 32 * wid;  // first row of this wave
+  const int32_t t = q0 + ql;
+  const int32_t b = static_cast<int32_t>(head / a.H);
+  const int32_t len = a.seq_len ? min(max(a.seq_len[b], 0), a.T) : a.T;
+  const bool row_active = t < len;
+  const int32_t tq = min(t, a.T - 1);
+
+  const uint16_t* Qr = a.Q + (head * a.T + tq) * kHeadDim + 8 * g;
+  bf16x8 bq[4];
+#pragma unroll
+  for (int kc = 0; kc < 4; ++kc) bq[kc] = *reinterpret_cast<const bf16x8*>(Qr + 16 * kc);
+
+  const uint16_t* Kh = a.Kc + head * static_cast<int64_t>(a.U) * kHeadDim;
+  const uint16_t* Vh = a.Vct + head * static_cast<int64_t>(kHeadDim) * a.Upad;
+  const uint32_t* mrow = DENSE ? nullptr : a.mbits + (head * a.T + tq) * a.KW;
+
+  // keys the block / this wave can see: position <= min(last row, len - 1) when causal
+  const int32_t wg_hi = min(wg_tile * 128 + 127, a.T - 1);
+  const int32_t u_end_wg = compact_count(a.causal ? min(wg_hi, len - 1) : len - 1, a.rlog, a.w);
+  const int32_t t_hi = min(q0 + 31, a.T - 1);
+  const int32_t u_end = q0 < a.T ? compact_count(a.causal ? min(t_hi, len - 1) : len - 1, a.rlog, a.w) : 0;
+  // below this position every key is admissible for every active row of the wave
+  const int32_t j_free = a.causal ? min(q0, len - 1) : len - 1;
+  const int32_t my_jmax = a.causal ? min(t, len - 1) : len - 1;
+  const int32_t nsteps = (u_end_wg + kChunk - 1) / kChunk;
+
+  // staging roles: K rows (tid >> 3) and (tid >> 3) + 32, 16-byte part tid & 7; V^T rows alike
+  const int srow = tid >> 3, spart = tid & 7;
+  uint4 kreg[2], vreg[2];
+  auto fetch = [&](int32_t step) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int32_t u = min(step * kChunk + srow + 32 * h, a.U - 1);
+      kreg[h] = *reinterpret_cast<const uint4*>(Kh + static_cast<int64_t>(u) * kHeadDim + spart * 8);
+      vreg[h] = *reinterpret_cast<const uint4*>(Vh + static_cast<int64_t>(step) * (kHeadDim * kChunk) +
+                                                (srow + 32 * h) * kChunk + spart * 8);
+    }
+  };
+  auto park = [&](int stage) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      *reinterpret_cast<uint4*>(&Ks[stage][(srow + 32 * h) * kKRow + spart * 8]) = kreg[h];
+      uint2* vd = reinterpret_cast<uint2*>(&Vs[stage][(srow + 32 * h) * kVRow + spart * 8]);
+      vd[0] = make_uint2(vreg[h].x, vreg[h].y);
+      vd[1] = make_uint2(vreg[h].z, vreg[h].w);
+    }
+  };
+
+  floatx16 oacc[2];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) { oacc[0][i] = 0.f; oacc[1][i] = 0.f; }
+  float m_run = -INFINITY, l_run = 0.f;
+
+  if (nsteps > 0) {
+    fetch(0);
+    park(0);
+  }
+  __syncthreads();
+  for (int32_t step = 0; step < nsteps; ++step) {
+    const int stage = step & 1;
+    if (step + 1 < nsteps) fetch(step + 1);
+#pragma unroll
+    for (int sc = 0; sc < 2; ++sc) {
+      const int32_t u0 = step * kChunk + 32 * sc;
+      if (u0 >= u_end) break;  // wave-uniform: beyond what this wave's rows can see
+      uint32_t bits = 0xffffffffu;
+      if (!DENSE) {
+        const int32_t col0 = u0 >> (RLOG < 5 ? RLOG : a.rlog);  // first column of the sub-chunk
+        const uint32_t word = row_active ? mrow[col0 >> 5] : 0u;
+        bits = word >> (col0 & 31);
+        constexpr uint32_t ncol = RLOG >= 5 ? 1u : (32u >> RLOG);
+        constexpr uint32_t cmask = ncol >= 32 ? 0xffffffffu : ((1u << ncol) - 1u);
+        if (__ballot((bits & cmask) != 0u) == 0ull) continue;  // no row of the wave uses it
+      }
+      // S^T sub-chunk = K (32 keys x 64) . Q_tile^T
+      const uint16_t* Kr = &Ks[stage][(32 * sc + ql) * kKRow + 8 * g];
+      floatx16 s;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) s[i] = 0.f;
+#pragma unroll
+      for (int kc = 0; kc < 4; ++kc)
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(Kr + 16 * kc), bq[kc],
+                                                    s, 0, 0, 0);
+      // admissibility of each (key, query) entry: reg i <-> key slot 8(i/4) + 4g + i%4.
+      // Interior sub-chunks need only the column bits; the few that straddle the causal
+      // diagonal or the end of the sequence also compare key positions.
+      const bool boundary =
+          (u0 + 32 > u_end) || (pos_of(min(u0 + 31, a.U - 1), a.rlog, a.w) > j_free);
+      float mx = -INFINITY;
+      if (!boundary) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int32_t slot = 8 * (i >> 2) + 4 * g + (i & 3);
+          const bool ok = DENSE ? row_active : (((bits >> (RLOG >= 5 ? 0 : (slot >> RLOG))) & 1u) != 0u);
+          s[i] = ok ? s[i] : -INFINITY;
+          mx = fmaxf(mx, s[i]);
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int32_t slot = 8 * (i >> 2) + 4 * g + (i & 3);
+          const int32_t u = u0 + slot;
+          const int32_t pu = pos_of(min(u, a.U - 1), a.rlog, a.w);
+          const uint32_t okb = (DENSE ? (row_active ? 1u : 0u) : ((bits >> (RLOG >= 5 ? 0 : (slot >> RLOG))) & 1u)) &
+                               (u < a.U ? 1u : 0u) & (pu <= my_jmax ? 1u : 0u);
+          s[i] = okb ? s[i] : -INFINITY;
+          mx = fmaxf(mx, s[i]);
+        }
+      }
+      mx = half_max(mx);
+      const float m_new = fmaxf(m_run, mx);
+      if (__ballot(m_new > m_run) != 0ull) {  // rescale only when some row's maximum moved
+        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+        const float corr = __builtin_amdgcn_exp2f((m_run - m_safe) * a.c);
+        l_run *= corr;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) { oacc[0][i] *= corr; oacc[1][i] *= corr; }
+        m_run = m_new;
+      }
+      const float mc = ((m_run == -INFINITY) ? 0.f : m_run) * a.c;
+      float p[16];
+      float psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        p[i] = __builtin_amdgcn_exp2f(fmaf(s[i], a.c, -mc));
+        psum += p[i];
+      }
+      l_run += psum;
+      bf16x8 bp[2];
+#pragma unroll
+      for (int c2 = 0; c2 < 2; ++c2) {
+        bf16x2 h[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const floatx2 f2 = {p[8 * c2 + 2 * e], p[8 * c2 + 2 * e + 1]};
+          h[e] = __builtin_convertvector(f2, bf16x2);
+        }
+        const bf16x4 lo = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3);
+        const bf16x4 hi = __builtin_shufflevector(h[2], h[3], 0, 1, 2, 3);
+        bp[c2] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+      // O^T += V^T P^T; V^T fragments in the key order of the P registers
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        const uint16_t* Vr = &Vs[stage][(32 * mt + ql) * kVRow + 32 * sc + 4 * g];
+#pragma unroll
+        for (int c2 = 0; c2 < 2; ++c2) {
+          const bf16x4 lo = *reinterpret_cast<const bf16x4*>(Vr + 16 * c2);
+          const bf16x4 hi = *reinterpret_cast<const bf16x4*>(Vr + 16 * c2 + 8);
+          const bf16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bp[c2], oacc[mt], 0, 0, 0);
+        }
+      }
+    }
+    if (step + 1 < nsteps) park(stage ^ 1);
+    __syncthreads();
+  }
+  l_run = half_sum(l_run);
+  if (t < a.T) {
+    const float inv = (row_active && l_run > 0.f) ? 1.f / l_run : 0.f;
+    uint16_t* Or = a.O + (head * a.T + t) * kHeadDim;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        // regs 4 q4 .. 4 q4 + 3 <-> d = 32 mt + 8 q4 + 4 g + 0..3
+        const floatx2 f01 = {oacc[mt][4 * q4] * inv, oacc[mt][4 * q4 + 1] * inv};
+        const floatx2 f23 = {oacc[mt][4 * q4 + 2] * inv, oacc[mt][4 * q4 + 3] * inv};
+        const bf16x2 h01 = __builtin_convertvector(f01, bf16x2), h23 = __builtin_convertvector(f23, bf16x2);
+        *reinterpret_cast<bf16x4*>(Or + 32 * mt + 8 * q4 + 4 * g) = __builtin_shufflevector(h01, h23, 0, 1, 2, 3);
+      }
+  }
+}
+
+// Gathers the compact key list and writes V transposed in 64-key tiles: Kc[u][:] = K[pos(u)][:]
+// (only when the list is a strict subset of the keys), Vct[u / 64][d][u % 64] = V[pos(u)][d],
+// zero for u >= U.  Block = 256 threads = 64 compact keys x 64 dims, transposed through LDS.
+__global__ __launch_bounds__(256) void compact_kv_kernel(const uint16_t* __restrict__ K,
+                                                         const uint16_t* __restrict__ V,
+                                                         uint16_t* __restrict__ Kc,
+                                                         uint16_t* __restrict__ Vct, int32_t T, int32_t U,
+                                                         int32_t Upad, int32_t rlog, int32_t w) {
+  __shared__ uint16_t tile[64][64 + 2];
+  const int64_t head = blockIdx.y;
+  const int32_t u0 = blockIdx.x * 64;
+  // phase 1: each thread moves 16 B (8 dims) of 4 keys
+  const int c8 = threadIdx.x & 7, kq = threadIdx.x >> 3;  // kq in 0..31
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const int32_t ul = kq + 32 * half, u = u0 + ul;
+    uint4 kv = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
+    if (u < U) {
+      const int64_t src = (head * T + pos_of(u, rlog, w)) * kHeadDim + c8 * 8;
+      vv = *reinterpret_cast<const uint4*>(V + src);
+      if (Kc) {
+        kv = *reinterpret_cast<const uint4*>(K + src);
+        *reinterpret_cast<uint4*>(Kc + (head * U + u) * kHeadDim + c8 * 8) = kv;
+      }
+    }
+    const uint32_t wds[4] = {vv.x, vv.y, vv.z, vv.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      tile[ul][c8 * 8 + 2 * i] = static_cast<uint16_t>(wds[i] & 0xffffu);
+      tile[ul][c8 * 8 + 2 * i + 1] = static_cast<uint16_t>(wds[i] >> 16);
+    }
+  }
+  __syncthreads();
+  // phase 2: thread writes 16 consecutive keys of one dim
+  const int d = threadIdx.x >> 2, part = threadIdx.x & 3;
+  uint16_t* dst = Vct + head * static_cast<int64_t>(kHeadDim) * Upad +
+                  static_cast<int64_t>(blockIdx.x) * (kHeadDim * 64) + d * 64 + part * 16;
+#pragma unroll
+  for (int i = 0; i < 16; i += 2) {
+    if (u0 + part * 16 + i < Upad) {
+      const uint32_t pk = static_cast<uint32_t>(tile[part * 16 + i][d]) |
+                          (static_cast<uint32_t>(tile[part * 16 + i + 1][d]) << 16);
+      *reinterpret_cast<uint32_t*>(dst + i) = pk;
+    }
+  }
+}
+
+}  // namespace
+
+bool tile_attn_supported(const Shape& s, sea_dtype dt, int32_t* rlog_out) {
+  if (dt != SEA_BF16 || s.T % s.K != 0) return false;
+  const int32_t w = s.T / s.K;
+  const int32_t r = w < s.rep_cap ? w : s.rep_cap;
+  if (r <= 0 || (r & (r - 1)) != 0) return false;
+  int32_t rlog = 0;
+  while ((1 << rlog) < r) ++rlog;
+  if (static_cast<int64_t>(w) * r > (int64_t(1) << 30)) return false;
+  if (rlog_out) *rlog_out = rlog;
+  return true;
+}
+
+// bytes of scratch for the compact K (if needed) and transposed V
+size_t tile_attn_workspace(const Shape& s) {
+  int32_t rlog = 0;
+  if (!tile_attn_supported(s, SEA_BF16, &rlog)) return 0;
+  const int32_t w = s.T / s.K, r = 1 << rlog;
+  const int64_t U = static_cast<int64_t>(s.K) * r, Upad = (U + 63) / 64 * 64;
+  size_t bytes = static_cast<size_t>(s.N) * kHeadDim * Upad * 2;
+  bytes = (bytes + 255) & ~size_t(255);
+  if (r < w) bytes += (static_cast<size_t>(s.N) * U * kHeadDim * 2 + 255) & ~size_t(255);
+  return bytes;
+}
+
+hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
+                            const uint32_t* mbits, uint16_t* O, void* ws, hipStream_t st) {
+  int32_t rlog = 0;
+  if (!tile_attn_supported(s, SEA_BF16, &rlog)) return hipErrorNotSupported;
+  const int32_t w = s.T / s.K, r = 1 << rlog;
+  const int32_t U = s.K * r, Upad = (U + 63) / 64 * 64;
+  char* base = static_cast<char*>(ws);
+  uint16_t* Vct = reinterpret_cast<uint16_t*>(base);
+  uint16_t* Kc = nullptr;
+  if (r < w) {
+    const size_t vbytes = (static_cast<size_t>(s.N) * kHeadDim * Upad * 2 + 255) & ~size_t(255);
+    Kc = reinterpret_cast<uint16_t*>(base + vbytes);
+  }
+  StageScope scope(SEA_STAGE_SPARSE, st);
+  hipLaunchKernelGGL(compact_kv_kernel, dim3(Upad / 64, s.N), dim3(256), 0, st, K, V, Kc, Vct, s.T, U, Upad,
+                     rlog, w);
+  TileArgs a{};
+  a.Q = Q; a.Kc = Kc ? Kc : K; a.Vct = Vct; a.mbits = mbits; a.O = O; a.seq_len = s.seq_len;
+  a.N = s.N; a.H = s.H; a.T = s.T; a.U = U; a.Upad = Upad; a.KW = (s.K + 31) / 32;
+  a.rlog = rlog; a.w = w; a.causal = s.causal;
+  a.c = s.scale * kLog2e;
+  const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 127) / 128)), block(256);
+  switch (rlog) {
+    case 0: hipLaunchKernelGGL((tile_attn_kernel<0, false>), grid, block, 0, st, a); break;
+    case 1: hipLaunchKernelGGL((tile_attn_kernel<1, false>), grid, block, 0, st, a); break;
+    case 2: hipLaunchKernelGGL((tile_attn_kernel<2, false>), grid, block, 0, st, a); break;
+    case 3: hipLaunchKernelGGL((tile_attn_kernel<3, false>), grid, block, 0, st, a); break;
+    case 4: hipLaunchKernelGGL((tile_attn_kernel<4, false>), grid, block, 0, st, a); break;
+    default: hipLaunchKernelGGL((tile_attn_kernel<5, false>), grid, block, 0, st, a); break;
+  }
+  return hipGetLastError();
+}
+
+size_t dense_attn_workspace(const Shape& s) {
+  const int64_t Upad = (static_cast<int64_t>(s.T) + 63) / 64 * 64;
+  return (static_cast<size_t>(s.N) * kHeadDim * Upad * 2 + 255) & ~size_t(255);
+}
+
+hipError_t launch_dense_attn(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* V,
+                             void* O, void* ws, hipStream_t st) {
+  if (dt != SEA_BF16) return hipErrorNotSupported;
+  const int32_t U = s.T, Upad = (U + 63) / 64 * 64;
+  uint16_t* Vct = static_cast<uint16_t*>(ws);
+  StageScope scope(SEA_STAGE_DENSE, st);
+  // dense: one "column" per key (r = 1, w = 1), so pos(u) = u
+  hipLaunchKernelGGL(compact_kv_kernel, dim3(Upad / 64, s.N), dim3(256), 0, st,
+                     static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V),
+                     static_cast<uint16_t*>(nullptr), Vct, s.T, U, Upad, 0, 1);
+  TileArgs a{};
+  a.Q = static_cast<const uint16_t*>(Q); a.Kc = static_cast<const uint16_t*>(K); a.Vct = Vct;
+  a.mbits = nullptr; a.O = static_cast<uint16_t*>(O); a.seq_len = s.seq_len;
+  a.N = s.N; a.H = s.H; a.T = s.T; a.U = U; a.Upad = Upad; a.KW = 0; a.rlog = 0; a.w = 1;
+  a.causal = s.causal; a.c = s.scale * kLog2e;
+  const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 127) / 128)), block(256);
+  hipLaunchKernelGGL((tile_attn_kernel<0, true>), grid, block, 0, st, a);
+  return hipGetLastError();
+}
+
+}  // namespace sea

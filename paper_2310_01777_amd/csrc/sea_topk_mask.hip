@@ -28,7 +28,7 @@ __device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
 template <int SLOTS>
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
     Shape s, const float* __restrict__ A_hat, int32_t* __restrict__ sel, int32_t* __restrict__ idx,
-    int32_t* __restrict__ cnt) {
+    int32_t* __restrict__ cnt, uint32_t* __restrict__ mbits) {
   __shared__ int32_t sh_sel[kWavesPerBlock][SLOTS * kWave];
   __shared__ int32_t sh_off[kWavesPerBlock][SLOTS * kWave + 1];
   const int wid = threadIdx.x >> 6;
@@ -39,14 +39,19 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
   const int32_t t = static_cast<int32_t>(row % s.T);
   const int32_t b = static_cast<int32_t>((row / s.T) / s.H);
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
-  int32_t* irow = idx + row * s.L;
+  int32_t* irow = idx ? idx + row * s.L : nullptr;
   int32_t* srow = sel ? sel + row * s.k_hat : nullptr;
+  const int32_t kw = (s.K + 31) / 32;  // mask words per row
+  uint32_t* mrow = mbits ? mbits + row * kw : nullptr;
 
   if (t >= len) {  // inactive row
-    for (int32_t x = lane; x < s.L; x += kWave) irow[x] = -1;
+    if (irow)
+      for (int32_t x = lane; x < s.L; x += kWave) irow[x] = -1;
     if (srow)
       for (int32_t x = lane; x < s.k_hat; x += kWave) srow[x] = -1;
-    if (lane == 0) cnt[row] = 0;
+    if (mrow)
+      for (int32_t x = lane; x < kw; x += kWave) mrow[x] = 0u;
+    if (cnt && lane == 0) cnt[row] = 0;
     return;
   }
   const int32_t jmax = (s.causal && t < len - 1) ? t : len - 1;  // last admissible key
@@ -83,6 +88,10 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
     const bool take = (key[q] > tau) || take_eq;
     const uint64_t tk = __ballot(take);
     if (take) sh_sel[wid][n_sel + lanes_below(tk, lane)] = q * kWave + lane;
+    if (mrow && lane == 0) {  // selected-column bits: column c is bit c % 32 of word c / 32
+      if (2 * q < kw) mrow[2 * q] = static_cast<uint32_t>(tk);
+      if (2 * q + 1 < kw) mrow[2 * q + 1] = static_cast<uint32_t>(tk >> 32);
+    }
     n_sel += popc64(tk);
     need_eq -= min(need_eq, popc64(eq));
   }
@@ -91,6 +100,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
   if (srow)
     for (int32_t x = lane; x < s.k_hat; x += kWave) srow[x] = (x < n_sel) ? sh_sel[wid][x] : -1;
 
+  if (!irow && !cnt) return;
   // expansion: selected column c emits r keys start + floor(i w / r), i < r
   const bool uniform = (s.T % s.K) == 0;
   int32_t total;
@@ -108,7 +118,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
         j = c * w + static_cast<int32_t>((static_cast<int64_t>(i) * w) / r);
         if (j > jmax) j = -1;
       }
-      if (x < s.L) irow[x] = j;
+      if (irow && x < s.L) irow[x] = j;
       kept += popc64(__ballot(j >= 0));
     }
     total = kept;  // dropped keys are a suffix: only the last selected column can overrun jmax
@@ -125,7 +135,8 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
       sh_off[wid][n_sel] = acc;
     }
     __builtin_amdgcn_wave_barrier();
-    for (int32_t x = lane; x < s.L; x += kWave) irow[x] = -1;
+    if (irow)
+      for (int32_t x = lane; x < s.L; x += kWave) irow[x] = -1;
     __builtin_amdgcn_wave_barrier();
     int32_t kept = 0;
     for (int32_t si = 0; si < n_sel; ++si) {
@@ -136,7 +147,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
       const int32_t off = sh_off[wid][si];
       for (int32_t i = lane; i < r; i += kWave) {
         const int32_t j = s0 + static_cast<int32_t>((static_cast<int64_t>(i) * w) / r);
-        if (j <= jmax && off + i < s.L) irow[off + i] = j;
+        if (irow && j <= jmax && off + i < s.L) irow[off + i] = j;
       }
       // count kept keys of this column (uniform value across the wave)
       int32_t lo = 0, hi = r;  // first i with s0 + floor(i w / r) > jmax
@@ -149,23 +160,23 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
     }
     total = kept;
   }
-  if (lane == 0) cnt[row] = total;
+  if (cnt && lane == 0) cnt[row] = total;
 }
 
 }  // namespace
 
 hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, int32_t* idx,
-                            int32_t* cnt, hipStream_t st) {
+                            int32_t* cnt, uint32_t* mbits, hipStream_t st) {
   const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
   const uint32_t grid = static_cast<uint32_t>((nrows + kWavesPerBlock - 1) / kWavesPerBlock);
   const dim3 block(kWavesPerBlock * kWave);
   const int slots = (s.K + kWave - 1) / kWave;
   StageScope scope(SEA_STAGE_TOPK_MASK, st);
-  if (slots <= 1) hipLaunchKernelGGL(topk_mask_kernel<1>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt);
-  else if (slots <= 2) hipLaunchKernelGGL(topk_mask_kernel<2>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt);
-  else if (slots <= 4) hipLaunchKernelGGL(topk_mask_kernel<4>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt);
-  else if (slots <= 8) hipLaunchKernelGGL(topk_mask_kernel<8>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt);
-  else hipLaunchKernelGGL(topk_mask_kernel<16>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt);
+  if (slots <= 1) hipLaunchKernelGGL(topk_mask_kernel<1>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);
+  else if (slots <= 2) hipLaunchKernelGGL(topk_mask_kernel<2>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);
+  else if (slots <= 4) hipLaunchKernelGGL(topk_mask_kernel<4>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);
+  else if (slots <= 8) hipLaunchKernelGGL(topk_mask_kernel<8>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);
+  else hipLaunchKernelGGL(topk_mask_kernel<16>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);
   return hipGetLastError();
 }
 

@@ -70,6 +70,14 @@ SMALL_CASES = [
     _wl("bf16_budget", 1, 2, 512, 64, 16, 4, k_budget=24),
     _wl("bf16_wideK", 1, 1, 640, 64, 320, 40),
     _wl("bf16_K_eq_T", 1, 2, 96, 32, 96, 11),
+    # column-structured masks that take the tiled matrix-core attention: r = 4, 16, 64 whole
+    # columns, r = 8 sampled out of 32 (compact key list), bidirectional with padding
+    _wl("bf16_tile_r4", 1, 2, 256, 64, 64, 13),
+    _wl("bf16_tile_r16", 2, 2, 512, 64, 32, 9),
+    _wl("bf16_tile_r64", 1, 2, 520 - 8, 64, 8, 3),
+    _wl("bf16_tile_sampled", 1, 2, 512, 64, 16, 4, k_budget=32),
+    _wl("bf16_tile_sampled_bidir", 2, 2, 448, 64, 14, 5, k_budget=40, causal=False, pad_frac=0.3),
+    _wl("bf16_tile_tail", 1, 3, 328, 64, 41, 10),
 ]
 
 
@@ -129,6 +137,31 @@ def test_full_selection_reduces_to_dense_attention(sea, dtype, causal):
     want = torch.softmax(S.masked_fill(~keep, float("-inf")), -1) @ V
     want = (want * valid[:, None, :, None]).numpy()
     assert_close(to_np64(g["O"]), want, TOL[dtype], "O vs dense")
+
+
+@pytest.mark.parametrize("causal,pad", [(True, 0.0), (False, 0.0), (True, 0.3), (False, 0.3)])
+@pytest.mark.parametrize("T", [64, 200, 1000])
+def test_dense_baseline_matches_library_softmax(sea, causal, pad, T):
+    """sea_dense_attn (the quadratic baseline) against torch.softmax in fp64."""
+    wl = _wl("dense", 2, 2, T, 32, 8, 2, causal=causal, pad_frac=pad)
+    x = synth.make_inputs(wl)
+    xd = _dev(x)
+    p = _params(sea, wl, xd["seq_len"])
+    O = torch.empty_like(xd["Q"])
+    ws = torch.empty(sea.sea_dense_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    print(f"[case] dense T{T} causal{int(causal)} pad{pad}", flush=True)
+    sea.sea_dense_attn(p, xd["Q"], xd["K"], xd["V"], O, ws)
+    torch.cuda.synchronize()
+    Q, K, V = (x[k].to(torch.float64) for k in "QKV")
+    S = wl.scale * Q @ K.transpose(-1, -2)
+    sl = x["seq_len"] if x["seq_len"] is not None else torch.full((wl.B,), T, dtype=torch.int32)
+    valid = torch.arange(T)[None, :] < sl[:, None]
+    keep = valid[:, None, None, :].expand(wl.B, 1, T, T).clone()
+    if causal:
+        keep &= torch.tril(torch.ones(T, T, dtype=torch.bool))
+    want = torch.softmax(S.masked_fill(~keep, float("-inf")), -1) @ V
+    want = (want * valid[:, None, :, None]).numpy()
+    assert_close(to_np64(O), want, TOL["bf16"], "dense O")
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
