@@ -73,6 +73,7 @@ __device__ __forceinline__ int32_t compact_count(int32_t jmax, int32_t rlog, int
 constexpr int kChunk = 64;   // keys staged in LDS per step (two 32-key MFMA sub-chunks)
 constexpr int kKRow = 72;    // halfwords per staged K row: 128 B + 16 B pad, conflict-free b128 reads
 constexpr int kVRow = 68;    // halfwords per staged V^T row: 128 B + 8 B pad, conflict-free b64 reads
+constexpr int kMaxMaskWords = 32;  // K <= 1024
 
 // Block = 4 waves = 128 consecutive query rows of one head (32 per wave).  The block walks the
 // compact key list in steps of 64 keys; each step's K rows and V^T tile are fetched once with
@@ -84,7 +85,9 @@ template <int RLOG, bool DENSE>
 __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[2][kChunk * kKRow];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[2][kHeadDim * kVRow];
-  const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+  __shared__ uint32_t Ms[DENSE ? 1 : 128 * (kMaxMaskWords + 1)];  // selected-column bits of the 128 rows
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, keep it scalar
   const int ql = lane & 31, g = lane >> 5;
   const uint32_t wgs = (a.T + 127) / 128;  // blocks per head
   const uint32_t lb = xcd_contiguous(blockIdx.x, gridDim.x);
@@ -105,7 +108,18 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
 
   const uint16_t* Kh = a.Kc + head * static_cast<int64_t>(a.U) * kHeadDim;
   const uint16_t* Vh = a.Vct + head * static_cast<int64_t>(kHeadDim) * a.Upad;
-  const uint32_t* mrow = DENSE ? nullptr : a.mbits + (head * a.T + tq) * a.KW;
+  // mask words of the block's rows -> LDS (row stride KW + 1 words: conflict-free per-row reads)
+  const int mstride = a.KW + 1;
+  if (!DENSE) {
+    const int32_t row0 = wg_tile * 128;
+    const uint32_t* msrc = a.mbits + (head * a.T + row0) * a.KW;
+    const int32_t nwords = min(128, a.T - row0) * a.KW;
+    for (int32_t x = tid; x < 128 * a.KW; x += 256) {
+      const int32_t r = x / a.KW, wi = x - r * a.KW;
+      Ms[r * mstride + wi] = x < nwords ? msrc[x] : 0u;
+    }
+  }
+  const uint32_t* mrow = DENSE ? nullptr : &Ms[(32 * wid + ql) * mstride];
 
   // keys the block / this wave can see: position <= min(last row, len - 1) when causal
   const int32_t wg_hi = min(wg_tile * 128 + 127, a.T - 1);
@@ -119,25 +133,28 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
 
   // staging roles: K rows (tid >> 3) and (tid >> 3) + 32, 16-byte part tid & 7; V^T rows alike
   const int srow = tid >> 3, spart = tid & 7;
-  uint4 kreg[2], vreg[2];
-  auto fetch = [&](int32_t step) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int32_t u = min(step * kChunk + srow + 32 * h, a.U - 1);
-      kreg[h] = *reinterpret_cast<const uint4*>(Kh + static_cast<int64_t>(u) * kHeadDim + spart * 8);
-      vreg[h] = *reinterpret_cast<const uint4*>(Vh + static_cast<int64_t>(step) * (kHeadDim * kChunk) +
-                                                (srow + 32 * h) * kChunk + spart * 8);
-    }
-  };
-  auto park = [&](int stage) {
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      *reinterpret_cast<uint4*>(&Ks[stage][(srow + 32 * h) * kKRow + spart * 8]) = kreg[h];
-      uint2* vd = reinterpret_cast<uint2*>(&Vs[stage][(srow + 32 * h) * kVRow + spart * 8]);
-      vd[0] = make_uint2(vreg[h].x, vreg[h].y);
-      vd[1] = make_uint2(vreg[h].z, vreg[h].w);
-    }
-  };
+  uint4 kreg0, kreg1, vreg0, vreg1;
+#define SEA_FETCH(step_)                                                                             \
+  do {                                                                                               \
+    const int32_t ua_ = min((step_) * kChunk + srow, a.U - 1);                                        \
+    const int32_t ub_ = min((step_) * kChunk + srow + 32, a.U - 1);                                   \
+    kreg0 = *reinterpret_cast<const uint4*>(Kh + static_cast<int64_t>(ua_) * kHeadDim + spart * 8);   \
+    kreg1 = *reinterpret_cast<const uint4*>(Kh + static_cast<int64_t>(ub_) * kHeadDim + spart * 8);   \
+    const uint16_t* vt_ = Vh + static_cast<int64_t>(step_) * (kHeadDim * kChunk) + srow * kChunk + spart * 8; \
+    vreg0 = *reinterpret_cast<const uint4*>(vt_);                                                    \
+    vreg1 = *reinterpret_cast<const uint4*>(vt_ + 32 * kChunk);                                      \
+  } while (0)
+#define SEA_PARK(stage_)                                                                             \
+  do {                                                                                               \
+    *reinterpret_cast<uint4*>(&Ks[stage_][srow * kKRow + spart * 8]) = kreg0;                         \
+    *reinterpret_cast<uint4*>(&Ks[stage_][(srow + 32) * kKRow + spart * 8]) = kreg1;                  \
+    uint2* va_ = reinterpret_cast<uint2*>(&Vs[stage_][srow * kVRow + spart * 8]);                     \
+    uint2* vb_ = reinterpret_cast<uint2*>(&Vs[stage_][(srow + 32) * kVRow + spart * 8]);              \
+    va_[0] = make_uint2(vreg0.x, vreg0.y);                                                           \
+    va_[1] = make_uint2(vreg0.z, vreg0.w);                                                           \
+    vb_[0] = make_uint2(vreg1.x, vreg1.y);                                                           \
+    vb_[1] = make_uint2(vreg1.z, vreg1.w);                                                           \
+  } while (0)
 
   floatx16 oacc[2];
 #pragma unroll
@@ -145,13 +162,13 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   float m_run = -INFINITY, l_run = 0.f;
 
   if (nsteps > 0) {
-    fetch(0);
-    park(0);
+    SEA_FETCH(0);
+    SEA_PARK(0);
   }
   __syncthreads();
   for (int32_t step = 0; step < nsteps; ++step) {
     const int stage = step & 1;
-    if (step + 1 < nsteps) fetch(step + 1);
+    if (step + 1 < nsteps) SEA_FETCH(step + 1);
 #pragma unroll
     for (int sc = 0; sc < 2; ++sc) {
       const int32_t u0 = step * kChunk + 32 * sc;
@@ -245,9 +262,11 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
         }
       }
     }
-    if (step + 1 < nsteps) park(stage ^ 1);
+    if (step + 1 < nsteps) SEA_PARK(stage ^ 1);
     __syncthreads();
   }
+#undef SEA_FETCH
+#undef SEA_PARK
   l_run = half_sum(l_run);
   if (t < a.T) {
     const float inv = (row_active && l_run > 0.f) ? 1.f / l_run : 0.f;
