@@ -35,10 +35,10 @@
  *   - right padding: keys and rows >= seq_len[b] are inactive;
  *   - ties in the selection go to the lower column; a column with no admissible
  *     key is never selected;
- *   - reduced-precision mode (bf16 inputs): phi(Q) and the K x m key-side state
- *     phi(K)^T V_I (for causal rows: the prefix state of the row's own bucket)
- *     are rounded to an 8-bit significand, round-to-nearest-even; nothing else
- *     is rounded.
+ *   - reduced-precision mode (bf16 inputs): phi(Q), the K x m key-side state
+ *     phi(K)^T V_I and, for the keys of a causal row's own bucket, phi(k_j)
+ *     are rounded to an 8-bit significand, round-to-nearest-even; products are
+ *     summed without further rounding.
  *
  * Pins (tests, CPU only): k^ = K reproduces dense softmax attention computed by
  * a library softmax; the estimate converges to bucket sums of the exact softmax
@@ -120,11 +120,10 @@ int ref_estimate(const ref_params* p, const double* Q, const double* K,
   const double rs = sqrt(p->scale);
   double* phiK = (double*)malloc(sizeof(double) * T * m);
   double* state = (double*)malloc(sizeof(double) * KK * m); /* phi(K)^T V_I */
-  double* pref = (double*)malloc(sizeof(double) * m);
   double* phiQ = (double*)malloc(sizeof(double) * m);
   double* arg = (double*)malloc(sizeof(double) * m);
   double* y = (double*)malloc(sizeof(double) * d);
-  if (!phiK || !state || !pref || !phiQ || !arg || !y) return -1;
+  if (!phiK || !state || !phiQ || !arg || !y) return -1;
 
   for (int64_t b = 0; b < p->B; ++b) {
     const int64_t len = seq_len ? seq_len[b] : T;
@@ -173,22 +172,23 @@ int ref_estimate(const ref_params* p, const double* Q, const double* K,
           if (p->round8) phiQ[i] = ref_round8(phiQ[i]);
         }
         const int64_t ct = bucket_of(t, T, KK);
-        if (p->causal) {
-          /* prefix state of the row's own bucket: keys of the bucket up to t */
-          for (int64_t i = 0; i < m; ++i) pref[i] = 0.0;
-          for (int64_t j = block_start(ct, T, KK); j <= t; ++j)
-            for (int64_t i = 0; i < m; ++i) pref[i] += phiK[j * m + i];
-          if (p->round8)
-            for (int64_t i = 0; i < m; ++i) pref[i] = ref_round8(pref[i]);
-        }
         double rowsum = 0.0;
         for (int64_t c = 0; c < KK; ++c) {
-          const double* s;
-          if (!p->causal || c < ct) s = state + c * m;
-          else if (c == ct) s = pref;
-          else continue;
           double acc = 0.0;
-          for (int64_t i = 0; i < m; ++i) acc += phiQ[i] * s[i];
+          if (!p->causal || c < ct) {
+            /* every key of the column is admissible: phi(q_t) . (phi(K)^T V_I)[c] */
+            const double* s = state + c * m;
+            for (int64_t i = 0; i < m; ++i) acc += phiQ[i] * s[i];
+          } else if (c == ct) {
+            /* the row's own column: only its keys j <= t (causal FAVOR+ prefix), key by key */
+            for (int64_t j = block_start(ct, T, KK); j <= t; ++j)
+              for (int64_t i = 0; i < m; ++i) {
+                const double f = phiK[j * m + i];
+                acc += phiQ[i] * (p->round8 ? ref_round8(f) : f);
+              }
+          } else {
+            continue;
+          }
           Arow[c] = acc;
           rowsum += acc;
         }
@@ -197,7 +197,7 @@ int ref_estimate(const ref_params* p, const double* Q, const double* K,
       }
     }
   }
-  free(phiK); free(state); free(pref); free(phiQ); free(arg); free(y);
+  free(phiK); free(state); free(phiQ); free(arg); free(y);
   return 0;
 }
 

@@ -7,7 +7,8 @@
 //   causal row using the inclusive prefix of its own bucket instead of the full bucket sum.
 //
 // Rounding points (the only places a value is narrowed to bf16): phi(Q) after a power-of-two
-// row shift (which commutes with the rounding), the bucket sums, and the per-row prefixes.
+// row shift (which commutes with the rounding), the bucket sums, and phi(k_j) of the keys of a
+// causal row's own bucket (that column is summed key by key, products accumulated in fp32).
 //
 // All three GEMM-shaped steps are "NT" products whose operands are row-major with the
 // contraction index contiguous, which is exactly the register layout of
@@ -15,7 +16,7 @@
 // so fragments are loaded straight from memory with one 128-bit load per lane.
 //
 // Workspace layout: phiQ bf16 [N][T][m] | phiK f32 [N][T][m] | state bf16 [N][K][m] |
-// prefix bf16 [N][T][m] (causal only).
+// phiKb bf16 [N][T][m] (causal only).
 #include "sea_internal.h"
 
 namespace sea {
@@ -146,11 +147,12 @@ __global__ __launch_bounds__(256) void state_bf16_kernel(Shape s, const float* _
   const int32_t j0 = block_start(c, s.T, s.K), j1 = block_start(c + 1, s.T, s.K);
   const float* col = phiK + (head * s.T) * s.m + i;
   float acc = 0.f;
-  if (prefix) {
+  if (prefix) {  // also keep each key's features, rounded, for the causal diagonal column
     uint16_t* pf = prefix + (head * s.T) * s.m + i;
     for (int32_t j = j0; j < j1; ++j) {
-      acc += col[static_cast<int64_t>(j) * s.m];
-      pf[static_cast<int64_t>(j) * s.m] = f32_to_bf16(acc);
+      const float f = col[static_cast<int64_t>(j) * s.m];
+      acc += f;
+      pf[static_cast<int64_t>(j) * s.m] = f32_to_bf16(f);
     }
   } else {
     for (int32_t j = j0; j < j1; ++j) acc += col[static_cast<int64_t>(j) * s.m];
@@ -187,16 +189,20 @@ __global__ __launch_bounds__(256) void contract_bf16_kernel(
 #pragma unroll
     for (int kc = 0; kc < MC; ++kc) afrag[kc] = load_frag(qrow + kc * 32);
   }
-  // diagonal column of the causal rows: phiQ[t] . prefix[t], rows as lanes lr
+  // diagonal column of the causal rows: sum over the keys j <= t of the row's own bucket of
+  // phiQ[t] . phiKb[j]; rows as lanes lr
   float diag_lr = 0.f;
   if (s.causal) {
-    const uint16_t* prow = prefix + (head * s.T + ta) * s.m + 8 * lg;
-    if (MC > 0) {
+    const int32_t jb = block_start(bucket_of(ta, s.T, s.K), s.T, s.K);
+    for (int32_t j = jb; j <= ta; ++j) {
+      const uint16_t* prow = prefix + (head * s.T + j) * s.m + 8 * lg;
+      if (MC > 0) {
 #pragma unroll
-      for (int kc = 0; kc < MC; ++kc) diag_lr = dot8(afrag[kc], load_frag(prow + kc * 32), diag_lr);
-    } else {
-      for (int kc = 0; kc < mc; ++kc)
-        diag_lr = dot8(load_frag(qrow + kc * 32), load_frag(prow + kc * 32), diag_lr);
+        for (int kc = 0; kc < MC; ++kc) diag_lr = dot8(afrag[kc], load_frag(prow + kc * 32), diag_lr);
+      } else {
+        for (int kc = 0; kc < mc; ++kc)
+          diag_lr = dot8(load_frag(qrow + kc * 32), load_frag(prow + kc * 32), diag_lr);
+      }
     }
     diag_lr += __shfl_xor(diag_lr, 16, kWave);
     diag_lr += __shfl_xor(diag_lr, 32, kWave);
