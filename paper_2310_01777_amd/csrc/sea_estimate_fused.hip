@@ -1,0 +1,448 @@
+// Fused random-feature estimate for the common shapes (bf16, K | T, column width a power of two
+// up to 64, m in {32, 64, 128, 256}, K <= 256): two kernels, no feature tensor ever reaches HBM.
+// (Sec. 3 "Performer (FAVOR+)", Sec. 3.1 "Attention Matrix Estimation".)
+//
+//   key_state_kernel      phi(K) on the matrix cores -> per-column sums -> state (bf16, K x m)
+//   estimate_rows_kernel  phi(Q) on the matrix cores, kept in registers as MFMA fragments ->
+//                         A_hat tile = phi(Q) state^T (state streamed through LDS) -> causal
+//                         masking, the row's own column from phi(Q) phi(K_own)^T with a
+//                         lower-triangular mask -> row normalisation -> fp32 A_hat
+//
+// Both projections are computed transposed, C[feature][row] = W X^T with v_mfma_f32_16x16x32_bf16,
+// so lane l owns row l % 16 and, per 16-feature tile ft, the four features 16 ft + 4 (l / 16) + i.
+// Two consecutive tiles give a lane 8 values = one MFMA operand fragment; the contraction slot
+// <-> feature map this implies (slot 8 lg + e of chunk kc <-> feature 32 kc + 16 (e / 4) + 4 lg +
+// e % 4) is used consistently for phi(Q), phi(K) and the stored state ("fragment order"), so
+// accumulators feed the next product without any shuffle or memory round trip.
+#include "sea_internal.h"
+
+namespace sea {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWRow = 72;  // halfwords per staged W row (128 B + 16 B pad): conflict-free b128 reads
+
+__device__ __forceinline__ floatx4 mfma16(bf16x8 a, bf16x8 b, floatx4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ float sumsq8(bf16x8 v) {
+  const uint4 u = __builtin_bit_cast(uint4, v);
+  const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+  float a = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float lo = bf16lo_to_f32(w[i]), hi = bf16hi_to_f32(w[i]);
+    a = fmaf(lo, lo, a);
+    a = fmaf(hi, hi, a);
+  }
+  return a;
+}
+// eight floats (two feature tiles x four features) -> one operand fragment, RNE
+__device__ __forceinline__ bf16x8 pack8(const float* lo4, const float* hi4) {
+  uint4 u;
+  u.x = pack_bf16(lo4[0], lo4[1]);
+  u.y = pack_bf16(lo4[2], lo4[3]);
+  u.z = pack_bf16(hi4[0], hi4[1]);
+  u.w = pack_bf16(hi4[2], hi4[3]);
+  return __builtin_bit_cast(bf16x8, u);
+}
+
+// sum over the 16 lanes of a DPP row (lanes with equal l / 16); every lane gets the total
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x) {
+  const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false);
+  return x + __int_as_float(y);
+}
+constexpr int kQuadXor1 = 0xB1;        // quad_perm [1,0,3,2]
+constexpr int kQuadXor2 = 0x4E;        // quad_perm [2,3,0,1]
+constexpr int kRowHalfMirror = 0x141;  // lane i <-> 7 - i within each 8
+constexpr int kRowMirror = 0x140;      // lane i <-> 15 - i within each 16
+// all-reduce over aligned groups of W lanes (W = 1, 2, 4, 8, 16) of a row
+template <int W>
+__device__ __forceinline__ float group_sum(float x) {
+  if (W >= 2) x = dpp_add<kQuadXor1>(x);
+  if (W >= 4) x = dpp_add<kQuadXor2>(x);
+  if (W >= 8) x = dpp_add<kRowHalfMirror>(x);
+  if (W >= 16) x = dpp_add<kRowMirror>(x);
+  return x;
+}
+
+// stage W (m rows of 64 bf16) into LDS with padded rows
+__device__ __forceinline__ void stage_w(const uint16_t* __restrict__ W, uint16_t* Ws, int m, int tid) {
+  for (int x = tid; x < m * 8; x += 256) {
+    const int r = x >> 3, part = x & 7;
+    *reinterpret_cast<uint4*>(&Ws[r * kWRow + part * 8]) =
+        *reinterpret_cast<const uint4*>(W + r * kHeadDim + part * 8);
+  }
+}
+
+// exponent arguments (log2 domain) of 16 rows x m features: arg[ft][i] for feature 16 ft + 4 lg + i
+template <int MC>
+__device__ __forceinline__ void project(const uint16_t* Ws, bf16x8 x0, bf16x8 x1, int lr, int lg,
+                                        float c_dot, float bias, floatx4 (&arg)[2 * MC]) {
+#pragma unroll
+  for (int ft = 0; ft < 2 * MC; ++ft) {
+    const uint16_t* w = &Ws[(ft * 16 + lr) * kWRow + 8 * lg];
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    acc = mfma16(*reinterpret_cast<const bf16x8*>(w), x0, acc);
+    acc = mfma16(*reinterpret_cast<const bf16x8*>(w + 32), x1, acc);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) arg[ft][i] = fmaf(c_dot, acc[i], -bias);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// key side: state[c] = bf16( sum over the keys of column c of phi(k_j) ), in fragment order.
+// Block = 4 waves = 64 keys of one head.  WLOG = log2(column width), 0..6.
+// ------------------------------------------------------------------------------------------
+template <int MC, int WLOG>
+__global__ __launch_bounds__(256) void key_state_kernel(Shape s, const uint16_t* __restrict__ K,
+                                                        const uint16_t* __restrict__ W,
+                                                        uint16_t* __restrict__ state, float c_dot,
+                                                        float c_norm) {
+  constexpr int m = 32 * MC;
+  constexpr int w = 1 << WLOG;
+  __shared__ __attribute__((aligned(16))) uint16_t Ws[m * kWRow];
+  __shared__ float part[w > 16 ? 4 * m : 1];  // per-wave sums when a column spans several waves
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lr = lane & 15, lg = lane >> 4;
+  const uint32_t tiles = (s.T + 63) / 64;
+  const int64_t head = blockIdx.x / tiles;
+  const int32_t r0 = static_cast<int32_t>(blockIdx.x % tiles) * 64 + wid * 16;
+  stage_w(W, Ws, m, tid);
+  __syncthreads();
+  const int32_t t = r0 + lr, tc = min(t, s.T - 1);
+  const int32_t b = static_cast<int32_t>(head / s.H);
+  const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
+  const bool active = t < len;
+  const uint16_t* X = K + (head * s.T + tc) * kHeadDim;
+  const bf16x8 x0 = *reinterpret_cast<const bf16x8*>(X + 8 * lg);
+  const bf16x8 x1 = *reinterpret_cast<const bf16x8*>(X + 32 + 8 * lg);
+  float nx = sumsq8(x0) + sumsq8(x1);
+  nx += __shfl_xor(nx, 16, kWave);
+  nx += __shfl_xor(nx, 32, kWave);
+  floatx4 v[2 * MC];
+  project<MC>(Ws, x0, x1, lr, lg, c_dot, c_norm * nx, v);
+#pragma unroll
+  for (int ft = 0; ft < 2 * MC; ++ft)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float f = active ? __builtin_amdgcn_exp2f(v[ft][i]) : 0.f;
+      v[ft][i] = group_sum<(w < 16 ? w : 16)>(f);  // sum over the keys of the column inside this wave
+    }
+  uint16_t* sh = state + head * static_cast<int64_t>(s.K) * m;
+  if (w <= 16) {
+    // lanes at the first key of each column write that column (rows past T belong to no column)
+    if ((lr & (w - 1)) == 0 && t < s.T) {
+      uint16_t* dst = sh + static_cast<int64_t>(t >> WLOG) * m + 8 * lg;
+#pragma unroll
+      for (int kc = 0; kc < MC; ++kc) {
+        const float lo[4] = {v[2 * kc][0], v[2 * kc][1], v[2 * kc][2], v[2 * kc][3]};
+        const float hi[4] = {v[2 * kc + 1][0], v[2 * kc + 1][1], v[2 * kc + 1][2], v[2 * kc + 1][3]};
+        *reinterpret_cast<bf16x8*>(dst + 32 * kc) = pack8(lo, hi);
+      }
+    }
+  } else {
+    // column spans 2 or 4 waves of this block: combine the wave sums through LDS
+    if (lr == 0) {
+#pragma unroll
+      for (int kc = 0; kc < MC; ++kc)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part[wid * m + 32 * kc + 8 * lg + e] = v[2 * kc + (e >> 2)][e & 3];
+    }
+    __syncthreads();
+    constexpr int wpc = w / 16;            // waves per column
+    constexpr int cols = 64 / w;           // columns per block
+    const int32_t col0 = static_cast<int32_t>(blockIdx.x % tiles) * cols;
+    for (int x = tid; x < cols * m; x += 256) {
+      const int cl = x / m, p = x - cl * m;
+      float acc = 0.f;
+#pragma unroll
+      for (int q = 0; q < wpc; ++q) acc += part[(cl * wpc + q) * m + p];
+      if (col0 + cl < s.K) sh[static_cast<int64_t>(col0 + cl) * m + p] = f32_to_bf16(acc);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// query side.  Block = 4 waves = 64 rows of one head (16 per wave).
+// ------------------------------------------------------------------------------------------
+constexpr int kColStage = 32;   // columns of the state staged in LDS per step
+constexpr int kMaxColTiles = 16;  // K <= 256
+
+template <int MC, bool CAUSAL, int WLOG>
+__global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint16_t* __restrict__ Q,
+                                                            const uint16_t* __restrict__ K,
+                                                            const uint16_t* __restrict__ W,
+                                                            const uint16_t* __restrict__ state,
+                                                            float* __restrict__ A_hat, float c_dot,
+                                                            float c_norm) {
+  constexpr int m = 32 * MC;
+  constexpr int w = 1 << WLOG;
+  constexpr int kSRow = m + 8;  // halfwords per staged state row (+16 B pad): conflict-free b128 reads
+  __shared__ __attribute__((aligned(16))) uint16_t Ws[m * kWRow];
+  __shared__ __attribute__((aligned(16))) uint16_t Ss[2][kColStage * kSRow];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lr = lane & 15, lg = lane >> 4;
+  const uint32_t tiles = (s.T + 63) / 64;
+  const uint32_t lb = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int64_t head = lb / tiles;
+  const int32_t wg_r0 = static_cast<int32_t>(tiles - 1 - lb % tiles) * 64;  // late (long) rows first
+  const int32_t r0 = wg_r0 + wid * 16;
+  const int32_t b = static_cast<int32_t>(head / s.H);
+  const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
+
+  // state staging: 32 columns x m halfwords per step, contiguous in memory
+  const uint16_t* sh = state + head * static_cast<int64_t>(s.K) * m;
+  constexpr int kVecPerStage = kColStage * m / 8;      // 16-byte vectors per step
+  constexpr int kVecPerThread = kVecPerStage / 256;    // 1, 2 or 4 (m = 64..256); m = 32 -> 0
+  static_assert(MC >= 2, "m >= 64");
+  uint4 sreg0 = {0u, 0u, 0u, 0u}, sreg1 = sreg0, sreg2 = sreg0, sreg3 = sreg0;  // named: stay in VGPRs
+  const int32_t ncols_wg = CAUSAL ? min(s.K, (min(wg_r0 + 63, s.T - 1) >> WLOG) + 1) : s.K;
+  const int32_t nstages = (ncols_wg + kColStage - 1) / kColStage;
+#define SEA_SFETCH1(reg_, q_, st_)                                                              \
+  if (kVecPerThread > (q_)) {                                                                  \
+    const int x_ = tid + 256 * (q_);                                                           \
+    const int col_ = min((st_) * kColStage + x_ / (m / 8), s.K - 1);                            \
+    reg_ = *reinterpret_cast<const uint4*>(sh + static_cast<int64_t>(col_) * m + (x_ % (m / 8)) * 8); \
+  }
+#define SEA_SFETCH(st_)          \
+  SEA_SFETCH1(sreg0, 0, st_)     \
+  SEA_SFETCH1(sreg1, 1, st_)     \
+  SEA_SFETCH1(sreg2, 2, st_)     \
+  SEA_SFETCH1(sreg3, 3, st_)
+#define SEA_SPARK1(reg_, q_, buf_)                                                              \
+  if (kVecPerThread > (q_)) {                                                                  \
+    const int x_ = tid + 256 * (q_);                                                           \
+    *reinterpret_cast<uint4*>(&Ss[buf_][(x_ / (m / 8)) * kSRow + (x_ % (m / 8)) * 8]) = reg_;    \
+  }
+#define SEA_SPARK(buf_)          \
+  SEA_SPARK1(sreg0, 0, buf_)     \
+  SEA_SPARK1(sreg1, 1, buf_)     \
+  SEA_SPARK1(sreg2, 2, buf_)     \
+  SEA_SPARK1(sreg3, 3, buf_)
+
+  stage_w(W, Ws, m, tid);
+  if (nstages > 0) {
+    SEA_SFETCH(0);
+    SEA_SPARK(0);
+  }
+  __syncthreads();
+
+  // ---- phi(Q) of this wave's 16 rows, as contraction fragments ----
+  const int32_t t = r0 + lr, tc = min(t, s.T - 1);
+  bf16x8 afrag[MC];
+  {
+    const uint16_t* X = Q + (head * s.T + tc) * kHeadDim;
+    const bf16x8 x0 = *reinterpret_cast<const bf16x8*>(X + 8 * lg);
+    const bf16x8 x1 = *reinterpret_cast<const bf16x8*>(X + 32 + 8 * lg);
+    float nx = sumsq8(x0) + sumsq8(x1);
+    nx += __shfl_xor(nx, 16, kWave);
+    nx += __shfl_xor(nx, 32, kWave);
+    floatx4 arg[2 * MC];
+    project<MC>(Ws, x0, x1, lr, lg, c_dot, c_norm * nx, arg);
+    float amax = -INFINITY;
+#pragma unroll
+    for (int ft = 0; ft < 2 * MC; ++ft)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) amax = fmaxf(amax, arg[ft][i]);
+    amax = fmaxf(amax, __shfl_xor(amax, 16, kWave));
+    amax = fmaxf(amax, __shfl_xor(amax, 32, kWave));
+    const float shift = ceilf(amax);  // power-of-two row scale: commutes with the bf16 rounding
+    const bool active = t < len;
+#pragma unroll
+    for (int kc = 0; kc < MC; ++kc) {
+      float lo[4], hi[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        lo[i] = active ? __builtin_amdgcn_exp2f(arg[2 * kc][i] - shift) : 0.f;
+        hi[i] = active ? __builtin_amdgcn_exp2f(arg[2 * kc + 1][i] - shift) : 0.f;
+      }
+      afrag[kc] = pack8(lo, hi);
+    }
+  }
+  // accumulator rows of this lane: r0 + 4 lg + i
+  float diag[4] = {0.f, 0.f, 0.f, 0.f};
+  if (CAUSAL) {
+    // the row's own column: sum over keys j <= t of that column of phi(q_t) . phi(k_j).  With
+    // w <= 16 all those keys are among the wave's own 16 rows: S = phi(Q) phi(K_own)^T, masked.
+    static_assert(!CAUSAL || w <= 16, "wider columns take the unfused path");
+    const uint16_t* X = K + (head * s.T + tc) * kHeadDim;
+    const bf16x8 y0 = *reinterpret_cast<const bf16x8*>(X + 8 * lg);
+    const bf16x8 y1 = *reinterpret_cast<const bf16x8*>(X + 32 + 8 * lg);
+    float ny = sumsq8(y0) + sumsq8(y1);
+    ny += __shfl_xor(ny, 16, kWave);
+    ny += __shfl_xor(ny, 32, kWave);
+    floatx4 arg[2 * MC];
+    project<MC>(Ws, y0, y1, lr, lg, c_dot, c_norm * ny, arg);
+    floatx4 sd = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kc = 0; kc < MC; ++kc) {
+      float lo[4], hi[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        lo[i] = __builtin_amdgcn_exp2f(arg[2 * kc][i]);
+        hi[i] = __builtin_amdgcn_exp2f(arg[2 * kc + 1][i]);
+      }
+      sd = mfma16(afrag[kc], pack8(lo, hi), sd);  // rows = queries 4 lg + i, col = key lr
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int rq = 4 * lg + i;  // query row within the wave; key row within the wave is lr
+      const bool ok = (lr <= rq) && ((lr >> WLOG) == (rq >> WLOG));
+      diag[i] = group_sum<16>(ok ? sd[i] : 0.f);
+    }
+  }
+
+  // ---- A_hat tile = phi(Q) state^T, state streamed through LDS ----
+  floatx4 acc[kMaxColTiles];
+#pragma unroll
+  for (int ct = 0; ct < kMaxColTiles; ++ct) acc[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
+  const int32_t ncols_wave = CAUSAL ? min(s.K, (min(r0 + 15, s.T - 1) >> WLOG) + 1) : s.K;
+#pragma unroll
+  for (int st = 0; st < kMaxColTiles * 16 / kColStage; ++st) {
+    if (st < nstages) {
+      if (st + 1 < nstages) { SEA_SFETCH(st + 1); }
+      if (r0 < s.T && st * kColStage < ncols_wave) {
+#pragma unroll
+        for (int h = 0; h < kColStage / 16; ++h) {
+          const uint16_t* brow = &Ss[st & 1][(16 * h + lr) * kSRow + 8 * lg];
+          floatx4 a4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kc = 0; kc < MC; ++kc)
+            a4 = mfma16(afrag[kc], *reinterpret_cast<const bf16x8*>(brow + 32 * kc), a4);
+          acc[st * (kColStage / 16) + h] = a4;
+        }
+      }
+      if (st + 1 < nstages) { SEA_SPARK((st + 1) & 1); }
+      __syncthreads();
+    }
+  }
+#undef SEA_SFETCH
+#undef SEA_SFETCH1
+#undef SEA_SPARK
+#undef SEA_SPARK1
+  if (r0 >= s.T) return;  // no barrier below
+
+  // ---- masking, the own column, normalisation ----
+  int32_t trow[4], ctrow[4];
+  bool act[4];
+  float rsum[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    trow[i] = r0 + 4 * lg + i;
+    act[i] = trow[i] < len;
+    ctrow[i] = CAUSAL ? (min(trow[i], s.T - 1) >> WLOG) : s.K;  // first masked column is ctrow + 1
+  }
+#pragma unroll
+  for (int ct = 0; ct < kMaxColTiles; ++ct) {
+    const int32_t cc = ct * 16 + lr;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      float v = acc[ct][i];
+      if (CAUSAL && cc == ctrow[i]) v = diag[i];
+      if (cc > ctrow[i] || cc >= s.K || !act[i]) v = 0.f;
+      acc[ct][i] = v;
+      rsum[i] += v;
+    }
+  }
+  float* out = A_hat + (head * s.T) * s.K;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float r = group_sum<16>(rsum[i]);
+    const float inv = r > 0.f ? 1.f / r : 0.f;
+    if (trow[i] < s.T) {
+#pragma unroll
+      for (int ct = 0; ct < kMaxColTiles; ++ct) {
+        const int32_t cc = ct * 16 + lr;
+        if (cc < s.K) out[static_cast<int64_t>(trow[i]) * s.K + cc] = acc[ct][i] * inv;
+      }
+    }
+  }
+}
+
+int wlog_of(const Shape& s) {
+  if (s.T % s.K != 0) return -1;
+  const int32_t w = s.T / s.K;
+  if ((w & (w - 1)) != 0) return -1;
+  int l = 0;
+  while ((1 << l) < w) ++l;
+  return l;
+}
+
+}  // namespace
+
+bool estimate_fused_supported(const Shape& s) {
+  const int wl = wlog_of(s);
+  if (wl < 0 || wl > 6) return false;
+  if (s.causal && wl > 4) return false;  // the own column must sit inside a wave's 16 rows
+  if (s.m != 64 && s.m != 128 && s.m != 256) return false;
+  if (s.K > 256) return false;
+  return true;
+}
+
+size_t estimate_fused_workspace(const Shape& s) {
+  return (static_cast<size_t>(s.N) * s.K * s.m * 2 + 255) & ~size_t(255);
+}
+
+namespace {
+
+template <int MC, int WLOG>
+void launch_both(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W, float* A_hat,
+                 uint16_t* state, float c_dot, float c_norm, hipStream_t st) {
+  const uint32_t tiles = (s.T + 63) / 64;
+  const dim3 grid(static_cast<uint32_t>(s.N) * tiles), block(256);
+  {
+    StageScope scope(SEA_STAGE_STATE, st);
+    hipLaunchKernelGGL((key_state_kernel<MC, WLOG>), grid, block, 0, st, s, K, W, state, c_dot, c_norm);
+  }
+  {
+    StageScope scope(SEA_STAGE_CONTRACT, st);
+    if (s.causal) {
+      if constexpr (WLOG <= 4)
+        hipLaunchKernelGGL((estimate_rows_kernel<MC, true, WLOG>), grid, block, 0, st, s, Q, K, W, state, A_hat,
+                           c_dot, c_norm);
+    } else {
+      hipLaunchKernelGGL((estimate_rows_kernel<MC, false, WLOG>), grid, block, 0, st, s, Q, K, W, state, A_hat,
+                         c_dot, c_norm);
+    }
+  }
+}
+
+template <int MC>
+void launch_w(const Shape& s, int wl, const uint16_t* Q, const uint16_t* K, const uint16_t* W, float* A_hat,
+              uint16_t* state, float c_dot, float c_norm, hipStream_t st) {
+  switch (wl) {
+    case 0: launch_both<MC, 0>(s, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
+    case 1: launch_both<MC, 1>(s, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
+    case 2: launch_both<MC, 2>(s, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
+    case 3: launch_both<MC, 3>(s, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
+    case 4: launch_both<MC, 4>(s, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
+    case 5: launch_both<MC, 5>(s, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
+    default: launch_both<MC, 6>(s, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_estimate_fused(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W,
+                                 float* A_hat, void* ws, hipStream_t st) {
+  if (!estimate_fused_supported(s)) return hipErrorNotSupported;
+  uint16_t* state = static_cast<uint16_t*>(ws);
+  const double l2e = 1.4426950408889634;
+  const float c_dot = static_cast<float>(l2e * sqrt(static_cast<double>(s.scale)));
+  const float c_norm = static_cast<float>(l2e * 0.5 * static_cast<double>(s.scale));
+  const int wl = wlog_of(s);
+  switch (s.m) {
+    case 64: launch_w<2>(s, wl, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
+    case 128: launch_w<4>(s, wl, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
+    default: launch_w<8>(s, wl, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace sea

@@ -78,6 +78,12 @@ SMALL_CASES = [
     _wl("bf16_tile_sampled", 1, 2, 512, 64, 16, 4, k_budget=32),
     _wl("bf16_tile_sampled_bidir", 2, 2, 448, 64, 14, 5, k_budget=40, causal=False, pad_frac=0.3),
     _wl("bf16_tile_tail", 1, 3, 328, 64, 41, 10),
+    # fused estimator corner shapes: one key per column, two keys, 64-key columns (bidirectional),
+    # m = 256 with K = 256
+    _wl("bf16_fused_w1", 1, 2, 128, 64, 128, 9),
+    _wl("bf16_fused_w2", 1, 2, 192, 128, 96, 20),
+    _wl("bf16_fused_w64_bidir", 2, 2, 768, 64, 12, 4, causal=False, pad_frac=0.3),
+    _wl("bf16_fused_m256", 1, 2, 1024, 256, 256, 31),
 ]
 
 
