@@ -121,12 +121,14 @@ int sea_sparse_attn(const sea_params* p, const void* Q, const void* K, const voi
 
 /*
  * The whole forward pass (Fig. "model structure", phases 1 and 2 back to back) on one stream.
- * A_hat_opt, sel_opt, idx_opt, cnt_opt may each be NULL when the caller does not want that
- * intermediate; results are identical either way.
+ * A_hat_opt, sel_opt, idx_opt, cnt_opt, mhat_opt may each be NULL when the caller does not want
+ * that intermediate; results are identical either way.  mhat_opt receives the compressed binary
+ * mask M^ of Sec. 3.1 "Linear Sparse Attention Mask Generation", bit-packed:
+ * uint32 [B][H][T][ceil(K/32)], bit c % 32 of word c / 32 set iff column c is selected.
  */
 int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V, const void* W,
                 void* O, float* A_hat_opt, int32_t* sel_opt, int32_t* idx_opt, int32_t* cnt_opt,
-                void* workspace, size_t workspace_bytes, void* hip_stream);
+                uint32_t* mhat_opt, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
  * Quadratic attention A = softmax(scale QK^T), C = AV (Sec. 3 "Preliminaries"), causal and/or

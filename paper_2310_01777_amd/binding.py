@@ -53,7 +53,7 @@ def _load() -> ctypes.CDLL:
     lib.sea_estimate.restype, lib.sea_estimate.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, sz, vp]
     lib.sea_topk_mask.restype, lib.sea_topk_mask.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp]
     lib.sea_sparse_attn.restype, lib.sea_sparse_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, i32, vp, vp]
-    lib.sea_forward.restype, lib.sea_forward.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.sea_forward.restype, lib.sea_forward.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.sea_dense_workspace_bytes.restype, lib.sea_dense_workspace_bytes.argtypes = sz, [P]
     lib.sea_dense_attn.restype, lib.sea_dense_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, sz, vp]
     lib.sea_profile_enable.restype, lib.sea_profile_enable.argtypes = ctypes.c_int, [ctypes.c_int]
@@ -175,7 +175,7 @@ def sea_sparse_attn(p: SeaParams, Q, K, V, idx, cnt, row_stride, O, stream=None)
 
 
 def sea_forward(p: SeaParams, Q, K, V, W, O, A_hat=None, sel=None, idx=None, cnt=None,
-                workspace=None, stream=None):
+                workspace=None, stream=None, mhat=None):
     n = p.B * p.H * p.T
     L = sea_row_stride(p)
     cp = p.c()
@@ -188,6 +188,7 @@ def sea_forward(p: SeaParams, Q, K, V, W, O, A_hat=None, sel=None, idx=None, cnt
                             _ptr(sel, torch.int32, n * p.k_hat, "sel"),
                             _ptr(idx, torch.int32, n * L, "idx"),
                             _ptr(cnt, torch.int32, n, "cnt"),
+                            _ptr(mhat, torch.int32, n * ((p.K + 31) // 32), "mhat"),
                             _ptr(workspace, None, None, "workspace"),
                             workspace.numel() * workspace.element_size(), _stream(stream)),
            "sea_forward")
@@ -243,5 +244,6 @@ def alloc_outputs(p: SeaParams, device="cuda", aux=True):
         out.update(A_hat=torch.empty(*n, p.K, dtype=torch.float32, device=device),
                    sel=torch.empty(*n, p.k_hat, dtype=torch.int32, device=device),
                    idx=torch.empty(*n, L, dtype=torch.int32, device=device),
-                   cnt=torch.empty(*n, dtype=torch.int32, device=device))
+                   cnt=torch.empty(*n, dtype=torch.int32, device=device),
+                   mhat=torch.empty(*n, (p.K + 31) // 32, dtype=torch.int32, device=device))
     return out

@@ -204,7 +204,7 @@ int sea_sparse_attn(const sea_params* p, const void* Q, const void* K, const voi
 
 int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V, const void* W,
                 void* O, float* A_hat_opt, int32_t* sel_opt, int32_t* idx_opt, int32_t* cnt_opt,
-                void* workspace, size_t workspace_bytes, void* hip_stream) {
+                uint32_t* mhat_opt, void* workspace, size_t workspace_bytes, void* hip_stream) {
   int rc = check_common(p);
   if (rc == SEA_OK) rc = check_mask_params(p);
   if (rc == SEA_OK) rc = check_estimate_params(p);
@@ -224,6 +224,30 @@ int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V
   const bool tiled = tile_attn_supported(s, p->dtype, nullptr);
 
   hipError_t e;
+  if (tiled) {
+    // column-structured mask: selection as bits, attention on 128-row tiles; A_hat and the row
+    // lists are written only if the caller asked for them
+    uint32_t* mbits = mhat_opt ? mhat_opt : reinterpret_cast<uint32_t*>(w);
+    w += align256(rows * ((s.K + 31) / 32) * sizeof(uint32_t));
+    const bool need_lists = sel_opt || idx_opt || cnt_opt;
+    if (estimate_fused_supported(s)) {
+      // estimate and per-row top-k^ in one kernel; the scores never leave the registers
+      e = launch_estimate_fused(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                                static_cast<const uint16_t*>(W), (A_hat_opt || need_lists) ? A_hat : nullptr,
+                                mbits, est_ws, st);
+      if (e != hipSuccess) return fail_hip(e);
+      if (need_lists) e = launch_topk_mask(s, A_hat, sel_opt, idx_opt, cnt_opt, nullptr, st);
+    } else {
+      e = launch_estimate_bf16(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                               static_cast<const uint16_t*>(W), A_hat, est_ws, st);
+      if (e != hipSuccess) return fail_hip(e);
+      e = launch_topk_mask(s, A_hat, sel_opt, idx_opt, cnt_opt, mbits, st);
+    }
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_tile_attn(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                         static_cast<const uint16_t*>(V), mbits, static_cast<uint16_t*>(O), w, st);
+    return e == hipSuccess ? SEA_OK : fail_hip(e);
+  }
   if (p->dtype == SEA_BF16)
     e = launch_estimate_bf16(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
                              static_cast<const uint16_t*>(W), A_hat, est_ws, st);
@@ -231,21 +255,10 @@ int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V
     e = launch_estimate_f64(s, static_cast<const float*>(Q), static_cast<const float*>(K),
                             static_cast<const float*>(W), A_hat, est_ws, st);
   if (e != hipSuccess) return fail_hip(e);
-  if (tiled) {
-    // column-structured mask: selection as bits, attention on 32-row tiles; the row lists are
-    // written only if the caller asked for them
-    uint32_t* mbits = reinterpret_cast<uint32_t*>(w);
-    w += align256(rows * ((s.K + 31) / 32) * sizeof(uint32_t));
-    e = launch_topk_mask(s, A_hat, sel_opt, idx_opt, cnt_opt, mbits, st);
-    if (e != hipSuccess) return fail_hip(e);
-    e = launch_tile_attn(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
-                         static_cast<const uint16_t*>(V), mbits, static_cast<uint16_t*>(O), w, st);
-    return e == hipSuccess ? SEA_OK : fail_hip(e);
-  }
   int32_t* idx = idx_opt ? idx_opt : reinterpret_cast<int32_t*>(w);
   w += align256(rows * static_cast<size_t>(s.L) * sizeof(int32_t));
   int32_t* cnt = cnt_opt ? cnt_opt : reinterpret_cast<int32_t*>(w);
-  e = launch_topk_mask(s, A_hat, sel_opt, idx, cnt, nullptr, st);
+  e = launch_topk_mask(s, A_hat, sel_opt, idx, cnt, mhat_opt, st);
   if (e != hipSuccess) return fail_hip(e);
   e = launch_sparse_attn(s, p->dtype, Q, K, V, idx, cnt, s.L, O, st);
   return e == hipSuccess ? SEA_OK : fail_hip(e);

@@ -306,7 +306,7 @@ hipError_t launch_estimate_bf16(const Shape& s, const uint16_t* Q, const uint16_
                                 const uint16_t* W, float* A_hat, void* ws, hipStream_t st) {
   // common shapes: two fused kernels, features never leave the chip (its scratch, the K x m
   // state, fits in the front of this path's workspace)
-  if (estimate_fused_supported(s)) return launch_estimate_fused(s, Q, K, W, A_hat, ws, st);
+  if (estimate_fused_supported(s)) return launch_estimate_fused(s, Q, K, W, A_hat, nullptr, ws, st);
   const size_t ntm = static_cast<size_t>(s.N) * s.T * s.m;
   const size_t nkm = static_cast<size_t>(s.N) * s.K * s.m;
   char* base = static_cast<char*>(ws);

@@ -6,7 +6,8 @@
 //   estimate_rows_kernel  phi(Q) on the matrix cores, kept in registers as MFMA fragments ->
 //                         A_hat tile = phi(Q) state^T (state streamed through LDS) -> causal
 //                         masking, the row's own column from phi(Q) phi(K_own)^T with a
-//                         lower-triangular mask -> row normalisation -> fp32 A_hat
+//                         lower-triangular mask -> row normalisation -> fp32 A_hat (optional)
+//                         -> per-row top-k^ in registers -> selected-column bits (optional)
 //
 // Both projections are computed transposed, C[feature][row] = W X^T with v_mfma_f32_16x16x32_bf16,
 // so lane l owns row l % 16 and, per 16-feature tile ft, the four features 16 ft + 4 (l / 16) + i.
@@ -60,6 +61,14 @@ constexpr int kQuadXor2 = 0x4E;        // quad_perm [2,3,0,1]
 constexpr int kRowHalfMirror = 0x141;  // lane i <-> 7 - i within each 8
 constexpr int kRowMirror = 0x140;      // lane i <-> 15 - i within each 16
 // all-reduce over aligned groups of W lanes (W = 1, 2, 4, 8, 16) of a row
+template <int W>
+__device__ __forceinline__ uint32_t group_sum_u(uint32_t x) {  // integer counts
+  if (W >= 2) x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), kQuadXor1, 0xf, 0xf, false));
+  if (W >= 4) x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), kQuadXor2, 0xf, 0xf, false));
+  if (W >= 8) x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), kRowHalfMirror, 0xf, 0xf, false));
+  if (W >= 16) x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), kRowMirror, 0xf, 0xf, false));
+  return x;
+}
 template <int W>
 __device__ __forceinline__ float group_sum(float x) {
   if (W >= 2) x = dpp_add<kQuadXor1>(x);
@@ -178,7 +187,8 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
                                                             const uint16_t* __restrict__ K,
                                                             const uint16_t* __restrict__ W,
                                                             const uint16_t* __restrict__ state,
-                                                            float* __restrict__ A_hat, float c_dot,
+                                                            float* __restrict__ A_hat,
+                                                            uint32_t* __restrict__ mbits, float c_dot,
                                                             float c_norm) {
   constexpr int m = 32 * MC;
   constexpr int w = 1 << WLOG;
@@ -350,17 +360,115 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
       rsum[i] += v;
     }
   }
-  float* out = A_hat + (head * s.T) * s.K;
+  float* out = A_hat ? A_hat + (head * s.T) * s.K : nullptr;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const float r = group_sum<16>(rsum[i]);
     const float inv = r > 0.f ? 1.f / r : 0.f;
-    if (trow[i] < s.T) {
+#pragma unroll
+    for (int ct = 0; ct < kMaxColTiles; ++ct) acc[ct][i] *= inv;
+    if (out && trow[i] < s.T) {
 #pragma unroll
       for (int ct = 0; ct < kMaxColTiles; ++ct) {
         const int32_t cc = ct * 16 + lr;
-        if (cc < s.K) out[static_cast<int64_t>(trow[i]) * s.K + cc] = acc[ct][i] * inv;
+        if (cc < s.K) out[static_cast<int64_t>(trow[i]) * s.K + cc] = acc[ct][i];
       }
+    }
+  }
+  if (!mbits) return;
+
+  // ---- per-row top-k^ on the normalised scores, in registers (Sec. 3.1 "Grouped Top-k^
+  // Selection", per-query grouping).  Row 4 lg + i lives in the 16 lanes of group lg, one
+  // score per (column tile, lane).  The k^-th largest score is found by a bitwise search on
+  // order-preserving integer keys; counts are summed over the 16 lanes with DPP.  Scores are
+  // in [0, 1], so the key's two top bits are known and the search starts below them.
+  const int32_t ntile = (ncols_wave + 15) >> 4;  // column tiles holding candidates (wave-uniform)
+  uint32_t tau[4], cge[4], nsel[4];
+  uint32_t key[kMaxColTiles][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int32_t jmax = CAUSAL ? min(trow[i], len - 1) : len - 1;
+    const int32_t ncand = act[i] ? (jmax >> WLOG) + 1 : 0;
+    nsel[i] = static_cast<uint32_t>(min(s.k_hat, ncand));
+    tau[i] = 0x80000000u;
+    cge[i] = static_cast<uint32_t>(ncand);
+#pragma unroll
+    for (int ct = 0; ct < kMaxColTiles; ++ct) {
+      const int32_t cc = ct * 16 + lr;
+      key[ct][i] = cc < ncand ? (__float_as_uint(acc[ct][i] + 0.0f) | 0x80000000u) : 0u;
+    }
+  }
+#pragma unroll 1
+  for (int bit = 29; bit >= 0; --bit) {
+    // done when every row's count of keys >= tau equals its quota
+    bool pending = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) pending |= (cge[i] != nsel[i]) && (nsel[i] != 0u);
+    if (__ballot(pending) == 0ull) break;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t trial = tau[i] | (1u << bit);
+      uint32_t cnt = 0;
+#pragma unroll
+      for (int ct = 0; ct < kMaxColTiles; ++ct)
+        if (ct < ntile) cnt += (key[ct][i] >= trial) ? 1u : 0u;
+      cnt = group_sum_u<16>(cnt);
+      const bool take = cnt >= nsel[i];
+      tau[i] = take ? trial : tau[i];
+      cge[i] = take ? cnt : cge[i];
+    }
+  }
+  // selection: keys >= tau; when more keys than the quota tie at tau (exact duplicates at the
+  // boundary), the lowest columns among them win
+  uint32_t selbits[4];  // bit ct set: column 16 ct + lr of row 4 lg + i is selected
+  bool excess = false;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) excess |= (cge[i] != nsel[i]) && (nsel[i] != 0u);
+  if (__ballot(excess) == 0ull) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint32_t bits = 0;
+#pragma unroll
+      for (int ct = 0; ct < kMaxColTiles; ++ct)
+        bits |= (nsel[i] != 0u && key[ct][i] >= tau[i]) ? (1u << ct) : 0u;
+      selbits[i] = bits;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint32_t cgt = 0;
+#pragma unroll
+      for (int ct = 0; ct < kMaxColTiles; ++ct) cgt += (key[ct][i] > tau[i]) ? 1u : 0u;
+      cgt = group_sum_u<16>(cgt);
+      int32_t need_eq = static_cast<int32_t>(nsel[i]) - static_cast<int32_t>(cgt);
+      uint32_t bits = 0;
+#pragma unroll
+      for (int ct = 0; ct < kMaxColTiles; ++ct) {
+        const uint32_t ky = key[ct][i];
+        const bool eq = (ky == tau[i]) && (nsel[i] != 0u);
+        const uint64_t eqm = __ballot(eq);
+        const uint32_t field = static_cast<uint32_t>(eqm >> (16 * lg)) & 0xffffu;  // this row's lanes
+        const int32_t below = __popc(field & ((1u << lr) - 1u));
+        const bool take = (nsel[i] != 0u) && ((ky > tau[i]) || (eq && below < need_eq));
+        bits |= take ? (1u << ct) : 0u;
+        need_eq -= min(need_eq, static_cast<int32_t>(__popc(field)));
+      }
+      selbits[i] = bits;
+    }
+  }
+  // mask words: word j holds columns 32 j .. 32 j + 31 = tiles 2 j (low half) and 2 j + 1
+  const int32_t kw = (s.K + 31) >> 5;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (trow[i] >= s.T) continue;
+    uint32_t* mrow = mbits + (head * s.T + trow[i]) * kw;
+#pragma unroll
+    for (int j = 0; j < kMaxColTiles / 2; ++j) {
+      const uint64_t b0 = __ballot((selbits[i] >> (2 * j)) & 1u);
+      const uint64_t b1 = __ballot((selbits[i] >> (2 * j + 1)) & 1u);
+      const uint32_t word = (static_cast<uint32_t>(b0 >> (16 * lg)) & 0xffffu) |
+                            ((static_cast<uint32_t>(b1 >> (16 * lg)) & 0xffffu) << 16);
+      if (lr == j && j < kw) mrow[j] = word;
     }
   }
 }
@@ -393,7 +501,7 @@ namespace {
 
 template <int MC, int WLOG>
 void launch_both(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W, float* A_hat,
-                 uint16_t* state, float c_dot, float c_norm, hipStream_t st) {
+                 uint32_t* mbits, uint16_t* state, float c_dot, float c_norm, hipStream_t st) {
   const uint32_t tiles = (s.T + 63) / 64;
   const dim3 grid(static_cast<uint32_t>(s.N) * tiles), block(256);
   {
@@ -405,32 +513,32 @@ void launch_both(const Shape& s, const uint16_t* Q, const uint16_t* K, const uin
     if (s.causal) {
       if constexpr (WLOG <= 4)
         hipLaunchKernelGGL((estimate_rows_kernel<MC, true, WLOG>), grid, block, 0, st, s, Q, K, W, state, A_hat,
-                           c_dot, c_norm);
+                           mbits, c_dot, c_norm);
     } else {
       hipLaunchKernelGGL((estimate_rows_kernel<MC, false, WLOG>), grid, block, 0, st, s, Q, K, W, state, A_hat,
-                         c_dot, c_norm);
+                         mbits, c_dot, c_norm);
     }
   }
 }
 
 template <int MC>
 void launch_w(const Shape& s, int wl, const uint16_t* Q, const uint16_t* K, const uint16_t* W, float* A_hat,
-              uint16_t* state, float c_dot, float c_norm, hipStream_t st) {
+              uint32_t* mbits, uint16_t* state, float c_dot, float c_norm, hipStream_t st) {
   switch (wl) {
-    case 0: launch_both<MC, 0>(s, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
-    case 1: launch_both<MC, 1>(s, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
-    case 2: launch_both<MC, 2>(s, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
-    case 3: launch_both<MC, 3>(s, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
-    case 4: launch_both<MC, 4>(s, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
-    case 5: launch_both<MC, 5>(s, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
-    default: launch_both<MC, 6>(s, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
+    case 0: launch_both<MC, 0>(s, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
+    case 1: launch_both<MC, 1>(s, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
+    case 2: launch_both<MC, 2>(s, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
+    case 3: launch_both<MC, 3>(s, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
+    case 4: launch_both<MC, 4>(s, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
+    case 5: launch_both<MC, 5>(s, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
+    default: launch_both<MC, 6>(s, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
   }
 }
 
 }  // namespace
 
 hipError_t launch_estimate_fused(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W,
-                                 float* A_hat, void* ws, hipStream_t st) {
+                                 float* A_hat, uint32_t* mbits, void* ws, hipStream_t st) {
   if (!estimate_fused_supported(s)) return hipErrorNotSupported;
   uint16_t* state = static_cast<uint16_t*>(ws);
   const double l2e = 1.4426950408889634;
@@ -438,9 +546,9 @@ hipError_t launch_estimate_fused(const Shape& s, const uint16_t* Q, const uint16
   const float c_norm = static_cast<float>(l2e * 0.5 * static_cast<double>(s.scale));
   const int wl = wlog_of(s);
   switch (s.m) {
-    case 64: launch_w<2>(s, wl, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
-    case 128: launch_w<4>(s, wl, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
-    default: launch_w<8>(s, wl, Q, K, W, A_hat, state, c_dot, c_norm, st); break;
+    case 64: launch_w<2>(s, wl, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
+    case 128: launch_w<4>(s, wl, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
+    default: launch_w<8>(s, wl, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
   }
   return hipGetLastError();
 }

@@ -37,8 +37,10 @@ size_t estimate_bf16_workspace(const Shape& s);
 // fused two-kernel estimator for K | T, power-of-two column width, m in {64,128,256}, K <= 256
 bool estimate_fused_supported(const Shape& s);
 size_t estimate_fused_workspace(const Shape& s);
+// A_hat and mbits ([N][T][ceil(K/32)] selected-column bits of the per-row top-k^) may each be
+// nullptr; at least one should be given
 hipError_t launch_estimate_fused(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W,
-                                 float* A_hat, void* ws, hipStream_t st);
+                                 float* A_hat, uint32_t* mbits, void* ws, hipStream_t st);
 
 // sel, idx, cnt, mbits may each be nullptr; mbits is [N][T][ceil(K/32)] selected-column bits
 hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, int32_t* idx,

@@ -77,7 +77,7 @@ def test_argument_validation_returns_codes_not_crashes(sea):
     assert lib.sea_topk_mask(ctypes.byref(cp), None, None, None, None, None) == sea.SEA_EINVAL
     assert lib.sea_sparse_attn(ctypes.byref(cp), None, None, None, None, None, 8, None, None) == sea.SEA_EINVAL
     assert lib.sea_forward(ctypes.byref(cp), None, None, None, None, None, None, None, None, None,
-                           None, 0, None) == sea.SEA_EINVAL
+                           None, None, 0, None) == sea.SEA_EINVAL
     m48 = P(1, 1, 128, 64, 48, 16, 4).c()
     one = ctypes.c_void_p(256)
     assert lib.sea_estimate(ctypes.byref(m48), one, one, one, one, one, 1 << 30, None) == sea.SEA_ENOTSUP

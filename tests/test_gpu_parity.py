@@ -45,7 +45,7 @@ def _gpu_forward(sea, wl, x):
     print(f"[case] {wl.name} B{wl.B} H{wl.H} T{wl.T} m{wl.m} K{wl.K} kh{wl.k_hat} kb{wl.k_budget} "
           f"causal{int(wl.causal)} {wl.dtype}", flush=True)
     sea.sea_forward(p, xd["Q"], xd["K"], xd["V"], xd["W"], out["O"], out["A_hat"], out["sel"],
-                    out["idx"], out["cnt"], ws)
+                    out["idx"], out["cnt"], ws, mhat=out["mhat"])
     torch.cuda.synchronize()
     return p, xd, {k: v.cpu() for k, v in out.items()}
 
@@ -55,6 +55,19 @@ def _oracle_forward(wl, x, rows=None):
     sl = None if x["seq_len"] is None else x["seq_len"].numpy()
     return p, oracle.forward(p, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), to_np64(x["W"]),
                              seq_len=sl, rows=rows)
+
+
+def _unpack_mhat(mhat, K):
+    """int32 words [..., ceil(K/32)] -> bool [..., K]"""
+    words = mhat.astype(np.uint32)
+    bits = (words[..., :, None] >> np.arange(32, dtype=np.uint32)) & 1
+    return bits.reshape(*mhat.shape[:-1], -1)[..., :K].astype(bool)
+
+
+def _sel_to_mask(sel, K):
+    m = np.zeros(sel.shape[:-1] + (K + 1,), dtype=bool)
+    np.put_along_axis(m, np.where(sel >= 0, sel, K), True, axis=-1)
+    return m[..., :K]
 
 
 SMALL_CASES = [
@@ -105,6 +118,8 @@ def test_forward_matches_oracle(sea, wl):
     assert np.array_equal(g["sel"].numpy(), sel_s)
     assert np.array_equal(g["idx"].numpy(), idx_s)
     assert np.array_equal(g["cnt"].numpy(), cnt_s)
+    # the bit-packed mask the attention stage consumed names exactly the same columns
+    assert np.array_equal(_unpack_mhat(g["mhat"].numpy(), wl.K), _sel_to_mask(sel_s, wl.K))
 
     # a6 stage-wise: oracle sparse attention over the GPU's lists
     O_s = oracle.sparse_attn(po, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), idx_s, cnt_s)
@@ -273,6 +288,17 @@ def test_optional_outputs_do_not_change_results(sea):
     sea.sea_forward(p, xd["Q"], xd["K"], xd["V"], xd["W"], O2, None, None, None, None, ws)
     torch.cuda.synchronize()
     assert torch.equal(O2.cpu(), g["O"])
+    # only the packed mask requested: the scores stay on chip, the selection must not change
+    for wl2 in (wl, synth.get_workload("c2"), synth.get_workload("c5")):
+        x2 = synth.make_inputs(wl2)
+        p2, xd2, g2 = _gpu_forward(sea, wl2, x2)
+        O3 = torch.empty_like(xd2["Q"])
+        mh = torch.empty_like(g2["mhat"], device="cuda")
+        ws2 = sea.alloc_workspace(p2)
+        sea.sea_forward(p2, xd2["Q"], xd2["K"], xd2["V"], xd2["W"], O3, None, None, None, None, ws2, mhat=mh)
+        torch.cuda.synchronize()
+        assert torch.equal(mh.cpu(), g2["mhat"]), wl2.name
+        assert torch.equal(O3.cpu(), g2["O"]), wl2.name
 
 
 # ---- full-size configurations, in the launch configuration bench.py times, on sampled rows ----
@@ -305,6 +331,7 @@ def test_full_size_sampled_rows(sea, name):
         assert np.array_equal(g["sel"][b, h][rows].numpy()[None, None], sel_s)
         assert np.array_equal(g["idx"][b, h][rows].numpy()[None, None], idx_s)
         assert np.array_equal(g["cnt"][b, h][rows].numpy()[None, None], cnt_s)
+        assert np.array_equal(_unpack_mhat(g["mhat"][b, h][rows].numpy(), wl.K), _sel_to_mask(sel_s[0, 0], wl.K))
         O_s = oracle.sparse_attn(po, to_np64(xs["Q"]), to_np64(xs["K"]), to_np64(xs["V"]), idx_s, cnt_s,
                                  rows=rows)
         assert_close(to_np64(g["O"][b, h][rows])[None, None], O_s, tol, f"O head {bh}")
