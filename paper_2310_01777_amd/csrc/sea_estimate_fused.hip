@@ -407,6 +407,8 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
     if (__ballot(pending) == 0ull) break;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
+      // skip the slot once its four rows (one per lane group) are settled
+      if (__ballot((cge[i] != nsel[i]) && (nsel[i] != 0u)) == 0ull) continue;
       const uint32_t trial = tau[i] | (1u << bit);
       uint32_t cnt = 0;
 #pragma unroll
