@@ -105,6 +105,10 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   bf16x8 bq[4];
 #pragma unroll
   for (int kc = 0; kc < 4; ++kc) bq[kc] = *reinterpret_cast<const bf16x8*>(Qr + 16 * kc);
+  // Re-define the fragments through an empty asm: inside the loop they then count as plain
+  // register values, not as results of memory loads the loop's own prefetch could be queued behind.
+#pragma unroll
+  for (int kc = 0; kc < 4; ++kc) asm volatile("" : "+v"(bq[kc]));
 
   const uint16_t* Kh = a.Kc + head * static_cast<int64_t>(a.U) * kHeadDim;
   const uint16_t* Vh = a.Vct + head * static_cast<int64_t>(kHeadDim) * a.Upad;
