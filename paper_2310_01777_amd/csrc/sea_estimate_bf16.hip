@@ -299,6 +299,7 @@ size_t estimate_bf16_workspace(const Shape& s) {
   const size_t nkm = static_cast<size_t>(s.N) * s.K * s.m;
   size_t bytes = ntm * 2 + ntm * 4 + ((nkm * 2 + 255) & ~size_t(255));
   if (s.causal) bytes += ntm * 2;
+  if (estimate_fused_supported(s)) bytes = max(bytes, estimate_fused_workspace(s));
   return bytes;
 }
 

@@ -1,5 +1,6 @@
 // Fused random-feature estimate for the common shapes (bf16, K | T, column width a power of two
-// up to 64, m in {32, 64, 128, 256}, K <= 256): two kernels, no feature tensor ever reaches HBM.
+// up to 128, m in {64, 128, 256}, K <= 256): two kernels; no feature tensor reaches HBM except,
+// for causal columns wider than 16 keys, the rounded per-key features the own-column term needs.
 // (Sec. 3 "Performer (FAVOR+)", Sec. 3.1 "Attention Matrix Estimation".)
 //
 //   key_state_kernel      phi(K) on the matrix cores -> per-column sums -> state (bf16, K x m)
@@ -107,21 +108,26 @@ __device__ __forceinline__ void project(const uint16_t* Ws, bf16x8 x0, bf16x8 x1
 // Block = 4 waves = 64 keys of one head.  WLOG = log2(column width), 0..6.
 // ------------------------------------------------------------------------------------------
 template <int MC, int WLOG>
-__global__ __launch_bounds__(256) void key_state_kernel(Shape s, const uint16_t* __restrict__ K,
-                                                        const uint16_t* __restrict__ W,
-                                                        uint16_t* __restrict__ state, float c_dot,
-                                                        float c_norm) {
+__global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
+    Shape s, const uint16_t* __restrict__ K, const uint16_t* __restrict__ W, uint16_t* __restrict__ state,
+    uint16_t* __restrict__ phiKb, float c_dot, float c_norm) {
   constexpr int m = 32 * MC;
   constexpr int w = 1 << WLOG;
+  constexpr int kWaves = w > 64 ? w / 16 : 4;  // waves per block: a column never spans two blocks
+  constexpr int kRows = 16 * kWaves;
   __shared__ __attribute__((aligned(16))) uint16_t Ws[m * kWRow];
-  __shared__ float part[w > 16 ? 4 * m : 1];  // per-wave sums when a column spans several waves
+  __shared__ float part[w > 16 ? kWaves * m : 1];  // per-wave sums when a column spans several waves
   const int tid = threadIdx.x, lane = tid & 63;
   const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 15, lg = lane >> 4;
-  const uint32_t tiles = (s.T + 63) / 64;
+  const uint32_t tiles = (s.T + kRows - 1) / kRows;
   const int64_t head = blockIdx.x / tiles;
-  const int32_t r0 = static_cast<int32_t>(blockIdx.x % tiles) * 64 + wid * 16;
-  stage_w(W, Ws, m, tid);
+  const int32_t r0 = static_cast<int32_t>(blockIdx.x % tiles) * kRows + wid * 16;
+  for (int x = tid; x < m * 8; x += 64 * kWaves) {
+    const int r = x >> 3, part8 = x & 7;
+    *reinterpret_cast<uint4*>(&Ws[r * kWRow + part8 * 8]) =
+        *reinterpret_cast<const uint4*>(W + r * kHeadDim + part8 * 8);
+  }
   __syncthreads();
   const int32_t t = r0 + lr, tc = min(t, s.T - 1);
   const int32_t b = static_cast<int32_t>(head / s.H);
@@ -138,10 +144,23 @@ __global__ __launch_bounds__(256) void key_state_kernel(Shape s, const uint16_t*
 #pragma unroll
   for (int ft = 0; ft < 2 * MC; ++ft)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float f = active ? __builtin_amdgcn_exp2f(v[ft][i]) : 0.f;
-      v[ft][i] = group_sum<(w < 16 ? w : 16)>(f);  // sum over the keys of the column inside this wave
+    for (int i = 0; i < 4; ++i) v[ft][i] = active ? __builtin_amdgcn_exp2f(v[ft][i]) : 0.f;
+  if (phiKb && t < s.T) {
+    // per-key features, rounded, in fragment order: read back by the query side for the keys
+    // of a causal row's own column that precede its wave
+    uint16_t* dst = phiKb + (head * s.T + t) * m + 8 * lg;
+#pragma unroll
+    for (int kc = 0; kc < MC; ++kc) {
+      const float lo[4] = {v[2 * kc][0], v[2 * kc][1], v[2 * kc][2], v[2 * kc][3]};
+      const float hi[4] = {v[2 * kc + 1][0], v[2 * kc + 1][1], v[2 * kc + 1][2], v[2 * kc + 1][3]};
+      *reinterpret_cast<bf16x8*>(dst + 32 * kc) = pack8(lo, hi);
     }
+  }
+#pragma unroll
+  for (int ft = 0; ft < 2 * MC; ++ft)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      v[ft][i] = group_sum<(w < 16 ? w : 16)>(v[ft][i]);  // sum over the keys of the column inside this wave
   uint16_t* sh = state + head * static_cast<int64_t>(s.K) * m;
   if (w <= 16) {
     // lanes at the first key of each column write that column (rows past T belong to no column)
@@ -155,7 +174,7 @@ __global__ __launch_bounds__(256) void key_state_kernel(Shape s, const uint16_t*
       }
     }
   } else {
-    // column spans 2 or 4 waves of this block: combine the wave sums through LDS
+    // column spans several waves of this block: combine the wave sums through LDS
     if (lr == 0) {
 #pragma unroll
       for (int kc = 0; kc < MC; ++kc)
@@ -164,9 +183,9 @@ __global__ __launch_bounds__(256) void key_state_kernel(Shape s, const uint16_t*
     }
     __syncthreads();
     constexpr int wpc = w / 16;            // waves per column
-    constexpr int cols = 64 / w;           // columns per block
+    constexpr int cols = kRows / w;        // columns per block
     const int32_t col0 = static_cast<int32_t>(blockIdx.x % tiles) * cols;
-    for (int x = tid; x < cols * m; x += 256) {
+    for (int x = tid; x < cols * m; x += 64 * kWaves) {
       const int cl = x / m, p = x - cl * m;
       float acc = 0.f;
 #pragma unroll
@@ -187,6 +206,7 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
                                                             const uint16_t* __restrict__ K,
                                                             const uint16_t* __restrict__ W,
                                                             const uint16_t* __restrict__ state,
+                                                            const uint16_t* __restrict__ phiKb,
                                                             float* __restrict__ A_hat,
                                                             uint32_t* __restrict__ mbits, float c_dot,
                                                             float c_norm) {
@@ -278,9 +298,9 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
   // accumulator rows of this lane: r0 + 4 lg + i
   float diag[4] = {0.f, 0.f, 0.f, 0.f};
   if (CAUSAL) {
-    // the row's own column: sum over keys j <= t of that column of phi(q_t) . phi(k_j).  With
-    // w <= 16 all those keys are among the wave's own 16 rows: S = phi(Q) phi(K_own)^T, masked.
-    static_assert(!CAUSAL || w <= 16, "wider columns take the unfused path");
+    // the row's own column: sum over keys j <= t of that column of phi(q_t) . phi(k_j).  Those
+    // keys are the wave's own 16 rows (S = phi(Q) phi(K_own)^T with a lower-triangular, same-column
+    // mask) and, for columns wider than 16, the 16-key tiles of the column before the wave.
     const uint16_t* X = K + (head * s.T + tc) * kHeadDim;
     const bf16x8 y0 = *reinterpret_cast<const bf16x8*>(X + 8 * lg);
     const bf16x8 y1 = *reinterpret_cast<const bf16x8*>(X + 32 + 8 * lg);
@@ -303,9 +323,20 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int rq = 4 * lg + i;  // query row within the wave; key row within the wave is lr
-      const bool ok = (lr <= rq) && ((lr >> WLOG) == (rq >> WLOG));
-      diag[i] = group_sum<16>(ok ? sd[i] : 0.f);
+      const bool ok = (lr <= rq) && (w >= 16 || (lr >> WLOG) == (rq >> WLOG));
+      sd[i] = ok ? sd[i] : 0.f;
     }
+    if (w > 16 && r0 < s.T) {
+      // earlier tiles of the same column: every key precedes every row of the wave
+      const int32_t tile0 = ((r0 >> WLOG) << WLOG) >> 4, tile1 = r0 >> 4;
+      for (int32_t kt = tile0; kt < tile1; ++kt) {
+        const uint16_t* src = phiKb + (head * s.T + kt * 16 + lr) * m + 8 * lg;
+#pragma unroll
+        for (int kc = 0; kc < MC; ++kc) sd = mfma16(afrag[kc], *reinterpret_cast<const bf16x8*>(src + 32 * kc), sd);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) diag[i] = group_sum<16>(sd[i]);
   }
 
   // ---- A_hat tile = phi(Q) state^T, state streamed through LDS ----
@@ -488,52 +519,55 @@ int wlog_of(const Shape& s) {
 
 bool estimate_fused_supported(const Shape& s) {
   const int wl = wlog_of(s);
-  if (wl < 0 || wl > 6) return false;
-  if (s.causal && wl > 4) return false;  // the own column must sit inside a wave's 16 rows
+  if (wl < 0 || wl > 7) return false;  // a column of 256 keys or more would span key-side blocks
   if (s.m != 64 && s.m != 128 && s.m != 256) return false;
   if (s.K > 256) return false;
   return true;
 }
 
 size_t estimate_fused_workspace(const Shape& s) {
-  return (static_cast<size_t>(s.N) * s.K * s.m * 2 + 255) & ~size_t(255);
+  size_t bytes = (static_cast<size_t>(s.N) * s.K * s.m * 2 + 255) & ~size_t(255);  // state
+  if (s.causal && wlog_of(s) > 4) bytes += static_cast<size_t>(s.N) * s.T * s.m * 2;  // phiKb
+  return bytes;
 }
 
 namespace {
 
 template <int MC, int WLOG>
 void launch_both(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W, float* A_hat,
-                 uint32_t* mbits, uint16_t* state, float c_dot, float c_norm, hipStream_t st) {
-  const uint32_t tiles = (s.T + 63) / 64;
-  const dim3 grid(static_cast<uint32_t>(s.N) * tiles), block(256);
+                 uint32_t* mbits, uint16_t* state, uint16_t* phiKb, float c_dot, float c_norm, hipStream_t st) {
+  constexpr int kKeyWaves = (1 << WLOG) > 64 ? (1 << WLOG) / 16 : 4;
   {
     StageScope scope(SEA_STAGE_STATE, st);
-    hipLaunchKernelGGL((key_state_kernel<MC, WLOG>), grid, block, 0, st, s, K, W, state, c_dot, c_norm);
+    const uint32_t ktiles = (s.T + 16 * kKeyWaves - 1) / (16 * kKeyWaves);
+    hipLaunchKernelGGL((key_state_kernel<MC, WLOG>), dim3(static_cast<uint32_t>(s.N) * ktiles),
+                       dim3(64 * kKeyWaves), 0, st, s, K, W, state, phiKb, c_dot, c_norm);
   }
   {
     StageScope scope(SEA_STAGE_CONTRACT, st);
-    if (s.causal) {
-      if constexpr (WLOG <= 4)
-        hipLaunchKernelGGL((estimate_rows_kernel<MC, true, WLOG>), grid, block, 0, st, s, Q, K, W, state, A_hat,
-                           mbits, c_dot, c_norm);
-    } else {
-      hipLaunchKernelGGL((estimate_rows_kernel<MC, false, WLOG>), grid, block, 0, st, s, Q, K, W, state, A_hat,
-                         mbits, c_dot, c_norm);
-    }
+    const uint32_t tiles = (s.T + 63) / 64;
+    const dim3 grid(static_cast<uint32_t>(s.N) * tiles), block(256);
+    if (s.causal)
+      hipLaunchKernelGGL((estimate_rows_kernel<MC, true, WLOG>), grid, block, 0, st, s, Q, K, W, state, phiKb,
+                         A_hat, mbits, c_dot, c_norm);
+    else
+      hipLaunchKernelGGL((estimate_rows_kernel<MC, false, WLOG>), grid, block, 0, st, s, Q, K, W, state, phiKb,
+                         A_hat, mbits, c_dot, c_norm);
   }
 }
 
 template <int MC>
 void launch_w(const Shape& s, int wl, const uint16_t* Q, const uint16_t* K, const uint16_t* W, float* A_hat,
-              uint32_t* mbits, uint16_t* state, float c_dot, float c_norm, hipStream_t st) {
+              uint32_t* mbits, uint16_t* state, uint16_t* phiKb, float c_dot, float c_norm, hipStream_t st) {
   switch (wl) {
-    case 0: launch_both<MC, 0>(s, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
-    case 1: launch_both<MC, 1>(s, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
-    case 2: launch_both<MC, 2>(s, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
-    case 3: launch_both<MC, 3>(s, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
-    case 4: launch_both<MC, 4>(s, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
-    case 5: launch_both<MC, 5>(s, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
-    default: launch_both<MC, 6>(s, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
+    case 0: launch_both<MC, 0>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
+    case 1: launch_both<MC, 1>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
+    case 2: launch_both<MC, 2>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
+    case 3: launch_both<MC, 3>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
+    case 4: launch_both<MC, 4>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
+    case 5: launch_both<MC, 5>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
+    case 6: launch_both<MC, 6>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
+    default: launch_both<MC, 7>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
   }
 }
 
@@ -543,14 +577,18 @@ hipError_t launch_estimate_fused(const Shape& s, const uint16_t* Q, const uint16
                                  float* A_hat, uint32_t* mbits, void* ws, hipStream_t st) {
   if (!estimate_fused_supported(s)) return hipErrorNotSupported;
   uint16_t* state = static_cast<uint16_t*>(ws);
+  const int wl = wlog_of(s);
+  uint16_t* phiKb = nullptr;
+  if (s.causal && wl > 4)
+    phiKb = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) +
+                                        ((static_cast<size_t>(s.N) * s.K * s.m * 2 + 255) & ~size_t(255)));
   const double l2e = 1.4426950408889634;
   const float c_dot = static_cast<float>(l2e * sqrt(static_cast<double>(s.scale)));
   const float c_norm = static_cast<float>(l2e * 0.5 * static_cast<double>(s.scale));
-  const int wl = wlog_of(s);
   switch (s.m) {
-    case 64: launch_w<2>(s, wl, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
-    case 128: launch_w<4>(s, wl, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
-    default: launch_w<8>(s, wl, Q, K, W, A_hat, mbits, state, c_dot, c_norm, st); break;
+    case 64: launch_w<2>(s, wl, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
+    case 128: launch_w<4>(s, wl, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
+    default: launch_w<8>(s, wl, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
   }
   return hipGetLastError();
 }

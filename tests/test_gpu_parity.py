@@ -97,6 +97,9 @@ SMALL_CASES = [
     _wl("bf16_fused_w2", 1, 2, 192, 128, 96, 20),
     _wl("bf16_fused_w64_bidir", 2, 2, 768, 64, 12, 4, causal=False, pad_frac=0.3),
     _wl("bf16_fused_m256", 1, 2, 1024, 256, 256, 31),
+    # causal columns wider than a wave's 16 rows: the own-column term reads earlier key tiles
+    _wl("bf16_fused_w128_causal", 1, 2, 1024 + 128, 64, 9, 3, k_budget=48),
+    _wl("bf16_fused_w32_causal_pad", 2, 2, 640, 128, 20, 6, k_budget=48, pad_frac=0.3),
 ]
 
 
