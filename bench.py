@@ -19,6 +19,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+# HBM bytes per launch of the sparse-attention kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (scaled by the copy-kernel factors 2.0 / 1.0); see profiles/sea_forward_<workload>.md
+MEASURED_TRAFFIC_BYTES = {"c2": 39.5e6 + 12.6e6, "c3": 218.3e6 + 67.1e6}
 
 
 def parse():
@@ -62,6 +65,24 @@ def cpu_baseline(wl, x, budget_s):
     return {"value": tokens / wall, "unit": "tokens/s", "cores": int(out["threads"]), "kind": "oracle",
             "sample": f"first {n} of {nheads} heads of {wl.name} (full T={wl.T}), fp64 C oracle, "
                       f"{wall:.2f} s wall; one head on one thread {one:.2f} s"}
+
+
+def issued_tile_flops(wl, seq_len):
+    """Flops of the 32-key x 32-query tiles the tiled attention visits (launch geometry only):
+    each wave of 32 rows walks the compact key list up to the last key its rows may see."""
+    w = wl.T // wl.K
+    r = w if wl.k_budget == 0 else min(w, max(1, wl.k_budget // wl.k_hat))
+    total = 0
+    for b in range(wl.B):
+        ln = wl.T if seq_len is None else int(seq_len[b])
+        for q0 in range(0, wl.T, 32):
+            jmax = min(q0 + 31, wl.T - 1, ln - 1) if wl.causal else ln - 1
+            if jmax < 0 or q0 >= wl.T:
+                continue
+            col, delta = divmod(jmax, w)
+            u_end = col * r + min(r, -(-(delta + 1) * r // w))
+            total += -(-u_end // 32)
+    return float(total) * wl.H * 32 * 32 * wl.d * 4
 
 
 def main():
@@ -119,26 +140,63 @@ def main():
     tokens = wl.B * wl.T
     ms_per_step = elapsed / args.steps * 1e3
     value = tokens * args.steps / elapsed
+    avg = {k: (v[0] / v[1]) for k, v in stages.items() if v[1] > 0}   # ms per launch
 
-    # roofline of the dominant kernel: sparse attention, bound by gathered bytes.
-    # algorithmic bytes per (query, key) pair: one K row + one V row + one int32 index;
-    # per query row: q in, o out.
+    # ---- roofline of the dominant kernel: the sparse attention stage ----
+    # Per (query, key) pair the stage does 4 d flops and, in the per-row gather accounting, moves
+    # one K row + one V row + one index; per query row q in and o out.
     es = 2 if wl.dtype == "bf16" else 4
     nrows = wl.B * wl.H * wl.T
-    sparse_ms, sparse_n = stages["sparse"]
-    sparse_avg_ms = sparse_ms / max(sparse_n, 1)
+    sparse_ms = avg.get("sparse", 0.0)
+    algo_flops = 4.0 * wl.d * pairs
     algo_bytes = pairs * (2 * wl.d * es + 4) + nrows * (2 * wl.d * es + 4)
-    achieved = algo_bytes / (sparse_avg_ms * 1e-3) / 1e9 if sparse_avg_ms > 0 else 0.0
-    roofline = {"kernel": "sparse_attn", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                "avg_kernel_ms": sparse_avg_ms, "algorithmic_bytes": algo_bytes, "pairs": pairs}
-    # estimator: issued matrix-core flops (two projections + contraction, dense count)
-    est_ms = sum(stages[k][0] for k in ("features", "state", "contract")) / max(stages["contract"][1], 1)
+    tiled = "compact" in avg            # the tiled matrix-core kernel ran (bf16, column-structured mask)
+    if tiled:
+        issued = issued_tile_flops(wl, x["seq_len"])
+        ach = algo_flops / (sparse_ms * 1e-3) / 1e12
+        roofline = {"kernel": "tile_attn_kernel", "bound": "mfma", "achieved": ach,
+                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "avg_kernel_ms": sparse_ms,
+                    "algorithmic_flops": algo_flops,
+                    "issued_flops": issued, "issued_tflops": issued / (sparse_ms * 1e-3) / 1e12,
+                    "pairs": pairs,
+                    "note": "achieved counts only the selected (query, key) pairs (4 d flops each); issued "
+                            "counts every pair of the 32x32 tiles the kernel visits"}
+    else:
+        ach = algo_bytes / (sparse_ms * 1e-3) / 1e9
+        roofline = {"kernel": "sparse_attn_kernel", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None, "avg_kernel_ms": sparse_ms,
+                    "algorithmic_bytes": algo_bytes, "pairs": pairs}
+    # the same stage in the per-row gather accounting (bytes a row-by-row gather would move)
+    gather_equiv = {"algorithmic_bytes": algo_bytes,
+                    "GBps": algo_bytes / (sparse_ms * 1e-3) / 1e9 if sparse_ms > 0 else 0.0,
+                    "frac_of_hbm_peak": algo_bytes / (sparse_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if sparse_ms > 0 else 0.0}
+    # estimator (features + state + contraction [+ in-register top-k]): dense matrix-core flop count
+    est_ms = sum(avg.get(k, 0.0) for k in ("features", "state", "contract"))
     est_flops = wl.B * wl.H * (4.0 * wl.T * wl.d * wl.m + 2.0 * wl.T * wl.m * wl.K)
     est = {"ms": est_ms, "dense_flops": est_flops,
            "tflops": est_flops / (est_ms * 1e-3) / 1e12 if est_ms > 0 else 0.0,
            "frac_of_bf16_mfma_peak": (est_flops / (est_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS)
-           if est_ms > 0 and wl.dtype == "bf16" else None}
+           if est_ms > 0 and wl.dtype == "bf16" else None,
+           "includes_topk": "topk_mask" not in avg}
+
+    # ---- dense (quadratic) attention on the same shape, same dtype, for comparison ----
+    dense = None
+    if wl.dtype == "bf16":
+        dws = torch.empty(sea.sea_dense_workspace_bytes(p), dtype=torch.uint8, device=dev)
+        Od = torch.empty_like(d["Q"])
+        for _ in range(3):
+            sea.sea_dense_attn(p, d["Q"], d["K"], d["V"], Od, dws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        nd = max(3, args.steps // 2)
+        for _ in range(nd):
+            sea.sea_dense_attn(p, d["Q"], d["K"], d["V"], Od, dws)
+        torch.cuda.synchronize()
+        dms = (time.perf_counter() - t0) / nd * 1e3
+        dflops = wl.B * wl.H * 4.0 * wl.d * wl.T * wl.T * (0.5 if wl.causal else 1.0)
+        dense = {"ms_per_call": dms, "tokens_per_s": tokens / (dms * 1e-3),
+                 "tflops": dflops / (dms * 1e-3) / 1e12, "kernel": "tile_attn_kernel<dense>"}
 
     out = {
         "metric": "SEA attn fwd tokens/s per layer + % HBM/MFMA roofline, T=1k..32k",
@@ -150,8 +208,10 @@ def main():
                                f"pad_frac={wl.pad_frac} clustered Q/K ({wl.centroids} centroids), seed {wl.seed}",
                    "row_stride": L, "mean_keys_per_active_row": pairs / max(active_rows, 1)},
         "roofline": roofline,
-        "stage_ms": {k: (v[0] / max(v[1], 1)) for k, v in stages.items() if v[1] > 0},
+        "gather_equivalent": gather_equiv,
+        "stage_ms": avg,
         "estimator": est,
+        "dense_attention": dense,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, x, args.cpu_seconds)

@@ -153,7 +153,8 @@ typedef enum {
   SEA_STAGE_TOPK_MASK = 3,/* a4 + a5                                                       */
   SEA_STAGE_SPARSE = 4,   /* a6                                                            */
   SEA_STAGE_DENSE = 5,    /* dense baseline                                                */
-  SEA_STAGE_COUNT = 6
+  SEA_STAGE_COMPACT = 6,  /* compact key list and transposed V for the tiled attention     */
+  SEA_STAGE_COUNT = 7
 } sea_stage;
 int sea_profile_enable(int on);
 int sea_profile_collect(double* host_ms /*[SEA_STAGE_COUNT]*/, int64_t* host_launches /*[SEA_STAGE_COUNT]*/);

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libsea_hip.so")
 
 SEA_F32, SEA_BF16 = 0, 1
 SEA_OK, SEA_EINVAL, SEA_ENOTSUP, SEA_EWORKSPACE, SEA_EHIP = 0, -1, -2, -3, -4
-STAGES = ("features", "state", "contract", "topk_mask", "sparse", "dense")
+STAGES = ("features", "state", "contract", "topk_mask", "sparse", "dense", "compact")
 
 
 class SeaParamsC(ctypes.Structure):

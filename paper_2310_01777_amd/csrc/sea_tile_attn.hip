@@ -374,9 +374,12 @@ hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K
     const size_t vbytes = (static_cast<size_t>(s.N) * kHeadDim * Upad * 2 + 255) & ~size_t(255);
     Kc = reinterpret_cast<uint16_t*>(base + vbytes);
   }
+  {
+    StageScope scope(SEA_STAGE_COMPACT, st);
+    hipLaunchKernelGGL(compact_kv_kernel, dim3(Upad / 64, s.N), dim3(256), 0, st, K, V, Kc, Vct, s.T, U, Upad,
+                       rlog, w);
+  }
   StageScope scope(SEA_STAGE_SPARSE, st);
-  hipLaunchKernelGGL(compact_kv_kernel, dim3(Upad / 64, s.N), dim3(256), 0, st, K, V, Kc, Vct, s.T, U, Upad,
-                     rlog, w);
   TileArgs a{};
   a.Q = Q; a.Kc = Kc ? Kc : K; a.Vct = Vct; a.mbits = mbits; a.O = O; a.seq_len = s.seq_len;
   a.N = s.N; a.H = s.H; a.T = s.T; a.U = U; a.Upad = Upad; a.KW = (s.K + 31) / 32;
