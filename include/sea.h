@@ -141,10 +141,12 @@ int sea_dense_attn(const sea_params* p, const void* Q, const void* K, const void
                    void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
- * Per-stage timing for benchmarks.  While enabled, each kernel launch made by the library is
- * bracketed by HIP events recorded on the launch stream.  sea_profile_collect() synchronises
- * those events, adds the elapsed milliseconds and launch counts per stage into the two host
- * arrays of length SEA_STAGE_COUNT, and forgets them.  Process-wide, not thread-safe.
+ * Per-stage timing for benchmarks.  stage_mask has bit (1 << stage) set for every stage to time
+ * (0 = off, -1 = all): launches of those stages are bracketed by HIP events recorded on the
+ * launch stream (each pair costs a few microseconds of stream time).  sea_profile_collect()
+ * synchronises those events, adds the elapsed milliseconds and launch counts per stage into
+ * the two host arrays of length SEA_STAGE_COUNT, and forgets them.  Process-wide, not
+ * thread-safe.
  */
 typedef enum {
   SEA_STAGE_FEATURES = 0, /* a1: feature maps phi(Q), phi(K)                              */
@@ -156,7 +158,7 @@ typedef enum {
   SEA_STAGE_COMPACT = 6,  /* compact key list and transposed V for the tiled attention     */
   SEA_STAGE_COUNT = 7
 } sea_stage;
-int sea_profile_enable(int on);
+int sea_profile_enable(int stage_mask);
 int sea_profile_collect(double* host_ms /*[SEA_STAGE_COUNT]*/, int64_t* host_launches /*[SEA_STAGE_COUNT]*/);
 
 const char* sea_strerror(int status);

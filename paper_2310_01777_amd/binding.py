@@ -211,8 +211,15 @@ def sea_dense_attn(p: SeaParams, Q, K, V, O, workspace, stream=None):
            "sea_dense_attn")
 
 
-def sea_profile_enable(on: bool):
-    _check(_lib.sea_profile_enable(int(bool(on))), "sea_profile_enable")
+def sea_profile_enable(stages=True):
+    """True/False for all/none, or an iterable of stage names from STAGES."""
+    if stages is True:
+        mask = -1
+    elif not stages:
+        mask = 0
+    else:
+        mask = sum(1 << STAGES.index(s) for s in stages)
+    _check(_lib.sea_profile_enable(mask), "sea_profile_enable")
 
 
 def sea_profile_collect():

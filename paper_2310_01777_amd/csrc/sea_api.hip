@@ -21,7 +21,7 @@ struct Span {
   sea_stage stage;
   hipEvent_t a, b;
 };
-bool g_profile = false;
+unsigned g_profile = 0;  // bit per sea_stage
 std::vector<Span> g_spans;
 std::vector<hipEvent_t> g_free_events;
 
@@ -102,7 +102,7 @@ size_t estimate_ws(const sea_params* p) {
 }  // namespace
 
 void stage_begin(sea_stage stage, hipStream_t st) {
-  if (!g_profile) return;
+  if (!(g_profile & (1u << stage))) return;
   Span sp{stage, take_event(), take_event()};
   if (!sp.a || !sp.b) return;
   (void)hipEventRecord(sp.a, st);
@@ -110,7 +110,7 @@ void stage_begin(sea_stage stage, hipStream_t st) {
 }
 
 void stage_end(sea_stage stage, hipStream_t st) {
-  if (!g_profile || g_spans.empty()) return;
+  if (!(g_profile & (1u << stage)) || g_spans.empty()) return;
   Span& sp = g_spans.back();
   if (sp.stage == stage) (void)hipEventRecord(sp.b, st);
 }
@@ -285,8 +285,8 @@ int sea_dense_attn(const sea_params* p, const void* Q, const void* K, const void
   return e == hipSuccess ? SEA_OK : fail_hip(e);
 }
 
-int sea_profile_enable(int on) {
-  g_profile = on != 0;
+int sea_profile_enable(int stage_mask) {
+  g_profile = static_cast<unsigned>(stage_mask) & ((1u << SEA_STAGE_COUNT) - 1u);
   return SEA_OK;
 }
 

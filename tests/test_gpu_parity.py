@@ -282,6 +282,25 @@ def test_padding_rows_and_zero_length(sea):
     assert_close(to_np64(g["O"]), o["O"], TOL["bf16"], "O padded")
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tiny_and_degenerate_shapes(sea, dtype):
+    """T = 1, K = 1, k^ = 1, T below one tile, a single row; every path must stay in bounds."""
+    for (B, H, T, m, K, kh, kb, causal) in [(1, 1, 1, 64, 1, 1, 0, True), (2, 1, 5, 64, 5, 2, 0, True),
+                                            (1, 2, 17, 64, 1, 1, 0, False), (1, 1, 64, 64, 64, 1, 0, True),
+                                            (1, 1, 33, 32, 11, 3, 4, True), (3, 1, 2, 64, 2, 2, 1, False)]:
+        wl = _wl("tiny", B, H, T, m, K, kh, k_budget=kb, causal=causal, dtype=dtype)
+        x = synth.make_inputs(wl)
+        _, _, g = _gpu_forward(sea, wl, x)
+        po, o = _oracle_forward(wl, x)
+        A_g = g["A_hat"].numpy().astype(np.float64)
+        assert_close(A_g, o["A_hat"], TOL[dtype], "A_hat tiny")
+        sel_s, idx_s, cnt_s = oracle.topk_mask(po, A_g)
+        assert np.array_equal(g["idx"].numpy(), idx_s) and np.array_equal(g["cnt"].numpy(), cnt_s)
+        assert np.array_equal(_unpack_mhat(g["mhat"].numpy(), K), _sel_to_mask(sel_s, K))
+        O_s = oracle.sparse_attn(po, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), idx_s, cnt_s)
+        assert_close(to_np64(g["O"]), O_s, TOL[dtype], "O tiny")
+
+
 def test_optional_outputs_do_not_change_results(sea):
     wl = _wl("noaux", 1, 2, 192, 64, 24, 5)
     x = synth.make_inputs(wl)
@@ -306,38 +325,47 @@ def test_optional_outputs_do_not_change_results(sea):
 
 # ---- full-size configurations, in the launch configuration bench.py times, on sampled rows ----
 
-FULL = ["c1", "c2", "c5", "c4_T8192"]
+FULL = ["c1", "c2", "c3", "c5", "c4_T8192", "c4_T32768"]
 
 
 @pytest.mark.parametrize("name", FULL)
 def test_full_size_sampled_rows(sea, name):
     wl = synth.get_workload(name)
     x = synth.make_inputs(wl)
-    p, xd, g = _gpu_forward(sea, wl, x)
+    xd = _dev(x)
+    p = _params(sea, wl, xd["seq_len"])
+    out = sea.alloc_outputs(p)
+    ws = sea.alloc_workspace(p)
+    print(f"[case] full {wl.name} B{wl.B} H{wl.H} T{wl.T} m{wl.m} K{wl.K} kh{wl.k_hat} kb{wl.k_budget}", flush=True)
+    sea.sea_forward(p, xd["Q"], xd["K"], xd["V"], xd["W"], out["O"], out["A_hat"], out["sel"],
+                    out["idx"], out["cnt"], ws, mhat=out["mhat"])
+    torch.cuda.synchronize()
     rng = np.random.default_rng(0)
     rows = np.unique(np.concatenate([[0, 1, wl.T // wl.K - 1, wl.T // wl.K, wl.T - 1],
                                      rng.integers(0, wl.T, 40)])).astype(np.int32)
+    rows_d = torch.as_tensor(rows.astype(np.int64), device="cuda")
     heads = sorted(set([0, wl.B * wl.H - 1] + rng.integers(0, wl.B * wl.H, 3).tolist()))
     tol = TOL[wl.dtype]
     n_diff = n_rows = 0
     for bh in heads:
         b, h = divmod(bh, wl.H)
+        g = {k: v[b, h].index_select(0, rows_d).cpu() for k, v in out.items()}   # sampled rows only
         one = replace(wl, B=1, H=1)
         xs = {k: x[k][b:b + 1, h:h + 1] for k in "QKV"}
         xs["W"] = x["W"]
         xs["seq_len"] = None if x["seq_len"] is None else x["seq_len"][b:b + 1]
         po, o = _oracle_forward(one, xs, rows=rows)
         sl = None if xs["seq_len"] is None else xs["seq_len"].numpy()
-        A_g = g["A_hat"][b, h][rows].numpy().astype(np.float64)[None, None]
+        A_g = g["A_hat"].numpy().astype(np.float64)[None, None]
         assert_close(A_g, o["A_hat"], tol, f"A_hat head {bh}")
         sel_s, idx_s, cnt_s = oracle.topk_mask(po, A_g, seq_len=sl, rows=rows)
-        assert np.array_equal(g["sel"][b, h][rows].numpy()[None, None], sel_s)
-        assert np.array_equal(g["idx"][b, h][rows].numpy()[None, None], idx_s)
-        assert np.array_equal(g["cnt"][b, h][rows].numpy()[None, None], cnt_s)
-        assert np.array_equal(_unpack_mhat(g["mhat"][b, h][rows].numpy(), wl.K), _sel_to_mask(sel_s[0, 0], wl.K))
+        assert np.array_equal(g["sel"].numpy()[None, None], sel_s)
+        assert np.array_equal(g["idx"].numpy()[None, None], idx_s)
+        assert np.array_equal(g["cnt"].numpy()[None, None], cnt_s)
+        assert np.array_equal(_unpack_mhat(g["mhat"].numpy(), wl.K), _sel_to_mask(sel_s[0, 0], wl.K))
         O_s = oracle.sparse_attn(po, to_np64(xs["Q"]), to_np64(xs["K"]), to_np64(xs["V"]), idx_s, cnt_s,
                                  rows=rows)
-        assert_close(to_np64(g["O"][b, h][rows])[None, None], O_s, tol, f"O head {bh}")
+        assert_close(to_np64(g["O"])[None, None], O_s, tol, f"O head {bh}")
         same = (sel_s == o["sel"]).all(-1)
         ncand = candidate_counts(1, 1, wl.T, wl.K, wl.causal, sl, rows)
         gaps = selection_gaps(o["A_hat"], o["sel"], ncand)
@@ -345,11 +373,15 @@ def test_full_size_sampled_rows(sea, name):
         assert not bad.any(), f"head {bh}: rows {rows[bad[0, 0]]} differ, gaps {gaps[bad]}"
         n_diff += int((~same).sum())
         n_rows += same.size
-    # properties that hold at any size, over the whole output
-    cnt = g["cnt"].numpy()
+    # properties that hold at any size, over the whole output (checked on the device)
     L = sea.sea_row_stride(p)
-    assert cnt.max() <= L and cnt.min() >= 0
-    idx = g["idx"].numpy()
-    assert ((idx >= 0).sum(-1) == cnt).all()
-    assert np.isfinite(to_np64(g["O"])).all()
+    cnt = out["cnt"]
+    assert int(cnt.max()) <= L and int(cnt.min()) >= 0
+    assert bool(((out["idx"] >= 0).sum(-1) == cnt).all())
+    assert bool(torch.isfinite(out["O"].float()).all())
+    pop = torch.zeros_like(cnt)
+    for sh in range(32):
+        pop += (out["mhat"] >> sh) .bitwise_and(1).sum(-1).to(torch.int32)
+    assert bool((pop == (out["sel"] >= 0).sum(-1)).all())      # mask bits and sel agree in number
+    assert bool((pop <= wl.k_hat).all())
     print(f"    sampled rows differing at near-ties: {n_diff} / {n_rows}", flush=True)
