@@ -39,7 +39,7 @@ class _RefParams(ctypes.Structure):
                 ("d", ctypes.c_int32), ("m", ctypes.c_int32), ("K", ctypes.c_int32),
                 ("k_hat", ctypes.c_int32), ("k_budget", ctypes.c_int32),
                 ("causal", ctypes.c_int32), ("round8", ctypes.c_int32),
-                ("scale", ctypes.c_double)]
+                ("grouping", ctypes.c_int32), ("scale", ctypes.c_double)]
 
 
 @dataclass
@@ -55,10 +55,12 @@ class Params:
     causal: bool = True
     scale: float = 0.125
     round8: bool = False  # True for the bf16 contract (rounding of phi(Q) and key state)
+    grouping: int = 0     # 0 per-query top-k^, 1 causal-per-batch (H k^ per time step over all heads)
 
     def c(self) -> _RefParams:
         return _RefParams(self.B, self.H, self.T, self.d, self.m, self.K, self.k_hat,
-                          self.k_budget, int(self.causal), int(self.round8), float(self.scale))
+                          self.k_budget, int(self.causal), int(self.round8), int(self.grouping),
+                          float(self.scale))
 
 
 _lib = None
@@ -72,6 +74,8 @@ def _load():
         lib.ref_k_hat.argtypes = [ctypes.c_int32] * 3
         lib.ref_row_stride.restype = ctypes.c_int32
         lib.ref_row_stride.argtypes = [ctypes.POINTER(_RefParams)]
+        lib.ref_sel_stride.restype = ctypes.c_int32
+        lib.ref_sel_stride.argtypes = [ctypes.POINTER(_RefParams)]
         lib.ref_round8.restype = ctypes.c_double
         lib.ref_round8.argtypes = [ctypes.c_double]
         for name in ("ref_estimate", "ref_topk_mask", "ref_sparse_attn", "ref_forward"):
@@ -100,6 +104,11 @@ def k_hat_from_k(k: int, K: int, T: int) -> int:
 def row_stride(p: Params) -> int:
     cp = p.c()
     return int(_load().ref_row_stride(ctypes.byref(cp)))
+
+
+def sel_stride(p: Params) -> int:
+    cp = p.c()
+    return int(_load().ref_sel_stride(ctypes.byref(cp)))
 
 
 def round8(x: float) -> float:
@@ -132,7 +141,7 @@ def topk_mask(p: Params, A_hat, seq_len=None, rows=None):
     assert A.shape == (p.B, p.H, n, p.K)
     sl, rw = _i32(seq_len), _i32(rows)
     L = row_stride(p)
-    sel = np.empty((p.B, p.H, n, p.k_hat), dtype=np.int32)
+    sel = np.empty((p.B, p.H, n, sel_stride(p)), dtype=np.int32)
     idx = np.empty((p.B, p.H, n, L), dtype=np.int32)
     cnt = np.empty((p.B, p.H, n), dtype=np.int32)
     cp = p.c()
@@ -174,7 +183,7 @@ def forward(p: Params, Q, K, V, W, seq_len=None, rows=None, heads=None, n_thread
     lo, hi = heads if heads is not None else (0, p.B * p.H)
     O = np.zeros((p.B, p.H, n, p.d), dtype=np.float64)
     A = np.zeros((p.B, p.H, n, p.K), dtype=np.float64) if want_aux else None
-    sel = np.full((p.B, p.H, n, p.k_hat), -1, dtype=np.int32) if want_aux else None
+    sel = np.full((p.B, p.H, n, sel_stride(p)), -1, dtype=np.int32) if want_aux else None
     idx = np.full((p.B, p.H, n, L), -1, dtype=np.int32) if want_aux else None
     cnt = np.zeros((p.B, p.H, n), dtype=np.int32) if want_aux else None
     cp = p.c()
@@ -182,6 +191,8 @@ def forward(p: Params, Q, K, V, W, seq_len=None, rows=None, heads=None, n_thread
                              _ptr(rw), ctypes.c_int32(n), ctypes.c_int32(lo), ctypes.c_int32(hi),
                              _ptr(O), _ptr(A), _ptr(sel), _ptr(idx), _ptr(cnt),
                              ctypes.c_int32(n_threads))
+    if rc == -2:
+        raise ValueError("with the causal-per-batch grouping the head range must cover whole batch elements")
     if rc < 0:
         raise MemoryError("ref_forward failed")
     return dict(O=O, A_hat=A, sel=sel, idx=idx, cnt=cnt, threads=rc)

@@ -15,7 +15,7 @@
  *   Sec. 3 "Performer (FAVOR+)"       phi(Q) (phi(K)^T phi(V)), linear in T
  *   Sec. 3.1 "Attention Matrix Estimation"   V_I = nearest-neighbour stretched
  *        identity, "Performer output is the attention matrix when V = I"
- *   Sec. 3.1 "Grouped Top-k^ Selection"      per-query grouping
+ *   Sec. 3.1 "Grouped Top-k^ Selection"      per-query and causal-per-batch grouping
  *   Sec. 3.1 "Linear Sparse Attention Mask Generation" + App. A.5.3
  *        k^ = max(1, round(k K / T)), nearest-neighbour expansion of the
  *        compressed mask, replication cap with uniform spacing
@@ -60,6 +60,7 @@ typedef struct {
   int32_t k_budget; /* the paper's k: cap on keys per row, 0 = no cap         */
   int32_t causal;
   int32_t round8;   /* 1: apply the reduced-precision rounding points         */
+  int32_t grouping; /* 0: per-query top-k^; 1: causal-per-batch (over heads)  */
   double scale;     /* logits = scale * q.k                                   */
 } ref_params;
 
@@ -88,10 +89,18 @@ static int64_t replication(int64_t w, int64_t k_hat, int64_t k_budget) {
   return w < cap ? w : cap;
 }
 
-/* row stride of the index list: k^ * replication of the widest column */
+/* most columns one row of one head can select: k^ per query; with the causal-per-batch
+   grouping a single head may take up to H k^ of the time step's quota (never more than K) */
+int32_t ref_sel_stride(const ref_params* p) {
+  if (p->grouping == 0) return p->k_hat;
+  int64_t q = (int64_t)p->H * p->k_hat;
+  return (int32_t)(q < p->K ? q : p->K);
+}
+
+/* row stride of the index list: (columns per row) * replication of the widest column */
 int32_t ref_row_stride(const ref_params* p) {
   int64_t wmax = ((int64_t)p->T + p->K - 1) / p->K;
-  return (int32_t)(p->k_hat * replication(wmax, p->k_hat, p->k_budget));
+  return (int32_t)(ref_sel_stride(p) * replication(wmax, p->k_hat, p->k_budget));
 }
 
 /* round to an 8-bit significand (bf16 precision, unbounded exponent), RNE */
@@ -201,61 +210,91 @@ int ref_estimate(const ref_params* p, const double* Q, const double* K,
   return 0;
 }
 
-/* ---- a4-a5: per-query top-k^ and expansion to key positions -------------- */
+/* ---- a4-a5: grouped top-k^ and expansion to key positions ------------------ */
+/* expansion of the columns flagged in taken[0..ncand) of one row (App. A.5.3) */
+static void expand_row(const ref_params* p, const uint8_t* taken, int64_t ncand, int64_t jmax,
+                       int32_t* srow, int32_t* irow, int32_t* cnt_out) {
+  const int64_t T = p->T, KK = p->K;
+  int64_t ns = 0, ni = 0;
+  for (int64_t c = 0; c < ncand; ++c) {
+    if (!taken[c]) continue;
+    if (srow) srow[ns] = (int32_t)c;
+    ++ns;
+    const int64_t s0 = block_start(c, T, KK);
+    const int64_t w = block_start(c + 1, T, KK) - s0;
+    const int64_t rep = replication(w, p->k_hat, p->k_budget);
+    for (int64_t i = 0; i < rep; ++i) {
+      const int64_t j = s0 + (i * w) / rep;
+      if (j <= jmax) irow[ni++] = (int32_t)j;
+    }
+  }
+  *cnt_out = (int32_t)ni;
+}
+
 /*
- * A_hat: [B][H][n_rows][K].  sel out: [B][H][n_rows][k_hat] ascending columns,
- * -1 padded (may be NULL).  idx out: [B][H][n_rows][L] ascending key positions,
- * -1 padded, L = ref_row_stride.  cnt out: [B][H][n_rows].
+ * A_hat: [B][H][n_rows][K].  sel out: [B][H][n_rows][S] ascending columns, -1 padded (may be
+ * NULL), S = ref_sel_stride.  idx out: [B][H][n_rows][L] ascending key positions, -1 padded,
+ * L = ref_row_stride.  cnt out: [B][H][n_rows].
+ * grouping 0 (Sec. 3.1 "per-query"): each row of each head keeps its k^ largest entries.
+ * grouping 1 (Sec. 3.1 "causal-per-batch"): A_hat is viewed as [T][H K]; each time step keeps
+ * the H k^ largest entries of its H x K slab, so heads share the step's quota.  Ties go to the
+ * lower flattened index h K + c.
  */
 int ref_topk_mask(const ref_params* p, const double* A_hat, const int32_t* seq_len,
                   const int32_t* rows, int32_t n_rows, int32_t* sel, int32_t* idx,
                   int32_t* cnt) {
-  const int64_t T = p->T, KK = p->K, kh = p->k_hat;
+  const int64_t T = p->T, KK = p->K, H = p->H;
   if (!rows) n_rows = p->T;
-  const int64_t L = ref_row_stride(p);
-  uint8_t* taken = (uint8_t*)malloc(KK);
+  const int64_t L = ref_row_stride(p), S = ref_sel_stride(p);
+  uint8_t* taken = (uint8_t*)malloc(H * KK);
   if (!taken) return -1;
   for (int64_t b = 0; b < p->B; ++b) {
     const int64_t len = seq_len ? seq_len[b] : T;
-    for (int64_t h = 0; h < p->H; ++h) {
-      for (int32_t r = 0; r < n_rows; ++r) {
-        const int64_t row = (b * p->H + h) * (int64_t)n_rows + r;
-        const int64_t t = row_at(rows, r);
-        const double* Arow = A_hat + row * KK;
-        int32_t* srow = sel ? sel + row * kh : NULL;
+    for (int32_t r = 0; r < n_rows; ++r) {
+      const int64_t t = row_at(rows, r);
+      /* last admissible key of this row and its candidate columns 0..ncand-1 */
+      const int64_t jmax = (p->causal && t < len - 1) ? t : len - 1;
+      const int64_t ncand = t < len ? bucket_of(jmax, T, KK) + 1 : 0;
+      memset(taken, 0, H * KK);
+      if (p->grouping == 0) {
+        const int64_t n = p->k_hat < ncand ? p->k_hat : ncand;
+        for (int64_t h = 0; h < H; ++h) {
+          const double* Arow = A_hat + ((b * H + h) * (int64_t)n_rows + r) * KK;
+          /* n passes of "largest remaining, lowest column on ties" */
+          for (int64_t s = 0; s < n; ++s) {
+            int64_t best = -1;
+            for (int64_t c = 0; c < ncand; ++c) {
+              if (taken[h * KK + c]) continue;
+              if (best < 0 || Arow[c] > Arow[best]) best = c;
+            }
+            taken[h * KK + best] = 1;
+          }
+        }
+      } else {
+        const int64_t quota = H * p->k_hat, total = H * ncand;
+        const int64_t n = quota < total ? quota : total;
+        for (int64_t s = 0; s < n; ++s) {
+          int64_t bh = -1, bc = -1;
+          double bv = 0.0;
+          for (int64_t h = 0; h < H; ++h) {
+            const double* Arow = A_hat + ((b * H + h) * (int64_t)n_rows + r) * KK;
+            for (int64_t c = 0; c < ncand; ++c) {
+              if (taken[h * KK + c]) continue;
+              if (bh < 0 || Arow[c] > bv) { bh = h; bc = c; bv = Arow[c]; }
+            }
+          }
+          taken[bh * KK + bc] = 1;
+        }
+      }
+      for (int64_t h = 0; h < H; ++h) {
+        const int64_t row = (b * H + h) * (int64_t)n_rows + r;
+        int32_t* srow = sel ? sel + row * S : NULL;
         int32_t* irow = idx + row * L;
         for (int64_t x = 0; x < L; ++x) irow[x] = -1;
-        if (srow) for (int64_t x = 0; x < kh; ++x) srow[x] = -1;
+        if (srow) for (int64_t x = 0; x < S; ++x) srow[x] = -1;
         cnt[row] = 0;
         if (t >= len) continue;
-        /* last admissible key of this row */
-        const int64_t jmax = (p->causal && t < len - 1) ? t : len - 1;
-        const int64_t ncand = bucket_of(jmax, T, KK) + 1; /* columns 0..ncand-1 */
-        const int64_t n = kh < ncand ? kh : ncand;
-        memset(taken, 0, KK);
-        /* n passes of "largest remaining, lowest column on ties" */
-        for (int64_t s = 0; s < n; ++s) {
-          int64_t best = -1;
-          for (int64_t c = 0; c < ncand; ++c) {
-            if (taken[c]) continue;
-            if (best < 0 || Arow[c] > Arow[best]) best = c;
-          }
-          taken[best] = 1;
-        }
-        int64_t ns = 0, ni = 0;
-        for (int64_t c = 0; c < ncand; ++c) {
-          if (!taken[c]) continue;
-          if (srow) srow[ns] = (int32_t)c;
-          ++ns;
-          const int64_t s0 = block_start(c, T, KK);
-          const int64_t w = block_start(c + 1, T, KK) - s0;
-          const int64_t rep = replication(w, kh, p->k_budget);
-          for (int64_t i = 0; i < rep; ++i) {
-            const int64_t j = s0 + (i * w) / rep;
-            if (j <= jmax) irow[ni++] = (int32_t)j;
-          }
-        }
-        cnt[row] = (int32_t)ni;
+        expand_row(p, taken + h * KK, ncand, jmax, srow, irow, &cnt[row]);
       }
     }
   }
@@ -326,7 +365,10 @@ int ref_forward(const ref_params* p, const double* Q, const double* K,
                 int32_t* idx, int32_t* cnt, int32_t n_threads) {
   const int64_t T = p->T, d = p->d, KK = p->K;
   if (!rows) n_rows = p->T;
-  const int64_t L = ref_row_stride(p);
+  const int64_t L = ref_row_stride(p), S = ref_sel_stride(p);
+  /* unit of independent work: one head (per-query) or one batch element (causal-per-batch) */
+  const int32_t G = p->grouping == 0 ? 1 : p->H;
+  if (head_lo % G != 0 || head_hi % G != 0) return -2;
   int used = 1, err = 0;
 #ifdef _OPENMP
   if (n_threads > 0) omp_set_num_threads(n_threads);
@@ -336,24 +378,26 @@ int ref_forward(const ref_params* p, const double* Q, const double* K,
     used = omp_get_num_threads();
 #pragma omp for schedule(dynamic, 1)
 #endif
-    for (int32_t bh = head_lo; bh < head_hi; ++bh) {
+    for (int32_t u = head_lo / G; u < head_hi / G; ++u) {
+      const int32_t bh = u * G;  /* first head of the unit */
       ref_params q = *p;
-      q.B = 1; q.H = 1;
+      q.B = 1; q.H = G;
       const int32_t b = bh / p->H;
       const int32_t* sl = seq_len ? seq_len + b : NULL;
       const int64_t rowbase = (int64_t)bh * n_rows;
-      double* Ah = (double*)malloc(sizeof(double) * (size_t)n_rows * KK);
-      int32_t* ih = (int32_t*)malloc(sizeof(int32_t) * (size_t)n_rows * (L > 0 ? L : 1));
-      int32_t* ch = (int32_t*)malloc(sizeof(int32_t) * (size_t)n_rows);
+      const size_t nr = (size_t)G * n_rows;
+      double* Ah = (double*)malloc(sizeof(double) * nr * KK);
+      int32_t* ih = (int32_t*)malloc(sizeof(int32_t) * nr * (L > 0 ? L : 1));
+      int32_t* ch = (int32_t*)malloc(sizeof(int32_t) * nr);
       if (!Ah || !ih || !ch) { err = -1; free(Ah); free(ih); free(ch); continue; }
       ref_estimate(&q, Q + (int64_t)bh * T * d, K + (int64_t)bh * T * d, W, sl, rows, n_rows, Ah);
-      ref_topk_mask(&q, Ah, sl, rows, n_rows, sel ? sel + rowbase * p->k_hat : NULL, ih, ch);
+      ref_topk_mask(&q, Ah, sl, rows, n_rows, sel ? sel + rowbase * S : NULL, ih, ch);
       ref_sparse_attn(&q, Q + (int64_t)bh * T * d, K + (int64_t)bh * T * d,
                       V + (int64_t)bh * T * d, ih, ch, rows, n_rows, (int32_t)L,
                       O + rowbase * d);
-      if (A_hat) memcpy(A_hat + rowbase * KK, Ah, sizeof(double) * (size_t)n_rows * KK);
-      if (idx) memcpy(idx + rowbase * L, ih, sizeof(int32_t) * (size_t)n_rows * L);
-      if (cnt) memcpy(cnt + rowbase, ch, sizeof(int32_t) * (size_t)n_rows);
+      if (A_hat) memcpy(A_hat + rowbase * KK, Ah, sizeof(double) * nr * KK);
+      if (idx) memcpy(idx + rowbase * L, ih, sizeof(int32_t) * nr * L);
+      if (cnt) memcpy(cnt + rowbase, ch, sizeof(int32_t) * nr);
       free(Ah); free(ih); free(ch);
     }
 #ifdef _OPENMP

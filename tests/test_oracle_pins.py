@@ -452,3 +452,80 @@ def test_forward_stage_composition_and_threads():
     part = oracle.forward(p, Q, K, V, W, heads=(2, 4))
     assert np.array_equal(part["O"].reshape(6, 64, 16)[2:4], O.reshape(6, 64, 16)[2:4])
     assert np.all(part["O"].reshape(6, 64, 16)[:2] == 0)
+
+
+# ----------------------------------------------------------------------------------------------
+# causal-per-batch grouping -- Sec. 3.1 "Grouped Top-k^ Selection", App. A.5.2
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_per_batch_grouping_equals_sort_of_flattened_slab(causal):
+    """Each time step keeps the H k^ largest entries of its H x K slab (A_hat viewed as
+    [T][H K]); ties go to the lower flattened index.  Checked against a stable library sort."""
+    g = np.random.default_rng(17)
+    B, H, T, K, kh = 2, 3, 48, 12, 4
+    p = oracle.Params(B=B, H=H, T=T, d=4, m=4, K=K, k_hat=kh, causal=causal, grouping=1)
+    A = g.random((B, H, T, K))
+    A[0] = np.round(A[0] * 5) / 5                      # many exact ties across heads
+    A[1, 1] *= 10.0                                     # one head dominates: it must exceed k^
+    seq_len = np.array([T, 31], dtype=np.int32)
+    sel, idx, cnt = oracle.topk_mask(p, A, seq_len=seq_len)
+    S = oracle.sel_stride(p)
+    assert S == min(K, H * kh) and sel.shape[-1] == S
+    w = T // K
+    took_more = False
+    for b in range(B):
+        for t in range(T):
+            if t >= seq_len[b]:
+                assert np.all(sel[b, :, t] == -1) and np.all(cnt[b, :, t] == 0)
+                continue
+            jmax = min(t, seq_len[b] - 1) if causal else seq_len[b] - 1
+            ncand = (jmax * K) // T + 1
+            slab = A[b, :, t, :ncand].reshape(-1)                  # index = h * ncand + c
+            n = min(H * kh, H * ncand)
+            order = np.argsort(-slab, kind="stable")[:n]           # equal values: lower (h, c) first
+            want = [set() for _ in range(H)]
+            for f in order:
+                want[f // ncand].add(int(f % ncand))
+            got_total = 0
+            for h in range(H):
+                got = sel[b, h, t][sel[b, h, t] >= 0].tolist()
+                assert got == sorted(want[h]), (b, t, h)
+                got_total += len(got)
+                took_more |= len(got) > kh
+                js = idx[b, h, t, :cnt[b, h, t]]
+                exp = [c * w + i for c in got for i in range(w) if c * w + i <= jmax]
+                assert js.tolist() == exp
+            assert got_total == n                                   # same number per time step
+    assert took_more
+
+
+def test_per_batch_grouping_with_one_head_is_per_query():
+    g = np.random.default_rng(3)
+    B, T, K, kh = 2, 40, 10, 3
+    A = g.random((B, 1, T, K))
+    pq = oracle.Params(B=B, H=1, T=T, d=4, m=4, K=K, k_hat=kh, causal=True, grouping=0)
+    pb = oracle.Params(B=B, H=1, T=T, d=4, m=4, K=K, k_hat=kh, causal=True, grouping=1)
+    a, b = oracle.topk_mask(pq, A), oracle.topk_mask(pb, A)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+def test_per_batch_forward_composition():
+    """forward with the grouping == estimate -> grouped selection -> sparse attention, and every
+    time step's lists hold the step's quota of columns."""
+    B, H, T, d, m, K, kh = 2, 3, 64, 8, 16, 8, 2
+    Q, Kk, V = _rand_qkv(B, H, T, d, seed=5)
+    W = synth.gaussian_orthogonal(m, d, 0).numpy()
+    p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=K, k_hat=kh, causal=True, scale=0.35, grouping=1)
+    f = oracle.forward(p, Q, Kk, V, W, n_threads=2)
+    A = oracle.estimate(p, Q, Kk, W)
+    sel, idx, cnt = oracle.topk_mask(p, A)
+    O = oracle.sparse_attn(p, Q, Kk, V, idx, cnt)
+    assert np.array_equal(f["A_hat"], A) and np.array_equal(f["sel"], sel)
+    assert np.array_equal(f["idx"], idx) and np.array_equal(f["O"], O)
+    nsel = (sel >= 0).sum(-1).sum(1)                                # per (b, t)
+    ncand = (np.arange(T) * K) // T + 1
+    assert np.array_equal(nsel, np.broadcast_to(np.minimum(H * kh, H * ncand), (B, T)))
+    with pytest.raises(ValueError):
+        oracle.forward(p, Q, Kk, V, W, heads=(1, 3))
