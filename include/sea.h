@@ -14,7 +14,7 @@
  *     the given stream (a hipStream_t passed as void*, NULL = default stream)
  *     and returns.
  *   - Tensors are dense row-major: Q, K, V, O are [B][H][T][d]; W is [m][d];
- *     A_hat is [B][H][T][K] float; sel is [B][H][T][k_hat] int32; idx is
+ *     A_hat is [B][H][T][K] float; sel is [B][H][T][S] int32 (S = sea_sel_stride()); idx is
  *     [B][H][T][L] int32 with L = sea_row_stride(); cnt is [B][H][T] int32.
  *     Q, K, V, W, O hold `dtype` elements (float or bfloat16).
  *   - Output buffers are fully overwritten: unused sel/idx slots are -1, rows at
@@ -64,13 +64,21 @@ typedef struct {
   sea_dtype dtype;     /* element type of Q, K, V, W, O                                     */
   const int32_t* seq_len; /* device [B] or NULL.  Right padding: keys and query rows at
                           positions >= seq_len[b] are inactive                              */
+  int32_t grouping;    /* Sec. 3.1 "Grouped Top-k^ Selection": 0 = per-query (each row of each
+                          head keeps k_hat entries); 1 = causal-per-batch (A_hat viewed as
+                          [T][H K]: each time step keeps H k_hat entries of its H x K slab, so
+                          heads share the quota; needs H K <= 16384)                         */
 } sea_params;
 
 /* k^ = max(1, round(k K / T)), halves rounded up (Sec. 3.1 "Linear Sparse Attention Mask
  * Generation").  Pure host arithmetic. */
 int32_t sea_k_hat(int32_t k, int32_t K, int32_t T);
 
-/* L, the row stride of idx: k_hat * r with r = ceil(T/K) keys per selected column, or
+/* S, the row stride of sel = the most columns one row of one head can select: k_hat, or
+ * min(K, H k_hat) with the causal-per-batch grouping.  Host arithmetic. */
+int32_t sea_sel_stride(const sea_params* p);
+
+/* L, the row stride of idx: S * r with r = ceil(T/K) keys per selected column, or
  * min(ceil(T/K), max(1, k_budget / k_hat)) when k_budget > 0.  Host arithmetic; returns a
  * negative sea_status on invalid parameters. */
 int32_t sea_row_stride(const sea_params* p);
@@ -99,7 +107,8 @@ int sea_estimate(const sea_params* p, const void* Q, const void* K, const void* 
  * Attention Mask Generation" / App. A.5.3 (sparse nearest-neighbour interpolation).
  *   For each active row: among the columns that hold an admissible key, take the
  *   min(k_hat, #columns) largest A_hat entries (equal values: lower column first); sel lists
- *   them ascending.  Column c covers keys [ceil(cT/K), ceil((c+1)T/K)), width w; a selected
+ *   them ascending.  With grouping = 1 the H rows of a time step are ranked together (equal
+ *   values: lower h K + c first) and min(H k_hat, H #columns) entries are kept.  Column c covers keys [ceil(cT/K), ceil((c+1)T/K)), width w; a selected
  *   column emits keys start + floor(i w / r), i < r; keys j > t (causal) or j >= seq_len are
  *   dropped.  idx lists the emitted keys ascending, cnt their number.
  * sel may be NULL.

@@ -27,7 +27,8 @@ class SeaParamsC(ctypes.Structure):
                 ("d", ctypes.c_int32), ("m", ctypes.c_int32), ("K", ctypes.c_int32),
                 ("k_hat", ctypes.c_int32), ("k_budget", ctypes.c_int32),
                 ("causal", ctypes.c_int32), ("scale", ctypes.c_float),
-                ("dtype", ctypes.c_int32), ("seq_len", ctypes.c_void_p)]
+                ("dtype", ctypes.c_int32), ("seq_len", ctypes.c_void_p),
+                ("grouping", ctypes.c_int32)]
 
 
 class SeaError(RuntimeError):
@@ -49,6 +50,7 @@ def _load() -> ctypes.CDLL:
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     lib.sea_k_hat.restype, lib.sea_k_hat.argtypes = i32, [i32, i32, i32]
     lib.sea_row_stride.restype, lib.sea_row_stride.argtypes = i32, [P]
+    lib.sea_sel_stride.restype, lib.sea_sel_stride.argtypes = i32, [P]
     lib.sea_workspace_bytes.restype, lib.sea_workspace_bytes.argtypes = sz, [P]
     lib.sea_estimate.restype, lib.sea_estimate.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, sz, vp]
     lib.sea_topk_mask.restype, lib.sea_topk_mask.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp]
@@ -83,6 +85,7 @@ class SeaParams:
     scale: float = 0.125
     dtype: str = "bf16"
     seq_len: Optional[torch.Tensor] = None
+    grouping: int = 0   # 0 per-query top-k^, 1 causal-per-batch
 
     def c(self) -> SeaParamsC:
         sl = None
@@ -92,7 +95,7 @@ class SeaParams:
             sl = t.data_ptr()
         return SeaParamsC(self.B, self.H, self.T, self.d, self.m, self.K, self.k_hat, self.k_budget,
                           int(self.causal), float(self.scale), SEA_BF16 if self.dtype == "bf16" else SEA_F32,
-                          sl)
+                          sl, int(self.grouping))
 
     @property
     def torch_dtype(self) -> torch.dtype:
@@ -134,6 +137,14 @@ def sea_row_stride(p: SeaParams) -> int:
     return L
 
 
+def sea_sel_stride(p: SeaParams) -> int:
+    cp = p.c()
+    S = int(_lib.sea_sel_stride(ctypes.byref(cp)))
+    if S < 0:
+        raise SeaError(S, "sea_sel_stride")
+    return S
+
+
 def sea_workspace_bytes(p: SeaParams) -> int:
     cp = p.c()
     return int(_lib.sea_workspace_bytes(ctypes.byref(cp)))
@@ -156,7 +167,7 @@ def sea_topk_mask(p: SeaParams, A_hat, sel, idx, cnt, stream=None):
     L = sea_row_stride(p)
     cp = p.c()
     _check(_lib.sea_topk_mask(ctypes.byref(cp), _ptr(A_hat, torch.float32, n * p.K, "A_hat"),
-                              _ptr(sel, torch.int32, n * p.k_hat, "sel"),
+                              _ptr(sel, torch.int32, n * sea_sel_stride(p), "sel"),
                               _ptr(idx, torch.int32, n * L, "idx"),
                               _ptr(cnt, torch.int32, n, "cnt"), _stream(stream)),
            "sea_topk_mask")
@@ -185,7 +196,7 @@ def sea_forward(p: SeaParams, Q, K, V, W, O, A_hat=None, sel=None, idx=None, cnt
                             _ptr(W, p.torch_dtype, p.m * p.d, "W"),
                             _ptr(O, p.torch_dtype, n * p.d, "O"),
                             _ptr(A_hat, torch.float32, n * p.K, "A_hat"),
-                            _ptr(sel, torch.int32, n * p.k_hat, "sel"),
+                            _ptr(sel, torch.int32, n * sea_sel_stride(p), "sel"),
                             _ptr(idx, torch.int32, n * L, "idx"),
                             _ptr(cnt, torch.int32, n, "cnt"),
                             _ptr(mhat, torch.int32, n * ((p.K + 31) // 32), "mhat"),
@@ -249,7 +260,7 @@ def alloc_outputs(p: SeaParams, device="cuda", aux=True):
     if aux:
         L = sea_row_stride(p)
         out.update(A_hat=torch.empty(*n, p.K, dtype=torch.float32, device=device),
-                   sel=torch.empty(*n, p.k_hat, dtype=torch.int32, device=device),
+                   sel=torch.empty(*n, sea_sel_stride(p), dtype=torch.int32, device=device),
                    idx=torch.empty(*n, L, dtype=torch.int32, device=device),
                    cnt=torch.empty(*n, dtype=torch.int32, device=device),
                    mhat=torch.empty(*n, (p.K + 31) // 32, dtype=torch.int32, device=device))

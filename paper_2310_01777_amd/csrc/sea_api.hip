@@ -51,7 +51,9 @@ int check_mask_params(const sea_params* p) {
   if (p->K <= 0 || p->K > p->T) return SEA_EINVAL;
   if (p->k_hat <= 0 || p->k_hat > p->K) return SEA_EINVAL;
   if (p->k_budget < 0) return SEA_EINVAL;
+  if (p->grouping != 0 && p->grouping != 1) return SEA_EINVAL;
   if (p->K > 1024) return SEA_ENOTSUP;
+  if (p->grouping == 1 && static_cast<int64_t>(p->H) * p->K > 16384) return SEA_ENOTSUP;
   return SEA_OK;
 }
 
@@ -67,10 +69,16 @@ int32_t rep_cap_of(const sea_params* p) {
   return cap < 1 ? 1 : cap;
 }
 
+int32_t sel_stride_of(const sea_params* p) {
+  if (p->grouping == 0) return p->k_hat;
+  const int64_t q = static_cast<int64_t>(p->H) * p->k_hat;
+  return static_cast<int32_t>(q < p->K ? q : p->K);
+}
+
 int32_t row_stride_of(const sea_params* p) {
   const int32_t wmax = (p->T + p->K - 1) / p->K;
   const int32_t cap = rep_cap_of(p);
-  const int64_t L = static_cast<int64_t>(p->k_hat) * (wmax < cap ? wmax : cap);
+  const int64_t L = static_cast<int64_t>(sel_stride_of(p)) * (wmax < cap ? wmax : cap);
   return L > INT32_MAX ? -1 : static_cast<int32_t>(L);
 }
 
@@ -83,6 +91,8 @@ Shape make_shape(const sea_params* p, bool with_mask) {
   s.K = p->K;
   s.k_hat = p->k_hat;
   s.causal = p->causal ? 1 : 0;
+  s.grouping = p->grouping;
+  s.sel_stride = sel_stride_of(p);
   s.scale = p->scale;
   s.seq_len = p->seq_len;
   if (with_mask) {
@@ -126,6 +136,12 @@ int32_t sea_k_hat(int32_t k, int32_t K, int32_t T) {
   const int64_t num = static_cast<int64_t>(k) * K;
   const int64_t r = (2 * num + T) / (2 * static_cast<int64_t>(T));
   return r < 1 ? 1 : static_cast<int32_t>(r > INT32_MAX ? INT32_MAX : r);
+}
+
+int32_t sea_sel_stride(const sea_params* p) {
+  int rc = check_common(p);
+  if (rc == SEA_OK) rc = check_mask_params(p);
+  return rc != SEA_OK ? rc : sel_stride_of(p);
 }
 
 int32_t sea_row_stride(const sea_params* p) {
@@ -230,7 +246,7 @@ int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V
     uint32_t* mbits = mhat_opt ? mhat_opt : reinterpret_cast<uint32_t*>(w);
     w += align256(rows * ((s.K + 31) / 32) * sizeof(uint32_t));
     const bool need_lists = sel_opt || idx_opt || cnt_opt;
-    if (estimate_fused_supported(s)) {
+    if (estimate_fused_supported(s) && s.grouping == 0) {
       // estimate and per-row top-k^ in one kernel; the scores never leave the registers
       e = launch_estimate_fused(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
                                 static_cast<const uint16_t*>(W), (A_hat_opt || need_lists) ? A_hat : nullptr,

@@ -22,6 +22,8 @@ struct Shape {
   int32_t rep_cap;  // max keys per selected column (>= 1), INT32_MAX-like when uncapped
   int32_t L;        // row stride of idx
   int32_t causal;
+  int32_t grouping;    // 0 per-query top-k^, 1 causal-per-batch
+  int32_t sel_stride;  // columns one row can select: k_hat, or min(K, H k_hat) when grouped
   float scale;
   const int32_t* seq_len;  // device [B] or nullptr
 };

@@ -40,7 +40,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
   const int32_t b = static_cast<int32_t>((row / s.T) / s.H);
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
   int32_t* irow = idx ? idx + row * s.L : nullptr;
-  int32_t* srow = sel ? sel + row * s.k_hat : nullptr;
+  int32_t* srow = sel ? sel + row * s.sel_stride : nullptr;
   const int32_t kw = (s.K + 31) / 32;  // mask words per row
   uint32_t* mrow = mbits ? mbits + row * kw : nullptr;
 
@@ -48,7 +48,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
     if (irow)
       for (int32_t x = lane; x < s.L; x += kWave) irow[x] = -1;
     if (srow)
-      for (int32_t x = lane; x < s.k_hat; x += kWave) srow[x] = -1;
+      for (int32_t x = lane; x < s.sel_stride; x += kWave) srow[x] = -1;
     if (mrow)
       for (int32_t x = lane; x < kw; x += kWave) mrow[x] = 0u;
     if (cnt && lane == 0) cnt[row] = 0;
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
   // n_sel == n by construction
   __builtin_amdgcn_wave_barrier();
   if (srow)
-    for (int32_t x = lane; x < s.k_hat; x += kWave) srow[x] = (x < n_sel) ? sh_sel[wid][x] : -1;
+    for (int32_t x = lane; x < s.sel_stride; x += kWave) srow[x] = (x < n_sel) ? sh_sel[wid][x] : -1;
 
   if (!irow && !cnt) return;
   // expansion: selected column c emits r keys start + floor(i w / r), i < r
@@ -163,6 +163,137 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
   if (cnt && lane == 0) cnt[row] = total;
 }
 
+// ------------------------------------------------------------------------------------------
+// Causal-per-batch grouping (Sec. 3.1): A_hat is viewed as [T][H K]; each time step keeps the
+// H k^ largest entries of its H x K slab.  One block per (batch element, time step); thread
+// tid holds the VPT consecutive flattened entries tid VPT .. tid VPT + VPT - 1 (flattened
+// index h K + c), so "lower flattened index first" among equal scores is (thread, slot) order.
+// ------------------------------------------------------------------------------------------
+template <int VPT>
+__global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* __restrict__ A_hat,
+                                                         int32_t* __restrict__ sel,
+                                                         int32_t* __restrict__ idx,
+                                                         int32_t* __restrict__ cnt,
+                                                         uint32_t* __restrict__ mbits) {
+  __shared__ uint32_t red[2][4];
+  __shared__ uint32_t scan[4];
+  extern __shared__ uint8_t flags[];  // [H * K] selected?
+  const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+  const int32_t t = static_cast<int32_t>(blockIdx.x % s.T);
+  const int32_t b = static_cast<int32_t>(blockIdx.x / s.T);
+  const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
+  const int32_t HK = s.H * s.K;
+  const int32_t kw = (s.K + 31) / 32;
+  const bool active = t < len;
+  const int32_t jmax = active ? ((s.causal && t < len - 1) ? t : len - 1) : -1;
+  const int32_t ncand = active ? bucket_of(jmax, s.T, s.K) + 1 : 0;
+  const int64_t quota = static_cast<int64_t>(s.H) * s.k_hat, total = static_cast<int64_t>(s.H) * ncand;
+  const uint32_t n = static_cast<uint32_t>(quota < total ? quota : total);
+
+  uint32_t key[VPT];
+#pragma unroll
+  for (int v = 0; v < VPT; ++v) {
+    const int32_t e = tid * VPT + v;
+    uint32_t k = 0u;
+    if (e < HK) {
+      const int32_t h = e / s.K, c = e - h * s.K;
+      if (c < ncand) k = ordered_key(A_hat[((static_cast<int64_t>(b) * s.H + h) * s.T + t) * s.K + c]);
+    }
+    key[v] = k;
+  }
+  // n-th largest key by bitwise search; block-wide counts: wave ballots, then 4 partial sums in LDS
+  uint32_t tau = 0;
+  if (n > 0) {
+#pragma unroll 1
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t trial = tau | (1u << bit);
+      uint32_t c = 0;
+#pragma unroll
+      for (int v = 0; v < VPT; ++v) c += popc64(__ballot(key[v] >= trial));
+      if (lane == 0) red[bit & 1][wid] = c;
+      __syncthreads();  // the buffers alternate, so one barrier per step is enough
+      const uint32_t c_ge = red[bit & 1][0] + red[bit & 1][1] + red[bit & 1][2] + red[bit & 1][3];
+      if (c_ge >= n) tau = trial;
+    }
+  }
+  uint32_t c_gt = 0;
+  {
+    uint32_t c = 0;
+#pragma unroll
+    for (int v = 0; v < VPT; ++v) c += popc64(__ballot(n > 0 && key[v] > tau));
+    if (lane == 0) red[1][wid] = c;  // the last search step used buffer 0
+    __syncthreads();
+    c_gt = red[1][0] + red[1][1] + red[1][2] + red[1][3];
+  }
+  uint32_t need_eq = n - c_gt;  // entries equal to tau that are kept, lowest flattened index first
+  // exclusive prefix over threads of the number of entries equal to tau
+  uint32_t my_eq = 0;
+#pragma unroll
+  for (int v = 0; v < VPT; ++v) my_eq += (n > 0 && key[v] == tau) ? 1u : 0u;
+  uint32_t incl = my_eq;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const uint32_t o = __shfl_up(incl, off, kWave);
+    if (lane >= off) incl += o;
+  }
+  if (lane == kWave - 1) scan[wid] = incl;
+  __syncthreads();
+  uint32_t before = incl - my_eq;
+  for (int q = 0; q < wid; ++q) before += scan[q];
+#pragma unroll
+  for (int v = 0; v < VPT; ++v) {
+    const int32_t e = tid * VPT + v;
+    bool take = false;
+    if (n > 0) {
+      if (key[v] > tau) take = true;
+      else if (key[v] == tau) { take = before < need_eq; ++before; }
+    }
+    if (e < HK) flags[e] = take ? 1 : 0;
+  }
+  __syncthreads();
+  // packed mask words: word j of head h holds columns 32 j .. 32 j + 31
+  if (mbits) {
+    for (int32_t x = tid; x < s.H * kw; x += 256) {
+      const int32_t h = x / kw, j = x - h * kw;
+      uint32_t word = 0;
+      for (int i = 0; i < 32; ++i) {
+        const int32_t c = 32 * j + i;
+        if (c < s.K && flags[h * s.K + c]) word |= 1u << i;
+      }
+      mbits[((static_cast<int64_t>(b) * s.H + h) * s.T + t) * kw + j] = word;
+    }
+  }
+  // row lists on request: one thread walks one head
+  if (sel || idx || cnt) {
+    for (int32_t h = tid; h < s.H; h += 256) {
+      const int64_t row = (static_cast<int64_t>(b) * s.H + h) * s.T + t;
+      int32_t* srow = sel ? sel + row * s.sel_stride : nullptr;
+      int32_t* irow = idx ? idx + row * s.L : nullptr;
+      int32_t ns = 0, ni = 0;
+      for (int32_t c = 0; c < ncand; ++c) {
+        if (!flags[h * s.K + c]) continue;
+        if (srow) srow[ns] = c;
+        ++ns;
+        const int32_t s0 = block_start(c, s.T, s.K);
+        const int32_t w = block_start(c + 1, s.T, s.K) - s0;
+        const int32_t r = min(w, s.rep_cap);
+        for (int32_t i = 0; i < r; ++i) {
+          const int32_t j = s0 + static_cast<int32_t>((static_cast<int64_t>(i) * w) / r);
+          if (j <= jmax) {
+            if (irow) irow[ni] = j;
+            ++ni;
+          }
+        }
+      }
+      if (srow)
+        for (int32_t x = ns; x < s.sel_stride; ++x) srow[x] = -1;
+      if (irow)
+        for (int32_t x = ni; x < s.L; ++x) irow[x] = -1;
+      if (cnt) cnt[row] = ni;
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, int32_t* idx,
@@ -172,6 +303,19 @@ hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, in
   const dim3 block(kWavesPerBlock * kWave);
   const int slots = (s.K + kWave - 1) / kWave;
   StageScope scope(SEA_STAGE_TOPK_MASK, st);
+  if (s.grouping == 1) {
+    const int32_t HK = s.H * s.K;
+    const int vpt = (HK + 255) / 256;
+    const dim3 ggrid(static_cast<uint32_t>(s.N / s.H) * s.T);
+    const size_t shm = static_cast<size_t>(HK);
+    if (vpt <= 4) hipLaunchKernelGGL(topk_group_kernel<4>, ggrid, block, shm, st, s, A_hat, sel, idx, cnt, mbits);
+    else if (vpt <= 8) hipLaunchKernelGGL(topk_group_kernel<8>, ggrid, block, shm, st, s, A_hat, sel, idx, cnt, mbits);
+    else if (vpt <= 16) hipLaunchKernelGGL(topk_group_kernel<16>, ggrid, block, shm, st, s, A_hat, sel, idx, cnt, mbits);
+    else if (vpt <= 32) hipLaunchKernelGGL(topk_group_kernel<32>, ggrid, block, shm, st, s, A_hat, sel, idx, cnt, mbits);
+    else if (vpt <= 64) hipLaunchKernelGGL(topk_group_kernel<64>, ggrid, block, shm, st, s, A_hat, sel, idx, cnt, mbits);
+    else return hipErrorNotSupported;
+    return hipGetLastError();
+  }
   if (slots <= 1) hipLaunchKernelGGL(topk_mask_kernel<1>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);
   else if (slots <= 2) hipLaunchKernelGGL(topk_mask_kernel<2>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);
   else if (slots <= 4) hipLaunchKernelGGL(topk_mask_kernel<4>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);

@@ -32,6 +32,7 @@ class Workload:
     pad_frac: float = 0.0  # > 0: random right padding of up to this fraction
     seed: int = 1234
     w_seed: int = 0
+    grouping: int = 0      # 0 per-query top-k^, 1 causal-per-batch (Sec. 3.1)
 
     @property
     def scale(self) -> float:

@@ -9,8 +9,8 @@ import torch
 
 import oracle
 from paper_2310_01777_amd import synth
-from tests.util import (GAP, TOL, assert_close, candidate_counts, oracle_params, selection_gaps,
-                        to_np64)
+from tests.util import (GAP, TOL, assert_close, candidate_counts, group_selection_gaps, oracle_params,
+                        selection_gaps, to_np64)
 
 pytestmark = pytest.mark.gpu
 
@@ -22,15 +22,15 @@ def sea():
 
 
 def _wl(name, B, H, T, m, K, k_hat, k_budget=0, causal=True, dtype="bf16", centroids=4,
-        pad_frac=0.0, seed=1234):
+        pad_frac=0.0, seed=1234, grouping=0):
     return synth.Workload(name, B, H, T, 64, m, K, k_hat, k_budget, causal, dtype, centroids,
-                          pad_frac, seed)
+                          pad_frac, seed, grouping=grouping)
 
 
 def _params(sea, wl, seq_len_dev=None):
     return sea.SeaParams(B=wl.B, H=wl.H, T=wl.T, d=wl.d, m=wl.m, K=wl.K, k_hat=wl.k_hat,
                          k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale, dtype=wl.dtype,
-                         seq_len=seq_len_dev)
+                         seq_len=seq_len_dev, grouping=wl.grouping)
 
 
 def _dev(x):
@@ -142,6 +142,54 @@ def test_forward_matches_oracle(sea, wl):
     Oo[~same] = 0.0
     assert_close(Og, Oo, tol, "O (end to end)")
     print(f"    rows differing at near-ties: {(~same).sum()} / {same.size}", flush=True)
+
+
+GROUPED_CASES = [
+    _wl("grp_bf16_tiled", 2, 4, 256, 64, 32, 6, grouping=1),
+    _wl("grp_bf16_c2_like", 1, 12, 512, 128, 32, 16, grouping=1),
+    _wl("grp_bf16_ragged_rowlists", 1, 3, 203, 64, 29, 5, grouping=1),
+    _wl("grp_bf16_bidir_pad", 2, 3, 256, 64, 32, 4, causal=False, pad_frac=0.3, grouping=1),
+    _wl("grp_bf16_budget", 1, 4, 512, 64, 16, 2, k_budget=16, grouping=1),
+    _wl("grp_f32", 1, 3, 160, 64, 20, 4, dtype="f32", grouping=1),
+    _wl("grp_bf16_big_slab", 1, 32, 256, 64, 256, 8, grouping=1),
+]
+
+
+@pytest.mark.parametrize("wl", GROUPED_CASES, ids=lambda w: w.name)
+def test_causal_per_batch_grouping(sea, wl):
+    """Sec. 3.1 causal-per-batch selection: the H rows of a time step share a quota of H k^."""
+    x = synth.make_inputs(wl)
+    p, xd, g = _gpu_forward(sea, wl, x)
+    po, o = _oracle_forward(wl, x)
+    sl = None if x["seq_len"] is None else x["seq_len"].numpy()
+    tol = TOL[wl.dtype]
+    assert sea.sea_sel_stride(p) == oracle.sel_stride(po) and sea.sea_row_stride(p) == oracle.row_stride(po)
+    A_g = g["A_hat"].numpy().astype(np.float64)
+    assert_close(A_g, o["A_hat"], tol, "A_hat")
+    # stage-wise: bit-identical selection and lists on the GPU's own scores
+    sel_s, idx_s, cnt_s = oracle.topk_mask(po, A_g, seq_len=sl)
+    assert np.array_equal(g["sel"].numpy(), sel_s)
+    assert np.array_equal(g["idx"].numpy(), idx_s)
+    assert np.array_equal(g["cnt"].numpy(), cnt_s)
+    assert np.array_equal(_unpack_mhat(g["mhat"].numpy(), wl.K), _sel_to_mask(sel_s, wl.K))
+    nsel = (sel_s >= 0).sum(-1).sum(1)
+    ncand = candidate_counts(wl.B, wl.H, wl.T, wl.K, wl.causal, sl)
+    assert np.array_equal(nsel, np.minimum(wl.H * wl.k_hat, ncand.sum(1)))   # the step's quota
+    O_s = oracle.sparse_attn(po, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), idx_s, cnt_s)
+    assert_close(to_np64(g["O"]), O_s, tol, "O (stage)")
+    # end to end: identical per-step selections except at near-ties of the oracle's slab
+    m_g, m_o = _sel_to_mask(g["sel"].numpy(), wl.K), _sel_to_mask(o["sel"], wl.K)
+    same = (m_g == m_o).all(-1).all(1)                                        # [B, T]
+    gaps = group_selection_gaps(o["A_hat"], m_o, ncand)
+    bad = ~same & ~(gaps < GAP[wl.dtype])
+    assert not bad.any(), f"{bad.sum()} steps differ with gap >= {GAP[wl.dtype]:g}"
+    assert (~same).mean() <= 0.05
+    keep = np.broadcast_to(same[:, None, :], m_g.shape[:3])
+    Og, Oo = to_np64(g["O"]).copy(), o["O"].copy()
+    Og[~keep] = 0.0
+    Oo[~keep] = 0.0
+    assert_close(Og, Oo, tol, "O (end to end)")
+    print(f"    steps differing at near-ties: {(~same).sum()} / {same.size}", flush=True)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])

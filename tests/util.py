@@ -23,7 +23,8 @@ def oracle_params(wl_or_p, round8=None) -> oracle.Params:
     p = wl_or_p
     r8 = (p.dtype == "bf16") if round8 is None else round8
     return oracle.Params(B=p.B, H=p.H, T=p.T, d=p.d, m=p.m, K=p.K, k_hat=p.k_hat,
-                         k_budget=p.k_budget, causal=bool(p.causal), scale=float(p.scale), round8=r8)
+                         k_budget=p.k_budget, causal=bool(p.causal), scale=float(p.scale), round8=r8,
+                         grouping=int(getattr(p, "grouping", 0)))
 
 
 def rel_errors(got: np.ndarray, ref: np.ndarray):
@@ -79,3 +80,23 @@ def candidate_counts(B, H, T, K, causal, seq_len, rows=None) -> np.ndarray:
             jmax = min(t, ln - 1) if causal else ln - 1
             out[b, :, r] = (jmax * K) // T + 1
     return out
+
+
+def group_selection_gaps(A_ref: np.ndarray, mask_ref: np.ndarray, ncand: np.ndarray) -> np.ndarray:
+    """Causal-per-batch grouping: relative gap between the smallest selected and the largest
+    unselected candidate score of each time step's H x K slab.  A_ref, mask_ref: [B,H,T,K];
+    ncand: [B,H,T] (same for every head).  Returns [B,T]; +inf where every candidate is taken."""
+    B, H, T, K = A_ref.shape
+    gaps = np.full((B, T), np.inf)
+    for b in range(B):
+        for t in range(T):
+            n = int(ncand[b, 0, t])
+            if n == 0:
+                continue
+            a = A_ref[b, :, t, :n].reshape(-1)
+            m = mask_ref[b, :, t, :n].reshape(-1)
+            if m.all() or not m.any():
+                continue
+            lo, hi = a[m].min(), a[~m].max()
+            gaps[b, t] = (lo - hi) / lo if lo > 0 else 0.0
+    return gaps
