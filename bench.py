@@ -31,6 +31,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2",
                     help="c1..c5 or c4_T<len>; c2 is the configuration the metric is quoted on")
+    ap.add_argument("--grouping", choices=["per_query", "causal_per_batch"], default="per_query",
+                    help="top-k^ grouping (Sec. 3.1); the headline metric uses per_query")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU-work budget of the oracle sample")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
@@ -49,15 +51,20 @@ def cpu_baseline(wl, x, budget_s):
     f64 = lambda t: t.to(torch.float64).numpy()
     nheads = wl.B * wl.H
     p = oracle.Params(B=wl.B, H=wl.H, T=wl.T, d=wl.d, m=wl.m, K=wl.K, k_hat=wl.k_hat,
-                      k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale, round8=wl.dtype == "bf16")
+                      k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale, round8=wl.dtype == "bf16",
+                      grouping=wl.grouping)
     Q, K, V, W = f64(x["Q"]), f64(x["K"]), f64(x["V"]), f64(x["W"])
     sl = None if x["seq_len"] is None else x["seq_len"].numpy()
     t0 = time.perf_counter()
-    oracle.forward(p, Q, K, V, W, seq_len=sl, heads=(0, 1), n_threads=1, want_aux=False)
+    oracle.forward(p, Q, K, V, W, seq_len=sl, heads=(0, wl.H if wl.grouping else 1), n_threads=1, want_aux=False)
+    one_heads = wl.H if wl.grouping else 1
     one = time.perf_counter() - t0
+    one /= one_heads
     n = int(max(1, min(nheads, budget_s / max(one, 1e-6))))
     n = max(min(nheads, cores), (n // cores) * cores) if n >= cores else n
     n = min(n, nheads)
+    if wl.grouping:                       # whole batch elements only
+        n = max(wl.H, (n // wl.H) * wl.H)
     t0 = time.perf_counter()
     out = oracle.forward(p, Q, K, V, W, seq_len=sl, heads=(0, n), n_threads=cores, want_aux=False)
     wall = time.perf_counter() - t0
@@ -106,11 +113,15 @@ def main():
         print(json.dumps({"copy_probe_bytes": args.copy_probe << 20, "copies": 3}))
         return
     wl = synth.get_workload(args.workload)
+    if args.grouping == "causal_per_batch":
+        import dataclasses
+        wl = dataclasses.replace(wl, name=wl.name + "+causal_per_batch", grouping=1)
     x = synth.make_inputs(wl)
     d = {k: x[k].to(dev) for k in "QKVW"}
     sl = None if x["seq_len"] is None else x["seq_len"].to(dev)
     p = sea.SeaParams(B=wl.B, H=wl.H, T=wl.T, d=wl.d, m=wl.m, K=wl.K, k_hat=wl.k_hat,
-                      k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale, dtype=wl.dtype, seq_len=sl)
+                      k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale, dtype=wl.dtype, seq_len=sl,
+                      grouping=wl.grouping)
     ws = sea.alloc_workspace(p, dev)
     O = torch.empty_like(d["Q"])
     L = sea.sea_row_stride(p)
