@@ -169,6 +169,16 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
 // tid holds the VPT consecutive flattened entries tid VPT .. tid VPT + VPT - 1 (flattened
 // index h K + c), so "lower flattened index first" among equal scores is (thread, slot) order.
 // ------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x) {
+  x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0xB1, 0xf, 0xf, false));   // quad xor 1
+  x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0x4E, 0xf, 0xf, false));   // quad xor 2
+  x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0x141, 0xf, 0xf, false));  // row_half_mirror
+  x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0x140, 0xf, 0xf, false));  // row_mirror
+  x += __shfl_xor(x, 16, kWave);
+  x += __shfl_xor(x, 32, kWave);
+  return x;
+}
+
 template <int VPT>
 __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* __restrict__ A_hat,
                                                          int32_t* __restrict__ sel,
@@ -191,45 +201,72 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
   const uint32_t n = static_cast<uint32_t>(quota < total ? quota : total);
 
   uint32_t key[VPT];
+  if (s.K % VPT == 0) {
+    // the thread's VPT entries lie in one head: 128-bit loads
+    const int32_t e0 = tid * VPT;
+    const int32_t h = e0 / s.K, c0 = e0 - h * s.K;
+    const float4* src = reinterpret_cast<const float4*>(
+        A_hat + ((static_cast<int64_t>(b) * s.H + min(h, s.H - 1)) * s.T + t) * s.K + c0);
 #pragma unroll
-  for (int v = 0; v < VPT; ++v) {
-    const int32_t e = tid * VPT + v;
-    uint32_t k = 0u;
-    if (e < HK) {
-      const int32_t h = e / s.K, c = e - h * s.K;
-      if (c < ncand) k = ordered_key(A_hat[((static_cast<int64_t>(b) * s.H + h) * s.T + t) * s.K + c]);
+    for (int v4 = 0; v4 < VPT / 4; ++v4) {
+      float4 f = {0.f, 0.f, 0.f, 0.f};
+      if (e0 < HK && c0 + 4 * v4 < ncand) f = src[v4];
+      const float fv[4] = {f.x, f.y, f.z, f.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        key[4 * v4 + q] = (e0 < HK && c0 + 4 * v4 + q < ncand) ? ordered_key(fv[q]) : 0u;
     }
-    key[v] = k;
+  } else {
+#pragma unroll
+    for (int v = 0; v < VPT; ++v) {
+      const int32_t e = tid * VPT + v;
+      uint32_t k = 0u;
+      if (e < HK) {
+        const int32_t h = e / s.K, c = e - h * s.K;
+        if (c < ncand) k = ordered_key(A_hat[((static_cast<int64_t>(b) * s.H + h) * s.T + t) * s.K + c]);
+      }
+      key[v] = k;
+    }
   }
   // n-th largest key by bitwise search; block-wide counts: wave ballots, then 4 partial sums in LDS
-  uint32_t tau = 0;
+  // Counts are kept on the vector units (per-thread compare-and-add, DPP row sums, two
+  // cross-row exchanges, four partial sums through LDS): the scalar unit, shared by the four
+  // SIMDs of a CU, would otherwise be the bottleneck.  The search stops as soon as exactly n
+  // keys are >= tau.
+  uint32_t tau = 0, c_ge = static_cast<uint32_t>(256 * VPT);
   if (n > 0) {
 #pragma unroll 1
-    for (int bit = 31; bit >= 0; --bit) {
+    for (int bit = 31; bit >= 0 && c_ge != n; --bit) {
       const uint32_t trial = tau | (1u << bit);
       uint32_t c = 0;
 #pragma unroll
-      for (int v = 0; v < VPT; ++v) c += popc64(__ballot(key[v] >= trial));
+      for (int v = 0; v < VPT; ++v) c += (key[v] >= trial) ? 1u : 0u;
+      c = wave_sum_u32(c);
       if (lane == 0) red[bit & 1][wid] = c;
       __syncthreads();  // the buffers alternate, so one barrier per step is enough
-      const uint32_t c_ge = red[bit & 1][0] + red[bit & 1][1] + red[bit & 1][2] + red[bit & 1][3];
-      if (c_ge >= n) tau = trial;
+      const uint32_t ct = red[bit & 1][0] + red[bit & 1][1] + red[bit & 1][2] + red[bit & 1][3];
+      if (ct >= n) { tau = trial; c_ge = ct; }
     }
   }
+  __syncthreads();
   uint32_t c_gt = 0;
-  {
+  if (c_ge == n) {
+    c_gt = n;  // no excess ties at the threshold: every key >= tau is kept (counted as "greater")
+  } else {
     uint32_t c = 0;
 #pragma unroll
-    for (int v = 0; v < VPT; ++v) c += popc64(__ballot(n > 0 && key[v] > tau));
-    if (lane == 0) red[1][wid] = c;  // the last search step used buffer 0
+    for (int v = 0; v < VPT; ++v) c += (n > 0 && key[v] > tau) ? 1u : 0u;
+    c = wave_sum_u32(c);
+    if (lane == 0) red[0][wid] = c;
     __syncthreads();
-    c_gt = red[1][0] + red[1][1] + red[1][2] + red[1][3];
+    c_gt = red[0][0] + red[0][1] + red[0][2] + red[0][3];
   }
+  const bool exact = (c_ge == n);
   uint32_t need_eq = n - c_gt;  // entries equal to tau that are kept, lowest flattened index first
   // exclusive prefix over threads of the number of entries equal to tau
   uint32_t my_eq = 0;
 #pragma unroll
-  for (int v = 0; v < VPT; ++v) my_eq += (n > 0 && key[v] == tau) ? 1u : 0u;
+  for (int v = 0; v < VPT; ++v) my_eq += (n > 0 && !exact && key[v] == tau) ? 1u : 0u;
   uint32_t incl = my_eq;
 #pragma unroll
   for (int off = 1; off < kWave; off <<= 1) {
@@ -245,7 +282,8 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
     const int32_t e = tid * VPT + v;
     bool take = false;
     if (n > 0) {
-      if (key[v] > tau) take = true;
+      if (exact) take = key[v] >= tau;
+      else if (key[v] > tau) take = true;
       else if (key[v] == tau) { take = before < need_eq; ++before; }
     }
     if (e < HK) flags[e] = take ? 1 : 0;
