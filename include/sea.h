@@ -140,6 +140,23 @@ int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V
                 uint32_t* mhat_opt, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * Sec. 3.1.1 "Output Calculation": C_sea = s_mix * (s_prob * C) + (1 - s_mix) * C_avg, row by row.
+ *   C: the sparse-attention output of sea_forward / sea_sparse_attn, [B][H][T][d] in `dtype`;
+ *   s_prob: device float [B][H][T] or NULL (= 1), the rescaling of the sparse probabilities
+ *   A* = s_prob * sigma(...), which by linearity rescales C; s_mix: device float [B][H][T].
+ *   Bidirectional (causal = 0): importance i^ = mean over the active rows of A_hat, stretched to
+ *   the keys by nearest neighbour; C_avg = average of the active value rows weighted by it (one
+ *   vector per head); A_hat [B][H][T][K] is required.  Causal: C_avg[t] = mean of v_0 .. v_t;
+ *   A_hat is ignored.  The paper learns s_prob and s_mix from the decoder's hidden state; here
+ *   the caller supplies them.  O may alias C.  Rows at or beyond seq_len give zeros.
+ *   Needs sea_output_mix_workspace_bytes() of 256-byte aligned scratch.
+ */
+size_t sea_output_mix_workspace_bytes(const sea_params* p);
+int sea_output_mix(const sea_params* p, const void* C, const void* V, const float* A_hat,
+                   const float* s_prob, const float* s_mix, void* O, void* workspace,
+                   size_t workspace_bytes, void* hip_stream);
+
+/*
  * Quadratic attention A = softmax(scale QK^T), C = AV (Sec. 3 "Preliminaries"), causal and/or
  * right-padded like the sparse path, computed tile by tile with no T x T buffer.  This is the
  * baseline the sparse path is reported against, not part of SEA.  bf16 only (SEA_ENOTSUP for

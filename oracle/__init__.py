@@ -78,7 +78,7 @@ def _load():
         lib.ref_sel_stride.argtypes = [ctypes.POINTER(_RefParams)]
         lib.ref_round8.restype = ctypes.c_double
         lib.ref_round8.argtypes = [ctypes.c_double]
-        for name in ("ref_estimate", "ref_topk_mask", "ref_sparse_attn", "ref_forward"):
+        for name in ("ref_estimate", "ref_topk_mask", "ref_sparse_attn", "ref_forward", "ref_output_mix"):
             getattr(lib, name).restype = ctypes.c_int
         _lib = lib
     return _lib
@@ -196,3 +196,24 @@ def forward(p: Params, Q, K, V, W, seq_len=None, rows=None, heads=None, n_thread
     if rc < 0:
         raise MemoryError("ref_forward failed")
     return dict(O=O, A_hat=A, sel=sel, idx=idx, cnt=cnt, threads=rc)
+
+
+def output_mix(p: Params, C, V, s_mix, s_prob=None, A_hat=None, seq_len=None):
+    """C_sea [B,H,T,d] = s_mix (s_prob C) + (1 - s_mix) C_avg -- Sec. 3.1.1 "Output Calculation".
+
+    A_hat [B,H,T,K] is needed for bidirectional attention only (importance pooling)."""
+    C, V, s_mix = _f64(C), _f64(V), _f64(s_mix)
+    assert C.shape == (p.B, p.H, p.T, p.d) and V.shape == C.shape and s_mix.shape == (p.B, p.H, p.T)
+    sp = None if s_prob is None else _f64(s_prob)
+    A = None
+    if not p.causal:
+        A = _f64(A_hat)
+        assert A.shape == (p.B, p.H, p.T, p.K)
+    sl = _i32(seq_len)
+    O = np.empty_like(C)
+    cp = p.c()
+    rc = _load().ref_output_mix(ctypes.byref(cp), _ptr(C), _ptr(V), _ptr(A), _ptr(sp), _ptr(s_mix),
+                                _ptr(sl), _ptr(O))
+    if rc != 0:
+        raise MemoryError("ref_output_mix failed")
+    return O

@@ -21,6 +21,7 @@
  *        compressed mask, replication cap with uniform spacing
  *   Sec. 3.1.1 "Sparse Attention Mechanism"  rho (masked QK^T on stored
  *        entries), sigma (softmax over stored entries), C = A* V
+ *   Sec. 3.1.1 "Output Calculation"          C_sea = s_mix C + (1 - s_mix) C_avg
  *
  * Readings taken where the paper is silent (each also listed in the design
  * notes of the repository):
@@ -344,6 +345,59 @@ int ref_sparse_attn(const ref_params* p, const double* Q, const double* K,
     }
   }
   free(s);
+  return 0;
+}
+
+/* ---- output mixing (Sec. 3.1.1 "Output Calculation") ------------------------ */
+/*
+ * C_sea = s_mix * (s_prob * C) + (1 - s_mix) * C_avg, row by row.
+ *   C: [B][H][T][d] sparse-attention output; s_prob (may be NULL = 1) rescales the sparse
+ *   probabilities A* = s_prob * sigma(...), which by linearity rescales C; s_mix: [B][H][T].
+ *   Bidirectional: importance i^ = mean over the active rows of A_hat (R^K), stretched to the
+ *   keys by nearest neighbour (i_j = i^[floor(j K / T)]), C_avg = weighted average of the active
+ *   value rows with weights i (one vector per head).  Causal: C_avg[t] = mean of v_0..v_t.
+ *   The scalers are learned in the paper; here the caller supplies them.
+ */
+int ref_output_mix(const ref_params* p, const double* C, const double* V, const double* A_hat,
+                   const double* s_prob, const double* s_mix, const int32_t* seq_len, double* O) {
+  const int64_t T = p->T, d = p->d, KK = p->K;
+  double* ihat = (double*)malloc(sizeof(double) * KK);
+  double* avg = (double*)malloc(sizeof(double) * d);
+  if (!ihat || !avg) return -1;
+  for (int64_t bh = 0; bh < (int64_t)p->B * p->H; ++bh) {
+    const int64_t len = seq_len ? seq_len[bh / p->H] : T;
+    const double* Ch = C + bh * T * d;
+    const double* Vh = V + bh * T * d;
+    double* Oh = O + bh * T * d;
+    for (int64_t e = 0; e < d; ++e) avg[e] = 0.0;
+    if (!p->causal) {
+      for (int64_t c = 0; c < KK; ++c) ihat[c] = 0.0;
+      for (int64_t t = 0; t < len; ++t)
+        for (int64_t c = 0; c < KK; ++c) ihat[c] += A_hat[(bh * T + t) * KK + c];
+      for (int64_t c = 0; c < KK; ++c) ihat[c] /= (len > 0 ? (double)len : 1.0);
+      double wsum = 0.0;
+      for (int64_t j = 0; j < len; ++j) {
+        const double wj = ihat[bucket_of(j, T, KK)];
+        wsum += wj;
+        for (int64_t e = 0; e < d; ++e) avg[e] += wj * Vh[j * d + e];
+      }
+      for (int64_t e = 0; e < d; ++e) avg[e] = wsum > 0.0 ? avg[e] / wsum : 0.0;
+    }
+    for (int64_t t = 0; t < T; ++t) {
+      if (t >= len) {
+        for (int64_t e = 0; e < d; ++e) Oh[t * d + e] = 0.0;
+        continue;
+      }
+      if (p->causal)  /* running sum of the values; the mean divides by the count t + 1 */
+        for (int64_t e = 0; e < d; ++e) avg[e] += Vh[t * d + e];
+      const double sm = s_mix[bh * T + t], sp = s_prob ? s_prob[bh * T + t] : 1.0;
+      for (int64_t e = 0; e < d; ++e) {
+        const double ca = p->causal ? avg[e] / (double)(t + 1) : avg[e];
+        Oh[t * d + e] = sm * sp * Ch[t * d + e] + (1.0 - sm) * ca;
+      }
+    }
+  }
+  free(ihat); free(avg);
   return 0;
 }
 

@@ -58,6 +58,8 @@ def _load() -> ctypes.CDLL:
     lib.sea_forward.restype, lib.sea_forward.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.sea_dense_workspace_bytes.restype, lib.sea_dense_workspace_bytes.argtypes = sz, [P]
     lib.sea_dense_attn.restype, lib.sea_dense_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, sz, vp]
+    lib.sea_output_mix_workspace_bytes.restype, lib.sea_output_mix_workspace_bytes.argtypes = sz, [P]
+    lib.sea_output_mix.restype, lib.sea_output_mix.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.sea_profile_enable.restype, lib.sea_profile_enable.argtypes = ctypes.c_int, [ctypes.c_int]
     lib.sea_profile_collect.restype = ctypes.c_int
     lib.sea_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
@@ -220,6 +222,25 @@ def sea_dense_attn(p: SeaParams, Q, K, V, O, workspace, stream=None):
                                _ptr(workspace, None, None, "workspace"),
                                workspace.numel() * workspace.element_size(), _stream(stream)),
            "sea_dense_attn")
+
+
+def sea_output_mix_workspace_bytes(p: SeaParams) -> int:
+    cp = p.c()
+    return int(_lib.sea_output_mix_workspace_bytes(ctypes.byref(cp)))
+
+
+def sea_output_mix(p: SeaParams, C, V, s_mix, O, workspace, s_prob=None, A_hat=None, stream=None):
+    n = p.B * p.H * p.T
+    cp = p.c()
+    _check(_lib.sea_output_mix(ctypes.byref(cp), _ptr(C, p.torch_dtype, n * p.d, "C"),
+                               _ptr(V, p.torch_dtype, n * p.d, "V"),
+                               _ptr(A_hat, torch.float32, n * p.K, "A_hat"),
+                               _ptr(s_prob, torch.float32, n, "s_prob"),
+                               _ptr(s_mix, torch.float32, n, "s_mix"),
+                               _ptr(O, p.torch_dtype, n * p.d, "O"),
+                               _ptr(workspace, None, None, "workspace"),
+                               workspace.numel() * workspace.element_size(), _stream(stream)),
+           "sea_output_mix")
 
 
 def sea_profile_enable(stages=True):

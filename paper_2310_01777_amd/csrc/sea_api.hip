@@ -301,6 +301,28 @@ int sea_dense_attn(const sea_params* p, const void* Q, const void* K, const void
   return e == hipSuccess ? SEA_OK : fail_hip(e);
 }
 
+size_t sea_output_mix_workspace_bytes(const sea_params* p) {
+  if (check_common(p) != SEA_OK) return 0;
+  return output_mix_workspace(make_shape(p, false));
+}
+
+int sea_output_mix(const sea_params* p, const void* C, const void* V, const float* A_hat,
+                   const float* s_prob, const float* s_mix, void* O, void* workspace,
+                   size_t workspace_bytes, void* hip_stream) {
+  const int rc = check_common(p);
+  if (rc != SEA_OK) return rc;
+  if (!C || !V || !s_mix || !O) return SEA_EINVAL;
+  if (!p->causal && (!A_hat || p->K <= 0 || p->K > p->T)) return SEA_EINVAL;
+  if (!p->causal && p->K > 1024) return SEA_ENOTSUP;
+  const Shape s = make_shape(p, false);
+  if (!workspace || workspace_bytes < output_mix_workspace(s) ||
+      reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+    return SEA_EWORKSPACE;
+  const hipError_t e = launch_output_mix(s, p->dtype, C, V, A_hat, s_prob, s_mix, O, workspace,
+                                         static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SEA_OK : fail_hip(e);
+}
+
 int sea_profile_enable(int stage_mask) {
   g_profile = static_cast<unsigned>(stage_mask) & ((1u << SEA_STAGE_COUNT) - 1u);
   return SEA_OK;

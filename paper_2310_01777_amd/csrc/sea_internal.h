@@ -62,6 +62,11 @@ hipError_t launch_sparse_attn(const Shape& s, sea_dtype dt, const void* Q, const
 hipError_t launch_dense_attn(const Shape& s, sea_dtype dt, const void* Q, const void* K,
                              const void* V, void* O, void* ws, hipStream_t st);
 
+size_t output_mix_workspace(const Shape& s);
+hipError_t launch_output_mix(const Shape& s, sea_dtype dt, const void* C, const void* V,
+                             const float* A_hat, const float* s_prob, const float* s_mix, void* O,
+                             void* ws, hipStream_t st);
+
 // ---- per-stage event timing (see sea_profile_enable) ----
 void stage_begin(sea_stage stage, hipStream_t st);
 void stage_end(sea_stage stage, hipStream_t st);

@@ -237,6 +237,34 @@ def test_dense_baseline_matches_library_softmax(sea, causal, pad, T):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("causal", [True, False])
+def test_output_mix_matches_oracle(sea, dtype, causal):
+    """Sec. 3.1.1 output mixing with caller-supplied scalers, on top of a real forward pass."""
+    wl = _wl("mix", 2, 3, 777 if causal else 320, 64, 37 if causal else 40, 6, causal=causal, dtype=dtype,
+             pad_frac=0.25)
+    x = synth.make_inputs(wl)
+    p, xd, g = _gpu_forward(sea, wl, x)
+    gen = torch.Generator().manual_seed(2)
+    s_mix = torch.rand(wl.B, wl.H, wl.T, generator=gen)
+    s_prob = torch.rand(wl.B, wl.H, wl.T, generator=gen)
+    ws = torch.empty(sea.sea_output_mix_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    C_dev, A_dev = g["O"].cuda(), g["A_hat"].cuda()
+    O = torch.empty_like(C_dev)
+    sea.sea_output_mix(p, C_dev, xd["V"], s_mix.cuda(), O, ws, s_prob=s_prob.cuda(), A_hat=A_dev)
+    torch.cuda.synchronize()
+    po = oracle_params(wl)
+    want = oracle.output_mix(po, to_np64(g["O"]), to_np64(x["V"]), s_mix.numpy(), s_prob=s_prob.numpy(),
+                             A_hat=g["A_hat"].numpy(), seq_len=x["seq_len"].numpy())
+    assert_close(to_np64(O), want, TOL[dtype], "C_sea")
+    # in place, and without s_prob
+    sea.sea_output_mix(p, C_dev, xd["V"], s_mix.cuda(), C_dev, ws, A_hat=A_dev)
+    torch.cuda.synchronize()
+    want = oracle.output_mix(po, to_np64(g["O"]), to_np64(x["V"]), s_mix.numpy(), A_hat=g["A_hat"].numpy(),
+                             seq_len=x["seq_len"].numpy())
+    assert_close(to_np64(C_dev), want, TOL[dtype], "C_sea in place")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_topk_mask_exact_on_planted_ties(sea, dtype):
     """Selection and expansion are integer work: bit-exact, including planted duplicates."""
     g = torch.Generator().manual_seed(5)

@@ -529,3 +529,48 @@ def test_per_batch_forward_composition():
     assert np.array_equal(nsel, np.broadcast_to(np.minimum(H * kh, H * ncand), (B, T)))
     with pytest.raises(ValueError):
         oracle.forward(p, Q, Kk, V, W, heads=(1, 3))
+
+
+# ----------------------------------------------------------------------------------------------
+# output mixing -- Sec. 3.1.1 "Output Calculation"
+# ----------------------------------------------------------------------------------------------
+
+def test_output_mix_limits_and_closed_forms():
+    g = np.random.default_rng(8)
+    B, H, T, d, K = 2, 2, 24, 6, 6
+    C, V = g.standard_normal((B, H, T, d)), g.standard_normal((B, H, T, d))
+    A = g.random((B, H, T, K)); A /= A.sum(-1, keepdims=True)
+    seq_len = np.array([T, 17], dtype=np.int32)
+    ones, zeros = np.ones((B, H, T)), np.zeros((B, H, T))
+    valid = (np.arange(T)[None, :] < seq_len[:, None])[:, None, :, None]
+    for causal in (True, False):
+        p = oracle.Params(B=B, H=H, T=T, d=d, m=4, K=K, k_hat=2, causal=causal)
+        # s_mix = 1, s_prob = 1: the sparse output passes through (padded rows are zero)
+        np.testing.assert_allclose(oracle.output_mix(p, C, V, ones, A_hat=A, seq_len=seq_len), C * valid, atol=1e-15)
+        # s_prob rescales the sparse part only
+        sp = g.random((B, H, T))
+        np.testing.assert_allclose(oracle.output_mix(p, C, V, ones, s_prob=sp, A_hat=A, seq_len=seq_len),
+                                   C * sp[..., None] * valid, atol=1e-15)
+        # s_mix = 0: the pooled context alone
+        got = oracle.output_mix(p, C, V, zeros, A_hat=A, seq_len=seq_len)
+        if causal:     # running mean of the values, library cumsum
+            want = np.cumsum(V, axis=2) / np.arange(1, T + 1)[None, None, :, None]
+        else:          # importance = column means of A_hat over active rows, stretched, weighted average
+            want = np.zeros_like(V)
+            for b in range(B):
+                ln = seq_len[b]
+                ih = A[b, :, :ln].mean(1)                                   # [H, K]
+                wj = ih[:, (np.arange(ln) * K) // T]                         # [H, ln]
+                pooled = np.einsum("hj,hjd->hd", wj, V[b, :, :ln]) / wj.sum(-1, keepdims=True)
+                want[b] = pooled[:, None, :]
+        np.testing.assert_allclose(got, want * valid, rtol=1e-12, atol=1e-14)
+        # constant values: any average of them is that constant
+        Vc = np.broadcast_to(np.array([1.0, -2.0, 3.0, 0.5, 0.0, 7.0]), V.shape).copy()
+        got = oracle.output_mix(p, C, Vc, zeros, A_hat=A, seq_len=seq_len)
+        np.testing.assert_allclose(got, Vc * valid, rtol=1e-12, atol=1e-14)
+        # linear in s_mix between the two limits
+        sm = g.random((B, H, T))
+        mix = oracle.output_mix(p, C, V, sm, s_prob=sp, A_hat=A, seq_len=seq_len)
+        a = oracle.output_mix(p, C, V, ones, s_prob=sp, A_hat=A, seq_len=seq_len)
+        z = oracle.output_mix(p, C, V, zeros, A_hat=A, seq_len=seq_len)
+        np.testing.assert_allclose(mix, sm[..., None] * a + (1 - sm[..., None]) * z, rtol=1e-12, atol=1e-14)
