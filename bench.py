@@ -218,6 +218,21 @@ def main():
         dense = {"ms_per_call": dms, "tokens_per_s": tokens / (dms * 1e-3),
                  "tflops": dflops / (dms * 1e-3) / 1e12, "kernel": "tile_attn_kernel<dense>"}
 
+    # ---- output mixing epilogue (Sec. 3.1.1), timed on its own: not part of the headline step ----
+    mix_ms = None
+    if wl.causal:   # the bidirectional form also needs A_hat, which the headline step does not keep
+        mws = torch.empty(sea.sea_output_mix_workspace_bytes(p), dtype=torch.uint8, device=dev)
+        s_mix = torch.rand(wl.B, wl.H, wl.T, device=dev)
+        Om = torch.empty_like(O)
+        for _ in range(3):
+            sea.sea_output_mix(p, O, d["V"], s_mix, Om, mws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            sea.sea_output_mix(p, O, d["V"], s_mix, Om, mws)
+        torch.cuda.synchronize()
+        mix_ms = (time.perf_counter() - t0) / 10 * 1e3
+
     out = {
         "metric": "SEA attn fwd tokens/s per layer + % HBM/MFMA roofline, T=1k..32k",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -232,6 +247,7 @@ def main():
         "stage_ms": avg,
         "estimator": est,
         "dense_attention": dense,
+        "output_mix_ms": mix_ms,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, x, args.cpu_seconds)
