@@ -413,7 +413,6 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
   // score per (column tile, lane).  The k^-th largest score is found by a bitwise search on
   // order-preserving integer keys; counts are summed over the 16 lanes with DPP.  Scores are
   // in [0, 1], so the key's two top bits are known and the search starts below them.
-  const int32_t ntile = (ncols_wave + 15) >> 4;  // column tiles holding candidates (wave-uniform)
   uint32_t tau[4], cge[4], nsel[4];
   uint32_t key[kMaxColTiles][4];
 #pragma unroll
@@ -443,8 +442,7 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
       const uint32_t trial = tau[i] | (1u << bit);
       uint32_t cnt = 0;
 #pragma unroll
-      for (int ct = 0; ct < kMaxColTiles; ++ct)
-        if (ct < ntile) cnt += (key[ct][i] >= trial) ? 1u : 0u;
+      for (int ct = 0; ct < kMaxColTiles; ++ct) cnt += (key[ct][i] >= trial) ? 1u : 0u;  // non-candidates are 0
       cnt = group_sum_u<16>(cnt);
       const bool take = cnt >= nsel[i];
       tau[i] = take ? trial : tau[i];
