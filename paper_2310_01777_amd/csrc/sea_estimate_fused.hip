@@ -329,10 +329,22 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
     if (w > 16 && r0 < s.T) {
       // earlier tiles of the same column: every key precedes every row of the wave
       const int32_t tile0 = ((r0 >> WLOG) << WLOG) >> 4, tile1 = r0 >> 4;
-      for (int32_t kt = tile0; kt < tile1; ++kt) {
-        const uint16_t* src = phiKb + (head * s.T + kt * 16 + lr) * m + 8 * lg;
+      if (tile0 < tile1) {
+        // fragments of the next tile are fetched while the current one is multiplied
+        const uint16_t* src = phiKb + (head * s.T + tile0 * 16 + lr) * m + 8 * lg;
+        bf16x8 cur[MC], nxt[MC];
 #pragma unroll
-        for (int kc = 0; kc < MC; ++kc) sd = mfma16(afrag[kc], *reinterpret_cast<const bf16x8*>(src + 32 * kc), sd);
+        for (int kc = 0; kc < MC; ++kc) cur[kc] = *reinterpret_cast<const bf16x8*>(src + 32 * kc);
+        for (int32_t kt = tile0; kt < tile1; ++kt) {
+          const uint16_t* nsrc = src + static_cast<int64_t>(kt + 1 < tile1 ? 16 : 0) * m;
+#pragma unroll
+          for (int kc = 0; kc < MC; ++kc) nxt[kc] = *reinterpret_cast<const bf16x8*>(nsrc + 32 * kc);
+#pragma unroll
+          for (int kc = 0; kc < MC; ++kc) sd = mfma16(afrag[kc], cur[kc], sd);
+#pragma unroll
+          for (int kc = 0; kc < MC; ++kc) cur[kc] = nxt[kc];
+          src = nsrc;
+        }
       }
     }
 #pragma unroll
