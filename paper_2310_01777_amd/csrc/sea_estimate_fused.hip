@@ -1,6 +1,8 @@
 // Fused random-feature estimate for the common shapes (bf16, K | T, column width a power of two
-// up to 128, m in {64, 128, 256}, K <= 256): two kernels; no feature tensor reaches HBM except,
-// for causal columns wider than 16 keys, the rounded per-key features the own-column term needs.
+// up to 128, m in {64, 128, 256}, K <= 256): two kernels; no feature tensor reaches HBM.  For causal
+// columns wider than 16 keys the key side also leaves, per 16-key tile, the sum of the rounded
+// features of the column's earlier tiles, split into three bf16 planes (24 bits, i.e. the fp32
+// sum itself), which is all the own-column term needs from outside the wave.
 // (Sec. 3 "Performer (FAVOR+)", Sec. 3.1 "Attention Matrix Estimation".)
 //
 //   key_state_kernel      phi(K) on the matrix cores -> per-column sums -> state (bf16, K x m)
@@ -110,13 +112,14 @@ __device__ __forceinline__ void project(const uint16_t* Ws, bf16x8 x0, bf16x8 x1
 template <int MC, int WLOG>
 __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
     Shape s, const uint16_t* __restrict__ K, const uint16_t* __restrict__ W, uint16_t* __restrict__ state,
-    uint16_t* __restrict__ phiKb, float c_dot, float c_norm) {
+    uint16_t* __restrict__ pref, float c_dot, float c_norm) {
   constexpr int m = 32 * MC;
   constexpr int w = 1 << WLOG;
   constexpr int kWaves = w > 64 ? w / 16 : 4;  // waves per block: a column never spans two blocks
   constexpr int kRows = 16 * kWaves;
   __shared__ __attribute__((aligned(16))) uint16_t Ws[m * kWRow];
-  __shared__ float part[w > 16 ? kWaves * m : 1];  // per-wave sums when a column spans several waves
+  __shared__ float part[w > 16 ? kWaves * m : 1];   // per-wave sums when a column spans several waves
+  __shared__ float tpart[w > 16 ? kWaves * m : 1];  // the same sums over the bf16-rounded features
   const int tid = threadIdx.x, lane = tid & 63;
   const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 15, lg = lane >> 4;
@@ -145,16 +148,15 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
   for (int ft = 0; ft < 2 * MC; ++ft)
 #pragma unroll
     for (int i = 0; i < 4; ++i) v[ft][i] = active ? __builtin_amdgcn_exp2f(v[ft][i]) : 0.f;
-  if (phiKb && t < s.T) {
-    // per-key features, rounded, in fragment order: read back by the query side for the keys
-    // of a causal row's own column that precede its wave
-    uint16_t* dst = phiKb + (head * s.T + t) * m + 8 * lg;
+  if (w > 16 && pref) {
+    // tile sums of the rounded per-key features (what a causal row's own-column term is made of)
 #pragma unroll
-    for (int kc = 0; kc < MC; ++kc) {
-      const float lo[4] = {v[2 * kc][0], v[2 * kc][1], v[2 * kc][2], v[2 * kc][3]};
-      const float hi[4] = {v[2 * kc + 1][0], v[2 * kc + 1][1], v[2 * kc + 1][2], v[2 * kc + 1][3]};
-      *reinterpret_cast<bf16x8*>(dst + 32 * kc) = pack8(lo, hi);
-    }
+    for (int ft = 0; ft < 2 * MC; ++ft)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float r = group_sum<16>(bf16_to_f32(f32_to_bf16(v[ft][i])));
+        if (lr == 0) tpart[wid * m + 32 * (ft >> 1) + 8 * lg + 4 * (ft & 1) + i] = r;
+      }
   }
 #pragma unroll
   for (int ft = 0; ft < 2 * MC; ++ft)
@@ -192,6 +194,26 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
       for (int q = 0; q < wpc; ++q) acc += part[(cl * wpc + q) * m + p];
       if (col0 + cl < s.K) sh[static_cast<int64_t>(col0 + cl) * m + p] = f32_to_bf16(acc);
     }
+    if (pref) {
+      // exclusive prefix over the column's tiles, as bf16 planes hi + lo + lo2 (each difference is
+      // exact in fp32, so the three planes carry the leading 24 bits of the sum)
+      const int64_t ntile = s.T >> 4;
+      const int64_t tile0 = static_cast<int64_t>(blockIdx.x % tiles) * kWaves;
+      for (int x = tid; x < kWaves * m; x += 64 * kWaves) {
+        const int q = x / m, p = x - q * m, qc = q & (wpc - 1);
+        if (qc == 0 || tile0 + q >= ntile) continue;  // a column's first tile has nothing before it
+        float P = 0.f;
+        for (int j = q - qc; j < q; ++j) P += tpart[j * m + p];
+        const uint16_t hi = f32_to_bf16(P);
+        const float r1 = P - bf16_to_f32(hi);
+        const uint16_t lo = f32_to_bf16(r1);
+        const uint16_t lo2 = f32_to_bf16(r1 - bf16_to_f32(lo));
+        uint16_t* dst = pref + ((head * ntile + tile0 + q) * 3) * m + p;
+        dst[0] = hi;
+        dst[m] = lo;
+        dst[2 * m] = lo2;
+      }
+    }
   }
 }
 
@@ -206,7 +228,7 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
                                                             const uint16_t* __restrict__ K,
                                                             const uint16_t* __restrict__ W,
                                                             const uint16_t* __restrict__ state,
-                                                            const uint16_t* __restrict__ phiKb,
+                                                            const uint16_t* __restrict__ pref,
                                                             float* __restrict__ A_hat,
                                                             uint32_t* __restrict__ mbits, float c_dot,
                                                             float c_norm) {
@@ -256,6 +278,17 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
   SEA_SPARK1(sreg2, 2, buf_)     \
   SEA_SPARK1(sreg3, 3, buf_)
 
+  // the wave's query (and, causal, key) rows are requested before the staging waits
+  const int32_t t = r0 + lr, tc = min(t, s.T - 1);
+  const uint16_t* Xq = Q + (head * s.T + tc) * kHeadDim;
+  const bf16x8 x0 = *reinterpret_cast<const bf16x8*>(Xq + 8 * lg);
+  const bf16x8 x1 = *reinterpret_cast<const bf16x8*>(Xq + 32 + 8 * lg);
+  const uint16_t* Xk = K + (head * s.T + tc) * kHeadDim;
+  bf16x8 y0 = x0, y1 = x1;
+  if (CAUSAL) {
+    y0 = *reinterpret_cast<const bf16x8*>(Xk + 8 * lg);
+    y1 = *reinterpret_cast<const bf16x8*>(Xk + 32 + 8 * lg);
+  }
   stage_w(W, Ws, m, tid);
   if (nstages > 0) {
     SEA_SFETCH(0);
@@ -264,12 +297,8 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
   __syncthreads();
 
   // ---- phi(Q) of this wave's 16 rows, as contraction fragments ----
-  const int32_t t = r0 + lr, tc = min(t, s.T - 1);
   bf16x8 afrag[MC];
   {
-    const uint16_t* X = Q + (head * s.T + tc) * kHeadDim;
-    const bf16x8 x0 = *reinterpret_cast<const bf16x8*>(X + 8 * lg);
-    const bf16x8 x1 = *reinterpret_cast<const bf16x8*>(X + 32 + 8 * lg);
     float nx = sumsq8(x0) + sumsq8(x1);
     nx += __shfl_xor(nx, 16, kWave);
     nx += __shfl_xor(nx, 32, kWave);
@@ -301,9 +330,6 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
     // the row's own column: sum over keys j <= t of that column of phi(q_t) . phi(k_j).  Those
     // keys are the wave's own 16 rows (S = phi(Q) phi(K_own)^T with a lower-triangular, same-column
     // mask) and, for columns wider than 16, the 16-key tiles of the column before the wave.
-    const uint16_t* X = K + (head * s.T + tc) * kHeadDim;
-    const bf16x8 y0 = *reinterpret_cast<const bf16x8*>(X + 8 * lg);
-    const bf16x8 y1 = *reinterpret_cast<const bf16x8*>(X + 32 + 8 * lg);
     float ny = sumsq8(y0) + sumsq8(y1);
     ny += __shfl_xor(ny, 16, kWave);
     ny += __shfl_xor(ny, 32, kWave);
@@ -326,25 +352,16 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
       const bool ok = (lr <= rq) && (w >= 16 || (lr >> WLOG) == (rq >> WLOG));
       sd[i] = ok ? sd[i] : 0.f;
     }
-    if (w > 16 && r0 < s.T) {
-      // earlier tiles of the same column: every key precedes every row of the wave
-      const int32_t tile0 = ((r0 >> WLOG) << WLOG) >> 4, tile1 = r0 >> 4;
-      if (tile0 < tile1) {
-        // fragments of the next tile are fetched while the current one is multiplied
-        const uint16_t* src = phiKb + (head * s.T + tile0 * 16 + lr) * m + 8 * lg;
-        bf16x8 cur[MC], nxt[MC];
+    if (w > 16 && r0 < s.T && ((r0 >> 4) & (w / 16 - 1)) != 0) {
+      // earlier tiles of the same column: every key precedes every row of the wave, so only their
+      // sum matters.  Its three planes are operand columns 0..2 (the rest zero); the row sum over
+      // the 16 result columns below then adds the three partial dots to the in-wave ones.
+      const uint16_t* src = pref + ((head * (s.T >> 4) + (r0 >> 4)) * 3 + min(lr, 2)) * m + 8 * lg;
 #pragma unroll
-        for (int kc = 0; kc < MC; ++kc) cur[kc] = *reinterpret_cast<const bf16x8*>(src + 32 * kc);
-        for (int32_t kt = tile0; kt < tile1; ++kt) {
-          const uint16_t* nsrc = src + static_cast<int64_t>(kt + 1 < tile1 ? 16 : 0) * m;
-#pragma unroll
-          for (int kc = 0; kc < MC; ++kc) nxt[kc] = *reinterpret_cast<const bf16x8*>(nsrc + 32 * kc);
-#pragma unroll
-          for (int kc = 0; kc < MC; ++kc) sd = mfma16(afrag[kc], cur[kc], sd);
-#pragma unroll
-          for (int kc = 0; kc < MC; ++kc) cur[kc] = nxt[kc];
-          src = nsrc;
-        }
+      for (int kc = 0; kc < MC; ++kc) {
+        uint4 f = *reinterpret_cast<const uint4*>(src + 32 * kc);
+        if (lr > 2) f = uint4{0u, 0u, 0u, 0u};
+        sd = mfma16(afrag[kc], __builtin_bit_cast(bf16x8, f), sd);
       }
     }
 #pragma unroll
@@ -537,7 +554,7 @@ bool estimate_fused_supported(const Shape& s) {
 
 size_t estimate_fused_workspace(const Shape& s) {
   size_t bytes = (static_cast<size_t>(s.N) * s.K * s.m * 2 + 255) & ~size_t(255);  // state
-  if (s.causal && wlog_of(s) > 4) bytes += static_cast<size_t>(s.N) * s.T * s.m * 2;  // phiKb
+  if (s.causal && wlog_of(s) > 4) bytes += static_cast<size_t>(s.N) * (s.T / 16) * 3 * s.m * 2;  // tile prefixes
   return bytes;
 }
 
@@ -545,39 +562,39 @@ namespace {
 
 template <int MC, int WLOG>
 void launch_both(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W, float* A_hat,
-                 uint32_t* mbits, uint16_t* state, uint16_t* phiKb, float c_dot, float c_norm, hipStream_t st) {
+                 uint32_t* mbits, uint16_t* state, uint16_t* pref, float c_dot, float c_norm, hipStream_t st) {
   constexpr int kKeyWaves = (1 << WLOG) > 64 ? (1 << WLOG) / 16 : 4;
   {
     StageScope scope(SEA_STAGE_STATE, st);
     const uint32_t ktiles = (s.T + 16 * kKeyWaves - 1) / (16 * kKeyWaves);
     hipLaunchKernelGGL((key_state_kernel<MC, WLOG>), dim3(static_cast<uint32_t>(s.N) * ktiles),
-                       dim3(64 * kKeyWaves), 0, st, s, K, W, state, phiKb, c_dot, c_norm);
+                       dim3(64 * kKeyWaves), 0, st, s, K, W, state, pref, c_dot, c_norm);
   }
   {
     StageScope scope(SEA_STAGE_CONTRACT, st);
     const uint32_t tiles = (s.T + 63) / 64;
     const dim3 grid(static_cast<uint32_t>(s.N) * tiles), block(256);
     if (s.causal)
-      hipLaunchKernelGGL((estimate_rows_kernel<MC, true, WLOG>), grid, block, 0, st, s, Q, K, W, state, phiKb,
+      hipLaunchKernelGGL((estimate_rows_kernel<MC, true, WLOG>), grid, block, 0, st, s, Q, K, W, state, pref,
                          A_hat, mbits, c_dot, c_norm);
     else
-      hipLaunchKernelGGL((estimate_rows_kernel<MC, false, WLOG>), grid, block, 0, st, s, Q, K, W, state, phiKb,
+      hipLaunchKernelGGL((estimate_rows_kernel<MC, false, WLOG>), grid, block, 0, st, s, Q, K, W, state, pref,
                          A_hat, mbits, c_dot, c_norm);
   }
 }
 
 template <int MC>
 void launch_w(const Shape& s, int wl, const uint16_t* Q, const uint16_t* K, const uint16_t* W, float* A_hat,
-              uint32_t* mbits, uint16_t* state, uint16_t* phiKb, float c_dot, float c_norm, hipStream_t st) {
+              uint32_t* mbits, uint16_t* state, uint16_t* pref, float c_dot, float c_norm, hipStream_t st) {
   switch (wl) {
-    case 0: launch_both<MC, 0>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
-    case 1: launch_both<MC, 1>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
-    case 2: launch_both<MC, 2>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
-    case 3: launch_both<MC, 3>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
-    case 4: launch_both<MC, 4>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
-    case 5: launch_both<MC, 5>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
-    case 6: launch_both<MC, 6>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
-    default: launch_both<MC, 7>(s, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
+    case 0: launch_both<MC, 0>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
+    case 1: launch_both<MC, 1>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
+    case 2: launch_both<MC, 2>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
+    case 3: launch_both<MC, 3>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
+    case 4: launch_both<MC, 4>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
+    case 5: launch_both<MC, 5>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
+    case 6: launch_both<MC, 6>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
+    default: launch_both<MC, 7>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
   }
 }
 
@@ -588,17 +605,17 @@ hipError_t launch_estimate_fused(const Shape& s, const uint16_t* Q, const uint16
   if (!estimate_fused_supported(s)) return hipErrorNotSupported;
   uint16_t* state = static_cast<uint16_t*>(ws);
   const int wl = wlog_of(s);
-  uint16_t* phiKb = nullptr;
+  uint16_t* pref = nullptr;
   if (s.causal && wl > 4)
-    phiKb = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) +
+    pref = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) +
                                         ((static_cast<size_t>(s.N) * s.K * s.m * 2 + 255) & ~size_t(255)));
   const double l2e = 1.4426950408889634;
   const float c_dot = static_cast<float>(l2e * sqrt(static_cast<double>(s.scale)));
   const float c_norm = static_cast<float>(l2e * 0.5 * static_cast<double>(s.scale));
   switch (s.m) {
-    case 64: launch_w<2>(s, wl, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
-    case 128: launch_w<4>(s, wl, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
-    default: launch_w<8>(s, wl, Q, K, W, A_hat, mbits, state, phiKb, c_dot, c_norm, st); break;
+    case 64: launch_w<2>(s, wl, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
+    case 128: launch_w<4>(s, wl, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
+    default: launch_w<8>(s, wl, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
   }
   return hipGetLastError();
 }
