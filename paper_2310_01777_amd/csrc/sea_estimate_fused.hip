@@ -224,7 +224,7 @@ constexpr int kColStage = 32;   // columns of the state staged in LDS per step
 constexpr int kMaxColTiles = 16;  // K <= 256
 
 template <int MC, bool CAUSAL, int WLOG>
-__global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint16_t* __restrict__ Q,
+__global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const uint16_t* __restrict__ Q,
                                                             const uint16_t* __restrict__ K,
                                                             const uint16_t* __restrict__ W,
                                                             const uint16_t* __restrict__ state,
@@ -235,8 +235,11 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
   constexpr int m = 32 * MC;
   constexpr int w = 1 << WLOG;
   constexpr int kSRow = m + 8;  // halfwords per staged state row (+16 B pad): conflict-free b128 reads
-  __shared__ __attribute__((aligned(16))) uint16_t Ws[m * kWRow];
-  __shared__ __attribute__((aligned(16))) uint16_t Ss[2][kColStage * kSRow];
+  // W is dead once both projections are done; the state stages then reuse its space
+  constexpr int kStageHalfwords = kColStage * kSRow;
+  constexpr int kSmemHalfwords = m * kWRow > 2 * kStageHalfwords ? m * kWRow : 2 * kStageHalfwords;
+  __shared__ __attribute__((aligned(16))) uint16_t smem[kSmemHalfwords];
+  uint16_t* const Ws = smem;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 15, lg = lane >> 4;
@@ -270,7 +273,7 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
 #define SEA_SPARK1(reg_, q_, buf_)                                                              \
   if (kVecPerThread > (q_)) {                                                                  \
     const int x_ = tid + 256 * (q_);                                                           \
-    *reinterpret_cast<uint4*>(&Ss[buf_][(x_ / (m / 8)) * kSRow + (x_ % (m / 8)) * 8]) = reg_;    \
+    *reinterpret_cast<uint4*>(&smem[(buf_) * kStageHalfwords + (x_ / (m / 8)) * kSRow + (x_ % (m / 8)) * 8]) = reg_;    \
   }
 #define SEA_SPARK(buf_)          \
   SEA_SPARK1(sreg0, 0, buf_)     \
@@ -290,10 +293,7 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
     y1 = *reinterpret_cast<const bf16x8*>(Xk + 32 + 8 * lg);
   }
   stage_w(W, Ws, m, tid);
-  if (nstages > 0) {
-    SEA_SFETCH(0);
-    SEA_SPARK(0);
-  }
+  if (nstages > 0) { SEA_SFETCH(0); }  // parked in LDS after the projections
   __syncthreads();
 
   // ---- phi(Q) of this wave's 16 rows, as contraction fragments ----
@@ -324,6 +324,7 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
       afrag[kc] = pack8(lo, hi);
     }
   }
+  __builtin_amdgcn_sched_barrier(0);  // keep the two projections' temporaries from overlapping
   // accumulator rows of this lane: r0 + 4 lg + i
   float diag[4] = {0.f, 0.f, 0.f, 0.f};
   if (CAUSAL) {
@@ -369,6 +370,9 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
   }
 
   // ---- A_hat tile = phi(Q) state^T, state streamed through LDS ----
+  __syncthreads();  // every wave is done with W
+  if (nstages > 0) { SEA_SPARK(0); }
+  __syncthreads();
   floatx4 acc[kMaxColTiles];
 #pragma unroll
   for (int ct = 0; ct < kMaxColTiles; ++ct) acc[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -380,7 +384,7 @@ __global__ __launch_bounds__(256) void estimate_rows_kernel(Shape s, const uint1
       if (r0 < s.T && st * kColStage < ncols_wave) {
 #pragma unroll
         for (int h = 0; h < kColStage / 16; ++h) {
-          const uint16_t* brow = &Ss[st & 1][(16 * h + lr) * kSRow + 8 * lg];
+          const uint16_t* brow = &smem[(st & 1) * kStageHalfwords + (16 * h + lr) * kSRow + 8 * lg];
           floatx4 a4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int kc = 0; kc < MC; ++kc)
