@@ -42,6 +42,7 @@ struct TileArgs {
   int32_t rlog;         // log2(keys per column r)
   int32_t w;            // column width in keys
   int32_t causal;
+  int32_t group_heads;  // heads per scheduling group (a multiple of 8 unless it is N)
   float c;              // scale * log2(e)
 };
 
@@ -73,7 +74,6 @@ __device__ __forceinline__ int32_t compact_count(int32_t jmax, int32_t rlog, int
 constexpr int kChunk = 64;   // keys staged in LDS per step (two 32-key MFMA sub-chunks)
 constexpr int kKRow = 72;    // halfwords per staged K row: 128 B + 16 B pad, conflict-free b128 reads
 constexpr int kVRow = 68;    // halfwords per staged V^T row: 128 B + 8 B pad, conflict-free b64 reads
-constexpr int kMaxMaskWords = 32;  // K <= 1024
 
 // Block = 4 waves = 128 consecutive query rows of one head (32 per wave).  The block walks the
 // compact key list in steps of 64 keys; each step's K rows and V^T tile are fetched once with
@@ -85,15 +85,21 @@ template <int RLOG, bool DENSE>
 __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[2][kChunk * kKRow];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[2][kHeadDim * kVRow];
-  __shared__ uint32_t Ms[DENSE ? 1 : 128 * (kMaxMaskWords + 1)];  // selected-column bits of the 128 rows
+  // selected-column bits of the 128 rows, (KW + 1) words per row (K <= 1024: at most 16.5 KB)
+  extern __shared__ uint32_t Ms[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, keep it scalar
   const int ql = lane & 31, g = lane >> 5;
   const uint32_t wgs = (a.T + 127) / 128;  // blocks per head
-  const uint32_t lb = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int64_t head = lb / wgs;
-  // heavy (late, causal) blocks first within a head
-  const int32_t wg_tile = static_cast<int32_t>(wgs - 1 - lb % wgs);
+  // Launch order = longest first: heads are taken in groups whose keys and values fit the L2s;
+  // inside a group the row tiles go from the last (most keys, causal) to the first, heads
+  // fastest.  Blocks are dealt round-robin to the 8 XCDs, so with 8 | group size a head stays on
+  // one XCD, and blocks that start late are the short ones that fill the gaps.
+  const uint32_t per_group = static_cast<uint32_t>(a.group_heads) * wgs;
+  const uint32_t grp = blockIdx.x / per_group, rem = blockIdx.x - grp * per_group;
+  const uint32_t nh = min(static_cast<uint32_t>(a.group_heads), static_cast<uint32_t>(a.N) - grp * a.group_heads);
+  const int64_t head = static_cast<int64_t>(grp) * a.group_heads + rem % nh;
+  const int32_t wg_tile = static_cast<int32_t>(wgs - 1 - rem / nh);
   const int32_t q0 = wg_tile * 128 + 32 * wid;  // first row of this wave
   const int32_t t = q0 + ql;
   const int32_t b = static_cast<int32_t>(head / a.H);
@@ -337,6 +343,16 @@ __global__ __launch_bounds__(256) void compact_kv_kernel(const uint16_t* __restr
 
 }  // namespace
 
+// Heads per scheduling group: the keys and values (2 x Upad x 128 B per head) of the heads an
+// XCD works on at one time should fit its 4 MB L2 with room to spare.
+int32_t group_heads_for(int32_t N, int64_t Upad) {
+  const int64_t per_head = 2 * Upad * kHeadDim * 2;
+  int64_t per_xcd = (3 << 20) / (per_head > 0 ? per_head : 1);
+  if (per_xcd < 1) per_xcd = 1;
+  const int64_t g = 8 * per_xcd;
+  return static_cast<int32_t>(g < N ? g : N);
+}
+
 bool tile_attn_supported(const Shape& s, sea_dtype dt, int32_t* rlog_out) {
   if (dt != SEA_BF16 || s.T % s.K != 0) return false;
   const int32_t w = s.T / s.K;
@@ -384,15 +400,17 @@ hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K
   a.Q = Q; a.Kc = Kc ? Kc : K; a.Vct = Vct; a.mbits = mbits; a.O = O; a.seq_len = s.seq_len;
   a.N = s.N; a.H = s.H; a.T = s.T; a.U = U; a.Upad = Upad; a.KW = (s.K + 31) / 32;
   a.rlog = rlog; a.w = w; a.causal = s.causal;
+  a.group_heads = group_heads_for(s.N, Upad);
   a.c = s.scale * kLog2e;
   const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 127) / 128)), block(256);
+  const size_t shm = static_cast<size_t>(128) * (a.KW + 1) * sizeof(uint32_t);
   switch (rlog) {
-    case 0: hipLaunchKernelGGL((tile_attn_kernel<0, false>), grid, block, 0, st, a); break;
-    case 1: hipLaunchKernelGGL((tile_attn_kernel<1, false>), grid, block, 0, st, a); break;
-    case 2: hipLaunchKernelGGL((tile_attn_kernel<2, false>), grid, block, 0, st, a); break;
-    case 3: hipLaunchKernelGGL((tile_attn_kernel<3, false>), grid, block, 0, st, a); break;
-    case 4: hipLaunchKernelGGL((tile_attn_kernel<4, false>), grid, block, 0, st, a); break;
-    default: hipLaunchKernelGGL((tile_attn_kernel<5, false>), grid, block, 0, st, a); break;
+    case 0: hipLaunchKernelGGL((tile_attn_kernel<0, false>), grid, block, shm, st, a); break;
+    case 1: hipLaunchKernelGGL((tile_attn_kernel<1, false>), grid, block, shm, st, a); break;
+    case 2: hipLaunchKernelGGL((tile_attn_kernel<2, false>), grid, block, shm, st, a); break;
+    case 3: hipLaunchKernelGGL((tile_attn_kernel<3, false>), grid, block, shm, st, a); break;
+    case 4: hipLaunchKernelGGL((tile_attn_kernel<4, false>), grid, block, shm, st, a); break;
+    default: hipLaunchKernelGGL((tile_attn_kernel<5, false>), grid, block, shm, st, a); break;
   }
   return hipGetLastError();
 }
@@ -417,6 +435,7 @@ hipError_t launch_dense_attn(const Shape& s, sea_dtype dt, const void* Q, const 
   a.mbits = nullptr; a.O = static_cast<uint16_t*>(O); a.seq_len = s.seq_len;
   a.N = s.N; a.H = s.H; a.T = s.T; a.U = U; a.Upad = Upad; a.KW = 0; a.rlog = 0; a.w = 1;
   a.causal = s.causal; a.c = s.scale * kLog2e;
+  a.group_heads = group_heads_for(s.N, Upad);
   const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 127) / 128)), block(256);
   hipLaunchKernelGGL((tile_attn_kernel<0, true>), grid, block, 0, st, a);
   return hipGetLastError();
