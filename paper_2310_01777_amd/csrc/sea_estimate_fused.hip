@@ -18,6 +18,8 @@
 // <-> feature map this implies (slot 8 lg + e of chunk kc <-> feature 32 kc + 16 (e / 4) + 4 lg +
 // e % 4) is used consistently for phi(Q), phi(K) and the stored state ("fragment order"), so
 // accumulators feed the next product without any shuffle or memory round trip.
+#include <algorithm>
+
 #include "sea_internal.h"
 
 namespace sea {
@@ -231,7 +233,7 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
                                                             const uint16_t* __restrict__ pref,
                                                             float* __restrict__ A_hat,
                                                             uint32_t* __restrict__ mbits, float c_dot,
-                                                            float c_norm) {
+                                                            float c_norm, int32_t group_heads) {
   constexpr int m = 32 * MC;
   constexpr int w = 1 << WLOG;
   constexpr int kSRow = m + 8;  // halfwords per staged state row (+16 B pad): conflict-free b128 reads
@@ -244,9 +246,14 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 15, lg = lane >> 4;
   const uint32_t tiles = (s.T + 63) / 64;
-  const uint32_t lb = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int64_t head = lb / tiles;
-  const int32_t wg_r0 = static_cast<int32_t>(tiles - 1 - lb % tiles) * 64;  // late (long) rows first
+  // Launch order = longest first: heads in groups whose state fits the L2s, inside a group the
+  // row tiles from the last (most columns, causal) to the first, heads fastest.  Blocks are dealt
+  // round-robin to the 8 XCDs, so with 8 | group size a head's state stays in one XCD's L2.
+  const uint32_t per_group = static_cast<uint32_t>(group_heads) * tiles;
+  const uint32_t grp = blockIdx.x / per_group, rem = blockIdx.x - grp * per_group;
+  const uint32_t nh = min(static_cast<uint32_t>(group_heads), static_cast<uint32_t>(s.N) - grp * group_heads);
+  const int64_t head = static_cast<int64_t>(grp) * group_heads + rem % nh;
+  const int32_t wg_r0 = static_cast<int32_t>(tiles - 1 - rem / nh) * 64;
   const int32_t r0 = wg_r0 + wid * 16;
   const int32_t b = static_cast<int32_t>(head / s.H);
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
@@ -578,12 +585,15 @@ void launch_both(const Shape& s, const uint16_t* Q, const uint16_t* K, const uin
     StageScope scope(SEA_STAGE_CONTRACT, st);
     const uint32_t tiles = (s.T + 63) / 64;
     const dim3 grid(static_cast<uint32_t>(s.N) * tiles), block(256);
+    // heads whose state (K x m bf16 each) shares an XCD's L2 at one time: 2 MB worth
+    const int64_t per_xcd = std::max<int64_t>(1, (int64_t(2) << 20) / (static_cast<int64_t>(s.K) * s.m * 2));
+    const int32_t gh = static_cast<int32_t>(std::min<int64_t>(s.N, 8 * per_xcd));
     if (s.causal)
       hipLaunchKernelGGL((estimate_rows_kernel<MC, true, WLOG>), grid, block, 0, st, s, Q, K, W, state, pref,
-                         A_hat, mbits, c_dot, c_norm);
+                         A_hat, mbits, c_dot, c_norm, gh);
     else
       hipLaunchKernelGGL((estimate_rows_kernel<MC, false, WLOG>), grid, block, 0, st, s, Q, K, W, state, pref,
-                         A_hat, mbits, c_dot, c_norm);
+                         A_hat, mbits, c_dot, c_norm, gh);
   }
 }
 
