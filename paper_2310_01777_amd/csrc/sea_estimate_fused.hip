@@ -223,9 +223,9 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
 // query side.  Block = 4 waves = 64 rows of one head (16 per wave).
 // ------------------------------------------------------------------------------------------
 constexpr int kColStage = 32;   // columns of the state staged in LDS per step
-constexpr int kMaxColTiles = 16;  // K <= 256
 
-template <int MC, bool CAUSAL, int WLOG>
+// NCT = 16-column tiles a row can have (4, 8 or 16 for K <= 64, 128, 256)
+template <int MC, bool CAUSAL, int WLOG, int NCT>
 __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const uint16_t* __restrict__ Q,
                                                             const uint16_t* __restrict__ K,
                                                             const uint16_t* __restrict__ W,
@@ -380,12 +380,12 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   __syncthreads();  // every wave is done with W
   if (nstages > 0) { SEA_SPARK(0); }
   __syncthreads();
-  floatx4 acc[kMaxColTiles];
+  floatx4 acc[NCT];
 #pragma unroll
-  for (int ct = 0; ct < kMaxColTiles; ++ct) acc[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int ct = 0; ct < NCT; ++ct) acc[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
   const int32_t ncols_wave = CAUSAL ? min(s.K, (min(r0 + 15, s.T - 1) >> WLOG) + 1) : s.K;
 #pragma unroll
-  for (int st = 0; st < kMaxColTiles * 16 / kColStage; ++st) {
+  for (int st = 0; st < NCT * 16 / kColStage; ++st) {
     if (st < nstages) {
       if (st + 1 < nstages) { SEA_SFETCH(st + 1); }
       if (r0 < s.T && st * kColStage < ncols_wave) {
@@ -420,7 +420,7 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     ctrow[i] = CAUSAL ? (min(trow[i], s.T - 1) >> WLOG) : s.K;  // first masked column is ctrow + 1
   }
 #pragma unroll
-  for (int ct = 0; ct < kMaxColTiles; ++ct) {
+  for (int ct = 0; ct < NCT; ++ct) {
     const int32_t cc = ct * 16 + lr;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -437,10 +437,10 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     const float r = group_sum<16>(rsum[i]);
     const float inv = r > 0.f ? 1.f / r : 0.f;
 #pragma unroll
-    for (int ct = 0; ct < kMaxColTiles; ++ct) acc[ct][i] *= inv;
+    for (int ct = 0; ct < NCT; ++ct) acc[ct][i] *= inv;
     if (out && trow[i] < s.T) {
 #pragma unroll
-      for (int ct = 0; ct < kMaxColTiles; ++ct) {
+      for (int ct = 0; ct < NCT; ++ct) {
         const int32_t cc = ct * 16 + lr;
         if (cc < s.K) out[static_cast<int64_t>(trow[i]) * s.K + cc] = acc[ct][i];
       }
@@ -454,7 +454,7 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   // order-preserving integer keys; counts are summed over the 16 lanes with DPP.  Scores are
   // in [0, 1], so the key's two top bits are known and the search starts below them.
   uint32_t tau[4], cge[4], nsel[4];
-  uint32_t key[kMaxColTiles][4];
+  uint32_t key[NCT][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int32_t jmax = CAUSAL ? min(trow[i], len - 1) : len - 1;
@@ -463,32 +463,46 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     tau[i] = 0x80000000u;
     cge[i] = static_cast<uint32_t>(ncand);
 #pragma unroll
-    for (int ct = 0; ct < kMaxColTiles; ++ct) {
+    for (int ct = 0; ct < NCT; ++ct) {
       const int32_t cc = ct * 16 + lr;
       key[ct][i] = cc < ncand ? (__float_as_uint(acc[ct][i] + 0.0f) | 0x80000000u) : 0u;
     }
   }
-#pragma unroll 1
-  for (int bit = 29; bit >= 0; --bit) {
-    // done when every row's count of keys >= tau equals its quota
-    bool pending = false;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) pending |= (cge[i] != nsel[i]) && (nsel[i] != 0u);
-    if (__ballot(pending) == 0ull) break;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      // skip the slot once its four rows (one per lane group) are settled
-      if (__ballot((cge[i] != nsel[i]) && (nsel[i] != 0u)) == 0ull) continue;
-      const uint32_t trial = tau[i] | (1u << bit);
-      uint32_t cnt = 0;
-#pragma unroll
-      for (int ct = 0; ct < kMaxColTiles; ++ct) cnt += (key[ct][i] >= trial) ? 1u : 0u;  // non-candidates are 0
-      cnt = group_sum_u<16>(cnt);
-      const bool take = cnt >= nsel[i];
-      tau[i] = take ? trial : tau[i];
-      cge[i] = take ? cnt : cge[i];
-    }
+  // The compare-and-count loop runs over the tiles that hold candidates of this wave's rows only
+  // (causal: the leading ones), in even steps so that a handful of loop bodies covers all cases.
+#define SEA_SEARCH(NT_)                                                                          \
+  _Pragma("unroll 1") for (int bit = 29; bit >= 0; --bit) {                                       \
+    /* done when every row's count of keys >= tau equals its quota */                            \
+    bool pending = false;                                                                        \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) pending |= (cge[i] != nsel[i]) && (nsel[i] != 0u); \
+    if (__ballot(pending) == 0ull) break;                                                        \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                               \
+      /* skip the slot once its four rows (one per lane group) are settled */                    \
+      if (__ballot((cge[i] != nsel[i]) && (nsel[i] != 0u)) == 0ull) continue;                    \
+      const uint32_t trial = tau[i] | (1u << bit);                                               \
+      uint32_t cnt = 0;                                                                          \
+      _Pragma("unroll") for (int ct = 0; ct < (NT_); ++ct) cnt += (key[ct][i] >= trial) ? 1u : 0u; \
+      cnt = group_sum_u<16>(cnt);                                                                \
+      const bool take = cnt >= nsel[i];                                                          \
+      tau[i] = take ? trial : tau[i];                                                            \
+      cge[i] = take ? cnt : cge[i];                                                              \
+    }                                                                                            \
   }
+  const int32_t nct_wave = CAUSAL ? min(NCT, (ncols_wave + 15) >> 4) : NCT;
+  if (NCT >= 16 && nct_wave > 12) {
+    SEA_SEARCH(NCT >= 16 ? 16 : NCT)
+  } else if (NCT >= 16 && nct_wave > 8) {
+    SEA_SEARCH(NCT >= 16 ? 12 : NCT)
+  } else if (NCT >= 8 && nct_wave > 6) {
+    SEA_SEARCH(NCT >= 8 ? 8 : NCT)
+  } else if (NCT >= 8 && nct_wave > 4) {
+    SEA_SEARCH(NCT >= 8 ? 6 : NCT)
+  } else if (nct_wave > 2) {
+    SEA_SEARCH(4)
+  } else {
+    SEA_SEARCH(2)
+  }
+#undef SEA_SEARCH
   // selection: keys >= tau; when more keys than the quota tie at tau (exact duplicates at the
   // boundary), the lowest columns among them win
   uint32_t selbits[4];  // bit ct set: column 16 ct + lr of row 4 lg + i is selected
@@ -500,7 +514,7 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     for (int i = 0; i < 4; ++i) {
       uint32_t bits = 0;
 #pragma unroll
-      for (int ct = 0; ct < kMaxColTiles; ++ct)
+      for (int ct = 0; ct < NCT; ++ct)
         bits |= (nsel[i] != 0u && key[ct][i] >= tau[i]) ? (1u << ct) : 0u;
       selbits[i] = bits;
     }
@@ -509,12 +523,12 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     for (int i = 0; i < 4; ++i) {
       uint32_t cgt = 0;
 #pragma unroll
-      for (int ct = 0; ct < kMaxColTiles; ++ct) cgt += (key[ct][i] > tau[i]) ? 1u : 0u;
+      for (int ct = 0; ct < NCT; ++ct) cgt += (key[ct][i] > tau[i]) ? 1u : 0u;
       cgt = group_sum_u<16>(cgt);
       int32_t need_eq = static_cast<int32_t>(nsel[i]) - static_cast<int32_t>(cgt);
       uint32_t bits = 0;
 #pragma unroll
-      for (int ct = 0; ct < kMaxColTiles; ++ct) {
+      for (int ct = 0; ct < NCT; ++ct) {
         const uint32_t ky = key[ct][i];
         const bool eq = (ky == tau[i]) && (nsel[i] != 0u);
         const uint64_t eqm = __ballot(eq);
@@ -534,7 +548,7 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     if (trow[i] >= s.T) continue;
     uint32_t* mrow = mbits + (head * s.T + trow[i]) * kw;
 #pragma unroll
-    for (int j = 0; j < kMaxColTiles / 2; ++j) {
+    for (int j = 0; j < NCT / 2; ++j) {
       const uint64_t b0 = __ballot((selbits[i] >> (2 * j)) & 1u);
       const uint64_t b1 = __ballot((selbits[i] >> (2 * j + 1)) & 1u);
       const uint32_t word = (static_cast<uint32_t>(b0 >> (16 * lg)) & 0xffffu) |
@@ -571,6 +585,18 @@ size_t estimate_fused_workspace(const Shape& s) {
 
 namespace {
 
+template <int MC, int WLOG, int NCT>
+void launch_rows(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W, float* A_hat,
+                 uint32_t* mbits, const uint16_t* state, const uint16_t* pref, float c_dot, float c_norm,
+                 int32_t gh, dim3 grid, hipStream_t st) {
+  if (s.causal)
+    hipLaunchKernelGGL((estimate_rows_kernel<MC, true, WLOG, NCT>), grid, dim3(256), 0, st, s, Q, K, W, state,
+                       pref, A_hat, mbits, c_dot, c_norm, gh);
+  else
+    hipLaunchKernelGGL((estimate_rows_kernel<MC, false, WLOG, NCT>), grid, dim3(256), 0, st, s, Q, K, W, state,
+                       pref, A_hat, mbits, c_dot, c_norm, gh);
+}
+
 template <int MC, int WLOG>
 void launch_both(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W, float* A_hat,
                  uint32_t* mbits, uint16_t* state, uint16_t* pref, float c_dot, float c_norm, hipStream_t st) {
@@ -584,16 +610,16 @@ void launch_both(const Shape& s, const uint16_t* Q, const uint16_t* K, const uin
   {
     StageScope scope(SEA_STAGE_CONTRACT, st);
     const uint32_t tiles = (s.T + 63) / 64;
-    const dim3 grid(static_cast<uint32_t>(s.N) * tiles), block(256);
+    const dim3 grid(static_cast<uint32_t>(s.N) * tiles);
     // heads whose state (K x m bf16 each) shares an XCD's L2 at one time: 2 MB worth
     const int64_t per_xcd = std::max<int64_t>(1, (int64_t(2) << 20) / (static_cast<int64_t>(s.K) * s.m * 2));
     const int32_t gh = static_cast<int32_t>(std::min<int64_t>(s.N, 8 * per_xcd));
-    if (s.causal)
-      hipLaunchKernelGGL((estimate_rows_kernel<MC, true, WLOG>), grid, block, 0, st, s, Q, K, W, state, pref,
-                         A_hat, mbits, c_dot, c_norm, gh);
+    if (s.K <= 64)
+      launch_rows<MC, WLOG, 4>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, gh, grid, st);
+    else if (s.K <= 128)
+      launch_rows<MC, WLOG, 8>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, gh, grid, st);
     else
-      hipLaunchKernelGGL((estimate_rows_kernel<MC, false, WLOG>), grid, block, 0, st, s, Q, K, W, state, pref,
-                         A_hat, mbits, c_dot, c_norm, gh);
+      launch_rows<MC, WLOG, 16>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, gh, grid, st);
   }
 }
 
