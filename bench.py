@@ -170,7 +170,7 @@ def main():
     sparse_ms = avg.get("sparse", 0.0)
     algo_flops = 4.0 * wl.d * pairs
     algo_bytes = pairs * (2 * wl.d * es + 4) + nrows * (2 * wl.d * es + 4)
-    tiled = "compact" in avg            # the tiled matrix-core kernel ran (bf16, column-structured mask)
+    tiled = sea.sea_attention_path(p) == 1   # the tiled matrix-core kernel ran (bf16, column-structured mask)
     if tiled:
         issued = issued_tile_flops(wl, x["seq_len"])
         ach = algo_flops / (sparse_ms * 1e-3) / 1e12

@@ -160,7 +160,8 @@ int sea_output_mix(const sea_params* p, const void* C, const void* V, const floa
  * Quadratic attention A = softmax(scale QK^T), C = AV (Sec. 3 "Preliminaries"), causal and/or
  * right-padded like the sparse path, computed tile by tile with no T x T buffer.  This is the
  * baseline the sparse path is reported against, not part of SEA.  bf16 only (SEA_ENOTSUP for
- * fp32); needs sea_dense_workspace_bytes() of 256-byte aligned scratch (a transposed copy of V).
+ * fp32).  sea_dense_workspace_bytes() is the scratch it needs, 256-byte aligned; this version
+ * needs none (returns 0) and then accepts workspace == NULL.
  */
 size_t sea_dense_workspace_bytes(const sea_params* p);
 int sea_dense_attn(const sea_params* p, const void* Q, const void* K, const void* V, void* O,
@@ -181,7 +182,7 @@ typedef enum {
   SEA_STAGE_TOPK_MASK = 3,/* a4 + a5                                                       */
   SEA_STAGE_SPARSE = 4,   /* a6                                                            */
   SEA_STAGE_DENSE = 5,    /* dense baseline                                                */
-  SEA_STAGE_COMPACT = 6,  /* compact key list and transposed V for the tiled attention     */
+  SEA_STAGE_COMPACT = 6,  /* reserved (no kernel: keys and values are read in place)          */
   SEA_STAGE_COUNT = 7
 } sea_stage;
 int sea_profile_enable(int stage_mask);
@@ -189,6 +190,14 @@ int sea_profile_collect(double* host_ms /*[SEA_STAGE_COUNT]*/, int64_t* host_lau
 
 const char* sea_strerror(int status);
 int sea_last_hip_error(void);
+/*
+ * Which kernel sea_forward's sparse attention stage (Sec. 3.1.1) runs for these parameters:
+ * 1 = the tiled matrix-core kernel over the column-structured mask (bf16, K | T, a power-of-two
+ * number of keys per selected column), 0 = the per-row index-list kernel.  Negative: the status
+ * code the parameters would be rejected with, negated.  Pure host computation.
+ */
+int sea_attention_path(const sea_params* p);
+
 const char* sea_version(void);
 
 #ifdef __cplusplus

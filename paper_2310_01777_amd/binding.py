@@ -65,6 +65,7 @@ def _load() -> ctypes.CDLL:
     lib.sea_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.sea_strerror.restype, lib.sea_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
     lib.sea_last_hip_error.restype, lib.sea_last_hip_error.argtypes = ctypes.c_int, []
+    lib.sea_attention_path.restype, lib.sea_attention_path.argtypes = ctypes.c_int, [P]
     lib.sea_version.restype, lib.sea_version.argtypes = ctypes.c_char_p, []
     return lib
 
@@ -212,7 +213,7 @@ def sea_dense_workspace_bytes(p: SeaParams) -> int:
     return int(_lib.sea_dense_workspace_bytes(ctypes.byref(cp)))
 
 
-def sea_dense_attn(p: SeaParams, Q, K, V, O, workspace, stream=None):
+def sea_dense_attn(p: SeaParams, Q, K, V, O, workspace=None, stream=None):
     n = p.B * p.H * p.T
     cp = p.c()
     _check(_lib.sea_dense_attn(ctypes.byref(cp), _ptr(Q, p.torch_dtype, n * p.d, "Q"),
@@ -220,7 +221,8 @@ def sea_dense_attn(p: SeaParams, Q, K, V, O, workspace, stream=None):
                                _ptr(V, p.torch_dtype, n * p.d, "V"),
                                _ptr(O, p.torch_dtype, n * p.d, "O"),
                                _ptr(workspace, None, None, "workspace"),
-                               workspace.numel() * workspace.element_size(), _stream(stream)),
+                               0 if workspace is None else workspace.numel() * workspace.element_size(),
+                               _stream(stream)),
            "sea_dense_attn")
 
 
@@ -260,6 +262,12 @@ def sea_profile_collect():
     cnt = (ctypes.c_int64 * len(STAGES))()
     _check(_lib.sea_profile_collect(ms, cnt), "sea_profile_collect")
     return {name: (ms[i], cnt[i]) for i, name in enumerate(STAGES)}
+
+
+def sea_attention_path(p: "SeaParams") -> int:
+    """1 = tiled matrix-core attention, 0 = per-row index lists, negative = rejected parameters."""
+    cp = p.c()
+    return int(_lib.sea_attention_path(ctypes.byref(cp)))
 
 
 def sea_version() -> str:

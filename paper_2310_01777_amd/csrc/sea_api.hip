@@ -156,7 +156,7 @@ size_t sea_workspace_bytes(const sea_params* p) {
   if (check_common(p) != SEA_OK || check_mask_params(p) != SEA_OK ||
       check_estimate_params(p) != SEA_OK || row_stride_of(p) < 0)
     return 0;
-  // estimator scratch and A_hat, then either the tiled path's mask bits + compact K / V^T or
+  // estimator scratch and A_hat, then either the tiled path's mask bits or
   // the row-list path's idx + cnt (for when the caller keeps none of them)
   const size_t rows = static_cast<size_t>(p->B) * p->H * p->T;
   const Shape s = make_shape(p, true);
@@ -292,8 +292,8 @@ int sea_dense_attn(const sea_params* p, const void* Q, const void* K, const void
   if (!Q || !K || !V || !O) return SEA_EINVAL;
   if (p->dtype != SEA_BF16) return SEA_ENOTSUP;
   const Shape s = make_shape(p, false);
-  if (!workspace || workspace_bytes < dense_attn_workspace(s) ||
-      reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+  const size_t need = dense_attn_workspace(s);  // currently none: K and V are read in place
+  if (need > 0 && (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 256 != 0))
     return SEA_EWORKSPACE;
   const hipError_t e =
       launch_dense_attn(s, p->dtype, Q, K, V, O, workspace, static_cast<hipStream_t>(hip_stream));
@@ -360,6 +360,13 @@ const char* sea_strerror(int status) {
 }
 
 int sea_last_hip_error(void) { return g_last_hip_error; }
+
+int sea_attention_path(const sea_params* p) {
+  int rc = check_common(p);
+  if (rc == SEA_OK) rc = check_mask_params(p);
+  if (rc != SEA_OK) return -rc;
+  return tile_attn_supported(make_shape(p, true), p->dtype, nullptr) ? 1 : 0;
+}
 
 const char* sea_version(void) { return "sea-hip 0.1 (gfx950)"; }
 

@@ -17,7 +17,9 @@
 // B lane l = col l%32, same elems; C reg i = row 8(i/4) + 4(l/32) + i%4, col l%32.
 // P leaves the first product in C layout (lane = query, regs = keys) and is fed back as the B
 // operand of the second product; its register order fixes which key each contraction slot
-// means, and the V^T fragments are fetched in that same order from a transposed copy of V.
+// means, and the V^T fragments are fetched in that same order from LDS, where the value rows of a
+// step are parked transposed (one 16-bit store per element; the key and value rows themselves
+// are gathered from K and V by position, so no compact or transposed copy exists in HBM).
 #include "sea_internal.h"
 
 namespace sea {
@@ -31,13 +33,13 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 struct TileArgs {
   const uint16_t* Q;    // [N][T][64]
-  const uint16_t* Kc;   // [N][U][64] compact keys (== K when whole columns are emitted)
-  const uint16_t* Vct;  // [N][Upad / 64][64][64] transposed compact values in 64-key tiles, zero padded
+  const uint16_t* K;    // [N][T][64]
+  const uint16_t* V;    // [N][T][64]
   const uint32_t* mbits;  // [N][T][KW] selected-column bits, nullptr for dense
   uint16_t* O;          // [N][T][64]
   const int32_t* seq_len;
   int32_t N, H, T;
-  int32_t U, Upad;      // compact keys per head, padded to a multiple of 32
+  int32_t U;            // compact keys per head: K r (all T keys when whole columns are emitted)
   int32_t KW;           // mask words per row
   int32_t rlog;         // log2(keys per column r)
   int32_t w;            // column width in keys
@@ -76,9 +78,9 @@ constexpr int kKRow = 72;    // halfwords per staged K row: 128 B + 16 B pad, co
 constexpr int kVRow = 68;    // halfwords per staged V^T row: 128 B + 8 B pad, conflict-free b64 reads
 
 // Block = 4 waves = 128 consecutive query rows of one head (32 per wave).  The block walks the
-// compact key list in steps of 64 keys; each step's K rows and V^T tile are fetched once with
-// full-line 128-bit loads, parked in LDS (double buffered, one barrier per step) and read by
-// all four waves as MFMA fragments.
+// compact key list in steps of 64 keys; each step's K and V rows are fetched once with full-line
+// 128-bit loads, parked in LDS (K as rows, V transposed; double buffered, one barrier per step)
+// and read by all four waves as MFMA fragments.
 // RLOG = log2(keys per column) for 1..16 keys per column, 5 for 32 or more (then a 32-key
 // sub-chunk lies inside one column and the actual shift is a.rlog).
 template <int RLOG, bool DENSE>
@@ -116,8 +118,8 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
 #pragma unroll
   for (int kc = 0; kc < 4; ++kc) asm volatile("" : "+v"(bq[kc]));
 
-  const uint16_t* Kh = a.Kc + head * static_cast<int64_t>(a.U) * kHeadDim;
-  const uint16_t* Vh = a.Vct + head * static_cast<int64_t>(kHeadDim) * a.Upad;
+  const uint16_t* Kh = a.K + head * static_cast<int64_t>(a.T) * kHeadDim;
+  const uint16_t* Vh = a.V + head * static_cast<int64_t>(a.T) * kHeadDim;
   // mask words of the block's rows -> LDS (row stride KW + 1 words: conflict-free per-row reads)
   const int mstride = a.KW + 1;
   if (!DENSE) {
@@ -141,29 +143,47 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   const int32_t my_jmax = a.causal ? min(t, len - 1) : len - 1;
   const int32_t nsteps = (u_end_wg + kChunk - 1) / kChunk;
 
-  // staging roles: K rows (tid >> 3) and (tid >> 3) + 32, 16-byte part tid & 7; V^T rows alike
+  // staging roles: 16-byte part tid & 7 of K rows (tid >> 3) and (tid >> 3) + 32 of the step, and
+  // of the V rows of the key pair 2 (tid >> 3), 2 (tid >> 3) + 1: a pair packs into one 32-bit
+  // word per dimension of the transposed tile.  Slots past the list re-read its last key; their
+  // scores are masked.
   const int srow = tid >> 3, spart = tid & 7;
   uint4 kreg0, kreg1, vreg0, vreg1;
+  // With at most 64 keys per column a step of 64 compact keys advances every slot's position by
+  // the same amount, so positions are a base plus step x stride (clamped to the last row: slots
+  // past the list only need an address that is in bounds).
+  const bool linear = a.rlog <= 6;
+  const int32_t pstride = linear ? (kChunk >> a.rlog) * a.w : 0;
+  const int32_t pa0 = pos_of(srow, a.rlog, a.w), pb0 = pos_of(srow + 32, a.rlog, a.w);
+  const int32_t pc0 = pos_of(2 * srow, a.rlog, a.w), pd0 = pos_of(2 * srow + 1, a.rlog, a.w);
+#define SEA_POS(base_, slot_, step_)                                                                 \
+  (linear ? min((base_) + (step_) * pstride, a.T - 1)                                                \
+          : pos_of(min((step_) * kChunk + (slot_), a.U - 1), a.rlog, a.w))
 #define SEA_FETCH(step_)                                                                             \
   do {                                                                                               \
-    const int32_t ua_ = min((step_) * kChunk + srow, a.U - 1);                                        \
-    const int32_t ub_ = min((step_) * kChunk + srow + 32, a.U - 1);                                   \
-    kreg0 = *reinterpret_cast<const uint4*>(Kh + static_cast<int64_t>(ua_) * kHeadDim + spart * 8);   \
-    kreg1 = *reinterpret_cast<const uint4*>(Kh + static_cast<int64_t>(ub_) * kHeadDim + spart * 8);   \
-    const uint16_t* vt_ = Vh + static_cast<int64_t>(step_) * (kHeadDim * kChunk) + srow * kChunk + spart * 8; \
-    vreg0 = *reinterpret_cast<const uint4*>(vt_);                                                    \
-    vreg1 = *reinterpret_cast<const uint4*>(vt_ + 32 * kChunk);                                      \
+    const uint32_t oa_ = static_cast<uint32_t>(SEA_POS(pa0, srow, step_)) * kHeadDim + spart * 8;     \
+    const uint32_t ob_ = static_cast<uint32_t>(SEA_POS(pb0, srow + 32, step_)) * kHeadDim + spart * 8; \
+    const uint32_t oc_ = static_cast<uint32_t>(SEA_POS(pc0, 2 * srow, step_)) * kHeadDim + spart * 8; \
+    const uint32_t od_ = static_cast<uint32_t>(SEA_POS(pd0, 2 * srow + 1, step_)) * kHeadDim + spart * 8; \
+    kreg0 = *reinterpret_cast<const uint4*>(Kh + oa_);                                               \
+    kreg1 = *reinterpret_cast<const uint4*>(Kh + ob_);                                               \
+    vreg0 = *reinterpret_cast<const uint4*>(Vh + oc_);                                               \
+    vreg1 = *reinterpret_cast<const uint4*>(Vh + od_);                                               \
   } while (0)
+  // dimensions 8 spart + e, e + 1 of the key pair: low halves of both keys, then high halves
+#define SEA_PARK_V1(stage_, e_, w0_, w1_)                                                            \
+  *reinterpret_cast<uint32_t*>(&Vs[stage_][(spart * 8 + (e_)) * kVRow + 2 * srow]) =                  \
+      __builtin_amdgcn_perm(w1_, w0_, 0x05040100u);                                                  \
+  *reinterpret_cast<uint32_t*>(&Vs[stage_][(spart * 8 + (e_) + 1) * kVRow + 2 * srow]) =              \
+      __builtin_amdgcn_perm(w1_, w0_, 0x07060302u);
 #define SEA_PARK(stage_)                                                                             \
   do {                                                                                               \
     *reinterpret_cast<uint4*>(&Ks[stage_][srow * kKRow + spart * 8]) = kreg0;                         \
     *reinterpret_cast<uint4*>(&Ks[stage_][(srow + 32) * kKRow + spart * 8]) = kreg1;                  \
-    uint2* va_ = reinterpret_cast<uint2*>(&Vs[stage_][srow * kVRow + spart * 8]);                     \
-    uint2* vb_ = reinterpret_cast<uint2*>(&Vs[stage_][(srow + 32) * kVRow + spart * 8]);              \
-    va_[0] = make_uint2(vreg0.x, vreg0.y);                                                           \
-    va_[1] = make_uint2(vreg0.z, vreg0.w);                                                           \
-    vb_[0] = make_uint2(vreg1.x, vreg1.y);                                                           \
-    vb_[1] = make_uint2(vreg1.z, vreg1.w);                                                           \
+    SEA_PARK_V1(stage_, 0, vreg0.x, vreg1.x)                                                         \
+    SEA_PARK_V1(stage_, 2, vreg0.y, vreg1.y)                                                         \
+    SEA_PARK_V1(stage_, 4, vreg0.z, vreg1.z)                                                         \
+    SEA_PARK_V1(stage_, 6, vreg0.w, vreg1.w)                                                         \
   } while (0)
 
   floatx16 oacc[2];
@@ -276,7 +296,9 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
     __syncthreads();
   }
 #undef SEA_FETCH
+#undef SEA_POS
 #undef SEA_PARK
+#undef SEA_PARK_V1
   l_run = half_sum(l_run);
   if (t < a.T) {
     const float inv = (row_active && l_run > 0.f) ? 1.f / l_run : 0.f;
@@ -294,59 +316,12 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   }
 }
 
-// Gathers the compact key list and writes V transposed in 64-key tiles: Kc[u][:] = K[pos(u)][:]
-// (only when the list is a strict subset of the keys), Vct[u / 64][d][u % 64] = V[pos(u)][d],
-// zero for u >= U.  Block = 256 threads = 64 compact keys x 64 dims, transposed through LDS.
-__global__ __launch_bounds__(256) void compact_kv_kernel(const uint16_t* __restrict__ K,
-                                                         const uint16_t* __restrict__ V,
-                                                         uint16_t* __restrict__ Kc,
-                                                         uint16_t* __restrict__ Vct, int32_t T, int32_t U,
-                                                         int32_t Upad, int32_t rlog, int32_t w) {
-  __shared__ uint16_t tile[64][64 + 2];
-  const int64_t head = blockIdx.y;
-  const int32_t u0 = blockIdx.x * 64;
-  // phase 1: each thread moves 16 B (8 dims) of 4 keys
-  const int c8 = threadIdx.x & 7, kq = threadIdx.x >> 3;  // kq in 0..31
-#pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    const int32_t ul = kq + 32 * half, u = u0 + ul;
-    uint4 kv = {0u, 0u, 0u, 0u}, vv = {0u, 0u, 0u, 0u};
-    if (u < U) {
-      const int64_t src = (head * T + pos_of(u, rlog, w)) * kHeadDim + c8 * 8;
-      vv = *reinterpret_cast<const uint4*>(V + src);
-      if (Kc) {
-        kv = *reinterpret_cast<const uint4*>(K + src);
-        *reinterpret_cast<uint4*>(Kc + (head * U + u) * kHeadDim + c8 * 8) = kv;
-      }
-    }
-    const uint32_t wds[4] = {vv.x, vv.y, vv.z, vv.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      tile[ul][c8 * 8 + 2 * i] = static_cast<uint16_t>(wds[i] & 0xffffu);
-      tile[ul][c8 * 8 + 2 * i + 1] = static_cast<uint16_t>(wds[i] >> 16);
-    }
-  }
-  __syncthreads();
-  // phase 2: thread writes 16 consecutive keys of one dim
-  const int d = threadIdx.x >> 2, part = threadIdx.x & 3;
-  uint16_t* dst = Vct + head * static_cast<int64_t>(kHeadDim) * Upad +
-                  static_cast<int64_t>(blockIdx.x) * (kHeadDim * 64) + d * 64 + part * 16;
-#pragma unroll
-  for (int i = 0; i < 16; i += 2) {
-    if (u0 + part * 16 + i < Upad) {
-      const uint32_t pk = static_cast<uint32_t>(tile[part * 16 + i][d]) |
-                          (static_cast<uint32_t>(tile[part * 16 + i + 1][d]) << 16);
-      *reinterpret_cast<uint32_t*>(dst + i) = pk;
-    }
-  }
-}
-
 }  // namespace
 
-// Heads per scheduling group: the keys and values (2 x Upad x 128 B per head) of the heads an
+// Heads per scheduling group: the keys and values (2 x U x 128 B per head) of the heads an
 // XCD works on at one time should fit its 4 MB L2 with room to spare.
-int32_t group_heads_for(int32_t N, int64_t Upad) {
-  const int64_t per_head = 2 * Upad * kHeadDim * 2;
+int32_t group_heads_for(int32_t N, int64_t U) {
+  const int64_t per_head = 2 * U * kHeadDim * 2;
   int64_t per_xcd = (3 << 20) / (per_head > 0 ? per_head : 1);
   if (per_xcd < 1) per_xcd = 1;
   const int64_t g = 8 * per_xcd;
@@ -361,46 +336,26 @@ bool tile_attn_supported(const Shape& s, sea_dtype dt, int32_t* rlog_out) {
   int32_t rlog = 0;
   while ((1 << rlog) < r) ++rlog;
   if (static_cast<int64_t>(w) * r > (int64_t(1) << 30)) return false;
+  if (s.T > (1 << 25)) return false;  // row offsets inside a head are 32-bit halfword counts
   if (rlog_out) *rlog_out = rlog;
   return true;
 }
 
-// bytes of scratch for the compact K (if needed) and transposed V
-size_t tile_attn_workspace(const Shape& s) {
-  int32_t rlog = 0;
-  if (!tile_attn_supported(s, SEA_BF16, &rlog)) return 0;
-  const int32_t w = s.T / s.K, r = 1 << rlog;
-  const int64_t U = static_cast<int64_t>(s.K) * r, Upad = (U + 63) / 64 * 64;
-  size_t bytes = static_cast<size_t>(s.N) * kHeadDim * Upad * 2;
-  bytes = (bytes + 255) & ~size_t(255);
-  if (r < w) bytes += (static_cast<size_t>(s.N) * U * kHeadDim * 2 + 255) & ~size_t(255);
-  return bytes;
-}
+// the tiled path reads K and V in place
+size_t tile_attn_workspace(const Shape&) { return 0; }
 
 hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
-                            const uint32_t* mbits, uint16_t* O, void* ws, hipStream_t st) {
+                            const uint32_t* mbits, uint16_t* O, void* /*ws*/, hipStream_t st) {
   int32_t rlog = 0;
   if (!tile_attn_supported(s, SEA_BF16, &rlog)) return hipErrorNotSupported;
   const int32_t w = s.T / s.K, r = 1 << rlog;
-  const int32_t U = s.K * r, Upad = (U + 63) / 64 * 64;
-  char* base = static_cast<char*>(ws);
-  uint16_t* Vct = reinterpret_cast<uint16_t*>(base);
-  uint16_t* Kc = nullptr;
-  if (r < w) {
-    const size_t vbytes = (static_cast<size_t>(s.N) * kHeadDim * Upad * 2 + 255) & ~size_t(255);
-    Kc = reinterpret_cast<uint16_t*>(base + vbytes);
-  }
-  {
-    StageScope scope(SEA_STAGE_COMPACT, st);
-    hipLaunchKernelGGL(compact_kv_kernel, dim3(Upad / 64, s.N), dim3(256), 0, st, K, V, Kc, Vct, s.T, U, Upad,
-                       rlog, w);
-  }
+  const int32_t U = s.K * r;
   StageScope scope(SEA_STAGE_SPARSE, st);
   TileArgs a{};
-  a.Q = Q; a.Kc = Kc ? Kc : K; a.Vct = Vct; a.mbits = mbits; a.O = O; a.seq_len = s.seq_len;
-  a.N = s.N; a.H = s.H; a.T = s.T; a.U = U; a.Upad = Upad; a.KW = (s.K + 31) / 32;
+  a.Q = Q; a.K = K; a.V = V; a.mbits = mbits; a.O = O; a.seq_len = s.seq_len;
+  a.N = s.N; a.H = s.H; a.T = s.T; a.U = U; a.KW = (s.K + 31) / 32;
   a.rlog = rlog; a.w = w; a.causal = s.causal;
-  a.group_heads = group_heads_for(s.N, Upad);
+  a.group_heads = group_heads_for(s.N, U);
   a.c = s.scale * kLog2e;
   const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 127) / 128)), block(256);
   const size_t shm = static_cast<size_t>(128) * (a.KW + 1) * sizeof(uint32_t);
@@ -415,27 +370,20 @@ hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K
   return hipGetLastError();
 }
 
-size_t dense_attn_workspace(const Shape& s) {
-  const int64_t Upad = (static_cast<int64_t>(s.T) + 63) / 64 * 64;
-  return (static_cast<size_t>(s.N) * kHeadDim * Upad * 2 + 255) & ~size_t(255);
-}
+size_t dense_attn_workspace(const Shape&) { return 0; }
 
 hipError_t launch_dense_attn(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* V,
-                             void* O, void* ws, hipStream_t st) {
+                             void* O, void* /*ws*/, hipStream_t st) {
   if (dt != SEA_BF16) return hipErrorNotSupported;
-  const int32_t U = s.T, Upad = (U + 63) / 64 * 64;
-  uint16_t* Vct = static_cast<uint16_t*>(ws);
   StageScope scope(SEA_STAGE_DENSE, st);
   // dense: one "column" per key (r = 1, w = 1), so pos(u) = u
-  hipLaunchKernelGGL(compact_kv_kernel, dim3(Upad / 64, s.N), dim3(256), 0, st,
-                     static_cast<const uint16_t*>(K), static_cast<const uint16_t*>(V),
-                     static_cast<uint16_t*>(nullptr), Vct, s.T, U, Upad, 0, 1);
   TileArgs a{};
-  a.Q = static_cast<const uint16_t*>(Q); a.Kc = static_cast<const uint16_t*>(K); a.Vct = Vct;
+  a.Q = static_cast<const uint16_t*>(Q); a.K = static_cast<const uint16_t*>(K);
+  a.V = static_cast<const uint16_t*>(V);
   a.mbits = nullptr; a.O = static_cast<uint16_t*>(O); a.seq_len = s.seq_len;
-  a.N = s.N; a.H = s.H; a.T = s.T; a.U = U; a.Upad = Upad; a.KW = 0; a.rlog = 0; a.w = 1;
+  a.N = s.N; a.H = s.H; a.T = s.T; a.U = s.T; a.KW = 0; a.rlog = 0; a.w = 1;
   a.causal = s.causal; a.c = s.scale * kLog2e;
-  a.group_heads = group_heads_for(s.N, Upad);
+  a.group_heads = group_heads_for(s.N, s.T);
   const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 127) / 128)), block(256);
   hipLaunchKernelGGL((tile_attn_kernel<0, true>), grid, block, 0, st, a);
   return hipGetLastError();
