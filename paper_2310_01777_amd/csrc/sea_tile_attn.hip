@@ -150,25 +150,34 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   const int srow = tid >> 3, spart = tid & 7;
   uint4 kreg0, kreg1, vreg0, vreg1;
   // With at most 64 keys per column a step of 64 compact keys advances every slot's position by
-  // the same amount, so positions are a base plus step x stride (clamped to the last row: slots
-  // past the list only need an address that is in bounds).
+  // the same amount, so the four row offsets (bytes inside the head, 32 bits) just step by a
+  // constant; they are clamped to the last row, since slots past the list only need an address
+  // that is in bounds.  Steps are fetched in order, one SEA_FETCH per step.
   const bool linear = a.rlog <= 6;
-  const int32_t pstride = linear ? (kChunk >> a.rlog) * a.w : 0;
-  const int32_t pa0 = pos_of(srow, a.rlog, a.w), pb0 = pos_of(srow + 32, a.rlog, a.w);
-  const int32_t pc0 = pos_of(2 * srow, a.rlog, a.w), pd0 = pos_of(2 * srow + 1, a.rlog, a.w);
-#define SEA_POS(base_, slot_, step_)                                                                 \
-  (linear ? min((base_) + (step_) * pstride, a.T - 1)                                                \
-          : pos_of(min((step_) * kChunk + (slot_), a.U - 1), a.rlog, a.w))
+  const uint32_t row_bytes = kHeadDim * 2, part_bytes = spart * 16;
+  const uint32_t off_max = static_cast<uint32_t>(a.T - 1) * row_bytes + part_bytes;
+  const uint32_t off_step = linear ? static_cast<uint32_t>((kChunk >> a.rlog) * a.w) * row_bytes : 0u;
+  uint32_t offa = static_cast<uint32_t>(pos_of(srow, a.rlog, a.w)) * row_bytes + part_bytes;
+  uint32_t offb = static_cast<uint32_t>(pos_of(srow + 32, a.rlog, a.w)) * row_bytes + part_bytes;
+  uint32_t offc = static_cast<uint32_t>(pos_of(2 * srow, a.rlog, a.w)) * row_bytes + part_bytes;
+  uint32_t offd = static_cast<uint32_t>(pos_of(2 * srow + 1, a.rlog, a.w)) * row_bytes + part_bytes;
+  const char* Kb = reinterpret_cast<const char*>(Kh);
+  const char* Vb = reinterpret_cast<const char*>(Vh);
+#define SEA_SLOT_OFF(slot_, step_)                                                                   \
+  (static_cast<uint32_t>(pos_of(min((step_) * kChunk + (slot_), a.U - 1), a.rlog, a.w)) * row_bytes + part_bytes)
 #define SEA_FETCH(step_)                                                                             \
   do {                                                                                               \
-    const uint32_t oa_ = static_cast<uint32_t>(SEA_POS(pa0, srow, step_)) * kHeadDim + spart * 8;     \
-    const uint32_t ob_ = static_cast<uint32_t>(SEA_POS(pb0, srow + 32, step_)) * kHeadDim + spart * 8; \
-    const uint32_t oc_ = static_cast<uint32_t>(SEA_POS(pc0, 2 * srow, step_)) * kHeadDim + spart * 8; \
-    const uint32_t od_ = static_cast<uint32_t>(SEA_POS(pd0, 2 * srow + 1, step_)) * kHeadDim + spart * 8; \
-    kreg0 = *reinterpret_cast<const uint4*>(Kh + oa_);                                               \
-    kreg1 = *reinterpret_cast<const uint4*>(Kh + ob_);                                               \
-    vreg0 = *reinterpret_cast<const uint4*>(Vh + oc_);                                               \
-    vreg1 = *reinterpret_cast<const uint4*>(Vh + od_);                                               \
+    if (!linear) {                                                                                   \
+      offa = SEA_SLOT_OFF(srow, step_);                                                              \
+      offb = SEA_SLOT_OFF(srow + 32, step_);                                                         \
+      offc = SEA_SLOT_OFF(2 * srow, step_);                                                          \
+      offd = SEA_SLOT_OFF(2 * srow + 1, step_);                                                      \
+    }                                                                                                \
+    kreg0 = *reinterpret_cast<const uint4*>(Kb + min(offa, off_max));                                \
+    kreg1 = *reinterpret_cast<const uint4*>(Kb + min(offb, off_max));                                \
+    vreg0 = *reinterpret_cast<const uint4*>(Vb + min(offc, off_max));                                \
+    vreg1 = *reinterpret_cast<const uint4*>(Vb + min(offd, off_max));                                \
+    offa += off_step; offb += off_step; offc += off_step; offd += off_step;                          \
   } while (0)
   // dimensions 8 spart + e, e + 1 of the key pair: low halves of both keys, then high halves
 #define SEA_PARK_V1(stage_, e_, w0_, w1_)                                                            \
@@ -296,7 +305,7 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
     __syncthreads();
   }
 #undef SEA_FETCH
-#undef SEA_POS
+#undef SEA_SLOT_OFF
 #undef SEA_PARK
 #undef SEA_PARK_V1
   l_run = half_sum(l_run);
@@ -336,7 +345,7 @@ bool tile_attn_supported(const Shape& s, sea_dtype dt, int32_t* rlog_out) {
   int32_t rlog = 0;
   while ((1 << rlog) < r) ++rlog;
   if (static_cast<int64_t>(w) * r > (int64_t(1) << 30)) return false;
-  if (s.T > (1 << 25)) return false;  // row offsets inside a head are 32-bit halfword counts
+  if (s.T > (1 << 24)) return false;  // row offsets inside a head are 32-bit byte counts
   if (rlog_out) *rlog_out = rlog;
   return true;
 }
