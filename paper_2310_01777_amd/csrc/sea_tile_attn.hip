@@ -235,16 +235,37 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
       // diagonal or the end of the sequence also compare key positions.
       const bool boundary =
           (u0 + 32 > u_end) || (pos_of(min(u0 + 31, a.U - 1), a.rlog, a.w) > j_free);
+      // Registers of one lane fall into groups that share a column (and so a mask bit): 4 for 4
+      // or 8 keys per column, 8 for 16, all 16 for 32 or more and for the dense kernel.  Interior
+      // sub-chunks then need one select per group on the group maximum and one on the exponent
+      // offset, instead of one per score.
+      constexpr int kGroup = DENSE ? 16 : (RLOG >= 5 ? 16 : (RLOG == 4 ? 8 : (RLOG >= 2 ? 4 : 1)));
+      constexpr int kGroups = 16 / kGroup;
+      bool gok[kGroups];
       float mx = -INFINITY;
-      if (!boundary) {
+      if (!boundary && kGroup > 1) {
+#pragma unroll
+        for (int gi = 0; gi < kGroups; ++gi) {
+          const int col = DENSE ? 0 : (RLOG >= 5 ? 0 : (RLOG == 2 ? 2 * gi + g : gi));  // column of the group
+          gok[gi] = DENSE ? row_active : (((bits >> col) & 1u) != 0u);
+          float gm = s[kGroup * gi];
+#pragma unroll
+          for (int e = 1; e < kGroup; ++e) gm = fmaxf(gm, s[kGroup * gi + e]);
+          mx = fmaxf(mx, gok[gi] ? gm : -INFINITY);
+        }
+      } else if (!boundary) {
+#pragma unroll
+        for (int gi = 0; gi < kGroups; ++gi) gok[gi] = true;  // masked through the scores below
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int32_t slot = 8 * (i >> 2) + 4 * g + (i & 3);
-          const bool ok = DENSE ? row_active : (((bits >> (RLOG >= 5 ? 0 : (slot >> RLOG))) & 1u) != 0u);
+          const bool ok = ((bits >> (slot >> RLOG)) & 1u) != 0u;
           s[i] = ok ? s[i] : -INFINITY;
           mx = fmaxf(mx, s[i]);
         }
       } else {
+#pragma unroll
+        for (int gi = 0; gi < kGroups; ++gi) gok[gi] = true;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int32_t slot = 8 * (i >> 2) + 4 * g + (i & 3);
@@ -257,10 +278,16 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
         }
       }
       mx = half_max(mx);
-      const float m_new = fmaxf(m_run, mx);
-      if (__ballot(m_new > m_run) != 0ull) {  // rescale only when some row's maximum moved
+      // The reference maximum only has to keep the exponentials in range, so it is refreshed (and
+      // the accumulators rescaled) when some row's maximum has grown by more than 2^8 in the
+      // exponent; until then p may reach 256 instead of 1, which fp32 sums and bf16 P carry as well.
+      const bool refresh = (mx - m_run) * a.c > 8.f;
+      if (__ballot(refresh) != 0ull) {
+        // rows that did not ask keep their reference (factor exactly 1): a row's arithmetic
+        // never depends on the other rows of its wave
+        const float m_new = refresh ? mx : m_run;
         const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float corr = __builtin_amdgcn_exp2f((m_run - m_safe) * a.c);
+        const float corr = refresh ? __builtin_amdgcn_exp2f((m_run - m_safe) * a.c) : 1.f;
         l_run *= corr;
 #pragma unroll
         for (int i = 0; i < 16; ++i) { oacc[0][i] *= corr; oacc[1][i] *= corr; }
@@ -268,14 +295,16 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
       }
       const float mc = ((m_run == -INFINITY) ? 0.f : m_run) * a.c;
       float p[16];
-      float psum = 0.f;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        p[i] = __builtin_amdgcn_exp2f(fmaf(s[i], a.c, -mc));
-        psum += p[i];
+      for (int gi = 0; gi < kGroups; ++gi) {
+        const float off = gok[gi] ? -mc : -INFINITY;  // a masked group's exponentials are exp2(-inf) = 0
+#pragma unroll
+        for (int e = 0; e < kGroup; ++e)
+          p[kGroup * gi + e] = __builtin_amdgcn_exp2f(fmaf(s[kGroup * gi + e], a.c, off));
       }
-      l_run += psum;
+      // P to bf16; the row sum is taken over the rounded values, the ones the product uses
       bf16x8 bp[2];
+      const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
 #pragma unroll
       for (int c2 = 0; c2 < 2; ++c2) {
         bf16x2 h[4];
@@ -283,6 +312,7 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
         for (int e = 0; e < 4; ++e) {
           const floatx2 f2 = {p[8 * c2 + 2 * e], p[8 * c2 + 2 * e + 1]};
           h[e] = __builtin_convertvector(f2, bf16x2);
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(h[e], ones, l_run, false);
         }
         const bf16x4 lo = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3);
         const bf16x4 hi = __builtin_shufflevector(h[2], h[3], 0, 1, 2, 3);
