@@ -541,19 +541,34 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
       selbits[i] = bits;
     }
   }
-  // mask words: word j holds columns 32 j .. 32 j + 31 = tiles 2 j (low half) and 2 j + 1
+  // mask words: word j holds columns 32 j .. 32 j + 31 = tiles 2 j (low half) and 2 j + 1.  Every
+  // lane of a row's group assembles the row's words; its first lane stores them as one vector.
   const int32_t kw = (s.K + 31) >> 5;
+  constexpr int kWords = NCT / 2;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    if (trow[i] >= s.T) continue;
-    uint32_t* mrow = mbits + (head * s.T + trow[i]) * kw;
+    uint32_t words[kWords];
 #pragma unroll
-    for (int j = 0; j < NCT / 2; ++j) {
+    for (int j = 0; j < kWords; ++j) {
       const uint64_t b0 = __ballot((selbits[i] >> (2 * j)) & 1u);
       const uint64_t b1 = __ballot((selbits[i] >> (2 * j + 1)) & 1u);
-      const uint32_t word = (static_cast<uint32_t>(b0 >> (16 * lg)) & 0xffffu) |
-                            ((static_cast<uint32_t>(b1 >> (16 * lg)) & 0xffffu) << 16);
-      if (lr == j && j < kw) mrow[j] = word;
+      words[j] = (static_cast<uint32_t>(b0 >> (16 * lg)) & 0xffffu) |
+                 ((static_cast<uint32_t>(b1 >> (16 * lg)) & 0xffffu) << 16);
+    }
+    if (trow[i] >= s.T || lr != 0) continue;
+    uint32_t* mrow = mbits + (head * s.T + trow[i]) * kw;
+    if (kw == kWords) {
+      if constexpr (kWords == 2) {
+        *reinterpret_cast<uint2*>(mrow) = make_uint2(words[0], words[1]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < kWords; j += 4)
+          *reinterpret_cast<uint4*>(mrow + j) = make_uint4(words[j], words[j + 1], words[j + 2], words[j + 3]);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < kWords; ++j)
+        if (j < kw) mrow[j] = words[j];
     }
   }
 }
