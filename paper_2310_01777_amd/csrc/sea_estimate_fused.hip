@@ -109,83 +109,113 @@ __device__ __forceinline__ void project(const uint16_t* Ws, bf16x8 x0, bf16x8 x1
 
 // ------------------------------------------------------------------------------------------
 // key side: state[c] = bf16( sum over the keys of column c of phi(k_j) ), in fragment order.
-// Block = 4 waves = 64 keys of one head.  WLOG = log2(column width), 0..6.
+// Block = 4 waves = 64 keys of one head (8 waves = 128 keys for 128-key columns, so that a column
+// never spans two blocks).  WLOG = log2(column width), 0..7.
+//
+// Here the projection is taken with the keys as accumulator rows, C[key][feature] = X W^T: a lane
+// then holds, per 16-feature tile, feature 16 ft + lr of the four keys 4 lg + i, so a column sum
+// is three adds in the lane plus at most two cross-lane steps per tile, and no feature array is
+// kept in registers.  Sums meet in LDS (one m-vector per wave and column part) and leave as
+// coalesced bf16 rows.
 // ------------------------------------------------------------------------------------------
+__device__ __forceinline__ float xor32_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
 template <int MC, int WLOG>
 __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
     Shape s, const uint16_t* __restrict__ K, const uint16_t* __restrict__ W, uint16_t* __restrict__ state,
     uint16_t* __restrict__ pref, float c_dot, float c_norm) {
   constexpr int m = 32 * MC;
   constexpr int w = 1 << WLOG;
-  constexpr int kWaves = w > 64 ? w / 16 : 4;  // waves per block: a column never spans two blocks
+  constexpr int kWaves = w > 64 ? w / 16 : 4;  // waves per block
   constexpr int kRows = 16 * kWaves;
+  constexpr int kPartsWave = (w >= 4 && w < 16) ? 16 / w : 1;  // column sums a wave leaves in LDS
+  constexpr int kSlots = kWaves * kPartsWave;
   __shared__ __attribute__((aligned(16))) uint16_t Ws[m * kWRow];
-  __shared__ float part[w > 16 ? kWaves * m : 1];   // per-wave sums when a column spans several waves
-  __shared__ float tpart[w > 16 ? kWaves * m : 1];  // the same sums over the bf16-rounded features
+  __shared__ float part[w >= 4 ? kSlots * m : 1];   // per wave and column part
+  __shared__ float tpart[w > 16 ? kWaves * m : 1];  // per wave, over the bf16-rounded features
   const int tid = threadIdx.x, lane = tid & 63;
   const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 15, lg = lane >> 4;
   const uint32_t tiles = (s.T + kRows - 1) / kRows;
   const int64_t head = blockIdx.x / tiles;
-  const int32_t r0 = static_cast<int32_t>(blockIdx.x % tiles) * kRows + wid * 16;
+  const int32_t blk_r0 = static_cast<int32_t>(blockIdx.x % tiles) * kRows;
+  const int32_t r0 = blk_r0 + wid * 16;
   for (int x = tid; x < m * 8; x += 64 * kWaves) {
     const int r = x >> 3, part8 = x & 7;
     *reinterpret_cast<uint4*>(&Ws[r * kWRow + part8 * 8]) =
         *reinterpret_cast<const uint4*>(W + r * kHeadDim + part8 * 8);
   }
   __syncthreads();
-  const int32_t t = r0 + lr, tc = min(t, s.T - 1);
   const int32_t b = static_cast<int32_t>(head / s.H);
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
-  const bool active = t < len;
-  const uint16_t* X = K + (head * s.T + tc) * kHeadDim;
+  // operand rows: key r0 + lr; accumulator rows: keys r0 + 4 lg + i
+  const uint16_t* X = K + (head * s.T + min(r0 + lr, s.T - 1)) * kHeadDim;
   const bf16x8 x0 = *reinterpret_cast<const bf16x8*>(X + 8 * lg);
   const bf16x8 x1 = *reinterpret_cast<const bf16x8*>(X + 32 + 8 * lg);
   float nx = sumsq8(x0) + sumsq8(x1);
   nx += __shfl_xor(nx, 16, kWave);
-  nx += __shfl_xor(nx, 32, kWave);
-  floatx4 v[2 * MC];
-  project<MC>(Ws, x0, x1, lr, lg, c_dot, c_norm * nx, v);
+  nx += __shfl_xor(nx, 32, kWave);  // |k|^2 of key lr, in every lane group
+  float bias[4];
+  bool act[4];
 #pragma unroll
-  for (int ft = 0; ft < 2 * MC; ++ft)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) v[ft][i] = active ? __builtin_amdgcn_exp2f(v[ft][i]) : 0.f;
-  if (w > 16 && pref) {
-    // tile sums of the rounded per-key features (what a causal row's own-column term is made of)
-#pragma unroll
-    for (int ft = 0; ft < 2 * MC; ++ft)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float r = group_sum<16>(bf16_to_f32(f32_to_bf16(v[ft][i])));
-        if (lr == 0) tpart[wid * m + 32 * (ft >> 1) + 8 * lg + 4 * (ft & 1) + i] = r;
-      }
+  for (int i = 0; i < 4; ++i) {
+    bias[i] = c_norm * __shfl(nx, (lane & 48) | (4 * lg + i), kWave);
+    act[i] = r0 + 4 * lg + i < len;
   }
-#pragma unroll
-  for (int ft = 0; ft < 2 * MC; ++ft)
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      v[ft][i] = group_sum<(w < 16 ? w : 16)>(v[ft][i]);  // sum over the keys of the column inside this wave
   uint16_t* sh = state + head * static_cast<int64_t>(s.K) * m;
-  if (w <= 16) {
-    // lanes at the first key of each column write that column (rows past T belong to no column)
-    if ((lr & (w - 1)) == 0 && t < s.T) {
-      uint16_t* dst = sh + static_cast<int64_t>(t >> WLOG) * m + 8 * lg;
 #pragma unroll
-      for (int kc = 0; kc < MC; ++kc) {
-        const float lo[4] = {v[2 * kc][0], v[2 * kc][1], v[2 * kc][2], v[2 * kc][3]};
-        const float hi[4] = {v[2 * kc + 1][0], v[2 * kc + 1][1], v[2 * kc + 1][2], v[2 * kc + 1][3]};
-        *reinterpret_cast<bf16x8*>(dst + 32 * kc) = pack8(lo, hi);
+  for (int ft = 0; ft < 2 * MC; ++ft) {
+    const uint16_t* wr = &Ws[(ft * 16 + lr) * kWRow + 8 * lg];
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    acc = mfma16(x0, *reinterpret_cast<const bf16x8*>(wr), acc);
+    acc = mfma16(x1, *reinterpret_cast<const bf16x8*>(wr + 32), acc);
+    float v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = act[i] ? __builtin_amdgcn_exp2f(fmaf(c_dot, acc[i], -bias[i])) : 0.f;
+    // where feature 16 ft + lr sits in a fragment-ordered row
+    const int slot = 32 * (ft >> 1) + 8 * (lr >> 2) + 4 * (ft & 1) + (lr & 3);
+    if (w == 1) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if (r0 + 4 * lg + i < s.T) sh[static_cast<int64_t>(r0 + 4 * lg + i) * m + slot] = f32_to_bf16(v[i]);
+    } else if (w == 2) {
+#pragma unroll
+      for (int i = 0; i < 4; i += 2)
+        if (r0 + 4 * lg + i < s.T)
+          sh[static_cast<int64_t>((r0 + 4 * lg + i) >> 1) * m + slot] = f32_to_bf16(v[i] + v[i + 1]);
+    } else {
+      float sum = (v[0] + v[1]) + (v[2] + v[3]);  // the four keys share a column
+      if (w >= 8) sum += __shfl_xor(sum, 16, kWave);
+      if (w >= 16) sum = xor32_sum(sum);
+      const bool writer = w == 4 ? true : (w == 8 ? (lg & 1) == 0 : lg == 0);
+      const int pw = w == 4 ? lg : (w == 8 ? lg >> 1 : 0);
+      if (writer) part[(wid * kPartsWave + pw) * m + slot] = sum;
+      if (w > 16 && pref) {
+        // the same tile sum over the rounded features: what a causal row's own-column term uses
+        float rs = (bf16_to_f32(f32_to_bf16(v[0])) + bf16_to_f32(f32_to_bf16(v[1]))) +
+                   (bf16_to_f32(f32_to_bf16(v[2])) + bf16_to_f32(f32_to_bf16(v[3])));
+        rs += __shfl_xor(rs, 16, kWave);
+        rs = xor32_sum(rs);
+        if (lg == 0) tpart[wid * m + slot] = rs;
       }
+    }
+  }
+  if (w < 4) return;
+  __syncthreads();
+  if (w <= 16) {
+    // each LDS vector is one finished column: columns blk_r0 / w + 0 .. kSlots - 1
+    const int32_t col0 = blk_r0 >> WLOG;
+    for (int x = tid; x < kSlots * m / 2; x += 64 * kWaves) {
+      const int cl = (2 * x) / m, p = 2 * x - cl * m;
+      if (col0 + cl < s.K)
+        *reinterpret_cast<uint32_t*>(&sh[static_cast<int64_t>(col0 + cl) * m + p]) =
+            pack_bf16(part[cl * m + p], part[cl * m + p + 1]);
     }
   } else {
-    // column spans several waves of this block: combine the wave sums through LDS
-    if (lr == 0) {
-#pragma unroll
-      for (int kc = 0; kc < MC; ++kc)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) part[wid * m + 32 * kc + 8 * lg + e] = v[2 * kc + (e >> 2)][e & 3];
-    }
-    __syncthreads();
+    // column spans several waves of this block
     constexpr int wpc = w / 16;            // waves per column
     constexpr int cols = kRows / w;        // columns per block
     const int32_t col0 = static_cast<int32_t>(blockIdx.x % tiles) * cols;
