@@ -46,6 +46,12 @@ struct TileArgs {
   int32_t causal;
   int32_t group_heads;  // heads per scheduling group (a multiple of 8 unless it is N)
   float c;              // scale * log2(e)
+  // bucket mode (one selected column per row): rows grouped by their column
+  const int32_t* perm;      // [N][T] row ids, bucket after bucket
+  const int32_t* bstart;    // [N][K + 1] first perm slot of each column's bucket
+  const int32_t* chunk_col; // [N][max_chunks] column of each 128-row chunk, -1 past the last
+  const int32_t* cstart;    // [N][K + 1] first chunk of each column
+  int32_t max_chunks, Kcols;
 };
 
 // combine a value with the one held by the same lane of the other 32-lane half of the wave
@@ -83,8 +89,15 @@ constexpr int kVRow = 68;    // halfwords per staged V^T row: 128 B + 8 B pad, c
 // and read by all four waves as MFMA fragments.
 // RLOG = log2(keys per column) for 1..16 keys per column, 5 for 32 or more (then a 32-key
 // sub-chunk lies inside one column and the actual shift is a.rlog).
-template <int RLOG, bool DENSE>
+//
+// MODE 0: rows in sequence order, per-(row, column) mask bits.  MODE 1: dense baseline (no mask
+// bits).  MODE 2: "bucket" form for k^ = 1 -- every row selected exactly one column, rows are
+// grouped by that column, and a block takes 128 rows of one bucket against the r keys of its
+// column, so every visited tile is fully used no matter how scattered the choices are.
+template <int RLOG, int MODE>
 __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
+  constexpr bool DENSE = MODE != 0;   // no per-column bits to look up
+  constexpr bool BUCKET = MODE == 2;
   __shared__ __attribute__((aligned(16))) uint16_t Ks[2][kChunk * kKRow];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[2][kHeadDim * kVRow];
   // selected-column bits of the 128 rows, (KW + 1) words per row (K <= 1024: at most 16.5 KB)
@@ -93,21 +106,36 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, keep it scalar
   const int ql = lane & 31, g = lane >> 5;
   const uint32_t wgs = (a.T + 127) / 128;  // blocks per head
-  // Launch order = longest first: heads are taken in groups whose keys and values fit the L2s;
-  // inside a group the row tiles go from the last (most keys, causal) to the first, heads
-  // fastest.  Blocks are dealt round-robin to the 8 XCDs, so with 8 | group size a head stays on
-  // one XCD, and blocks that start late are the short ones that fill the gaps.
-  const uint32_t per_group = static_cast<uint32_t>(a.group_heads) * wgs;
-  const uint32_t grp = blockIdx.x / per_group, rem = blockIdx.x - grp * per_group;
-  const uint32_t nh = min(static_cast<uint32_t>(a.group_heads), static_cast<uint32_t>(a.N) - grp * a.group_heads);
-  const int64_t head = static_cast<int64_t>(grp) * a.group_heads + rem % nh;
-  const int32_t wg_tile = static_cast<int32_t>(wgs - 1 - rem / nh);
-  const int32_t q0 = wg_tile * 128 + 32 * wid;  // first row of this wave
-  const int32_t t = q0 + ql;
+  int64_t head;
+  int32_t wg_tile = 0, q0 = 0, t;
+  int32_t ubase = 0, ulim = a.U;  // compact keys this block may touch: [ubase, ulim)
+  if (BUCKET) {
+    head = blockIdx.x / static_cast<uint32_t>(a.max_chunks);
+    const int32_t chunk = static_cast<int32_t>(blockIdx.x % static_cast<uint32_t>(a.max_chunks));
+    const int32_t col = a.chunk_col[head * a.max_chunks + chunk];
+    if (col < 0) return;  // past the last chunk of this head (block-uniform)
+    const int32_t* bs = a.bstart + head * (a.Kcols + 1);
+    const int32_t slot = bs[col] + (chunk - a.cstart[head * (a.Kcols + 1) + col]) * 128 + 32 * wid + ql;
+    t = slot < bs[col + 1] ? a.perm[head * a.T + slot] : -1;
+    ubase = col << a.rlog;
+    ulim = ubase + (1 << a.rlog);
+  } else {
+    // Launch order = longest first: heads are taken in groups whose keys and values fit the L2s;
+    // inside a group the row tiles go from the last (most keys, causal) to the first, heads
+    // fastest.  Blocks are dealt round-robin to the 8 XCDs, so with 8 | group size a head stays on
+    // one XCD, and blocks that start late are the short ones that fill the gaps.
+    const uint32_t per_group = static_cast<uint32_t>(a.group_heads) * wgs;
+    const uint32_t grp = blockIdx.x / per_group, rem = blockIdx.x - grp * per_group;
+    const uint32_t nh = min(static_cast<uint32_t>(a.group_heads), static_cast<uint32_t>(a.N) - grp * a.group_heads);
+    head = static_cast<int64_t>(grp) * a.group_heads + rem % nh;
+    wg_tile = static_cast<int32_t>(wgs - 1 - rem / nh);
+    q0 = wg_tile * 128 + 32 * wid;  // first row of this wave
+    t = q0 + ql;
+  }
   const int32_t b = static_cast<int32_t>(head / a.H);
   const int32_t len = a.seq_len ? min(max(a.seq_len[b], 0), a.T) : a.T;
-  const bool row_active = t < len;
-  const int32_t tq = min(t, a.T - 1);
+  const bool row_active = t >= 0 && t < len;
+  const int32_t tq = min(max(t, 0), a.T - 1);
 
   const uint16_t* Qr = a.Q + (head * a.T + tq) * kHeadDim + 8 * g;
   bf16x8 bq[4];
@@ -134,14 +162,22 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   const uint32_t* mrow = DENSE ? nullptr : &Ms[(32 * wid + ql) * mstride];
 
   // keys the block / this wave can see: position <= min(last row, len - 1) when causal
-  const int32_t wg_hi = min(wg_tile * 128 + 127, a.T - 1);
-  const int32_t u_end_wg = compact_count(a.causal ? min(wg_hi, len - 1) : len - 1, a.rlog, a.w);
-  const int32_t t_hi = min(q0 + 31, a.T - 1);
-  const int32_t u_end = q0 < a.T ? compact_count(a.causal ? min(t_hi, len - 1) : len - 1, a.rlog, a.w) : 0;
-  // below this position every key is admissible for every active row of the wave
-  const int32_t j_free = a.causal ? min(q0, len - 1) : len - 1;
+  int32_t u_end_wg, u_end, j_free;
+  if (BUCKET) {
+    u_end_wg = u_end = ulim;
+    // rows of a bucket come from anywhere in the sequence: with causal attention or padding every
+    // sub-chunk compares positions
+    j_free = (a.causal || len < a.T) ? -1 : a.T - 1;
+  } else {
+    const int32_t wg_hi = min(wg_tile * 128 + 127, a.T - 1);
+    u_end_wg = compact_count(a.causal ? min(wg_hi, len - 1) : len - 1, a.rlog, a.w);
+    const int32_t t_hi = min(q0 + 31, a.T - 1);
+    u_end = q0 < a.T ? compact_count(a.causal ? min(t_hi, len - 1) : len - 1, a.rlog, a.w) : 0;
+    // below this position every key is admissible for every active row of the wave
+    j_free = a.causal ? min(q0, len - 1) : len - 1;
+  }
   const int32_t my_jmax = a.causal ? min(t, len - 1) : len - 1;
-  const int32_t nsteps = (u_end_wg + kChunk - 1) / kChunk;
+  const int32_t nsteps = (u_end_wg - ubase + kChunk - 1) / kChunk;
 
   // staging roles: 16-byte part tid & 7 of K rows (tid >> 3) and (tid >> 3) + 32 of the step, and
   // of the V rows of the key pair 2 (tid >> 3), 2 (tid >> 3) + 1: a pair packs into one 32-bit
@@ -157,14 +193,14 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   const uint32_t row_bytes = kHeadDim * 2, part_bytes = spart * 16;
   const uint32_t off_max = static_cast<uint32_t>(a.T - 1) * row_bytes + part_bytes;
   const uint32_t off_step = linear ? static_cast<uint32_t>((kChunk >> a.rlog) * a.w) * row_bytes : 0u;
-  uint32_t offa = static_cast<uint32_t>(pos_of(srow, a.rlog, a.w)) * row_bytes + part_bytes;
-  uint32_t offb = static_cast<uint32_t>(pos_of(srow + 32, a.rlog, a.w)) * row_bytes + part_bytes;
-  uint32_t offc = static_cast<uint32_t>(pos_of(2 * srow, a.rlog, a.w)) * row_bytes + part_bytes;
-  uint32_t offd = static_cast<uint32_t>(pos_of(2 * srow + 1, a.rlog, a.w)) * row_bytes + part_bytes;
+  uint32_t offa = static_cast<uint32_t>(pos_of(ubase + srow, a.rlog, a.w)) * row_bytes + part_bytes;
+  uint32_t offb = static_cast<uint32_t>(pos_of(ubase + srow + 32, a.rlog, a.w)) * row_bytes + part_bytes;
+  uint32_t offc = static_cast<uint32_t>(pos_of(ubase + 2 * srow, a.rlog, a.w)) * row_bytes + part_bytes;
+  uint32_t offd = static_cast<uint32_t>(pos_of(ubase + 2 * srow + 1, a.rlog, a.w)) * row_bytes + part_bytes;
   const char* Kb = reinterpret_cast<const char*>(Kh);
   const char* Vb = reinterpret_cast<const char*>(Vh);
 #define SEA_SLOT_OFF(slot_, step_)                                                                   \
-  (static_cast<uint32_t>(pos_of(min((step_) * kChunk + (slot_), a.U - 1), a.rlog, a.w)) * row_bytes + part_bytes)
+  (static_cast<uint32_t>(pos_of(min(ubase + (step_) * kChunk + (slot_), a.U - 1), a.rlog, a.w)) * row_bytes + part_bytes)
 #define SEA_FETCH(step_)                                                                             \
   do {                                                                                               \
     if (!linear) {                                                                                   \
@@ -210,9 +246,10 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
     if (step + 1 < nsteps) SEA_FETCH(step + 1);
 #pragma unroll
     for (int sc = 0; sc < 2; ++sc) {
-      const int32_t u0 = step * kChunk + 32 * sc;
+      const int32_t u0 = ubase + step * kChunk + 32 * sc;
       if (u0 >= u_end) break;  // wave-uniform: beyond what this wave's rows can see
       uint32_t bits = 0xffffffffu;
+      if (BUCKET && __ballot(row_active) == 0ull) break;  // a wave past the end of its bucket
       if (!DENSE) {
         const int32_t col0 = u0 >> (RLOG < 5 ? RLOG : a.rlog);  // first column of the sub-chunk
         const uint32_t word = row_active ? mrow[col0 >> 5] : 0u;
@@ -272,7 +309,7 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
           const int32_t u = u0 + slot;
           const int32_t pu = pos_of(min(u, a.U - 1), a.rlog, a.w);
           const uint32_t okb = (DENSE ? (row_active ? 1u : 0u) : ((bits >> (RLOG >= 5 ? 0 : (slot >> RLOG))) & 1u)) &
-                               (u < a.U ? 1u : 0u) & (pu <= my_jmax ? 1u : 0u);
+                               (u < ulim ? 1u : 0u) & (pu <= my_jmax ? 1u : 0u);
           s[i] = okb ? s[i] : -INFINITY;
           mx = fmaxf(mx, s[i]);
         }
@@ -339,7 +376,7 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
 #undef SEA_PARK
 #undef SEA_PARK_V1
   l_run = half_sum(l_run);
-  if (t < a.T) {
+  if (t >= 0 && t < a.T) {
     const float inv = (row_active && l_run > 0.f) ? 1.f / l_run : 0.f;
     uint16_t* Or = a.O + (head * a.T + t) * kHeadDim;
 #pragma unroll
@@ -352,6 +389,106 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
         const bf16x2 h01 = __builtin_convertvector(f01, bf16x2), h23 = __builtin_convertvector(f23, bf16x2);
         *reinterpret_cast<bf16x4*>(Or + 32 * mt + 8 * q4 + 4 * g) = __builtin_shufflevector(h01, h23, 0, 1, 2, 3);
       }
+  }
+}
+
+// ---- k^ = 1: group the rows of a head by the one column each selected (Sec. 3.1, App. A.5.3:
+// the long-sequence regime where k K < T) ----
+constexpr int kBucketRows = 256;
+
+__global__ __launch_bounds__(256) void zero_i32_kernel(int32_t* __restrict__ p, int64_t n) {
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+// column of every row (first set mask bit, -1 if none) and the bucket sizes
+__global__ __launch_bounds__(kBucketRows) void bucket_count_kernel(const uint32_t* __restrict__ mbits,
+                                                                   int32_t* __restrict__ colid,
+                                                                   int32_t* __restrict__ cnt, int32_t T,
+                                                                   int32_t KW, int32_t Kc) {
+  extern __shared__ int32_t hist[];  // Kc counters
+  const int64_t head = blockIdx.y;
+  const int32_t row = blockIdx.x * kBucketRows + threadIdx.x;
+  for (int c = threadIdx.x; c < Kc; c += kBucketRows) hist[c] = 0;
+  __syncthreads();
+  int32_t col = -1;
+  if (row < T) {
+    const uint32_t* mw = mbits + (head * T + row) * KW;
+    for (int32_t j = KW - 1; j >= 0; --j) {
+      const uint32_t word = mw[j];
+      if (word != 0u) col = 32 * j + (__ffs(static_cast<int>(word)) - 1);
+    }
+    colid[head * T + row] = col;
+    if (col >= 0) atomicAdd(&hist[col], 1);
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < Kc; c += kBucketRows)
+    if (hist[c] != 0) atomicAdd(&cnt[head * Kc + c], hist[c]);
+}
+
+// per head: bucket offsets, the 128-row chunks of each bucket, and which column each chunk is
+__global__ __launch_bounds__(1024) void bucket_scan_kernel(const int32_t* __restrict__ cnt,
+                                                           int32_t* __restrict__ bstart,
+                                                           int32_t* __restrict__ cstart,
+                                                           int32_t* __restrict__ cursor,
+                                                           int32_t* __restrict__ chunk_col, int32_t Kc,
+                                                           int32_t max_chunks) {
+  __shared__ int32_t rows_s[1024], chunks_s[1024];
+  const int64_t head = blockIdx.x;
+  const int c = threadIdx.x;
+  const int32_t n = c < Kc ? cnt[head * Kc + c] : 0;
+  const int32_t nch = (n + 127) >> 7;
+  rows_s[c] = n;
+  chunks_s[c] = nch;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {  // inclusive scans
+    const int32_t ar = c >= off ? rows_s[c - off] : 0, ac = c >= off ? chunks_s[c - off] : 0;
+    __syncthreads();
+    rows_s[c] += ar;
+    chunks_s[c] += ac;
+    __syncthreads();
+  }
+  const int32_t r0 = rows_s[c] - n, c0 = chunks_s[c] - nch;
+  const int32_t total_chunks = chunks_s[1023];
+  if (c < Kc) {
+    bstart[head * (Kc + 1) + c] = r0;
+    cstart[head * (Kc + 1) + c] = c0;
+    cursor[head * Kc + c] = r0;
+    for (int32_t j = 0; j < nch; ++j) chunk_col[head * max_chunks + c0 + j] = c;
+  }
+  if (c == 0) {
+    bstart[head * (Kc + 1) + Kc] = rows_s[1023];
+    cstart[head * (Kc + 1) + Kc] = total_chunks;
+  }
+  for (int32_t x = total_chunks + c; x < max_chunks; x += 1024) chunk_col[head * max_chunks + x] = -1;
+}
+
+// row ids into their buckets (order inside a bucket is whatever the atomics give: no result
+// depends on it); rows that selected nothing (padding, no admissible key) get a zero output
+__global__ __launch_bounds__(kBucketRows) void bucket_scatter_kernel(const int32_t* __restrict__ colid,
+                                                                     int32_t* __restrict__ cursor,
+                                                                     int32_t* __restrict__ perm,
+                                                                     uint16_t* __restrict__ O, int32_t T,
+                                                                     int32_t Kc) {
+  extern __shared__ int32_t hist[];  // Kc counters, then Kc bases
+  int32_t* base = hist + Kc;
+  const int64_t head = blockIdx.y;
+  const int32_t row = blockIdx.x * kBucketRows + threadIdx.x;
+  for (int c = threadIdx.x; c < Kc; c += kBucketRows) hist[c] = 0;
+  __syncthreads();
+  const int32_t col = row < T ? colid[head * T + row] : -1;
+  int32_t rank = 0;
+  if (col >= 0) rank = atomicAdd(&hist[col], 1);
+  __syncthreads();
+  for (int c = threadIdx.x; c < Kc; c += kBucketRows)
+    base[c] = hist[c] != 0 ? atomicAdd(&cursor[head * Kc + c], hist[c]) : 0;
+  __syncthreads();
+  if (col >= 0) {
+    perm[head * T + base[col] + rank] = row;
+  } else if (row < T) {
+    uint4* o = reinterpret_cast<uint4*>(O + (head * T + row) * kHeadDim);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = make_uint4(0u, 0u, 0u, 0u);
   }
 }
 
@@ -380,15 +517,59 @@ bool tile_attn_supported(const Shape& s, sea_dtype dt, int32_t* rlog_out) {
   return true;
 }
 
-// the tiled path reads K and V in place
-size_t tile_attn_workspace(const Shape&) { return 0; }
+namespace {
+// k^ = 1 under per-query grouping: one column per row, rows bucketed by column
+bool bucket_mode(const Shape& s) { return s.k_hat == 1 && s.grouping == 0; }
+int32_t bucket_max_chunks(const Shape& s) { return (s.T + 127) / 128 + s.K; }
+size_t al256(size_t b) { return (b + 255) & ~size_t(255); }
+}  // namespace
+
+// the tiled path reads K and V in place; only the bucket form needs scratch: column per row,
+// permutation, per-column counters / offsets / cursors and the chunk table
+size_t tile_attn_workspace(const Shape& s) {
+  if (!tile_attn_supported(s, SEA_BF16, nullptr) || !bucket_mode(s)) return 0;
+  const size_t N = static_cast<size_t>(s.N);
+  return 2 * al256(N * s.T * 4) + 2 * al256(N * s.K * 4) + 2 * al256(N * (s.K + 1) * 4) +
+         al256(N * bucket_max_chunks(s) * 4);
+}
 
 hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
-                            const uint32_t* mbits, uint16_t* O, void* /*ws*/, hipStream_t st) {
+                            const uint32_t* mbits, uint16_t* O, void* ws, hipStream_t st) {
   int32_t rlog = 0;
   if (!tile_attn_supported(s, SEA_BF16, &rlog)) return hipErrorNotSupported;
   const int32_t w = s.T / s.K, r = 1 << rlog;
   const int32_t U = s.K * r;
+  if (bucket_mode(s)) {
+    StageScope scope(SEA_STAGE_SPARSE, st);
+    const size_t N = static_cast<size_t>(s.N);
+    const int32_t KW = (s.K + 31) / 32, max_chunks = bucket_max_chunks(s);
+    char* base = static_cast<char*>(ws);
+    int32_t* colid = reinterpret_cast<int32_t*>(base); base += al256(N * s.T * 4);
+    int32_t* perm = reinterpret_cast<int32_t*>(base);  base += al256(N * s.T * 4);
+    int32_t* cnt = reinterpret_cast<int32_t*>(base);   base += al256(N * s.K * 4);
+    int32_t* cursor = reinterpret_cast<int32_t*>(base); base += al256(N * s.K * 4);
+    int32_t* bstart = reinterpret_cast<int32_t*>(base); base += al256(N * (s.K + 1) * 4);
+    int32_t* cstart = reinterpret_cast<int32_t*>(base); base += al256(N * (s.K + 1) * 4);
+    int32_t* chunk_col = reinterpret_cast<int32_t*>(base);
+    const int64_t ncnt = static_cast<int64_t>(N) * s.K;
+    hipLaunchKernelGGL(zero_i32_kernel, dim3(static_cast<uint32_t>((ncnt + 255) / 256)), dim3(256), 0, st, cnt, ncnt);
+    const dim3 rgrid((s.T + kBucketRows - 1) / kBucketRows, static_cast<uint32_t>(s.N));
+    hipLaunchKernelGGL(bucket_count_kernel, rgrid, dim3(kBucketRows), s.K * sizeof(int32_t), st, mbits, colid, cnt,
+                       s.T, KW, s.K);
+    hipLaunchKernelGGL(bucket_scan_kernel, dim3(static_cast<uint32_t>(s.N)), dim3(1024), 0, st, cnt, bstart, cstart,
+                       cursor, chunk_col, s.K, max_chunks);
+    hipLaunchKernelGGL(bucket_scatter_kernel, rgrid, dim3(kBucketRows), 2 * s.K * sizeof(int32_t), st, colid, cursor,
+                       perm, O, s.T, s.K);
+    TileArgs a{};
+    a.Q = Q; a.K = K; a.V = V; a.mbits = nullptr; a.O = O; a.seq_len = s.seq_len;
+    a.N = s.N; a.H = s.H; a.T = s.T; a.U = U; a.KW = 0; a.rlog = rlog; a.w = w; a.causal = s.causal;
+    a.group_heads = s.N;
+    a.c = s.scale * kLog2e;
+    a.perm = perm; a.bstart = bstart; a.chunk_col = chunk_col; a.cstart = cstart;
+    a.max_chunks = max_chunks; a.Kcols = s.K;
+    hipLaunchKernelGGL((tile_attn_kernel<0, 2>), dim3(static_cast<uint32_t>(s.N) * max_chunks), dim3(256), 0, st, a);
+    return hipGetLastError();
+  }
   StageScope scope(SEA_STAGE_SPARSE, st);
   TileArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.mbits = mbits; a.O = O; a.seq_len = s.seq_len;
@@ -399,12 +580,12 @@ hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K
   const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 127) / 128)), block(256);
   const size_t shm = static_cast<size_t>(128) * (a.KW + 1) * sizeof(uint32_t);
   switch (rlog) {
-    case 0: hipLaunchKernelGGL((tile_attn_kernel<0, false>), grid, block, shm, st, a); break;
-    case 1: hipLaunchKernelGGL((tile_attn_kernel<1, false>), grid, block, shm, st, a); break;
-    case 2: hipLaunchKernelGGL((tile_attn_kernel<2, false>), grid, block, shm, st, a); break;
-    case 3: hipLaunchKernelGGL((tile_attn_kernel<3, false>), grid, block, shm, st, a); break;
-    case 4: hipLaunchKernelGGL((tile_attn_kernel<4, false>), grid, block, shm, st, a); break;
-    default: hipLaunchKernelGGL((tile_attn_kernel<5, false>), grid, block, shm, st, a); break;
+    case 0: hipLaunchKernelGGL((tile_attn_kernel<0, 0>), grid, block, shm, st, a); break;
+    case 1: hipLaunchKernelGGL((tile_attn_kernel<1, 0>), grid, block, shm, st, a); break;
+    case 2: hipLaunchKernelGGL((tile_attn_kernel<2, 0>), grid, block, shm, st, a); break;
+    case 3: hipLaunchKernelGGL((tile_attn_kernel<3, 0>), grid, block, shm, st, a); break;
+    case 4: hipLaunchKernelGGL((tile_attn_kernel<4, 0>), grid, block, shm, st, a); break;
+    default: hipLaunchKernelGGL((tile_attn_kernel<5, 0>), grid, block, shm, st, a); break;
   }
   return hipGetLastError();
 }
@@ -424,7 +605,7 @@ hipError_t launch_dense_attn(const Shape& s, sea_dtype dt, const void* Q, const 
   a.causal = s.causal; a.c = s.scale * kLog2e;
   a.group_heads = group_heads_for(s.N, s.T);
   const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 127) / 128)), block(256);
-  hipLaunchKernelGGL((tile_attn_kernel<0, true>), grid, block, 0, st, a);
+  hipLaunchKernelGGL((tile_attn_kernel<0, 1>), grid, block, 0, st, a);
   return hipGetLastError();
 }
 

@@ -55,14 +55,30 @@ WORKLOADS = {
     "c5": Workload("c5", 32, 12, 512, 64, 128, 64, 16, 0, False, "bf16", 8, pad_frac=0.25),
 }
 C4_LENGTHS = (4096, 8192, 16384, 32768)
+# BERT-shaped bidirectional layer on long random inputs with the paper's own rule for k^: k = 64
+# fixed, k^ = max(1, round(k K / T)) (1 from T = 8192 on), at most k keys per selected column
+# (Sec. 3.1 "Linear Sparse Attention Mask Generation", App. A.5.3; lengths of the App. A.1 tables)
+C6_K = 64
+C6_LENGTHS = (4096, 8192, 16384, 32768, 65536, 131072)
+
+
+def _c6(T: int, causal: bool) -> Workload:
+    K = 128
+    k_hat = max(1, (2 * C6_K * K + T) // (2 * T))  # round half up
+    return Workload(f"c6{'c' if causal else ''}_T{T}", 1, 12, T, 64, 128, K, k_hat, C6_K, causal, "bf16", 16)
 
 
 def get_workload(name: str) -> Workload:
-    """'c1'..'c5', or 'c4_T8192' style names for the long-context sweep."""
+    """'c1'..'c5', 'c4_T8192' style names for the long-context sweep, 'c6_T65536' / 'c6c_T65536'
+    (bidirectional / causal) for the fixed-k regime."""
     if name in WORKLOADS:
         return WORKLOADS[name]
     if name.startswith("c4_T"):
         return WORKLOADS["c4"].with_T(int(name[4:]))
+    if name.startswith("c6_T"):
+        return _c6(int(name[4:]), False)
+    if name.startswith("c6c_T"):
+        return _c6(int(name[5:]), True)
     raise KeyError(name)
 
 

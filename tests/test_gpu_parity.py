@@ -100,6 +100,11 @@ SMALL_CASES = [
     # causal columns wider than a wave's 16 rows: the own-column term reads earlier key tiles
     _wl("bf16_fused_w128_causal", 1, 2, 1024 + 128, 64, 9, 3, k_budget=48),
     _wl("bf16_fused_w32_causal_pad", 2, 2, 640, 128, 20, 6, k_budget=48, pad_frac=0.3),
+    # one selected column per row (k^ = 1): rows are bucketed by column before the attention
+    _wl("bf16_bucket_causal", 1, 2, 2048, 64, 16, 1, k_budget=32),
+    _wl("bf16_bucket_bidir_pad", 2, 2, 1024, 64, 16, 1, k_budget=64, causal=False, pad_frac=0.3),
+    _wl("bf16_bucket_r8", 1, 2, 512, 64, 32, 1, k_budget=8),
+    _wl("bf16_bucket_whole_columns", 1, 3, 520 - 8, 64, 8, 1, causal=False),
 ]
 
 
