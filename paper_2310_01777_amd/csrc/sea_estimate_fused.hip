@@ -110,7 +110,8 @@ __device__ __forceinline__ void project(const uint16_t* Ws, bf16x8 x0, bf16x8 x1
 // ------------------------------------------------------------------------------------------
 // key side: state[c] = bf16( sum over the keys of column c of phi(k_j) ), in fragment order.
 // Block = 4 waves = 64 keys of one head (8 waves = 128 keys for 128-key columns, so that a column
-// never spans two blocks).  WLOG = log2(column width), 0..7.
+// never spans two blocks; wider columns are finished by wide_columns_kernel).  WLOG = log2(column
+// width), 0..7.
 //
 // Here the projection is taken with the keys as accumulator rows, C[key][feature] = X W^T: a lane
 // then holds, per 16-feature tile, feature 16 ft + lr of the four keys 4 lg + i, so a column sum
@@ -126,7 +127,8 @@ __device__ __forceinline__ float xor32_sum(float x) {
 template <int MC, int WLOG>
 __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
     Shape s, const uint16_t* __restrict__ K, const uint16_t* __restrict__ W, uint16_t* __restrict__ state,
-    uint16_t* __restrict__ pref, float c_dot, float c_norm) {
+    uint16_t* __restrict__ pref, float* __restrict__ bsum_u, float* __restrict__ bsum_r, float c_dot,
+    float c_norm) {
   constexpr int m = 32 * MC;
   constexpr int w = 1 << WLOG;
   constexpr int kWaves = w > 64 ? w / 16 : 4;  // waves per block
@@ -224,7 +226,20 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
       float acc = 0.f;
 #pragma unroll
       for (int q = 0; q < wpc; ++q) acc += part[(cl * wpc + q) * m + p];
-      if (col0 + cl < s.K) sh[static_cast<int64_t>(col0 + cl) * m + p] = f32_to_bf16(acc);
+      if (WLOG == 7 && bsum_u) {
+        // columns wider than this block: leave the block's sums (and, causal, the sums of the
+        // rounded features) for the kernel that walks each column's blocks
+        const int64_t blk = head * tiles + blockIdx.x % tiles;
+        bsum_u[blk * m + p] = acc;
+        if (bsum_r) {
+          float racc = 0.f;
+#pragma unroll
+          for (int q = 0; q < wpc; ++q) racc += tpart[q * m + p];
+          bsum_r[blk * m + p] = racc;
+        }
+      } else if (col0 + cl < s.K) {
+        sh[static_cast<int64_t>(col0 + cl) * m + p] = f32_to_bf16(acc);
+      }
     }
     if (pref) {
       // exclusive prefix over the column's tiles, as bf16 planes hi + lo + lo2 (each difference is
@@ -249,23 +264,55 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
   }
 }
 
+// Columns of 256 keys or more: one block per (head, column) adds up the column's 128-key blocks.
+// Causal: the sum of the rounded features of the column's earlier blocks goes out per block as
+// three bf16 planes, like the tile prefixes inside a block.
+__global__ __launch_bounds__(256) void wide_columns_kernel(Shape s, const float* __restrict__ bsum_u,
+                                                           const float* __restrict__ bsum_r,
+                                                           uint16_t* __restrict__ state,
+                                                           uint16_t* __restrict__ bpref, int32_t nb) {
+  const int32_t m = s.m, p = threadIdx.x;
+  if (p >= m) return;
+  const int64_t head = blockIdx.x / static_cast<uint32_t>(s.K);
+  const int32_t c = static_cast<int32_t>(blockIdx.x % static_cast<uint32_t>(s.K));
+  const int64_t blk0 = head * (s.T >> 7) + static_cast<int64_t>(c) * nb;
+  float acc_u = 0.f, acc_r = 0.f;
+  for (int32_t j = 0; j < nb; ++j) {
+    if (bpref && j > 0) {
+      const uint16_t hi = f32_to_bf16(acc_r);
+      const float r1 = acc_r - bf16_to_f32(hi);
+      const uint16_t lo = f32_to_bf16(r1);
+      const uint16_t lo2 = f32_to_bf16(r1 - bf16_to_f32(lo));
+      uint16_t* dst = bpref + ((blk0 + j) * 3) * m + p;
+      dst[0] = hi;
+      dst[m] = lo;
+      dst[2 * m] = lo2;
+    }
+    acc_u += bsum_u[(blk0 + j) * m + p];
+    if (bsum_r) acc_r += bsum_r[(blk0 + j) * m + p];
+  }
+  state[(head * s.K + c) * m + p] = f32_to_bf16(acc_u);
+}
+
 // ------------------------------------------------------------------------------------------
 // query side.  Block = 4 waves = 64 rows of one head (16 per wave).
 // ------------------------------------------------------------------------------------------
 constexpr int kColStage = 32;   // columns of the state staged in LDS per step
 
-// NCT = 16-column tiles a row can have (4, 8 or 16 for K <= 64, 128, 256)
+// NCT = 16-column tiles a row can have (4, 8 or 16 for K <= 64, 128, 256).  WLOG = log2(column
+// width) for widths up to 16; 5 stands for every wider column (the shift is then read from the shape).
 template <int MC, bool CAUSAL, int WLOG, int NCT>
 __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const uint16_t* __restrict__ Q,
                                                             const uint16_t* __restrict__ K,
                                                             const uint16_t* __restrict__ W,
                                                             const uint16_t* __restrict__ state,
                                                             const uint16_t* __restrict__ pref,
+                                                            const uint16_t* __restrict__ bpref,
                                                             float* __restrict__ A_hat,
                                                             uint32_t* __restrict__ mbits, float c_dot,
                                                             float c_norm, int32_t group_heads) {
   constexpr int m = 32 * MC;
-  constexpr int w = 1 << WLOG;
+  const int wl = WLOG >= 5 ? 31 - __clz(s.T / s.K) : WLOG;  // log2(column width)
   constexpr int kSRow = m + 8;  // halfwords per staged state row (+16 B pad): conflict-free b128 reads
   // W is dead once both projections are done; the state stages then reuse its space
   constexpr int kStageHalfwords = kColStage * kSRow;
@@ -294,7 +341,7 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   constexpr int kVecPerThread = kVecPerStage / 256;    // 1, 2 or 4 (m = 64..256); m = 32 -> 0
   static_assert(MC >= 2, "m >= 64");
   uint4 sreg0 = {0u, 0u, 0u, 0u}, sreg1 = sreg0, sreg2 = sreg0, sreg3 = sreg0;  // named: stay in VGPRs
-  const int32_t ncols_wg = CAUSAL ? min(s.K, (min(wg_r0 + 63, s.T - 1) >> WLOG) + 1) : s.K;
+  const int32_t ncols_wg = CAUSAL ? min(s.K, (min(wg_r0 + 63, s.T - 1) >> wl) + 1) : s.K;
   const int32_t nstages = (ncols_wg + kColStage - 1) / kColStage;
 #define SEA_SFETCH1(reg_, q_, st_)                                                              \
   if (kVecPerThread > (q_)) {                                                                  \
@@ -387,19 +434,33 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int rq = 4 * lg + i;  // query row within the wave; key row within the wave is lr
-      const bool ok = (lr <= rq) && (w >= 16 || (lr >> WLOG) == (rq >> WLOG));
+      const bool ok = (lr <= rq) && (WLOG >= 4 || (lr >> WLOG) == (rq >> WLOG));
       sd[i] = ok ? sd[i] : 0.f;
     }
-    if (w > 16 && r0 < s.T && ((r0 >> 4) & (w / 16 - 1)) != 0) {
-      // earlier tiles of the same column: every key precedes every row of the wave, so only their
-      // sum matters.  Its three planes are operand columns 0..2 (the rest zero); the row sum over
-      // the 16 result columns below then adds the three partial dots to the in-wave ones.
-      const uint16_t* src = pref + ((head * (s.T >> 4) + (r0 >> 4)) * 3 + min(lr, 2)) * m + 8 * lg;
+    // Earlier keys of the same column: every one of them precedes every row of the wave, so only
+    // their sum matters.  It comes as three bf16 planes = operand columns 0..2 (the rest zero);
+    // the row sum over the 16 result columns below then adds the three partial dots to the
+    // in-wave ones.  Two levels: tiles before this one inside its 128-key block (its column, if
+    // narrower), and, for columns wider than that, the column's blocks before this one.
+    if (WLOG >= 5 && r0 < s.T) {
+      const int tl = min(wl, 7) - 4;  // log2(tiles per prefix group)
+      if (((r0 >> 4) & ((1 << tl) - 1)) != 0) {
+        const uint16_t* src = pref + ((head * (s.T >> 4) + (r0 >> 4)) * 3 + min(lr, 2)) * m + 8 * lg;
 #pragma unroll
-      for (int kc = 0; kc < MC; ++kc) {
-        uint4 f = *reinterpret_cast<const uint4*>(src + 32 * kc);
-        if (lr > 2) f = uint4{0u, 0u, 0u, 0u};
-        sd = mfma16(afrag[kc], __builtin_bit_cast(bf16x8, f), sd);
+        for (int kc = 0; kc < MC; ++kc) {
+          uint4 f = *reinterpret_cast<const uint4*>(src + 32 * kc);
+          if (lr > 2) f = uint4{0u, 0u, 0u, 0u};
+          sd = mfma16(afrag[kc], __builtin_bit_cast(bf16x8, f), sd);
+        }
+      }
+      if (wl > 7 && ((r0 >> 7) & ((1 << (wl - 7)) - 1)) != 0) {
+        const uint16_t* src = bpref + ((head * (s.T >> 7) + (r0 >> 7)) * 3 + min(lr, 2)) * m + 8 * lg;
+#pragma unroll
+        for (int kc = 0; kc < MC; ++kc) {
+          uint4 f = *reinterpret_cast<const uint4*>(src + 32 * kc);
+          if (lr > 2) f = uint4{0u, 0u, 0u, 0u};
+          sd = mfma16(afrag[kc], __builtin_bit_cast(bf16x8, f), sd);
+        }
       }
     }
 #pragma unroll
@@ -413,7 +474,7 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   floatx4 acc[NCT];
 #pragma unroll
   for (int ct = 0; ct < NCT; ++ct) acc[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
-  const int32_t ncols_wave = CAUSAL ? min(s.K, (min(r0 + 15, s.T - 1) >> WLOG) + 1) : s.K;
+  const int32_t ncols_wave = CAUSAL ? min(s.K, (min(r0 + 15, s.T - 1) >> wl) + 1) : s.K;
 #pragma unroll
   for (int st = 0; st < NCT * 16 / kColStage; ++st) {
     if (st < nstages) {
@@ -447,7 +508,7 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   for (int i = 0; i < 4; ++i) {
     trow[i] = r0 + 4 * lg + i;
     act[i] = trow[i] < len;
-    ctrow[i] = CAUSAL ? (min(trow[i], s.T - 1) >> WLOG) : s.K;  // first masked column is ctrow + 1
+    ctrow[i] = CAUSAL ? (min(trow[i], s.T - 1) >> wl) : s.K;  // first masked column is ctrow + 1
   }
 #pragma unroll
   for (int ct = 0; ct < NCT; ++ct) {
@@ -488,7 +549,7 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int32_t jmax = CAUSAL ? min(trow[i], len - 1) : len - 1;
-    const int32_t ncand = act[i] ? (jmax >> WLOG) + 1 : 0;
+    const int32_t ncand = act[i] ? (jmax >> wl) + 1 : 0;
     nsel[i] = static_cast<uint32_t>(min(s.k_hat, ncand));
     tau[i] = 0x80000000u;
     cge[i] = static_cast<uint32_t>(ncand);
@@ -616,70 +677,110 @@ int wlog_of(const Shape& s) {
 
 bool estimate_fused_supported(const Shape& s) {
   const int wl = wlog_of(s);
-  if (wl < 0 || wl > 7) return false;  // a column of 256 keys or more would span key-side blocks
+  if (wl < 0 || wl > 20) return false;
   if (s.m != 64 && s.m != 128 && s.m != 256) return false;
   if (s.K > 256) return false;
   return true;
 }
 
-size_t estimate_fused_workspace(const Shape& s) {
-  size_t bytes = (static_cast<size_t>(s.N) * s.K * s.m * 2 + 255) & ~size_t(255);  // state
-  if (s.causal && wlog_of(s) > 4) bytes += static_cast<size_t>(s.N) * (s.T / 16) * 3 * s.m * 2;  // tile prefixes
-  return bytes;
+namespace {
+size_t up256(size_t b) { return (b + 255) & ~size_t(255); }
+struct FusedWs {
+  size_t state, pref, bsum_u, bsum_r, bpref, total;
+};
+// state | tile prefixes (causal, columns > 16) | for columns > 128: block sums, rounded block sums
+// and block prefixes (the last two causal only)
+FusedWs fused_layout(const Shape& s) {
+  const int wl = wlog_of(s);
+  const size_t N = static_cast<size_t>(s.N);
+  FusedWs f{};
+  size_t off = 0;
+  f.state = off; off += up256(N * s.K * s.m * 2);
+  f.pref = off;  if (s.causal && wl > 4) off += up256(N * (s.T / 16) * 3 * s.m * 2);
+  f.bsum_u = off; if (wl > 7) off += up256(N * (s.T / 128) * s.m * 4);
+  f.bsum_r = off; if (wl > 7 && s.causal) off += up256(N * (s.T / 128) * s.m * 4);
+  f.bpref = off;  if (wl > 7 && s.causal) off += up256(N * (s.T / 128) * 3 * s.m * 2);
+  f.total = off;
+  return f;
 }
+}  // namespace
+
+size_t estimate_fused_workspace(const Shape& s) { return fused_layout(s).total; }
 
 namespace {
 
+struct FusedPtrs {
+  uint16_t* state;
+  uint16_t* pref;
+  float* bsum_u;
+  float* bsum_r;
+  uint16_t* bpref;
+};
+
 template <int MC, int WLOG, int NCT>
 void launch_rows(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W, float* A_hat,
-                 uint32_t* mbits, const uint16_t* state, const uint16_t* pref, float c_dot, float c_norm,
-                 int32_t gh, dim3 grid, hipStream_t st) {
+                 uint32_t* mbits, const FusedPtrs& f, float c_dot, float c_norm, int32_t gh, dim3 grid,
+                 hipStream_t st) {
   if (s.causal)
-    hipLaunchKernelGGL((estimate_rows_kernel<MC, true, WLOG, NCT>), grid, dim3(256), 0, st, s, Q, K, W, state,
-                       pref, A_hat, mbits, c_dot, c_norm, gh);
+    hipLaunchKernelGGL((estimate_rows_kernel<MC, true, WLOG, NCT>), grid, dim3(256), 0, st, s, Q, K, W, f.state,
+                       f.pref, f.bpref, A_hat, mbits, c_dot, c_norm, gh);
   else
-    hipLaunchKernelGGL((estimate_rows_kernel<MC, false, WLOG, NCT>), grid, dim3(256), 0, st, s, Q, K, W, state,
-                       pref, A_hat, mbits, c_dot, c_norm, gh);
+    hipLaunchKernelGGL((estimate_rows_kernel<MC, false, WLOG, NCT>), grid, dim3(256), 0, st, s, Q, K, W, f.state,
+                       f.pref, f.bpref, A_hat, mbits, c_dot, c_norm, gh);
 }
 
 template <int MC, int WLOG>
-void launch_both(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W, float* A_hat,
-                 uint32_t* mbits, uint16_t* state, uint16_t* pref, float c_dot, float c_norm, hipStream_t st) {
+void launch_key(const Shape& s, const uint16_t* K, const uint16_t* W, const FusedPtrs& f, float c_dot,
+                float c_norm, hipStream_t st) {
   constexpr int kKeyWaves = (1 << WLOG) > 64 ? (1 << WLOG) / 16 : 4;
-  {
-    StageScope scope(SEA_STAGE_STATE, st);
-    const uint32_t ktiles = (s.T + 16 * kKeyWaves - 1) / (16 * kKeyWaves);
-    hipLaunchKernelGGL((key_state_kernel<MC, WLOG>), dim3(static_cast<uint32_t>(s.N) * ktiles),
-                       dim3(64 * kKeyWaves), 0, st, s, K, W, state, pref, c_dot, c_norm);
-  }
-  {
-    StageScope scope(SEA_STAGE_CONTRACT, st);
-    const uint32_t tiles = (s.T + 63) / 64;
-    const dim3 grid(static_cast<uint32_t>(s.N) * tiles);
-    // heads whose state (K x m bf16 each) shares an XCD's L2 at one time: 2 MB worth
-    const int64_t per_xcd = std::max<int64_t>(1, (int64_t(2) << 20) / (static_cast<int64_t>(s.K) * s.m * 2));
-    const int32_t gh = static_cast<int32_t>(std::min<int64_t>(s.N, 8 * per_xcd));
-    if (s.K <= 64)
-      launch_rows<MC, WLOG, 4>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, gh, grid, st);
-    else if (s.K <= 128)
-      launch_rows<MC, WLOG, 8>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, gh, grid, st);
-    else
-      launch_rows<MC, WLOG, 16>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, gh, grid, st);
-  }
+  const uint32_t ktiles = (s.T + 16 * kKeyWaves - 1) / (16 * kKeyWaves);
+  hipLaunchKernelGGL((key_state_kernel<MC, WLOG>), dim3(static_cast<uint32_t>(s.N) * ktiles),
+                     dim3(64 * kKeyWaves), 0, st, s, K, W, f.state, f.pref, f.bsum_u, f.bsum_r, c_dot, c_norm);
+}
+
+template <int MC, int WLOG>
+void launch_rows_k(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W, float* A_hat,
+                   uint32_t* mbits, const FusedPtrs& f, float c_dot, float c_norm, hipStream_t st) {
+  const uint32_t tiles = (s.T + 63) / 64;
+  const dim3 grid(static_cast<uint32_t>(s.N) * tiles);
+  // heads whose state (K x m bf16 each) shares an XCD's L2 at one time: 2 MB worth
+  const int64_t per_xcd = std::max<int64_t>(1, (int64_t(2) << 20) / (static_cast<int64_t>(s.K) * s.m * 2));
+  const int32_t gh = static_cast<int32_t>(std::min<int64_t>(s.N, 8 * per_xcd));
+  if (s.K <= 64)
+    launch_rows<MC, WLOG, 4>(s, Q, K, W, A_hat, mbits, f, c_dot, c_norm, gh, grid, st);
+  else if (s.K <= 128)
+    launch_rows<MC, WLOG, 8>(s, Q, K, W, A_hat, mbits, f, c_dot, c_norm, gh, grid, st);
+  else
+    launch_rows<MC, WLOG, 16>(s, Q, K, W, A_hat, mbits, f, c_dot, c_norm, gh, grid, st);
 }
 
 template <int MC>
 void launch_w(const Shape& s, int wl, const uint16_t* Q, const uint16_t* K, const uint16_t* W, float* A_hat,
-              uint32_t* mbits, uint16_t* state, uint16_t* pref, float c_dot, float c_norm, hipStream_t st) {
+              uint32_t* mbits, const FusedPtrs& f, float c_dot, float c_norm, hipStream_t st) {
+  {
+    StageScope scope(SEA_STAGE_STATE, st);
+    switch (wl) {
+      case 0: launch_key<MC, 0>(s, K, W, f, c_dot, c_norm, st); break;
+      case 1: launch_key<MC, 1>(s, K, W, f, c_dot, c_norm, st); break;
+      case 2: launch_key<MC, 2>(s, K, W, f, c_dot, c_norm, st); break;
+      case 3: launch_key<MC, 3>(s, K, W, f, c_dot, c_norm, st); break;
+      case 4: launch_key<MC, 4>(s, K, W, f, c_dot, c_norm, st); break;
+      case 5: launch_key<MC, 5>(s, K, W, f, c_dot, c_norm, st); break;
+      case 6: launch_key<MC, 6>(s, K, W, f, c_dot, c_norm, st); break;
+      default: launch_key<MC, 7>(s, K, W, f, c_dot, c_norm, st); break;
+    }
+    if (wl > 7)
+      hipLaunchKernelGGL(wide_columns_kernel, dim3(static_cast<uint32_t>(s.N) * s.K), dim3(256), 0, st, s,
+                         f.bsum_u, f.bsum_r, f.state, f.bpref, 1 << (wl - 7));
+  }
+  StageScope scope(SEA_STAGE_CONTRACT, st);
   switch (wl) {
-    case 0: launch_both<MC, 0>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
-    case 1: launch_both<MC, 1>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
-    case 2: launch_both<MC, 2>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
-    case 3: launch_both<MC, 3>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
-    case 4: launch_both<MC, 4>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
-    case 5: launch_both<MC, 5>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
-    case 6: launch_both<MC, 6>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
-    default: launch_both<MC, 7>(s, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
+    case 0: launch_rows_k<MC, 0>(s, Q, K, W, A_hat, mbits, f, c_dot, c_norm, st); break;
+    case 1: launch_rows_k<MC, 1>(s, Q, K, W, A_hat, mbits, f, c_dot, c_norm, st); break;
+    case 2: launch_rows_k<MC, 2>(s, Q, K, W, A_hat, mbits, f, c_dot, c_norm, st); break;
+    case 3: launch_rows_k<MC, 3>(s, Q, K, W, A_hat, mbits, f, c_dot, c_norm, st); break;
+    case 4: launch_rows_k<MC, 4>(s, Q, K, W, A_hat, mbits, f, c_dot, c_norm, st); break;
+    default: launch_rows_k<MC, 5>(s, Q, K, W, A_hat, mbits, f, c_dot, c_norm, st); break;
   }
 }
 
@@ -688,19 +789,26 @@ void launch_w(const Shape& s, int wl, const uint16_t* Q, const uint16_t* K, cons
 hipError_t launch_estimate_fused(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W,
                                  float* A_hat, uint32_t* mbits, void* ws, hipStream_t st) {
   if (!estimate_fused_supported(s)) return hipErrorNotSupported;
-  uint16_t* state = static_cast<uint16_t*>(ws);
   const int wl = wlog_of(s);
-  uint16_t* pref = nullptr;
-  if (s.causal && wl > 4)
-    pref = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) +
-                                        ((static_cast<size_t>(s.N) * s.K * s.m * 2 + 255) & ~size_t(255)));
+  const FusedWs lay = fused_layout(s);
+  char* base = static_cast<char*>(ws);
+  FusedPtrs f{};
+  f.state = reinterpret_cast<uint16_t*>(base + lay.state);
+  if (s.causal && wl > 4) f.pref = reinterpret_cast<uint16_t*>(base + lay.pref);
+  if (wl > 7) {
+    f.bsum_u = reinterpret_cast<float*>(base + lay.bsum_u);
+    if (s.causal) {
+      f.bsum_r = reinterpret_cast<float*>(base + lay.bsum_r);
+      f.bpref = reinterpret_cast<uint16_t*>(base + lay.bpref);
+    }
+  }
   const double l2e = 1.4426950408889634;
   const float c_dot = static_cast<float>(l2e * sqrt(static_cast<double>(s.scale)));
   const float c_norm = static_cast<float>(l2e * 0.5 * static_cast<double>(s.scale));
   switch (s.m) {
-    case 64: launch_w<2>(s, wl, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
-    case 128: launch_w<4>(s, wl, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
-    default: launch_w<8>(s, wl, Q, K, W, A_hat, mbits, state, pref, c_dot, c_norm, st); break;
+    case 64: launch_w<2>(s, wl, Q, K, W, A_hat, mbits, f, c_dot, c_norm, st); break;
+    case 128: launch_w<4>(s, wl, Q, K, W, A_hat, mbits, f, c_dot, c_norm, st); break;
+    default: launch_w<8>(s, wl, Q, K, W, A_hat, mbits, f, c_dot, c_norm, st); break;
   }
   return hipGetLastError();
 }

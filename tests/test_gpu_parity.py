@@ -105,6 +105,10 @@ SMALL_CASES = [
     _wl("bf16_bucket_bidir_pad", 2, 2, 1024, 64, 16, 1, k_budget=64, causal=False, pad_frac=0.3),
     _wl("bf16_bucket_r8", 1, 2, 512, 64, 32, 1, k_budget=8),
     _wl("bf16_bucket_whole_columns", 1, 3, 520 - 8, 64, 8, 1, causal=False),
+    # columns wider than the key kernel's 128-key blocks: block sums and block prefixes
+    _wl("bf16_fused_w256_causal", 1, 2, 2048, 64, 8, 2, k_budget=32),
+    _wl("bf16_fused_w512_bidir_pad", 2, 1, 2048, 128, 4, 1, k_budget=64, causal=False, pad_frac=0.3),
+    _wl("bf16_fused_w512_causal_bucket", 1, 2, 4096, 64, 8, 1, k_budget=32),
 ]
 
 
