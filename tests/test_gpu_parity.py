@@ -410,7 +410,7 @@ def test_optional_outputs_do_not_change_results(sea):
 
 # ---- full-size configurations, in the launch configuration bench.py times, on sampled rows ----
 
-FULL = ["c1", "c2", "c3", "c5", "c4_T8192", "c4_T32768"]
+FULL = ["c1", "c2", "c3", "c5", "c4_T8192", "c4_T32768", "c6_T131072", "c6c_T65536"]
 
 
 @pytest.mark.parametrize("name", FULL)
@@ -426,7 +426,9 @@ def test_full_size_sampled_rows(sea, name):
                     out["idx"], out["cnt"], ws, mhat=out["mhat"])
     torch.cuda.synchronize()
     rng = np.random.default_rng(0)
-    rows = np.unique(np.concatenate([[0, 1, wl.T // wl.K - 1, wl.T // wl.K, wl.T - 1],
+    w = wl.T // wl.K
+    edges = [0, 1, 15, 16, 127, 128, w - 1, w, 3 * w + 127, 3 * w + 128, wl.T - w, wl.T - 1]  # tile, block, column edges
+    rows = np.unique(np.concatenate([[r for r in edges if 0 <= r < wl.T],
                                      rng.integers(0, wl.T, 40)])).astype(np.int32)
     rows_d = torch.as_tensor(rows.astype(np.int64), device="cuda")
     heads = sorted(set([0, wl.B * wl.H - 1] + rng.integers(0, wl.B * wl.H, 3).tolist()))
