@@ -79,6 +79,11 @@ def issued_tile_flops(wl, seq_len):
     each wave of 32 rows walks the compact key list up to the last key its rows may see."""
     w = wl.T // wl.K
     r = w if wl.k_budget == 0 else min(w, max(1, wl.k_budget // wl.k_hat))
+    if wl.k_hat == 1 and not wl.grouping:
+        # bucket form: every active row against the r keys of its one column (32-key granules;
+        # partly filled 32-row tiles at bucket ends not counted)
+        rows = sum((wl.T if seq_len is None else int(seq_len[b])) for b in range(wl.B)) * wl.H
+        return float(rows) * (-(-r // 32) * 32) * wl.d * 4
     total = 0
     for b in range(wl.B):
         ln = wl.T if seq_len is None else int(seq_len[b])

@@ -75,6 +75,14 @@ __device__ __forceinline__ uint32_t group_sum_u(uint32_t x) {  // integer counts
   return x;
 }
 template <int W>
+__device__ __forceinline__ uint32_t group_max_u(uint32_t x) {
+  if (W >= 2) x = max(x, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), kQuadXor1, 0xf, 0xf, false)));
+  if (W >= 4) x = max(x, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), kQuadXor2, 0xf, 0xf, false)));
+  if (W >= 8) x = max(x, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), kRowHalfMirror, 0xf, 0xf, false)));
+  if (W >= 16) x = max(x, static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), kRowMirror, 0xf, 0xf, false)));
+  return x;
+}
+template <int W>
 __device__ __forceinline__ float group_sum(float x) {
   if (W >= 2) x = dpp_add<kQuadXor1>(x);
   if (W >= 4) x = dpp_add<kQuadXor2>(x);
@@ -580,7 +588,22 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     }                                                                                            \
   }
   const int32_t nct_wave = CAUSAL ? min(NCT, (ncols_wave + 15) >> 4) : NCT;
-  if (NCT >= 16 && nct_wave > 12) {
+  if (s.k_hat == 1) {
+    // one column per row: the threshold is the row maximum itself (several columns holding it
+    // are told apart by the tie rule below)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      uint32_t mx = 0u;
+#pragma unroll
+      for (int ct = 0; ct < NCT; ++ct) mx = max(mx, key[ct][i]);
+      mx = group_max_u<16>(mx);
+      uint32_t cnt = 0;
+#pragma unroll
+      for (int ct = 0; ct < NCT; ++ct) cnt += (key[ct][i] >= mx) ? 1u : 0u;
+      tau[i] = mx;
+      cge[i] = group_sum_u<16>(cnt);
+    }
+  } else if (NCT >= 16 && nct_wave > 12) {
     SEA_SEARCH(NCT >= 16 ? 16 : NCT)
   } else if (NCT >= 16 && nct_wave > 8) {
     SEA_SEARCH(NCT >= 16 ? 12 : NCT)
