@@ -354,6 +354,26 @@ def test_causality_and_determinism_on_gpu(sea):
         assert torch.equal(a[k][:, :, :t0 + 1], b[k][:, :, :t0 + 1]), k
 
 
+def test_bucketed_rows_are_reproducible(sea):
+    """k^ = 1: the order of rows inside a column's bucket comes from atomics, the outputs do not
+    depend on it (two runs bit-identical), and rows <= t0 ignore later positions."""
+    wl = _wl("bucket_repro", 2, 3, 1024, 64, 32, 1, k_budget=16)
+    x = synth.make_inputs(wl)
+    _, _, a = _gpu_forward(sea, wl, x)
+    for _ in range(3):
+        _, _, a2 = _gpu_forward(sea, wl, x)
+        for k in a:
+            assert torch.equal(a[k], a2[k]), k
+    t0 = 700
+    y = {k: (v.clone() if isinstance(v, torch.Tensor) else v) for k, v in x.items()}
+    gen = torch.Generator().manual_seed(5)
+    for k in "QKV":
+        y[k][:, :, t0 + 1:] = (torch.randn(y[k][:, :, t0 + 1:].shape, generator=gen) * 2).to(y[k].dtype)
+    _, _, b = _gpu_forward(sea, wl, y)
+    for k in a:
+        assert torch.equal(a[k][:, :, :t0 + 1], b[k][:, :, :t0 + 1]), k
+
+
 def test_padding_rows_and_zero_length(sea):
     """seq_len = 0 for a batch element: every output of it is inert; other elements unaffected."""
     wl = _wl("pad0", 2, 2, 128, 32, 16, 4, causal=False)
