@@ -68,13 +68,23 @@ def _c6(T: int, causal: bool) -> Workload:
     return Workload(f"c6{'c' if causal else ''}_T{T}", 1, 12, T, 64, 128, K, k_hat, C6_K, causal, "bf16", 16)
 
 
+def _c7(T: int) -> Workload:
+    """c4's layer with the paper's own rule instead of a fixed k^: k = 512 keys per row at every T,
+    k^ = max(1, round(k K / T)) = 32, 16, 8, 4 for T = 4096 .. 32768, whole columns emitted."""
+    K, k = 256, 512
+    k_hat = max(1, (2 * k * K + T) // (2 * T))
+    return replace(WORKLOADS["c4"], name=f"c7_T{T}", T=T, k_hat=k_hat, k_budget=0)
+
+
 def get_workload(name: str) -> Workload:
     """'c1'..'c5', 'c4_T8192' style names for the long-context sweep, 'c6_T65536' / 'c6c_T65536'
-    (bidirectional / causal) for the fixed-k regime."""
+    (bidirectional / causal) for the fixed-k regime, 'c7_T8192' for c4 under the paper's k^ rule."""
     if name in WORKLOADS:
         return WORKLOADS[name]
     if name.startswith("c4_T"):
         return WORKLOADS["c4"].with_T(int(name[4:]))
+    if name.startswith("c7_T"):
+        return _c7(int(name[4:]))
     if name.startswith("c6_T"):
         return _c6(int(name[4:]), False)
     if name.startswith("c6c_T"):

@@ -109,6 +109,9 @@ SMALL_CASES = [
     _wl("bf16_fused_w256_causal", 1, 2, 2048, 64, 8, 2, k_budget=32),
     _wl("bf16_fused_w512_bidir_pad", 2, 1, 2048, 128, 4, 1, k_budget=64, causal=False, pad_frac=0.3),
     _wl("bf16_fused_w512_causal_bucket", 1, 2, 4096, 64, 8, 1, k_budget=32),
+    # whole columns of 256 keys: more keys per column than one staging step holds
+    _wl("bf16_whole_w256_causal", 1, 2, 1024, 64, 4, 2),
+    _wl("bf16_whole_w128_bidir_pad", 2, 1, 1024, 64, 8, 3, causal=False, pad_frac=0.3),
 ]
 
 
@@ -430,7 +433,7 @@ def test_optional_outputs_do_not_change_results(sea):
 
 # ---- full-size configurations, in the launch configuration bench.py times, on sampled rows ----
 
-FULL = ["c1", "c2", "c3", "c5", "c4_T8192", "c4_T32768", "c6_T131072", "c6c_T65536"]
+FULL = ["c1", "c2", "c3", "c5", "c4_T8192", "c4_T32768", "c6_T131072", "c6c_T65536", "c7_T32768"]
 
 
 @pytest.mark.parametrize("name", FULL)
