@@ -47,11 +47,17 @@ struct TileArgs {
   int32_t group_heads;  // heads per scheduling group (a multiple of 8 unless it is N)
   float c;              // scale * log2(e)
   // bucket mode (one selected column per row): rows grouped by their column
-  const int32_t* perm;      // [N][T] row ids, bucket after bucket
+  const int32_t* perm;      // [N][entries] row id | slot << 24, bucket after bucket
   const int32_t* bstart;    // [N][K + 1] first perm slot of each column's bucket
   const int32_t* chunk_col; // [N][max_chunks] column of each 128-row chunk, -1 past the last
   const int32_t* cstart;    // [N][K + 1] first chunk of each column
   int32_t max_chunks, Kcols;
+  int64_t perm_stride;  // entries per head in perm
+  // several columns per row (2 <= k^ <= 8): each (row, selected column) pair is one bucket entry
+  // whose normalised partial output and (reference maximum, sum) go here, merged per row later
+  uint16_t* part_o;   // [N][T][slots][64] bf16, nullptr when k^ = 1
+  float* part_ml;     // [N][T][slots][2]
+  int32_t slots;
 };
 
 // combine a value with the one held by the same lane of the other 32-lane half of the wave
@@ -107,7 +113,7 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   const int ql = lane & 31, g = lane >> 5;
   const uint32_t wgs = (a.T + 127) / 128;  // blocks per head
   int64_t head;
-  int32_t wg_tile = 0, q0 = 0, t;
+  int32_t wg_tile = 0, q0 = 0, t, eslot = 0;
   int32_t ubase = 0, ulim = a.U;  // compact keys this block may touch: [ubase, ulim)
   if (BUCKET) {
     head = blockIdx.x / static_cast<uint32_t>(a.max_chunks);
@@ -116,7 +122,9 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
     if (col < 0) return;  // past the last chunk of this head (block-uniform)
     const int32_t* bs = a.bstart + head * (a.Kcols + 1);
     const int32_t slot = bs[col] + (chunk - a.cstart[head * (a.Kcols + 1) + col]) * 128 + 32 * wid + ql;
-    t = slot < bs[col + 1] ? a.perm[head * a.T + slot] : -1;
+    const int32_t entry = slot < bs[col + 1] ? a.perm[head * a.perm_stride + slot] : -1;
+    t = entry < 0 ? -1 : (entry & 0xffffff);
+    eslot = entry < 0 ? 0 : (entry >> 24);
     ubase = col << a.rlog;
     ulim = ubase + (1 << a.rlog);
   } else {
@@ -379,6 +387,14 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   if (t >= 0 && t < a.T) {
     const float inv = (row_active && l_run > 0.f) ? 1.f / l_run : 0.f;
     uint16_t* Or = a.O + (head * a.T + t) * kHeadDim;
+    if (BUCKET && a.part_o) {
+      const int64_t e = (head * a.T + t) * a.slots + eslot;
+      Or = a.part_o + e * kHeadDim;
+      if (g == 0) {
+        a.part_ml[2 * e] = m_run;
+        a.part_ml[2 * e + 1] = row_active ? l_run : 0.f;
+      }
+    }
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -401,9 +417,8 @@ __global__ __launch_bounds__(256) void zero_i32_kernel(int32_t* __restrict__ p, 
   if (i < n) p[i] = 0;
 }
 
-// column of every row (first set mask bit, -1 if none) and the bucket sizes
+// bucket sizes: every set mask bit of a row is one entry of that column's bucket
 __global__ __launch_bounds__(kBucketRows) void bucket_count_kernel(const uint32_t* __restrict__ mbits,
-                                                                   int32_t* __restrict__ colid,
                                                                    int32_t* __restrict__ cnt, int32_t T,
                                                                    int32_t KW, int32_t Kc) {
   extern __shared__ int32_t hist[];  // Kc counters
@@ -411,15 +426,16 @@ __global__ __launch_bounds__(kBucketRows) void bucket_count_kernel(const uint32_
   const int32_t row = blockIdx.x * kBucketRows + threadIdx.x;
   for (int c = threadIdx.x; c < Kc; c += kBucketRows) hist[c] = 0;
   __syncthreads();
-  int32_t col = -1;
   if (row < T) {
     const uint32_t* mw = mbits + (head * T + row) * KW;
-    for (int32_t j = KW - 1; j >= 0; --j) {
-      const uint32_t word = mw[j];
-      if (word != 0u) col = 32 * j + (__ffs(static_cast<int>(word)) - 1);
+    for (int32_t j = 0; j < KW; ++j) {
+      uint32_t word = mw[j];
+      while (word != 0u) {
+        const int bit = __ffs(static_cast<int>(word)) - 1;
+        word &= word - 1u;
+        atomicAdd(&hist[32 * j + bit], 1);
+      }
     }
-    colid[head * T + row] = col;
-    if (col >= 0) atomicAdd(&hist[col], 1);
   }
   __syncthreads();
   for (int c = threadIdx.x; c < Kc; c += kBucketRows)
@@ -463,33 +479,93 @@ __global__ __launch_bounds__(1024) void bucket_scan_kernel(const int32_t* __rest
   for (int32_t x = total_chunks + c; x < max_chunks; x += 1024) chunk_col[head * max_chunks + x] = -1;
 }
 
-// row ids into their buckets (order inside a bucket is whatever the atomics give: no result
-// depends on it); rows that selected nothing (padding, no admissible key) get a zero output
-__global__ __launch_bounds__(kBucketRows) void bucket_scatter_kernel(const int32_t* __restrict__ colid,
+// entries into their buckets (order inside a bucket is whatever the atomics give: no result
+// depends on it).  An entry is the row id with, above bit 24, its rank among the row's selected
+// columns.  With one column per row, rows that selected nothing (padding, no admissible key) get
+// their zero output here; with several, the merge kernel writes every row.
+constexpr int kMaxSlots = 8;
+__global__ __launch_bounds__(kBucketRows) void bucket_scatter_kernel(const uint32_t* __restrict__ mbits,
                                                                      int32_t* __restrict__ cursor,
                                                                      int32_t* __restrict__ perm,
-                                                                     uint16_t* __restrict__ O, int32_t T,
-                                                                     int32_t Kc) {
+                                                                     uint16_t* __restrict__ O_zero, int32_t T,
+                                                                     int32_t KW, int32_t Kc, int64_t perm_stride) {
   extern __shared__ int32_t hist[];  // Kc counters, then Kc bases
   int32_t* base = hist + Kc;
   const int64_t head = blockIdx.y;
   const int32_t row = blockIdx.x * kBucketRows + threadIdx.x;
   for (int c = threadIdx.x; c < Kc; c += kBucketRows) hist[c] = 0;
   __syncthreads();
-  const int32_t col = row < T ? colid[head * T + row] : -1;
-  int32_t rank = 0;
-  if (col >= 0) rank = atomicAdd(&hist[col], 1);
+  int32_t cols[kMaxSlots], ranks[kMaxSlots];
+  int n = 0;
+  if (row < T) {
+    const uint32_t* mw = mbits + (head * T + row) * KW;
+    for (int32_t j = 0; j < KW; ++j) {
+      uint32_t word = mw[j];
+      while (word != 0u && n < kMaxSlots) {
+        const int bit = __ffs(static_cast<int>(word)) - 1;
+        word &= word - 1u;
+        const int32_t col = 32 * j + bit;
+        const int32_t rank = atomicAdd(&hist[col], 1);
+#pragma unroll
+        for (int q = 0; q < kMaxSlots; ++q)
+          if (q == n) { cols[q] = col; ranks[q] = rank; }
+        ++n;
+      }
+    }
+  }
   __syncthreads();
   for (int c = threadIdx.x; c < Kc; c += kBucketRows)
     base[c] = hist[c] != 0 ? atomicAdd(&cursor[head * Kc + c], hist[c]) : 0;
   __syncthreads();
-  if (col >= 0) {
-    perm[head * T + base[col] + rank] = row;
-  } else if (row < T) {
-    uint4* o = reinterpret_cast<uint4*>(O + (head * T + row) * kHeadDim);
+#pragma unroll
+  for (int q = 0; q < kMaxSlots; ++q)
+    if (q < n) perm[head * perm_stride + base[cols[q]] + ranks[q]] = row | (q << 24);
+  if (O_zero && n == 0 && row < T) {
+    uint4* o = reinterpret_cast<uint4*>(O_zero + (head * T + row) * kHeadDim);
 #pragma unroll
     for (int i = 0; i < 8; ++i) o[i] = make_uint4(0u, 0u, 0u, 0u);
   }
+}
+
+// several columns per row: O[t] = sum_s w_s On_s / sum_s w_s with w_s = l_s 2^((m_s - M) c), over
+// the row's entries (On_s normalised partial outputs, m_s reference maxima, l_s sums)
+__global__ __launch_bounds__(256) void bucket_merge_kernel(const uint32_t* __restrict__ mbits,
+                                                           const uint16_t* __restrict__ part_o,
+                                                           const float* __restrict__ part_ml,
+                                                           uint16_t* __restrict__ O, int64_t rows, int32_t KW,
+                                                           int32_t slots, float c) {
+  const int64_t gid = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  const int64_t row = gid >> 3;
+  const int part = static_cast<int>(gid & 7);
+  if (row >= rows) return;
+  int n = 0;
+  for (int32_t j = 0; j < KW; ++j) n += __popc(mbits[row * KW + j]);
+  n = min(n, slots);
+  float M = -INFINITY;
+  for (int q = 0; q < n; ++q) M = fmaxf(M, part_ml[2 * (row * slots + q)]);
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  float wsum = 0.f;
+  for (int q = 0; q < n; ++q) {
+    const int64_t e = row * slots + q;
+    const float l = part_ml[2 * e + 1];
+    if (!(l > 0.f)) continue;
+    const float wq = l * __builtin_amdgcn_exp2f((part_ml[2 * e] - M) * c);
+    const uint4 v = *reinterpret_cast<const uint4*>(part_o + e * kHeadDim + part * 8);
+    const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      acc[2 * i] = fmaf(wq, bf16lo_to_f32(wds[i]), acc[2 * i]);
+      acc[2 * i + 1] = fmaf(wq, bf16hi_to_f32(wds[i]), acc[2 * i + 1]);
+    }
+    wsum += wq;
+  }
+  const float inv = wsum > 0.f ? 1.f / wsum : 0.f;
+  uint4 o;
+  o.x = pack_bf16(acc[0] * inv, acc[1] * inv);
+  o.y = pack_bf16(acc[2] * inv, acc[3] * inv);
+  o.z = pack_bf16(acc[4] * inv, acc[5] * inv);
+  o.w = pack_bf16(acc[6] * inv, acc[7] * inv);
+  *reinterpret_cast<uint4*>(O + row * kHeadDim + part * 8) = o;
 }
 
 }  // namespace
@@ -518,19 +594,42 @@ bool tile_attn_supported(const Shape& s, sea_dtype dt, int32_t* rlog_out) {
 }
 
 namespace {
-// k^ = 1 under per-query grouping: one column per row, rows bucketed by column
-bool bucket_mode(const Shape& s) { return s.k_hat == 1 && s.grouping == 0; }
-int32_t bucket_max_chunks(const Shape& s) { return (s.T + 127) / 128 + s.K; }
+// Few columns per row under per-query grouping: rows (k^ = 1) or (row, column) entries (k^ <= 8,
+// and no more than an eighth of the columns) are bucketed by column
+bool bucket_mode(const Shape& s) {
+  return s.grouping == 0 && (s.k_hat == 1 || (s.k_hat <= kMaxSlots && 8 * s.k_hat <= s.K));
+}
 size_t al256(size_t b) { return (b + 255) & ~size_t(255); }
+struct BucketWs {
+  size_t perm, cnt, cursor, bstart, cstart, chunk_col, part_o, part_ml, total;
+  int64_t entries;      // perm slots per head
+  int32_t max_chunks;
+};
+BucketWs bucket_layout(const Shape& s) {
+  BucketWs b{};
+  const size_t N = static_cast<size_t>(s.N);
+  b.entries = static_cast<int64_t>(s.T) * s.k_hat;
+  b.max_chunks = static_cast<int32_t>((b.entries + 127) / 128) + s.K;
+  size_t off = 0;
+  b.perm = off; off += al256(N * b.entries * 4);
+  b.cnt = off; off += al256(N * s.K * 4);
+  b.cursor = off; off += al256(N * s.K * 4);
+  b.bstart = off; off += al256(N * (s.K + 1) * 4);
+  b.cstart = off; off += al256(N * (s.K + 1) * 4);
+  b.chunk_col = off; off += al256(N * b.max_chunks * 4);
+  b.part_o = off; if (s.k_hat > 1) off += al256(N * b.entries * kHeadDim * 2);
+  b.part_ml = off; if (s.k_hat > 1) off += al256(N * b.entries * 2 * 4);
+  b.total = off;
+  return b;
+}
 }  // namespace
 
-// the tiled path reads K and V in place; only the bucket form needs scratch: column per row,
-// permutation, per-column counters / offsets / cursors and the chunk table
+// the tiled path reads K and V in place; only the bucket form needs scratch: the permutation,
+// per-column counters / offsets / cursors, the chunk table and (several columns per row) the
+// partial results
 size_t tile_attn_workspace(const Shape& s) {
   if (!tile_attn_supported(s, SEA_BF16, nullptr) || !bucket_mode(s)) return 0;
-  const size_t N = static_cast<size_t>(s.N);
-  return 2 * al256(N * s.T * 4) + 2 * al256(N * s.K * 4) + 2 * al256(N * (s.K + 1) * 4) +
-         al256(N * bucket_max_chunks(s) * 4);
+  return bucket_layout(s).total;
 }
 
 hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
@@ -541,33 +640,44 @@ hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K
   const int32_t U = s.K * r;
   if (bucket_mode(s)) {
     StageScope scope(SEA_STAGE_SPARSE, st);
-    const size_t N = static_cast<size_t>(s.N);
-    const int32_t KW = (s.K + 31) / 32, max_chunks = bucket_max_chunks(s);
+    const BucketWs lay = bucket_layout(s);
+    const int32_t KW = (s.K + 31) / 32;
     char* base = static_cast<char*>(ws);
-    int32_t* colid = reinterpret_cast<int32_t*>(base); base += al256(N * s.T * 4);
-    int32_t* perm = reinterpret_cast<int32_t*>(base);  base += al256(N * s.T * 4);
-    int32_t* cnt = reinterpret_cast<int32_t*>(base);   base += al256(N * s.K * 4);
-    int32_t* cursor = reinterpret_cast<int32_t*>(base); base += al256(N * s.K * 4);
-    int32_t* bstart = reinterpret_cast<int32_t*>(base); base += al256(N * (s.K + 1) * 4);
-    int32_t* cstart = reinterpret_cast<int32_t*>(base); base += al256(N * (s.K + 1) * 4);
-    int32_t* chunk_col = reinterpret_cast<int32_t*>(base);
-    const int64_t ncnt = static_cast<int64_t>(N) * s.K;
+    int32_t* perm = reinterpret_cast<int32_t*>(base + lay.perm);
+    int32_t* cnt = reinterpret_cast<int32_t*>(base + lay.cnt);
+    int32_t* cursor = reinterpret_cast<int32_t*>(base + lay.cursor);
+    int32_t* bstart = reinterpret_cast<int32_t*>(base + lay.bstart);
+    int32_t* cstart = reinterpret_cast<int32_t*>(base + lay.cstart);
+    int32_t* chunk_col = reinterpret_cast<int32_t*>(base + lay.chunk_col);
+    const bool multi = s.k_hat > 1;
+    const int64_t ncnt = static_cast<int64_t>(s.N) * s.K;
     hipLaunchKernelGGL(zero_i32_kernel, dim3(static_cast<uint32_t>((ncnt + 255) / 256)), dim3(256), 0, st, cnt, ncnt);
     const dim3 rgrid((s.T + kBucketRows - 1) / kBucketRows, static_cast<uint32_t>(s.N));
-    hipLaunchKernelGGL(bucket_count_kernel, rgrid, dim3(kBucketRows), s.K * sizeof(int32_t), st, mbits, colid, cnt,
-                       s.T, KW, s.K);
+    hipLaunchKernelGGL(bucket_count_kernel, rgrid, dim3(kBucketRows), s.K * sizeof(int32_t), st, mbits, cnt, s.T, KW,
+                       s.K);
     hipLaunchKernelGGL(bucket_scan_kernel, dim3(static_cast<uint32_t>(s.N)), dim3(1024), 0, st, cnt, bstart, cstart,
-                       cursor, chunk_col, s.K, max_chunks);
-    hipLaunchKernelGGL(bucket_scatter_kernel, rgrid, dim3(kBucketRows), 2 * s.K * sizeof(int32_t), st, colid, cursor,
-                       perm, O, s.T, s.K);
+                       cursor, chunk_col, s.K, lay.max_chunks);
+    hipLaunchKernelGGL(bucket_scatter_kernel, rgrid, dim3(kBucketRows), 2 * s.K * sizeof(int32_t), st, mbits, cursor,
+                       perm, multi ? static_cast<uint16_t*>(nullptr) : O, s.T, KW, s.K, lay.entries);
     TileArgs a{};
     a.Q = Q; a.K = K; a.V = V; a.mbits = nullptr; a.O = O; a.seq_len = s.seq_len;
     a.N = s.N; a.H = s.H; a.T = s.T; a.U = U; a.KW = 0; a.rlog = rlog; a.w = w; a.causal = s.causal;
     a.group_heads = s.N;
     a.c = s.scale * kLog2e;
     a.perm = perm; a.bstart = bstart; a.chunk_col = chunk_col; a.cstart = cstart;
-    a.max_chunks = max_chunks; a.Kcols = s.K;
+    a.max_chunks = lay.max_chunks; a.Kcols = s.K; a.perm_stride = lay.entries;
+    a.slots = s.k_hat;
+    if (multi) {
+      a.part_o = reinterpret_cast<uint16_t*>(base + lay.part_o);
+      a.part_ml = reinterpret_cast<float*>(base + lay.part_ml);
+    }
+    const int32_t max_chunks = lay.max_chunks;
     hipLaunchKernelGGL((tile_attn_kernel<0, 2>), dim3(static_cast<uint32_t>(s.N) * max_chunks), dim3(256), 0, st, a);
+    if (multi) {
+      const int64_t rows = static_cast<int64_t>(s.N) * s.T;
+      hipLaunchKernelGGL(bucket_merge_kernel, dim3(static_cast<uint32_t>((rows * 8 + 255) / 256)), dim3(256), 0, st,
+                         mbits, a.part_o, a.part_ml, O, rows, KW, s.k_hat, a.c);
+    }
     return hipGetLastError();
   }
   StageScope scope(SEA_STAGE_SPARSE, st);

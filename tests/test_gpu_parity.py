@@ -109,6 +109,11 @@ SMALL_CASES = [
     _wl("bf16_fused_w256_causal", 1, 2, 2048, 64, 8, 2, k_budget=32),
     _wl("bf16_fused_w512_bidir_pad", 2, 1, 2048, 128, 4, 1, k_budget=64, causal=False, pad_frac=0.3),
     _wl("bf16_fused_w512_causal_bucket", 1, 2, 4096, 64, 8, 1, k_budget=32),
+    # a few columns per row (2 <= k^ <= 8, at most K / 8): (row, column) entries bucketed by column,
+    # partial results merged per row
+    _wl("bf16_multi_k3_causal", 1, 2, 1024, 64, 64, 3, k_budget=48),
+    _wl("bf16_multi_k2_bidir_pad", 2, 2, 512, 64, 32, 2, causal=False, pad_frac=0.3),
+    _wl("bf16_multi_k8_causal", 1, 2, 2048, 64, 64, 8, k_budget=64),
     # whole columns of 256 keys: more keys per column than one staging step holds
     _wl("bf16_whole_w256_causal", 1, 2, 1024, 64, 4, 2),
     _wl("bf16_whole_w128_bidir_pad", 2, 1, 1024, 64, 8, 3, causal=False, pad_frac=0.3),
