@@ -173,9 +173,12 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   int32_t u_end_wg, u_end, j_free;
   if (BUCKET) {
     u_end_wg = u_end = ulim;
-    // rows of a bucket come from anywhere in the sequence: with causal attention or padding every
-    // sub-chunk compares positions
-    j_free = (a.causal || len < a.T) ? -1 : a.T - 1;
+    // rows of a bucket come from anywhere in the sequence: positions are compared only in the
+    // sub-chunks that reach past the earliest limit among the wave's rows
+    int32_t jm = row_active ? (a.causal ? min(t, len - 1) : len - 1) : 0x7fffffff;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) jm = min(jm, __shfl_xor(jm, off, 64));
+    j_free = jm;
   } else {
     const int32_t wg_hi = min(wg_tile * 128 + 127, a.T - 1);
     u_end_wg = compact_count(a.causal ? min(wg_hi, len - 1) : len - 1, a.rlog, a.w);
@@ -541,17 +544,25 @@ __global__ __launch_bounds__(256) void bucket_merge_kernel(const uint32_t* __res
   int n = 0;
   for (int32_t j = 0; j < KW; ++j) n += __popc(mbits[row * KW + j]);
   n = min(n, slots);
+  // all of the row's entries are requested before any is used
+  float ms[kMaxSlots], ls[kMaxSlots];
+  uint4 vs[kMaxSlots];
   float M = -INFINITY;
-  for (int q = 0; q < n; ++q) M = fmaxf(M, part_ml[2 * (row * slots + q)]);
+#pragma unroll
+  for (int q = 0; q < kMaxSlots; ++q) {
+    const int64_t e = row * slots + min(q, max(n - 1, 0));
+    ms[q] = part_ml[2 * e];
+    ls[q] = q < n ? part_ml[2 * e + 1] : 0.f;
+    vs[q] = *reinterpret_cast<const uint4*>(part_o + e * kHeadDim + part * 8);
+    if (q < n) M = fmaxf(M, ms[q]);
+  }
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   float wsum = 0.f;
-  for (int q = 0; q < n; ++q) {
-    const int64_t e = row * slots + q;
-    const float l = part_ml[2 * e + 1];
-    if (!(l > 0.f)) continue;
-    const float wq = l * __builtin_amdgcn_exp2f((part_ml[2 * e] - M) * c);
-    const uint4 v = *reinterpret_cast<const uint4*>(part_o + e * kHeadDim + part * 8);
-    const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int q = 0; q < kMaxSlots; ++q) {
+    if (!(ls[q] > 0.f)) continue;
+    const float wq = ls[q] * __builtin_amdgcn_exp2f((ms[q] - M) * c);
+    const uint32_t wds[4] = {vs[q].x, vs[q].y, vs[q].z, vs[q].w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       acc[2 * i] = fmaf(wq, bf16lo_to_f32(wds[i]), acc[2 * i]);
