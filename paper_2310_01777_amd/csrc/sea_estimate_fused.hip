@@ -100,6 +100,19 @@ __device__ __forceinline__ void stage_w(const uint16_t* __restrict__ W, uint16_t
   }
 }
 
+// raw projections w_f . x of 16 rows x m features: dots[ft][i] for feature 16 ft + 4 lg + i
+template <int MC>
+__device__ __forceinline__ void project_dots(const uint16_t* Ws, bf16x8 x0, bf16x8 x1, int lr, int lg,
+                                             floatx4 (&dots)[2 * MC]) {
+#pragma unroll
+  for (int ft = 0; ft < 2 * MC; ++ft) {
+    const uint16_t* w = &Ws[(ft * 16 + lr) * kWRow + 8 * lg];
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    acc = mfma16(*reinterpret_cast<const bf16x8*>(w), x0, acc);
+    dots[ft] = mfma16(*reinterpret_cast<const bf16x8*>(w + 32), x1, acc);
+  }
+}
+
 // exponent arguments (log2 domain) of 16 rows x m features: arg[ft][i] for feature 16 ft + 4 lg + i
 template <int MC>
 __device__ __forceinline__ void project(const uint16_t* Ws, bf16x8 x0, bf16x8 x1, int lr, int lg,
@@ -394,24 +407,28 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     float nx = sumsq8(x0) + sumsq8(x1);
     nx += __shfl_xor(nx, 16, kWave);
     nx += __shfl_xor(nx, 32, kWave);
-    floatx4 arg[2 * MC];
-    project<MC>(Ws, x0, x1, lr, lg, c_dot, c_norm * nx, arg);
-    float amax = -INFINITY;
+    floatx4 dots[2 * MC];
+    project_dots<MC>(Ws, x0, x1, lr, lg, dots);
+    float dmax = -INFINITY;
 #pragma unroll
     for (int ft = 0; ft < 2 * MC; ++ft)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) amax = fmaxf(amax, arg[ft][i]);
-    amax = fmaxf(amax, __shfl_xor(amax, 16, kWave));
-    amax = fmaxf(amax, __shfl_xor(amax, 32, kWave));
-    const float shift = ceilf(amax);  // power-of-two row scale: commutes with the bf16 rounding
-    const bool active = t < len;
+      for (int i = 0; i < 4; ++i) dmax = fmaxf(dmax, dots[ft][i]);
+    dmax = fmaxf(dmax, __shfl_xor(dmax, 16, kWave));
+    dmax = fmaxf(dmax, __shfl_xor(dmax, 32, kWave));
+    // Largest exponent argument of the row (the map dot -> c_dot dot - bias is monotone), rounded up:
+    // a power-of-two row scale, which commutes with the bf16 rounding.  Inactive rows get an
+    // infinite shift, i.e. all-zero features.
+    const float bias = c_norm * nx;
+    const float shift = t < len ? ceilf(fmaf(c_dot, dmax, -bias)) : INFINITY;
+    const float off = -(bias + shift);
 #pragma unroll
     for (int kc = 0; kc < MC; ++kc) {
       float lo[4], hi[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        lo[i] = active ? __builtin_amdgcn_exp2f(arg[2 * kc][i] - shift) : 0.f;
-        hi[i] = active ? __builtin_amdgcn_exp2f(arg[2 * kc + 1][i] - shift) : 0.f;
+        lo[i] = __builtin_amdgcn_exp2f(fmaf(c_dot, dots[2 * kc][i], off));
+        hi[i] = __builtin_amdgcn_exp2f(fmaf(c_dot, dots[2 * kc + 1][i], off));
       }
       afrag[kc] = pack8(lo, hi);
     }
@@ -509,25 +526,39 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   if (r0 >= s.T) return;  // no barrier below
 
   // ---- masking, the own column, normalisation ----
-  int32_t trow[4], ctrow[4];
+  // last[i] = last admissible column of row i (-1: inactive row); causal rows take their own
+  // column (= last) from diag.  Column cc = 16 ct + lr is the own one iff 16 ct == e, masked iff
+  // 16 ct > e, with e = last - lr.  Tiles wholly below every row's last column need neither test,
+  // tiles above the wave's last one are cleared.
+  int32_t trow[4], ncnd[4], e[4];
   bool act[4];
   float rsum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     trow[i] = r0 + 4 * lg + i;
     act[i] = trow[i] < len;
-    ctrow[i] = CAUSAL ? (min(trow[i], s.T - 1) >> wl) : s.K;  // first masked column is ctrow + 1
+    const int32_t jmax = CAUSAL ? min(trow[i], len - 1) : len - 1;
+    ncnd[i] = act[i] ? (jmax >> wl) + 1 : 0;
+    e[i] = ncnd[i] - 1 - lr;
   }
+  const bool act_all = r0 + 15 < len;  // wave-uniform
+  const int32_t ct_free = act_all ? (((CAUSAL ? r0 : len - 1) >> wl) >> 4) : 0;
 #pragma unroll
   for (int ct = 0; ct < NCT; ++ct) {
-    const int32_t cc = ct * 16 + lr;
+    if (ct < ct_free) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float v = acc[ct][i];
-      if (CAUSAL && cc == ctrow[i]) v = diag[i];
-      if (cc > ctrow[i] || cc >= s.K || !act[i]) v = 0.f;
-      acc[ct][i] = v;
-      rsum[i] += v;
+      for (int i = 0; i < 4; ++i) rsum[i] += acc[ct][i];
+    } else if (ct * 16 < ncols_wave) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float v = acc[ct][i];
+        if (CAUSAL && ct * 16 == e[i]) v = diag[i];
+        if (ct * 16 > e[i]) v = 0.f;
+        acc[ct][i] = v;
+        rsum[i] += v;
+      }
+    } else {
+      acc[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
   }
   float* out = A_hat ? A_hat + (head * s.T) * s.K : nullptr;
@@ -556,15 +587,19 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   uint32_t key[NCT][4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int32_t jmax = CAUSAL ? min(trow[i], len - 1) : len - 1;
-    const int32_t ncand = act[i] ? (jmax >> wl) + 1 : 0;
-    nsel[i] = static_cast<uint32_t>(min(s.k_hat, ncand));
+    nsel[i] = static_cast<uint32_t>(min(s.k_hat, ncnd[i]));
     tau[i] = 0x80000000u;
-    cge[i] = static_cast<uint32_t>(ncand);
+    cge[i] = static_cast<uint32_t>(ncnd[i]);
+  }
 #pragma unroll
-    for (int ct = 0; ct < NCT; ++ct) {
-      const int32_t cc = ct * 16 + lr;
-      key[ct][i] = cc < ncand ? (__float_as_uint(acc[ct][i] + 0.0f) | 0x80000000u) : 0u;
+  for (int ct = 0; ct < NCT; ++ct) {
+    if (ct < ct_free) {  // every column of the tile is a candidate of every row
+#pragma unroll
+      for (int i = 0; i < 4; ++i) key[ct][i] = __float_as_uint(acc[ct][i] + 0.0f) | 0x80000000u;
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        key[ct][i] = ct * 16 <= e[i] ? (__float_as_uint(acc[ct][i] + 0.0f) | 0x80000000u) : 0u;
     }
   }
   // The compare-and-count loop runs over the tiles that hold candidates of this wave's rows only
