@@ -185,8 +185,9 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
   bool act[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    bias[i] = c_norm * __shfl(nx, (lane & 48) | (4 * lg + i), kWave);
     act[i] = r0 + 4 * lg + i < len;
+    // keys past the sequence end get an infinite bias: their features are exp2(-inf) = 0
+    bias[i] = act[i] ? c_norm * __shfl(nx, (lane & 48) | (4 * lg + i), kWave) : INFINITY;
   }
   uint16_t* sh = state + head * static_cast<int64_t>(s.K) * m;
 #pragma unroll
@@ -197,7 +198,7 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
     acc = mfma16(x1, *reinterpret_cast<const bf16x8*>(wr + 32), acc);
     float v[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = act[i] ? __builtin_amdgcn_exp2f(fmaf(c_dot, acc[i], -bias[i])) : 0.f;
+    for (int i = 0; i < 4; ++i) v[i] = __builtin_amdgcn_exp2f(fmaf(c_dot, acc[i], -bias[i]));
     // where feature 16 ft + lr sits in a fragment-ordered row
     const int slot = 32 * (ft >> 1) + 8 * (lr >> 2) + 4 * (ft & 1) + (lr & 3);
     if (w == 1) {
