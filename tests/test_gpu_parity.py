@@ -114,6 +114,9 @@ SMALL_CASES = [
     _wl("bf16_multi_k3_causal", 1, 2, 1024, 64, 64, 3, k_budget=48),
     _wl("bf16_multi_k2_bidir_pad", 2, 2, 512, 64, 32, 2, causal=False, pad_frac=0.3),
     _wl("bf16_multi_k8_causal", 1, 2, 2048, 64, 64, 8, k_budget=64),
+    # K = 24: one mask word per row where the rows kernel holds two, 768 rows = 6 blocks of 128
+    _wl("bf16_bucket_K24", 1, 2, 768, 64, 24, 1, k_budget=16),
+    _wl("bf16_multi_K24_bidir", 1, 2, 768, 64, 24, 3, k_budget=24, causal=False),
     # whole columns of 256 keys: more keys per column than one staging step holds
     _wl("bf16_whole_w256_causal", 1, 2, 1024, 64, 4, 2),
     _wl("bf16_whole_w128_bidir_pad", 2, 1, 1024, 64, 8, 3, causal=False, pad_frac=0.3),
