@@ -385,6 +385,43 @@ def test_bucketed_rows_are_reproducible(sea):
         assert torch.equal(a[k][:, :, :t0 + 1], b[k][:, :, :t0 + 1]), k
 
 
+@pytest.mark.parametrize("shape", ["tiles", "buckets", "multi"])
+def test_forward_replays_in_a_hip_graph(sea, shape):
+    """sea_forward enqueues kernels only (no allocation, no synchronisation, no memset), so a
+    captured graph of it can be replayed: every replay, with new inputs written into the same
+    buffers and eager work in between, must equal the eager call bit for bit."""
+    wl = {"tiles": _wl("graph_tiles", 1, 2, 512, 64, 32, 8),
+          "buckets": _wl("graph_buckets", 1, 2, 1024, 64, 16, 1, k_budget=32),
+          "multi": _wl("graph_multi", 1, 2, 1024, 64, 64, 3, k_budget=48)}[shape]
+    x = synth.make_inputs(wl)
+    xd = _dev(x)
+    p = _params(sea, wl, xd["seq_len"])
+    ws = sea.alloc_workspace(p)
+    O_graph = torch.empty_like(xd["Q"])
+    O_eager = torch.empty_like(xd["Q"])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sea.sea_forward(p, xd["Q"], xd["K"], xd["V"], xd["W"], O_graph, None, None, None, None, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sea.sea_forward(p, xd["Q"], xd["K"], xd["V"], xd["W"], O_graph, None, None, None, None, ws)
+    gen = torch.Generator().manual_seed(11)
+    for it in range(4):
+        if it > 0:   # new inputs in place, plus unrelated eager work between replays
+            for k in "QKV":
+                xd[k].copy_((torch.randn(xd[k].shape, generator=gen) * (1.0 + 0.5 * it)).to(xd[k].dtype))
+            _ = (xd["Q"].float() @ xd["K"].float().transpose(-1, -2)).sum().item()
+        graph.replay()
+        torch.cuda.synchronize()
+        ws2 = sea.alloc_workspace(p)
+        sea.sea_forward(p, xd["Q"], xd["K"], xd["V"], xd["W"], O_eager, None, None, None, None, ws2)
+        torch.cuda.synchronize()
+        assert torch.equal(O_graph, O_eager), f"replay {it}"
+
+
 def test_padding_rows_and_zero_length(sea):
     """seq_len = 0 for a batch element: every output of it is inert; other elements unaffected."""
     wl = _wl("pad0", 2, 2, 128, 32, 16, 4, causal=False)
