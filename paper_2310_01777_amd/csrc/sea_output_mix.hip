@@ -24,22 +24,61 @@ __device__ __forceinline__ void st<float>(float* p, float v) { *p = v; }
 template <>
 __device__ __forceinline__ void st<uint16_t>(uint16_t* p, float v) { *p = f32_to_bf16(v); }
 
+// eight consecutive elements of a row <-> eight floats
+__device__ __forceinline__ void load8(const float* p, float (&v)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const uint16_t* p, float (&v)[8]) {
+  const uint4 u = *reinterpret_cast<const uint4*>(p);
+  const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { v[2 * i] = bf16lo_to_f32(w[i]); v[2 * i + 1] = bf16hi_to_f32(w[i]); }
+}
+__device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ void store8(uint16_t* p, const float (&v)[8]) {
+  uint4 u;
+  u.x = pack_bf16(v[0], v[1]); u.y = pack_bf16(v[2], v[3]);
+  u.z = pack_bf16(v[4], v[5]); u.w = pack_bf16(v[6], v[7]);
+  *reinterpret_cast<uint4*>(p) = u;
+}
+
+// Causal mixing works on chunks of 256 rows.  A thread owns 8 consecutive rows x 8 dimensions
+// (slot = tid / 8, dimension group = tid % 8), so every load is 16 or 32 bytes and the 8 lanes of
+// a row cover it whole; the eight row loads of a thread are independent.
+
 // ---- causal pass 1: per (head, 256-row chunk) column sums of V -> part[N][chunks][64] ----
 template <typename T>
 __global__ __launch_bounds__(256) void chunk_sums_kernel(Shape s, const T* __restrict__ V,
                                                          double* __restrict__ part) {
-  __shared__ double red[4][kHeadDim];
-  const int d = threadIdx.x & 63, q = threadIdx.x >> 6;
+  __shared__ float red[32][kHeadDim + 1];
+  const int slot = threadIdx.x >> 3, dg = threadIdx.x & 7;
   const uint32_t chunks = (s.T + kChunkRows - 1) / kChunkRows;
   const int64_t head = blockIdx.x / chunks;
-  const int32_t r0 = static_cast<int32_t>(blockIdx.x % chunks) * kChunkRows + q * 64;
+  const int32_t r0 = static_cast<int32_t>(blockIdx.x % chunks) * kChunkRows + slot * 8;
   const int32_t b = static_cast<int32_t>(head / s.H);
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
-  double acc = 0.0;
-  for (int32_t t = r0; t < min(r0 + 64, len); ++t) acc += ld<T>(V + (head * s.T + t) * kHeadDim + d);
-  red[q][d] = acc;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    if (r0 + r < len) {
+      float v[8];
+      load8(V + (head * s.T + r0 + r) * kHeadDim + dg * 8, v);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] += v[i];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) red[slot][dg * 8 + i] = acc[i];
   __syncthreads();
-  if (q == 0) part[static_cast<int64_t>(blockIdx.x) * kHeadDim + d] = red[0][d] + red[1][d] + red[2][d] + red[3][d];
+  if (threadIdx.x < kHeadDim) {
+    double tot = 0.0;
+    for (int q = 0; q < 32; ++q) tot += red[q][threadIdx.x];
+    part[static_cast<int64_t>(blockIdx.x) * kHeadDim + threadIdx.x] = tot;
+  }
 }
 
 // ---- causal pass 2: offset = sum of earlier chunks, in-chunk running sums, mix ----
@@ -49,33 +88,66 @@ __global__ __launch_bounds__(256) void mix_causal_kernel(Shape s, const T* __res
                                                          const double* __restrict__ part,
                                                          const float* __restrict__ s_prob,
                                                          const float* __restrict__ s_mix, T* __restrict__ O) {
-  __shared__ double qsum[4][kHeadDim];
-  const int d = threadIdx.x & 63, q = threadIdx.x >> 6;
+  __shared__ float red[32][kHeadDim + 1];
+  __shared__ double offs[33][kHeadDim];  // exclusive prefix of the 32 slots (row 32: unused total)
+  const int slot = threadIdx.x >> 3, dg = threadIdx.x & 7;
   const uint32_t chunks = (s.T + kChunkRows - 1) / kChunkRows;
   const int64_t head = blockIdx.x / chunks;
   const uint32_t chunk = blockIdx.x % chunks;
-  const int32_t r0 = static_cast<int32_t>(chunk) * kChunkRows + q * 64;
+  const int32_t r0 = static_cast<int32_t>(chunk) * kChunkRows + slot * 8;
   const int32_t b = static_cast<int32_t>(head / s.H);
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
-  double off = 0.0;
-  for (uint32_t c = 0; c < chunk; ++c) off += part[(head * chunks + c) * kHeadDim + d];
-  // sums of this thread's 64 rows, then the offsets of the four quarters
-  double mine = 0.0;
-  for (int32_t t = r0; t < min(r0 + 64, len); ++t) mine += ld<T>(V + (head * s.T + t) * kHeadDim + d);
-  qsum[q][d] = mine;
-  __syncthreads();
-  for (int x = 0; x < q; ++x) off += qsum[x][d];
-  double run = off;
-  for (int32_t t = r0; t < min(r0 + 64, s.T); ++t) {
-    const int64_t e = (head * s.T + t) * kHeadDim + d;
-    if (t >= len) {
-      st<T>(O + e, 0.f);
-      continue;
+  // the thread's 8 rows x 8 dimensions of V, kept for the second sweep
+  float v[8][8];
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    if (r0 + r < len) {
+      load8(V + (head * s.T + r0 + r) * kHeadDim + dg * 8, v[r]);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[r][i] = 0.f;
     }
-    run += ld<T>(V + e);
-    const float sm = s_mix[head * s.T + t], sp = s_prob ? s_prob[head * s.T + t] : 1.f;
-    const double avg = run / static_cast<double>(t + 1);
-    st<T>(O + e, static_cast<float>(static_cast<double>(sm) * sp * ld<T>(C + e) + (1.0 - sm) * avg));
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] += v[r][i];
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) red[slot][dg * 8 + i] = acc[i];
+  __syncthreads();
+  if (threadIdx.x < kHeadDim) {
+    const int d = threadIdx.x;
+    double run = 0.0;
+    for (uint32_t c = 0; c < chunk; ++c) run += part[(head * chunks + c) * kHeadDim + d];
+    for (int q = 0; q < 32; ++q) {
+      offs[q][d] = run;
+      run += red[q][d];
+    }
+  }
+  __syncthreads();
+  double run[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) run[i] = offs[slot][dg * 8 + i];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const int32_t t = r0 + r;
+    if (t >= s.T) break;
+    const int64_t e = (head * s.T + t) * kHeadDim + dg * 8;
+    float o[8];
+    if (t >= len) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = 0.f;
+    } else {
+      float c[8];
+      load8(C + e, c);
+      const float sm = s_mix[head * s.T + t], sp = s_prob ? s_prob[head * s.T + t] : 1.f;
+      const double inv = 1.0 / static_cast<double>(t + 1);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        run[i] += v[r][i];
+        o[i] = static_cast<float>(static_cast<double>(sm) * sp * c[i] + (1.0 - sm) * (run[i] * inv));
+      }
+    }
+    store8(O + e, o);
   }
 }
 
