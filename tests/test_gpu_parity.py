@@ -3,6 +3,8 @@ seeded inputs.  Integer work (selection, expansion) must be bit-exact; floating 
 the contract's relative tolerances (1e-5 fp32, 2e-2 bf16)."""
 from dataclasses import replace
 
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -123,7 +125,38 @@ SMALL_CASES = [
 ]
 
 
-@pytest.mark.parametrize("wl", SMALL_CASES, ids=lambda w: w.name)
+def _random_cases(n, seed):
+    """Seeded draw of valid small shapes across every dispatch: column widths that are and are
+    not powers of two, K that does and does not divide T, all feature counts, k^ from 1 up, key
+    budgets, both directions, padding."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        K = int(rng.choice([3, 4, 7, 8, 16, 24, 32, 48, 64, 100, 128, 256]))
+        if rng.random() < 0.75:
+            w = int(rng.choice([1, 2, 4, 8, 16, 32, 64, 128, 256, 3, 5, 12]))
+            T = K * w
+        else:
+            T = int(rng.integers(K, 900))
+        if T < 16 or T > 2048:
+            continue
+        m = int(rng.choice([32, 64, 96, 128, 256]))
+        k_hat = int(min(K, rng.choice([1, 1, 2, 3, 5, 8, 13, 32, 64])))
+        k_budget = int(rng.choice([0, 0, 8, 16, 33, 64, 200]))
+        causal = bool(rng.random() < 0.6)
+        pad = float(rng.choice([0.0, 0.0, 0.3]))
+        B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+        dtype = "f32" if rng.random() < 0.2 else "bf16"
+        out.append(_wl(f"rnd{len(out)}_T{T}_K{K}_m{m}_kh{k_hat}_kb{k_budget}_c{int(causal)}_p{int(pad > 0)}_{dtype}",
+                       B, H, T, m, K, k_hat, k_budget=k_budget, causal=causal, pad_frac=pad, dtype=dtype))
+    return out
+
+
+# SEA_RANDOM_CASES / SEA_RANDOM_SEED widen or move the random draw for a one-off sweep
+_RANDOM = _random_cases(int(os.environ.get("SEA_RANDOM_CASES", "40")), int(os.environ.get("SEA_RANDOM_SEED", "2024")))
+
+
+@pytest.mark.parametrize("wl", SMALL_CASES + _RANDOM, ids=lambda w: w.name)
 def test_forward_matches_oracle(sea, wl):
     x = synth.make_inputs(wl)
     p, xd, g = _gpu_forward(sea, wl, x)
