@@ -27,6 +27,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
 
 constexpr int kWRow = 72;  // halfwords per staged W row (128 B + 16 B pad): conflict-free b128 reads
 
@@ -73,6 +74,17 @@ __device__ __forceinline__ uint32_t group_sum_u(uint32_t x) {  // integer counts
   if (W >= 8) x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), kRowHalfMirror, 0xf, 0xf, false));
   if (W >= 16) x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), kRowMirror, 0xf, 0xf, false));
   return x;
+}
+// four independent 16-lane sums, step by step
+__device__ __forceinline__ void group_sum4_u(uint32_t (&x)[4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) x[i] += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x[i]), kQuadXor1, 0xf, 0xf, false));
+#pragma unroll
+  for (int i = 0; i < 4; ++i) x[i] += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x[i]), kQuadXor2, 0xf, 0xf, false));
+#pragma unroll
+  for (int i = 0; i < 4; ++i) x[i] += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x[i]), kRowHalfMirror, 0xf, 0xf, false));
+#pragma unroll
+  for (int i = 0; i < 4; ++i) x[i] += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x[i]), kRowMirror, 0xf, 0xf, false));
 }
 template <int W>
 __device__ __forceinline__ uint32_t group_max_u(uint32_t x) {
@@ -600,28 +612,66 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     } else {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        key[ct][i] = ct * 16 <= e[i] ? (__float_as_uint(acc[ct][i] + 0.0f) | 0x80000000u) : 0u;
+        key[ct][i] = ct * 16 <= e[i] ? (__float_as_uint(acc[ct][i] + 0.0f) | 0x80000000u) : 0x40000000u;
     }
   }
   // The compare-and-count loop runs over the tiles that hold candidates of this wave's rows only
   // (causal: the leading ones), in even steps so that a handful of loop bodies covers all cases.
-#define SEA_SEARCH(NT_)                                                                          \
-  _Pragma("unroll 1") for (int bit = 29; bit >= 0; --bit) {                                       \
+// Bits 29..16 are searched on the keys' high halves, two keys per register: both halves of
+// hp - trial (16-bit wrap-around differences; candidates and trial lie in [0x8000, 0xc000),
+// non-candidates are 0x4000) have bit 15 set exactly for keys below the trial, and those bits are
+// counted four differences at a time.  The trial's low half is zero in that phase, so the counts
+// are those of the full keys.  Bits 15..0 then compare whole keys.
+#define SEA_SEARCH_STEP(COUNT_BODY_)                                                             \
     /* done when every row's count of keys >= tau equals its quota */                            \
+    bool pend[4];                                                                                \
     bool pending = false;                                                                        \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) pending |= (cge[i] != nsel[i]) && (nsel[i] != 0u); \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                               \
+      pend[i] = (cge[i] != nsel[i]) && (nsel[i] != 0u);                                          \
+      pending |= pend[i];                                                                        \
+    }                                                                                            \
     if (__ballot(pending) == 0ull) break;                                                        \
+    uint32_t cnts[4] = {0u, 0u, 0u, 0u};                                                         \
     _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                               \
       /* skip the slot once its four rows (one per lane group) are settled */                    \
-      if (__ballot((cge[i] != nsel[i]) && (nsel[i] != 0u)) == 0ull) continue;                    \
+      if (__ballot(pend[i]) == 0ull) continue;                                                   \
       const uint32_t trial = tau[i] | (1u << bit);                                               \
       uint32_t cnt = 0;                                                                          \
-      _Pragma("unroll") for (int ct = 0; ct < (NT_); ++ct) cnt += (key[ct][i] >= trial) ? 1u : 0u; \
-      cnt = group_sum_u<16>(cnt);                                                                \
-      const bool take = cnt >= nsel[i];                                                          \
-      tau[i] = take ? trial : tau[i];                                                            \
-      cge[i] = take ? cnt : cge[i];                                                              \
+      COUNT_BODY_                                                                                \
+      cnts[i] = cnt;                                                                             \
     }                                                                                            \
+    /* the four lane-group sums side by side: their cross-lane steps fill each other's gaps */   \
+    group_sum4_u(cnts);                                                                          \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                               \
+      const bool take = pend[i] && cnts[i] >= nsel[i];                                           \
+      tau[i] = take ? (tau[i] | (1u << bit)) : tau[i];                                           \
+      cge[i] = take ? cnts[i] : cge[i];                                                          \
+    }
+#define SEA_SEARCH(NT_)                                                                          \
+  {                                                                                              \
+    ushort2v hp[(NT_) / 2][4];                                                                   \
+    _Pragma("unroll") for (int pr = 0; pr < (NT_) / 2; ++pr)                                      \
+      _Pragma("unroll") for (int i = 0; i < 4; ++i)                                               \
+        hp[pr][i] = __builtin_bit_cast(ushort2v, __builtin_amdgcn_perm(key[2 * pr + 1][i], key[2 * pr][i], 0x07060302u)); \
+    _Pragma("unroll 1") for (int bit = 29; bit >= 16; --bit) {                                    \
+      SEA_SEARCH_STEP(                                                                           \
+        const uint32_t th = trial >> 16;                                                         \
+        const ushort2v th2 = __builtin_bit_cast(ushort2v, th | (th << 16));                      \
+        uint32_t below = 0;                                                                      \
+        _Pragma("unroll") for (int pr = 0; pr < (NT_) / 2; pr += 2) {                             \
+          const uint32_t d0 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr][i] - th2)); \
+          const uint32_t d1 = (pr + 1 < (NT_) / 2)                                               \
+              ? __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr + 1 < (NT_) / 2 ? pr + 1 : pr][i] - th2)) : 0u; \
+          /* the four sign bytes of two differences */                                           \
+          const uint32_t sb = __builtin_amdgcn_perm(d1, d0, 0x07050301u) & 0x80808080u;          \
+          below += static_cast<uint32_t>(__popc(sb));                                            \
+        }                                                                                        \
+        cnt = static_cast<uint32_t>(NT_) - below;)                                               \
+    }                                                                                            \
+  }                                                                                              \
+  _Pragma("unroll 1") for (int bit = 15; bit >= 0; --bit) {                                       \
+    SEA_SEARCH_STEP(                                                                             \
+      _Pragma("unroll") for (int ct = 0; ct < (NT_); ++ct) cnt += (key[ct][i] >= trial) ? 1u : 0u;) \
   }
   const int32_t nct_wave = CAUSAL ? min(NCT, (ncols_wave + 15) >> 4) : NCT;
   if (s.k_hat == 1) {
@@ -653,6 +703,7 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     SEA_SEARCH(2)
   }
 #undef SEA_SEARCH
+#undef SEA_SEARCH_STEP
   // selection: keys >= tau; when more keys than the quota tie at tau (exact duplicates at the
   // boundary), the lowest columns among them win
   uint32_t selbits[4];  // bit ct set: column 16 ct + lr of row 4 lg + i is selected
