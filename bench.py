@@ -101,8 +101,8 @@ def issued_tile_flops(wl, seq_len):
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (heads are independent; see DESIGN.md for how "
-              "the path would shard); rerun with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the B*H heads are independent, so more GPUs "
+              "would each take a share of them with no exchange); rerun with --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2310_01777_amd import binding as sea
