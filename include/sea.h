@@ -134,6 +134,11 @@ int sea_sparse_attn(const sea_params* p, const void* Q, const void* K, const voi
  * that intermediate; results are identical either way.  mhat_opt receives the compressed binary
  * mask M^ of Sec. 3.1 "Linear Sparse Attention Mask Generation", bit-packed:
  * uint32 [B][H][T][ceil(K/32)], bit c % 32 of word c / 32 set iff column c is selected.
+ * Every output is a deterministic function of the inputs (runs are bit-identical): where the
+ * attention stage groups rows by their selected column (bf16, K | T, per-query grouping and
+ * k_hat = 1 or k_hat <= min(8, K/8)) the order inside a group comes from atomics, but no result
+ * depends on it.  Only kernels are enqueued (no allocation, memset or synchronisation), so the
+ * call can be captured in a HIP graph.  Calls that share a workspace must not overlap.
  */
 int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V, const void* W,
                 void* O, float* A_hat_opt, int32_t* sel_opt, int32_t* idx_opt, int32_t* cnt_opt,
