@@ -317,6 +317,35 @@ def test_output_mix_matches_oracle(sea, dtype, causal):
     assert_close(to_np64(C_dev), want, TOL[dtype], "C_sea in place")
 
 
+def test_grouped_topk_mask_exact_on_planted_ties(sea):
+    """Causal-per-batch grouping: the H x K slab of a time step is ranked as one list; equal scores
+    go to the lower flattened index h K + c.  Bit-exact against the oracle with planted duplicates
+    across and inside heads, for slab sizes that use one to many values per thread."""
+    g = torch.Generator().manual_seed(9)
+    for (T, K, H, kh, kb) in [(128, 32, 2, 7, 0), (96, 24, 5, 3, 0), (256, 256, 3, 5, 0),
+                              (512, 64, 12, 9, 40), (64, 8, 1, 2, 0), (256, 128, 32, 16, 0)]:
+        B = 2
+        A = torch.rand(B, H, T, K, generator=g)
+        A[0] = torch.round(A[0] * 4) / 4               # many ties across heads
+        A[1, 0] = 0.25
+        A[1, -1, :, ::3] = 0.0
+        seq_len = torch.tensor([T, max(1, T - 37)], dtype=torch.int32)
+        wl = _wl("gtopk", B, H, T, 32, K, kh, k_budget=kb, causal=True, grouping=1)
+        p = _params(sea, wl, seq_len.cuda())
+        L, S = sea.sea_row_stride(p), sea.sea_sel_stride(p)
+        sel = torch.empty(B, H, T, S, dtype=torch.int32, device="cuda")
+        idx = torch.empty(B, H, T, L, dtype=torch.int32, device="cuda")
+        cnt = torch.empty(B, H, T, dtype=torch.int32, device="cuda")
+        print(f"[case] grouped topk T{T} K{K} H{H} kh{kh} kb{kb}", flush=True)
+        sea.sea_topk_mask(p, A.cuda(), sel, idx, cnt)
+        torch.cuda.synchronize()
+        po = oracle_params(wl)
+        s_o, i_o, c_o = oracle.topk_mask(po, A.numpy(), seq_len=seq_len.numpy())
+        assert np.array_equal(sel.cpu().numpy(), s_o)
+        assert np.array_equal(idx.cpu().numpy(), i_o)
+        assert np.array_equal(cnt.cpu().numpy(), c_o)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_topk_mask_exact_on_planted_ties(sea, dtype):
     """Selection and expansion are integer work: bit-exact, including planted duplicates."""
