@@ -165,9 +165,10 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
 
 // ------------------------------------------------------------------------------------------
 // Causal-per-batch grouping (Sec. 3.1): A_hat is viewed as [T][H K]; each time step keeps the
-// H k^ largest entries of its H x K slab.  One block per (batch element, time step); thread
-// tid holds the VPT consecutive flattened entries tid VPT .. tid VPT + VPT - 1 (flattened
-// index h K + c), so "lower flattened index first" among equal scores is (thread, slot) order.
+// H k^ largest entries of its H x K slab.  One block per (batch element, time step); the slab
+// (flattened index h K + c) is dealt to the threads in groups of four entries, group gi of thread
+// tid starting at entry (gi 256 + tid) 4, so "lower flattened index first" among equal scores is
+// (group, thread, slot) order.
 // ------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t wave_sum_u32(uint32_t x) {
   x += static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(x), 0xB1, 0xf, 0xf, false));   // quad xor 1
@@ -200,32 +201,33 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
   const int64_t quota = static_cast<int64_t>(s.H) * s.k_hat, total = static_cast<int64_t>(s.H) * ncand;
   const uint32_t n = static_cast<uint32_t>(quota < total ? quota : total);
 
+  // A thread owns VPT / 4 groups of four consecutive entries of the flattened slab: group gi of
+  // thread tid starts at entry (gi * 256 + tid) * 4, so the lanes of a wave read consecutive 16-byte
+  // pieces (full lines) and the flattened order is (group, thread, slot) order.
   uint32_t key[VPT];
-  if (s.K % VPT == 0) {
-    // the thread's VPT entries lie in one head: 128-bit loads
-    const int32_t e0 = tid * VPT;
-    const int32_t h = e0 / s.K, c0 = e0 - h * s.K;
-    const float4* src = reinterpret_cast<const float4*>(
-        A_hat + ((static_cast<int64_t>(b) * s.H + min(h, s.H - 1)) * s.T + t) * s.K + c0);
 #pragma unroll
-    for (int v4 = 0; v4 < VPT / 4; ++v4) {
+  for (int gi = 0; gi < VPT / 4; ++gi) {
+    const int32_t e0 = (gi * 256 + tid) * 4;
+    if ((s.K & 3) == 0) {
+      // the four entries lie in one head: one 128-bit load
+      const int32_t h = e0 / s.K, c0 = e0 - h * s.K;
       float4 f = {0.f, 0.f, 0.f, 0.f};
-      if (e0 < HK && c0 + 4 * v4 < ncand) f = src[v4];
+      if (e0 < HK && c0 < ncand)
+        f = *reinterpret_cast<const float4*>(A_hat + ((static_cast<int64_t>(b) * s.H + h) * s.T + t) * s.K + c0);
       const float fv[4] = {f.x, f.y, f.z, f.w};
 #pragma unroll
-      for (int q = 0; q < 4; ++q)
-        key[4 * v4 + q] = (e0 < HK && c0 + 4 * v4 + q < ncand) ? ordered_key(fv[q]) : 0u;
-    }
-  } else {
+      for (int q = 0; q < 4; ++q) key[4 * gi + q] = (e0 < HK && c0 + q < ncand) ? ordered_key(fv[q]) : 0u;
+    } else {
 #pragma unroll
-    for (int v = 0; v < VPT; ++v) {
-      const int32_t e = tid * VPT + v;
-      uint32_t k = 0u;
-      if (e < HK) {
-        const int32_t h = e / s.K, c = e - h * s.K;
-        if (c < ncand) k = ordered_key(A_hat[((static_cast<int64_t>(b) * s.H + h) * s.T + t) * s.K + c]);
+      for (int q = 0; q < 4; ++q) {
+        const int32_t e = e0 + q;
+        uint32_t k = 0u;
+        if (e < HK) {
+          const int32_t h = e / s.K, c = e - h * s.K;
+          if (c < ncand) k = ordered_key(A_hat[((static_cast<int64_t>(b) * s.H + h) * s.T + t) * s.K + c]);
+        }
+        key[4 * gi + q] = k;
       }
-      key[v] = k;
     }
   }
   // n-th largest key by bitwise search; block-wide counts: wave ballots, then 4 partial sums in LDS
@@ -261,32 +263,44 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
     __syncthreads();
     c_gt = red[0][0] + red[0][1] + red[0][2] + red[0][3];
   }
-  const bool exact = (c_ge == n);
-  uint32_t need_eq = n - c_gt;  // entries equal to tau that are kept, lowest flattened index first
-  // exclusive prefix over threads of the number of entries equal to tau
-  uint32_t my_eq = 0;
+  const bool exact = (c_ge == n);   // block-uniform
+  const uint32_t need_eq = n - c_gt;  // entries equal to tau that are kept, lowest flattened index first
+  if (exact || n == 0) {
 #pragma unroll
-  for (int v = 0; v < VPT; ++v) my_eq += (n > 0 && !exact && key[v] == tau) ? 1u : 0u;
-  uint32_t incl = my_eq;
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const uint32_t o = __shfl_up(incl, off, kWave);
-    if (lane >= off) incl += o;
-  }
-  if (lane == kWave - 1) scan[wid] = incl;
-  __syncthreads();
-  uint32_t before = incl - my_eq;
-  for (int q = 0; q < wid; ++q) before += scan[q];
-#pragma unroll
-  for (int v = 0; v < VPT; ++v) {
-    const int32_t e = tid * VPT + v;
-    bool take = false;
-    if (n > 0) {
-      if (exact) take = key[v] >= tau;
-      else if (key[v] > tau) take = true;
-      else if (key[v] == tau) { take = before < need_eq; ++before; }
+    for (int v = 0; v < VPT; ++v) {
+      const int32_t e = ((v >> 2) * 256 + tid) * 4 + (v & 3);
+      if (e < HK) flags[e] = (n > 0 && key[v] >= tau) ? 1 : 0;
     }
-    if (e < HK) flags[e] = take ? 1 : 0;
+  } else {
+    // ties at the threshold: walk the groups in flattened order, each with an exclusive prefix over
+    // the threads of its number of entries equal to tau
+    uint32_t base = 0;
+#pragma unroll 1
+    for (int gi = 0; gi < VPT / 4; ++gi) {
+      uint32_t my_eq = 0;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) my_eq += (key[4 * gi + q] == tau) ? 1u : 0u;
+      uint32_t incl = my_eq;
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) {
+        const uint32_t o = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += o;
+      }
+      if (lane == kWave - 1) scan[wid] = incl;
+      __syncthreads();
+      uint32_t before = base + incl - my_eq;
+      for (int q = 0; q < wid; ++q) before += scan[q];
+      base += scan[0] + scan[1] + scan[2] + scan[3];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int32_t e = (gi * 256 + tid) * 4 + q;
+        const uint32_t ky = key[4 * gi + q];
+        bool take = ky > tau;
+        if (ky == tau) { take = before < need_eq; ++before; }
+        if (e < HK) flags[e] = take ? 1 : 0;
+      }
+      __syncthreads();  // scan[] is rewritten by the next group
+    }
   }
   __syncthreads();
   // packed mask words: word j of head h holds columns 32 j .. 32 j + 31
