@@ -205,12 +205,18 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
   // thread tid starts at entry (gi * 256 + tid) * 4, so the lanes of a wave read consecutive 16-byte
   // pieces (full lines) and the flattened order is (group, thread, slot) order.
   uint32_t key[VPT];
+  // head and column of the thread's first entry; a group further on is 1024 entries further on
+  const int32_t adv_h = 1024 / s.K, adv_c = 1024 - adv_h * s.K;  // block-uniform
+  int32_t gh = (tid * 4) / s.K, gc = tid * 4 - gh * s.K;
 #pragma unroll
   for (int gi = 0; gi < VPT / 4; ++gi) {
     const int32_t e0 = (gi * 256 + tid) * 4;
     if ((s.K & 3) == 0) {
       // the four entries lie in one head: one 128-bit load
-      const int32_t h = e0 / s.K, c0 = e0 - h * s.K;
+      const int32_t h = gh, c0 = gc;
+      gh += adv_h;
+      gc += adv_c;
+      if (gc >= s.K) { gc -= s.K; ++gh; }
       float4 f = {0.f, 0.f, 0.f, 0.f};
       if (e0 < HK && c0 < ncand)
         f = *reinterpret_cast<const float4*>(A_hat + ((static_cast<int64_t>(b) * s.H + h) * s.T + t) * s.K + c0);
@@ -236,9 +242,49 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
   // SIMDs of a CU, would otherwise be the bottleneck.  The search stops as soon as exactly n
   // keys are >= tau.
   uint32_t tau = 0, c_ge = static_cast<uint32_t>(256 * VPT);
+  // Scores of an estimate lie in [0, 2): their keys are 0x80000000 + (less than 2^30), so bits 31
+  // and 30 of the threshold are known and bits 29..16 can be searched on the keys' high halves, two
+  // keys per register (16-bit wrap-around differences against the trial have bit 15 set exactly
+  // for keys below it once non-candidates are given 0x4000; the sign bytes of two registers are
+  // gathered by one byte permute and counted).  Any other input takes the general 32-bit search.
+  bool in_range = true;
+#pragma unroll
+  for (int v = 0; v < VPT; ++v) in_range &= (key[v] == 0u) || ((key[v] >> 30) == 2u);
+  const bool fast = __syncthreads_and(in_range ? 1 : 0) != 0;
+  int bit = 31;
+  if (n > 0 && fast && VPT <= 32) {  // the largest slabs have no registers to spare for the packed copy
+    typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
+    ushort2v hp[VPT / 2];
+#pragma unroll
+    for (int pr = 0; pr < VPT / 2; ++pr) {
+      const uint32_t k0 = key[2 * pr] ? key[2 * pr] : 0x40000000u, k1 = key[2 * pr + 1] ? key[2 * pr + 1] : 0x40000000u;
+      hp[pr] = __builtin_bit_cast(ushort2v, __builtin_amdgcn_perm(k1, k0, 0x07060302u));
+    }
+    tau = 0x80000000u;
+    c_ge = static_cast<uint32_t>(total);  // every candidate's key is >= 0x80000000
+#pragma unroll 1
+    for (bit = 29; bit >= 16 && c_ge != n; --bit) {
+      const uint32_t trial = tau | (1u << bit);
+      const uint32_t th = trial >> 16;
+      const ushort2v th2 = __builtin_bit_cast(ushort2v, th | (th << 16));
+      uint32_t below = 0;
+#pragma unroll
+      for (int pr = 0; pr < VPT / 2; pr += 2) {
+        const uint32_t d0 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr] - th2));
+        const uint32_t d1 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr + 1] - th2));
+        below += static_cast<uint32_t>(__popc(__builtin_amdgcn_perm(d1, d0, 0x07050301u) & 0x80808080u));
+      }
+      const uint32_t c = wave_sum_u32(static_cast<uint32_t>(VPT) - below);
+      if (lane == 0) red[bit & 1][wid] = c;
+      __syncthreads();  // the buffers alternate, so one barrier per step is enough
+      const uint32_t ct = red[bit & 1][0] + red[bit & 1][1] + red[bit & 1][2] + red[bit & 1][3];
+      if (ct >= n) { tau = trial; c_ge = ct; }
+    }
+    bit = 15;
+  }
   if (n > 0) {
 #pragma unroll 1
-    for (int bit = 31; bit >= 0 && c_ge != n; --bit) {
+    for (; bit >= 0 && c_ge != n; --bit) {
       const uint32_t trial = tau | (1u << bit);
       uint32_t c = 0;
 #pragma unroll
@@ -265,11 +311,33 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
   }
   const bool exact = (c_ge == n);   // block-uniform
   const uint32_t need_eq = n - c_gt;  // entries equal to tau that are kept, lowest flattened index first
+  const bool want_lists = sel || idx || cnt;
+  // 32 | K: the 32 entries of eight consecutive threads' groups are exactly one mask word
+  const bool words_from_regs = (exact || n == 0) && mbits && (s.K & 31) == 0;
   if (exact || n == 0) {
+    if (want_lists || (mbits && !words_from_regs)) {
 #pragma unroll
-    for (int v = 0; v < VPT; ++v) {
-      const int32_t e = ((v >> 2) * 256 + tid) * 4 + (v & 3);
-      if (e < HK) flags[e] = (n > 0 && key[v] >= tau) ? 1 : 0;
+      for (int v = 0; v < VPT; ++v) {
+        const int32_t e = ((v >> 2) * 256 + tid) * 4 + (v & 3);
+        if (e < HK) flags[e] = (n > 0 && key[v] >= tau) ? 1 : 0;
+      }
+    }
+    if (words_from_regs) {
+#pragma unroll
+      for (int gi = 0; gi < VPT / 4; ++gi) {
+        const int32_t e0 = (gi * 256 + tid) * 4;
+        uint32_t nib = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) nib |= (n > 0 && key[4 * gi + q] >= tau) ? (1u << q) : 0u;
+        uint32_t word = nib << (4 * (lane & 7));
+        word |= static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(word), 0xB1, 0xf, 0xf, false));
+        word |= static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(word), 0x4E, 0xf, 0xf, false));
+        word |= static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(word), 0x141, 0xf, 0xf, false));
+        if ((lane & 7) == 0 && e0 < HK) {
+          const int32_t h = e0 / s.K, c0 = e0 - h * s.K;
+          mbits[((static_cast<int64_t>(b) * s.H + h) * s.T + t) * kw + (c0 >> 5)] = word;
+        }
+      }
     }
   } else {
     // ties at the threshold: walk the groups in flattened order, each with an exclusive prefix over
@@ -304,7 +372,7 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
   }
   __syncthreads();
   // packed mask words: word j of head h holds columns 32 j .. 32 j + 31
-  if (mbits) {
+  if (mbits && !words_from_regs) {
     for (int32_t x = tid; x < s.H * kw; x += 256) {
       const int32_t h = x / kw, j = x - h * kw;
       uint32_t word = 0;
