@@ -129,6 +129,22 @@ int sea_sparse_attn(const sea_params* p, const void* Q, const void* K, const voi
                     void* hip_stream);
 
 /*
+ * Phases (2b) + (2c) from the compressed binary mask M^ of Sec. 3.1 "Linear Sparse Attention Mask
+ * Generation" (the bit-packed form sea_forward writes to mhat_opt): row t attends, for every set
+ * bit c of its mask row, the r keys start_c + floor(i w / r), i < r, of column c that are
+ * admissible (j <= t when causal, j < seq_len) -- the expansion of App. A.5.3 is implicit -- and
+ * O[t] is the softmax-weighted sum of their values as in sea_sparse_attn.  This is the attention
+ * stage of sea_forward on its own; it needs the column-structured form, sea_attention_path(p) == 1
+ * (SEA_ENOTSUP otherwise), and sea_mask_attn_workspace_bytes() of 256-byte aligned scratch (0 for
+ * most shapes; then workspace may be NULL).  A mask row may hold at most k_hat set bits (or, with
+ * grouping = 1, any number); where rows are grouped by column (see sea_forward) further bits are
+ * ignored.  Rows without set bits give zeros.
+ */
+size_t sea_mask_attn_workspace_bytes(const sea_params* p);
+int sea_mask_attn(const sea_params* p, const void* Q, const void* K, const void* V, const uint32_t* mhat,
+                  void* O, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * The whole forward pass (Fig. "model structure", phases 1 and 2 back to back) on one stream.
  * A_hat_opt, sel_opt, idx_opt, cnt_opt, mhat_opt may each be NULL when the caller does not want
  * that intermediate; results are identical either way.  mhat_opt receives the compressed binary

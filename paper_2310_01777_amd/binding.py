@@ -66,6 +66,8 @@ def _load() -> ctypes.CDLL:
     lib.sea_strerror.restype, lib.sea_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
     lib.sea_last_hip_error.restype, lib.sea_last_hip_error.argtypes = ctypes.c_int, []
     lib.sea_attention_path.restype, lib.sea_attention_path.argtypes = ctypes.c_int, [P]
+    lib.sea_mask_attn_workspace_bytes.restype, lib.sea_mask_attn_workspace_bytes.argtypes = sz, [P]
+    lib.sea_mask_attn.restype, lib.sea_mask_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.sea_version.restype, lib.sea_version.argtypes = ctypes.c_char_p, []
     return lib
 
@@ -186,6 +188,25 @@ def sea_sparse_attn(p: SeaParams, Q, K, V, idx, cnt, row_stride, O, stream=None)
                                 _ptr(cnt, torch.int32, n, "cnt"), int(row_stride),
                                 _ptr(O, p.torch_dtype, n * p.d, "O"), _stream(stream)),
            "sea_sparse_attn")
+
+
+def sea_mask_attn_workspace_bytes(p: SeaParams) -> int:
+    cp = p.c()
+    return int(_lib.sea_mask_attn_workspace_bytes(ctypes.byref(cp)))
+
+
+def sea_mask_attn(p: SeaParams, Q, K, V, mhat, O, workspace=None, stream=None):
+    n = p.B * p.H * p.T
+    cp = p.c()
+    _check(_lib.sea_mask_attn(ctypes.byref(cp), _ptr(Q, p.torch_dtype, n * p.d, "Q"),
+                              _ptr(K, p.torch_dtype, n * p.d, "K"),
+                              _ptr(V, p.torch_dtype, n * p.d, "V"),
+                              _ptr(mhat, torch.int32, n * ((p.K + 31) // 32), "mhat"),
+                              _ptr(O, p.torch_dtype, n * p.d, "O"),
+                              _ptr(workspace, None, None, "workspace"),
+                              0 if workspace is None else workspace.numel() * workspace.element_size(),
+                              _stream(stream)),
+           "sea_mask_attn")
 
 
 def sea_forward(p: SeaParams, Q, K, V, W, O, A_hat=None, sel=None, idx=None, cnt=None,

@@ -218,6 +218,30 @@ int sea_sparse_attn(const sea_params* p, const void* Q, const void* K, const voi
   return e == hipSuccess ? SEA_OK : fail_hip(e);
 }
 
+size_t sea_mask_attn_workspace_bytes(const sea_params* p) {
+  if (check_common(p) != SEA_OK || check_mask_params(p) != SEA_OK) return 0;
+  const Shape s = make_shape(p, true);
+  if (!tile_attn_supported(s, p->dtype, nullptr)) return 0;
+  return align256(tile_attn_workspace(s));
+}
+
+int sea_mask_attn(const sea_params* p, const void* Q, const void* K, const void* V, const uint32_t* mhat,
+                  void* O, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_common(p);
+  if (rc == SEA_OK) rc = check_mask_params(p);
+  if (rc != SEA_OK) return rc;
+  if (!Q || !K || !V || !mhat || !O) return SEA_EINVAL;
+  const Shape s = make_shape(p, true);
+  if (!tile_attn_supported(s, p->dtype, nullptr)) return SEA_ENOTSUP;
+  const size_t need = align256(tile_attn_workspace(s));
+  if (need > 0 && (!workspace || workspace_bytes < need || reinterpret_cast<uintptr_t>(workspace) % 256 != 0))
+    return SEA_EWORKSPACE;
+  const hipError_t e = launch_tile_attn(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                                        static_cast<const uint16_t*>(V), mhat, static_cast<uint16_t*>(O),
+                                        workspace, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SEA_OK : fail_hip(e);
+}
+
 int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V, const void* W,
                 void* O, float* A_hat_opt, int32_t* sel_opt, int32_t* idx_opt, int32_t* cnt_opt,
                 uint32_t* mhat_opt, void* workspace, size_t workspace_bytes, void* hip_stream) {

@@ -423,7 +423,7 @@ __global__ __launch_bounds__(256) void zero_i32_kernel(int32_t* __restrict__ p, 
 // bucket sizes: every set mask bit of a row is one entry of that column's bucket
 __global__ __launch_bounds__(kBucketRows) void bucket_count_kernel(const uint32_t* __restrict__ mbits,
                                                                    int32_t* __restrict__ cnt, int32_t T,
-                                                                   int32_t KW, int32_t Kc) {
+                                                                   int32_t KW, int32_t Kc, int32_t slots) {
   extern __shared__ int32_t hist[];  // Kc counters
   const int64_t head = blockIdx.y;
   const int32_t row = blockIdx.x * kBucketRows + threadIdx.x;
@@ -431,12 +431,14 @@ __global__ __launch_bounds__(kBucketRows) void bucket_count_kernel(const uint32_
   __syncthreads();
   if (row < T) {
     const uint32_t* mw = mbits + (head * T + row) * KW;
+    int n = 0;  // a row has at most `slots` entries: further bits of a foreign mask are ignored
     for (int32_t j = 0; j < KW; ++j) {
       uint32_t word = mw[j];
-      while (word != 0u) {
+      while (word != 0u && n < slots) {
         const int bit = __ffs(static_cast<int>(word)) - 1;
         word &= word - 1u;
         atomicAdd(&hist[32 * j + bit], 1);
+        ++n;
       }
     }
   }
@@ -491,7 +493,8 @@ __global__ __launch_bounds__(kBucketRows) void bucket_scatter_kernel(const uint3
                                                                      int32_t* __restrict__ cursor,
                                                                      int32_t* __restrict__ perm,
                                                                      uint16_t* __restrict__ O_zero, int32_t T,
-                                                                     int32_t KW, int32_t Kc, int64_t perm_stride) {
+                                                                     int32_t KW, int32_t Kc, int64_t perm_stride,
+                                                                     int32_t slots) {
   extern __shared__ int32_t hist[];  // Kc counters, then Kc bases
   int32_t* base = hist + Kc;
   const int64_t head = blockIdx.y;
@@ -504,7 +507,7 @@ __global__ __launch_bounds__(kBucketRows) void bucket_scatter_kernel(const uint3
     const uint32_t* mw = mbits + (head * T + row) * KW;
     for (int32_t j = 0; j < KW; ++j) {
       uint32_t word = mw[j];
-      while (word != 0u && n < kMaxSlots) {
+      while (word != 0u && n < slots) {
         const int bit = __ffs(static_cast<int>(word)) - 1;
         word &= word - 1u;
         const int32_t col = 32 * j + bit;
@@ -665,11 +668,11 @@ hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K
     hipLaunchKernelGGL(zero_i32_kernel, dim3(static_cast<uint32_t>((ncnt + 255) / 256)), dim3(256), 0, st, cnt, ncnt);
     const dim3 rgrid((s.T + kBucketRows - 1) / kBucketRows, static_cast<uint32_t>(s.N));
     hipLaunchKernelGGL(bucket_count_kernel, rgrid, dim3(kBucketRows), s.K * sizeof(int32_t), st, mbits, cnt, s.T, KW,
-                       s.K);
+                       s.K, s.k_hat);
     hipLaunchKernelGGL(bucket_scan_kernel, dim3(static_cast<uint32_t>(s.N)), dim3(1024), 0, st, cnt, bstart, cstart,
                        cursor, chunk_col, s.K, lay.max_chunks);
     hipLaunchKernelGGL(bucket_scatter_kernel, rgrid, dim3(kBucketRows), 2 * s.K * sizeof(int32_t), st, mbits, cursor,
-                       perm, multi ? static_cast<uint16_t*>(nullptr) : O, s.T, KW, s.K, lay.entries);
+                       perm, multi ? static_cast<uint16_t*>(nullptr) : O, s.T, KW, s.K, lay.entries, s.k_hat);
     TileArgs a{};
     a.Q = Q; a.K = K; a.V = V; a.mbits = nullptr; a.O = O; a.seq_len = s.seq_len;
     a.N = s.N; a.H = s.H; a.T = s.T; a.U = U; a.KW = 0; a.rlog = rlog; a.w = w; a.causal = s.causal;

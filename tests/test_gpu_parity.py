@@ -409,6 +409,61 @@ def test_sparse_attn_arbitrary_lists(sea, dtype):
     assert (O[0, 0, :5] == 0).all()
 
 
+def _pack_mask(mask):
+    """bool [..., K] -> int32 words [..., ceil(K/32)], bit c % 32 of word c // 32."""
+    K = mask.shape[-1]
+    KW = (K + 31) // 32
+    padded = np.zeros(mask.shape[:-1] + (KW * 32,), dtype=np.uint64)
+    padded[..., :K] = mask
+    words = (padded.reshape(*mask.shape[:-1], KW, 32) << np.arange(32, dtype=np.uint64)).sum(-1)
+    return words.astype(np.uint32).view(np.int32)
+
+
+@pytest.mark.parametrize("case", [(2, 3, 1024, 64, 8, 0, True), (2, 3, 1024, 32, 1, 16, True),
+                                  (1, 4, 2048, 64, 4, 0, False), (2, 2, 512, 128, 16, 64, True),
+                                  (1, 2, 4096, 16, 1, 0, True)])
+def test_mask_attn_from_a_foreign_mask(sea, case):
+    """The attention stage on its own: a mask that does not come from the estimator (top-k^ of
+    random scores, taken by the oracle) against the oracle's attention over the expanded lists,
+    in the tiled, the one-column bucket and the several-column bucket forms."""
+    B, H, T, K, kh, kb, causal = case
+    wl = _wl("mask_attn", B, H, T, 64, K, kh, k_budget=kb, causal=causal, pad_frac=0.3)
+    x = synth.make_inputs(wl)
+    g = torch.Generator().manual_seed(31)
+    A = torch.rand(B, H, T, K, generator=g)
+    po = oracle_params(wl)
+    sl = None if x["seq_len"] is None else x["seq_len"].numpy()
+    s_o, i_o, c_o = oracle.topk_mask(po, A.numpy(), seq_len=sl)
+    want = oracle.sparse_attn(po, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), i_o, c_o)
+    mhat = torch.from_numpy(_pack_mask(_sel_to_mask(s_o, K))).cuda()
+    xd = _dev(x)
+    p = _params(sea, wl, xd["seq_len"])
+    assert sea.sea_attention_path(p) == 1
+    nbytes = sea.sea_mask_attn_workspace_bytes(p)
+    ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda")
+    O = torch.full((B, H, T, 64), float("nan"), dtype=torch.bfloat16, device="cuda")
+    print(f"[case] mask_attn B{B} H{H} T{T} K{K} kh{kh} kb{kb} causal{int(causal)} ws{nbytes}", flush=True)
+    sea.sea_mask_attn(p, xd["Q"], xd["K"], xd["V"], mhat, O, ws)
+    torch.cuda.synchronize()
+    assert_close(to_np64(O), want, TOL["bf16"], "O from mask")
+    # and the stage reproduces the forward pass bit for bit from the mask that pass wrote
+    _, _, out = _gpu_forward(sea, wl, x)
+    O2 = torch.empty_like(O)
+    sea.sea_mask_attn(p, xd["Q"], xd["K"], xd["V"], out["mhat"].cuda(), O2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(O2.cpu(), out["O"])
+
+
+def test_mask_attn_rejects_unstructured_shapes(sea):
+    wl = _wl("mask_attn_bad", 1, 2, 300, 64, 17, 5)
+    p = _params(sea, wl)
+    assert sea.sea_mask_attn_workspace_bytes(p) == 0
+    one = torch.zeros(300 * 2 * 64, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(sea.SeaError) as e:
+        sea.sea_mask_attn(p, one, one, one, torch.zeros(600, dtype=torch.int32, device="cuda"), one)
+    assert e.value.status == sea.SEA_ENOTSUP
+
+
 def test_causality_and_determinism_on_gpu(sea):
     """Rows <= t0 do not change when later positions change; two runs are bit-identical."""
     wl = _wl("causality", 1, 2, 256, 64, 32, 6)
