@@ -217,3 +217,49 @@ def output_mix(p: Params, C, V, s_mix, s_prob=None, A_hat=None, seq_len=None):
     if rc != 0:
         raise MemoryError("ref_output_mix failed")
     return O
+
+
+def flatcsr(p: Params, idx, cnt):
+    """FlatCSR tensor of the expanded mask -- Sec. 3.1.1 "FlatCSR" and App. A.5 "FlatCSR: Modified
+    CSR Format To Handle Grouped Mask": M* [B][H][T][T] with the head and query axes exchanged and
+    (head, key) flattened into one column axis, stored as CSR.  Row b T + t holds, ascending, the
+    columns h T + j of the keys j that head h attends from query t.
+
+    Returns (crow int64 [B T + 1], col int32 [nnz])."""
+    idx, cnt = _i32(idx), _i32(cnt)
+    assert cnt.shape == (p.B, p.H, p.T) and idx.shape[:3] == cnt.shape
+    crow = np.zeros(p.B * p.T + 1, dtype=np.int64)
+    col = []
+    for b in range(p.B):
+        for t in range(p.T):
+            n = 0
+            for h in range(p.H):
+                keys = idx[b, h, t, :cnt[b, h, t]]
+                col.append(h * p.T + keys.astype(np.int64))
+                n += len(keys)
+            crow[b * p.T + t + 1] = crow[b * p.T + t] + n
+    col = np.concatenate(col) if col else np.zeros(0, dtype=np.int64)
+    return crow, col.astype(np.int32)
+
+
+def flatcsr_attn(p: Params, Q, K, V, crow, col):
+    """Sparse attention (Sec. 3.1.1) read from the FlatCSR tensor: entry h T + j of row b T + t is
+    key j of head h for query t; the softmax runs over the entries of one head in one row.
+    The tensor is taken apart into per-head key lists, then attended as in ``sparse_attn``."""
+    crow = np.asarray(crow, dtype=np.int64)
+    col = np.asarray(col, dtype=np.int64)
+    lists = {}
+    L = 1
+    for b in range(p.B):
+        for t in range(p.T):
+            e = col[crow[b * p.T + t]:crow[b * p.T + t + 1]]
+            for h in range(p.H):
+                keys = e[e // p.T == h] - h * p.T
+                lists[b, h, t] = keys
+                L = max(L, len(keys))
+    idx = np.full((p.B, p.H, p.T, L), -1, dtype=np.int32)
+    cnt = np.zeros((p.B, p.H, p.T), dtype=np.int32)
+    for (b, h, t), keys in lists.items():
+        idx[b, h, t, :len(keys)] = keys
+        cnt[b, h, t] = len(keys)
+    return sparse_attn(p, Q, K, V, idx, cnt)

@@ -574,3 +574,65 @@ def test_output_mix_limits_and_closed_forms():
         a = oracle.output_mix(p, C, V, ones, s_prob=sp, A_hat=A, seq_len=seq_len)
         z = oracle.output_mix(p, C, V, zeros, A_hat=A, seq_len=seq_len)
         np.testing.assert_allclose(mix, sm[..., None] * a + (1 - sm[..., None]) * z, rtol=1e-12, atol=1e-14)
+
+
+# ----------------------------------------------------------------------------------------------
+# FlatCSR tensor (Sec. 3.1.1 "FlatCSR", App. A.5)
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("grouping,causal", [(0, False), (0, True), (1, True)])
+def test_flatcsr_equals_library_csr_of_the_transposed_flattened_mask(grouping, causal):
+    """Build the dense mask M* [B,H,T,T] from the selected columns by the column-range definition
+    (not from the lists), exchange head and query axes, flatten (head, key), and let the library
+    make the CSR tensor: row pointers and column indices must be identical."""
+    import scipy.sparse
+    B, H, T, d, m, K, kh, kb = 2, 3, 40, 4, 8, 8, 2, 6
+    Q, Kk, V = _rand_qkv(B, H, T, d, seed=21)
+    W = synth.gaussian_orthogonal(m, d, 0).numpy()
+    sl = np.array([T, T - 7], dtype=np.int32)
+    p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=K, k_hat=kh, k_budget=kb, causal=causal, scale=0.5,
+                      grouping=grouping)
+    out = oracle.forward(p, Q, Kk, V, W, seq_len=sl)
+    w, r = T // K, min(T // K, max(1, kb // kh))
+    M = np.zeros((B, H, T, T), dtype=bool)
+    for b, h, t in np.ndindex(B, H, T):
+        if t >= sl[b]:
+            continue
+        for c in out["sel"][b, h, t]:
+            if c < 0:
+                continue
+            for i in range(r):
+                j = c * w + (i * w) // r
+                if j < sl[b] and (j <= t or not causal):
+                    M[b, h, t, j] = True
+    want = scipy.sparse.csr_matrix(M.transpose(0, 2, 1, 3).reshape(B * T, H * T))
+    want.sort_indices()
+    crow, col = oracle.flatcsr(p, out["idx"], out["cnt"])
+    assert np.array_equal(crow, want.indptr) and np.array_equal(col, want.indices)
+    assert crow[-1] == out["cnt"].sum()
+    if grouping == 1:      # every time step keeps H k^ columns, up to r keys each
+        per_row = np.diff(crow).reshape(B, T)
+        assert per_row.max() <= H * kh * r
+    # attention read back from the tensor = attention over the lists = masked dense softmax
+    got = oracle.flatcsr_attn(p, Q, Kk, V, crow, col)
+    np.testing.assert_array_equal(got, out["O"])
+    S = 0.5 * torch.from_numpy(Q) @ torch.from_numpy(Kk).transpose(-1, -2)
+    S = S.masked_fill(~torch.from_numpy(M), float("-inf"))
+    dense = torch.nan_to_num(torch.softmax(S, -1), nan=0.0) @ torch.from_numpy(V)
+    np.testing.assert_allclose(got, dense.numpy(), rtol=1e-12, atol=1e-13)
+
+
+def test_flatcsr_hand_enumerated():
+    """T = 4, H = 2, one batch element: lists written by hand."""
+    p = oracle.Params(B=1, H=2, T=4, d=4, m=8, K=2, k_hat=1)
+    idx = np.full((1, 2, 4, 2), -1, dtype=np.int32)
+    cnt = np.zeros((1, 2, 4), dtype=np.int32)
+    idx[0, 0, 0, :1], cnt[0, 0, 0] = [0], 1
+    idx[0, 1, 0, :1], cnt[0, 1, 0] = [0], 1
+    idx[0, 0, 1, :2], cnt[0, 0, 1] = [0, 1], 2                 # head 1 attends nothing at t = 1
+    idx[0, 1, 2, :2], cnt[0, 1, 2] = [2, 3], 2                 # head 0 attends nothing at t = 2
+    idx[0, 0, 3, :2], cnt[0, 0, 3] = [2, 3], 2
+    idx[0, 1, 3, :2], cnt[0, 1, 3] = [0, 1], 2
+    crow, col = oracle.flatcsr(p, idx, cnt)
+    assert crow.tolist() == [0, 2, 4, 6, 10]
+    assert col.tolist() == [0, 4, 0, 1, 6, 7, 2, 3, 4, 5]
