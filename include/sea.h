@@ -129,6 +129,34 @@ int sea_sparse_attn(const sea_params* p, const void* Q, const void* K, const voi
                     void* hip_stream);
 
 /*
+ * Sec. 3.1.1 "FlatCSR" and App. A.5 "FlatCSR: Modified CSR Format To Handle Grouped Mask": the
+ * expanded mask M* [B][H][T][T] with the head and query axes exchanged and (head, key) flattened
+ * into one column axis, stored as CSR, so that one time step -- the group of the causal-per-batch
+ * selection -- is one CSR row.
+ *   crow [B T + 1] (device, int64): crow[b T + t] = first entry of row (b, t); crow[B T] = nnz.
+ *   col  [col_capacity] (device, int32): entries h T + j, heads ascending and keys ascending
+ *        inside a head, for the keys j that idx / cnt (as sea_topk_mask or sea_forward wrote them,
+ *        row stride `row_stride`) list for head h at query t.  Needs H T < 2^31.
+ * Entries beyond col_capacity are not written, crow is complete either way: crow[B T] >
+ * col_capacity tells the caller the array was too small.  B H T row_stride always suffices; so
+ * does B T H k_hat r with r keys per selected column (either grouping).
+ * Workspace: sea_flatcsr_workspace_bytes(), 256-byte aligned.
+ */
+size_t sea_flatcsr_workspace_bytes(const sea_params* p);
+int sea_flatcsr(const sea_params* p, const int32_t* idx, const int32_t* cnt, int32_t row_stride,
+                int64_t* crow, int32_t* col, int64_t col_capacity, void* workspace, size_t workspace_bytes,
+                void* hip_stream);
+
+/*
+ * Phase (2c) read from the FlatCSR tensor (App. A.5: the kernel undoes the flattening and the
+ * exchange of axes itself): O[b][h][t] = sum_j softmax_j(scale q_t.k_j) v_j over the entries
+ * h T + j of CSR row b T + t, arithmetic as in sea_sparse_attn.  Columns of a CSR row must ascend;
+ * a row (b, h, t) without entries gives zeros.
+ */
+int sea_flatcsr_attn(const sea_params* p, const void* Q, const void* K, const void* V, const int64_t* crow,
+                     const int32_t* col, void* O, void* hip_stream);
+
+/*
  * Phases (2b) + (2c) from the compressed binary mask M^ of Sec. 3.1 "Linear Sparse Attention Mask
  * Generation" (the bit-packed form sea_forward writes to mhat_opt): row t attends, for every set
  * bit c of its mask row, the r keys start_c + floor(i w / r), i < r, of column c that are

@@ -66,6 +66,10 @@ def _load() -> ctypes.CDLL:
     lib.sea_strerror.restype, lib.sea_strerror.argtypes = ctypes.c_char_p, [ctypes.c_int]
     lib.sea_last_hip_error.restype, lib.sea_last_hip_error.argtypes = ctypes.c_int, []
     lib.sea_attention_path.restype, lib.sea_attention_path.argtypes = ctypes.c_int, [P]
+    lib.sea_flatcsr_workspace_bytes.restype, lib.sea_flatcsr_workspace_bytes.argtypes = sz, [P]
+    lib.sea_flatcsr.restype = ctypes.c_int
+    lib.sea_flatcsr.argtypes = [P, vp, vp, ctypes.c_int32, vp, vp, ctypes.c_int64, vp, sz, vp]
+    lib.sea_flatcsr_attn.restype, lib.sea_flatcsr_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, vp, vp]
     lib.sea_mask_attn_workspace_bytes.restype, lib.sea_mask_attn_workspace_bytes.argtypes = sz, [P]
     lib.sea_mask_attn.restype, lib.sea_mask_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.sea_version.restype, lib.sea_version.argtypes = ctypes.c_char_p, []
@@ -188,6 +192,35 @@ def sea_sparse_attn(p: SeaParams, Q, K, V, idx, cnt, row_stride, O, stream=None)
                                 _ptr(cnt, torch.int32, n, "cnt"), int(row_stride),
                                 _ptr(O, p.torch_dtype, n * p.d, "O"), _stream(stream)),
            "sea_sparse_attn")
+
+
+def sea_flatcsr_workspace_bytes(p: SeaParams) -> int:
+    cp = p.c()
+    return int(_lib.sea_flatcsr_workspace_bytes(ctypes.byref(cp)))
+
+
+def sea_flatcsr(p: SeaParams, idx, cnt, row_stride, crow, col, workspace, stream=None):
+    n = p.B * p.H * p.T
+    cp = p.c()
+    _check(_lib.sea_flatcsr(ctypes.byref(cp), _ptr(idx, torch.int32, n * row_stride, "idx"),
+                            _ptr(cnt, torch.int32, n, "cnt"), int(row_stride),
+                            _ptr(crow, torch.int64, p.B * p.T + 1, "crow"),
+                            _ptr(col, torch.int32, None, "col"), col.numel(),
+                            _ptr(workspace, None, None, "workspace"),
+                            workspace.numel() * workspace.element_size(), _stream(stream)),
+           "sea_flatcsr")
+
+
+def sea_flatcsr_attn(p: SeaParams, Q, K, V, crow, col, O, stream=None):
+    n = p.B * p.H * p.T
+    cp = p.c()
+    _check(_lib.sea_flatcsr_attn(ctypes.byref(cp), _ptr(Q, p.torch_dtype, n * p.d, "Q"),
+                                 _ptr(K, p.torch_dtype, n * p.d, "K"),
+                                 _ptr(V, p.torch_dtype, n * p.d, "V"),
+                                 _ptr(crow, torch.int64, p.B * p.T + 1, "crow"),
+                                 _ptr(col, torch.int32, None, "col"),
+                                 _ptr(O, p.torch_dtype, n * p.d, "O"), _stream(stream)),
+           "sea_flatcsr_attn")
 
 
 def sea_mask_attn_workspace_bytes(p: SeaParams) -> int:

@@ -213,7 +213,40 @@ int sea_sparse_attn(const sea_params* p, const void* Q, const void* K, const voi
   if (rc != SEA_OK) return rc;
   if (!Q || !K || !V || !idx || !cnt || !O || row_stride <= 0) return SEA_EINVAL;
   const Shape s = make_shape(p, false);
-  const hipError_t e = launch_sparse_attn(s, p->dtype, Q, K, V, idx, cnt, row_stride, O,
+  const hipError_t e = launch_sparse_attn(s, p->dtype, Q, K, V, idx, cnt, row_stride, nullptr, O,
+                                          static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SEA_OK : fail_hip(e);
+}
+
+size_t sea_flatcsr_workspace_bytes(const sea_params* p) {
+  if (check_common(p) != SEA_OK) return 0;
+  return align256(flatcsr_workspace(make_shape(p, false)));
+}
+
+int sea_flatcsr(const sea_params* p, const int32_t* idx, const int32_t* cnt, int32_t row_stride,
+                int64_t* crow, int32_t* col, int64_t col_capacity, void* workspace, size_t workspace_bytes,
+                void* hip_stream) {
+  const int rc = check_common(p);
+  if (rc != SEA_OK) return rc;
+  if (!idx || !cnt || !crow || !col || row_stride <= 0 || col_capacity < 0) return SEA_EINVAL;
+  if (static_cast<int64_t>(p->H) * p->T > INT32_MAX) return SEA_ENOTSUP;  // columns h T + j are int32
+  const Shape s = make_shape(p, false);
+  if (!workspace || workspace_bytes < align256(flatcsr_workspace(s)) ||
+      reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+    return SEA_EWORKSPACE;
+  const hipError_t e = launch_flatcsr(s, idx, cnt, row_stride, crow, col, col_capacity, workspace,
+                                      static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SEA_OK : fail_hip(e);
+}
+
+int sea_flatcsr_attn(const sea_params* p, const void* Q, const void* K, const void* V, const int64_t* crow,
+                     const int32_t* col, void* O, void* hip_stream) {
+  const int rc = check_common(p);
+  if (rc != SEA_OK) return rc;
+  if (!Q || !K || !V || !crow || !col || !O) return SEA_EINVAL;
+  if (static_cast<int64_t>(p->H) * p->T > INT32_MAX) return SEA_ENOTSUP;
+  const Shape s = make_shape(p, false);
+  const hipError_t e = launch_sparse_attn(s, p->dtype, Q, K, V, col, nullptr, 0, crow, O,
                                           static_cast<hipStream_t>(hip_stream));
   return e == hipSuccess ? SEA_OK : fail_hip(e);
 }
@@ -300,7 +333,7 @@ int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V
   int32_t* cnt = cnt_opt ? cnt_opt : reinterpret_cast<int32_t*>(w);
   e = launch_topk_mask(s, A_hat, sel_opt, idx, cnt, mhat_opt, st);
   if (e != hipSuccess) return fail_hip(e);
-  e = launch_sparse_attn(s, p->dtype, Q, K, V, idx, cnt, s.L, O, st);
+  e = launch_sparse_attn(s, p->dtype, Q, K, V, idx, cnt, s.L, nullptr, O, st);
   return e == hipSuccess ? SEA_OK : fail_hip(e);
 }
 

@@ -55,9 +55,16 @@ hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K
                             const uint32_t* mbits, uint16_t* O, void* ws, hipStream_t st);
 size_t dense_attn_workspace(const Shape& s);
 
+// per-row lists (crow == nullptr: idx [N][T][L], cnt [N][T]) or the FlatCSR tensor (crow [B T + 1],
+// idx = its column array, cnt and L unused)
 hipError_t launch_sparse_attn(const Shape& s, sea_dtype dt, const void* Q, const void* K,
                               const void* V, const int32_t* idx, const int32_t* cnt, int32_t L,
-                              void* O, hipStream_t st);
+                              const int64_t* crow, void* O, hipStream_t st);
+
+// FlatCSR tensor from the per-row lists: crow [B T + 1], col [cap] (entries past cap are dropped)
+size_t flatcsr_workspace(const Shape& s);
+hipError_t launch_flatcsr(const Shape& s, const int32_t* idx, const int32_t* cnt, int32_t L, int64_t* crow,
+                          int32_t* col, int64_t cap, void* ws, hipStream_t st);
 
 hipError_t launch_dense_attn(const Shape& s, sea_dtype dt, const void* Q, const void* K,
                              const void* V, void* O, void* ws, hipStream_t st);

@@ -16,13 +16,44 @@ constexpr int kUnroll = 4;
 __device__ __forceinline__ float wave_xor_f(float v, int mask) { return __shfl_xor(v, mask, kWave); }
 __device__ __forceinline__ double wave_xor_d(double v, int mask) { return __shfl_xor(v, mask, kWave); }
 
+// Where a row's key list lives.  Per-row lists: idx + row L, cnt[row] entries.  FlatCSR tensor
+// (crow != nullptr, idx = its column array): row (b, h, t) owns the entries of CSR row b T + t
+// whose column h' T + j has h' = h -- one contiguous run because columns ascend -- found by two
+// binary searches; the key is the entry minus h T.
+struct KeyList {
+  const int32_t* p;
+  int32_t n;
+  int32_t base;
+};
+__device__ __forceinline__ KeyList key_list(const Shape& s, int64_t row, const int32_t* __restrict__ idx,
+                                            const int32_t* __restrict__ cnt, int32_t L,
+                                            const int64_t* __restrict__ crow) {
+  if (crow == nullptr) return {idx + row * L, min(cnt[row], L), 0};
+  const int64_t head = row / s.T, t = row - head * s.T;
+  const int64_t b = head / s.H, h = head - b * s.H;
+  const int64_t beg = crow[b * s.T + t], end = crow[b * s.T + t + 1];
+  int64_t bound[2];
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    const int64_t key = (h + e) * s.T;
+    int64_t a = beg, z = end;
+    while (a < z) {
+      const int64_t mid = (a + z) >> 1;
+      if (idx[mid] < key) a = mid + 1; else z = mid;
+    }
+    bound[e] = a;
+  }
+  return {idx + bound[0], static_cast<int32_t>(bound[1] - bound[0]), static_cast<int32_t>(h * s.T)};
+}
+
 // ------------------------------------------------------------------------------------------
 // bf16: 8 lanes per row, 8 rows per wave load, fp32 logits (log2 domain) and accumulators
 // ------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void sparse_attn_bf16_kernel(
     Shape s, const uint16_t* __restrict__ Q, const uint16_t* __restrict__ K,
     const uint16_t* __restrict__ V, const int32_t* __restrict__ idx,
-    const int32_t* __restrict__ cnt, int32_t L, uint16_t* __restrict__ O) {
+    const int32_t* __restrict__ cnt, int32_t L, const int64_t* __restrict__ crow,
+    uint16_t* __restrict__ O) {
   const uint32_t lb = xcd_contiguous(blockIdx.x, gridDim.x);
   const int64_t row = static_cast<int64_t>(lb) * kWavesPerBlock + (threadIdx.x >> 6);
   const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
@@ -45,8 +76,9 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void sparse_attn_bf16_kernel
       qf[2 * i + 1] = bf16hi_to_f32(w[i]) * f;
     }
   }
-  const int32_t n = min(cnt[row], L);
-  const int32_t* irow = idx + row * L;
+  const KeyList kl = key_list(s, row, idx, cnt, L, crow);
+  const int32_t n = kl.n;
+  const int32_t* irow = kl.p;
 
   float m_run = -INFINITY, l_run = 0.f;
   float o[8];
@@ -59,7 +91,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void sparse_attn_bf16_kernel
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const int32_t p = k0 + u * 8 + g;
-      int32_t j = (p < n) ? irow[p] : -1;
+      int32_t j = (p < n) ? irow[p] - kl.base : -1;
       ok[u] = static_cast<uint32_t>(j) < static_cast<uint32_t>(s.T);
       j = ok[u] ? j : 0;
       kv[u] = *reinterpret_cast<const uint4*>(Kh + static_cast<int64_t>(j) * kHeadDim + c8 * 8);
@@ -129,7 +161,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void sparse_attn_bf16_kernel
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void sparse_attn_f32_kernel(
     Shape s, const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
     const int32_t* __restrict__ idx, const int32_t* __restrict__ cnt, int32_t L,
-    float* __restrict__ O) {
+    const int64_t* __restrict__ crow, float* __restrict__ O) {
   const uint32_t lb = xcd_contiguous(blockIdx.x, gridDim.x);
   const int64_t row = static_cast<int64_t>(lb) * kWavesPerBlock + (threadIdx.x >> 6);
   const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
@@ -144,8 +176,9 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void sparse_attn_f32_kernel(
   const float4 q4 = *reinterpret_cast<const float4*>(Q + row * kHeadDim + c16 * 4);
   const double qd[4] = {q4.x, q4.y, q4.z, q4.w};
   const double f = static_cast<double>(s.scale) * 1.4426950408889634;
-  const int32_t n = min(cnt[row], L);
-  const int32_t* irow = idx + row * L;
+  const KeyList kl = key_list(s, row, idx, cnt, L, crow);
+  const int32_t n = kl.n;
+  const int32_t* irow = kl.p;
 
   double m_run = -INFINITY;
   float l_run = 0.f;
@@ -157,7 +190,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void sparse_attn_f32_kernel(
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const int32_t p = k0 + u * 4 + g;
-      int32_t j = (p < n) ? irow[p] : -1;
+      int32_t j = (p < n) ? irow[p] - kl.base : -1;
       ok[u] = static_cast<uint32_t>(j) < static_cast<uint32_t>(s.T);
       j = ok[u] ? j : 0;
       kv[u] = *reinterpret_cast<const float4*>(Kh + static_cast<int64_t>(j) * kHeadDim + c16 * 4);
@@ -214,18 +247,18 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void sparse_attn_f32_kernel(
 
 hipError_t launch_sparse_attn(const Shape& s, sea_dtype dt, const void* Q, const void* K,
                               const void* V, const int32_t* idx, const int32_t* cnt, int32_t L,
-                              void* O, hipStream_t st) {
+                              const int64_t* crow, void* O, hipStream_t st) {
   const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
   const uint32_t grid = static_cast<uint32_t>((nrows + kWavesPerBlock - 1) / kWavesPerBlock);
   StageScope scope(SEA_STAGE_SPARSE, st);
   if (dt == SEA_BF16) {
     hipLaunchKernelGGL(sparse_attn_bf16_kernel, dim3(grid), dim3(kWavesPerBlock * kWave), 0, st, s,
                        static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
-                       static_cast<const uint16_t*>(V), idx, cnt, L, static_cast<uint16_t*>(O));
+                       static_cast<const uint16_t*>(V), idx, cnt, L, crow, static_cast<uint16_t*>(O));
   } else {
     hipLaunchKernelGGL(sparse_attn_f32_kernel, dim3(grid), dim3(kWavesPerBlock * kWave), 0, st, s,
                        static_cast<const float*>(Q), static_cast<const float*>(K),
-                       static_cast<const float*>(V), idx, cnt, L, static_cast<float*>(O));
+                       static_cast<const float*>(V), idx, cnt, L, crow, static_cast<float*>(O));
   }
   return hipGetLastError();
 }

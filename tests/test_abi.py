@@ -79,6 +79,9 @@ def test_argument_validation_returns_codes_not_crashes(sea):
     assert lib.sea_forward(ctypes.byref(cp), None, None, None, None, None, None, None, None, None,
                            None, None, 0, None) == sea.SEA_EINVAL
     assert lib.sea_mask_attn(ctypes.byref(cp), None, None, None, None, None, None, 0, None) == sea.SEA_EINVAL
+    assert lib.sea_flatcsr(ctypes.byref(cp), None, None, 8, None, None, 0, None, 0, None) == sea.SEA_EINVAL
+    assert lib.sea_flatcsr_attn(ctypes.byref(cp), None, None, None, None, None, None, None) == sea.SEA_EINVAL
+    assert sea.sea_flatcsr_workspace_bytes(ok) >= 8
     odd = P(1, 2, 300, 64, 96, 17, 5).c()            # K does not divide T: no column-structured form
     assert lib.sea_mask_attn_workspace_bytes(ctypes.byref(odd)) == 0
     m48 = P(1, 1, 128, 64, 48, 16, 4).c()
@@ -89,6 +92,8 @@ def test_argument_validation_returns_codes_not_crashes(sea):
     assert lib.sea_estimate(ctypes.byref(cp), one, one, one, one, ctypes.c_void_p(8), 1 << 30, None) \
         == sea.SEA_EWORKSPACE
     assert lib.sea_mask_attn(ctypes.byref(odd), one, one, one, one, one, None, 0, None) == sea.SEA_ENOTSUP
+    assert lib.sea_flatcsr(ctypes.byref(cp), one, one, 8, one, one, 16, None, 0, None) == sea.SEA_EWORKSPACE
+    assert lib.sea_flatcsr(ctypes.byref(cp), one, one, 0, one, one, 16, one, 1 << 20, None) == sea.SEA_EINVAL
     one_col = P(1, 2, 1024, 64, 64, 32, 1, k_budget=16)      # rows bucketed by column need scratch
     assert sea.sea_mask_attn_workspace_bytes(one_col) > 0
     assert lib.sea_mask_attn(ctypes.byref(one_col.c()), one, one, one, one, one, None, 0, None) \

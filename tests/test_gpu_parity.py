@@ -454,6 +454,50 @@ def test_mask_attn_from_a_foreign_mask(sea, case):
     assert torch.equal(O2.cpu(), out["O"])
 
 
+@pytest.mark.parametrize("case", [(2, 3, 300, 17, 5, 0, True, "bf16", 0), (2, 4, 512, 32, 3, 12, True, "bf16", 1),
+                                  (1, 2, 130, 24, 24, 0, False, "f32", 0), (3, 5, 1030, 64, 2, 16, True, "f32", 1),
+                                  (1, 12, 2048, 128, 4, 64, True, "bf16", 1)])
+def test_flatcsr_tensor_and_attention(sea, case):
+    """The FlatCSR tensor built from the lists a forward pass wrote: row pointers and columns
+    bit-exact against the oracle's, attention read from the tensor equal to the oracle's and
+    bit-identical to the list kernel; a column array that is too small is never overrun."""
+    B, H, T, K, kh, kb, causal, dtype, grouping = case
+    wl = _wl("flatcsr", B, H, T, 32, K, kh, k_budget=kb, causal=causal, dtype=dtype, pad_frac=0.3,
+             grouping=grouping)
+    x = synth.make_inputs(wl)
+    p, xd, out = _gpu_forward(sea, wl, x)
+    idx, cnt = out["idx"].cuda(), out["cnt"].cuda()
+    L = sea.sea_row_stride(p)
+    po = oracle_params(wl)
+    crow_o, col_o = oracle.flatcsr(po, out["idx"].numpy(), out["cnt"].numpy())
+    nnz = int(crow_o[-1])
+    ws = torch.empty(max(256, sea.sea_flatcsr_workspace_bytes(p)), dtype=torch.uint8, device="cuda")
+    crow = torch.full((B * T + 1,), -7, dtype=torch.int64, device="cuda")
+    col = torch.full((nnz + 64,), -7, dtype=torch.int32, device="cuda")
+    print(f"[case] flatcsr B{B} H{H} T{T} K{K} kh{kh} kb{kb} grouping{grouping} {dtype} nnz{nnz}", flush=True)
+    sea.sea_flatcsr(p, idx, cnt, L, crow, col[:nnz], ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(crow.cpu().numpy(), crow_o)
+    assert np.array_equal(col[:nnz].cpu().numpy(), col_o)
+    assert (col[nnz:] == -7).all()
+    # too small: complete row pointers, nothing written past the capacity given
+    small = torch.full((nnz,), -7, dtype=torch.int32, device="cuda")
+    crow2 = torch.empty_like(crow)
+    sea.sea_flatcsr(p, idx, cnt, L, crow2, small[:nnz // 2], ws)
+    torch.cuda.synchronize()
+    assert torch.equal(crow2, crow)
+    assert np.array_equal(small[:nnz // 2].cpu().numpy(), col_o[:nnz // 2]) and (small[nnz // 2:] == -7).all()
+    # attention read from the tensor
+    O = torch.full((B, H, T, 64), float("nan"), dtype=p.torch_dtype, device="cuda")
+    sea.sea_flatcsr_attn(p, xd["Q"], xd["K"], xd["V"], crow, col, O)
+    O2 = torch.empty_like(O)
+    sea.sea_sparse_attn(p, xd["Q"], xd["K"], xd["V"], idx, cnt, L, O2)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O2)
+    want = oracle.flatcsr_attn(po, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), crow_o, col_o)
+    assert_close(to_np64(O), want, TOL[dtype], "O from FlatCSR")
+
+
 def test_mask_attn_rejects_unstructured_shapes(sea):
     wl = _wl("mask_attn_bad", 1, 2, 300, 64, 17, 5)
     p = _params(sea, wl)
