@@ -39,7 +39,7 @@ class _RefParams(ctypes.Structure):
                 ("d", ctypes.c_int32), ("m", ctypes.c_int32), ("K", ctypes.c_int32),
                 ("k_hat", ctypes.c_int32), ("k_budget", ctypes.c_int32),
                 ("causal", ctypes.c_int32), ("round8", ctypes.c_int32),
-                ("grouping", ctypes.c_int32), ("scale", ctypes.c_double)]
+                ("grouping", ctypes.c_int32), ("geometry", ctypes.c_int32), ("scale", ctypes.c_double)]
 
 
 @dataclass
@@ -56,11 +56,12 @@ class Params:
     scale: float = 0.125
     round8: bool = False  # True for the bf16 contract (rounding of phi(Q) and key state)
     grouping: int = 0     # 0 per-query top-k^, 1 causal-per-batch (H k^ per time step over all heads)
+    geometry: int = 0     # 0 fixed key buckets; 1 a causal row spreads its K columns over its own t + 1 keys
 
     def c(self) -> _RefParams:
         return _RefParams(self.B, self.H, self.T, self.d, self.m, self.K, self.k_hat,
                           self.k_budget, int(self.causal), int(self.round8), int(self.grouping),
-                          float(self.scale))
+                          int(self.geometry), float(self.scale))
 
 
 _lib = None

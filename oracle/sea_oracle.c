@@ -32,6 +32,11 @@
  *     stretch of I_K, so FAVOR+(Q,K,V_I) is itself a T x K matrix, normalised
  *     per row (linear-attention normaliser); causal rows only see keys j <= t;
  *   - key buckets are fixed: key j belongs to column floor(j K / T);
+ *     geometry = 1 is the other reading, App. A.4 (figure of the masking
+ *     process): a causal row t is resized to its own width, so its column c
+ *     holds the keys [ceil(c (t+1) / K), ceil((c+1)(t+1) / K)) -- the whole
+ *     method for that row is the bidirectional one on a sequence of t + 1 keys;
+ *     no reduced-precision rounding points apply in this geometry;
  *   - masked-out keys are excluded from the softmax (not given logit zero);
  *   - right padding: keys and rows >= seq_len[b] are inactive;
  *   - ties in the selection go to the lower column; a column with no admissible
@@ -62,6 +67,9 @@ typedef struct {
   int32_t causal;
   int32_t round8;   /* 1: apply the reduced-precision rounding points         */
   int32_t grouping; /* 0: per-query top-k^; 1: causal-per-batch (over heads)  */
+  int32_t geometry; /* 0: key j belongs to column floor(j K / T) for every row;
+                       1 (causal only): row t spreads its K columns over its own
+                       t + 1 keys, column floor(j K / (t + 1))               */
   double scale;     /* logits = scale * q.k                                   */
 } ref_params;
 
@@ -183,6 +191,18 @@ int ref_estimate(const ref_params* p, const double* Q, const double* K,
         }
         const int64_t ct = bucket_of(t, T, KK);
         double rowsum = 0.0;
+        if (p->geometry == 1) {
+          /* the row's own width: FAVOR+ with V_I the (t+1) x K stretch of the identity */
+          for (int64_t j = 0; j <= t; ++j) {
+            double dotp = 0.0;
+            for (int64_t i = 0; i < m; ++i) dotp += phiQ[i] * phiK[j * m + i];
+            Arow[bucket_of(j, t + 1, KK)] += dotp;
+            rowsum += dotp;
+          }
+          if (rowsum > 0.0)
+            for (int64_t c = 0; c < KK; ++c) Arow[c] /= rowsum;
+          continue;
+        }
         for (int64_t c = 0; c < KK; ++c) {
           double acc = 0.0;
           if (!p->causal || c < ct) {
@@ -214,8 +234,8 @@ int ref_estimate(const ref_params* p, const double* Q, const double* K,
 /* ---- a4-a5: grouped top-k^ and expansion to key positions ------------------ */
 /* expansion of the columns flagged in taken[0..ncand) of one row (App. A.5.3) */
 static void expand_row(const ref_params* p, const uint8_t* taken, int64_t ncand, int64_t jmax,
-                       int32_t* srow, int32_t* irow, int32_t* cnt_out) {
-  const int64_t T = p->T, KK = p->K;
+                       int64_t T, int32_t* srow, int32_t* irow, int32_t* cnt_out) {
+  const int64_t KK = p->K;  /* T: the width the row's columns are spread over */
   int64_t ns = 0, ni = 0;
   for (int64_t c = 0; c < ncand; ++c) {
     if (!taken[c]) continue;
@@ -248,31 +268,40 @@ int ref_topk_mask(const ref_params* p, const double* A_hat, const int32_t* seq_l
   if (!rows) n_rows = p->T;
   const int64_t L = ref_row_stride(p), S = ref_sel_stride(p);
   uint8_t* taken = (uint8_t*)malloc(H * KK);
-  if (!taken) return -1;
+  uint8_t* empty = (uint8_t*)malloc(KK);
+  if (!taken || !empty) return -1;
   for (int64_t b = 0; b < p->B; ++b) {
     const int64_t len = seq_len ? seq_len[b] : T;
     for (int32_t r = 0; r < n_rows; ++r) {
       const int64_t t = row_at(rows, r);
       /* last admissible key of this row and its candidate columns 0..ncand-1 */
       const int64_t jmax = (p->causal && t < len - 1) ? t : len - 1;
-      const int64_t ncand = t < len ? bucket_of(jmax, T, KK) + 1 : 0;
+      /* Tw: the width the row's K columns are spread over.  Columns 0..ncand-1 can hold an
+         admissible key; with the row's own width (Tw = t + 1 < K) some of them are empty */
+      const int64_t Tw = p->geometry == 1 ? t + 1 : T;
+      const int64_t ncand = t < len ? bucket_of(jmax, Tw, KK) + 1 : 0;
+      int64_t nfull = 0;
+      for (int64_t c = 0; c < ncand; ++c) {
+        empty[c] = block_start(c + 1, Tw, KK) <= block_start(c, Tw, KK);
+        nfull += !empty[c];
+      }
       memset(taken, 0, H * KK);
       if (p->grouping == 0) {
-        const int64_t n = p->k_hat < ncand ? p->k_hat : ncand;
+        const int64_t n = p->k_hat < nfull ? p->k_hat : nfull;
         for (int64_t h = 0; h < H; ++h) {
           const double* Arow = A_hat + ((b * H + h) * (int64_t)n_rows + r) * KK;
           /* n passes of "largest remaining, lowest column on ties" */
           for (int64_t s = 0; s < n; ++s) {
             int64_t best = -1;
             for (int64_t c = 0; c < ncand; ++c) {
-              if (taken[h * KK + c]) continue;
+              if (taken[h * KK + c] || empty[c]) continue;
               if (best < 0 || Arow[c] > Arow[best]) best = c;
             }
             taken[h * KK + best] = 1;
           }
         }
       } else {
-        const int64_t quota = H * p->k_hat, total = H * ncand;
+        const int64_t quota = H * p->k_hat, total = H * nfull;
         const int64_t n = quota < total ? quota : total;
         for (int64_t s = 0; s < n; ++s) {
           int64_t bh = -1, bc = -1;
@@ -280,7 +309,7 @@ int ref_topk_mask(const ref_params* p, const double* A_hat, const int32_t* seq_l
           for (int64_t h = 0; h < H; ++h) {
             const double* Arow = A_hat + ((b * H + h) * (int64_t)n_rows + r) * KK;
             for (int64_t c = 0; c < ncand; ++c) {
-              if (taken[h * KK + c]) continue;
+              if (taken[h * KK + c] || empty[c]) continue;
               if (bh < 0 || Arow[c] > bv) { bh = h; bc = c; bv = Arow[c]; }
             }
           }
@@ -295,11 +324,11 @@ int ref_topk_mask(const ref_params* p, const double* A_hat, const int32_t* seq_l
         if (srow) for (int64_t x = 0; x < S; ++x) srow[x] = -1;
         cnt[row] = 0;
         if (t >= len) continue;
-        expand_row(p, taken + h * KK, ncand, jmax, srow, irow, &cnt[row]);
+        expand_row(p, taken + h * KK, ncand, jmax, Tw, srow, irow, &cnt[row]);
       }
     }
   }
-  free(taken);
+  free(taken); free(empty);
   return 0;
 }
 

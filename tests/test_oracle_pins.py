@@ -636,3 +636,100 @@ def test_flatcsr_hand_enumerated():
     crow, col = oracle.flatcsr(p, idx, cnt)
     assert crow.tolist() == [0, 2, 4, 6, 10]
     assert col.tolist() == [0, 4, 0, 1, 6, 7, 2, 3, 4, 5]
+
+
+# ----------------------------------------------------------------------------------------------
+# per-row width geometry (App. A.4, figure of the masking process: a causal row is resized to
+# its own width t + 1)
+# ----------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("kb", [0, 6])
+def test_row_width_row_equals_bidirectional_run_on_the_prefix(kb):
+    """Row t of the per-row-width geometry is the last row of the bidirectional method (fixed
+    buckets, already pinned above) run on the first t + 1 positions only: same A_hat row, same
+    columns, same keys, same output.  Checked for every t with t + 1 >= K."""
+    B, H, T, d, m, Kc, kh = 1, 2, 45, 8, 16, 6, 2
+    Q, K, V = _rand_qkv(B, H, T, d, seed=14)
+    W = synth.gaussian_orthogonal(m, d, 0).numpy()
+    p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=Kc, k_hat=kh, k_budget=kb, causal=True, scale=0.4,
+                      geometry=1)
+    a = oracle.forward(p, Q, K, V, W)
+    for t in range(Kc - 1, T):
+        n = t + 1
+        q = oracle.Params(B=B, H=H, T=n, d=d, m=m, K=Kc, k_hat=kh, k_budget=kb, causal=False, scale=0.4)
+        b = oracle.forward(q, Q[:, :, :n], K[:, :, :n], V[:, :, :n], W, rows=[t])
+        np.testing.assert_allclose(a["A_hat"][:, :, t], b["A_hat"][:, :, 0], rtol=1e-11, atol=1e-15)
+        assert np.array_equal(a["sel"][:, :, t], b["sel"][:, :, 0]), t
+        c = b["cnt"][:, :, 0]
+        assert np.array_equal(a["cnt"][:, :, t], c), t
+        L = b["idx"].shape[-1]
+        assert np.array_equal(a["idx"][:, :, t, :L], b["idx"][:, :, 0]), t
+        assert (a["idx"][:, :, t, L:] == -1).all()
+        np.testing.assert_allclose(a["O"][:, :, t], b["O"][:, :, 0], rtol=1e-11, atol=1e-14)
+
+
+def test_row_width_mask_is_the_library_resize_of_each_row():
+    """k_budget = 0: row t of M* is the nearest-neighbour resize of row t of M^ (K wide) to t + 1
+    pixels, also when t + 1 < K (columns without a pixel are never selected).  The library resize
+    is used where its float index arithmetic agrees with floor(j K / (t + 1)); the exact integer
+    gather is checked everywhere."""
+    T, Kc, kh = 40, 8, 3
+    g = np.random.default_rng(5)
+    p = oracle.Params(B=1, H=1, T=T, d=4, m=4, K=Kc, k_hat=kh, causal=True, geometry=1)
+    A = g.random((1, 1, T, Kc))
+    sel, idx, cnt = oracle.topk_mask(p, A)
+    lib_checked = 0
+    for t in range(T):
+        n = t + 1
+        src = (np.arange(n) * Kc) // n
+        s = sel[0, 0, t][sel[0, 0, t] >= 0]
+        assert len(s) == min(kh, n, Kc)
+        assert set(s) <= set(src)                                    # only columns holding a key
+        # the selected ones are the largest among the columns that hold a key
+        live = np.unique(src)
+        order = live[np.argsort(-A[0, 0, t, live], kind="stable")][:len(s)]
+        assert sorted(order) == s.tolist()
+        Mhat = np.zeros(Kc, dtype=np.float32)
+        Mhat[s] = 1.0
+        want = Mhat[src]
+        got = np.zeros(n, dtype=np.float32)
+        got[idx[0, 0, t, :cnt[0, 0, t]]] = 1.0
+        assert np.array_equal(got, want), t
+        lib = torch.nn.functional.interpolate(torch.from_numpy(Mhat)[None, None], size=n,
+                                              mode="nearest")[0, 0].numpy()
+        lib_src = torch.nn.functional.interpolate(torch.arange(Kc, dtype=torch.float32)[None, None], size=n,
+                                                  mode="nearest")[0, 0].numpy().astype(np.int64)
+        if np.array_equal(lib_src, src):
+            assert np.array_equal(lib, got), t
+            lib_checked += 1
+    assert lib_checked >= T // 2
+
+
+def test_row_width_last_row_is_the_fixed_bucket_row_and_rows_are_causal():
+    B, H, T, d, m, Kc, kh = 2, 2, 48, 8, 16, 8, 3
+    Q, K, V = _rand_qkv(B, H, T, d, seed=15)
+    W = synth.gaussian_orthogonal(m, d, 0).numpy()
+    sl = np.array([T, 31], dtype=np.int32)
+    p1 = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=Kc, k_hat=kh, causal=True, scale=0.3, geometry=1)
+    p0 = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=Kc, k_hat=kh, causal=True, scale=0.3, geometry=0)
+    a = oracle.forward(p1, Q, K, V, W, seq_len=sl)
+    f = oracle.forward(p0, Q, K, V, W, seq_len=sl)
+    # t + 1 = T: both geometries put key j in column floor(j K / T)
+    np.testing.assert_allclose(a["A_hat"][0, :, T - 1], f["A_hat"][0, :, T - 1], rtol=1e-11)
+    assert np.array_equal(a["idx"][0, :, T - 1], f["idx"][0, :, T - 1])
+    np.testing.assert_allclose(a["A_hat"].sum(-1)[a["cnt"] > 0], 1.0, rtol=1e-12)
+    assert (a["cnt"][1, :, 31:] == 0).all() and (a["O"][1, :, 31:] == 0).all()
+    for t in range(T):
+        assert (a["idx"][:, :, t] <= t).all()
+    # every row with at least K keys spreads its selection over its whole prefix: unlike the
+    # fixed buckets, early rows are not dense
+    assert a["cnt"][0, 0, 20] == kh * (21 // Kc) or a["cnt"][0, 0, 20] <= kh * (21 // Kc + 1)
+    # causality, bit for bit
+    t0 = 25
+    g = np.random.default_rng(1)
+    Q2, K2, V2 = Q.copy(), K.copy(), V.copy()
+    for X in (Q2, K2, V2):
+        X[:, :, t0 + 1:] = g.standard_normal(X[:, :, t0 + 1:].shape) * 3
+    b = oracle.forward(p1, Q2, K2, V2, W, seq_len=sl)
+    for key in ("O", "A_hat", "sel", "idx", "cnt"):
+        assert np.array_equal(a[key][:, :, :t0 + 1], b[key][:, :, :t0 + 1]), key
