@@ -34,6 +34,9 @@ def parse():
                     help="c1..c5 or c4_T<len>; c2 is the configuration the metric is quoted on")
     ap.add_argument("--grouping", choices=["per_query", "causal_per_batch"], default="per_query",
                     help="top-k^ grouping (Sec. 3.1); the headline metric uses per_query")
+    ap.add_argument("--geometry", choices=["fixed", "row_width"], default="fixed",
+                    help="how the K columns map to keys: the same key buckets for every row (headline), or "
+                         "each causal row resized to its own t + 1 keys (App. A.4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU-work budget of the oracle sample")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
@@ -52,8 +55,8 @@ def cpu_baseline(wl, x, budget_s):
     f64 = lambda t: t.to(torch.float64).numpy()
     nheads = wl.B * wl.H
     p = oracle.Params(B=wl.B, H=wl.H, T=wl.T, d=wl.d, m=wl.m, K=wl.K, k_hat=wl.k_hat,
-                      k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale, round8=wl.dtype == "bf16",
-                      grouping=wl.grouping)
+                      k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale,
+                      round8=wl.dtype == "bf16" and wl.geometry == 0, grouping=wl.grouping, geometry=wl.geometry)
     Q, K, V, W = f64(x["Q"]), f64(x["K"]), f64(x["V"]), f64(x["W"])
     sl = None if x["seq_len"] is None else x["seq_len"].numpy()
     t0 = time.perf_counter()
@@ -122,12 +125,15 @@ def main():
     if args.grouping == "causal_per_batch":
         import dataclasses
         wl = dataclasses.replace(wl, name=wl.name + "+causal_per_batch", grouping=1)
+    if args.geometry == "row_width":
+        import dataclasses
+        wl = dataclasses.replace(wl, name=wl.name + "+row_width", geometry=1)
     x = synth.make_inputs(wl)
     d = {k: x[k].to(dev) for k in "QKVW"}
     sl = None if x["seq_len"] is None else x["seq_len"].to(dev)
     p = sea.SeaParams(B=wl.B, H=wl.H, T=wl.T, d=wl.d, m=wl.m, K=wl.K, k_hat=wl.k_hat,
                       k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale, dtype=wl.dtype, seq_len=sl,
-                      grouping=wl.grouping)
+                      grouping=wl.grouping, geometry=wl.geometry)
     ws = sea.alloc_workspace(p, dev)
     O = torch.empty_like(d["Q"])
     L = sea.sea_row_stride(p)

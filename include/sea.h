@@ -68,6 +68,15 @@ typedef struct {
                           head keeps k_hat entries); 1 = causal-per-batch (A_hat viewed as
                           [T][H K]: each time step keeps H k_hat entries of its H x K slab, so
                           heads share the quota; needs H K <= 16384)                         */
+  int32_t geometry;    /* how the K columns map to keys.  0: key j belongs to column
+                          floor(j K / T) for every row.  1 (causal only; App. A.4, figure of
+                          the masking process): row t is resized to its own width, its column
+                          c holds the keys [ceil(c (t+1) / K), ceil((c+1)(t+1) / K)) -- the
+                          estimate, the selection (columns without a key are no candidates)
+                          and the expansion of row t are those of a sequence of t + 1 keys.
+                          Needs grouping = 0 and m in {64, 128, 256}; the estimate then runs
+                          on fp32 features (fp64 for SEA_F32) from a running key state, and
+                          the attention stage works from per-row key lists                */
 } sea_params;
 
 /* k^ = max(1, round(k K / T)), halves rounded up (Sec. 3.1 "Linear Sparse Attention Mask
@@ -242,8 +251,8 @@ int sea_last_hip_error(void);
 /*
  * Which kernel sea_forward's sparse attention stage (Sec. 3.1.1) runs for these parameters:
  * 1 = the tiled matrix-core kernel over the column-structured mask (bf16, K | T, a power-of-two
- * number of keys per selected column), 0 = the per-row index-list kernel.  Negative: the status
- * code the parameters would be rejected with, negated.  Pure host computation.
+ * number of keys per selected column, fixed key buckets), 0 = the per-row index-list kernel.
+ * Negative: the sea_status the parameters would be rejected with.  Pure host computation.
  */
 int sea_attention_path(const sea_params* p);
 

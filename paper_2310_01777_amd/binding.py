@@ -28,7 +28,7 @@ class SeaParamsC(ctypes.Structure):
                 ("k_hat", ctypes.c_int32), ("k_budget", ctypes.c_int32),
                 ("causal", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("dtype", ctypes.c_int32), ("seq_len", ctypes.c_void_p),
-                ("grouping", ctypes.c_int32)]
+                ("grouping", ctypes.c_int32), ("geometry", ctypes.c_int32)]
 
 
 class SeaError(RuntimeError):
@@ -95,6 +95,7 @@ class SeaParams:
     dtype: str = "bf16"
     seq_len: Optional[torch.Tensor] = None
     grouping: int = 0   # 0 per-query top-k^, 1 causal-per-batch
+    geometry: int = 0   # 0 fixed key buckets, 1 a causal row spreads its columns over its own t + 1 keys
 
     def c(self) -> SeaParamsC:
         sl = None
@@ -104,7 +105,7 @@ class SeaParams:
             sl = t.data_ptr()
         return SeaParamsC(self.B, self.H, self.T, self.d, self.m, self.K, self.k_hat, self.k_budget,
                           int(self.causal), float(self.scale), SEA_BF16 if self.dtype == "bf16" else SEA_F32,
-                          sl, int(self.grouping))
+                          sl, int(self.grouping), int(self.geometry))
 
     @property
     def torch_dtype(self) -> torch.dtype:

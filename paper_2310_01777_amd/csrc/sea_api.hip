@@ -54,12 +54,16 @@ int check_mask_params(const sea_params* p) {
   if (p->grouping != 0 && p->grouping != 1) return SEA_EINVAL;
   if (p->K > 1024) return SEA_ENOTSUP;
   if (p->grouping == 1 && static_cast<int64_t>(p->H) * p->K > 16384) return SEA_ENOTSUP;
+  if (p->geometry != 0 && p->geometry != 1) return SEA_EINVAL;
+  if (p->geometry == 1 && !p->causal) return SEA_EINVAL;  // the row's own width is a causal notion
+  if (p->geometry == 1 && p->grouping == 1) return SEA_ENOTSUP;
   return SEA_OK;
 }
 
 int check_estimate_params(const sea_params* p) {
   if (p->m <= 0) return SEA_EINVAL;
   if (p->m % 32 != 0 || p->m > 1024) return SEA_ENOTSUP;
+  if (p->geometry == 1 && p->m != 64 && p->m != 128 && p->m != 256) return SEA_ENOTSUP;
   return SEA_OK;
 }
 
@@ -92,6 +96,7 @@ Shape make_shape(const sea_params* p, bool with_mask) {
   s.k_hat = p->k_hat;
   s.causal = p->causal ? 1 : 0;
   s.grouping = p->grouping;
+  s.geometry = p->geometry;
   s.sel_stride = sel_stride_of(p);
   s.scale = p->scale;
   s.seq_len = p->seq_len;
@@ -106,6 +111,7 @@ size_t align256(size_t x) { return (x + 255) & ~size_t(255); }
 
 size_t estimate_ws(const sea_params* p) {
   const Shape s = make_shape(p, false);
+  if (s.geometry == 1) return align256(estimate_rowwidth_workspace(s, p->dtype));
   return align256(p->dtype == SEA_BF16 ? estimate_bf16_workspace(s) : estimate_f64_workspace(s));
 }
 
@@ -184,7 +190,9 @@ int sea_estimate(const sea_params* p, const void* Q, const void* K, const void* 
   const Shape s = make_shape(p, true);
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   hipError_t e;
-  if (p->dtype == SEA_BF16)
+  if (s.geometry == 1)
+    e = launch_estimate_rowwidth(s, p->dtype, Q, K, W, A_hat, workspace, st);
+  else if (p->dtype == SEA_BF16)
     e = launch_estimate_bf16(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
                              static_cast<const uint16_t*>(W), A_hat, workspace, st);
   else
@@ -321,7 +329,9 @@ int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V
                          static_cast<const uint16_t*>(V), mbits, static_cast<uint16_t*>(O), w, st);
     return e == hipSuccess ? SEA_OK : fail_hip(e);
   }
-  if (p->dtype == SEA_BF16)
+  if (s.geometry == 1)
+    e = launch_estimate_rowwidth(s, p->dtype, Q, K, W, A_hat, est_ws, st);
+  else if (p->dtype == SEA_BF16)
     e = launch_estimate_bf16(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
                              static_cast<const uint16_t*>(W), A_hat, est_ws, st);
   else
@@ -421,7 +431,7 @@ int sea_last_hip_error(void) { return g_last_hip_error; }
 int sea_attention_path(const sea_params* p) {
   int rc = check_common(p);
   if (rc == SEA_OK) rc = check_mask_params(p);
-  if (rc != SEA_OK) return -rc;
+  if (rc != SEA_OK) return rc;
   return tile_attn_supported(make_shape(p, true), p->dtype, nullptr) ? 1 : 0;
 }
 

@@ -24,6 +24,7 @@ struct Shape {
   int32_t causal;
   int32_t grouping;    // 0 per-query top-k^, 1 causal-per-batch
   int32_t sel_stride;  // columns one row can select: k_hat, or min(K, H k_hat) when grouped
+  int32_t geometry;    // 0 fixed key buckets, 1 a causal row spreads its K columns over its own t + 1 keys
   float scale;
   const int32_t* seq_len;  // device [B] or nullptr
 };
@@ -43,6 +44,12 @@ size_t estimate_fused_workspace(const Shape& s);
 // nullptr; at least one should be given
 hipError_t launch_estimate_fused(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W,
                                  float* A_hat, uint32_t* mbits, void* ws, hipStream_t st);
+
+// per-row width geometry (causal, m in {64,128,256}): prefix table of phi(K), K + 1 gathered dot products per row
+bool estimate_rowwidth_supported(const Shape& s);
+size_t estimate_rowwidth_workspace(const Shape& s, sea_dtype dt);
+hipError_t launch_estimate_rowwidth(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* W,
+                                    float* A_hat, void* ws, hipStream_t st);
 
 // sel, idx, cnt, mbits may each be nullptr; mbits is [N][T][ceil(K/32)] selected-column bits
 hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, int32_t* idx,

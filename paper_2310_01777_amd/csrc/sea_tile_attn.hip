@@ -596,6 +596,7 @@ int32_t group_heads_for(int32_t N, int64_t U) {
 
 bool tile_attn_supported(const Shape& s, sea_dtype dt, int32_t* rlog_out) {
   if (dt != SEA_BF16 || s.T % s.K != 0) return false;
+  if (s.geometry != 0) return false;  // a row's own column ranges: no structure shared between rows
   const int32_t w = s.T / s.K;
   const int32_t r = w < s.rep_cap ? w : s.rep_cap;
   if (r <= 0 || (r & (r - 1)) != 0) return false;

@@ -25,7 +25,9 @@ __device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
   return __popcll(mask & ((1ull << lane) - 1ull));
 }
 
-template <int SLOTS>
+// ROWW: per-row width geometry -- a causal row t spreads its K columns over its own t + 1 keys
+// (column c = keys [ceil(c (t+1) / K), ceil((c+1)(t+1) / K)); empty columns are no candidates).
+template <int SLOTS, bool ROWW>
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
     Shape s, const float* __restrict__ A_hat, int32_t* __restrict__ sel, int32_t* __restrict__ idx,
     int32_t* __restrict__ cnt, uint32_t* __restrict__ mbits) {
@@ -55,14 +57,17 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
     return;
   }
   const int32_t jmax = (s.causal && t < len - 1) ? t : len - 1;  // last admissible key
-  const int32_t ncand = bucket_of(jmax, s.T, s.K) + 1;           // candidate columns 0..ncand-1
-  const int32_t n = min(s.k_hat, ncand);
+  const int32_t Tw = ROWW ? t + 1 : s.T;                         // width the K columns are spread over
+  const int32_t ncand = bucket_of(jmax, Tw, s.K) + 1;            // candidate columns 0..ncand-1
+  const int32_t n = min(s.k_hat, ROWW ? min(s.K, Tw) : ncand);   // ROWW: min(K, t + 1) columns hold a key
 
   uint32_t key[SLOTS];
 #pragma unroll
   for (int q = 0; q < SLOTS; ++q) {
     const int32_t c = q * kWave + lane;
-    key[q] = (c < ncand) ? ordered_key(A_hat[row * s.K + c]) : 0u;  // c < ncand <= K
+    bool cand = c < ncand;  // c < ncand <= K
+    if (ROWW) cand = cand && block_start(c + 1, Tw, s.K) > block_start(c, Tw, s.K);
+    key[q] = cand ? ordered_key(A_hat[row * s.K + c]) : 0u;
   }
   // largest tau with #{key >= tau} >= n  ==  the n-th largest key
   uint32_t tau = 0;
@@ -102,7 +107,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
 
   if (!irow && !cnt) return;
   // expansion: selected column c emits r keys start + floor(i w / r), i < r
-  const bool uniform = (s.T % s.K) == 0;
+  const bool uniform = !ROWW && (s.T % s.K) == 0;
   int32_t total;
   if (uniform) {
     const int32_t w = s.T / s.K;
@@ -129,7 +134,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
       for (int32_t si = 0; si < n_sel; ++si) {
         sh_off[wid][si] = acc;
         const int32_t c = sh_sel[wid][si];
-        const int32_t w = block_start(c + 1, s.T, s.K) - block_start(c, s.T, s.K);
+        const int32_t w = block_start(c + 1, Tw, s.K) - block_start(c, Tw, s.K);
         acc += min(w, s.rep_cap);
       }
       sh_off[wid][n_sel] = acc;
@@ -141,8 +146,8 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
     int32_t kept = 0;
     for (int32_t si = 0; si < n_sel; ++si) {
       const int32_t c = sh_sel[wid][si];
-      const int32_t s0 = block_start(c, s.T, s.K);
-      const int32_t w = block_start(c + 1, s.T, s.K) - s0;
+      const int32_t s0 = block_start(c, Tw, s.K);
+      const int32_t w = block_start(c + 1, Tw, s.K) - s0;
       const int32_t r = min(w, s.rep_cap);
       const int32_t off = sh_off[wid][si];
       for (int32_t i = lane; i < r; i += kWave) {
@@ -436,11 +441,19 @@ hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, in
     else return hipErrorNotSupported;
     return hipGetLastError();
   }
-  if (slots <= 1) hipLaunchKernelGGL(topk_mask_kernel<1>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);
-  else if (slots <= 2) hipLaunchKernelGGL(topk_mask_kernel<2>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);
-  else if (slots <= 4) hipLaunchKernelGGL(topk_mask_kernel<4>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);
-  else if (slots <= 8) hipLaunchKernelGGL(topk_mask_kernel<8>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);
-  else hipLaunchKernelGGL(topk_mask_kernel<16>, dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);
+#define SEA_TOPK(SL)                                                                                               \
+  do {                                                                                                             \
+    if (s.geometry == 1)                                                                                           \
+      hipLaunchKernelGGL((topk_mask_kernel<SL, true>), dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);  \
+    else                                                                                                           \
+      hipLaunchKernelGGL((topk_mask_kernel<SL, false>), dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits); \
+  } while (0)
+  if (slots <= 1) SEA_TOPK(1);
+  else if (slots <= 2) SEA_TOPK(2);
+  else if (slots <= 4) SEA_TOPK(4);
+  else if (slots <= 8) SEA_TOPK(8);
+  else SEA_TOPK(16);
+#undef SEA_TOPK
   return hipGetLastError();
 }
 

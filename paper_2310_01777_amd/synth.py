@@ -33,6 +33,7 @@ class Workload:
     seed: int = 1234
     w_seed: int = 0
     grouping: int = 0      # 0 per-query top-k^, 1 causal-per-batch (Sec. 3.1)
+    geometry: int = 0      # 0 fixed key buckets, 1 a causal row resized to its own width (App. A.4)
 
     @property
     def scale(self) -> float:

@@ -24,15 +24,15 @@ def sea():
 
 
 def _wl(name, B, H, T, m, K, k_hat, k_budget=0, causal=True, dtype="bf16", centroids=4,
-        pad_frac=0.0, seed=1234, grouping=0):
+        pad_frac=0.0, seed=1234, grouping=0, geometry=0):
     return synth.Workload(name, B, H, T, 64, m, K, k_hat, k_budget, causal, dtype, centroids,
-                          pad_frac, seed, grouping=grouping)
+                          pad_frac, seed, grouping=grouping, geometry=geometry)
 
 
 def _params(sea, wl, seq_len_dev=None):
     return sea.SeaParams(B=wl.B, H=wl.H, T=wl.T, d=wl.d, m=wl.m, K=wl.K, k_hat=wl.k_hat,
                          k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale, dtype=wl.dtype,
-                         seq_len=seq_len_dev, grouping=wl.grouping)
+                         seq_len=seq_len_dev, grouping=wl.grouping, geometry=wl.geometry)
 
 
 def _dev(x):
@@ -452,6 +452,60 @@ def test_mask_attn_from_a_foreign_mask(sea, case):
     sea.sea_mask_attn(p, xd["Q"], xd["K"], xd["V"], out["mhat"].cuda(), O2, ws)
     torch.cuda.synchronize()
     assert torch.equal(O2.cpu(), out["O"])
+
+
+ROW_WIDTH_CASES = [
+    _wl("rw_bf16", 2, 3, 300, 64, 16, 3, geometry=1),
+    _wl("rw_bf16_budget_pad", 2, 2, 520, 128, 32, 4, k_budget=16, pad_frac=0.3, geometry=1),
+    _wl("rw_f32", 1, 2, 200, 64, 24, 5, dtype="f32", geometry=1),
+    _wl("rw_f32_m256", 1, 1, 150, 256, 10, 2, dtype="f32", pad_frac=0.2, geometry=1),
+    _wl("rw_bf16_three_slots", 1, 2, 777, 256, 192, 8, geometry=1),
+    _wl("rw_bf16_one_column", 1, 2, 256, 64, 8, 1, k_budget=4, geometry=1),
+    _wl("rw_bf16_long", 1, 1, 8192, 128, 128, 4, k_budget=32, geometry=1),
+]
+
+
+@pytest.mark.parametrize("wl", ROW_WIDTH_CASES, ids=lambda w: w.name)
+def test_row_width_geometry(sea, wl):
+    """App. A.4: a causal row resized to its own width t + 1.  Estimate within tolerance, the
+    selection and expansion bit-exact on the GPU's own scores (rows shorter than K included),
+    attention within tolerance, end to end identical lists except at near-ties."""
+    x = synth.make_inputs(wl)
+    p, xd, g = _gpu_forward(sea, wl, x)
+    assert sea.sea_attention_path(p) == 0
+    rows = None if wl.T <= 1024 else sorted(set(range(0, 140)) | set(range(wl.T - 40, wl.T))
+                                            | set(range(1000, wl.T, 97)))
+    po = oracle_params(wl)
+    sl = None if x["seq_len"] is None else x["seq_len"].numpy()
+    o = oracle.forward(po, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), to_np64(x["W"]),
+                       seq_len=sl, rows=rows)
+    pick = slice(None) if rows is None else rows
+    tol = TOL[wl.dtype]
+    A_g = g["A_hat"].numpy().astype(np.float64)[:, :, pick]
+    assert (A_g >= 0).all()
+    assert_close(A_g, o["A_hat"], tol, "A_hat")
+    np.testing.assert_allclose(A_g.sum(-1)[o["cnt"] > 0], 1.0, atol=1e-5)
+    sel_s, idx_s, cnt_s = oracle.topk_mask(po, A_g, seq_len=sl, rows=rows)
+    gs, gi, gc = (g[k].numpy()[:, :, pick] for k in ("sel", "idx", "cnt"))
+    assert np.array_equal(gs, sel_s)
+    assert np.array_equal(gi, idx_s)
+    assert np.array_equal(gc, cnt_s)
+    O_g = to_np64(g["O"])[:, :, pick]
+    O_s = oracle.sparse_attn(po, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), idx_s, cnt_s, rows=rows)
+    assert_close(O_g, O_s, tol, "O (stage)")
+    same = (gs == o["sel"]).all(-1)
+    for b, h, r in zip(*np.nonzero(~same)):
+        a = o["A_hat"][b, h, r]
+        mine, theirs = set(gs[b, h, r]) - {-1}, set(o["sel"][b, h, r]) - {-1}
+        lo, hi = min(a[c] for c in theirs), max(a[c] for c in mine - theirs)
+        assert (lo - hi) / lo < GAP[wl.dtype], (b, h, r, lo, hi)
+    assert (~same).mean() <= 0.02
+    assert np.array_equal(gi[same], o["idx"][same]) and np.array_equal(gc[same], o["cnt"][same])
+    Og, Oo = O_g.copy(), o["O"].copy()
+    Og[~same] = 0.0
+    Oo[~same] = 0.0
+    assert_close(Og, Oo, tol, "O (end to end)")
+    print(f"    rows differing at near-ties: {(~same).sum()} / {same.size}", flush=True)
 
 
 @pytest.mark.parametrize("case", [(2, 3, 300, 17, 5, 0, True, "bf16", 0), (2, 4, 512, 32, 3, 12, True, "bf16", 1),

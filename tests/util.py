@@ -21,10 +21,12 @@ def to_np64(t: torch.Tensor) -> np.ndarray:
 
 def oracle_params(wl_or_p, round8=None) -> oracle.Params:
     p = wl_or_p
-    r8 = (p.dtype == "bf16") if round8 is None else round8
+    geometry = int(getattr(p, "geometry", 0))
+    # the per-row width geometry has no reduced-precision rounding points
+    r8 = (p.dtype == "bf16" and geometry == 0) if round8 is None else round8
     return oracle.Params(B=p.B, H=p.H, T=p.T, d=p.d, m=p.m, K=p.K, k_hat=p.k_hat,
                          k_budget=p.k_budget, causal=bool(p.causal), scale=float(p.scale), round8=r8,
-                         grouping=int(getattr(p, "grouping", 0)))
+                         grouping=int(getattr(p, "grouping", 0)), geometry=geometry)
 
 
 def rel_errors(got: np.ndarray, ref: np.ndarray):
@@ -69,7 +71,7 @@ def selection_gaps(A_ref: np.ndarray, sel_ref: np.ndarray, ncand: np.ndarray) ->
 
 
 def candidate_counts(B, H, T, K, causal, seq_len, rows=None) -> np.ndarray:
-    """Number of candidate columns per row (0 for inactive rows)."""
+    """Number of candidate columns per row (0 for inactive rows); fixed key buckets."""
     rows = np.arange(T) if rows is None else np.asarray(rows)
     out = np.zeros((B, H, len(rows)), dtype=np.int64)
     for b in range(B):
