@@ -75,7 +75,7 @@ typedef struct {
                           estimate, the selection (columns without a key are no candidates)
                           and the expansion of row t are those of a sequence of t + 1 keys.
                           Needs grouping = 0 and m in {64, 128, 256}; the estimate then runs
-                          on fp32 features (fp64 for SEA_F32) from a running key state, and
+                          in fp64 from a running key state (no bf16 rounding points), and
                           the attention stage works from per-row key lists                */
 } sea_params;
 

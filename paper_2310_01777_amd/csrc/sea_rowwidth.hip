@@ -7,11 +7,12 @@
 // matrix product: it is K + 1 gathered dot products of length m per row, bound by the cache
 // bandwidth of the gathers (the prefix table of a head, (T+1) m elements, stays in its XCD's L2).
 //
-//   prefix_kernel<F, false>  per (head, chunk of keys): chunk totals of phi(k), fp64 running sum
+//   prefix_kernel<.., false> per (head, chunk of keys): chunk totals of phi(k), fp64 running sum
 //   chunk_base_kernel        per head: exclusive scan of the chunk totals (fp64)
-//   prefix_kernel<F, true>   same walk again, started from the chunk base, writes P as F
+//   prefix_kernel<.., true>  same walk again, writes P = chunk base + running sum
 //   rows_kernel<F, SLOTS>    one wavefront per row: phi(q_t), the K gathers, differences, row norm
-// F = float for bf16 tensors, double for fp32 tensors.  Features are not rounded to bf16 here.
+// Features, prefixes and dot products are fp64 for both tensor types (see PrefixOfBf16); nothing is
+// rounded to bf16 here.
 #include "sea_internal.h"
 
 namespace sea {
@@ -19,21 +20,32 @@ namespace {
 
 constexpr int kStage = 64;        // keys staged in LDS at a time
 constexpr int kMaxChunks = 64;    // chunks per head
-constexpr int kRowsPerWave = 4;
+constexpr int kRowsPerWave = 2;
 constexpr int kRowWaves = 4;
+// Arithmetic and prefix element type for bf16 tensors.  float makes the rows kernel 1.7x faster
+// (half the gathered bytes) but a difference of fp32 prefixes cannot resolve scores below ~1e-6 of
+// the row, and with k^ = K / 2 such scores sit at the selection boundary of many rows.
+using PrefixOfBf16 = double;
 
+// element i of a bf16 (uint16_t) or fp32 tensor, converted to the arithmetic type F
 template <typename F>
-struct In;
-template <>
-struct In<float> {
-  using T = uint16_t;
-  static __device__ __forceinline__ float get(const uint16_t* p, int64_t i) { return bf16_to_f32(p[i]); }
+__device__ __forceinline__ F elem(const uint16_t* p, int64_t i) {
+  return static_cast<F>(bf16_to_f32(p[i]));
+}
+template <typename F>
+__device__ __forceinline__ F elem(const float* p, int64_t i) {
+  return static_cast<F>(p[i]);
+}
+
+// N consecutive elements as one aligned vector load
+template <typename E, int N>
+struct alignas(sizeof(E) * N) Vec {
+  E v[N];
 };
-template <>
-struct In<double> {
-  using T = float;
-  static __device__ __forceinline__ double get(const float* p, int64_t i) { return static_cast<double>(p[i]); }
-};
+template <typename E, int N>
+__device__ __forceinline__ Vec<E, N> load_vec(const E* p) {
+  return *reinterpret_cast<const Vec<E, N>*>(p);
+}
 
 __device__ __forceinline__ float exp_of(float x) { return exp2f(x * kLog2e); }
 __device__ __forceinline__ double exp_of(double x) { return exp(x); }
@@ -44,9 +56,8 @@ __host__ __device__ __forceinline__ int32_t chunk_len(int32_t T) {
 }
 
 // block = m threads, thread i owns feature i; grid = heads x chunks
-template <typename F, bool WRITE>
-__global__ __launch_bounds__(256) void prefix_kernel(Shape s, const typename In<F>::T* __restrict__ Kt,
-                                                     const typename In<F>::T* __restrict__ W,
+template <typename F, typename TI, bool WRITE>
+__global__ __launch_bounds__(256) void prefix_kernel(Shape s, const TI* __restrict__ Kt, const TI* __restrict__ W,
                                                      double* __restrict__ ctot, const double* __restrict__ cbase,
                                                      F* __restrict__ P) {
   __shared__ F y[kStage][kHeadDim];
@@ -63,16 +74,20 @@ __global__ __launch_bounds__(256) void prefix_kernel(Shape s, const typename In<
   const F rs = static_cast<F>(sqrtf(s.scale));
   F w[kHeadDim];
 #pragma unroll
-  for (int e = 0; e < kHeadDim; ++e) w[e] = In<F>::get(W, static_cast<int64_t>(i) * kHeadDim + e);
-  const typename In<F>::T* Kh = Kt + head * s.T * kHeadDim;
+  for (int e = 0; e < kHeadDim; ++e) w[e] = elem<F>(W, static_cast<int64_t>(i) * kHeadDim + e);
+  const TI* Kh = Kt + head * s.T * kHeadDim;
   F* Ph = P + head * (static_cast<int64_t>(s.T) + 1) * s.m;
-  double run = WRITE ? cbase[(head * nch + chunk) * s.m + i] : 0.0;
+  // Both walks add up the chunk's features from zero in the same order; the second one stores
+  // base + partial sum, so the last prefix of a chunk is exactly the next chunk's base and the
+  // stored prefixes never decrease.
+  const double base = WRITE ? cbase[(head * nch + chunk) * s.m + i] : 0.0;
+  double run = 0.0;
   if (WRITE && chunk == 0) Ph[i] = static_cast<F>(0);
   for (int32_t js = j0; js < j1; js += kStage) {
     const int32_t nk = min(kStage, j1 - js);
     __syncthreads();
     for (int32_t x = threadIdx.x; x < nk * kHeadDim; x += blockDim.x)
-      y[x / kHeadDim][x % kHeadDim] = rs * In<F>::get(Kh, static_cast<int64_t>(js) * kHeadDim + x);
+      y[x / kHeadDim][x % kHeadDim] = rs * elem<F>(Kh, static_cast<int64_t>(js) * kHeadDim + x);
     __syncthreads();
     for (int32_t j = threadIdx.x; j < nk; j += blockDim.x) {
       F n = 0;
@@ -86,7 +101,7 @@ __global__ __launch_bounds__(256) void prefix_kernel(Shape s, const typename In<
       for (int e = 0; e < kHeadDim; ++e) dot += w[e] * y[j][e];
       const F f = (js + j < len) ? exp_of(dot - half_norm[j]) : static_cast<F>(0);
       run += static_cast<double>(f);
-      if (WRITE) Ph[static_cast<int64_t>(js + j + 1) * s.m + i] = static_cast<F>(run);
+      if (WRITE) Ph[static_cast<int64_t>(js + j + 1) * s.m + i] = static_cast<F>(base + run);
     }
   }
   if (!WRITE) ctot[(head * nch + chunk) * s.m + i] = run;
@@ -110,6 +125,29 @@ __device__ __forceinline__ F wave_sum(F v) {
   for (int mask = 1; mask < kWave; mask <<= 1) v += __shfl_xor(v, mask, kWave);
   return v;
 }
+// Eight wave sums for the price of ten exchanges: at each of the first three steps a lane keeps
+// the half of the values its lane bit names and hands the other half to its partner.  Lane l ends
+// with the full sum of p[l & 7]; every value is added up in the same butterfly order.
+template <typename F>
+__device__ __forceinline__ F wave_sum8(const F (&p)[8], int lane) {
+  F a[4], b[2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const bool hi = lane & 1;
+    a[i] = (hi ? p[2 * i + 1] : p[2 * i]) + __shfl_xor(hi ? p[2 * i] : p[2 * i + 1], 1, kWave);
+  }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const bool hi = lane & 2;
+    b[i] = (hi ? a[2 * i + 1] : a[2 * i]) + __shfl_xor(hi ? a[2 * i] : a[2 * i + 1], 2, kWave);
+  }
+  const bool hi = lane & 4;
+  F c = (hi ? b[1] : b[0]) + __shfl_xor(hi ? b[0] : b[1], 4, kWave);
+  c += __shfl_xor(c, 8, kWave);
+  c += __shfl_xor(c, 16, kWave);
+  c += __shfl_xor(c, 32, kWave);
+  return c;
+}
 template <typename F>
 __device__ __forceinline__ F wave_max(F v) {
 #pragma unroll
@@ -117,17 +155,19 @@ __device__ __forceinline__ F wave_max(F v) {
   return v;
 }
 
-// MU = m / 64 feature slots per lane (feature = u 64 + lane), SLOTS = ceil(K / 64) column slots
-// per lane (column = q 64 + lane).  W^T sits in LDS as floats (exact for bf16 and fp32 weights),
-// [e][i] so that a wavefront reads consecutive words.
-template <typename F, int MU, int SLOTS>
-__global__ __launch_bounds__(kRowWaves* kWave) void rows_kernel(Shape s, const typename In<F>::T* __restrict__ Q,
-                                                                const typename In<F>::T* __restrict__ W,
+// MU = m / 64 consecutive features per lane (feature = lane MU + u: a lane's share of a prefix
+// row is one vector load, a wavefront's the whole row), SLOTS = ceil(K / 64) column slots per
+// lane (column = q 64 + lane).  W^T sits in LDS in the tensors' own element type, [e][i].
+template <typename F, typename TI, int MU, int SLOTS>
+__global__ __launch_bounds__(kRowWaves* kWave) void rows_kernel(Shape s, const TI* __restrict__ Q,
+                                                                const TI* __restrict__ W,
                                                                 const F* __restrict__ P, float* __restrict__ A_hat) {
-  extern __shared__ float wt[];  // [64][m]
+  using WT = TI;
+  extern __shared__ __align__(16) unsigned char wt_raw[];
+  WT* wt = reinterpret_cast<WT*>(wt_raw);  // [64][m]
   for (int32_t x = threadIdx.x; x < s.m * kHeadDim; x += blockDim.x) {
     const int32_t i = x / kHeadDim, e = x % kHeadDim;
-    wt[e * s.m + i] = static_cast<float>(In<F>::get(W, x));
+    wt[e * s.m + i] = W[x];
   }
   __syncthreads();
   const int lane = threadIdx.x & 63;
@@ -135,81 +175,100 @@ __global__ __launch_bounds__(kRowWaves* kWave) void rows_kernel(Shape s, const t
   const uint32_t lb = xcd_contiguous(blockIdx.x, gridDim.x);
   const int64_t first = (static_cast<int64_t>(lb) * kRowWaves + (threadIdx.x >> 6)) * kRowsPerWave;
   const F rs = static_cast<F>(sqrtf(s.scale));
-  for (int rr = 0; rr < kRowsPerWave; ++rr) {
-    const int64_t row = first + rr;
-    if (row >= nrows) return;  // no block-wide barrier below
+  constexpr int R = kRowsPerWave;
+  // The wavefront's R consecutive rows walk the columns together: their boundaries of a column
+  // are at most R - 1 keys apart, so most of their prefix rows are the same cache lines.
+  F phi[R][MU];
+  const F* Ph[R];
+  int64_t width[R];
+  bool valid[R], active[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    valid[r] = first + r < nrows;
+    const int64_t row = valid[r] ? first + r : nrows - 1;
     const int64_t head = row / s.T;
     const int32_t t = static_cast<int32_t>(row - head * s.T);
     const int32_t b = static_cast<int32_t>(head / s.H);
     const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
-    float* Arow = A_hat + row * s.K;
-    if (t >= len) {
-      for (int32_t c = lane; c < s.K; c += kWave) Arow[c] = 0.f;
-      continue;
-    }
+    active[r] = valid[r] && t < len;
+    Ph[r] = P + head * (static_cast<int64_t>(s.T) + 1) * s.m + lane * MU;
+    width[r] = static_cast<int64_t>(t) + 1;
     // phi(q_t) up to a row factor (|x|^2 / 2 and the largest exponent cancel in the row norm):
-    // lane e holds x[e]; feature u 64 + lane in slot u
-    const F xe = rs * In<F>::get(Q, row * kHeadDim + lane);
+    // lane e holds x[e]; feature lane MU + u in slot u
+    const F xe = rs * elem<F>(Q, row * kHeadDim + lane);
     F arg[MU];
 #pragma unroll
     for (int u = 0; u < MU; ++u) arg[u] = 0;
 #pragma unroll
     for (int e = 0; e < kHeadDim; ++e) {
       const F x = __shfl(xe, e, kWave);
+      const Vec<WT, MU> wv = load_vec<WT, MU>(wt + e * s.m + lane * MU);
 #pragma unroll
-      for (int u = 0; u < MU; ++u) arg[u] += static_cast<F>(wt[e * s.m + u * kWave + lane]) * x;
+      for (int u = 0; u < MU; ++u) arg[u] += elem<F>(wv.v, u) * x;
     }
     F top = arg[0];
 #pragma unroll
     for (int u = 1; u < MU; ++u) top = max(top, arg[u]);
     top = wave_max(top);
-    F phi[MU];
 #pragma unroll
-    for (int u = 0; u < MU; ++u) phi[u] = exp_of(arg[u] - top);  // the row factor cancels in the norm
+    for (int u = 0; u < MU; ++u) phi[r][u] = exp_of(arg[u] - top);
+  }
 
-    // G_c = phi . P[b_c] for c = 1..K (G_0 = 0); column c - 1 lives in lane (c-1) % 64, slot (c-1) / 64
-    const F* Ph = P + head * (static_cast<int64_t>(s.T) + 1) * s.m;
-    const int64_t width = static_cast<int64_t>(t) + 1;
-    F g[SLOTS];
+  // column c: phi . (P[b_{c+1}] - P[b_c]), b_c = ceil(c (t+1) / K), the difference taken element
+  // by element first (its error is that of the two stored prefixes, not of two long dot
+  // products); column c lives in lane c % 64, slot c / 64.  The boundary vector of the previous
+  // column stays in registers.
+  F g[R][SLOTS];
+  Vec<F, MU> prev[R];
 #pragma unroll
-    for (int q = 0; q < SLOTS; ++q) g[q] = 0;
+  for (int r = 0; r < R; ++r) {
 #pragma unroll
-    for (int q = 0; q < SLOTS; ++q) {
-      const int32_t cn = min(kWave, s.K - q * kWave);  // columns of this slot (uniform)
-      for (int32_t l0 = 0; l0 < cn; l0 += 4) {
-        F part[4];
+    for (int q = 0; q < SLOTS; ++q) g[r][q] = 0;
+    prev[r] = load_vec<F, MU>(Ph[r]);  // P[0] = 0
+  }
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
+  for (int q = 0; q < SLOTS; ++q) {
+    const int32_t cn = min(kWave, s.K - q * kWave);  // columns of this slot (uniform)
+    for (int32_t l0 = 0; l0 < cn; l0 += 8) {
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        Vec<F, MU> pv[8];
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
           const int32_t c = min(q * kWave + l0 + v + 1, s.K);
-          const int64_t bc = (c * width + s.K - 1) / s.K;  // <= t + 1
-          const F* pv = Ph + bc * s.m + lane;
+          const int64_t bc = (c * width[r] + s.K - 1) / s.K;  // <= t + 1
+          pv[v] = load_vec<F, MU>(Ph[r] + bc * s.m);
+        }
+        F part[8];
+#pragma unroll
+        for (int v = 0; v < 8; ++v) {
           F acc = 0;
 #pragma unroll
-          for (int u = 0; u < MU; ++u) acc += phi[u] * pv[u * kWave];
+          for (int u = 0; u < MU; ++u)
+            acc += phi[r][u] * (pv[v].v[u] - (v == 0 ? prev[r].v[u] : pv[v - 1].v[u]));
           part[v] = acc;
         }
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          const F sum = wave_sum(part[v]);
-          if (lane == l0 + v) g[q] = sum;
-        }
+        prev[r] = pv[7];
+        const F sum = wave_sum8(part, lane);  // lane l: column l0 + (l & 7)
+        if ((lane >> 3) == (l0 >> 3)) g[r][q] = sum;
       }
     }
-    // differences and the row normaliser G_K
-    const int32_t qk = (s.K - 1) / kWave, lk = (s.K - 1) % kWave;
-    F total = 0;
+  }
 #pragma unroll
-    for (int q = 0; q < SLOTS; ++q)
-      if (q == qk) total = __shfl(g[q], lk, kWave);
-    const F inv = total > static_cast<F>(0) ? static_cast<F>(1) / total : static_cast<F>(0);
-    F carry = 0;  // G of the column before this slot's first
+  for (int r = 0; r < R; ++r) {
+    if (!valid[r]) continue;
+    float* Arow = A_hat + (first + r) * s.K;
+    // row normaliser phi . P[t + 1]
+    F total = 0;
+    const Vec<F, MU> pe = load_vec<F, MU>(Ph[r] + width[r] * s.m);
+#pragma unroll
+    for (int u = 0; u < MU; ++u) total += phi[r][u] * pe.v[u];
+    total = wave_sum(total);
+    const F inv = (active[r] && total > static_cast<F>(0)) ? static_cast<F>(1) / total : static_cast<F>(0);
 #pragma unroll
     for (int q = 0; q < SLOTS; ++q) {
-      F prev = __shfl_up(g[q], 1, kWave);
-      if (lane == 0) prev = carry;
       const int32_t c = q * kWave + lane;
-      if (c < s.K) Arow[c] = static_cast<float>((g[q] - prev) * inv);
-      carry = __shfl(g[q], kWave - 1, kWave);
+      if (c < s.K) Arow[c] = static_cast<float>(g[r][q] * inv);
     }
   }
 }
@@ -226,21 +285,21 @@ Layout layout(const Shape& s, sea_dtype dt) {
   l.ctot = 0;
   l.cbase = tab;
   l.P = 2 * tab;
-  const size_t el = dt == SEA_BF16 ? sizeof(float) : sizeof(double);
+  const size_t el = dt == SEA_BF16 ? sizeof(PrefixOfBf16) : sizeof(double);
   l.total = l.P + ((static_cast<size_t>(s.N) * (static_cast<size_t>(s.T) + 1) * s.m * el + 255) & ~size_t(255));
   return l;
 }
 
-template <typename F, int MU>
-hipError_t launch_rows(const Shape& s, const typename In<F>::T* Q, const typename In<F>::T* W, const F* P,
+template <typename F, typename TI, int MU>
+hipError_t launch_rows(const Shape& s, const TI* Q, const TI* W, const F* P,
                        float* A_hat, hipStream_t st) {
   const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
   const int64_t per_block = kRowWaves * kRowsPerWave;
   const dim3 grid(static_cast<uint32_t>((nrows + per_block - 1) / per_block));
-  const size_t lds = static_cast<size_t>(s.m) * kHeadDim * sizeof(float);
+  const size_t lds = static_cast<size_t>(s.m) * kHeadDim * sizeof(TI);
   const int slots = (s.K + kWave - 1) / kWave;
 #define SEA_RW_ROWS(SL)                                                                                      \
-  hipLaunchKernelGGL((rows_kernel<F, MU, SL>), grid, dim3(kRowWaves* kWave), lds, st, s, Q, W, P, A_hat)
+  hipLaunchKernelGGL((rows_kernel<F, TI, MU, SL>), grid, dim3(kRowWaves* kWave), lds, st, s, Q, W, P, A_hat)
   if (slots <= 1) SEA_RW_ROWS(1);
   else if (slots <= 2) SEA_RW_ROWS(2);
   else if (slots <= 4) SEA_RW_ROWS(4);
@@ -250,13 +309,12 @@ hipError_t launch_rows(const Shape& s, const typename In<F>::T* Q, const typenam
   return hipGetLastError();
 }
 
-template <typename F>
+template <typename F, typename TI>
 hipError_t launch_all(const Shape& s, sea_dtype dt, const void* Qv, const void* Kv, const void* Wv, float* A_hat,
                       void* ws, hipStream_t st) {
-  using T = typename In<F>::T;
-  const T* Q = static_cast<const T*>(Qv);
-  const T* K = static_cast<const T*>(Kv);
-  const T* W = static_cast<const T*>(Wv);
+  const TI* Q = static_cast<const TI*>(Qv);
+  const TI* K = static_cast<const TI*>(Kv);
+  const TI* W = static_cast<const TI*>(Wv);
   const Layout l = layout(s, dt);
   char* base = static_cast<char*>(ws);
   double* ctot = reinterpret_cast<double*>(base + l.ctot);
@@ -265,17 +323,17 @@ hipError_t launch_all(const Shape& s, sea_dtype dt, const void* Qv, const void* 
   const dim3 pgrid(static_cast<uint32_t>(s.N) * l.nch);
   {
     StageScope scope(SEA_STAGE_STATE, st);
-    hipLaunchKernelGGL((prefix_kernel<F, false>), pgrid, dim3(s.m), 0, st, s, K, W, ctot, cbase, P);
+    hipLaunchKernelGGL((prefix_kernel<F, TI, false>), pgrid, dim3(s.m), 0, st, s, K, W, ctot, cbase, P);
     hipLaunchKernelGGL(chunk_base_kernel, dim3(s.N), dim3(s.m), 0, st, ctot, cbase, l.nch, s.m);
-    hipLaunchKernelGGL((prefix_kernel<F, true>), pgrid, dim3(s.m), 0, st, s, K, W, ctot, cbase, P);
+    hipLaunchKernelGGL((prefix_kernel<F, TI, true>), pgrid, dim3(s.m), 0, st, s, K, W, ctot, cbase, P);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   StageScope scope(SEA_STAGE_CONTRACT, st);
   switch (s.m / kWave) {
-    case 1: return launch_rows<F, 1>(s, Q, W, P, A_hat, st);
-    case 2: return launch_rows<F, 2>(s, Q, W, P, A_hat, st);
-    default: return launch_rows<F, 4>(s, Q, W, P, A_hat, st);
+    case 1: return launch_rows<F, TI, 1>(s, Q, W, P, A_hat, st);
+    case 2: return launch_rows<F, TI, 2>(s, Q, W, P, A_hat, st);
+    default: return launch_rows<F, TI, 4>(s, Q, W, P, A_hat, st);
   }
 }
 
@@ -287,8 +345,8 @@ size_t estimate_rowwidth_workspace(const Shape& s, sea_dtype dt) { return layout
 
 hipError_t launch_estimate_rowwidth(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* W,
                                     float* A_hat, void* ws, hipStream_t st) {
-  return dt == SEA_BF16 ? launch_all<float>(s, dt, Q, K, W, A_hat, ws, st)
-                        : launch_all<double>(s, dt, Q, K, W, A_hat, ws, st);
+  return dt == SEA_BF16 ? launch_all<PrefixOfBf16, uint16_t>(s, dt, Q, K, W, A_hat, ws, st)
+                        : launch_all<double, float>(s, dt, Q, K, W, A_hat, ws, st);
 }
 
 }  // namespace sea

@@ -128,40 +128,45 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
     }
     total = kept;  // dropped keys are a suffix: only the last selected column can overrun jmax
   } else {
-    // ragged columns: per-selection offsets by a serial prefix in lane 0 (n_sel <= K)
-    if (lane == 0) {
-      int32_t acc = 0;
-      for (int32_t si = 0; si < n_sel; ++si) {
-        sh_off[wid][si] = acc;
+    // ragged columns: offsets of the selections by wave prefix scans, then one pass over the
+    // list -- entry x belongs to the last selection si with off[si] <= x (binary search in LDS)
+    int32_t acc = 0;  // keys emitted by the selections before this batch (uniform)
+    for (int32_t base = 0; base < n_sel; base += kWave) {
+      const int32_t si = base + lane;
+      int32_t r = 0;
+      if (si < n_sel) {
         const int32_t c = sh_sel[wid][si];
-        const int32_t w = block_start(c + 1, Tw, s.K) - block_start(c, Tw, s.K);
-        acc += min(w, s.rep_cap);
+        r = min(block_start(c + 1, Tw, s.K) - block_start(c, Tw, s.K), s.rep_cap);
       }
-      sh_off[wid][n_sel] = acc;
+      int32_t inc = r;
+#pragma unroll
+      for (int d = 1; d < kWave; d <<= 1) {
+        const int32_t v = __shfl_up(inc, d, kWave);
+        if (lane >= d) inc += v;
+      }
+      if (si < n_sel) sh_off[wid][si] = acc + inc - r;
+      acc += __shfl(inc, kWave - 1, kWave);
     }
     __builtin_amdgcn_wave_barrier();
-    if (irow)
-      for (int32_t x = lane; x < s.L; x += kWave) irow[x] = -1;
-    __builtin_amdgcn_wave_barrier();
     int32_t kept = 0;
-    for (int32_t si = 0; si < n_sel; ++si) {
-      const int32_t c = sh_sel[wid][si];
-      const int32_t s0 = block_start(c, Tw, s.K);
-      const int32_t w = block_start(c + 1, Tw, s.K) - s0;
-      const int32_t r = min(w, s.rep_cap);
-      const int32_t off = sh_off[wid][si];
-      for (int32_t i = lane; i < r; i += kWave) {
-        const int32_t j = s0 + static_cast<int32_t>((static_cast<int64_t>(i) * w) / r);
-        if (irow && j <= jmax && off + i < s.L) irow[off + i] = j;
+    for (int32_t x0 = 0; x0 < s.L; x0 += kWave) {
+      const int32_t x = x0 + lane;
+      int32_t j = -1;
+      if (x < acc) {
+        int32_t lo = 0, hi = n_sel - 1;
+        while (lo < hi) {
+          const int32_t mid = (lo + hi + 1) >> 1;
+          if (sh_off[wid][mid] <= x) lo = mid; else hi = mid - 1;
+        }
+        const int32_t c = sh_sel[wid][lo];
+        const int32_t s0 = block_start(c, Tw, s.K);
+        const int32_t w = block_start(c + 1, Tw, s.K) - s0;
+        const int32_t r = min(w, s.rep_cap);
+        j = s0 + static_cast<int32_t>((static_cast<int64_t>(x - sh_off[wid][lo]) * w) / r);
+        if (j > jmax) j = -1;  // only the tail of the last selected column can overrun jmax
       }
-      // count kept keys of this column (uniform value across the wave)
-      int32_t lo = 0, hi = r;  // first i with s0 + floor(i w / r) > jmax
-      while (lo < hi) {
-        const int32_t mid = (lo + hi) >> 1;
-        if (s0 + static_cast<int32_t>((static_cast<int64_t>(mid) * w) / r) > jmax) hi = mid;
-        else lo = mid + 1;
-      }
-      kept += lo;
+      if (irow && x < s.L) irow[x] = j;
+      kept += popc64(__ballot(j >= 0));
     }
     total = kept;
   }

@@ -462,7 +462,28 @@ ROW_WIDTH_CASES = [
     _wl("rw_bf16_three_slots", 1, 2, 777, 256, 192, 8, geometry=1),
     _wl("rw_bf16_one_column", 1, 2, 256, 64, 8, 1, k_budget=4, geometry=1),
     _wl("rw_bf16_long", 1, 1, 8192, 128, 128, 4, k_budget=32, geometry=1),
+    replace(synth.get_workload("c2"), name="c2+row_width", geometry=1),      # full size, sampled rows
 ]
+
+
+def _random_row_width_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        K = int(rng.choice([3, 8, 24, 32, 64, 100, 128, 256, 300]))
+        T = int(rng.integers(K, 700))
+        m = int(rng.choice([64, 128, 256]))
+        k_hat = int(min(K, rng.choice([1, 2, 3, 5, 8, 13, 32])))
+        k_budget = int(rng.choice([0, 0, 8, 33, 64]))
+        pad = float(rng.choice([0.0, 0.3]))
+        dtype = "f32" if rng.random() < 0.3 else "bf16"
+        out.append(_wl(f"rw_rnd{len(out)}_T{T}_K{K}_m{m}_kh{k_hat}_kb{k_budget}_p{int(pad > 0)}_{dtype}",
+                       int(rng.integers(1, 3)), int(rng.integers(1, 4)), T, m, K, k_hat, k_budget=k_budget,
+                       pad_frac=pad, dtype=dtype, geometry=1))
+    return out
+
+
+ROW_WIDTH_CASES += _random_row_width_cases(12, 77)
 
 
 @pytest.mark.parametrize("wl", ROW_WIDTH_CASES, ids=lambda w: w.name)
@@ -498,7 +519,10 @@ def test_row_width_geometry(sea, wl):
         a = o["A_hat"][b, h, r]
         mine, theirs = set(gs[b, h, r]) - {-1}, set(o["sel"][b, h, r]) - {-1}
         lo, hi = min(a[c] for c in theirs), max(a[c] for c in mine - theirs)
-        assert (lo - hi) / lo < GAP[wl.dtype], (b, h, r, lo, hi)
+        # near-tie: relative gap below the dtype's bound, or both scores (shares of a row that sums
+        # to 1, taken from differences of fp64 prefix sums of the whole row) below what fp64 can
+        # tell apart: m * 2^-53 < 1e-13 of the row
+        assert (lo - hi) / lo < GAP[wl.dtype] or lo - hi < 1e-12, (b, h, r, lo, hi)
     assert (~same).mean() <= 0.02
     assert np.array_equal(gi[same], o["idx"][same]) and np.array_equal(gc[same], o["cnt"][same])
     Og, Oo = O_g.copy(), o["O"].copy()
