@@ -220,11 +220,17 @@ __global__ __launch_bounds__(kRowWaves* kWave) void rows_kernel(Shape s, const T
   // column stays in registers.
   F g[R][SLOTS];
   Vec<F, MU> prev[R];
+  // c (t+1) = fq K + fr, stepped from column to column (no division per boundary)
+  int32_t wq[R], wr[R], fq[R], fr[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) {
 #pragma unroll
     for (int q = 0; q < SLOTS; ++q) g[r][q] = 0;
     prev[r] = load_vec<F, MU>(Ph[r]);  // P[0] = 0
+    wq[r] = static_cast<int32_t>(width[r] / s.K);
+    wr[r] = static_cast<int32_t>(width[r] - static_cast<int64_t>(wq[r]) * s.K);
+    fq[r] = 0;
+    fr[r] = 0;
   }
 #pragma unroll
   for (int q = 0; q < SLOTS; ++q) {
@@ -235,8 +241,15 @@ __global__ __launch_bounds__(kRowWaves* kWave) void rows_kernel(Shape s, const T
         Vec<F, MU> pv[8];
 #pragma unroll
         for (int v = 0; v < 8; ++v) {
-          const int32_t c = min(q * kWave + l0 + v + 1, s.K);
-          const int64_t bc = (c * width[r] + s.K - 1) / s.K;  // <= t + 1
+          if (q * kWave + l0 + v + 1 <= s.K) {  // next column; past the last one the boundary stays t + 1
+            fq[r] += wq[r];
+            fr[r] += wr[r];
+            if (fr[r] >= s.K) {
+              fr[r] -= s.K;
+              ++fq[r];
+            }
+          }
+          const int64_t bc = fq[r] + (fr[r] > 0 ? 1 : 0);  // ceil(c (t+1) / K) <= t + 1
           pv[v] = load_vec<F, MU>(Ph[r] + bc * s.m);
         }
         F part[8];
