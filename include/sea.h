@@ -74,7 +74,7 @@ typedef struct {
                           c holds the keys [ceil(c (t+1) / K), ceil((c+1)(t+1) / K)) -- the
                           estimate, the selection (columns without a key are no candidates)
                           and the expansion of row t are those of a sequence of t + 1 keys.
-                          Needs grouping = 0 and m in {64, 128, 256}; the estimate then runs
+                          Needs m in {64, 128, 256}; the estimate then runs
                           in fp64 from a running key state (no bf16 rounding points), and
                           the attention stage works from per-row key lists                */
 } sea_params;

@@ -56,7 +56,6 @@ int check_mask_params(const sea_params* p) {
   if (p->grouping == 1 && static_cast<int64_t>(p->H) * p->K > 16384) return SEA_ENOTSUP;
   if (p->geometry != 0 && p->geometry != 1) return SEA_EINVAL;
   if (p->geometry == 1 && !p->causal) return SEA_EINVAL;  // the row's own width is a causal notion
-  if (p->geometry == 1 && p->grouping == 1) return SEA_ENOTSUP;
   return SEA_OK;
 }
 
@@ -174,6 +173,7 @@ size_t sea_workspace_bytes(const sea_params* p) {
   } else {
     bytes += align256(rows * static_cast<size_t>(row_stride_of(p)) * sizeof(int32_t));
     bytes += align256(rows * sizeof(int32_t));
+    if (p->grouping == 1) bytes += align256(rows * ((p->K + 31) / 32) * sizeof(uint32_t));
   }
   return bytes;
 }
@@ -341,7 +341,10 @@ int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V
   int32_t* idx = idx_opt ? idx_opt : reinterpret_cast<int32_t*>(w);
   w += align256(rows * static_cast<size_t>(s.L) * sizeof(int32_t));
   int32_t* cnt = cnt_opt ? cnt_opt : reinterpret_cast<int32_t*>(w);
-  e = launch_topk_mask(s, A_hat, sel_opt, idx, cnt, mhat_opt, st);
+  w += align256(rows * sizeof(int32_t));
+  uint32_t* mbits = mhat_opt;
+  if (!mbits && s.grouping == 1) mbits = reinterpret_cast<uint32_t*>(w);  // selection as bits, lists from them
+  e = launch_topk_mask(s, A_hat, sel_opt, idx, cnt, mbits, st);
   if (e != hipSuccess) return fail_hip(e);
   e = launch_sparse_attn(s, p->dtype, Q, K, V, idx, cnt, s.L, nullptr, O, st);
   return e == hipSuccess ? SEA_OK : fail_hip(e);

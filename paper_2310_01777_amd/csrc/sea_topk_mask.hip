@@ -27,7 +27,9 @@ __device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
 
 // ROWW: per-row width geometry -- a causal row t spreads its K columns over its own t + 1 keys
 // (column c = keys [ceil(c (t+1) / K), ceil((c+1)(t+1) / K)); empty columns are no candidates).
-template <int SLOTS, bool ROWW>
+// FROMBITS: the selection was already made (mbits holds it, A_hat is not read); only the lists
+// are written -- the expansion pass after the causal-per-batch kernel.
+template <int SLOTS, bool ROWW, bool FROMBITS>
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
     Shape s, const float* __restrict__ A_hat, int32_t* __restrict__ sel, int32_t* __restrict__ idx,
     int32_t* __restrict__ cnt, uint32_t* __restrict__ mbits) {
@@ -46,12 +48,12 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
   const int32_t kw = (s.K + 31) / 32;  // mask words per row
   uint32_t* mrow = mbits ? mbits + row * kw : nullptr;
 
-  if (t >= len) {  // inactive row
+  if (t >= len) {  // inactive row (FROMBITS: its mask words are already zero)
     if (irow)
       for (int32_t x = lane; x < s.L; x += kWave) irow[x] = -1;
     if (srow)
       for (int32_t x = lane; x < s.sel_stride; x += kWave) srow[x] = -1;
-    if (mrow)
+    if (mrow && !FROMBITS)
       for (int32_t x = lane; x < kw; x += kWave) mrow[x] = 0u;
     if (cnt && lane == 0) cnt[row] = 0;
     return;
@@ -61,46 +63,57 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
   const int32_t ncand = bucket_of(jmax, Tw, s.K) + 1;            // candidate columns 0..ncand-1
   const int32_t n = min(s.k_hat, ROWW ? min(s.K, Tw) : ncand);   // ROWW: min(K, t + 1) columns hold a key
 
-  uint32_t key[SLOTS];
-#pragma unroll
-  for (int q = 0; q < SLOTS; ++q) {
-    const int32_t c = q * kWave + lane;
-    bool cand = c < ncand;  // c < ncand <= K
-    if (ROWW) cand = cand && block_start(c + 1, Tw, s.K) > block_start(c, Tw, s.K);
-    key[q] = cand ? ordered_key(A_hat[row * s.K + c]) : 0u;
-  }
-  // largest tau with #{key >= tau} >= n  ==  the n-th largest key
-  uint32_t tau = 0;
-#pragma unroll 1
-  for (int bit = 31; bit >= 0; --bit) {
-    const uint32_t trial = tau | (1u << bit);
-    int c_ge = 0;
-#pragma unroll
-    for (int q = 0; q < SLOTS; ++q) c_ge += popc64(__ballot(key[q] >= trial));
-    if (c_ge >= n) tau = trial;
-  }
-  int c_gt = 0;
-#pragma unroll
-  for (int q = 0; q < SLOTS; ++q) c_gt += popc64(__ballot(key[q] > tau));
-  int need_eq = n - c_gt;  // how many of the entries equal to tau are taken, lowest columns first
-
-  // compaction in ascending column order (slot-major, then lane)
   int n_sel = 0;
+  if (FROMBITS) {
 #pragma unroll
-  for (int q = 0; q < SLOTS; ++q) {
-    const uint64_t eq = __ballot(key[q] == tau);
-    const bool take_eq = (key[q] == tau) && (lanes_below(eq, lane) < need_eq);
-    const bool take = (key[q] > tau) || take_eq;
-    const uint64_t tk = __ballot(take);
-    if (take) sh_sel[wid][n_sel + lanes_below(tk, lane)] = q * kWave + lane;
-    if (mrow && lane == 0) {  // selected-column bits: column c is bit c % 32 of word c / 32
-      if (2 * q < kw) mrow[2 * q] = static_cast<uint32_t>(tk);
-      if (2 * q + 1 < kw) mrow[2 * q + 1] = static_cast<uint32_t>(tk >> 32);
+    for (int q = 0; q < SLOTS; ++q) {
+      const int32_t c = q * kWave + lane;
+      const bool take = c < s.K && ((mrow[c >> 5] >> (c & 31)) & 1u);
+      const uint64_t tk = __ballot(take);
+      if (take) sh_sel[wid][n_sel + lanes_below(tk, lane)] = c;
+      n_sel += popc64(tk);
     }
-    n_sel += popc64(tk);
-    need_eq -= min(need_eq, popc64(eq));
+  } else {
+    uint32_t key[SLOTS];
+  #pragma unroll
+    for (int q = 0; q < SLOTS; ++q) {
+      const int32_t c = q * kWave + lane;
+      bool cand = c < ncand;  // c < ncand <= K
+      if (ROWW) cand = cand && block_start(c + 1, Tw, s.K) > block_start(c, Tw, s.K);
+      key[q] = cand ? ordered_key(A_hat[row * s.K + c]) : 0u;
+    }
+    // largest tau with #{key >= tau} >= n  ==  the n-th largest key
+    uint32_t tau = 0;
+  #pragma unroll 1
+    for (int bit = 31; bit >= 0; --bit) {
+      const uint32_t trial = tau | (1u << bit);
+      int c_ge = 0;
+  #pragma unroll
+      for (int q = 0; q < SLOTS; ++q) c_ge += popc64(__ballot(key[q] >= trial));
+      if (c_ge >= n) tau = trial;
+    }
+    int c_gt = 0;
+  #pragma unroll
+    for (int q = 0; q < SLOTS; ++q) c_gt += popc64(__ballot(key[q] > tau));
+    int need_eq = n - c_gt;  // how many of the entries equal to tau are taken, lowest columns first
+
+    // compaction in ascending column order (slot-major, then lane)
+  #pragma unroll
+    for (int q = 0; q < SLOTS; ++q) {
+      const uint64_t eq = __ballot(key[q] == tau);
+      const bool take_eq = (key[q] == tau) && (lanes_below(eq, lane) < need_eq);
+      const bool take = (key[q] > tau) || take_eq;
+      const uint64_t tk = __ballot(take);
+      if (take) sh_sel[wid][n_sel + lanes_below(tk, lane)] = q * kWave + lane;
+      if (mrow && lane == 0) {  // selected-column bits: column c is bit c % 32 of word c / 32
+        if (2 * q < kw) mrow[2 * q] = static_cast<uint32_t>(tk);
+        if (2 * q + 1 < kw) mrow[2 * q + 1] = static_cast<uint32_t>(tk >> 32);
+      }
+      n_sel += popc64(tk);
+      need_eq -= min(need_eq, popc64(eq));
+    }
   }
-  // n_sel == n by construction
+  // n_sel == n by construction (FROMBITS: the number of set bits)
   __builtin_amdgcn_wave_barrier();
   if (srow)
     for (int32_t x = lane; x < s.sel_stride; x += kWave) srow[x] = (x < n_sel) ? sh_sel[wid][x] : -1;
@@ -207,8 +220,16 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
   const int32_t kw = (s.K + 31) / 32;
   const bool active = t < len;
   const int32_t jmax = active ? ((s.causal && t < len - 1) ? t : len - 1) : -1;
-  const int32_t ncand = active ? bucket_of(jmax, s.T, s.K) + 1 : 0;
-  const int64_t quota = static_cast<int64_t>(s.H) * s.k_hat, total = static_cast<int64_t>(s.H) * ncand;
+  // per-row width geometry: the K columns are spread over the row's own t + 1 keys; when that is
+  // fewer than K keys, only t + 1 of the columns hold one
+  const int32_t Tw = s.geometry == 1 ? t + 1 : s.T;
+  const int32_t ncand = active ? bucket_of(jmax, Tw, s.K) + 1 : 0;
+  const bool holes = s.geometry == 1 && Tw < s.K;
+  auto is_cand = [&](int32_t c) {
+    return c < ncand && (!holes || block_start(c + 1, Tw, s.K) > block_start(c, Tw, s.K));
+  };
+  const int64_t quota = static_cast<int64_t>(s.H) * s.k_hat;
+  const int64_t total = static_cast<int64_t>(s.H) * (holes ? min(Tw, ncand) : ncand);
   const uint32_t n = static_cast<uint32_t>(quota < total ? quota : total);
 
   // A thread owns VPT / 4 groups of four consecutive entries of the flattened slab: group gi of
@@ -232,7 +253,7 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
         f = *reinterpret_cast<const float4*>(A_hat + ((static_cast<int64_t>(b) * s.H + h) * s.T + t) * s.K + c0);
       const float fv[4] = {f.x, f.y, f.z, f.w};
 #pragma unroll
-      for (int q = 0; q < 4; ++q) key[4 * gi + q] = (e0 < HK && c0 + q < ncand) ? ordered_key(fv[q]) : 0u;
+      for (int q = 0; q < 4; ++q) key[4 * gi + q] = (e0 < HK && is_cand(c0 + q)) ? ordered_key(fv[q]) : 0u;
     } else {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
@@ -240,7 +261,7 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
         uint32_t k = 0u;
         if (e < HK) {
           const int32_t h = e / s.K, c = e - h * s.K;
-          if (c < ncand) k = ordered_key(A_hat[((static_cast<int64_t>(b) * s.H + h) * s.T + t) * s.K + c]);
+          if (is_cand(c)) k = ordered_key(A_hat[((static_cast<int64_t>(b) * s.H + h) * s.T + t) * s.K + c]);
         }
         key[4 * gi + q] = k;
       }
@@ -404,8 +425,8 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
         if (!flags[h * s.K + c]) continue;
         if (srow) srow[ns] = c;
         ++ns;
-        const int32_t s0 = block_start(c, s.T, s.K);
-        const int32_t w = block_start(c + 1, s.T, s.K) - s0;
+        const int32_t s0 = block_start(c, Tw, s.K);
+        const int32_t w = block_start(c + 1, Tw, s.K) - s0;
         const int32_t r = min(w, s.rep_cap);
         for (int32_t i = 0; i < r; ++i) {
           const int32_t j = s0 + static_cast<int32_t>((static_cast<int64_t>(i) * w) / r);
@@ -433,25 +454,41 @@ hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, in
   const dim3 block(kWavesPerBlock * kWave);
   const int slots = (s.K + kWave - 1) / kWave;
   StageScope scope(SEA_STAGE_TOPK_MASK, st);
+  bool from_bits = false;
   if (s.grouping == 1) {
+    // With a mask buffer at hand the slab kernel only selects; the lists are then written by the
+    // per-row kernel from the bits (one wavefront per row instead of one thread per head).
+    const bool lists = sel || idx || cnt;
+    from_bits = lists && mbits;
+    int32_t* const sel_g = from_bits ? nullptr : sel;
+    int32_t* const idx_g = from_bits ? nullptr : idx;
+    int32_t* const cnt_g = from_bits ? nullptr : cnt;
     const int32_t HK = s.H * s.K;
     const int vpt = (HK + 255) / 256;
     const dim3 ggrid(static_cast<uint32_t>(s.N / s.H) * s.T);
     const size_t shm = static_cast<size_t>(HK);
-    if (vpt <= 4) hipLaunchKernelGGL(topk_group_kernel<4>, ggrid, block, shm, st, s, A_hat, sel, idx, cnt, mbits);
-    else if (vpt <= 8) hipLaunchKernelGGL(topk_group_kernel<8>, ggrid, block, shm, st, s, A_hat, sel, idx, cnt, mbits);
-    else if (vpt <= 16) hipLaunchKernelGGL(topk_group_kernel<16>, ggrid, block, shm, st, s, A_hat, sel, idx, cnt, mbits);
-    else if (vpt <= 32) hipLaunchKernelGGL(topk_group_kernel<32>, ggrid, block, shm, st, s, A_hat, sel, idx, cnt, mbits);
-    else if (vpt <= 64) hipLaunchKernelGGL(topk_group_kernel<64>, ggrid, block, shm, st, s, A_hat, sel, idx, cnt, mbits);
+    if (vpt <= 4) hipLaunchKernelGGL(topk_group_kernel<4>, ggrid, block, shm, st, s, A_hat, sel_g, idx_g, cnt_g, mbits);
+    else if (vpt <= 8) hipLaunchKernelGGL(topk_group_kernel<8>, ggrid, block, shm, st, s, A_hat, sel_g, idx_g, cnt_g, mbits);
+    else if (vpt <= 16) hipLaunchKernelGGL(topk_group_kernel<16>, ggrid, block, shm, st, s, A_hat, sel_g, idx_g, cnt_g, mbits);
+    else if (vpt <= 32) hipLaunchKernelGGL(topk_group_kernel<32>, ggrid, block, shm, st, s, A_hat, sel_g, idx_g, cnt_g, mbits);
+    else if (vpt <= 64) hipLaunchKernelGGL(topk_group_kernel<64>, ggrid, block, shm, st, s, A_hat, sel_g, idx_g, cnt_g, mbits);
     else return hipErrorNotSupported;
-    return hipGetLastError();
+    if (!from_bits) return hipGetLastError();
   }
 #define SEA_TOPK(SL)                                                                                               \
   do {                                                                                                             \
-    if (s.geometry == 1)                                                                                           \
-      hipLaunchKernelGGL((topk_mask_kernel<SL, true>), dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits);  \
+    if (from_bits && s.geometry == 1)                                                                              \
+      hipLaunchKernelGGL((topk_mask_kernel<SL, true, true>), dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt,    \
+                         mbits);                                                                                   \
+    else if (from_bits)                                                                                            \
+      hipLaunchKernelGGL((topk_mask_kernel<SL, false, true>), dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt,   \
+                         mbits);                                                                                   \
+    else if (s.geometry == 1)                                                                                      \
+      hipLaunchKernelGGL((topk_mask_kernel<SL, true, false>), dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt,   \
+                         mbits);                                                                                   \
     else                                                                                                           \
-      hipLaunchKernelGGL((topk_mask_kernel<SL, false>), dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt, mbits); \
+      hipLaunchKernelGGL((topk_mask_kernel<SL, false, false>), dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt,  \
+                         mbits);                                                                                   \
   } while (0)
   if (slots <= 1) SEA_TOPK(1);
   else if (slots <= 2) SEA_TOPK(2);

@@ -106,11 +106,10 @@ def test_argument_validation_returns_codes_not_crashes(sea):
     assert sea.sea_attention_path(P(1, 2, 300, 64, 96, 17, 5)) == 0            # K does not divide T
     assert sea.sea_attention_path(P(1, 2, 768, 64, 64, 64, 8, k_budget=24)) == 0   # r = 3
     assert sea.sea_attention_path(P(1, 1, 64, 64, 32, 16, 17)) == sea.SEA_EINVAL
-    # per-row width geometry: causal only, per-query grouping only, key lists for the attention
+    # per-row width geometry: causal only, key lists for the attention
     assert sea.sea_attention_path(P(1, 2, 2048, 64, 128, 128, 64, geometry=1)) == 0
     for bad, code in ((P(1, 2, 256, 64, 64, 16, 4, causal=False, geometry=1), sea.SEA_EINVAL),
-                      (P(1, 2, 256, 64, 64, 16, 4, geometry=2), sea.SEA_EINVAL),
-                      (P(1, 2, 256, 64, 64, 16, 4, geometry=1, grouping=1), sea.SEA_ENOTSUP)):
+                      (P(1, 2, 256, 64, 64, 16, 4, geometry=2), sea.SEA_EINVAL)):
         with pytest.raises(sea.SeaError) as e:
             sea.sea_row_stride(bad)
         assert e.value.status == code

@@ -463,6 +463,11 @@ ROW_WIDTH_CASES = [
     _wl("rw_bf16_one_column", 1, 2, 256, 64, 8, 1, k_budget=4, geometry=1),
     _wl("rw_bf16_long", 1, 1, 8192, 128, 128, 4, k_budget=32, geometry=1),
     replace(synth.get_workload("c2"), name="c2+row_width", geometry=1),      # full size, sampled rows
+    # the paper's own setting: causal-per-batch selection in this geometry
+    _wl("rw_grouped", 2, 4, 300, 64, 16, 3, grouping=1, geometry=1),
+    _wl("rw_grouped_budget_pad", 2, 3, 520, 128, 32, 4, k_budget=16, pad_frac=0.3, grouping=1, geometry=1),
+    _wl("rw_grouped_f32", 1, 3, 200, 64, 24, 5, dtype="f32", grouping=1, geometry=1),
+    _wl("rw_grouped_wide_slab", 1, 12, 400, 128, 128, 16, grouping=1, geometry=1),
 ]
 
 
@@ -515,14 +520,20 @@ def test_row_width_geometry(sea, wl):
     O_s = oracle.sparse_attn(po, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), idx_s, cnt_s, rows=rows)
     assert_close(O_g, O_s, tol, "O (stage)")
     same = (gs == o["sel"]).all(-1)
-    for b, h, r in zip(*np.nonzero(~same)):
-        a = o["A_hat"][b, h, r]
-        mine, theirs = set(gs[b, h, r]) - {-1}, set(o["sel"][b, h, r]) - {-1}
-        lo, hi = min(a[c] for c in theirs), max(a[c] for c in mine - theirs)
-        # near-tie: relative gap below the dtype's bound, or both scores (shares of a row that sums
-        # to 1, taken from differences of fp64 prefix sums of the whole row) below what fp64 can
-        # tell apart: m * 2^-53 < 1e-13 of the row
-        assert (lo - hi) / lo < GAP[wl.dtype] or lo - hi < 1e-12, (b, h, r, lo, hi)
+    if wl.grouping == 1:                       # heads share a time step's quota: compare whole slabs
+        same = np.broadcast_to(same.all(1, keepdims=True), same.shape).copy()
+    for b, r in sorted(set(zip(*np.nonzero(~same)[::2]))):
+        heads = range(wl.H) if wl.grouping == 1 else sorted(set(np.nonzero(~same[b, :, r])[0]))
+        groups = [list(heads)] if wl.grouping == 1 else [[h] for h in heads]
+        for grp in groups:
+            mine = {(h, c) for h in grp for c in gs[b, h, r] if c >= 0}
+            theirs = {(h, c) for h in grp for c in o["sel"][b, h, r] if c >= 0}
+            a = o["A_hat"][b, :, r]
+            lo, hi = min(a[h, c] for h, c in theirs), max(a[h, c] for h, c in mine - theirs)
+            # near-tie: relative gap below the dtype's bound, or both scores (shares of a row that
+            # sums to 1, taken from differences of fp64 prefix sums of the whole row) below what
+            # fp64 can tell apart: m * 2^-53 < 1e-13 of the row
+            assert (lo - hi) / lo < GAP[wl.dtype] or lo - hi < 1e-12, (b, grp, r, lo, hi)
     assert (~same).mean() <= 0.02
     assert np.array_equal(gi[same], o["idx"][same]) and np.array_equal(gc[same], o["cnt"][same])
     Og, Oo = O_g.copy(), o["O"].copy()
