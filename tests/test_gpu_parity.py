@@ -635,14 +635,16 @@ def test_bucketed_rows_are_reproducible(sea):
         assert torch.equal(a[k][:, :, :t0 + 1], b[k][:, :, :t0 + 1]), k
 
 
-@pytest.mark.parametrize("shape", ["tiles", "buckets", "multi"])
+@pytest.mark.parametrize("shape", ["tiles", "buckets", "multi", "row_width", "row_width_grouped"])
 def test_forward_replays_in_a_hip_graph(sea, shape):
     """sea_forward enqueues kernels only (no allocation, no synchronisation, no memset), so a
     captured graph of it can be replayed: every replay, with new inputs written into the same
     buffers and eager work in between, must equal the eager call bit for bit."""
     wl = {"tiles": _wl("graph_tiles", 1, 2, 512, 64, 32, 8),
           "buckets": _wl("graph_buckets", 1, 2, 1024, 64, 16, 1, k_budget=32),
-          "multi": _wl("graph_multi", 1, 2, 1024, 64, 64, 3, k_budget=48)}[shape]
+          "multi": _wl("graph_multi", 1, 2, 1024, 64, 64, 3, k_budget=48),
+          "row_width": _wl("graph_rw", 1, 2, 600, 64, 24, 3, geometry=1),
+          "row_width_grouped": _wl("graph_rwg", 1, 3, 320, 64, 32, 2, k_budget=8, grouping=1, geometry=1)}[shape]
     x = synth.make_inputs(wl)
     xd = _dev(x)
     p = _params(sea, wl, xd["seq_len"])
@@ -702,6 +704,39 @@ def test_tiny_and_degenerate_shapes(sea, dtype):
         assert np.array_equal(_unpack_mhat(g["mhat"].numpy(), K), _sel_to_mask(sel_s, K))
         O_s = oracle.sparse_attn(po, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), idx_s, cnt_s)
         assert_close(to_np64(g["O"]), O_s, TOL[dtype], "O tiny")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_row_width_tiny_degenerate_and_causal(sea, dtype):
+    """Per-row width geometry at T = 1, K = 1, K = T, a zero-length batch element; every path in
+    bounds, lists bit-exact; and rows <= t0 ignore later positions bit for bit."""
+    for (B, H, T, m, K, kh, kb) in [(1, 1, 1, 64, 1, 1, 0), (2, 1, 5, 64, 5, 2, 0), (1, 2, 17, 64, 1, 1, 0),
+                                    (1, 1, 64, 128, 64, 1, 0), (1, 1, 33, 64, 11, 3, 4), (3, 1, 2, 256, 2, 2, 1)]:
+        wl = _wl("rw_tiny", B, H, T, m, K, kh, k_budget=kb, dtype=dtype, geometry=1)
+        x = synth.make_inputs(wl)
+        if B == 3:
+            x["seq_len"] = torch.tensor([0, 2, 1], dtype=torch.int32)
+        _, _, g = _gpu_forward(sea, wl, x)
+        po, o = _oracle_forward(wl, x)
+        sl = None if x["seq_len"] is None else x["seq_len"].numpy()
+        A_g = g["A_hat"].numpy().astype(np.float64)
+        assert_close(A_g, o["A_hat"], TOL[dtype], "A_hat tiny")
+        sel_s, idx_s, cnt_s = oracle.topk_mask(po, A_g, seq_len=sl)
+        assert np.array_equal(g["sel"].numpy(), sel_s)
+        assert np.array_equal(g["idx"].numpy(), idx_s) and np.array_equal(g["cnt"].numpy(), cnt_s)
+        O_s = oracle.sparse_attn(po, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), idx_s, cnt_s)
+        assert_close(to_np64(g["O"]), O_s, TOL[dtype], "O tiny")
+    wl = _wl("rw_causality", 1, 2, 300, 64, 32, 6, dtype=dtype, geometry=1)
+    x = synth.make_inputs(wl)
+    _, _, a = _gpu_forward(sea, wl, x)
+    t0 = 137
+    y = {k: (v.clone() if isinstance(v, torch.Tensor) else v) for k, v in x.items()}
+    gen = torch.Generator().manual_seed(3)
+    for k in "QKV":
+        y[k][:, :, t0 + 1:] = (torch.randn(y[k][:, :, t0 + 1:].shape, generator=gen) * 2).to(y[k].dtype)
+    _, _, b = _gpu_forward(sea, wl, y)
+    for k in a:
+        assert torch.equal(a[k][:, :, :t0 + 1], b[k][:, :, :t0 + 1]), k
 
 
 def test_optional_outputs_do_not_change_results(sea):
