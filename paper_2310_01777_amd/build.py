@@ -1,9 +1,11 @@
 """Compile the HIP sources under csrc/ into libsea_hip.so (in-tree) for gfx950."""
 from __future__ import annotations
 
+import concurrent.futures
 import glob
 import os
 import subprocess
+import tempfile
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
@@ -33,17 +35,28 @@ def is_stale() -> bool:
 
 
 def build(verbose: bool = False) -> str:
-    """Always recompiles.  Returns the path of the shared library."""
+    """Always recompiles: one hipcc per source file (in parallel), then one link.  Returns the
+    path of the shared library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(_ROOT, "include"), "-I", CSRC,
-           "-o", LIB, *sources()]
-    res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
-    err = "\n".join(ln for ln in res.stderr.splitlines() if noise not in ln)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + err)
-    if verbose and err.strip():
-        print(err)
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    inc = ["-I", os.path.join(_ROOT, "include"), "-I", CSRC]
+
+    def run(cmd):
+        res = subprocess.run(cmd, capture_output=True, text=True)
+        err = "\n".join(ln for ln in res.stderr.splitlines() if noise not in ln)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + err)
+        return err
+
+    with tempfile.TemporaryDirectory(prefix="sea_build_") as tmp:
+        jobs = [(src, os.path.join(tmp, os.path.basename(src) + ".o")) for src in sources()]
+        workers = max(1, min(len(jobs), int(os.environ.get("MAX_JOBS", os.cpu_count() or 1))))
+        with concurrent.futures.ThreadPoolExecutor(workers) as pool:
+            logs = list(pool.map(lambda j: run([hipcc, *flags, *inc, "-c", j[0], "-o", j[1]]), jobs))
+        logs.append(run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *[o for _, o in jobs]]))
+    if verbose and any(l.strip() for l in logs):
+        print("\n".join(l for l in logs if l.strip()))
     return LIB
 
 

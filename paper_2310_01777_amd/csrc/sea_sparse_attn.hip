@@ -13,6 +13,12 @@ namespace {
 constexpr int kWavesPerBlock = 4;
 constexpr int kUnroll = 4;
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16x2 as_bf16x2(uint32_t w) {
+  bf16x2 h;
+  __builtin_memcpy(&h, &w, sizeof(h));
+  return h;
+}
 __device__ __forceinline__ float wave_xor_f(float v, int mask) { return __shfl_xor(v, mask, kWave); }
 __device__ __forceinline__ double wave_xor_d(double v, int mask) { return __shfl_xor(v, mask, kWave); }
 
@@ -65,17 +71,11 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void sparse_attn_bf16_kernel
   const uint16_t* Kh = K + head * s.T * kHeadDim;
   const uint16_t* Vh = V + head * s.T * kHeadDim;
 
-  float qf[8];
-  {
-    const uint4 qv = *reinterpret_cast<const uint4*>(Q + row * kHeadDim + c8 * 8);
-    const float f = s.scale * kLog2e;
-    const uint32_t w[4] = {qv.x, qv.y, qv.z, qv.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      qf[2 * i] = bf16lo_to_f32(w[i]) * f;
-      qf[2 * i + 1] = bf16hi_to_f32(w[i]) * f;
-    }
-  }
+  // q stays in bf16 pairs: q.k is four packed dot-product instructions per lane (exact products,
+  // fp32 sums); the logit scale is applied to the finished dot product
+  const uint4 qv = *reinterpret_cast<const uint4*>(Q + row * kHeadDim + c8 * 8);
+  const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w};
+  const float f = s.scale * kLog2e;
   const KeyList kl = key_list(s, row, idx, cnt, L, crow);
   const int32_t n = kl.n;
   const int32_t* irow = kl.p;
@@ -104,14 +104,11 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void sparse_attn_bf16_kernel
       const uint32_t w[4] = {kv[u].x, kv[u].y, kv[u].z, kv[u].w};
       float a = 0.f;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        a = fmaf(qf[2 * i], bf16lo_to_f32(w[i]), a);
-        a = fmaf(qf[2 * i + 1], bf16hi_to_f32(w[i]), a);
-      }
+      for (int i = 0; i < 4; ++i) a = __builtin_amdgcn_fdot2_f32_bf16(as_bf16x2(qw[i]), as_bf16x2(w[i]), a, false);
       a += wave_xor_f(a, 1);
       a += wave_xor_f(a, 2);
       a += wave_xor_f(a, 4);
-      sc[u] = ok[u] ? a : -INFINITY;
+      sc[u] = ok[u] ? a * f : -INFINITY;
       mx = fmaxf(mx, sc[u]);
     }
     mx = fmaxf(mx, wave_xor_f(mx, 8));
