@@ -105,6 +105,8 @@ size_t sea_workspace_bytes(const sea_params* p);
  * dtype = SEA_BF16: phi(Q) and the key-side state phi(K)^T V_I (for a causal row also the
  * prefix state of its own column) are rounded to bfloat16 and contracted on the matrix
  * cores with fp32 accumulation.  dtype = SEA_F32: all products accumulate in fp64.
+ * geometry = 1: V_I of row t is the (t+1) x K stretch, A_hat[t][c] = phi(q_t) . sum of phi(k_j)
+ * over the keys of the row's own column c, normalised per row; all of it in fp64, either dtype.
  * The feature exponent is not stabilised on the key side: log2(e) * |w_i|^2 / 2 must stay
  * below the fp32 exponent range (true for any Gaussian W with d = 64).
  */
@@ -120,6 +122,8 @@ int sea_estimate(const sea_params* p, const void* Q, const void* K, const void* 
  *   values: lower h K + c first) and min(H k_hat, H #columns) entries are kept.  Column c covers keys [ceil(cT/K), ceil((c+1)T/K)), width w; a selected
  *   column emits keys start + floor(i w / r), i < r; keys j > t (causal) or j >= seq_len are
  *   dropped.  idx lists the emitted keys ascending, cnt their number.
+ *   With geometry = 1 read T in the column formulas as the row's own width t + 1; columns that
+ *   hold no key of the row are no candidates.
  * sel may be NULL.
  */
 int sea_topk_mask(const sea_params* p, const float* A_hat, int32_t* sel, int32_t* idx,

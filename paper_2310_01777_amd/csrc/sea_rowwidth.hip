@@ -10,7 +10,8 @@
 //   prefix_kernel<.., false> per (head, chunk of keys): chunk totals of phi(k), fp64 running sum
 //   chunk_base_kernel        per head: exclusive scan of the chunk totals (fp64)
 //   prefix_kernel<.., true>  same walk again, writes P = chunk base + running sum
-//   rows_kernel<F, SLOTS>    one wavefront per row: phi(q_t), the K gathers, differences, row norm
+//   rows_kernel              one wavefront per two consecutive rows: phi(q_t), the K gathers of
+//                            neighbouring prefix rows, their differences, row norm
 // Features, prefixes and dot products are fp64 for both tensor types (see PrefixOfBf16); nothing is
 // rounded to bf16 here.
 #include "sea_internal.h"
