@@ -219,6 +219,13 @@ def main():
            "frac_of_bf16_mfma_peak": (est_flops / (est_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS)
            if est_ms > 0 and wl.dtype == "bf16" else None,
            "includes_topk": "topk_mask" not in avg}
+    if wl.geometry == 1:
+        # per-row width geometry: the contraction is K + 1 gathered fp64 prefix rows of m features per
+        # query row, served by the caches
+        gbytes = float(nrows) * (wl.K + 1) * wl.m * 8
+        cms = avg.get("contract", 0.0)
+        est.update({"frac_of_bf16_mfma_peak": None, "rows_kernel_ms": cms, "gathered_bytes": gbytes,
+                    "gather_TBps": gbytes / (cms * 1e-3) / 1e12 if cms > 0 else 0.0})
 
     # ---- dense (quadratic) attention on the same shape, same dtype, for comparison ----
     dense = None

@@ -733,3 +733,35 @@ def test_row_width_last_row_is_the_fixed_bucket_row_and_rows_are_causal():
     b = oracle.forward(p1, Q2, K2, V2, W, seq_len=sl)
     for key in ("O", "A_hat", "sel", "idx", "cnt"):
         assert np.array_equal(a[key][:, :, :t0 + 1], b[key][:, :, :t0 + 1]), key
+
+
+def test_row_width_with_per_batch_grouping_equals_sort_over_columns_that_hold_a_key():
+    """Causal-per-batch selection in the per-row width geometry: each time step keeps the H k^
+    largest entries among the columns that hold a key of that row (stable library sort; ties to
+    the lower h K + c), and every selected column expands to its own key range of the row."""
+    g = np.random.default_rng(23)
+    B, H, T, K, kh = 2, 3, 40, 12, 2
+    p = oracle.Params(B=B, H=H, T=T, d=4, m=4, K=K, k_hat=kh, causal=True, grouping=1, geometry=1)
+    A = g.random((B, H, T, K))
+    A[0] = np.round(A[0] * 4) / 4
+    A[1, 2] *= 10.0
+    seq_len = np.array([T, 29], dtype=np.int32)
+    sel, idx, cnt = oracle.topk_mask(p, A, seq_len=seq_len)
+    for b in range(B):
+        for t in range(T):
+            if t >= seq_len[b]:
+                assert np.all(sel[b, :, t] == -1) and np.all(cnt[b, :, t] == 0)
+                continue
+            n_keys = t + 1
+            col_of_key = (np.arange(n_keys) * K) // n_keys
+            live = np.unique(col_of_key)
+            flat = np.array([(h, c) for h in range(H) for c in live])      # ascending h K + c
+            scores = np.array([A[b, h, t, c] for h, c in flat])
+            n = min(H * kh, len(flat))
+            order = np.argsort(-scores, kind="stable")[:n]
+            want = [sorted(int(c) for hh, c in flat[order] if hh == h) for h in range(H)]
+            for h in range(H):
+                got = sel[b, h, t][sel[b, h, t] >= 0].tolist()
+                assert got == want[h], (b, t, h)
+                keys = [int(j) for j in range(n_keys) if col_of_key[j] in got]
+                assert idx[b, h, t, :cnt[b, h, t]].tolist() == keys, (b, t, h)
