@@ -740,7 +740,7 @@ def test_row_width_with_per_batch_grouping_equals_sort_over_columns_that_hold_a_
     largest entries among the columns that hold a key of that row (stable library sort; ties to
     the lower h K + c), and every selected column expands to its own key range of the row."""
     g = np.random.default_rng(23)
-    B, H, T, K, kh = 2, 3, 40, 12, 2
+    B, H, T, K, kh = 2, 3, 40, 12, 5       # early rows: quota H k^ above the columns that hold a key
     p = oracle.Params(B=B, H=H, T=T, d=4, m=4, K=K, k_hat=kh, causal=True, grouping=1, geometry=1)
     A = g.random((B, H, T, K))
     A[0] = np.round(A[0] * 4) / 4
