@@ -482,13 +482,16 @@ def _random_row_width_cases(n, seed):
         k_budget = int(rng.choice([0, 0, 8, 33, 64]))
         pad = float(rng.choice([0.0, 0.3]))
         dtype = "f32" if rng.random() < 0.3 else "bf16"
-        out.append(_wl(f"rw_rnd{len(out)}_T{T}_K{K}_m{m}_kh{k_hat}_kb{k_budget}_p{int(pad > 0)}_{dtype}",
+        grouping = int(rng.random() < 0.3)
+        out.append(_wl(f"rw_rnd{len(out)}_T{T}_K{K}_m{m}_kh{k_hat}_kb{k_budget}_p{int(pad > 0)}_g{grouping}_{dtype}",
                        int(rng.integers(1, 3)), int(rng.integers(1, 4)), T, m, K, k_hat, k_budget=k_budget,
-                       pad_frac=pad, dtype=dtype, geometry=1))
+                       pad_frac=pad, dtype=dtype, grouping=grouping, geometry=1))
     return out
 
 
-ROW_WIDTH_CASES += _random_row_width_cases(12, 77)
+# SEA_RW_RANDOM_CASES / SEA_RW_RANDOM_SEED widen or move this draw for a one-off sweep
+ROW_WIDTH_CASES += _random_row_width_cases(int(os.environ.get("SEA_RW_RANDOM_CASES", "12")),
+                                           int(os.environ.get("SEA_RW_RANDOM_SEED", "77")))
 
 
 @pytest.mark.parametrize("wl", ROW_WIDTH_CASES, ids=lambda w: w.name)
