@@ -124,3 +124,19 @@ def test_row_stride_agrees_with_oracle_helper(sea):
         p = sea.SeaParams(1, 1, T, 64, 32, K, kh, k_budget=kb)
         po = oracle.Params(B=1, H=1, T=T, d=64, m=32, K=K, k_hat=kh, k_budget=kb)
         assert sea.sea_row_stride(p) == oracle.row_stride(po)
+
+
+def test_workspace_sizes_closed_forms(sea):
+    """Host arithmetic of the scratch sizes the stage entry points ask for."""
+    P = sea.SeaParams
+    a256 = lambda n: (n + 255) // 256 * 256
+    for (B, H, T) in [(1, 2, 128), (3, 5, 1000), (2, 12, 2048)]:
+        p = P(B, H, T, 64, 64, 8, 2)
+        assert sea.sea_flatcsr_workspace_bytes(p) == a256((B * T + 255) // 256 * 8)
+    # the attention stage on a mask needs scratch only where rows are grouped by column
+    assert sea.sea_mask_attn_workspace_bytes(P(1, 2, 2048, 64, 128, 128, 64)) == 0
+    assert sea.sea_mask_attn_workspace_bytes(P(1, 2, 1024, 64, 64, 32, 1, k_budget=16)) > 0
+    assert sea.sea_mask_attn_workspace_bytes(P(1, 2, 2048, 64, 128, 128, 64, geometry=1)) == 0   # not offered
+    # per-row width geometry: prefix table (T + 1) m fp64 per head dominates the estimator scratch
+    p1 = P(2, 3, 512, 64, 128, 32, 4, geometry=1)
+    assert sea.sea_workspace_bytes(p1) >= 2 * 3 * 513 * 128 * 8
