@@ -119,6 +119,10 @@ SMALL_CASES = [
     # K = 24: one mask word per row where the rows kernel holds two, 768 rows = 6 blocks of 128
     _wl("bf16_bucket_K24", 1, 2, 768, 64, 24, 1, k_budget=16),
     _wl("bf16_multi_K24_bidir", 1, 2, 768, 64, 24, 3, k_budget=24, causal=False),
+    # the largest K and m the library takes (1024 each), in both tensor types
+    _wl("bf16_max_K", 1, 1, 1024, 32, 1024, 100),
+    _wl("bf16_max_m", 1, 1, 256, 1024, 16, 3),
+    _wl("f32_max_K_max_m", 1, 1, 1100, 1024, 1024, 7, dtype="f32"),
     # whole columns of 256 keys: more keys per column than one staging step holds
     _wl("bf16_whole_w256_causal", 1, 2, 1024, 64, 4, 2),
     _wl("bf16_whole_w128_bidir_pad", 2, 1, 1024, 64, 8, 3, causal=False, pad_frac=0.3),
@@ -462,6 +466,7 @@ ROW_WIDTH_CASES = [
     _wl("rw_bf16_three_slots", 1, 2, 777, 256, 192, 8, geometry=1),
     _wl("rw_bf16_one_column", 1, 2, 256, 64, 8, 1, k_budget=4, geometry=1),
     _wl("rw_bf16_long", 1, 1, 8192, 128, 128, 4, k_budget=32, geometry=1),
+    _wl("rw_max_K", 1, 1, 1200, 64, 1024, 50, geometry=1),                     # sixteen column slots per lane
     replace(synth.get_workload("c2"), name="c2+row_width", geometry=1),      # full size, sampled rows
     # the paper's own setting: causal-per-batch selection in this geometry
     _wl("rw_grouped", 2, 4, 300, 64, 16, 3, grouping=1, geometry=1),
