@@ -209,6 +209,7 @@ GROUPED_CASES = [
     _wl("grp_bf16_budget", 1, 4, 512, 64, 16, 2, k_budget=16, grouping=1),
     _wl("grp_f32", 1, 3, 160, 64, 20, 4, dtype="f32", grouping=1),
     _wl("grp_bf16_big_slab", 1, 32, 256, 64, 256, 8, grouping=1),
+    _wl("grp_bf16_largest_slab", 1, 64, 256, 64, 256, 4, grouping=1),      # H K = 16384, the limit
 ]
 
 
