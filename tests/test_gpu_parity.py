@@ -748,6 +748,33 @@ def test_row_width_tiny_degenerate_and_causal(sea, dtype):
         assert torch.equal(a[k][:, :, :t0 + 1], b[k][:, :, :t0 + 1]), k
 
 
+@pytest.mark.parametrize("wl", [_wl("peaked_tiles", 1, 2, 512, 128, 32, 8),
+                                _wl("peaked_buckets", 1, 2, 1024, 64, 16, 1, k_budget=32),
+                                _wl("peaked_multi", 1, 2, 1024, 64, 64, 3, k_budget=48),
+                                _wl("peaked_lists", 1, 2, 300, 64, 17, 5),
+                                _wl("peaked_f32", 1, 2, 200, 64, 25, 6, dtype="f32"),
+                                _wl("peaked_row_width", 1, 2, 400, 64, 32, 6, geometry=1)],
+                         ids=lambda w: w.name)
+def test_large_logits(sea, wl):
+    """Queries and keys scaled up so that logits reach several tens and the softmax is sharply
+    peaked: the streaming softmax (reference maximum refreshed only on large growth, partial
+    results merged across buckets) and the feature exponents must hold the same tolerances."""
+    x = synth.make_inputs(wl)
+    for k in "QK":
+        x[k] = (x[k].float() * 1.8).to(x[k].dtype)
+    logits = (x["Q"].float() @ x["K"].float().transpose(-1, -2)) * wl.scale
+    assert logits.abs().max() > 40
+    p, xd, g = _gpu_forward(sea, wl, x)
+    po, o = _oracle_forward(wl, x)
+    tol = TOL[wl.dtype]
+    A_g = g["A_hat"].numpy().astype(np.float64)
+    assert_close(A_g, o["A_hat"], tol, "A_hat")
+    sel_s, idx_s, cnt_s = oracle.topk_mask(po, A_g)
+    assert np.array_equal(g["idx"].numpy(), idx_s) and np.array_equal(g["cnt"].numpy(), cnt_s)
+    O_s = oracle.sparse_attn(po, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), idx_s, cnt_s)
+    assert_close(to_np64(g["O"]), O_s, tol, "O (stage)")
+
+
 def test_optional_outputs_do_not_change_results(sea):
     wl = _wl("noaux", 1, 2, 192, 64, 24, 5)
     x = synth.make_inputs(wl)
