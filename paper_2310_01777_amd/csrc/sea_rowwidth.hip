@@ -10,7 +10,7 @@
 //   prefix_kernel<.., false> per (head, chunk of keys): chunk totals of phi(k), fp64 running sum
 //   chunk_base_kernel        per head: exclusive scan of the chunk totals (fp64)
 //   prefix_kernel<.., true>  same walk again, writes P = chunk base + running sum
-//   rows_kernel              one wavefront per two consecutive rows: phi(q_t), the K gathers of
+//   rows_kernel              one wavefront per two or four consecutive rows: phi(q_t), the K gathers of
 //                            neighbouring prefix rows, their differences, row norm
 // Features, prefixes and dot products are fp64 for both tensor types (see PrefixOfBf16); nothing is
 // rounded to bf16 here.
@@ -21,7 +21,6 @@ namespace {
 
 constexpr int kStage = 64;        // keys staged in LDS at a time
 constexpr int kMaxChunks = 64;    // chunks per head
-constexpr int kRowsPerWave = 2;
 constexpr int kRowWaves = 4;
 // Arithmetic and prefix element type for bf16 tensors.  float makes the rows kernel 1.7x faster
 // (half the gathered bytes) but a difference of fp32 prefixes cannot resolve scores below ~1e-6 of
@@ -156,10 +155,10 @@ __device__ __forceinline__ F wave_max(F v) {
   return v;
 }
 
-// MU = m / 64 consecutive features per lane (feature = lane MU + u: a lane's share of a prefix
+// R consecutive rows per wavefront, MU = m / 64 consecutive features per lane (feature = lane MU + u: a lane's share of a prefix
 // row is one vector load, a wavefront's the whole row), SLOTS = ceil(K / 64) column slots per
 // lane (column = q 64 + lane).  W^T sits in LDS in the tensors' own element type, [e][i].
-template <typename F, typename TI, int MU, int SLOTS>
+template <typename F, typename TI, int MU, int SLOTS, int R>
 __global__ __launch_bounds__(kRowWaves* kWave) void rows_kernel(Shape s, const TI* __restrict__ Q,
                                                                 const TI* __restrict__ W,
                                                                 const F* __restrict__ P, float* __restrict__ A_hat) {
@@ -174,9 +173,8 @@ __global__ __launch_bounds__(kRowWaves* kWave) void rows_kernel(Shape s, const T
   const int lane = threadIdx.x & 63;
   const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
   const uint32_t lb = xcd_contiguous(blockIdx.x, gridDim.x);
-  const int64_t first = (static_cast<int64_t>(lb) * kRowWaves + (threadIdx.x >> 6)) * kRowsPerWave;
+  const int64_t first = (static_cast<int64_t>(lb) * kRowWaves + (threadIdx.x >> 6)) * R;
   const F rs = static_cast<F>(sqrtf(s.scale));
-  constexpr int R = kRowsPerWave;
   // The wavefront's R consecutive rows walk the columns together: their boundaries of a column
   // are at most R - 1 keys apart, so most of their prefix rows are the same cache lines.
   F phi[R][MU];
@@ -308,12 +306,15 @@ template <typename F, typename TI, int MU>
 hipError_t launch_rows(const Shape& s, const TI* Q, const TI* W, const F* P,
                        float* A_hat, hipStream_t st) {
   const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
-  const int64_t per_block = kRowWaves * kRowsPerWave;
+  // rows a wavefront walks together: four while a lane's share of a prefix row is at most two
+  // elements, two for m = 256 (four elements), where more rows would cost a wave of occupancy
+  constexpr int R = MU <= 2 ? 4 : 2;
+  const int64_t per_block = kRowWaves * R;
   const dim3 grid(static_cast<uint32_t>((nrows + per_block - 1) / per_block));
   const size_t lds = static_cast<size_t>(s.m) * kHeadDim * sizeof(TI);
   const int slots = (s.K + kWave - 1) / kWave;
 #define SEA_RW_ROWS(SL)                                                                                      \
-  hipLaunchKernelGGL((rows_kernel<F, TI, MU, SL>), grid, dim3(kRowWaves* kWave), lds, st, s, Q, W, P, A_hat)
+  hipLaunchKernelGGL((rows_kernel<F, TI, MU, SL, R>), grid, dim3(kRowWaves* kWave), lds, st, s, Q, W, P, A_hat)
   if (slots <= 1) SEA_RW_ROWS(1);
   else if (slots <= 2) SEA_RW_ROWS(2);
   else if (slots <= 4) SEA_RW_ROWS(4);
