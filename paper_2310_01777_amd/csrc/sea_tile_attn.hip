@@ -28,6 +28,13 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+// 64-bit LDS read with the 16-bit transpose across each group of 16 lanes (ds_read_b64_tr_b16)
+__device__ __forceinline__ bf16x4 lds_transpose4(const uint16_t* p) {
+  const shortx4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) shortx4*)(p));
+  return __builtin_bit_cast(bf16x4, r);
+}
 typedef float floatx2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -87,7 +94,8 @@ __device__ __forceinline__ int32_t compact_count(int32_t jmax, int32_t rlog, int
 
 constexpr int kChunk = 64;   // keys staged in LDS per step (two 32-key MFMA sub-chunks)
 constexpr int kKRow = 72;    // halfwords per staged K row: 128 B + 16 B pad, conflict-free b128 reads
-constexpr int kVRow = 68;    // halfwords per staged V^T row: 128 B + 8 B pad, conflict-free b64 reads
+constexpr int kVRow = 64;    // halfwords per staged V row: no padding; the 64-byte halves of rows 2, 3 (mod 4)
+                             // are exchanged, which makes the four rows of a transpose read hit distinct banks
 
 // Block = 4 waves = 128 consecutive query rows of one head (32 per wave).  The block walks the
 // compact key list in steps of 64 keys; each step's K and V rows are fetched once with full-line
@@ -105,7 +113,7 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   constexpr bool DENSE = MODE != 0;   // no per-column bits to look up
   constexpr bool BUCKET = MODE == 2;
   __shared__ __attribute__((aligned(16))) uint16_t Ks[2][kChunk * kKRow];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[2][kHeadDim * kVRow];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[2][kChunk * kVRow];
   // selected-column bits of the 128 rows, (KW + 1) words per row (K <= 1024: at most 16.5 KB)
   extern __shared__ uint32_t Ms[];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -190,11 +198,11 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   const int32_t my_jmax = a.causal ? min(t, len - 1) : len - 1;
   const int32_t nsteps = (u_end_wg - ubase + kChunk - 1) / kChunk;
 
-  // staging roles: 16-byte part tid & 7 of K rows (tid >> 3) and (tid >> 3) + 32 of the step, and
-  // of the V rows of the key pair 2 (tid >> 3), 2 (tid >> 3) + 1: a pair packs into one 32-bit
-  // word per dimension of the transposed tile.  Slots past the list re-read its last key; their
-  // scores are masked.
+  // staging roles: 16-byte part tid & 7 of the K and V rows (tid >> 3) and (tid >> 3) + 32 of the
+  // step.  V is parked as it lies in memory; the product reads it through the LDS transpose read.
+  // Slots past the list re-read its last key; their scores are masked.
   const int srow = tid >> 3, spart = tid & 7;
+  const int vpart = spart ^ (((srow >> 1) & 1) << 2);  // V rows 2, 3 (mod 4): halves exchanged
   uint4 kreg0, kreg1, vreg0, vreg1;
   // With at most 64 keys per column a step of 64 compact keys advances every slot's position by
   // the same amount, so the four row offsets (bytes inside the head, 32 bits) just step by a
@@ -206,8 +214,6 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   const uint32_t off_step = linear ? static_cast<uint32_t>((kChunk >> a.rlog) * a.w) * row_bytes : 0u;
   uint32_t offa = static_cast<uint32_t>(pos_of(ubase + srow, a.rlog, a.w)) * row_bytes + part_bytes;
   uint32_t offb = static_cast<uint32_t>(pos_of(ubase + srow + 32, a.rlog, a.w)) * row_bytes + part_bytes;
-  uint32_t offc = static_cast<uint32_t>(pos_of(ubase + 2 * srow, a.rlog, a.w)) * row_bytes + part_bytes;
-  uint32_t offd = static_cast<uint32_t>(pos_of(ubase + 2 * srow + 1, a.rlog, a.w)) * row_bytes + part_bytes;
   const char* Kb = reinterpret_cast<const char*>(Kh);
   const char* Vb = reinterpret_cast<const char*>(Vh);
 #define SEA_SLOT_OFF(slot_, step_)                                                                   \
@@ -217,29 +223,19 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
     if (!linear) {                                                                                   \
       offa = SEA_SLOT_OFF(srow, step_);                                                              \
       offb = SEA_SLOT_OFF(srow + 32, step_);                                                         \
-      offc = SEA_SLOT_OFF(2 * srow, step_);                                                          \
-      offd = SEA_SLOT_OFF(2 * srow + 1, step_);                                                      \
     }                                                                                                \
     kreg0 = *reinterpret_cast<const uint4*>(Kb + min(offa, off_max));                                \
     kreg1 = *reinterpret_cast<const uint4*>(Kb + min(offb, off_max));                                \
-    vreg0 = *reinterpret_cast<const uint4*>(Vb + min(offc, off_max));                                \
-    vreg1 = *reinterpret_cast<const uint4*>(Vb + min(offd, off_max));                                \
-    offa += off_step; offb += off_step; offc += off_step; offd += off_step;                          \
+    vreg0 = *reinterpret_cast<const uint4*>(Vb + min(offa, off_max));                                \
+    vreg1 = *reinterpret_cast<const uint4*>(Vb + min(offb, off_max));                                \
+    offa += off_step; offb += off_step;                                                              \
   } while (0)
-  // dimensions 8 spart + e, e + 1 of the key pair: low halves of both keys, then high halves
-#define SEA_PARK_V1(stage_, e_, w0_, w1_)                                                            \
-  *reinterpret_cast<uint32_t*>(&Vs[stage_][(spart * 8 + (e_)) * kVRow + 2 * srow]) =                  \
-      __builtin_amdgcn_perm(w1_, w0_, 0x05040100u);                                                  \
-  *reinterpret_cast<uint32_t*>(&Vs[stage_][(spart * 8 + (e_) + 1) * kVRow + 2 * srow]) =              \
-      __builtin_amdgcn_perm(w1_, w0_, 0x07060302u);
 #define SEA_PARK(stage_)                                                                             \
   do {                                                                                               \
     *reinterpret_cast<uint4*>(&Ks[stage_][srow * kKRow + spart * 8]) = kreg0;                         \
     *reinterpret_cast<uint4*>(&Ks[stage_][(srow + 32) * kKRow + spart * 8]) = kreg1;                  \
-    SEA_PARK_V1(stage_, 0, vreg0.x, vreg1.x)                                                         \
-    SEA_PARK_V1(stage_, 2, vreg0.y, vreg1.y)                                                         \
-    SEA_PARK_V1(stage_, 4, vreg0.z, vreg1.z)                                                         \
-    SEA_PARK_V1(stage_, 6, vreg0.w, vreg1.w)                                                         \
+    *reinterpret_cast<uint4*>(&Vs[stage_][srow * kVRow + vpart * 8]) = vreg0;                         \
+    *reinterpret_cast<uint4*>(&Vs[stage_][(srow + 32) * kVRow + vpart * 8]) = vreg1;                  \
   } while (0)
 
   floatx16 oacc[2];
@@ -366,14 +362,19 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
         const bf16x4 hi = __builtin_shufflevector(h[2], h[3], 0, 1, 2, 3);
         bp[c2] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       }
-      // O^T += V^T P^T; V^T fragments in the key order of the P registers
+      // O^T += V^T P^T; V^T fragments in the key order of the P registers.  The LDS transpose
+      // read hands lane i of a 16-lane group element i % 4 of the 8 bytes that lanes 4 e + i / 4
+      // (e = 0..3) of the group point at: with lane r pointing at dims 4 (r % 4) .. + 3 of key
+      // r / 4, lane i receives dim i of keys 0..3 -- four consecutive keys of one dimension.
+      // Lanes 8..15 of a group point at rows 2, 3 (mod 4), whose halves are stored exchanged.
 #pragma unroll
       for (int mt = 0; mt < 2; ++mt) {
-        const uint16_t* Vr = &Vs[stage][(32 * mt + ql) * kVRow + 32 * sc + 4 * g];
+        const uint16_t* Vr = &Vs[stage][(32 * sc + 4 * g + ((ql & 15) >> 2)) * kVRow +
+                                        32 * (mt ^ ((ql >> 3) & 1)) + (ql & 16) + 4 * (ql & 3)];
 #pragma unroll
         for (int c2 = 0; c2 < 2; ++c2) {
-          const bf16x4 lo = *reinterpret_cast<const bf16x4*>(Vr + 16 * c2);
-          const bf16x4 hi = *reinterpret_cast<const bf16x4*>(Vr + 16 * c2 + 8);
+          const bf16x4 lo = lds_transpose4(Vr + (16 * c2) * kVRow);
+          const bf16x4 hi = lds_transpose4(Vr + (16 * c2 + 8) * kVRow);
           const bf16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bp[c2], oacc[mt], 0, 0, 0);
         }
@@ -385,7 +386,6 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
 #undef SEA_FETCH
 #undef SEA_SLOT_OFF
 #undef SEA_PARK
-#undef SEA_PARK_V1
   l_run = half_sum(l_run);
   if (t >= 0 && t < a.T) {
     const float inv = (row_active && l_run > 0.f) ? 1.f / l_run : 0.f;
