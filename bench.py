@@ -21,7 +21,7 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 # HBM bytes per launch of the sparse-attention kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (scaled by the copy-kernel factors 2.0 / 1.0); see profiles/sea_forward_<workload>.md
-MEASURED_TRAFFIC_BYTES = {"c2": 39.5e6 + 12.6e6, "c3": 260.6e6 + 67.1e6, "c4_T32768": 191.9e6 + 134.2e6,
+MEASURED_TRAFFIC_BYTES = {"c2": 39.5e6 + 12.6e6, "c3": 262.4e6 + 67.1e6, "c4_T32768": 189.7e6 + 134.2e6,
                           "c6_T131072": 265.8e6 + 201.5e6}
 
 
