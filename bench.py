@@ -28,8 +28,8 @@ MEASURED_TRAFFIC_BYTES = {"c2": 39.5e6 + 12.6e6, "c3": 262.4e6 + 67.1e6, "c4_T32
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)   # c2: about 20 ms of timed work
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2",
                     help="c1..c5 or c4_T<len>; c2 is the configuration the metric is quoted on")
     ap.add_argument("--grouping", choices=["per_query", "causal_per_batch"], default="per_query",
