@@ -67,21 +67,26 @@ class Params:
 _lib = None
 
 
+def _open(path):
+    """Load a build of the oracle (the tests also load deliberately broken builds this way)."""
+    lib = ctypes.CDLL(path)
+    lib.ref_k_hat.restype = ctypes.c_int32
+    lib.ref_k_hat.argtypes = [ctypes.c_int32] * 3
+    lib.ref_row_stride.restype = ctypes.c_int32
+    lib.ref_row_stride.argtypes = [ctypes.POINTER(_RefParams)]
+    lib.ref_sel_stride.restype = ctypes.c_int32
+    lib.ref_sel_stride.argtypes = [ctypes.POINTER(_RefParams)]
+    lib.ref_round8.restype = ctypes.c_double
+    lib.ref_round8.argtypes = [ctypes.c_double]
+    for name in ("ref_estimate", "ref_topk_mask", "ref_sparse_attn", "ref_forward", "ref_output_mix"):
+        getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
 def _load():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
-        lib.ref_k_hat.restype = ctypes.c_int32
-        lib.ref_k_hat.argtypes = [ctypes.c_int32] * 3
-        lib.ref_row_stride.restype = ctypes.c_int32
-        lib.ref_row_stride.argtypes = [ctypes.POINTER(_RefParams)]
-        lib.ref_sel_stride.restype = ctypes.c_int32
-        lib.ref_sel_stride.argtypes = [ctypes.POINTER(_RefParams)]
-        lib.ref_round8.restype = ctypes.c_double
-        lib.ref_round8.argtypes = [ctypes.c_double]
-        for name in ("ref_estimate", "ref_topk_mask", "ref_sparse_attn", "ref_forward", "ref_output_mix"):
-            getattr(lib, name).restype = ctypes.c_int
-        _lib = lib
+        _lib = _open(build())
     return _lib
 
 

@@ -201,6 +201,57 @@ def test_forward_matches_oracle(sea, wl):
     print(f"    rows differing at near-ties: {(~same).sum()} / {same.size}", flush=True)
 
 
+# ---- bf16 against the PLAIN definition (no rounding points in the oracle) ----
+# Each of phi(q), the column sums and the own-column key features is rounded to bf16 once: at most
+# 2^-8 relative per element, so a score (a sum of m positive products of two rounded factors) moves
+# by at most 2^-7 of itself and two scores can change order only when their relative gap is below
+# 2^-6.  That is the near-tie window here; the share of such rows is asserted per configuration.
+PLAIN_GAP = 2.0 ** -6
+PLAIN_CASES = [
+    (_wl("plain_causal", 2, 3, 320, 128, 40, 9), None),
+    (_wl("plain_bidir_pad", 3, 2, 256, 128, 32, 8, causal=False, pad_frac=0.3), None),
+    (_wl("plain_w32_causal_pad", 2, 2, 640, 128, 20, 6, k_budget=48, pad_frac=0.3), None),
+    (_wl("plain_m256", 1, 2, 1024, 256, 256, 31), None),
+    (_wl("plain_ragged_cols", 1, 2, 300, 96, 17, 5), None),
+    (_wl("plain_bucket", 1, 2, 2048, 64, 16, 1, k_budget=32), None),
+    (synth.get_workload("c2"), (0, 4)),          # full size, all rows of the first heads
+    (synth.get_workload("c5"), (0, 8)),
+    (synth.get_workload("c3"), (0, 2)),
+]
+
+
+@pytest.mark.parametrize("wl,heads", PLAIN_CASES, ids=lambda v: v.name if hasattr(v, "name") else None)
+def test_bf16_forward_against_the_plain_definition(sea, wl, heads):
+    """The bf16 HIP path against the oracle with NO reduced-precision points: FAVOR+ with the
+    stretched identity exactly as Sec. 3 "Performer (FAVOR+)" and Sec. 3.1 "Attention Matrix
+    Estimation" write it, in fp64.  A_hat and O within the bf16 tolerance; the selection identical
+    except on a bounded share of rows whose gap in the plain oracle is a near-tie."""
+    x = synth.make_inputs(wl)
+    p, xd, g = _gpu_forward(sea, wl, x)
+    po = oracle_params(wl, round8=False)
+    sl = None if x["seq_len"] is None else x["seq_len"].numpy()
+    o = oracle.forward(po, to_np64(x["Q"]), to_np64(x["K"]), to_np64(x["V"]), to_np64(x["W"]), seq_len=sl,
+                       heads=heads)
+    lo, hi = heads if heads is not None else (0, wl.B * wl.H)
+    pick = lambda a: a.reshape((wl.B * wl.H,) + a.shape[2:])[lo:hi][None]
+    A_g, A_o = pick(g["A_hat"].numpy()).astype(np.float64), pick(o["A_hat"])
+    assert_close(A_g, A_o, TOL["bf16"], "A_hat vs plain")
+    sel_g, sel_o = pick(g["sel"].numpy()), pick(o["sel"])
+    same = (sel_g == sel_o).all(-1)
+    ncand = pick(candidate_counts(wl.B, wl.H, wl.T, wl.K, wl.causal, sl))
+    gaps = selection_gaps(A_o, sel_o, ncand)
+    bad = ~same & ~(gaps < PLAIN_GAP)
+    assert not bad.any(), f"{bad.sum()} rows differ with a plain-oracle gap >= 2^-6 (largest {gaps[~same].max():.3g})"
+    frac = float((~same).mean())
+    assert frac <= 0.015, f"{wl.name}: {(~same).sum()} of {same.size} rows select differently from the plain oracle"
+    assert np.array_equal(pick(g["idx"].numpy())[same], pick(o["idx"])[same])
+    Og, Oo = pick(to_np64(g["O"])).copy(), pick(o["O"]).copy()
+    Og[~same] = 0.0
+    Oo[~same] = 0.0
+    assert_close(Og, Oo, TOL["bf16"], "O vs plain")
+    print(f"    rows differing from the plain oracle: {(~same).sum()} / {same.size} ({100 * frac:.2f} %)", flush=True)
+
+
 GROUPED_CASES = [
     _wl("grp_bf16_tiled", 2, 4, 256, 64, 32, 6, grouping=1),
     _wl("grp_bf16_c2_like", 1, 12, 512, 128, 32, 16, grouping=1),
@@ -799,7 +850,8 @@ def test_optional_outputs_do_not_change_results(sea):
 
 # ---- full-size configurations, in the launch configuration bench.py times, on sampled rows ----
 
-FULL = ["c1", "c2", "c3", "c5", "c4_T8192", "c4_T32768", "c6_T131072", "c6c_T65536", "c7_T32768"]
+FULL = ["c1", "c2", "c3", "c5", "c4_T4096", "c4_T8192", "c4_T16384", "c4_T32768", "c6_T131072", "c6c_T65536",
+        "c7_T32768"]
 
 
 @pytest.mark.parametrize("name", FULL)
@@ -818,9 +870,9 @@ def test_full_size_sampled_rows(sea, name):
     w = wl.T // wl.K
     edges = [0, 1, 15, 16, 127, 128, w - 1, w, 3 * w + 127, 3 * w + 128, wl.T - w, wl.T - 1]  # tile, block, column edges
     rows = np.unique(np.concatenate([[r for r in edges if 0 <= r < wl.T],
-                                     rng.integers(0, wl.T, 40)])).astype(np.int32)
+                                     rng.integers(0, wl.T, 200)])).astype(np.int32)
     rows_d = torch.as_tensor(rows.astype(np.int64), device="cuda")
-    heads = sorted(set([0, wl.B * wl.H - 1] + rng.integers(0, wl.B * wl.H, 3).tolist()))
+    heads = sorted(set([0, wl.B * wl.H - 1] + rng.choice(wl.B * wl.H, 7, replace=False).tolist()))
     tol = TOL[wl.dtype]
     n_diff = n_rows = 0
     for bh in heads:
@@ -861,3 +913,5 @@ def test_full_size_sampled_rows(sea, name):
     assert bool((pop == (out["sel"] >= 0).sum(-1)).all())      # mask bits and sel agree in number
     assert bool((pop <= wl.k_hat).all())
     print(f"    sampled rows differing at near-ties: {n_diff} / {n_rows}", flush=True)
+    # the exempted share is bounded per configuration, not only reported
+    assert n_diff <= max(2, int(0.02 * n_rows)), f"{wl.name}: {n_diff} of {n_rows} sampled rows exempted as near-ties"

@@ -357,6 +357,125 @@ def test_estimate_literal_favor_with_stretched_identity():
             np.testing.assert_allclose(A[0, h], raw / raw.sum(-1, keepdims=True), rtol=1e-11)
 
 
+def _solve_for_features(a, b):
+    """A 2-vector x with exp(x_0 - |x|^2/2) = a and exp(x_1 - |x|^2/2) = b (W = I_2, scale 1): with
+    r = |x|^2/2, x = (ln a + r, ln b + r) and 2 r^2 + 2 r (ln a + ln b - 1) + ln^2 a + ln^2 b = 0."""
+    la, lb = np.log(a), np.log(b)
+    half = la + lb - 1.0
+    r = (-half - np.sqrt(half * half - 2.0 * (la * la + lb * lb))) / 2.0
+    return np.array([la + r, lb + r])
+
+
+def test_reduced_precision_points_hand_built_case():
+    """Where the reduced-precision mode rounds (Sec. 3 "Performer (FAVOR+)", Sec. 3.1 "Attention
+    Matrix Estimation", read for bf16 tensors): phi(q_t); the finished column sums phi(K)^T V_I;
+    and, for a causal row's own column, each phi(k_j) before the key-by-key sum.  T = 4, K = 2,
+    m = d = 2, W = I: inputs are solved so that the features are the round numbers below, and the
+    bf16 neighbours of those numbers are written out by hand (n / 2^e).  Rounding a different
+    quantity (the own column after its sum, the state key by key, phi(q) not at all) moves the
+    expected values by 1e-4 or more, the oracle must agree to 1e-12."""
+    fk = [(1.3, 0.7), (0.9, 1.1), (1.23, 0.57), (0.81, 1.37)]       # phi(k_0..3)
+    fq = [(0.6, 0.8), (0.52, 0.77), (0.37, 0.93), (0.9, 0.45)]      # phi(q_0..3), all below 1: shift 0
+    bf = {1.3: 166 / 128, 0.7: 179 / 256, 0.9: 230 / 256, 1.1: 141 / 128, 1.23: 157 / 128,
+          0.57: 146 / 256, 0.81: 207 / 256, 1.37: 175 / 128, 0.37: 189 / 512, 0.93: 238 / 256,
+          0.45: 230 / 512, 0.6: 154 / 256, 0.8: 205 / 256, 0.52: 133 / 256, 0.77: 197 / 256,
+          2.2: 141 / 64, 1.8: 230 / 128, 2.04: 131 / 64, 1.94: 248 / 128}
+    for v, r in bf.items():   # the hand-written neighbours are the library's bf16 casts
+        assert float(torch.tensor(v, dtype=torch.float32).to(torch.bfloat16)) == r, v
+    K = np.array([_solve_for_features(*f) for f in fk])[None, None]
+    Q = np.array([_solve_for_features(*f) for f in fq])[None, None]
+    W = np.eye(2)
+    state0 = (bf[2.2], bf[1.8])      # bf16(1.3 + 0.9), bf16(0.7 + 1.1): rounded after the sum
+    state1 = (bf[2.04], bf[1.94])    # bf16(1.23 + 0.81), bf16(0.57 + 1.37)
+    dot = lambda u, v: u[0] * v[0] + u[1] * v[1]
+    p = oracle.Params(B=1, H=1, T=4, d=2, m=2, K=2, k_hat=1, causal=True, scale=1.0, round8=True)
+    A = oracle.estimate(p, Q, K, W)[0, 0]
+    for t in range(4):
+        q = (bf[fq[t][0]], bf[fq[t][1]])
+        if t < 2:      # own column 0: its keys 0..t, each rounded, then summed
+            own = tuple(sum(bf[fk[j][i]] for j in range(t + 1)) for i in range(2))
+            want = np.array([dot(q, own), 0.0])
+        else:          # column 0 from the rounded state; own column 1: keys 2..t rounded one by one
+            own = tuple(sum(bf[fk[j][i]] for j in range(2, t + 1)) for i in range(2))
+            want = np.array([dot(q, state0), dot(q, own)])
+        np.testing.assert_allclose(A[t], want / want.sum(), rtol=0, atol=1e-12)
+    # t = 3 tells "own column rounded after its sum" apart, t = 2 "phi(q) not rounded"
+    q3 = (bf[0.9], bf[0.45])
+    wrong_own = dot(q3, (float(torch.tensor(1.23 + 0.81).to(torch.bfloat16)), float(torch.tensor(0.57 + 1.37).to(torch.bfloat16))))
+    assert abs(dot(q3, state0) / (dot(q3, state0) + wrong_own) - A[3, 0]) > 5e-4
+    pb = oracle.Params(B=1, H=1, T=4, d=2, m=2, K=2, k_hat=1, causal=False, scale=1.0, round8=True)
+    Ab = oracle.estimate(pb, Q, K, W)[0, 0]
+    for t in range(4):
+        q = (bf[fq[t][0]], bf[fq[t][1]])
+        want = np.array([dot(q, state0), dot(q, state1)])
+        np.testing.assert_allclose(Ab[t], want / want.sum(), rtol=0, atol=1e-12)
+    # and the plain mode on the same inputs is the unrounded arithmetic
+    pp = oracle.Params(B=1, H=1, T=4, d=2, m=2, K=2, k_hat=1, causal=False, scale=1.0)
+    Ap = oracle.estimate(pp, Q, K, W)[0, 0]
+    for t in range(4):
+        want = np.array([dot(fq[t], (2.2, 1.8)), dot(fq[t], (2.04, 1.94))])
+        np.testing.assert_allclose(Ap[t], want / want.sum(), rtol=0, atol=1e-12)
+
+
+def test_reduced_precision_points_with_library_casts():
+    """The same three rounding points on a random layer, with the library's bf16 cast applied to
+    exactly those quantities inside a matmul formulation through the T x T kernel matrix (causal:
+    whole columns from the rounded state, the row's own column from rounded per-key features)."""
+    B, H, T, d, m, Kc = 1, 2, 48, 6, 16, 6
+    Q, K, _ = _rand_qkv(B, H, T, d, seed=18, std=0.8)
+    W = synth.gaussian_orthogonal(m, d, 3).numpy().astype(np.float64)
+    scale = 0.4
+    cast = lambda a: torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    col = (np.arange(T) * Kc) // T
+    VI = np.eye(Kc)[col]
+    for causal in (False, True):
+        p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=Kc, k_hat=2, causal=causal, scale=scale, round8=True)
+        A = oracle.estimate(p, Q, K, W)
+        for h in range(H):
+            x, y = np.sqrt(scale) * Q[0, h], np.sqrt(scale) * K[0, h]
+            aq = x @ W.T - 0.5 * (x * x).sum(-1, keepdims=True)
+            # power-of-two row scale: exact in every format, cancels in the normaliser
+            fq = np.exp(aq - np.ceil(aq.max(-1, keepdims=True) / np.log(2.0)) * np.log(2.0))
+            fk = np.exp(y @ W.T - 0.5 * (y * y).sum(-1, keepdims=True))
+            # fp32 casts before the bf16 one would round twice; 0.5 ulp(fp32) << 0.5 ulp(bf16), and
+            # the inputs are generic, so the double rounding never lands on a bf16 tie here
+            fq_r, fk_r, state_r = cast(fq), cast(fk), cast(fk.T @ VI)
+            raw = fq_r @ state_r
+            if causal:
+                own = np.tril(fq_r @ fk_r.T) * (col[:, None] == col[None, :])
+                raw = np.where(np.arange(Kc)[None, :] < col[:, None], raw, 0.0)
+                raw[np.arange(T), col] = own.sum(-1)
+            np.testing.assert_allclose(A[0, h], raw / raw.sum(-1, keepdims=True), rtol=1e-9)
+
+
+@pytest.mark.parametrize("wl", [
+    synth.Workload("r8_causal_wide_columns", 1, 4, 1024, 64, 128, 32, 8, 0, True, "bf16", 8),
+    synth.Workload("r8_bidir_padded", 3, 2, 512, 64, 64, 32, 8, 0, False, "bf16", 8, pad_frac=0.3)],
+    ids=lambda w: w.name)
+def test_reduced_precision_mode_stays_close_to_the_plain_definition(wl):
+    """The bf16 contract is a perturbation of the plain fp64 definition, nothing else: per head
+    the two estimates differ by at most 2^-7 of the largest entry (a few bf16 half-units, averaged
+    down by the m-term sums), at least 99 % of the rows select the same columns, and rows with the
+    same selection give the same output.  A rounding applied to a quantity with a wide dynamic
+    range (logits, un-shifted features, prefix states of many keys) breaks these bounds."""
+    x = synth.make_inputs(wl)
+    f = lambda t: t.to(torch.float64).numpy()
+    sl = None if x["seq_len"] is None else x["seq_len"].numpy()
+    out = []
+    for r8 in (False, True):
+        p = oracle.Params(B=wl.B, H=wl.H, T=wl.T, d=wl.d, m=wl.m, K=wl.K, k_hat=wl.k_hat, causal=wl.causal,
+                          scale=wl.scale, round8=r8)
+        out.append(oracle.forward(p, f(x["Q"]), f(x["K"]), f(x["V"]), f(x["W"]), seq_len=sl))
+    plain, r8 = out
+    A0 = plain["A_hat"].reshape(wl.B * wl.H, -1)
+    A1 = r8["A_hat"].reshape(wl.B * wl.H, -1)
+    assert (np.abs(A1 - A0).max(1) <= 2.0 ** -7 * np.abs(A0).max(1)).all()
+    assert not np.array_equal(A0, A1)                       # the mode does round something
+    same = (plain["sel"] == r8["sel"]).all(-1)
+    assert same.mean() >= 0.99, same.mean()
+    assert np.array_equal(plain["O"][same], r8["O"][same])
+
+
 def test_selection_invariant_to_row_scaling_of_queries_features():
     """A positive per-row factor on phi(Q) (e.g. any stabiliser) cancels in the normaliser:
     scaling q_t changes |x|^2 but A_hat rows still sum to one and the oracle's power-of-two row
