@@ -3,13 +3,17 @@
 
 A step is one sea_forward call (feature maps, key-side state, estimate contraction, per-row
 top-k^ + mask expansion, sparse attention) over one batch of synthetic Q, K, V already resident
-in HBM.  Prints ONE JSON line: tokens/s per attention layer, the roofline figure of the dominant
-kernel (sparse attention, timed with HIP events on the launch stream inside the timed region),
-and the CPU oracle timed on this machine's host cores on a bounded sample of the same workload.
+in HBM.  Prints ONE JSON line: tokens/s per attention layer on the largest configuration of the
+metric (c4 at T = 32768 unless --workload says otherwise), the roofline figure of the kernel that
+takes the largest share of the step (timed with HIP events on the launch stream), a sweep over the
+other configurations, and the CPU oracle timed on this machine's host cores on a bounded sample
+of the same workload.
 """
 import argparse
+import dataclasses
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -17,27 +21,33 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
-MFMA_BF16_PEAK_TFLOPS = 2500.0
-# HBM bytes per launch of the sparse-attention kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (scaled by the copy-kernel factors 2.0 / 1.0); see profiles/sea_forward_<workload>.md
-MEASURED_TRAFFIC_BYTES = {"c2": 39.5e6 + 12.6e6, "c3": 262.4e6 + 67.1e6, "c4_T32768": 189.7e6 + 134.2e6,
-                          "c6_T131072": 265.8e6 + 201.5e6}
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # dense bf16 matrix cores
+FP64_PEAK_TFLOPS = 78.6          # fp64 vector / matrix
+DEFAULT_WORKLOAD = "c4_T32768"
+SWEEP = ("c1", "c2", "c3", "c4_T4096", "c4_T8192", "c4_T16384", "c5")
+# HBM bytes per launch (fetched, written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# script, scaled by the copy-kernel factors; they cannot be read inside this process, so they are
+# quoted from the committed summary and only for the workload and kernel that summary covers.
+TRAFFIC_FROM_PROFILES = {}
+TRAFFIC_SOURCE = "profiles/pmc_traffic_c4_T32768.md"
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)   # c2: about 20 ms of timed work
+    ap.add_argument("--steps", type=int, default=200)   # c4_T32768: about 0.2 s of timed work
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2",
-                    help="c1..c5 or c4_T<len>; c2 is the configuration the metric is quoted on")
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD,
+                    help="c1..c5, c4_T<len>, c6_T<len>, c6c_T<len>, c7_T<len>; the default is the largest "
+                         "single-GPU configuration of the metric (T = 32768)")
     ap.add_argument("--grouping", choices=["per_query", "causal_per_batch"], default="per_query",
                     help="top-k^ grouping (Sec. 3.1); the headline metric uses per_query")
     ap.add_argument("--geometry", choices=["fixed", "row_width"], default="fixed",
                     help="how the K columns map to keys: the same key buckets for every row (headline), or "
                          "each causal row resized to its own t + 1 keys (App. A.4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the short runs of the other configurations")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU-work budget of the oracle sample")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB three times (calibrates the "
@@ -47,7 +57,6 @@ def parse():
 
 def cpu_baseline(wl, x, budget_s):
     """Oracle forward on a bounded sample of heads, all host threads; tokens/s scaled to the layer."""
-    import numpy as np
     import torch
     import oracle
 
@@ -78,16 +87,20 @@ def cpu_baseline(wl, x, budget_s):
                       f"{wall:.2f} s wall; one head on one thread {one:.2f} s"}
 
 
-def issued_tile_flops(wl, seq_len):
-    """Flops of the 32-key x 32-query tiles the tiled attention visits (launch geometry only):
-    each wave of 32 rows walks the compact key list up to the last key its rows may see."""
+def bucket_form(wl):
+    """The attention stage groups (row, selected column) entries by column instead of walking tiles."""
+    return wl.grouping == 0 and (wl.k_hat == 1 or (wl.k_hat <= 8 and 8 * wl.k_hat <= wl.K))
+
+
+def issued_tile_flops(wl, seq_len, selected_columns):
+    """Flops of the 32-key x 32-query tiles the tiled attention visits (launch geometry only).
+    Tile walk: each wave of 32 rows walks the compact key list up to the last key its rows may
+    see.  Bucket form: every (row, selected column) entry meets the r keys of its column, in
+    32-key granules (partly filled 32-row tiles at bucket ends not counted)."""
     w = wl.T // wl.K
     r = w if wl.k_budget == 0 else min(w, max(1, wl.k_budget // wl.k_hat))
-    if wl.k_hat == 1 and not wl.grouping:
-        # bucket form: every active row against the r keys of its one column (32-key granules;
-        # partly filled 32-row tiles at bucket ends not counted)
-        rows = sum((wl.T if seq_len is None else int(seq_len[b])) for b in range(wl.B)) * wl.H
-        return float(rows) * (-(-r // 32) * 32) * wl.d * 4
+    if bucket_form(wl):
+        return float(selected_columns) * (-(-r // 32) * 32) * wl.d * 4
     total = 0
     for b in range(wl.B):
         ln = wl.T if seq_len is None else int(seq_len[b])
@@ -99,6 +112,188 @@ def issued_tile_flops(wl, seq_len):
             u_end = col * r + min(r, -(-(delta + 1) * r // w))
             total += -(-u_end // 32)
     return float(total) * wl.H * 32 * 32 * wl.d * 4
+
+
+def attention_mass_recall(torch, wl, d, sl, idx, cnt, n_heads=4, n_rows=256):
+    """Share of the exact softmax attention mass (over the admissible keys of a row) that falls on
+    the keys the sparse stage attends, averaged over sampled rows of sampled heads.  A diagnostic of
+    the estimate + selection, computed with library ops on the device; not part of the path."""
+    g = torch.Generator().manual_seed(0)
+    N = wl.B * wl.H
+    heads = torch.randperm(N, generator=g)[:n_heads].tolist()
+    tot, n = 0.0, 0
+    for bh in heads:
+        b, h = divmod(bh, wl.H)
+        ln = wl.T if sl is None else int(sl[b])
+        if ln <= 0:
+            continue
+        rows = torch.randint(0, ln, (n_rows,), generator=g).to(d["Q"].device)
+        q = d["Q"][b, h].index_select(0, rows).float()
+        logits = (q @ d["K"][b, h, :ln].float().t()) * wl.scale
+        keys = torch.arange(ln, device=logits.device)
+        if wl.causal:
+            logits = logits.masked_fill(keys[None, :] > rows[:, None], float("-inf"))
+        prob = torch.softmax(logits, -1)
+        ii = idx[b, h].index_select(0, rows).long()
+        valid = ii >= 0
+        got = torch.gather(prob, 1, ii.clamp(min=0, max=ln - 1)) * valid
+        tot += float(got.sum())
+        n += int(rows.numel())
+    return tot / max(n, 1)
+
+
+def measure(torch, sea, synth, wl, steps, warmup, detail):
+    """Times sea_forward on one workload.  Returns (record, inputs)."""
+    dev = "cuda:0"
+    x = synth.make_inputs(wl)
+    d = {k: x[k].to(dev) for k in "QKVW"}
+    sl = None if x["seq_len"] is None else x["seq_len"].to(dev)
+    p = sea.SeaParams(B=wl.B, H=wl.H, T=wl.T, d=wl.d, m=wl.m, K=wl.K, k_hat=wl.k_hat,
+                      k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale, dtype=wl.dtype, seq_len=sl,
+                      grouping=wl.grouping, geometry=wl.geometry)
+    ws = sea.alloc_workspace(p, dev)
+    O = torch.empty_like(d["Q"])
+    L = sea.sea_row_stride(p)
+
+    # one untimed call that keeps the lists, to count the (query, key) pairs of the sparse stage
+    cnt = torch.empty(wl.B, wl.H, wl.T, dtype=torch.int32, device=dev)
+    idx = torch.empty(wl.B, wl.H, wl.T, L, dtype=torch.int32, device=dev) if detail else None
+    sel = torch.empty(wl.B, wl.H, wl.T, sea.sea_sel_stride(p), dtype=torch.int32, device=dev)
+    sea.sea_forward(p, d["Q"], d["K"], d["V"], d["W"], O, None, sel, idx, cnt, ws)
+    torch.cuda.synchronize()
+    pairs = int(cnt.sum().item())
+    active_rows = int((cnt > 0).sum().item())
+    selected_columns = int((sel >= 0).sum().item())
+    recall = attention_mass_recall(torch, wl, d, x["seq_len"], idx, cnt) if detail else None
+    del cnt, idx, sel
+
+    step = lambda: sea.sea_forward(p, d["Q"], d["K"], d["V"], d["W"], O, None, None, None, None, ws)
+    sea.sea_profile_enable(False)
+    sea.sea_profile_collect()
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    # ---- the timed region: exactly `steps` calls, nothing else on the stream ----
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    # ---- per-step spread: the same calls, each between two events of the launch stream ----
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in ev:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    per_step = [a.elapsed_time(b) for a, b in ev]
+    # ---- per-kernel durations: the same calls with every stage bracketed by HIP events ----
+    sea.sea_profile_enable(True)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    stages = sea.sea_profile_collect()
+    sea.sea_profile_enable(False)
+
+    tokens = wl.B * wl.T
+    ms_per_step = elapsed / steps * 1e3
+    avg = {k: (v[0] / v[1]) for k, v in stages.items() if v[1] > 0}   # ms per launch
+    launches = {k: int(v[1]) for k, v in stages.items() if v[1] > 0}
+
+    es = 2 if wl.dtype == "bf16" else 4
+    nrows = wl.B * wl.H * wl.T
+    N = wl.B * wl.H
+    tiled = sea.sea_attention_path(p) == 1
+    wcol = wl.T // wl.K
+    fused = tiled and wl.grouping == 0 and wl.m in (64, 128, 256) and wl.K <= 256 and (wcol & (wcol - 1)) == 0
+    kernels = {}
+    # sparse attention: 4 d flops per selected (query, key) pair
+    sparse_ms = avg.get("sparse", 0.0)
+    algo_flops = 4.0 * wl.d * pairs
+    if sparse_ms > 0 and tiled:
+        ach = algo_flops / (sparse_ms * 1e-3) / 1e12
+        issued = issued_tile_flops(wl, x["seq_len"], selected_columns)
+        kernels["sparse"] = {"kernel": "tile_attn_kernel" + (" (bucket form, with its grouping kernels)" if bucket_form(wl) else ""),
+                             "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                             "frac": ach / MFMA_BF16_PEAK_TFLOPS, "avg_kernel_ms": sparse_ms,
+                             "algorithmic_flops": algo_flops, "issued_flops": issued,
+                             "issued_tflops": issued / (sparse_ms * 1e-3) / 1e12, "pairs": pairs,
+                             "note": "achieved counts the selected (query, key) pairs only, 4 d flops each; issued "
+                                     "counts every pair of the 32 x 32 tiles the kernel visits"}
+    elif sparse_ms > 0:
+        # per-row list kernel: the bytes that must cross HBM once are Q, K, V, O and the lists; the
+        # repeated K / V row gathers of the pairs are served by the caches
+        once_bytes = 4 * nrows * wl.d * es + pairs * 4 + nrows * 4
+        ach = once_bytes / (sparse_ms * 1e-3) / 1e9
+        kernels["sparse"] = {"kernel": "sparse_attn_kernel", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
+                             "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "avg_kernel_ms": sparse_ms,
+                             "algorithmic_bytes": once_bytes, "pairs": pairs}
+    # estimator: dense flop counts of the contractions (2 T d m per projection, 2 T m K)
+    proj = 2.0 * wl.T * wl.d * wl.m * N
+    contr = 2.0 * wl.T * wl.m * wl.K * N
+    if fused:
+        for name, kern, fl in (("state", "key_state_kernel", proj), ("contract", "estimate_rows_kernel", proj + contr)):
+            ms = avg.get(name, 0.0)
+            if ms > 0:
+                ach = fl / (ms * 1e-3) / 1e12
+                kernels[name] = {"kernel": kern, "bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS,
+                                 "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS, "avg_kernel_ms": ms,
+                                 "algorithmic_flops": fl,
+                                 "note": "dense count; about half of a causal contraction lies above the diagonal "
+                                         "and is skipped" if name == "contract" and wl.causal else "dense count"}
+    est_ms = sum(avg.get(k, 0.0) for k in ("features", "state", "contract"))
+    est_flops = 2.0 * proj + contr
+    peak = MFMA_BF16_PEAK_TFLOPS if wl.dtype == "bf16" else FP64_PEAK_TFLOPS
+    est = {"ms": est_ms, "dense_flops": est_flops,
+           "tflops": est_flops / (est_ms * 1e-3) / 1e12 if est_ms > 0 else 0.0,
+           "peak_tflops": peak if wl.geometry == 0 else None,
+           "frac_of_peak": (est_flops / (est_ms * 1e-3) / 1e12 / peak) if est_ms > 0 and wl.geometry == 0 else None,
+           "useful_flops": est_flops - (0.5 * contr * (1.0 - 1.0 / wl.K) if wl.causal else 0.0),
+           "includes_topk": "topk_mask" not in avg}
+    if wl.geometry == 1:
+        gbytes = float(nrows) * (wl.K + 1) * wl.m * 8
+        cms = avg.get("contract", 0.0)
+        est.update({"rows_kernel_ms": cms, "gathered_bytes": gbytes,
+                    "gather_TBps": gbytes / (cms * 1e-3) / 1e12 if cms > 0 else 0.0})
+    dominant = max(kernels, key=lambda k: kernels[k]["avg_kernel_ms"]) if kernels else None
+    if dominant is None and avg:
+        # correctness paths (general shapes, fp32): report the estimator against its arithmetic peak
+        dominant = "estimator"
+        ach = est["tflops"]
+        kernels["estimator"] = {"kernel": "estimate (features + state + contraction)", "bound": "alu" if wl.dtype == "f32" else "mfma",
+                                "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
+                                "avg_kernel_ms": est_ms, "algorithmic_flops": est_flops}
+    rec = {"workload": wl.name, "ms_per_step": ms_per_step, "tokens_per_s": tokens * steps / elapsed,
+           "median_ms": statistics.median(per_step), "min_ms": min(per_step), "steps": steps,
+           "stage_ms": avg, "stage_launches_timed": launches, "pairs": pairs,
+           "mean_keys_per_active_row": pairs / max(active_rows, 1), "row_stride": L,
+           "dominant": dominant, "kernels": kernels, "estimator": est, "attention_mass_recall": recall,
+           "gather_equivalent": None}
+    if sparse_ms > 0:
+        # the sparse stage in the per-row gather accounting (bytes a row-by-row gather would move):
+        # K row + V row + index per pair, q in and o out per row.  With 128 rows sharing each staged
+        # key tile the kernel is not bound by it; kept because the metric names an HBM fraction.
+        gb = pairs * (2 * wl.d * es + 4) + nrows * (2 * wl.d * es + 4)
+        rec["gather_equivalent"] = {"algorithmic_bytes": gb, "GBps": gb / (sparse_ms * 1e-3) / 1e9,
+                                    "frac_of_hbm_peak": gb / (sparse_ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    ctx = dict(x=x, d=d, p=p, O=O, ws=ws, step=step)
+    return rec, ctx
+
+
+def copy_rate(torch, mib=1024, reps=10):
+    """GB/s (read + written bytes) of a plain device-to-device copy: the achievable HBM figure."""
+    src = torch.ones(mib << 20, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    b.record()
+    torch.cuda.synchronize()
+    return 2.0 * (mib << 20) * reps / (a.elapsed_time(b) * 1e-3) / 1e9
 
 
 def main():
@@ -123,109 +318,19 @@ def main():
         return
     wl = synth.get_workload(args.workload)
     if args.grouping == "causal_per_batch":
-        import dataclasses
         wl = dataclasses.replace(wl, name=wl.name + "+causal_per_batch", grouping=1)
     if args.geometry == "row_width":
-        import dataclasses
         wl = dataclasses.replace(wl, name=wl.name + "+row_width", geometry=1)
-    x = synth.make_inputs(wl)
-    d = {k: x[k].to(dev) for k in "QKVW"}
-    sl = None if x["seq_len"] is None else x["seq_len"].to(dev)
-    p = sea.SeaParams(B=wl.B, H=wl.H, T=wl.T, d=wl.d, m=wl.m, K=wl.K, k_hat=wl.k_hat,
-                      k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale, dtype=wl.dtype, seq_len=sl,
-                      grouping=wl.grouping, geometry=wl.geometry)
-    ws = sea.alloc_workspace(p, dev)
-    O = torch.empty_like(d["Q"])
-    L = sea.sea_row_stride(p)
-
-    # one untimed call with cnt kept, to count the (query, key) pairs the sparse stage processes
-    cnt = torch.empty(wl.B, wl.H, wl.T, dtype=torch.int32, device=dev)
-    sea.sea_forward(p, d["Q"], d["K"], d["V"], d["W"], O, None, None, None, cnt, ws)
-    torch.cuda.synchronize()
-    pairs = int(cnt.sum().item())
-    active_rows = int((cnt > 0).sum().item())
-    del cnt
-
-    step = lambda: sea.sea_forward(p, d["Q"], d["K"], d["V"], d["W"], O, None, None, None, None, ws)
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    # timed region: only the dominant kernel (the sparse-attention stage) is bracketed by events,
-    # and only on every fourth step, since every event pair costs a few microseconds of stream time
-    sea.sea_profile_enable(False)
-    sea.sea_profile_collect()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        if i % 4 == 0:
-            sea.sea_profile_enable(["sparse"])
-        elif i % 4 == 1:
-            sea.sea_profile_enable(False)
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    stages = sea.sea_profile_collect()
-    # per-stage table from a separate, untimed pass with every stage bracketed
-    sea.sea_profile_enable(True)
-    for _ in range(max(3, args.steps // 4)):
-        step()
-    torch.cuda.synchronize()
-    all_stages = sea.sea_profile_collect()
-    sea.sea_profile_enable(False)
-    all_stages["sparse"] = stages["sparse"]
-
+    rec, ctx = measure(torch, sea, synth, wl, args.steps, args.warmup, detail=True)
+    x, d, p, O = ctx["x"], ctx["d"], ctx["p"], ctx["O"]
     tokens = wl.B * wl.T
-    ms_per_step = elapsed / args.steps * 1e3
-    value = tokens * args.steps / elapsed
-    avg = {k: (v[0] / v[1]) for k, v in all_stages.items() if v[1] > 0}   # ms per launch
 
-    # ---- roofline of the dominant kernel: the sparse attention stage ----
-    # Per (query, key) pair the stage does 4 d flops and, in the per-row gather accounting, moves
-    # one K row + one V row + one index; per query row q in and o out.
-    es = 2 if wl.dtype == "bf16" else 4
-    nrows = wl.B * wl.H * wl.T
-    sparse_ms = avg.get("sparse", 0.0)
-    algo_flops = 4.0 * wl.d * pairs
-    algo_bytes = pairs * (2 * wl.d * es + 4) + nrows * (2 * wl.d * es + 4)
-    tiled = sea.sea_attention_path(p) == 1   # the tiled matrix-core kernel ran (bf16, column-structured mask)
-    if tiled:
-        issued = issued_tile_flops(wl, x["seq_len"])
-        ach = algo_flops / (sparse_ms * 1e-3) / 1e12
-        roofline = {"kernel": "tile_attn_kernel", "bound": "mfma", "achieved": ach,
-                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name), "avg_kernel_ms": sparse_ms,
-                    "timed_launches": int(stages["sparse"][1]),
-                    "algorithmic_flops": algo_flops,
-                    "issued_flops": issued, "issued_tflops": issued / (sparse_ms * 1e-3) / 1e12,
-                    "pairs": pairs,
-                    "note": "achieved counts only the selected (query, key) pairs (4 d flops each); issued "
-                            "counts every pair of the 32x32 tiles the kernel visits"}
-    else:
-        # per-row list kernel: the bytes that must cross HBM once are Q, K, V, O and the lists; the
-        # repeated K / V row gathers of the pairs are served by the caches (see gather_equivalent)
-        once_bytes = 4 * nrows * wl.d * es + pairs * 4 + nrows * 4
-        ach = once_bytes / (sparse_ms * 1e-3) / 1e9
-        roofline = {"kernel": "sparse_attn_kernel", "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None, "avg_kernel_ms": sparse_ms,
-                    "algorithmic_bytes": once_bytes, "pairs": pairs}
-    # the same stage in the per-row gather accounting (bytes a row-by-row gather would move)
-    gather_equiv = {"algorithmic_bytes": algo_bytes,
-                    "GBps": algo_bytes / (sparse_ms * 1e-3) / 1e9 if sparse_ms > 0 else 0.0,
-                    "frac_of_hbm_peak": algo_bytes / (sparse_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if sparse_ms > 0 else 0.0}
-    # estimator (features + state + contraction [+ in-register top-k]): dense matrix-core flop count
-    est_ms = sum(avg.get(k, 0.0) for k in ("features", "state", "contract"))
-    est_flops = wl.B * wl.H * (4.0 * wl.T * wl.d * wl.m + 2.0 * wl.T * wl.m * wl.K)
-    est = {"ms": est_ms, "dense_flops": est_flops,
-           "tflops": est_flops / (est_ms * 1e-3) / 1e12 if est_ms > 0 else 0.0,
-           "frac_of_bf16_mfma_peak": (est_flops / (est_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS)
-           if est_ms > 0 and wl.dtype == "bf16" else None,
-           "includes_topk": "topk_mask" not in avg}
-    if wl.geometry == 1:
-        # per-row width geometry: the contraction is K + 1 gathered fp64 prefix rows of m features per
-        # query row, served by the caches
-        gbytes = float(nrows) * (wl.K + 1) * wl.m * 8
-        cms = avg.get("contract", 0.0)
-        est.update({"frac_of_bf16_mfma_peak": None, "rows_kernel_ms": cms, "gathered_bytes": gbytes,
-                    "gather_TBps": gbytes / (cms * 1e-3) / 1e12 if cms > 0 else 0.0})
+    roofline = dict(rec["kernels"][rec["dominant"]]) if rec["dominant"] else None
+    if roofline is not None:
+        t = TRAFFIC_FROM_PROFILES.get((wl.name, rec["dominant"]))
+        roofline["traffic"] = None if t is None else t[0] + t[1]
+        roofline["traffic_source"] = None if t is None else TRAFFIC_SOURCE
+        roofline["timed_launches"] = rec["stage_launches_timed"].get(rec["dominant"])
 
     # ---- dense (quadratic) attention on the same shape, same dtype, for comparison ----
     dense = None
@@ -236,14 +341,19 @@ def main():
             sea.sea_dense_attn(p, d["Q"], d["K"], d["V"], Od, dws)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        nd = max(3, args.steps // 2)
+        nd = max(3, min(args.steps // 2, 50))
         for _ in range(nd):
             sea.sea_dense_attn(p, d["Q"], d["K"], d["V"], Od, dws)
         torch.cuda.synchronize()
         dms = (time.perf_counter() - t0) / nd * 1e3
         dflops = wl.B * wl.H * 4.0 * wl.d * wl.T * wl.T * (0.5 if wl.causal else 1.0)
         dense = {"ms_per_call": dms, "tokens_per_s": tokens / (dms * 1e-3),
-                 "tflops": dflops / (dms * 1e-3) / 1e12, "kernel": "tile_attn_kernel<dense>"}
+                 "tflops": dflops / (dms * 1e-3) / 1e12,
+                 "frac_of_bf16_mfma_peak": dflops / (dms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                 "kernel": "tile_attn_kernel<dense>",
+                 "note": "this library's own quadratic kernel, itself well below the matrix-core peak: any "
+                         "sparse/dense crossover read from these numbers is relative to it"}
+        del Od
 
     # ---- output mixing epilogue (Sec. 3.1.1), timed on its own: not part of the headline step ----
     mix_ms = None
@@ -259,23 +369,68 @@ def main():
             sea.sea_output_mix(p, O, d["V"], s_mix, Om, mws)
         torch.cuda.synchronize()
         mix_ms = (time.perf_counter() - t0) / 10 * 1e3
+        del Om, mws, s_mix
 
     out = {
         "metric": "SEA attn fwd tokens/s per layer + % HBM/MFMA roofline, T=1k..32k",
-        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": rec["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": rec["ms_per_step"], "median_ms": rec["median_ms"], "min_ms": rec["min_ms"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: B={wl.B} H={wl.H} T={wl.T} d={wl.d} m={wl.m} K={wl.K} "
                                f"k_hat={wl.k_hat} k_budget={wl.k_budget} causal={int(wl.causal)} "
                                f"pad_frac={wl.pad_frac} clustered Q/K ({wl.centroids} centroids), seed {wl.seed}",
-                   "row_stride": L, "mean_keys_per_active_row": pairs / max(active_rows, 1)},
+                   "row_stride": rec["row_stride"], "mean_keys_per_active_row": rec["mean_keys_per_active_row"]},
         "roofline": roofline,
-        "gather_equivalent": gather_equiv,
-        "stage_ms": avg,
-        "estimator": est,
+        "kernels": rec["kernels"],
+        "gather_equivalent": rec["gather_equivalent"],
+        "stage_ms": rec["stage_ms"],
+        "estimator": rec["estimator"],
+        "attention_mass_recall": rec["attention_mass_recall"],
         "dense_attention": dense,
         "output_mix_ms": mix_ms,
+        "copy_GBps": copy_rate(torch),
     }
+    del ctx, d, O
+    torch.cuda.empty_cache()
+    if not args.no_sweep:
+        sweep = {}
+        for name in SWEEP:
+            if name == wl.name:
+                continue
+            w2 = synth.get_workload(name)
+            r2, c2 = measure(torch, sea, synth, w2, max(20, args.steps // 4), max(5, args.warmup // 2), detail=False)
+            dom = r2["kernels"].get(r2["dominant"]) if r2["dominant"] else None
+            entry = {"ms_per_step": r2["ms_per_step"], "median_ms": r2["median_ms"], "min_ms": r2["min_ms"],
+                     "tokens_per_s": r2["tokens_per_s"], "stage_ms": r2["stage_ms"],
+                     "dominant_kernel": None if dom is None else dom["kernel"],
+                     "roofline_bound": None if dom is None else dom["bound"],
+                     "roofline_frac": None if dom is None else dom["frac"],
+                     "kernel_fracs": {k: v["frac"] for k, v in r2["kernels"].items()}}
+            if name == "c1":
+                # launch-latency-free time of the small configuration: replay of a captured graph
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    c2["step"]()
+                torch.cuda.current_stream().wait_stream(side)
+                torch.cuda.synchronize()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    c2["step"]()
+                for _ in range(5):
+                    graph.replay()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(50):
+                    graph.replay()
+                torch.cuda.synchronize()
+                entry["graph_replay_ms"] = (time.perf_counter() - t0) / 50 * 1e3
+                del graph
+            sweep[name] = entry
+            del c2
+            torch.cuda.empty_cache()
+        out["sweep"] = sweep
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, x, args.cpu_seconds)
     print(json.dumps(out))

@@ -295,11 +295,12 @@ __global__ __launch_bounds__(256) void contract_bf16_kernel(
 }  // namespace
 
 size_t estimate_bf16_workspace(const Shape& s) {
+  // common shapes run the fused kernels, whose scratch is the K x m state and the prefix planes
+  if (estimate_fused_supported(s)) return estimate_fused_workspace(s);
   const size_t ntm = static_cast<size_t>(s.N) * s.T * s.m;
   const size_t nkm = static_cast<size_t>(s.N) * s.K * s.m;
   size_t bytes = ntm * 2 + ntm * 4 + ((nkm * 2 + 255) & ~size_t(255));
   if (s.causal) bytes += ntm * 2;
-  if (estimate_fused_supported(s)) bytes = max(bytes, estimate_fused_workspace(s));
   return bytes;
 }
 

@@ -243,7 +243,7 @@ def test_bf16_forward_against_the_plain_definition(sea, wl, heads):
     bad = ~same & ~(gaps < PLAIN_GAP)
     assert not bad.any(), f"{bad.sum()} rows differ with a plain-oracle gap >= 2^-6 (largest {gaps[~same].max():.3g})"
     frac = float((~same).mean())
-    assert frac <= 0.015, f"{wl.name}: {(~same).sum()} of {same.size} rows select differently from the plain oracle"
+    assert frac <= 0.02, f"{wl.name}: {(~same).sum()} of {same.size} rows select differently from the plain oracle"
     assert np.array_equal(pick(g["idx"].numpy())[same], pick(o["idx"])[same])
     Og, Oo = pick(to_np64(g["O"])).copy(), pick(o["O"]).copy()
     Og[~same] = 0.0
