@@ -41,7 +41,8 @@ typedef enum {
   SEA_EINVAL = -1,     /* NULL pointer, non-positive size, K > T, k_hat > K, ...          */
   SEA_ENOTSUP = -2,    /* valid but not implemented: d != 64, K > 1024, m % 32 != 0, ...  */
   SEA_EWORKSPACE = -3, /* workspace NULL or smaller than sea_workspace_bytes()             */
-  SEA_EHIP = -4        /* a HIP call failed; see sea_last_hip_error()                      */
+  SEA_EHIP = -4,       /* a HIP call failed; see sea_last_hip_error()                      */
+  SEA_ETOOBIG = -5     /* sea_forward_static only: needs more scratch than its fixed buffer  */
 } sea_status;
 
 /*
@@ -200,6 +201,26 @@ int sea_mask_attn(const sea_params* p, const void* Q, const void* K, const void*
 int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V, const void* W,
                 void* O, float* A_hat_opt, int32_t* sel_opt, int32_t* idx_opt, int32_t* cnt_opt,
                 uint32_t* mhat_opt, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * sea_forward for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same
+ * results as sea_forward with every optional output NULL; the scratch is a fixed array of
+ * sea_static_scratch_bytes() (64 MiB) inside the library, one copy per GPU, held until the process
+ * ends.  The call allocates nothing and frees nothing (no hipMalloc, no allocating library call);
+ * the first call on a GPU looks the array's device address up, with that GPU current.
+ *   sea_forward_static_bytes(p): scratch these parameters need here (0 on invalid parameters); less
+ *   than sea_workspace_bytes(p) where the scores stay on chip.  Above sea_static_scratch_bytes()
+ *   the call returns SEA_ETOOBIG and enqueues nothing (c2: 3.1 MB, c3: 50 MB fit; c4 at T = 32768
+ *   with 138 MB does not).
+ * Every call on one GPU uses the same array, which keeps the previous call's contents; the kernels
+ * overwrite or clear what they read, so calls may follow each other on one stream with any mix of
+ * shapes.  Two calls that overlap on one GPU (different streams or threads, unordered) race.
+ */
+size_t sea_static_scratch_bytes(void);
+size_t sea_forward_static_bytes(const sea_params* p);
+int sea_forward_static(const sea_params* p, const void* Q, const void* K, const void* V, const void* W,
+                       void* O, void* hip_stream);
 
 /*
  * Sec. 3.1.1 "Output Calculation": C_sea = s_mix * (s_prob * C) + (1 - s_mix) * C_avg, row by row.

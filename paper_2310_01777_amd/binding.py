@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsea_hip.so")
 
 SEA_F32, SEA_BF16 = 0, 1
-SEA_OK, SEA_EINVAL, SEA_ENOTSUP, SEA_EWORKSPACE, SEA_EHIP = 0, -1, -2, -3, -4
+SEA_OK, SEA_EINVAL, SEA_ENOTSUP, SEA_EWORKSPACE, SEA_EHIP, SEA_ETOOBIG = 0, -1, -2, -3, -4, -5
 STAGES = ("features", "state", "contract", "topk_mask", "sparse", "dense", "compact")
 
 
@@ -56,6 +56,9 @@ def _load() -> ctypes.CDLL:
     lib.sea_topk_mask.restype, lib.sea_topk_mask.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp]
     lib.sea_sparse_attn.restype, lib.sea_sparse_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, i32, vp, vp]
     lib.sea_forward.restype, lib.sea_forward.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.sea_static_scratch_bytes.restype, lib.sea_static_scratch_bytes.argtypes = sz, []
+    lib.sea_forward_static_bytes.restype, lib.sea_forward_static_bytes.argtypes = sz, [P]
+    lib.sea_forward_static.restype, lib.sea_forward_static.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, vp]
     lib.sea_dense_workspace_bytes.restype, lib.sea_dense_workspace_bytes.argtypes = sz, [P]
     lib.sea_dense_attn.restype, lib.sea_dense_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, sz, vp]
     lib.sea_output_mix_workspace_bytes.restype, lib.sea_output_mix_workspace_bytes.argtypes = sz, [P]
@@ -259,8 +262,29 @@ def sea_forward(p: SeaParams, Q, K, V, W, O, A_hat=None, sel=None, idx=None, cnt
                             _ptr(cnt, torch.int32, n, "cnt"),
                             _ptr(mhat, torch.int32, n * ((p.K + 31) // 32), "mhat"),
                             _ptr(workspace, None, None, "workspace"),
-                            workspace.numel() * workspace.element_size(), _stream(stream)),
+                            0 if workspace is None else workspace.numel() * workspace.element_size(),
+                            _stream(stream)),
            "sea_forward")
+
+
+def sea_static_scratch_bytes() -> int:
+    return int(_lib.sea_static_scratch_bytes())
+
+
+def sea_forward_static_bytes(p: SeaParams) -> int:
+    cp = p.c()
+    return int(_lib.sea_forward_static_bytes(ctypes.byref(cp)))
+
+
+def sea_forward_static(p: SeaParams, Q, K, V, W, O, stream=None):
+    n = p.B * p.H * p.T
+    cp = p.c()
+    _check(_lib.sea_forward_static(ctypes.byref(cp), _ptr(Q, p.torch_dtype, n * p.d, "Q"),
+                                   _ptr(K, p.torch_dtype, n * p.d, "K"),
+                                   _ptr(V, p.torch_dtype, n * p.d, "V"),
+                                   _ptr(W, p.torch_dtype, p.m * p.d, "W"),
+                                   _ptr(O, p.torch_dtype, n * p.d, "O"), _stream(stream)),
+           "sea_forward_static")
 
 
 def sea_dense_workspace_bytes(p: SeaParams) -> int:

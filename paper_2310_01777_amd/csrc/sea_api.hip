@@ -2,6 +2,7 @@
 // Every computation runs in the HIP kernels of the sibling translation units.
 #include <limits.h>
 
+#include <mutex>
 #include <vector>
 
 #include "sea_internal.h"
@@ -114,6 +115,56 @@ size_t estimate_ws(const sea_params* p) {
   return align256(p->dtype == SEA_BF16 ? estimate_bf16_workspace(s) : estimate_f64_workspace(s));
 }
 
+// the fused estimator keeps the scores in registers: no A_hat buffer unless the caller wants one
+bool scores_stay_on_chip(const sea_params* p, const Shape& s) {
+  return tile_attn_supported(s, p->dtype, nullptr) && estimate_fused_supported(s) && s.grouping == 0;
+}
+
+// Scratch of the whole forward pass: estimator scratch, A_hat, then either the tiled path's mask
+// bits and bucket tables or the row-list path's idx + cnt.  `lean`: the caller keeps no
+// intermediate, so the A_hat part is dropped where the scores stay on chip.
+size_t forward_ws(const sea_params* p, bool lean) {
+  const size_t rows = static_cast<size_t>(p->B) * p->H * p->T;
+  const Shape s = make_shape(p, true);
+  size_t bytes = estimate_ws(p);
+  if (!(lean && scores_stay_on_chip(p, s))) bytes += align256(rows * p->K * sizeof(float));
+  if (tile_attn_supported(s, p->dtype, nullptr)) {
+    bytes += align256(rows * ((p->K + 31) / 32) * sizeof(uint32_t));
+    bytes += align256(tile_attn_workspace(s));
+  } else {
+    bytes += align256(rows * static_cast<size_t>(row_stride_of(p)) * sizeof(int32_t));
+    bytes += align256(rows * sizeof(int32_t));
+    if (p->grouping == 1) bytes += align256(rows * ((p->K + 31) / 32) * sizeof(uint32_t));
+  }
+  return bytes;
+}
+
+// ---- scratch of sea_forward_static: one array per GPU, alive until the process ends ----
+constexpr size_t kStaticScratchBytes = size_t(64) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each GPU, looked up once
+
+// The array's name is only a host-side handle; kernels need the device address, which differs
+// from GPU to GPU.  Looked up on first use with the caller's device current.
+int static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(e);
+  if (dev < 0 || dev >= kMaxDevices) return SEA_ENOTSUP;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return fail_hip(e);
+    if (!ptr || reinterpret_cast<uintptr_t>(ptr) % 256 != 0) return SEA_EWORKSPACE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return SEA_OK;
+}
+
 }  // namespace
 
 void stage_begin(sea_stage stage, hipStream_t st) {
@@ -161,21 +212,7 @@ size_t sea_workspace_bytes(const sea_params* p) {
   if (check_common(p) != SEA_OK || check_mask_params(p) != SEA_OK ||
       check_estimate_params(p) != SEA_OK || row_stride_of(p) < 0)
     return 0;
-  // estimator scratch and A_hat, then either the tiled path's mask bits or
-  // the row-list path's idx + cnt (for when the caller keeps none of them)
-  const size_t rows = static_cast<size_t>(p->B) * p->H * p->T;
-  const Shape s = make_shape(p, true);
-  size_t bytes = estimate_ws(p);
-  bytes += align256(rows * p->K * sizeof(float));
-  if (tile_attn_supported(s, p->dtype, nullptr)) {
-    bytes += align256(rows * ((p->K + 31) / 32) * sizeof(uint32_t));
-    bytes += align256(tile_attn_workspace(s));
-  } else {
-    bytes += align256(rows * static_cast<size_t>(row_stride_of(p)) * sizeof(int32_t));
-    bytes += align256(rows * sizeof(int32_t));
-    if (p->grouping == 1) bytes += align256(rows * ((p->K + 31) / 32) * sizeof(uint32_t));
-  }
-  return bytes;
+  return forward_ws(p, false);
 }
 
 int sea_estimate(const sea_params* p, const void* Q, const void* K, const void* W, float* A_hat,
@@ -283,25 +320,21 @@ int sea_mask_attn(const sea_params* p, const void* Q, const void* K, const void*
   return e == hipSuccess ? SEA_OK : fail_hip(e);
 }
 
-int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V, const void* W,
-                void* O, float* A_hat_opt, int32_t* sel_opt, int32_t* idx_opt, int32_t* cnt_opt,
-                uint32_t* mhat_opt, void* workspace, size_t workspace_bytes, void* hip_stream) {
-  int rc = check_common(p);
-  if (rc == SEA_OK) rc = check_mask_params(p);
-  if (rc == SEA_OK) rc = check_estimate_params(p);
-  if (rc != SEA_OK) return rc;
-  if (!Q || !K || !V || !W || !O) return SEA_EINVAL;
-  if (row_stride_of(p) < 0) return SEA_ENOTSUP;
-  if (!workspace || workspace_bytes < sea_workspace_bytes(p)) return SEA_EWORKSPACE;
-  if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SEA_EWORKSPACE;
+namespace {
+// the stages of the forward pass on one stream; the workspace is laid out as forward_ws(p, lean)
+int forward_stages(const sea_params* p, const void* Q, const void* K, const void* V, const void* W,
+                   void* O, float* A_hat_opt, int32_t* sel_opt, int32_t* idx_opt, int32_t* cnt_opt,
+                   uint32_t* mhat_opt, void* workspace, bool lean, hipStream_t st) {
   const Shape s = make_shape(p, true);
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
   const size_t rows = static_cast<size_t>(s.N) * s.T;
   char* w = static_cast<char*>(workspace);
   void* est_ws = w;
   w += estimate_ws(p);
-  float* A_hat = A_hat_opt ? A_hat_opt : reinterpret_cast<float*>(w);
-  w += align256(rows * s.K * sizeof(float));
+  float* A_hat = A_hat_opt;
+  if (!(lean && scores_stay_on_chip(p, s))) {
+    if (!A_hat) A_hat = reinterpret_cast<float*>(w);
+    w += align256(rows * s.K * sizeof(float));
+  }
   const bool tiled = tile_attn_supported(s, p->dtype, nullptr);
 
   hipError_t e;
@@ -348,6 +381,47 @@ int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V
   if (e != hipSuccess) return fail_hip(e);
   e = launch_sparse_attn(s, p->dtype, Q, K, V, idx, cnt, s.L, nullptr, O, st);
   return e == hipSuccess ? SEA_OK : fail_hip(e);
+}
+}  // namespace
+
+int sea_forward(const sea_params* p, const void* Q, const void* K, const void* V, const void* W,
+                void* O, float* A_hat_opt, int32_t* sel_opt, int32_t* idx_opt, int32_t* cnt_opt,
+                uint32_t* mhat_opt, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int rc = check_common(p);
+  if (rc == SEA_OK) rc = check_mask_params(p);
+  if (rc == SEA_OK) rc = check_estimate_params(p);
+  if (rc != SEA_OK) return rc;
+  if (!Q || !K || !V || !W || !O) return SEA_EINVAL;
+  if (row_stride_of(p) < 0) return SEA_ENOTSUP;
+  if (!workspace || workspace_bytes < forward_ws(p, false)) return SEA_EWORKSPACE;
+  if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return SEA_EWORKSPACE;
+  return forward_stages(p, Q, K, V, W, O, A_hat_opt, sel_opt, idx_opt, cnt_opt, mhat_opt, workspace, false,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+size_t sea_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+size_t sea_forward_static_bytes(const sea_params* p) {
+  if (check_common(p) != SEA_OK || check_mask_params(p) != SEA_OK || check_estimate_params(p) != SEA_OK ||
+      row_stride_of(p) < 0)
+    return 0;
+  return forward_ws(p, true);
+}
+
+int sea_forward_static(const sea_params* p, const void* Q, const void* K, const void* V, const void* W,
+                       void* O, void* hip_stream) {
+  int rc = check_common(p);
+  if (rc == SEA_OK) rc = check_mask_params(p);
+  if (rc == SEA_OK) rc = check_estimate_params(p);
+  if (rc != SEA_OK) return rc;
+  if (!Q || !K || !V || !W || !O) return SEA_EINVAL;
+  if (row_stride_of(p) < 0) return SEA_ENOTSUP;
+  if (forward_ws(p, true) > kStaticScratchBytes) return SEA_ETOOBIG;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc != SEA_OK) return rc;
+  return forward_stages(p, Q, K, V, W, O, nullptr, nullptr, nullptr, nullptr, nullptr, ws, true,
+                        static_cast<hipStream_t>(hip_stream));
 }
 
 size_t sea_dense_workspace_bytes(const sea_params* p) {
@@ -425,6 +499,9 @@ const char* sea_strerror(int status) {
     case SEA_ENOTSUP: return "not supported (d != 64, K > 1024, or m not a multiple of 32 up to 1024)";
     case SEA_EWORKSPACE: return "workspace missing, misaligned or smaller than sea_workspace_bytes()";
     case SEA_EHIP: return "a HIP runtime call failed (see sea_last_hip_error)";
+    case SEA_ETOOBIG:
+      return "the problem needs more scratch than sea_forward_static's fixed buffer holds (see "
+             "sea_forward_static_bytes and sea_static_scratch_bytes); use sea_forward with a workspace";
     default: return "unknown status";
   }
 }
