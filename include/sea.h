@@ -103,13 +103,18 @@ size_t sea_workspace_bytes(const sea_params* p);
  *   V_I = the T x K one-hot matrix with V_I[j][floor(j K / T)] = 1 (nearest-neighbour stretch
  *   of the identity); A_hat = rownorm( phi(Q) (phi(K)^T V_I) ), where a causal row t only
  *   sums keys j <= t.  Rows sum to 1; columns holding no admissible key are 0.
- * dtype = SEA_BF16: phi(Q) and the key-side state phi(K)^T V_I (for a causal row also the
- * prefix state of its own column) are rounded to bfloat16 and contracted on the matrix
- * cores with fp32 accumulation.  dtype = SEA_F32: all products accumulate in fp64.
+ * dtype = SEA_BF16: phi(Q) (after a power-of-two row scale) and the finished column sums
+ * phi(K)^T V_I are rounded to bfloat16 and contracted on the matrix cores with fp32
+ * accumulation; a causal row's own column is summed key by key over j <= t from phi(k_j) rounded
+ * to bfloat16 (no prefix state is rounded).  dtype = SEA_F32: all products accumulate in fp64.
  * geometry = 1: V_I of row t is the (t+1) x K stretch, A_hat[t][c] = phi(q_t) . sum of phi(k_j)
  * over the keys of the row's own column c, normalised per row; all of it in fp64, either dtype.
- * The feature exponent is not stabilised on the key side: log2(e) * |w_i|^2 / 2 must stay
- * below the fp32 exponent range (true for any Gaussian W with d = 64).
+ * The feature exponent is not stabilised on the key side (a data-dependent key stabiliser would
+ * make causal results depend on future keys).  Two bounds follow for dtype = SEA_BF16, where the
+ * features are fp32: above, log2(e) |w_i|^2 / 2 must stay inside the fp32 exponent range (true for
+ * any Gaussian W with d = 64); below, a key with scale |k|^2 / 2 - sqrt(scale) w_i.k above about
+ * 87 for every i has all-zero features and drops out of the estimate (with unit-variance inputs
+ * and scale = d^-1/2 this needs |k|^2 > 1000, far outside the stated workloads).
  */
 int sea_estimate(const sea_params* p, const void* Q, const void* K, const void* W,
                  float* A_hat, void* workspace, size_t workspace_bytes, void* hip_stream);
@@ -255,8 +260,9 @@ int sea_dense_attn(const sea_params* p, const void* Q, const void* K, const void
  * (0 = off, -1 = all): launches of those stages are bracketed by HIP events recorded on the
  * launch stream (each pair costs a few microseconds of stream time).  sea_profile_collect()
  * synchronises those events, adds the elapsed milliseconds and launch counts per stage into
- * the two host arrays of length SEA_STAGE_COUNT, and forgets them.  Process-wide, not
- * thread-safe.
+ * the two host arrays of length SEA_STAGE_COUNT, and forgets them.  Process-wide state behind
+ * a mutex: with timing on, calls from several threads are safe but their spans interleave, so
+ * keep timing off (the default) when calls run concurrently.
  */
 typedef enum {
   SEA_STAGE_FEATURES = 0, /* a1: feature maps phi(Q), phi(K)                              */

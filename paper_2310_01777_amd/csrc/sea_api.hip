@@ -23,6 +23,7 @@ struct Span {
   hipEvent_t a, b;
 };
 unsigned g_profile = 0;  // bit per sea_stage
+std::mutex g_profile_mutex;  // guards the span and event lists
 std::vector<Span> g_spans;
 std::vector<hipEvent_t> g_free_events;
 
@@ -169,6 +170,7 @@ int static_scratch(void** out) {
 
 void stage_begin(sea_stage stage, hipStream_t st) {
   if (!(g_profile & (1u << stage))) return;
+  std::lock_guard<std::mutex> lock(g_profile_mutex);
   Span sp{stage, take_event(), take_event()};
   if (!sp.a || !sp.b) return;
   (void)hipEventRecord(sp.a, st);
@@ -176,7 +178,9 @@ void stage_begin(sea_stage stage, hipStream_t st) {
 }
 
 void stage_end(sea_stage stage, hipStream_t st) {
-  if (!(g_profile & (1u << stage)) || g_spans.empty()) return;
+  if (!(g_profile & (1u << stage))) return;
+  std::lock_guard<std::mutex> lock(g_profile_mutex);
+  if (g_spans.empty()) return;
   Span& sp = g_spans.back();
   if (sp.stage == stage) (void)hipEventRecord(sp.b, st);
 }
@@ -475,6 +479,7 @@ int sea_profile_enable(int stage_mask) {
 int sea_profile_collect(double* host_ms, int64_t* host_launches) {
   if (!host_ms || !host_launches) return SEA_EINVAL;
   int rc = SEA_OK;
+  std::lock_guard<std::mutex> lock(g_profile_mutex);
   for (Span& sp : g_spans) {
     float ms = 0.f;
     hipError_t e = hipEventSynchronize(sp.b);

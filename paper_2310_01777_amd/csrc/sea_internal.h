@@ -112,14 +112,15 @@ __device__ __forceinline__ float bf16lo_to_f32(uint32_t pair) { return __uint_as
 __device__ __forceinline__ float bf16hi_to_f32(uint32_t pair) {
   return __uint_as_float(pair & 0xffff0000u);
 }
-// round-to-nearest-even, finite inputs
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return static_cast<uint16_t>(u >> 16);
-}
+// float -> bfloat16, round to nearest even: the hardware pair conversion (v_cvt_pk_bf16_f32)
+typedef __bf16 sea_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float sea_floatx2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  return static_cast<uint32_t>(f32_to_bf16(lo)) | (static_cast<uint32_t>(f32_to_bf16(hi)) << 16);
+  const sea_floatx2 f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, sea_bf16x2));
+}
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  return static_cast<uint16_t>(pack_bf16(f, 0.f) & 0xffffu);
 }
 
 // first key of column c: ceil(c T / K); column of key j: floor(j K / T)

@@ -18,8 +18,9 @@
 // P leaves the first product in C layout (lane = query, regs = keys) and is fed back as the B
 // operand of the second product; its register order fixes which key each contraction slot
 // means, and the V^T fragments are fetched in that same order from LDS, where the value rows of a
-// step are parked transposed (one 16-bit store per element; the key and value rows themselves
-// are gathered from K and V by position, so no compact or transposed copy exists in HBM).
+// step are parked as they lie in memory and transposed on the way out by the LDS transpose read
+// (the key and value rows themselves are gathered from K and V by position, so no compact or
+// transposed copy exists in HBM).
 #include "sea_internal.h"
 
 namespace sea {

@@ -63,18 +63,22 @@ C6_K = 64
 C6_LENGTHS = (4096, 8192, 16384, 32768, 65536, 131072)
 
 
+# k^ of the c6 / c7 layers at each length, as a table: the rule k^ = max(1, round(k K / T)) is the
+# method's arithmetic and lives in the library and the oracle, not in this input generator (the
+# harness test checks this table against both)
+C6_K_HAT = {4096: 2, 8192: 1, 16384: 1, 32768: 1, 65536: 1, 131072: 1}       # k = 64, K = 128
+C7_K_HAT = {4096: 32, 8192: 16, 16384: 8, 32768: 4}                           # k = 512, K = 256
+
+
 def _c6(T: int, causal: bool) -> Workload:
-    K = 128
-    k_hat = max(1, (2 * C6_K * K + T) // (2 * T))  # round half up
-    return Workload(f"c6{'c' if causal else ''}_T{T}", 1, 12, T, 64, 128, K, k_hat, C6_K, causal, "bf16", 16)
+    return Workload(f"c6{'c' if causal else ''}_T{T}", 1, 12, T, 64, 128, 128, C6_K_HAT[T], C6_K, causal, "bf16", 16)
 
 
 def _c7(T: int) -> Workload:
     """c4's layer with the paper's own rule instead of a fixed k^: k = 512 keys per row at every T,
-    k^ = max(1, round(k K / T)) = 32, 16, 8, 4 for T = 4096 .. 32768, whole columns emitted."""
-    K, k = 256, 512
-    k_hat = max(1, (2 * k * K + T) // (2 * T))
-    return replace(WORKLOADS["c4"], name=f"c7_T{T}", T=T, k_hat=k_hat, k_budget=0)
+    k^ = 32, 16, 8, 4 for T = 4096 .. 32768 (Sec. 3.1 "Linear Sparse Attention Mask Generation"),
+    whole columns emitted."""
+    return replace(WORKLOADS["c4"], name=f"c7_T{T}", T=T, k_hat=C7_K_HAT[T], k_budget=0)
 
 
 def get_workload(name: str) -> Workload:
