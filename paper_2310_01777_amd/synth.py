@@ -141,3 +141,27 @@ def make_inputs(wl: Workload):
     dt = torch_dtype(wl.dtype)
     seq_len = padding_lengths(wl.B, wl.T, wl.pad_frac, wl.seed) if wl.pad_frac > 0 else None
     return dict(Q=Q.to(dt), K=K.to(dt), V=V.to(dt), W=W.to(dt), seq_len=seq_len)
+
+
+def decoder_weights(H: int, d: int, K: int, c_s: int = 2, c_h: int = 4, seed: int = 7, dtype: str = "bf16"):
+    """Random stand-ins for the learned decoder of Sec. 3.1 "CNN Decoder" / App. A.5.1 (the trained
+    weights do not exist here): Gaussian entries scaled by fan-in^-1/2, small Gaussian biases.
+    Shapes: mu_w [2d, 3d], nu1_w [2d, 2d], nu2_w [K c_h / c_s, 2d], conv1_w / conv2_w [C, 3, 3, C],
+    conv3_w [H, 3, 3, C] (out, ky, kx, in; C = H c_h), mix_w / prob_w [2d]; biases fp32."""
+    g = torch.Generator().manual_seed(seed)
+    dh, C, Wd = 2 * d, H * c_h, K // c_s
+    dt = torch_dtype(dtype)
+
+    def mat(*shape, fan_in):
+        return (torch.randn(*shape, generator=g) * fan_in ** -0.5).to(dt)
+
+    def vec(n):
+        return torch.randn(n, generator=g) * 0.1
+
+    return dict(mu_w=mat(dh, 3 * d, fan_in=3 * d), mu_b=vec(dh),
+                nu1_w=mat(dh, dh, fan_in=dh), nu1_b=vec(dh),
+                nu2_w=mat(Wd * c_h, dh, fan_in=dh), nu2_b=vec(Wd * c_h),
+                conv1_w=mat(C, 3, 3, C, fan_in=9 * C), conv1_b=vec(C),
+                conv2_w=mat(C, 3, 3, C, fan_in=9 * C), conv2_b=vec(C),
+                conv3_w=mat(H, 3, 3, C, fan_in=9 * C) * 4.0, conv3_b=vec(H),
+                mix_w=mat(dh, fan_in=dh), mix_b=vec(1), prob_w=mat(dh, fan_in=dh), prob_b=vec(1))
