@@ -245,6 +245,50 @@ int sea_output_mix(const sea_params* p, const void* C, const void* V, const floa
                    size_t workspace_bytes, void* hip_stream);
 
 /*
+ * The learned decoder of Sec. 3.1 "CNN Decoder" / App. A.5.1 "Attention Estimator CNN", with
+ * caller-supplied weights (the paper trains them by distillation; random weights make this a
+ * throughput workload).  dtype = SEA_BF16 only.  Fixed here: c_s = 2, c_h = 4, hidden width
+ * d' = 2 d = 128; mu = linear + ReLU; nu = linear + ReLU + linear; ReLU after the first two
+ * convolutions.  All weight matrices are bf16 row-major [out][in], biases fp32; C = 4 H channels.
+ *   C_perf = FAVOR+(Q, K, [V_I; V]) per head, V_I the T x d nearest-neighbour stretch of I_d, rows
+ *            normalised by phi(q_t) . sum_j phi(k_j) (causal: j <= t);
+ *   Z = mu([C_perf; V]) in R^{T x d'};  s_mix, s_prob = sigmoid(mix_w . Z + mix_b), likewise prob;
+ *   Z^ = nu(Z) in R^{T x (K/c_s) c_h}, entry x c_h + ch -> pixel (t, x), channel h c_h + ch;
+ *   conv1, conv2: 3x3, C -> C, ReLU; conv3: 3x3, C -> H, on the image resized (nearest) to T x K;
+ *   one zero column left and right; causal: every layer reads rows t - 2 .. t and the height is
+ *   not reduced; bidirectional: conv1 has height stride c_s and rows c_s i - 1 .. c_s i + 1, the
+ *   others rows i - 1 .. i + 1;  A_hat[h][t][:] = softmax over the K columns.
+ * Positions at or beyond seq_len: keys drop out of C_perf, rows of Z^ are zero, rows of A_hat,
+ * s_mix, s_prob are zero.  Conv weights are [out][ky][kx][in].
+ */
+typedef struct {
+  const void* mu_w;    const float* mu_b;     /* [128][192], [128]                     */
+  const void* nu1_w;   const float* nu1_b;    /* [128][128], [128]                     */
+  const void* nu2_w;   const float* nu2_b;    /* [(K / 2) 4][128], [(K / 2) 4]         */
+  const void* conv1_w; const float* conv1_b;  /* [C][3][3][C], [C]                     */
+  const void* conv2_w; const float* conv2_b;  /* [C][3][3][C], [C]                     */
+  const void* conv3_w; const float* conv3_b;  /* [H][3][3][C], [H]                     */
+  const void* mix_w;   const float* mix_b;    /* [128], [1]                            */
+  const void* prob_w;  const float* prob_b;   /* [128], [1]                            */
+} sea_decoder_weights;
+
+/* Scratch of sea_decoder_estimate / sea_decoder_forward (0 on invalid or unsupported parameters). */
+size_t sea_decoder_workspace_bytes(const sea_params* p);
+
+/* A_hat [B][H][T][K] float (rows are softmaxes); s_mix_opt, s_prob_opt [B][H][T] float or NULL.
+ * Needs m in {64, 128, 256}, K even, H even, geometry = 0 (SEA_ENOTSUP otherwise). */
+int sea_decoder_estimate(const sea_params* p, const sea_decoder_weights* w, const void* Q, const void* K,
+                         const void* V, const void* W, float* A_hat, float* s_mix_opt, float* s_prob_opt,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The paper's whole layer: decoder estimate -> grouped top-k^ (p->grouping) and mask expansion ->
+ * sparse attention -> C_sea = s_mix (s_prob C) + (1 - s_mix) C_avg (sea_output_mix with the
+ * decoder's scalers).  O [B][H][T][d]; A_hat_opt may be NULL. */
+int sea_decoder_forward(const sea_params* p, const sea_decoder_weights* w, const void* Q, const void* K,
+                        const void* V, const void* W, void* O, float* A_hat_opt, void* workspace,
+                        size_t workspace_bytes, void* hip_stream);
+
+/*
  * Quadratic attention A = softmax(scale QK^T), C = AV (Sec. 3 "Preliminaries"), causal and/or
  * right-padded like the sparse path, computed tile by tile with no T x T buffer.  This is the
  * baseline the sparse path is reported against, not part of SEA.  bf16 only (SEA_ENOTSUP for

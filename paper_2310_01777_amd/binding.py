@@ -31,6 +31,12 @@ class SeaParamsC(ctypes.Structure):
                 ("grouping", ctypes.c_int32), ("geometry", ctypes.c_int32)]
 
 
+class SeaDecoderWeightsC(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("mu_w", "mu_b", "nu1_w", "nu1_b", "nu2_w", "nu2_b", "conv1_w", "conv1_b",
+                                               "conv2_w", "conv2_b", "conv3_w", "conv3_b", "mix_w", "mix_b",
+                                               "prob_w", "prob_b")]
+
+
 class SeaError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -59,6 +65,12 @@ def _load() -> ctypes.CDLL:
     lib.sea_static_scratch_bytes.restype, lib.sea_static_scratch_bytes.argtypes = sz, []
     lib.sea_forward_static_bytes.restype, lib.sea_forward_static_bytes.argtypes = sz, [P]
     lib.sea_forward_static.restype, lib.sea_forward_static.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, vp]
+    DW = ctypes.POINTER(SeaDecoderWeightsC)
+    lib.sea_decoder_workspace_bytes.restype, lib.sea_decoder_workspace_bytes.argtypes = sz, [P]
+    lib.sea_decoder_estimate.restype = ctypes.c_int
+    lib.sea_decoder_estimate.argtypes = [P, DW, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.sea_decoder_forward.restype = ctypes.c_int
+    lib.sea_decoder_forward.argtypes = [P, DW, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.sea_dense_workspace_bytes.restype, lib.sea_dense_workspace_bytes.argtypes = sz, [P]
     lib.sea_dense_attn.restype, lib.sea_dense_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, sz, vp]
     lib.sea_output_mix_workspace_bytes.restype, lib.sea_output_mix_workspace_bytes.argtypes = sz, [P]
@@ -285,6 +297,51 @@ def sea_forward_static(p: SeaParams, Q, K, V, W, O, stream=None):
                                    _ptr(W, p.torch_dtype, p.m * p.d, "W"),
                                    _ptr(O, p.torch_dtype, n * p.d, "O"), _stream(stream)),
            "sea_forward_static")
+
+
+def _decoder_weights(p: SeaParams, w: dict) -> SeaDecoderWeightsC:
+    """dict of device tensors (matrices in bf16, biases in fp32) -> the C struct of pointers."""
+    C, Wd = 4 * p.H, p.K // 2
+    shapes = dict(mu_w=128 * 192, mu_b=128, nu1_w=128 * 128, nu1_b=128, nu2_w=Wd * 4 * 128, nu2_b=Wd * 4,
+                  conv1_w=C * 9 * C, conv1_b=C, conv2_w=C * 9 * C, conv2_b=C, conv3_w=p.H * 9 * C, conv3_b=p.H,
+                  mix_w=128, mix_b=1, prob_w=128, prob_b=1)
+    out = SeaDecoderWeightsC()
+    for name, n in shapes.items():
+        dt = torch.float32 if name.endswith("_b") else torch.bfloat16
+        setattr(out, name, _ptr(w[name], dt, n, name))
+    return out
+
+
+def sea_decoder_workspace_bytes(p: SeaParams) -> int:
+    cp = p.c()
+    return int(_lib.sea_decoder_workspace_bytes(ctypes.byref(cp)))
+
+
+def sea_decoder_estimate(p: SeaParams, weights: dict, Q, K, V, W, A_hat, workspace, s_mix=None, s_prob=None, stream=None):
+    n = p.B * p.H * p.T
+    cp, cw = p.c(), _decoder_weights(p, weights)
+    _check(_lib.sea_decoder_estimate(ctypes.byref(cp), ctypes.byref(cw), _ptr(Q, p.torch_dtype, n * p.d, "Q"),
+                                     _ptr(K, p.torch_dtype, n * p.d, "K"), _ptr(V, p.torch_dtype, n * p.d, "V"),
+                                     _ptr(W, p.torch_dtype, p.m * p.d, "W"),
+                                     _ptr(A_hat, torch.float32, n * p.K, "A_hat"),
+                                     _ptr(s_mix, torch.float32, n, "s_mix"), _ptr(s_prob, torch.float32, n, "s_prob"),
+                                     _ptr(workspace, None, None, "workspace"),
+                                     0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                     _stream(stream)),
+           "sea_decoder_estimate")
+
+
+def sea_decoder_forward(p: SeaParams, weights: dict, Q, K, V, W, O, workspace, A_hat=None, stream=None):
+    n = p.B * p.H * p.T
+    cp, cw = p.c(), _decoder_weights(p, weights)
+    _check(_lib.sea_decoder_forward(ctypes.byref(cp), ctypes.byref(cw), _ptr(Q, p.torch_dtype, n * p.d, "Q"),
+                                    _ptr(K, p.torch_dtype, n * p.d, "K"), _ptr(V, p.torch_dtype, n * p.d, "V"),
+                                    _ptr(W, p.torch_dtype, p.m * p.d, "W"), _ptr(O, p.torch_dtype, n * p.d, "O"),
+                                    _ptr(A_hat, torch.float32, n * p.K, "A_hat"),
+                                    _ptr(workspace, None, None, "workspace"),
+                                    0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                    _stream(stream)),
+           "sea_decoder_forward")
 
 
 def sea_dense_workspace_bytes(p: SeaParams) -> int:

@@ -428,6 +428,108 @@ int sea_forward_static(const sea_params* p, const void* Q, const void* K, const 
                         static_cast<hipStream_t>(hip_stream));
 }
 
+namespace {
+// decoder scratch | A_hat | s_mix | s_prob | mask bits and bucket tables, or idx + cnt (+ bits) | mixing scratch
+struct DecFwdWs {
+  size_t dec, A_hat, s_mix, s_prob, att, mix, total;
+};
+DecFwdWs decoder_forward_layout(const sea_params* p) {
+  const Shape s = make_shape(p, true);
+  const size_t rows = static_cast<size_t>(s.N) * s.T;
+  DecFwdWs w{};
+  size_t off = 0;
+  w.dec = off; off += align256(decoder_workspace(s));
+  w.A_hat = off; off += align256(rows * s.K * sizeof(float));
+  w.s_mix = off; off += align256(rows * sizeof(float));
+  w.s_prob = off; off += align256(rows * sizeof(float));
+  w.att = off;
+  off += align256(rows * ((s.K + 31) / 32) * sizeof(uint32_t));
+  if (tile_attn_supported(s, p->dtype, nullptr)) {
+    off += align256(tile_attn_workspace(s));
+  } else {
+    off += align256(rows * static_cast<size_t>(s.L) * sizeof(int32_t));
+    off += align256(rows * sizeof(int32_t));
+  }
+  w.mix = off; off += align256(output_mix_workspace(s));
+  w.total = off;
+  return w;
+}
+int check_decoder(const sea_params* p) {
+  int rc = check_common(p);
+  if (rc == SEA_OK) rc = check_mask_params(p);
+  if (rc == SEA_OK) rc = check_estimate_params(p);
+  if (rc != SEA_OK) return rc;
+  if (row_stride_of(p) < 0) return SEA_ENOTSUP;
+  if (!decoder_supported(make_shape(p, true), p->dtype)) return SEA_ENOTSUP;
+  return SEA_OK;
+}
+bool weights_complete(const sea_decoder_weights* w) {
+  return w && w->mu_w && w->mu_b && w->nu1_w && w->nu1_b && w->nu2_w && w->nu2_b && w->conv1_w && w->conv1_b &&
+         w->conv2_w && w->conv2_b && w->conv3_w && w->conv3_b && w->mix_w && w->mix_b && w->prob_w && w->prob_b;
+}
+}  // namespace
+
+size_t sea_decoder_workspace_bytes(const sea_params* p) {
+  if (check_decoder(p) != SEA_OK) return 0;
+  return decoder_forward_layout(p).total;
+}
+
+int sea_decoder_estimate(const sea_params* p, const sea_decoder_weights* w, const void* Q, const void* K,
+                         const void* V, const void* W, float* A_hat, float* s_mix_opt, float* s_prob_opt,
+                         void* workspace, size_t workspace_bytes, void* hip_stream) {
+  const int rc = check_decoder(p);
+  if (rc != SEA_OK) return rc;
+  if (!Q || !K || !V || !W || !A_hat || !weights_complete(w)) return SEA_EINVAL;
+  const Shape s = make_shape(p, true);
+  if (!workspace || workspace_bytes < align256(decoder_workspace(s)) ||
+      reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+    return SEA_EWORKSPACE;
+  const hipError_t e = launch_decoder_estimate(s, *w, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                                               static_cast<const uint16_t*>(V), static_cast<const uint16_t*>(W), A_hat,
+                                               s_mix_opt, s_prob_opt, workspace, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SEA_OK : fail_hip(e);
+}
+
+int sea_decoder_forward(const sea_params* p, const sea_decoder_weights* w, const void* Q, const void* K,
+                        const void* V, const void* W, void* O, float* A_hat_opt, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  const int rc = check_decoder(p);
+  if (rc != SEA_OK) return rc;
+  if (!Q || !K || !V || !W || !O || !weights_complete(w)) return SEA_EINVAL;
+  const DecFwdWs lay = decoder_forward_layout(p);
+  if (!workspace || workspace_bytes < lay.total || reinterpret_cast<uintptr_t>(workspace) % 256 != 0)
+    return SEA_EWORKSPACE;
+  const Shape s = make_shape(p, true);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  char* base = static_cast<char*>(workspace);
+  const size_t rows = static_cast<size_t>(s.N) * s.T;
+  float* A_hat = A_hat_opt ? A_hat_opt : reinterpret_cast<float*>(base + lay.A_hat);
+  float* s_mix = reinterpret_cast<float*>(base + lay.s_mix);
+  float* s_prob = reinterpret_cast<float*>(base + lay.s_prob);
+  hipError_t e = launch_decoder_estimate(s, *w, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                                         static_cast<const uint16_t*>(V), static_cast<const uint16_t*>(W), A_hat, s_mix,
+                                         s_prob, base + lay.dec, st);
+  if (e != hipSuccess) return fail_hip(e);
+  char* att = base + lay.att;
+  uint32_t* mbits = reinterpret_cast<uint32_t*>(att);
+  att += align256(rows * ((s.K + 31) / 32) * sizeof(uint32_t));
+  if (tile_attn_supported(s, p->dtype, nullptr)) {
+    e = launch_topk_mask(s, A_hat, nullptr, nullptr, nullptr, mbits, st);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_tile_attn(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                         static_cast<const uint16_t*>(V), mbits, static_cast<uint16_t*>(O), att, st);
+  } else {
+    int32_t* idx = reinterpret_cast<int32_t*>(att);
+    int32_t* cnt = reinterpret_cast<int32_t*>(att + align256(rows * static_cast<size_t>(s.L) * sizeof(int32_t)));
+    e = launch_topk_mask(s, A_hat, nullptr, idx, cnt, s.grouping == 1 ? mbits : nullptr, st);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_sparse_attn(s, p->dtype, Q, K, V, idx, cnt, s.L, nullptr, O, st);
+  }
+  if (e != hipSuccess) return fail_hip(e);
+  e = launch_output_mix(s, p->dtype, O, V, A_hat, s_prob, s_mix, O, base + lay.mix, st);
+  return e == hipSuccess ? SEA_OK : fail_hip(e);
+}
+
 size_t sea_dense_workspace_bytes(const sea_params* p) {
   if (check_common(p) != SEA_OK || p->dtype != SEA_BF16) return 0;
   return dense_attn_workspace(make_shape(p, false));

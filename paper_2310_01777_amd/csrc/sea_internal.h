@@ -81,6 +81,13 @@ hipError_t launch_output_mix(const Shape& s, sea_dtype dt, const void* C, const 
                              const float* A_hat, const float* s_prob, const float* s_mix, void* O,
                              void* ws, hipStream_t st);
 
+// decoder path (bf16, m in {64,128,256}, even K, 8 | 4 H, fixed key buckets)
+bool decoder_supported(const Shape& s, sea_dtype dt);
+size_t decoder_workspace(const Shape& s);
+hipError_t launch_decoder_estimate(const Shape& s, const sea_decoder_weights& wt, const uint16_t* Q, const uint16_t* K,
+                                   const uint16_t* V, const uint16_t* W, float* A_hat, float* s_mix, float* s_prob,
+                                   void* ws, hipStream_t st);
+
 // ---- per-stage event timing (see sea_profile_enable) ----
 void stage_begin(sea_stage stage, hipStream_t st);
 void stage_end(sea_stage stage, hipStream_t st);
