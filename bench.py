@@ -48,6 +48,7 @@ def parse():
                          "each causal row resized to its own t + 1 keys (App. A.4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the short runs of the other configurations")
+    ap.add_argument("--no-decoder", action="store_true", help="skip the decoder-shaped layer (c2 and c5 shapes)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="CPU-work budget of the oracle sample")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MiB",
                     help="only run a plain device copy of this many MiB three times (calibrates the "
@@ -301,6 +302,59 @@ def measure(torch, sea, synth, wl, steps, warmup, detail):
     return rec, ctx
 
 
+def decoder_leg(torch, sea, synth, name, steps):
+    """The paper's whole layer with its learned decoder (Sec. 3.1 "CNN Decoder", App. A.5.1) on random
+    stand-in weights: sea_decoder_forward = Performer output on [V_I; V], MLPs, three-layer CNN, softmax,
+    top-k^, sparse attention, output mixing.  A throughput workload: no quality claim.  Reports the
+    dense / sparse split the paper's Fig. "complexity" gives for its own implementation."""
+    dev = "cuda:0"
+    wl = synth.get_workload(name)
+    x = synth.make_inputs(wl)
+    d = {k: x[k].to(dev) for k in "QKVW"}
+    sl = None if x["seq_len"] is None else x["seq_len"].to(dev)
+    p = sea.SeaParams(B=wl.B, H=wl.H, T=wl.T, d=wl.d, m=wl.m, K=wl.K, k_hat=wl.k_hat, k_budget=wl.k_budget,
+                      causal=wl.causal, scale=wl.scale, dtype=wl.dtype, seq_len=sl)
+    nbytes = sea.sea_decoder_workspace_bytes(p)
+    if nbytes == 0:
+        return None
+    wd = {k: v.to(dev) for k, v in synth.decoder_weights(wl.H, wl.d, wl.K).items()}
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    O = torch.empty_like(d["Q"])
+    step = lambda: sea.sea_decoder_forward(p, wd, d["Q"], d["K"], d["V"], d["W"], O, ws)
+    for _ in range(3):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    sea.sea_profile_enable(True)
+    sea.sea_profile_collect()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    st = sea.sea_profile_collect()
+    sea.sea_profile_enable(False)
+    avg = {k: v[0] / v[1] for k, v in st.items() if v[1] > 0}
+    dense_ms = sum(avg.get(k, 0.0) for k in ("features", "state", "contract"))
+    sparse_ms = avg.get("topk_mask", 0.0) + avg.get("sparse", 0.0)
+    C, Wd, N = 4 * wl.H, wl.K // 2, wl.B * wl.H
+    T1 = wl.T if wl.causal else -(-wl.T // 2)
+    conv_flops = 2.0 * wl.B * 9 * C * (C * T1 * Wd * 2 + wl.H * wl.T * wl.K)
+    mlp_flops = 2.0 * N * wl.T * 128 * (192 + 128 + 4 * Wd)
+    lin_flops = 2.0 * N * wl.T * wl.m * (2 * 144 + (32 if wl.causal else 0)) + 4.0 * N * wl.T * wl.d * wl.m
+    cms = avg.get("contract", 0.0)
+    return {"workload": wl.name, "ms_per_step": ms, "tokens_per_s": wl.B * wl.T / (ms * 1e-3), "stage_ms": avg,
+            "dense_ms": dense_ms, "sparse_ms": sparse_ms,
+            "dense_share": dense_ms / max(dense_ms + sparse_ms, 1e-12),
+            "mlp_cnn_tflops": (conv_flops + mlp_flops) / (cms * 1e-3) / 1e12 if cms > 0 else None,
+            "mlp_cnn_frac_of_bf16_mfma_peak": (conv_flops + mlp_flops) / (cms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS if cms > 0 else None,
+            "performer_flops": lin_flops, "weights": "random (Gaussian, fan-in scaled), seed 7",
+            "note": "stages: features = phi(Q), phi(K); state = linear attention on [V_I; V]; contract = mu, nu, "
+                    "CNN, softmax; topk_mask + sparse = selection and sparse attention"}
+
+
 def copy_rate(torch, mib=1024, reps=10):
     """GB/s (read + written bytes) of a plain device-to-device copy: the achievable HBM figure."""
     src = torch.ones(mib << 20, dtype=torch.uint8, device="cuda:0")
@@ -452,6 +506,9 @@ def main():
             del c2
             torch.cuda.empty_cache()
         out["sweep"] = sweep
+    if not args.no_decoder:
+        out["decoder"] = {name: decoder_leg(torch, sea, synth, name, max(5, args.steps // 20)) for name in ("c2", "c5")}
+        torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, x, args.cpu_seconds)
     print(json.dumps(out))
