@@ -326,7 +326,10 @@ __global__ __launch_bounds__(256) void dec_concat_kernel(const float* __restrict
 // [B][Tin][Xin][Cin], read through an optional nearest resize to Tv x Xv (source index
 // floor(v * size / vsize)); zero outside the (virtual) image.  Computed transposed,
 // C[cout][pixel] = W x X^T: the lane is the pixel, a lane holds four consecutive output channels.
-// Block = 4 waves, wave = 32 pixels x up to 128 output channels (blockIdx.y picks the slab).
+// Wide layers (dec_conv_lds_kernel): block = 4 waves, wave = 64 pixels x up to 128 output channels
+// (blockIdx.y picks the channel slab); the weights of the block's channels go through LDS in slabs of
+// 128 contraction elements (fetched into registers one slab ahead), the pixels' operand fragments
+// come straight from memory.
 // ------------------------------------------------------------------------------------------
 struct ConvArgs {
   const uint16_t* in;
@@ -339,6 +342,144 @@ struct ConvArgs {
   const int32_t* seq_len;
 };
 
+constexpr int kSlabK = 128;            // contraction elements of the weights staged per step
+constexpr int kSlabRow = kSlabK + 8;   // halfwords per staged weight row (+16 B: b128 reads spread over the banks)
+
+__global__ __launch_bounds__(256, 2) void dec_conv_lds_kernel(ConvArgs a) {
+  // weights of the block's 128 output channels for one slab of the contraction, shared by the four waves
+  __shared__ __attribute__((aligned(16))) uint16_t Wsl[128 * kSlabRow];
+  const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int64_t npix = static_cast<int64_t>(a.B) * a.Tout * a.Xout;
+  const int64_t pix0 = (static_cast<int64_t>(blockIdx.x) * 4 + wid) * 64;  // may lie past the end: the wave then only stages
+  const int32_t cout0 = blockIdx.y * 128;
+  const int32_t ntiles = min(8, (a.Cout - cout0 + 15) / 16);
+  const int32_t ktot = a.taps * a.Cin;
+  const int32_t nslabs = (ktot + kSlabK - 1) / kSlabK;
+  // this lane's four pixels (operand columns)
+  int32_t pb[4], pt[4], px[4];
+  bool pok[4];
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt) {
+    const int64_t p = pix0 + 16 * mt + lr;
+    pok[mt] = p < npix;
+    const int64_t pc = pok[mt] ? p : npix - 1;
+    px[mt] = static_cast<int32_t>(pc % a.Xout);
+    pt[mt] = static_cast<int32_t>((pc / a.Xout) % a.Tout);
+    pb[mt] = static_cast<int32_t>(pc / (static_cast<int64_t>(a.Xout) * a.Tout));
+  }
+  floatx4 acc[8][4];
+#pragma unroll
+  for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) acc[nt][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // staging role: 16-byte piece (tid & 15) of rows (tid >> 4) + 16 q, q < 8
+  const int srow = tid >> 4, spart = tid & 15;
+  uint4 wreg[8];
+  auto fetch = [&](int32_t slab) {
+    const int32_t k = slab * kSlabK + 8 * spart;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int32_t co = cout0 + srow + 16 * q;
+      wreg[q] = (co < a.Cout && k < ktot) ? *reinterpret_cast<const uint4*>(a.w + static_cast<int64_t>(co) * ktot + k)
+                                          : make_uint4(0u, 0u, 0u, 0u);
+    }
+  };
+  auto park = [&]() {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) *reinterpret_cast<uint4*>(&Wsl[(srow + 16 * q) * kSlabRow + 8 * spart]) = wreg[q];
+  };
+  fetch(0);
+  park();
+  __syncthreads();
+  for (int32_t slab = 0; slab < nslabs; ++slab) {
+    if (slab + 1 < nslabs) fetch(slab + 1);
+    if (pix0 < npix) {
+#pragma unroll
+      for (int ks = 0; ks < kSlabK / 32; ++ks) {
+        const int32_t kbase = slab * kSlabK + 32 * ks;
+        if (kbase >= ktot) break;
+        const int32_t k0 = kbase + 8 * lg;
+        const bool kok = k0 < ktot;
+        const int32_t tap = kok ? k0 / a.Cin : 0, c0 = kok ? k0 - tap * a.Cin : 0;
+        const int32_t ky = a.taps == 9 ? tap / 3 : 0, kx = a.taps == 9 ? tap - 3 * ky : 0;
+        bf16x8 xf[4];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+          const int32_t tv = pt[mt] * a.stride_t + ky - a.pad_top;
+          const int32_t xv = a.taps == 9 ? px[mt] + kx - 1 : px[mt];
+          const bool ok = kok && pok[mt] && tv >= 0 && tv < a.Tv && xv >= 0 && xv < a.Xv;
+          if (ok) {
+            const int32_t ts = a.Tv == a.Tin ? tv : static_cast<int32_t>((static_cast<int64_t>(tv) * a.Tin) / a.Tv);
+            const int32_t xs = a.Xv == a.Xin ? xv : static_cast<int32_t>((static_cast<int64_t>(xv) * a.Xin) / a.Xv);
+            xf[mt] = load8(a.in + ((static_cast<int64_t>(pb[mt]) * a.Tin + ts) * a.Xin + xs) * a.Cin + c0);
+          } else {
+            xf[mt] = zero8();
+          }
+        }
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) {
+          if (nt < ntiles) {
+            const bf16x8 wf = *reinterpret_cast<const bf16x8*>(&Wsl[(16 * nt + lr) * kSlabRow + 32 * ks + 8 * lg]);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) acc[nt][mt] = mfma16(wf, xf[mt], acc[nt][mt]);
+          }
+        }
+      }
+    }
+    __syncthreads();  // every wave is done with the slab
+    if (slab + 1 < nslabs) {
+      park();
+      __syncthreads();
+    }
+  }
+  if (pix0 >= npix) return;
+  // epilogue: tile (nt, mt): rows = output channels cout0 + 16 nt + 4 lg + i, column = pixel lr of tile mt
+#pragma unroll
+  for (int nt = 0; nt < 8; ++nt) {
+    if (nt >= ntiles) continue;
+    const int32_t co = cout0 + 16 * nt + 4 * lg;
+    if (co >= a.Cout) continue;
+    float bv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bv[i] = co + i < a.Cout ? a.bias[co + i] : 0.f;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+      if (!pok[mt]) continue;
+      float v[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        v[i] = acc[nt][mt][i] + bv[i];
+        if (a.relu) v[i] = fmaxf(v[i], 0.f);
+      }
+      const int64_t p = pix0 + 16 * mt + lr;
+      if (a.mode == 0) {
+        uint2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) + p * a.Cout + co) = pk;
+      } else if (a.mode == 1) {
+        // row p = (b h, t); outputs co .. co + 3 = compressed column co / 4, extra channels 0..3
+        const int64_t n = p / a.T;
+        const int32_t t = static_cast<int32_t>(p - n * a.T);
+        const int32_t b = static_cast<int32_t>(n / a.H), h = static_cast<int32_t>(n - static_cast<int64_t>(b) * a.H);
+        const int32_t len = a.seq_len ? min(max(a.seq_len[b], 0), a.T) : a.T;
+        uint2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        if (t >= len) pk = make_uint2(0u, 0u);
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) +
+                                  ((static_cast<int64_t>(b) * a.T + t) * a.Wd + (co >> 2)) * a.C + h * kCh) = pk;
+      } else {
+        float* o = static_cast<float*>(a.out);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (co + i < a.Cout)
+            o[((static_cast<int64_t>(pb[mt]) * a.Cout + co + i) * a.Tout + pt[mt]) * a.Xout + px[mt]] = v[i];
+      }
+    }
+  }
+}
+
+// The same product for few output channels or a short contraction: wave = 32 pixels, every operand
+// fragment straight from memory (the weights stay in the caches), no barriers.
 __global__ __launch_bounds__(256) void dec_conv_kernel(ConvArgs a) {
   const int lane = threadIdx.x & 63, wid = threadIdx.x >> 6;
   const int lr = lane & 15, lg = lane >> 4;
@@ -520,8 +661,12 @@ DecWs dec_layout(const Shape& s) {
 
 void launch_conv(const ConvArgs& a, hipStream_t st) {
   const int64_t npix = static_cast<int64_t>(a.B) * a.Tout * a.Xout;
-  const dim3 grid(static_cast<uint32_t>((npix + 127) / 128), static_cast<uint32_t>((a.Cout + 127) / 128));
-  hipLaunchKernelGGL(dec_conv_kernel, grid, dim3(256), 0, st, a);
+  const uint32_t slabs = static_cast<uint32_t>((a.Cout + 127) / 128);
+  if (a.Cout >= 96 && a.taps * a.Cin >= 512) {
+    hipLaunchKernelGGL(dec_conv_lds_kernel, dim3(static_cast<uint32_t>((npix + 255) / 256), slabs), dim3(256), 0, st, a);
+  } else {
+    hipLaunchKernelGGL(dec_conv_kernel, dim3(static_cast<uint32_t>((npix + 127) / 128), slabs), dim3(256), 0, st, a);
+  }
 }
 
 }  // namespace
