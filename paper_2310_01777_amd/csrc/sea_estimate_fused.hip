@@ -103,6 +103,41 @@ __device__ __forceinline__ float group_sum(float x) {
   return x;
 }
 
+// all-reduce over the four lanes l % 16 + 16 q of a wave (one lane of each 16-lane row): the
+// row-swap instructions hand every lane the value of its partner row, two steps cover all four
+__device__ __forceinline__ uint32_t rows_sum_u(uint32_t x) {
+  const auto a = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+  const uint32_t y = a[0] + a[1];
+  const auto b = __builtin_amdgcn_permlane32_swap(y, y, false, false);
+  return b[0] + b[1];
+}
+__device__ __forceinline__ uint32_t rows_or_u(uint32_t x) {
+  const auto a = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+  const uint32_t y = a[0] | a[1];
+  const auto b = __builtin_amdgcn_permlane32_swap(y, y, false, false);
+  return b[0] | b[1];
+}
+__device__ __forceinline__ uint32_t rows_max_u(uint32_t x) {
+  const auto a = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+  const uint32_t y = max(a[0], a[1]);
+  const auto b = __builtin_amdgcn_permlane32_swap(y, y, false, false);
+  return max(b[0], b[1]);
+}
+__device__ __forceinline__ float rows_sum(float x) {
+  const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  const float y = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+// sum over the rows and, for each lane, the sum over the rows below its own (rows in order 0..3)
+__device__ __forceinline__ uint32_t rows_sum_prefix_u(uint32_t x, int lg, uint32_t* below) {
+  const auto a = __builtin_amdgcn_permlane16_swap(x, x, false, false);   // a[0]: even row of the pair, a[1]: odd
+  const uint32_t pair = a[0] + a[1];
+  const auto b = __builtin_amdgcn_permlane32_swap(pair, pair, false, false);  // b[0]: rows 0,1; b[1]: rows 2,3
+  *below = ((lg & 1) ? a[0] : 0u) + ((lg & 2) ? b[0] : 0u);
+  return b[0] + b[1];
+}
+
 // stage W (m rows of 64 bf16) into LDS with padded rows
 __device__ __forceinline__ void stage_w(const uint16_t* __restrict__ W, uint16_t* Ws, int m, int tid) {
   for (int x = tid; x < m * 8; x += 256) {
@@ -447,8 +482,10 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     }
   }
   __builtin_amdgcn_sched_barrier(0);  // keep the two projections' temporaries from overlapping
-  // accumulator rows of this lane: r0 + 4 lg + i
-  float diag[4] = {0.f, 0.f, 0.f, 0.f};
+  // From here on every product is taken with the query rows as accumulator COLUMNS: lane l % 16 is
+  // the query row, so a row of A_hat lives in the four lanes l % 16 + 16 q (16 values each per 64
+  // columns) and every per-row reduction is two row-swap steps.
+  float diag = 0.f;
   if (CAUSAL) {
     // the row's own column: sum over keys j <= t of that column of phi(q_t) . phi(k_j).  Those
     // keys are the wave's own 16 rows (S = phi(Q) phi(K_own)^T with a lower-triangular, same-column
@@ -467,17 +504,17 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
         lo[i] = __builtin_amdgcn_exp2f(arg[2 * kc][i]);
         hi[i] = __builtin_amdgcn_exp2f(arg[2 * kc + 1][i]);
       }
-      sd = mfma16(afrag[kc], pack8(lo, hi), sd);  // rows = queries 4 lg + i, col = key lr
+      sd = mfma16(pack8(lo, hi), afrag[kc], sd);  // rows = keys 4 lg + i, col = query lr
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int rq = 4 * lg + i;  // query row within the wave; key row within the wave is lr
-      const bool ok = (lr <= rq) && (WLOG >= 4 || (lr >> WLOG) == (rq >> WLOG));
+      const int rk = 4 * lg + i;  // key row within the wave; the query row within the wave is lr
+      const bool ok = (rk <= lr) && (WLOG >= 4 || (rk >> WLOG) == (lr >> WLOG));
       sd[i] = ok ? sd[i] : 0.f;
     }
     // Earlier keys of the same column: every one of them precedes every row of the wave, so only
-    // their sum matters.  It comes as three bf16 planes = operand columns 0..2 (the rest zero);
-    // the row sum over the 16 result columns below then adds the three partial dots to the
+    // their sum matters.  It comes as three bf16 planes = operand rows 0..2 (the rest zero);
+    // the sum over the 16 result rows below then adds the three partial dots to the
     // in-wave ones.  Two levels: tiles before this one inside its 128-key block (its column, if
     // narrower), and, for columns wider than that, the column's blocks before this one.
     if (WLOG >= 5 && r0 < s.T) {
@@ -488,7 +525,7 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
         for (int kc = 0; kc < MC; ++kc) {
           uint4 f = *reinterpret_cast<const uint4*>(src + 32 * kc);
           if (lr > 2) f = uint4{0u, 0u, 0u, 0u};
-          sd = mfma16(afrag[kc], __builtin_bit_cast(bf16x8, f), sd);
+          sd = mfma16(__builtin_bit_cast(bf16x8, f), afrag[kc], sd);
         }
       }
       if (wl > 7 && ((r0 >> 7) & ((1 << (wl - 7)) - 1)) != 0) {
@@ -497,12 +534,11 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
         for (int kc = 0; kc < MC; ++kc) {
           uint4 f = *reinterpret_cast<const uint4*>(src + 32 * kc);
           if (lr > 2) f = uint4{0u, 0u, 0u, 0u};
-          sd = mfma16(afrag[kc], __builtin_bit_cast(bf16x8, f), sd);
+          sd = mfma16(__builtin_bit_cast(bf16x8, f), afrag[kc], sd);
         }
       }
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) diag[i] = group_sum<16>(sd[i]);
+    diag = rows_sum((sd[0] + sd[1]) + (sd[2] + sd[3]));
   }
 
   // ---- A_hat tile = phi(Q) state^T, state streamed through LDS ----
@@ -524,7 +560,7 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
           floatx4 a4 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int kc = 0; kc < MC; ++kc)
-            a4 = mfma16(afrag[kc], *reinterpret_cast<const bf16x8*>(brow + 32 * kc), a4);
+            a4 = mfma16(*reinterpret_cast<const bf16x8*>(brow + 32 * kc), afrag[kc], a4);
           acc[st * (kColStage / 16) + h] = a4;
         }
       }
@@ -539,71 +575,68 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   if (r0 >= s.T) return;  // no barrier below
 
   // ---- masking, the own column, normalisation ----
-  // last[i] = last admissible column of row i (-1: inactive row); causal rows take their own
-  // column (= last) from diag.  Column cc = 16 ct + lr is the own one iff 16 ct == e, masked iff
-  // 16 ct > e, with e = last - lr.  Tiles wholly below every row's last column need neither test,
-  // tiles above the wave's last one are cleared.
-  int32_t trow[4], ncnd[4], e[4];
-  bool act[4];
-  float rsum[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    trow[i] = r0 + 4 * lg + i;
-    act[i] = trow[i] < len;
-    const int32_t jmax = CAUSAL ? min(trow[i], len - 1) : len - 1;
-    ncnd[i] = act[i] ? (jmax >> wl) + 1 : 0;
-    e[i] = ncnd[i] - 1 - lr;
-  }
+  // acc[ct][i] = raw score of row r0 + lr, column cc = 16 ct + 4 lg + i.  last = last admissible
+  // column of the row (-1: inactive row); a causal row takes its own column (= last) from diag.
+  // Tiles wholly below every row's last column need no test, tiles above the wave's last one are
+  // cleared.
+  const int32_t trow = r0 + lr;
+  const bool act = trow < len;
+  const int32_t jmax = CAUSAL ? min(trow, len - 1) : len - 1;
+  const int32_t ncnd = act ? (jmax >> wl) + 1 : 0;
+  const int32_t e = ncnd - 1 - 4 * lg;  // column 16 ct + 4 lg + i is the own one iff 16 ct + i == e
   const bool act_all = r0 + 15 < len;  // wave-uniform
   const int32_t ct_free = act_all ? (((CAUSAL ? r0 : len - 1) >> wl) >> 4) : 0;
+  float rsum = 0.f;
 #pragma unroll
   for (int ct = 0; ct < NCT; ++ct) {
     if (ct < ct_free) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) rsum[i] += acc[ct][i];
+      rsum += (acc[ct][0] + acc[ct][1]) + (acc[ct][2] + acc[ct][3]);
     } else if (ct * 16 < ncols_wave) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         float v = acc[ct][i];
-        if (CAUSAL && ct * 16 == e[i]) v = diag[i];
-        if (ct * 16 > e[i]) v = 0.f;
+        if (CAUSAL && ct * 16 + i == e) v = diag;
+        if (ct * 16 + i > e) v = 0.f;
         acc[ct][i] = v;
-        rsum[i] += v;
+        rsum += v;
       }
     } else {
       acc[ct] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
   }
-  float* out = A_hat ? A_hat + (head * s.T) * s.K : nullptr;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const float r = group_sum<16>(rsum[i]);
+  {
+    const float r = rows_sum(rsum);
     const float inv = r > 0.f ? 1.f / r : 0.f;
 #pragma unroll
-    for (int ct = 0; ct < NCT; ++ct) acc[ct][i] *= inv;
-    if (out && trow[i] < s.T) {
+    for (int ct = 0; ct < NCT; ++ct)
 #pragma unroll
-      for (int ct = 0; ct < NCT; ++ct) {
-        const int32_t cc = ct * 16 + lr;
-        if (cc < s.K) out[static_cast<int64_t>(trow[i]) * s.K + cc] = acc[ct][i];
+      for (int i = 0; i < 4; ++i) acc[ct][i] *= inv;
+    if (A_hat && trow < s.T) {
+      float* out = A_hat + (head * s.T + trow) * s.K;
+      if ((s.K & 3) == 0) {
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct)
+          if (ct * 16 + 4 * lg < s.K)
+            *reinterpret_cast<float4*>(out + ct * 16 + 4 * lg) = make_float4(acc[ct][0], acc[ct][1], acc[ct][2], acc[ct][3]);
+      } else {
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (ct * 16 + 4 * lg + i < s.K) out[ct * 16 + 4 * lg + i] = acc[ct][i];
       }
     }
   }
   if (!mbits) return;
 
   // ---- per-row top-k^ on the normalised scores, in registers (Sec. 3.1 "Grouped Top-k^
-  // Selection", per-query grouping).  Row 4 lg + i lives in the 16 lanes of group lg, one
-  // score per (column tile, lane).  The k^-th largest score is found by a bitwise search on
-  // order-preserving integer keys; counts are summed over the 16 lanes with DPP.  Scores are
-  // in [0, 1], so the key's two top bits are known and the search starts below them.
-  uint32_t tau[4], cge[4], nsel[4];
+  // Selection", per-query grouping).  A row lives in four lanes, 4 NCT scores each.  The k^-th
+  // largest score is found by a bitwise search on order-preserving integer keys; every lane counts
+  // its own scores and the four counts meet in two row-swap steps.  Scores are in [0, 1], so the
+  // key's two top bits are known and the search starts below them.
+  const uint32_t nsel = static_cast<uint32_t>(min(s.k_hat, ncnd));
+  uint32_t tau = 0x80000000u, cge = static_cast<uint32_t>(ncnd);
   uint32_t key[NCT][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    nsel[i] = static_cast<uint32_t>(min(s.k_hat, ncnd[i]));
-    tau[i] = 0x80000000u;
-    cge[i] = static_cast<uint32_t>(ncnd[i]);
-  }
 #pragma unroll
   for (int ct = 0; ct < NCT; ++ct) {
     if (ct < ct_free) {  // every column of the tile is a candidate of every row
@@ -612,83 +645,71 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     } else {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        key[ct][i] = ct * 16 <= e[i] ? (__float_as_uint(acc[ct][i] + 0.0f) | 0x80000000u) : 0x40000000u;
+        key[ct][i] = ct * 16 + i <= e ? (__float_as_uint(acc[ct][i] + 0.0f) | 0x80000000u) : 0x40000000u;
     }
   }
   // The compare-and-count loop runs over the tiles that hold candidates of this wave's rows only
   // (causal: the leading ones), in even steps so that a handful of loop bodies covers all cases.
-// Bits 29..16 are searched on the keys' high halves, two keys per register: both halves of
-// hp - trial (16-bit wrap-around differences; candidates and trial lie in [0x8000, 0xc000),
-// non-candidates are 0x4000) have bit 15 set exactly for keys below the trial, and those bits are
-// counted four differences at a time.  The trial's low half is zero in that phase, so the counts
-// are those of the full keys.  Bits 15..0 then compare whole keys.
+  // Bits 29..16 are searched on the keys' high halves, two keys per register: both halves of
+  // hp - trial (16-bit wrap-around differences; candidates and trial lie in [0x8000, 0xc000),
+  // non-candidates are 0x4000) have bit 15 set exactly for keys below the trial, and those bits are
+  // counted four differences at a time.  The trial's low half is zero in that phase, so the counts
+  // are those of the full keys.  Bits 15..0 then compare whole keys.
 #define SEA_SEARCH_STEP(COUNT_BODY_)                                                             \
     /* done when every row's count of keys >= tau equals its quota */                            \
-    bool pend[4];                                                                                \
-    bool pending = false;                                                                        \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                               \
-      pend[i] = (cge[i] != nsel[i]) && (nsel[i] != 0u);                                          \
-      pending |= pend[i];                                                                        \
-    }                                                                                            \
-    if (__ballot(pending) == 0ull) break;                                                        \
-    uint32_t cnts[4] = {0u, 0u, 0u, 0u};                                                         \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                               \
-      /* skip the slot once its four rows (one per lane group) are settled */                    \
-      if (__ballot(pend[i]) == 0ull) continue;                                                   \
-      const uint32_t trial = tau[i] | (1u << bit);                                               \
-      uint32_t cnt = 0;                                                                          \
-      COUNT_BODY_                                                                                \
-      cnts[i] = cnt;                                                                             \
-    }                                                                                            \
-    /* the four lane-group sums side by side: their cross-lane steps fill each other's gaps */   \
-    group_sum4_u(cnts);                                                                          \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                               \
-      const bool take = pend[i] && cnts[i] >= nsel[i];                                           \
-      tau[i] = take ? (tau[i] | (1u << bit)) : tau[i];                                           \
-      cge[i] = take ? cnts[i] : cge[i];                                                          \
-    }
+    const bool pend = (cge != nsel) && (nsel != 0u);                                             \
+    if (__ballot(pend) == 0ull) break;                                                           \
+    const uint32_t trial = tau | (1u << bit);                                                    \
+    uint32_t cnt = 0;                                                                            \
+    COUNT_BODY_                                                                                  \
+    cnt = rows_sum_u(cnt);                                                                       \
+    const bool take = pend && cnt >= nsel;                                                       \
+    tau = take ? trial : tau;                                                                    \
+    cge = take ? cnt : cge;
 #define SEA_SEARCH(NT_)                                                                          \
   {                                                                                              \
-    ushort2v hp[(NT_) / 2][4];                                                                   \
-    _Pragma("unroll") for (int pr = 0; pr < (NT_) / 2; ++pr)                                      \
-      _Pragma("unroll") for (int i = 0; i < 4; ++i)                                               \
-        hp[pr][i] = __builtin_bit_cast(ushort2v, __builtin_amdgcn_perm(key[2 * pr + 1][i], key[2 * pr][i], 0x07060302u)); \
+    ushort2v hp[2 * (NT_)];                                                                      \
+    _Pragma("unroll") for (int ct = 0; ct < (NT_); ++ct) {                                        \
+      hp[2 * ct] = __builtin_bit_cast(ushort2v, __builtin_amdgcn_perm(key[ct][1], key[ct][0], 0x07060302u)); \
+      hp[2 * ct + 1] = __builtin_bit_cast(ushort2v, __builtin_amdgcn_perm(key[ct][3], key[ct][2], 0x07060302u)); \
+    }                                                                                            \
     _Pragma("unroll 1") for (int bit = 29; bit >= 16; --bit) {                                    \
       SEA_SEARCH_STEP(                                                                           \
         const uint32_t th = trial >> 16;                                                         \
         const ushort2v th2 = __builtin_bit_cast(ushort2v, th | (th << 16));                      \
         uint32_t below = 0;                                                                      \
-        _Pragma("unroll") for (int pr = 0; pr < (NT_) / 2; pr += 2) {                             \
-          const uint32_t d0 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr][i] - th2)); \
-          const uint32_t d1 = (pr + 1 < (NT_) / 2)                                               \
-              ? __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr + 1 < (NT_) / 2 ? pr + 1 : pr][i] - th2)) : 0u; \
+        _Pragma("unroll") for (int pr = 0; pr < 2 * (NT_); pr += 2) {                             \
+          const uint32_t d0 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr] - th2)); \
+          const uint32_t d1 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr + 1] - th2)); \
           /* the four sign bytes of two differences */                                           \
           const uint32_t sb = __builtin_amdgcn_perm(d1, d0, 0x07050301u) & 0x80808080u;          \
           below += static_cast<uint32_t>(__popc(sb));                                            \
         }                                                                                        \
-        cnt = static_cast<uint32_t>(NT_) - below;)                                               \
+        cnt = 4u * static_cast<uint32_t>(NT_) - below;)                                          \
     }                                                                                            \
   }                                                                                              \
   _Pragma("unroll 1") for (int bit = 15; bit >= 0; --bit) {                                       \
     SEA_SEARCH_STEP(                                                                             \
-      _Pragma("unroll") for (int ct = 0; ct < (NT_); ++ct) cnt += (key[ct][i] >= trial) ? 1u : 0u;) \
+      _Pragma("unroll") for (int ct = 0; ct < (NT_); ++ct)                                        \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) cnt += (key[ct][i] >= trial) ? 1u : 0u;)   \
   }
   const int32_t nct_wave = CAUSAL ? min(NCT, (ncols_wave + 15) >> 4) : NCT;
   if (s.k_hat == 1) {
     // one column per row: the threshold is the row maximum itself (several columns holding it
     // are told apart by the tie rule below)
+    uint32_t mx = 0u;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      uint32_t mx = 0u;
+    for (int ct = 0; ct < NCT; ++ct)
 #pragma unroll
-      for (int ct = 0; ct < NCT; ++ct) mx = max(mx, key[ct][i]);
-      mx = group_max_u<16>(mx);
-      uint32_t cnt = 0;
+      for (int i = 0; i < 4; ++i) mx = max(mx, key[ct][i]);
+    mx = rows_max_u(mx);
+    uint32_t cnt = 0;
 #pragma unroll
-      for (int ct = 0; ct < NCT; ++ct) cnt += (key[ct][i] >= mx) ? 1u : 0u;
-      tau[i] = mx;
-      cge[i] = group_sum_u<16>(cnt);
-    }
+    for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) cnt += (key[ct][i] >= mx) ? 1u : 0u;
+    tau = mx;
+    cge = rows_sum_u(cnt);
   } else if (NCT >= 16 && nct_wave > 12) {
     SEA_SEARCH(NCT >= 16 ? 16 : NCT)
   } else if (NCT >= 16 && nct_wave > 8) {
@@ -705,72 +726,70 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
 #undef SEA_SEARCH
 #undef SEA_SEARCH_STEP
   // selection: keys >= tau; when more keys than the quota tie at tau (exact duplicates at the
-  // boundary), the lowest columns among them win
-  uint32_t selbits[4];  // bit ct set: column 16 ct + lr of row 4 lg + i is selected
-  bool excess = false;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) excess |= (cge[i] != nsel[i]) && (nsel[i] != 0u);
+  // boundary), the lowest columns among them win.  nib[ct]: bit i set iff column 16 ct + 4 lg + i
+  // of this lane's row is selected.
+  uint32_t nib[NCT];
+  const bool excess = (cge != nsel) && (nsel != 0u);
   if (__ballot(excess) == 0ull) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int ct = 0; ct < NCT; ++ct) {
       uint32_t bits = 0;
 #pragma unroll
-      for (int ct = 0; ct < NCT; ++ct)
-        bits |= (nsel[i] != 0u && key[ct][i] >= tau[i]) ? (1u << ct) : 0u;
-      selbits[i] = bits;
+      for (int i = 0; i < 4; ++i) bits |= (nsel != 0u && key[ct][i] >= tau) ? (1u << i) : 0u;
+      nib[ct] = bits;
+    }
+  } else {
+    uint32_t cgt = 0;
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) cgt += (key[ct][i] > tau) ? 1u : 0u;
+    cgt = rows_sum_u(cgt);
+    int32_t need_eq = static_cast<int32_t>(nsel) - static_cast<int32_t>(cgt);  // ties still to take, in column order
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+      uint32_t eqm = 0, gtm = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        eqm |= (key[ct][i] == tau && nsel != 0u) ? (1u << i) : 0u;
+        gtm |= (key[ct][i] > tau && nsel != 0u) ? (1u << i) : 0u;
+      }
+      // columns ascend with (ct, lg, i): ties of lower lane rows of this tile come first
+      uint32_t below;
+      const uint32_t total = rows_sum_prefix_u(static_cast<uint32_t>(__popc(eqm)), lg, &below);
+      uint32_t bits = gtm;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int32_t rank = static_cast<int32_t>(below) + __popc(eqm & ((1u << i) - 1u));
+        if (((eqm >> i) & 1u) && rank < need_eq) bits |= 1u << i;
+      }
+      nib[ct] = bits;
+      need_eq -= min(need_eq, static_cast<int32_t>(total));
+    }
+  }
+  // mask words: word j holds columns 32 j .. 32 j + 31 = tiles 2 j (low half) and 2 j + 1; this lane's
+  // four columns of a tile sit at bits 4 lg .. 4 lg + 3 of the tile's half.  The four lanes of a row
+  // combine their parts; the lane of the first row stores them as vectors.
+  const int32_t kw = (s.K + 31) >> 5;
+  constexpr int kWords = NCT / 2;
+  uint32_t words[kWords];
+#pragma unroll
+  for (int j = 0; j < kWords; ++j)
+    words[j] = rows_or_u((nib[2 * j] << (4 * lg)) | (nib[2 * j + 1] << (16 + 4 * lg)));
+  if (trow >= s.T || lg != 0) return;
+  uint32_t* mrow = mbits + (head * s.T + trow) * kw;
+  if (kw == kWords) {
+    if constexpr (kWords == 2) {
+      *reinterpret_cast<uint2*>(mrow) = make_uint2(words[0], words[1]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < kWords; j += 4)
+        *reinterpret_cast<uint4*>(mrow + j) = make_uint4(words[j], words[j + 1], words[j + 2], words[j + 3]);
     }
   } else {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      uint32_t cgt = 0;
-#pragma unroll
-      for (int ct = 0; ct < NCT; ++ct) cgt += (key[ct][i] > tau[i]) ? 1u : 0u;
-      cgt = group_sum_u<16>(cgt);
-      int32_t need_eq = static_cast<int32_t>(nsel[i]) - static_cast<int32_t>(cgt);
-      uint32_t bits = 0;
-#pragma unroll
-      for (int ct = 0; ct < NCT; ++ct) {
-        const uint32_t ky = key[ct][i];
-        const bool eq = (ky == tau[i]) && (nsel[i] != 0u);
-        const uint64_t eqm = __ballot(eq);
-        const uint32_t field = static_cast<uint32_t>(eqm >> (16 * lg)) & 0xffffu;  // this row's lanes
-        const int32_t below = __popc(field & ((1u << lr) - 1u));
-        const bool take = (nsel[i] != 0u) && ((ky > tau[i]) || (eq && below < need_eq));
-        bits |= take ? (1u << ct) : 0u;
-        need_eq -= min(need_eq, static_cast<int32_t>(__popc(field)));
-      }
-      selbits[i] = bits;
-    }
-  }
-  // mask words: word j holds columns 32 j .. 32 j + 31 = tiles 2 j (low half) and 2 j + 1.  Every
-  // lane of a row's group assembles the row's words; its first lane stores them as one vector.
-  const int32_t kw = (s.K + 31) >> 5;
-  constexpr int kWords = NCT / 2;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    uint32_t words[kWords];
-#pragma unroll
-    for (int j = 0; j < kWords; ++j) {
-      const uint64_t b0 = __ballot((selbits[i] >> (2 * j)) & 1u);
-      const uint64_t b1 = __ballot((selbits[i] >> (2 * j + 1)) & 1u);
-      words[j] = (static_cast<uint32_t>(b0 >> (16 * lg)) & 0xffffu) |
-                 ((static_cast<uint32_t>(b1 >> (16 * lg)) & 0xffffu) << 16);
-    }
-    if (trow[i] >= s.T || lr != 0) continue;
-    uint32_t* mrow = mbits + (head * s.T + trow[i]) * kw;
-    if (kw == kWords) {
-      if constexpr (kWords == 2) {
-        *reinterpret_cast<uint2*>(mrow) = make_uint2(words[0], words[1]);
-      } else {
-#pragma unroll
-        for (int j = 0; j < kWords; j += 4)
-          *reinterpret_cast<uint4*>(mrow + j) = make_uint4(words[j], words[j + 1], words[j + 2], words[j + 3]);
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < kWords; ++j)
-        if (j < kw) mrow[j] = words[j];
-    }
+    for (int j = 0; j < kWords; ++j)
+      if (j < kw) mrow[j] = words[j];
   }
 }
 

@@ -301,6 +301,44 @@ def test_causal_per_batch_grouping(sea, wl):
     print(f"    steps differing at near-ties: {(~same).sum()} / {same.size}", flush=True)
 
 
+@pytest.mark.parametrize("case", [(1, 2, 512, 64, 64, 9, 0, True), (2, 2, 512, 128, 32, 5, 0, False),
+                                  (1, 2, 1024, 256, 256, 64, 0, True), (1, 2, 2048, 64, 16, 3, 32, True),
+                                  (1, 2, 300, 96, 20, 7, 0, True)])
+def test_exact_ties_take_the_lowest_columns(sea, case):
+    """Q = K = 0: every feature is 1, so all whole columns of a row score exactly the same (closed
+    form: keys in the column / admissible keys) and the k^ selected ones must be the lowest columns
+    (a causal row's partly filled own column scores less).  Exercises the tie rule of the in-register
+    selection, where the tied columns sit in different lanes and registers."""
+    B, H, T, m, K, kh, kb, causal = case
+    wl = _wl("ties", B, H, T, m, K, kh, k_budget=kb, causal=causal, pad_frac=0.0 if causal else 0.3)
+    x = synth.make_inputs(wl)
+    x["Q"] = torch.zeros_like(x["Q"])
+    x["K"] = torch.zeros_like(x["K"])
+    p, xd, g = _gpu_forward(sea, wl, x)
+    po, o = _oracle_forward(wl, x)
+    sl = None if x["seq_len"] is None else x["seq_len"].numpy()
+    A_g = g["A_hat"].numpy().astype(np.float64)
+    assert_close(A_g, o["A_hat"], TOL["bf16"], "A_hat")
+    sel_s, idx_s, cnt_s = oracle.topk_mask(po, A_g, seq_len=sl)
+    assert np.array_equal(_unpack_mhat(g["mhat"].numpy(), wl.K), _sel_to_mask(sel_s, wl.K))
+    assert np.array_equal(g["sel"].numpy(), sel_s) and np.array_equal(g["idx"].numpy(), idx_s)
+    # the closed form itself: with T % K == 0 every full column ties exactly, the lowest k^ win
+    if T % K == 0:
+        w = T // K
+        for b in range(B):
+            ln = T if sl is None else int(sl[b])
+            for t in (0, w - 1, w, 5 * w + 3, ln - 1):
+                if t >= ln:
+                    continue
+                jmax = min(t, ln - 1) if causal else ln - 1
+                nfull, part = divmod(jmax + 1, w)
+                want = list(range(min(kh, nfull)))
+                if len(want) < kh and part > 0:
+                    want.append(nfull)
+                got = g["sel"][b, 0, t].numpy()
+                assert got[got >= 0].tolist() == want, (b, t, got, want)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("causal", [False, True])
 def test_full_selection_reduces_to_dense_attention(sea, dtype, causal):
