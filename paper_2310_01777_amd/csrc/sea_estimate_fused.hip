@@ -191,6 +191,11 @@ __device__ __forceinline__ float xor32_sum(float x) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
+// x + the value of the lane 16 further (or back) in the same half of the wave
+__device__ __forceinline__ float xor16_sum(float x) {
+  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
 
 template <int MC, int WLOG>
 __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
@@ -259,18 +264,21 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
           sh[static_cast<int64_t>((r0 + 4 * lg + i) >> 1) * m + slot] = f32_to_bf16(v[i] + v[i + 1]);
     } else {
       float sum = (v[0] + v[1]) + (v[2] + v[3]);  // the four keys share a column
-      if (w >= 8) sum += __shfl_xor(sum, 16, kWave);
+      if (w >= 8) sum = xor16_sum(sum);
       if (w >= 16) sum = xor32_sum(sum);
       const bool writer = w == 4 ? true : (w == 8 ? (lg & 1) == 0 : lg == 0);
       const int pw = w == 4 ? lg : (w == 8 ? lg >> 1 : 0);
       if (writer) part[(wid * kPartsWave + pw) * m + slot] = sum;
       if (w > 16 && pref) {
-        // the same tile sum over the rounded features: what a causal row's own-column term uses
-        float rs = (bf16_to_f32(f32_to_bf16(v[0])) + bf16_to_f32(f32_to_bf16(v[1]))) +
-                   (bf16_to_f32(f32_to_bf16(v[2])) + bf16_to_f32(f32_to_bf16(v[3])));
-        rs += __shfl_xor(rs, 16, kWave);
-        rs = xor32_sum(rs);
-        if (lg == 0) tpart[wid * m + slot] = rs;
+        // The same tile sum over the ROUNDED features (what a causal row's own-column term uses), on
+        // the matrix pipe: the four keys of this lane, rounded, are contraction slots 0..3 of an
+        // operand whose column is the feature; against an all-ones operand every result row is the
+        // sum over the wave's 16 keys, accumulated in fp32.
+        uint4 u = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), 0u, 0u};
+        const uint4 one = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+        const floatx4 rs = mfma16(__builtin_bit_cast(bf16x8, one), __builtin_bit_cast(bf16x8, u),
+                                  floatx4{0.f, 0.f, 0.f, 0.f});
+        if (lg == 0) tpart[wid * m + slot] = rs[0];
       }
     }
   }
