@@ -7,8 +7,11 @@
 //
 // This is the reference-precision mode: every dot product and the exponential are fp64 so
 // that the per-row top-k^ taken on A_hat agrees with an fp64 evaluation except where two
-// scores differ by less than ~1e-7 relative.  MI355X runs fp64 FMAs at half the fp32 vector
-// rate, and this mode is used for the small fp32 configuration only.
+// scores differ by less than ~1e-7 relative.  The projections and the contraction run on the
+// matrix cores (v_mfma_f64_16x16x4_f64: lane l supplies A[row l % 16][k l / 16] and
+// B[k l / 16][col l % 16], and receives D[row 4 i + l / 16][col l % 16] in register i); the
+// contraction index is free to permute as long as both operands agree, which lets every lane read
+// its sixteen operand values as contiguous floats.
 //
 // Workspace layout (doubles): phiQ [N][T][m], phiK/prefix [N][T][m], stateT [N][m][K].
 #include "sea_internal.h"
@@ -16,50 +19,108 @@
 namespace sea {
 namespace {
 
-constexpr int kRowsPerBlock = 4;  // one wave per row
+typedef double doublex4 __attribute__((ext_vector_type(4)));
 
-// phi for one row per wave.  which = 0: queries (row-max shifted, any shift cancels in the
-// normaliser), 1: keys (no shift; zero beyond seq_len).
-__global__ __launch_bounds__(kRowsPerBlock* kWave) void features_f64_kernel(
-    Shape s, const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ W,
-    double* __restrict__ phiQ, double* __restrict__ phiK) {
-  __shared__ double xs[kRowsPerBlock][kHeadDim];
+__device__ __forceinline__ doublex4 mfma_f64(double a, double b, doublex4 c) {
+  return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+
+// exp(x) in fp64: x = k ln 2 + r, |r| <= 0.35, Taylor series to r^13 (error < 1e-17 relative)
+__device__ __forceinline__ double exp_f64(double x) {
+  const double k = rint(x * 1.4426950408889634074);
+  double r = fma(-k, 6.93147180369123816490e-01, x);
+  r = fma(-k, 1.90821492927058770002e-10, r);
+  double p = 1.0 / 6227020800.0;
+  p = fma(p, r, 1.0 / 479001600.0);
+  p = fma(p, r, 1.0 / 39916800.0);
+  p = fma(p, r, 1.0 / 3628800.0);
+  p = fma(p, r, 1.0 / 362880.0);
+  p = fma(p, r, 1.0 / 40320.0);
+  p = fma(p, r, 1.0 / 5040.0);
+  p = fma(p, r, 1.0 / 720.0);
+  p = fma(p, r, 1.0 / 120.0);
+  p = fma(p, r, 1.0 / 24.0);
+  p = fma(p, r, 1.0 / 6.0);
+  p = fma(p, r, 0.5);
+  p = fma(p, r, 1.0);
+  p = fma(p, r, 1.0);
+  return ldexp(p, static_cast<int>(k));
+}
+
+// phi for 16 rows per wave.  which = 0: queries (row-max shifted, any shift cancels in the
+// normaliser), 1: keys (no shift; zero beyond seq_len).  D[row = token 4 i + lg][col = feature lr];
+// contraction slot (step s, lane group lg) stands for dimension 16 lg + s.
+__global__ __launch_bounds__(256) void features_f64_kernel(Shape s, const float* __restrict__ Q,
+                                                           const float* __restrict__ K, const float* __restrict__ W,
+                                                           double* __restrict__ phiQ, double* __restrict__ phiK) {
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
-  const int64_t gr = static_cast<int64_t>(blockIdx.x) * kRowsPerBlock + wid;  // over 2 * nrows
-  if (gr >= 2 * nrows) return;
-  const int which = gr >= nrows;
-  const int64_t row = which ? gr - nrows : gr;
-  const float* X = which ? K : Q;
-  double* out = (which ? phiK : phiQ) + row * s.m;
-  const int32_t t = static_cast<int32_t>(row % s.T);
-  const int32_t b = static_cast<int32_t>((row / s.T) / s.H);
+  const int lr = lane & 15, lg = lane >> 4;
+  const uint32_t tiles = (s.T + 15) / 16;
+  const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + wid;   // over 2 N tiles
+  const int64_t nw = static_cast<int64_t>(s.N) * tiles;
+  if (wave >= 2 * nw) return;
+  const int which = wave >= nw;
+  const int64_t wv = which ? wave - nw : wave;
+  const int64_t head = wv / tiles;
+  const int32_t r0 = static_cast<int32_t>(wv % tiles) * 16;
+  const int32_t b = static_cast<int32_t>(head / s.H);
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
-  if (t >= len) {
-    for (int i = lane; i < s.m; i += kWave) out[i] = 0.0;
-    return;
-  }
+  const float* X = (which ? K : Q) + (head * s.T + min(r0 + lr, s.T - 1)) * kHeadDim + 16 * lg;
   const double rs = sqrt(static_cast<double>(s.scale));
-  const double xv = rs * static_cast<double>(X[row * kHeadDim + lane]);
-  xs[wid][lane] = xv;
-  double nx = xv * xv;
+  double xa[16];
+  double nx = 0.0;
 #pragma unroll
-  for (int mask = 1; mask < kWave; mask <<= 1) nx += __shfl_xor(nx, mask, kWave);
-  __builtin_amdgcn_wave_barrier();
-  double amax = -INFINITY;
-  for (int i = lane; i < s.m; i += kWave) {
-    const float* w = W + static_cast<int64_t>(i) * kHeadDim;
-    double dot = 0.0;
-#pragma unroll 8
-    for (int e = 0; e < kHeadDim; ++e) dot = fma(static_cast<double>(w[e]), xs[wid][e], dot);
-    const double a = dot - 0.5 * nx;
-    out[i] = a;  // exponent argument for now
-    amax = fmax(amax, a);
+  for (int q = 0; q < 4; ++q) {
+    const float4 v = *reinterpret_cast<const float4*>(X + 4 * q);
+    xa[4 * q] = rs * v.x; xa[4 * q + 1] = rs * v.y; xa[4 * q + 2] = rs * v.z; xa[4 * q + 3] = rs * v.w;
   }
 #pragma unroll
-  for (int mask = 1; mask < kWave; mask <<= 1) amax = fmax(amax, __shfl_xor(amax, mask, kWave));
-  const double shift = which ? 0.0 : amax;
-  for (int i = lane; i < s.m; i += kWave) out[i] = exp(out[i] - shift);
+  for (int e = 0; e < 16; ++e) nx = fma(xa[e], xa[e], nx);
+  nx += __shfl_xor(nx, 16, kWave);
+  nx += __shfl_xor(nx, 32, kWave);  // |x|^2 of token r0 + lr, in every lane group
+  // this lane's four result rows are tokens r0 + 4 i + lg
+  double half_n[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) half_n[i] = 0.5 * __shfl(nx, 4 * i + lg, kWave);
+  double* out = (which ? phiK : phiQ) + (head * s.T) * s.m;
+  double amax[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+  for (int ft = 0; ft < s.m / 16; ++ft) {
+    const float* w = W + static_cast<int64_t>(ft * 16 + lr) * kHeadDim + 16 * lg;
+    doublex4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 v = *reinterpret_cast<const float4*>(w + 4 * q);
+      acc = mfma_f64(xa[4 * q], static_cast<double>(v.x), acc);
+      acc = mfma_f64(xa[4 * q + 1], static_cast<double>(v.y), acc);
+      acc = mfma_f64(xa[4 * q + 2], static_cast<double>(v.z), acc);
+      acc = mfma_f64(xa[4 * q + 3], static_cast<double>(v.w), acc);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int32_t t = r0 + 4 * i + lg;
+      const double a = acc[i] - half_n[i];
+      amax[i] = fmax(amax[i], a);
+      if (t < s.T) out[static_cast<int64_t>(t) * s.m + ft * 16 + lr] = a;  // exponent argument for now
+    }
+  }
+  double shift[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    double mx = amax[i];
+#pragma unroll
+    for (int mask = 1; mask < 16; mask <<= 1) mx = fmax(mx, __shfl_xor(mx, mask, kWave));
+    shift[i] = which ? 0.0 : mx;
+  }
+  // second pass over the lane's own values
+  for (int ft = 0; ft < s.m / 16; ++ft) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int32_t t = r0 + 4 * i + lg;
+      if (t >= s.T) continue;
+      double* o = out + static_cast<int64_t>(t) * s.m + ft * 16 + lr;
+      *o = t < len ? exp_f64(*o - shift[i]) : 0.0;
+    }
+  }
 }
 
 // One thread per (head, column c, feature i): walk the keys of the column, turning phiK into
@@ -82,68 +143,131 @@ __global__ __launch_bounds__(256) void state_f64_kernel(Shape s, double* __restr
   stateT[(head * s.m + i) * s.K + c] = acc;
 }
 
-// A_hat rows: 8 rows per block, 32 threads per row, thread owns columns lane32 + 32 q.
-template <int CPT>  // columns per thread = ceil(K / 32)
+// A_hat rows: one wave per 16 rows.  Tile (16 tokens x 16 columns) = phiQ x state over the m features
+// (contraction slot (step s, lane group lg) = feature 4 s + lg); a causal row's own column is the
+// diagonal of phiQ x prefix^T.  Column tiles are taken in groups of NCT that stay in registers; with
+// one group (K <= 16 NCT) a single pass normalises and stores, with more the groups are computed
+// twice: once for the row sums, once for the normalised output.
+template <int NCT>
 __global__ __launch_bounds__(256) void contract_f64_kernel(Shape s, const double* __restrict__ phiQ,
                                                            const double* __restrict__ pref,
                                                            const double* __restrict__ stateT,
                                                            float* __restrict__ A_hat) {
-  extern __shared__ double fq[];  // [8][m]
-  const int r = threadIdx.x >> 5, l32 = threadIdx.x & 31;
-  const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
-  const int64_t row0 = static_cast<int64_t>(blockIdx.x) * 8;
-  for (int x = threadIdx.x; x < 8 * s.m; x += 256) {
-    const int64_t rr = row0 + x / s.m;
-    fq[x] = rr < nrows ? phiQ[rr * s.m + (x % s.m)] : 0.0;
-  }
-  __syncthreads();
-  const int64_t row = row0 + r;
-  if (row >= nrows) return;  // no barrier below
-  const int64_t head = row / s.T;
-  const int32_t t = static_cast<int32_t>(row % s.T);
+  const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int lr = lane & 15, lg = lane >> 4;
+  const uint32_t tiles = (s.T + 15) / 16;
+  const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + wid;
+  if (wave >= static_cast<int64_t>(s.N) * tiles) return;
+  const int64_t head = wave / tiles;
+  const int32_t r0 = static_cast<int32_t>(wave % tiles) * 16;
   const int32_t b = static_cast<int32_t>(head / s.H);
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
-  float* out = A_hat + row * s.K;
-  if (t >= len) {
-    for (int c = l32; c < s.K; c += 32) out[c] = 0.f;
-    return;
-  }
-  const int32_t ct = bucket_of(t, s.T, s.K);
-  const int32_t cfull = s.causal ? ct : s.K;  // columns [0, cfull) use the full bucket sum
-  const double* st = stateT + head * s.m * s.K;
-  const double* q = fq + r * s.m;
-  double acc[CPT];
+  const double* qrow = phiQ + (head * s.T + min(r0 + lr, s.T - 1)) * s.m + lg;   // A operand: token lr
+  const double* prow = pref + (head * s.T + min(r0 + lr, s.T - 1)) * s.m + lg;   // B operand: token lr as column
+  const double* st = stateT + head * static_cast<int64_t>(s.m) * s.K;
+  // columns this wave needs: causal rows stop at the last row's own column
+  const int32_t t_hi = min(r0 + 15, s.T - 1);
+  const int32_t ncols = s.causal ? min(s.K, bucket_of(t_hi, s.T, s.K) + 1) : s.K;
+  const int32_t ngroups = (ncols + 16 * NCT - 1) / (16 * NCT);
+
+  // this lane's rows: tokens r0 + 4 i + lg
+  double diag[4] = {0.0, 0.0, 0.0, 0.0}, rsum[4] = {0.0, 0.0, 0.0, 0.0}, inv[4];
+  int32_t tcol[4];
+  bool act[4];
 #pragma unroll
-  for (int k = 0; k < CPT; ++k) acc[k] = 0.0;
-  for (int i = 0; i < s.m; ++i) {
-    const double qi = q[i];
-#pragma unroll
-    for (int k = 0; k < CPT; ++k) {
-      const int c = l32 + 32 * k;
-      if (c < cfull) acc[k] = fma(qi, st[static_cast<int64_t>(i) * s.K + c], acc[k]);
-    }
+  for (int i = 0; i < 4; ++i) {
+    const int32_t t = r0 + 4 * i + lg;
+    act[i] = t < len;
+    tcol[i] = act[i] ? bucket_of(t, s.T, s.K) : -1;
   }
   if (s.causal) {
-    // diagonal column: phi(q_t) . prefix_t, computed by the 32 threads of the row together
-    const double* pf = pref + row * s.m;
-    double dsum = 0.0;
-    for (int i = l32; i < s.m; i += 32) dsum = fma(q[i], pf[i], dsum);
+    doublex4 dg = {0.0, 0.0, 0.0, 0.0};
+    for (int32_t f = 0; f < s.m; f += 4) dg = mfma_f64(qrow[f], prow[f], dg);
+    // the diagonal entry of token u sits in lane (lr = u, lg = u % 4), register u / 4
 #pragma unroll
-    for (int mask = 1; mask < 32; mask <<= 1) dsum += __shfl_xor(dsum, mask, kWave);
-#pragma unroll
-    for (int k = 0; k < CPT; ++k)
-      if (l32 + 32 * k == ct) acc[k] = dsum;
+    for (int i = 0; i < 4; ++i) diag[i] = __shfl(dg[i], 16 * lg + 4 * i + lg, kWave);
   }
-  double rsum = 0.0;
+  doublex4 acc[NCT];
+  auto group = [&](int32_t g) {
+    const int32_t c0 = 16 * NCT * g;
 #pragma unroll
-  for (int k = 0; k < CPT; ++k) rsum += acc[k];
+    for (int ct = 0; ct < NCT; ++ct) acc[ct] = doublex4{0.0, 0.0, 0.0, 0.0};
+    for (int32_t f = 0; f < s.m; f += 4) {
+      const double a = qrow[f];
 #pragma unroll
-  for (int mask = 1; mask < 32; mask <<= 1) rsum += __shfl_xor(rsum, mask, kWave);
-  const double inv = rsum > 0.0 ? 1.0 / rsum : 0.0;
+      for (int ct = 0; ct < NCT; ++ct) {
+        if (c0 + 16 * ct < ncols) {
+          const int32_t c = min(c0 + 16 * ct + lr, s.K - 1);
+          acc[ct] = mfma_f64(a, st[static_cast<int64_t>(f + lg) * s.K + c], acc[ct]);
+        }
+      }
+    }
 #pragma unroll
-  for (int k = 0; k < CPT; ++k) {
-    const int c = l32 + 32 * k;
-    if (c < s.K) out[c] = static_cast<float>(acc[k] * inv);
+    for (int ct = 0; ct < NCT; ++ct) {
+      const int32_t c = c0 + 16 * ct + lr;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        double v = acc[ct][i];
+        if (s.causal) {
+          if (c == tcol[i]) v = diag[i];
+          if (c > tcol[i]) v = 0.0;
+        }
+        if (!act[i] || c >= s.K || c0 + 16 * ct >= ncols) v = 0.0;
+        acc[ct][i] = v;
+      }
+    }
+  };
+  auto add_sums = [&]() {
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) rsum[i] += acc[ct][i];
+  };
+  auto store = [&](int32_t g) {
+    const int32_t c0 = 16 * NCT * g;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int32_t t = r0 + 4 * i + lg;
+      if (t >= s.T) continue;
+      float* out = A_hat + (head * s.T + t) * s.K;
+#pragma unroll
+      for (int ct = 0; ct < NCT; ++ct) {
+        const int32_t c = c0 + 16 * ct + lr;
+        if (c < s.K) out[c] = static_cast<float>(acc[ct][i] * inv[i]);
+      }
+    }
+  };
+  auto finish_sums = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      double r = rsum[i];
+#pragma unroll
+      for (int mask = 1; mask < 16; mask <<= 1) r += __shfl_xor(r, mask, kWave);
+      inv[i] = r > 0.0 ? 1.0 / r : 0.0;
+    }
+  };
+  const int32_t all_groups = (s.K + 16 * NCT - 1) / (16 * NCT);  // groups past ncols hold zeros only
+  if (ngroups <= 1) {
+    group(0);
+    add_sums();
+    finish_sums();
+    store(0);
+  } else {
+    for (int32_t g = 0; g < ngroups; ++g) {
+      group(g);
+      add_sums();
+    }
+    finish_sums();
+    for (int32_t g = 0; g < ngroups; ++g) {
+      group(g);
+      store(g);
+    }
+  }
+  // columns past the wave's last one: zeros
+  for (int32_t g = max(ngroups, 1); g < all_groups; ++g) {
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) acc[ct] = doublex4{0.0, 0.0, 0.0, 0.0};
+    store(g);
   }
 }
 
@@ -161,12 +285,11 @@ hipError_t launch_estimate_f64(const Shape& s, const float* Q, const float* K, c
   double* phiQ = static_cast<double*>(ws);
   double* phiK = phiQ + ntm;
   double* stateT = phiK + ntm;
-  const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
   {
     StageScope scope(SEA_STAGE_FEATURES, st);
-    const uint32_t grid = static_cast<uint32_t>((2 * nrows + kRowsPerBlock - 1) / kRowsPerBlock);
-    hipLaunchKernelGGL(features_f64_kernel, dim3(grid), dim3(kRowsPerBlock * kWave), 0, st, s, Q, K,
-                       W, phiQ, phiK);
+    const int64_t waves = 2 * static_cast<int64_t>(s.N) * ((s.T + 15) / 16);
+    hipLaunchKernelGGL(features_f64_kernel, dim3(static_cast<uint32_t>((waves + 3) / 4)), dim3(256), 0, st, s, Q, K, W,
+                       phiQ, phiK);
   }
   {
     StageScope scope(SEA_STAGE_STATE, st);
@@ -176,18 +299,14 @@ hipError_t launch_estimate_f64(const Shape& s, const float* Q, const float* K, c
   }
   {
     StageScope scope(SEA_STAGE_CONTRACT, st);
-    const uint32_t grid = static_cast<uint32_t>((nrows + 7) / 8);
-    const size_t shm = 8 * static_cast<size_t>(s.m) * sizeof(double);
-    const int cpt = (s.K + 31) / 32;
-#define SEA_LAUNCH_CONTRACT(C)                                                                   \
-  hipLaunchKernelGGL(contract_f64_kernel<C>, dim3(grid), dim3(256), shm, st, s, phiQ, phiK, stateT, \
-                     A_hat)
-    if (cpt <= 1) SEA_LAUNCH_CONTRACT(1);
-    else if (cpt <= 2) SEA_LAUNCH_CONTRACT(2);
-    else if (cpt <= 4) SEA_LAUNCH_CONTRACT(4);
-    else if (cpt <= 8) SEA_LAUNCH_CONTRACT(8);
-    else if (cpt <= 16) SEA_LAUNCH_CONTRACT(16);
-    else SEA_LAUNCH_CONTRACT(32);
+    const int64_t waves = static_cast<int64_t>(s.N) * ((s.T + 15) / 16);
+    const dim3 grid(static_cast<uint32_t>((waves + 3) / 4));
+    const int nct = (s.K + 15) / 16;
+#define SEA_LAUNCH_CONTRACT(C) hipLaunchKernelGGL(contract_f64_kernel<C>, grid, dim3(256), 0, st, s, phiQ, phiK, stateT, A_hat)
+    if (nct <= 2) SEA_LAUNCH_CONTRACT(2);
+    else if (nct <= 4) SEA_LAUNCH_CONTRACT(4);
+    else if (nct <= 8) SEA_LAUNCH_CONTRACT(8);
+    else SEA_LAUNCH_CONTRACT(16);
 #undef SEA_LAUNCH_CONTRACT
   }
   return hipGetLastError();
