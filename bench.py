@@ -29,8 +29,9 @@ SWEEP = ("c1", "c2", "c3", "c4_T4096", "c4_T8192", "c4_T16384", "c5")
 # HBM bytes per launch (fetched, written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script, scaled by the copy-kernel factors; they cannot be read inside this process, so they are
 # quoted from the committed summary and only for the workload and kernel that summary covers.
-TRAFFIC_FROM_PROFILES = {}
-TRAFFIC_SOURCE = "profiles/pmc_traffic_c4_T32768.md"
+TRAFFIC_FROM_PROFILES = {("c4_T32768", "sparse"): (190.2e6, 134.2e6), ("c4_T32768", "contract"): (361.7e6, 33.6e6),
+                         ("c4_T32768", "state"): (134.6e6, 92.3e6)}
+TRAFFIC_SOURCE = "profiles/sea_forward_c4_T32768.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not measured in this run)"
 
 
 def parse():
