@@ -110,7 +110,7 @@ constexpr int kVRow = 64;    // halfwords per staged V row: no padding; the 64-b
 // grouped by that column, and a block takes 128 rows of one bucket against the r keys of its
 // column, so every visited tile is fully used no matter how scattered the choices are.
 template <int RLOG, int MODE>
-__global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
+__global__ __launch_bounds__(256, 4) void tile_attn_kernel(TileArgs a) {
   constexpr bool DENSE = MODE != 0;   // no per-column bits to look up
   constexpr bool BUCKET = MODE == 2;
   __shared__ __attribute__((aligned(16))) uint16_t Ks[2][kChunk * kKRow];
@@ -242,7 +242,13 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
   floatx16 oacc[2];
 #pragma unroll
   for (int i = 0; i < 16; ++i) { oacc[0][i] = 0.f; oacc[1][i] = 0.f; }
-  float m_run = -INFINITY, l_run = 0.f;
+  // Streaming softmax in the exponent's own units: a score enters as y = s c - m_ref (log2 units,
+  // one fused multiply-add with the group's offset, -inf for a masked group), so the row maximum
+  // is the plain maximum of y and no score is touched twice.
+  // m_thr = how far a row's maximum may exceed its reference: -inf until the row has one.  Both
+  // halves of a row (lanes l, l + 32) always hold the same m_ref and m_thr.
+  float m_ref = 0.f, m_thr = -INFINITY, l_run = 0.f;
+  constexpr float kRefSlack = 8.f;
 
   if (nsteps > 0) {
     SEA_FETCH(0);
@@ -256,8 +262,8 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
     for (int sc = 0; sc < 2; ++sc) {
       const int32_t u0 = ubase + step * kChunk + 32 * sc;
       if (u0 >= u_end) break;  // wave-uniform: beyond what this wave's rows can see
-      uint32_t bits = 0xffffffffu;
       if (BUCKET && __ballot(row_active) == 0ull) break;  // a wave past the end of its bucket
+      uint32_t bits = 0xffffffffu;
       if (!DENSE) {
         const int32_t col0 = u0 >> (RLOG < 5 ? RLOG : a.rlog);  // first column of the sub-chunk
         const uint32_t word = row_active ? mrow[col0 >> 5] : 0u;
@@ -268,99 +274,86 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
       }
       // S^T sub-chunk = K (32 keys x 64) . Q_tile^T
       const uint16_t* Kr = &Ks[stage][(32 * sc + ql) * kKRow + 8 * g];
-      floatx16 s;
+      floatx16 sv;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s[i] = 0.f;
+      for (int i = 0; i < 16; ++i) sv[i] = 0.f;
 #pragma unroll
       for (int kc = 0; kc < 4; ++kc)
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(Kr + 16 * kc), bq[kc],
-                                                    s, 0, 0, 0);
+        sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(*reinterpret_cast<const bf16x8*>(Kr + 16 * kc), bq[kc],
+                                                     sv, 0, 0, 0);
       // admissibility of each (key, query) entry: reg i <-> key slot 8(i/4) + 4g + i%4.
       // Interior sub-chunks need only the column bits; the few that straddle the causal
       // diagonal or the end of the sequence also compare key positions.
       const bool boundary =
           (u0 + 32 > u_end) || (pos_of(min(u0 + 31, a.U - 1), a.rlog, a.w) > j_free);
       // Registers of one lane fall into groups that share a column (and so a mask bit): 4 for 4
-      // or 8 keys per column, 8 for 16, all 16 for 32 or more and for the dense kernel.  Interior
-      // sub-chunks then need one select per group on the group maximum and one on the exponent
-      // offset, instead of one per score.
+      // or 8 keys per column, 8 for 16, all 16 for 32 or more and for the dense kernel.  One
+      // bit-select per group picks its offset (-m_ref or -inf).
       constexpr int kGroup = DENSE ? 16 : (RLOG >= 5 ? 16 : (RLOG == 4 ? 8 : (RLOG >= 2 ? 4 : 1)));
       constexpr int kGroups = 16 / kGroup;
-      bool gok[kGroups];
-      float mx = -INFINITY;
+      float y[16];
       if (!boundary && kGroup > 1) {
+        const uint32_t ref_bits = __float_as_uint(-m_ref), inf_bits = 0xff800000u;
 #pragma unroll
         for (int gi = 0; gi < kGroups; ++gi) {
           const int col = DENSE ? 0 : (RLOG >= 5 ? 0 : (RLOG == 2 ? 2 * gi + g : gi));  // column of the group
-          gok[gi] = DENSE ? row_active : (((bits >> col) & 1u) != 0u);
-          float gm = s[kGroup * gi];
+          // all ones where the group's column is selected
+          const uint32_t sel = DENSE ? (row_active ? ~0u : 0u)
+                                     : static_cast<uint32_t>(static_cast<int32_t>(bits << (31 - col)) >> 31);
+          const float off = __uint_as_float((sel & ref_bits) | (~sel & inf_bits));
 #pragma unroll
-          for (int e = 1; e < kGroup; ++e) gm = fmaxf(gm, s[kGroup * gi + e]);
-          mx = fmaxf(mx, gok[gi] ? gm : -INFINITY);
-        }
-      } else if (!boundary) {
-#pragma unroll
-        for (int gi = 0; gi < kGroups; ++gi) gok[gi] = true;  // masked through the scores below
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int32_t slot = 8 * (i >> 2) + 4 * g + (i & 3);
-          const bool ok = ((bits >> (slot >> RLOG)) & 1u) != 0u;
-          s[i] = ok ? s[i] : -INFINITY;
-          mx = fmaxf(mx, s[i]);
+          for (int e = 0; e < kGroup; ++e) y[kGroup * gi + e] = fmaf(sv[kGroup * gi + e], a.c, off);
         }
       } else {
 #pragma unroll
-        for (int gi = 0; gi < kGroups; ++gi) gok[gi] = true;
-#pragma unroll
         for (int i = 0; i < 16; ++i) {
           const int32_t slot = 8 * (i >> 2) + 4 * g + (i & 3);
-          const int32_t u = u0 + slot;
-          const int32_t pu = pos_of(min(u, a.U - 1), a.rlog, a.w);
-          const uint32_t okb = (DENSE ? (row_active ? 1u : 0u) : ((bits >> (RLOG >= 5 ? 0 : (slot >> RLOG))) & 1u)) &
-                               (u < ulim ? 1u : 0u) & (pu <= my_jmax ? 1u : 0u);
-          s[i] = okb ? s[i] : -INFINITY;
-          mx = fmaxf(mx, s[i]);
+          uint32_t okb = DENSE ? (row_active ? 1u : 0u) : ((bits >> (RLOG >= 5 ? 0 : (slot >> RLOG))) & 1u);
+          if (boundary) {
+            const int32_t u = u0 + slot;
+            const int32_t pu = pos_of(min(u, a.U - 1), a.rlog, a.w);
+            okb &= (u < ulim ? 1u : 0u) & (pu <= my_jmax ? 1u : 0u);
+          }
+          y[i] = okb ? fmaf(sv[i], a.c, -m_ref) : -INFINITY;
         }
       }
-      mx = half_max(mx);
-      // The reference maximum only has to keep the exponentials in range, so it is refreshed (and
-      // the accumulators rescaled) when some row's maximum has grown by more than 2^8 in the
-      // exponent; until then p may reach 256 instead of 1, which fp32 sums and bf16 P carry as well.
-      const bool refresh = (mx - m_run) * a.c > 8.f;
+      float ymax = fmaxf(fmaxf(y[0], y[1]), y[2]);
+#pragma unroll
+      for (int i = 3; i < 15; i += 2) ymax = fmaxf(fmaxf(ymax, y[i]), y[i + 1]);
+      ymax = half_max(fmaxf(ymax, y[15]));
+      // The reference only has to keep the exponentials in range, so it is moved (and the
+      // accumulators rescaled) when some row's maximum exceeds it by more than 8 in the exponent,
+      // or when the row has none yet; until then p may reach 256 instead of 1, which fp32 sums and
+      // bf16 P carry as well.
+      const bool refresh = ymax > m_thr;
       if (__ballot(refresh) != 0ull) {
         // rows that did not ask keep their reference (factor exactly 1): a row's arithmetic
         // never depends on the other rows of its wave
-        const float m_new = refresh ? mx : m_run;
-        const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-        const float corr = refresh ? __builtin_amdgcn_exp2f((m_run - m_safe) * a.c) : 1.f;
+        const float delta = refresh ? ymax : 0.f;
+        const float corr = (refresh && m_thr > 0.f) ? __builtin_amdgcn_exp2f(-delta) : 1.f;
         l_run *= corr;
 #pragma unroll
         for (int i = 0; i < 16; ++i) { oacc[0][i] *= corr; oacc[1][i] *= corr; }
-        m_run = m_new;
-      }
-      const float mc = ((m_run == -INFINITY) ? 0.f : m_run) * a.c;
-      float p[16];
+        m_ref += delta;
+        m_thr = refresh ? kRefSlack : m_thr;
 #pragma unroll
-      for (int gi = 0; gi < kGroups; ++gi) {
-        const float off = gok[gi] ? -mc : -INFINITY;  // a masked group's exponentials are exp2(-inf) = 0
-#pragma unroll
-        for (int e = 0; e < kGroup; ++e)
-          p[kGroup * gi + e] = __builtin_amdgcn_exp2f(fmaf(s[kGroup * gi + e], a.c, off));
+        for (int i = 0; i < 16; ++i) y[i] -= delta;
       }
-      // P to bf16; the row sum is taken over the rounded values, the ones the product uses
-      bf16x8 bp[2];
+      // P to bf16 (exp2(-inf) = 0 for masked entries); the row sum is taken over the rounded
+      // values, the ones the product uses
+      bf16x2 h[8];
       const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
 #pragma unroll
-      for (int c2 = 0; c2 < 2; ++c2) {
-        bf16x2 h[4];
+      for (int e = 0; e < 8; ++e) {
+        const floatx2 f2 = {__builtin_amdgcn_exp2f(y[2 * e]), __builtin_amdgcn_exp2f(y[2 * e + 1])};
+        h[e] = __builtin_convertvector(f2, bf16x2);
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(h[e], ones, l_run, false);
+      }
+      bf16x8 bp[2];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const floatx2 f2 = {p[8 * c2 + 2 * e], p[8 * c2 + 2 * e + 1]};
-          h[e] = __builtin_convertvector(f2, bf16x2);
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(h[e], ones, l_run, false);
-        }
-        const bf16x4 lo = __builtin_shufflevector(h[0], h[1], 0, 1, 2, 3);
-        const bf16x4 hi = __builtin_shufflevector(h[2], h[3], 0, 1, 2, 3);
+      for (int c2 = 0; c2 < 2; ++c2) {
+        const bf16x4 lo = __builtin_shufflevector(h[4 * c2], h[4 * c2 + 1], 0, 1, 2, 3);
+        const bf16x4 hi = __builtin_shufflevector(h[4 * c2 + 2], h[4 * c2 + 3], 0, 1, 2, 3);
         bp[c2] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       }
       // O^T += V^T P^T; V^T fragments in the key order of the P registers.  The LDS transpose
@@ -395,7 +388,7 @@ __global__ __launch_bounds__(256) void tile_attn_kernel(TileArgs a) {
       const int64_t e = (head * a.T + t) * a.slots + eslot;
       Or = a.part_o + e * kHeadDim;
       if (g == 0) {
-        a.part_ml[2 * e] = m_run;
+        a.part_ml[2 * e] = m_thr > 0.f ? m_ref : -INFINITY;
         a.part_ml[2 * e + 1] = row_active ? l_run : 0.f;
       }
     }
@@ -534,13 +527,13 @@ __global__ __launch_bounds__(kBucketRows) void bucket_scatter_kernel(const uint3
   }
 }
 
-// several columns per row: O[t] = sum_s w_s On_s / sum_s w_s with w_s = l_s 2^((m_s - M) c), over
-// the row's entries (On_s normalised partial outputs, m_s reference maxima, l_s sums)
+// several columns per row: O[t] = sum_s w_s On_s / sum_s w_s with w_s = l_s 2^(m_s - M), over the
+// row's entries (On_s normalised partial outputs, m_s references in log2 units, l_s sums)
 __global__ __launch_bounds__(256) void bucket_merge_kernel(const uint32_t* __restrict__ mbits,
                                                            const uint16_t* __restrict__ part_o,
                                                            const float* __restrict__ part_ml,
                                                            uint16_t* __restrict__ O, int64_t rows, int32_t KW,
-                                                           int32_t slots, float c) {
+                                                           int32_t slots) {
   const int64_t gid = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
   const int64_t row = gid >> 3;
   const int part = static_cast<int>(gid & 7);
@@ -565,7 +558,7 @@ __global__ __launch_bounds__(256) void bucket_merge_kernel(const uint32_t* __res
 #pragma unroll
   for (int q = 0; q < kMaxSlots; ++q) {
     if (!(ls[q] > 0.f)) continue;
-    const float wq = ls[q] * __builtin_amdgcn_exp2f((ms[q] - M) * c);
+    const float wq = ls[q] * __builtin_amdgcn_exp2f(ms[q] - M);
     const uint32_t wds[4] = {vs[q].x, vs[q].y, vs[q].z, vs[q].w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -692,7 +685,7 @@ hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K
     if (multi) {
       const int64_t rows = static_cast<int64_t>(s.N) * s.T;
       hipLaunchKernelGGL(bucket_merge_kernel, dim3(static_cast<uint32_t>((rows * 8 + 255) / 256)), dim3(256), 0, st,
-                         mbits, a.part_o, a.part_ml, O, rows, KW, s.k_hat, a.c);
+                         mbits, a.part_o, a.part_ml, O, rows, KW, s.k_hat);
     }
     return hipGetLastError();
   }
