@@ -176,8 +176,10 @@ __global__ __launch_bounds__(256) void dec_features_kernel(Shape s, int32_t Tp, 
 __device__ __forceinline__ uint16_t one_bf16() { return 0x3f80; }
 
 // eight values U[j][v] for consecutive or listed tokens j, as a bf16 fragment
+// [vi_lo, vi_hi): the tokens j with V_I[j][v] = 1, i.e. floor(j d / T) == v (empty for v >= 64)
 template <typename F>
-__device__ __forceinline__ bf16x8 value_frag(int32_t v, const uint16_t* VtRow, int32_t T, int32_t d, F&& token_of) {
+__device__ __forceinline__ bf16x8 value_frag(int32_t v, const uint16_t* VtRow, int32_t T, int32_t vi_lo, int32_t vi_hi,
+                                             F&& token_of) {
   if (v >= 64 && v < 128) {
     // V^T row v - 64: two 8-byte pieces (tokens token_of(0) .. + 3 and token_of(4) .. + 3)
     const uint2 a = *reinterpret_cast<const uint2*>(VtRow + token_of(0));
@@ -193,7 +195,7 @@ __device__ __forceinline__ bf16x8 value_frag(int32_t v, const uint16_t* VtRow, i
     for (int h = 0; h < 2; ++h) {
       const int32_t j = token_of(e + h);
       bool on = false;
-      if (v < 64) on = j < T && static_cast<int32_t>((static_cast<int64_t>(j) * d) / T) == v;  // V_I[j][v]
+      if (v < 64) on = j >= vi_lo && j < vi_hi;                                                 // V_I[j][v]
       else if (v == 128) on = j < T;                                                            // normaliser column
       pair |= on ? (static_cast<uint32_t>(one_bf16()) << (16 * h)) : 0u;
     }
@@ -203,22 +205,80 @@ __device__ __forceinline__ bf16x8 value_frag(int32_t v, const uint16_t* VtRow, i
   return __builtin_bit_cast(bf16x8, u);
 }
 
-template <int MC>
-__global__ __launch_bounds__(64) void dec_linattn_kernel(Shape s, int32_t Tp, const uint16_t* __restrict__ phiQ,
-                                                         const uint16_t* __restrict__ phiK,
-                                                         const uint16_t* __restrict__ phiKT,
-                                                         const uint16_t* __restrict__ Vt, float* __restrict__ acc_out) {
+// Block = nine waves, one per slice of 16 value columns, all working on the same head and the
+// same chunk: the chunk's phi(Q), phi(K) and phi(K)^T tiles are fetched once per block and parked
+// in LDS in operand-fragment order (fragment = the 16 bytes one lane feeds to one product), so the
+// features are read from memory once per head instead of once per slice.
+// The sequence is cut into G segments of `cps` chunks so that enough blocks are in flight: with
+// PHASE 0 a wave sums phi(K)^T U over its own segment and leaves the tile registers in `seg_state`
+// ([head][slice][segment][2 MC tiles][64 lanes] float4); with PHASE 1 it starts from the sum of the
+// segments before its own (causal) or of all segments (bidirectional) and emits its chunks.  G = 1:
+// PHASE 1 alone walks the whole sequence.
+constexpr int kLinWaves = 9;
+template <int MC, int PHASE>
+__global__ __launch_bounds__(64 * kLinWaves) void dec_linattn_kernel(Shape s, int32_t Tp, int32_t G, int32_t cps,
+                                                                     const uint16_t* __restrict__ phiQ,
+                                                                     const uint16_t* __restrict__ phiK,
+                                                                     const uint16_t* __restrict__ phiKT,
+                                                                     const uint16_t* __restrict__ Vt,
+                                                                     float* __restrict__ acc_out,
+                                                                     float4* __restrict__ seg_state) {
   constexpr int m = 32 * MC;
-  const int lane = threadIdx.x, lr = lane & 15, lg = lane >> 4;
-  const int64_t head = blockIdx.x / 9;
-  const int32_t v0 = static_cast<int32_t>(blockIdx.x % 9) * 16;
+  constexpr int kFrags = 2 * MC * 64;  // fragments per tile: Q and K [kc][half][lane], K^T [x][lane]
+  constexpr int kThreads = 64 * kLinWaves;
+  constexpr int kPer = (3 * kFrags + kThreads - 1) / kThreads;  // fragments a thread moves per chunk
+  __shared__ __attribute__((aligned(16))) uint4 tiles[3 * kFrags];
+  const int tid = threadIdx.x, lane = tid & 63, lr = lane & 15, lg = lane >> 4;
+  const int slice = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int32_t seg = static_cast<int32_t>(blockIdx.x % static_cast<uint32_t>(G));
+  const int64_t head = blockIdx.x / static_cast<uint32_t>(G);
+  const int64_t hs = head * 9 + slice;  // (head, slice)
+  const int32_t v0 = slice * 16;
   const int32_t vcol = v0 + lr;  // the value column this lane stands for as an operand row / column
+  // floor(j d / T) == v  <=>  ceil(v T / d) <= j < ceil((v + 1) T / d)
+  const int32_t vi_lo = vcol < 64 ? static_cast<int32_t>((static_cast<int64_t>(vcol) * s.T + kHeadDim - 1) / kHeadDim) : 0;
+  const int32_t vi_hi =
+      vcol < 64 ? min(s.T, static_cast<int32_t>((static_cast<int64_t>(vcol + 1) * s.T + kHeadDim - 1) / kHeadDim)) : 0;
   const uint16_t* VtRow = Vt + (head * kHeadDim + max(0, min(vcol - 64, 63))) * static_cast<int64_t>(Tp);
   const uint16_t* Qh = phiQ + head * static_cast<int64_t>(s.T) * m;
   const uint16_t* Kh = phiK + head * static_cast<int64_t>(s.T) * m;
   const uint16_t* KTh = phiKT + head * static_cast<int64_t>(m) * Tp;
   float* Oh = acc_out + head * static_cast<int64_t>(s.T) * kValCols;
   const int32_t nchunks = Tp / 32;
+
+  // the block's loader: fragment id -> its 16 bytes in memory.  `which` 0: phi(Q), 1: phi(K) (rows
+  // clamped to the last token; rows past it are masked or multiply zeros), 2: phi(K)^T.
+  uint4 held[kPer];
+  auto fetch = [&](int32_t t0, bool want_q, bool want_k, bool want_kt) {
+#pragma unroll
+    for (int r = 0; r < kPer; ++r) {
+      const int id = tid + r * kThreads;
+      if (id >= 3 * kFrags) break;
+      const int which = id / kFrags, fid = id % kFrags;
+      const int x = fid >> 6, fl = fid & 63, flr = fl & 15, flg = fl >> 4;
+      const uint16_t* src;
+      bool want;
+      if (which < 2) {
+        const int kc = x >> 1, half = x & 1;
+        const int32_t row = min(t0 + 16 * half + flr, s.T - 1);
+        src = (which ? Kh : Qh) + static_cast<int64_t>(row) * m + 32 * kc + 8 * flg;
+        want = which ? want_k : want_q;
+      } else {
+        const int f = 32 * (x >> 1) + 8 * (flr >> 2) + 4 * (x & 1) + (flr & 3);
+        src = KTh + static_cast<int64_t>(f) * Tp + t0 + 8 * flg;
+        want = want_kt;
+      }
+      if (want) held[r] = *reinterpret_cast<const uint4*>(src);
+    }
+  };
+  auto park = [&]() {
+#pragma unroll
+    for (int r = 0; r < kPer; ++r) {
+      const int id = tid + r * kThreads;
+      if (id < 3 * kFrags) tiles[id] = held[r];
+    }
+  };
+  auto frag = [&](int which, int x) { return __builtin_bit_cast(bf16x8, tiles[which * kFrags + x * 64 + lane]); };
 
   floatx4 S[2 * MC];
 #pragma unroll
@@ -227,12 +287,9 @@ __global__ __launch_bounds__(64) void dec_linattn_kernel(Shape s, int32_t Tp, co
   auto update = [&](int32_t t0) {
     // S[f][v] += sum_j phi(K)^T[f][j] U[j][v]: A rows = features (in the order of the tile rows),
     // B column = this lane's value column, contraction over the chunk's 32 tokens
-    const bf16x8 ub = value_frag(vcol, VtRow, s.T, kHeadDim, [&](int e) { return t0 + 8 * lg + e; });
+    const bf16x8 ub = value_frag(vcol, VtRow, s.T, vi_lo, vi_hi, [&](int e) { return t0 + 8 * lg + e; });
 #pragma unroll
-    for (int x = 0; x < 2 * MC; ++x) {
-      const int f = 32 * (x >> 1) + 8 * (lr >> 2) + 4 * (x & 1) + (lr & 3);
-      S[x] = mfma16(load8(KTh + static_cast<int64_t>(f) * Tp + t0 + 8 * lg), ub, S[x]);
-    }
+    for (int x = 0; x < 2 * MC; ++x) S[x] = mfma16(frag(2, x), ub, S[x]);
   };
   auto emit = [&](int32_t t0, bool causal) {
     floatx4 OT[2] = {floatx4{0.f, 0.f, 0.f, 0.f}, floatx4{0.f, 0.f, 0.f, 0.f}};
@@ -241,17 +298,14 @@ __global__ __launch_bounds__(64) void dec_linattn_kernel(Shape s, int32_t Tp, co
     for (int a = 0; a < 2; ++a)
 #pragma unroll
       for (int c = 0; c < 2; ++c) PT[a][c] = floatx4{0.f, 0.f, 0.f, 0.f};
-    const int32_t tq0 = min(t0 + lr, s.T - 1), tq1 = min(t0 + 16 + lr, s.T - 1);
 #pragma unroll
     for (int kc = 0; kc < MC; ++kc) {
-      const bf16x8 q0 = load8(Qh + static_cast<int64_t>(tq0) * m + 32 * kc + 8 * lg);
-      const bf16x8 q1 = load8(Qh + static_cast<int64_t>(tq1) * m + 32 * kc + 8 * lg);
+      const bf16x8 q0 = frag(0, 2 * kc), q1 = frag(0, 2 * kc + 1);
       const bf16x8 sf = pack8(S[2 * kc], S[2 * kc + 1]);  // rows = this slice's value columns
       OT[0] = mfma16(sf, q0, OT[0]);
       OT[1] = mfma16(sf, q1, OT[1]);
       if (causal) {
-        const bf16x8 k0 = load8(Kh + static_cast<int64_t>(tq0) * m + 32 * kc + 8 * lg);
-        const bf16x8 k1 = load8(Kh + static_cast<int64_t>(tq1) * m + 32 * kc + 8 * lg);
+        const bf16x8 k0 = frag(1, 2 * kc), k1 = frag(1, 2 * kc + 1);
         PT[0][0] = mfma16(k0, q0, PT[0][0]);
         PT[0][1] = mfma16(k0, q1, PT[0][1]);
         PT[1][0] = mfma16(k1, q0, PT[1][0]);
@@ -271,7 +325,7 @@ __global__ __launch_bounds__(64) void dec_linattn_kernel(Shape s, int32_t Tp, co
           }
       // contraction slots of the second product follow the register order of P^T: slot e < 4 is
       // key t0 + 4 lg + e, slot e >= 4 key t0 + 16 + 4 lg + e - 4
-      const bf16x8 ua = value_frag(vcol, VtRow, s.T, kHeadDim,
+      const bf16x8 ua = value_frag(vcol, VtRow, s.T, vi_lo, vi_hi,
                                    [&](int e) { return t0 + (e < 4 ? 4 * lg + e : 16 + 4 * lg + e - 4); });
       OT[0] = mfma16(ua, pack8(PT[0][0], PT[1][0]), OT[0]);
       OT[1] = mfma16(ua, pack8(PT[0][1], PT[1][1]), OT[1]);
@@ -285,16 +339,44 @@ __global__ __launch_bounds__(64) void dec_linattn_kernel(Shape s, int32_t Tp, co
             make_float4(OT[tt][0], OT[tt][1], OT[tt][2], OT[tt][3]);
     }
   };
-
-  if (s.causal) {
-    for (int32_t c = 0; c < nchunks; ++c) {
-      emit(32 * c, true);
-      update(32 * c);
+  // one pass over chunks [c0, c1): the next chunk's fragments travel while this one is computed.
+  // Every branch here is uniform over the block (barriers inside).
+  auto walk = [&](int32_t c0, int32_t c1, bool do_emit, bool causal, bool do_update) {
+    const bool want_q = do_emit, want_k = do_emit && causal, want_kt = do_update;
+    if (c0 < c1) fetch(32 * c0, want_q, want_k, want_kt);
+    for (int32_t c = c0; c < c1; ++c) {
+      __syncthreads();  // the previous chunk's fragments are no longer read
+      park();
+      __syncthreads();
+      if (c + 1 < c1) fetch(32 * (c + 1), want_q, want_k, want_kt);
+      if (do_emit) emit(32 * c, causal);
+      if (do_update && !(do_emit && c + 1 == c1)) update(32 * c);  // the state after the last emitted chunk is not used
     }
-  } else {
-    for (int32_t c = 0; c < nchunks; ++c) update(32 * c);
-    for (int32_t c = 0; c < nchunks; ++c) emit(32 * c, false);
+  };
+
+  const int32_t c_begin = min(nchunks, seg * cps), c_end = min(nchunks, c_begin + cps);
+  float4* my_state = seg_state + (hs * G + seg) * (2 * MC * 64) + lane;
+  if (PHASE == 0) {
+    if (s.causal && seg == G - 1) return;  // nothing comes after the last segment (uniform over the block)
+    walk(c_begin, c_end, false, false, true);
+#pragma unroll
+    for (int x = 0; x < 2 * MC; ++x) my_state[x * 64] = make_float4(S[x][0], S[x][1], S[x][2], S[x][3]);
+    return;
   }
+  if (G > 1) {
+    const int32_t upto = s.causal ? seg : G;
+    const float4* st = seg_state + hs * G * (2 * MC * 64) + lane;
+    for (int32_t g = 0; g < upto; ++g) {
+#pragma unroll
+      for (int x = 0; x < 2 * MC; ++x) {
+        const float4 v = st[(static_cast<int64_t>(g) * 2 * MC + x) * 64];
+        S[x][0] += v.x; S[x][1] += v.y; S[x][2] += v.z; S[x][3] += v.w;
+      }
+    }
+  } else if (!s.causal) {
+    walk(0, nchunks, false, false, true);
+  }
+  walk(c_begin, c_end, true, s.causal != 0, s.causal != 0);
 }
 
 // [C_perf; V]: rows of 192 bf16; C_perf = sums / normaliser (column 128)
@@ -633,8 +715,9 @@ __global__ __launch_bounds__(256) void dec_scalers_kernel(const uint16_t* __rest
 size_t up256(size_t b) { return (b + 255) & ~size_t(255); }
 
 struct DecWs {
-  size_t phiQ, phiK, phiKT, Vt, acc, X, Z, hid, img, y1, y2, total;
+  size_t phiQ, phiK, phiKT, Vt, acc, seg, X, Z, hid, img, y1, y2, total;
   int32_t Tp, T1, Wd, C;
+  int32_t G, cps;  // linear attention: segments per sequence, chunks of 32 tokens per segment
 };
 DecWs dec_layout(const Shape& s) {
   DecWs w{};
@@ -649,6 +732,16 @@ DecWs dec_layout(const Shape& s) {
   w.phiKT = off; off += up256(N * s.m * static_cast<size_t>(w.Tp) * 2);
   w.Vt = off; off += up256(N * kHeadDim * static_cast<size_t>(w.Tp) * 2);
   w.acc = off; off += up256(N * T * kValCols * 4);
+  {
+    // segments: enough (head, slice, segment) waves to fill the chip, at least four chunks each
+    const int32_t nchunks = w.Tp / 32;
+    int32_t G = 1;
+    while (static_cast<int64_t>(s.N) * 9 * G < 3072 && G < 16 && nchunks / (2 * G) >= 4) G *= 2;
+    w.G = G;
+    w.cps = (nchunks + G - 1) / G;
+    w.seg = off;
+    if (G > 1) off += up256(N * 9 * G * static_cast<size_t>(s.m) * 16 * 4);
+  }
   w.X = off; off += up256(N * T * 192 * 2);
   w.Z = off; off += up256(N * T * 128 * 2);
   w.hid = off; off += up256(N * T * 128 * 2);
@@ -702,12 +795,22 @@ hipError_t launch_decoder_estimate(const Shape& s, const sea_decoder_weights& wt
   {
     StageScope scope(SEA_STAGE_STATE, st);
     float* acc = reinterpret_cast<float*>(base + lay.acc);
-    const dim3 grid(static_cast<uint32_t>(s.N) * 9);
+    const dim3 grid(static_cast<uint32_t>(s.N) * lay.G);
+    float4* seg = reinterpret_cast<float4*>(base + lay.seg);
+#define SEA_LINATTN(MC_)                                                                                  \
+    do {                                                                                                  \
+      if (lay.G > 1)                                                                                      \
+        hipLaunchKernelGGL((dec_linattn_kernel<MC_, 0>), grid, dim3(64 * kLinWaves), 0, st, s, lay.Tp, lay.G, lay.cps, \
+                           u16(lay.phiQ), u16(lay.phiK), u16(lay.phiKT), u16(lay.Vt), acc, seg);          \
+      hipLaunchKernelGGL((dec_linattn_kernel<MC_, 1>), grid, dim3(64 * kLinWaves), 0, st, s, lay.Tp, lay.G, lay.cps,   \
+                         u16(lay.phiQ), u16(lay.phiK), u16(lay.phiKT), u16(lay.Vt), acc, seg);            \
+    } while (0)
     switch (s.m) {
-      case 64: hipLaunchKernelGGL(dec_linattn_kernel<2>, grid, dim3(64), 0, st, s, lay.Tp, u16(lay.phiQ), u16(lay.phiK), u16(lay.phiKT), u16(lay.Vt), acc); break;
-      case 128: hipLaunchKernelGGL(dec_linattn_kernel<4>, grid, dim3(64), 0, st, s, lay.Tp, u16(lay.phiQ), u16(lay.phiK), u16(lay.phiKT), u16(lay.Vt), acc); break;
-      default: hipLaunchKernelGGL(dec_linattn_kernel<8>, grid, dim3(64), 0, st, s, lay.Tp, u16(lay.phiQ), u16(lay.phiK), u16(lay.phiKT), u16(lay.Vt), acc); break;
+      case 64: SEA_LINATTN(2); break;
+      case 128: SEA_LINATTN(4); break;
+      default: SEA_LINATTN(8); break;
     }
+#undef SEA_LINATTN
     hipLaunchKernelGGL(dec_concat_kernel, dim3(static_cast<uint32_t>((rows * 24 + 255) / 256)), dim3(256), 0, st, acc, V,
                        u16(lay.X), rows);
   }
