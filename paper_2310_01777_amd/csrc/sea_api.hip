@@ -132,6 +132,8 @@ size_t forward_ws(const sea_params* p, bool lean) {
   if (tile_attn_supported(s, p->dtype, nullptr)) {
     bytes += align256(rows * ((p->K + 31) / 32) * sizeof(uint32_t));
     bytes += align256(tile_attn_workspace(s));
+  } else if (p->dtype == SEA_F32 && tile_attn_f32_supported(s)) {
+    bytes += align256(rows * ((p->K + 31) / 32) * sizeof(uint32_t));
   } else {
     bytes += align256(rows * static_cast<size_t>(row_stride_of(p)) * sizeof(int32_t));
     bytes += align256(rows * sizeof(int32_t));
@@ -375,6 +377,15 @@ int forward_stages(const sea_params* p, const void* Q, const void* K, const void
     e = launch_estimate_f64(s, static_cast<const float*>(Q), static_cast<const float*>(K),
                             static_cast<const float*>(W), A_hat, est_ws, st);
   if (e != hipSuccess) return fail_hip(e);
+  if (p->dtype == SEA_F32 && tile_attn_f32_supported(s)) {
+    // fp32 tensors, column-structured mask: selection as bits, attention on 16-row tiles
+    uint32_t* mbits = mhat_opt ? mhat_opt : reinterpret_cast<uint32_t*>(w);
+    e = launch_topk_mask(s, A_hat, sel_opt, idx_opt, cnt_opt, mbits, st);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_tile_attn_f32(s, static_cast<const float*>(Q), static_cast<const float*>(K),
+                             static_cast<const float*>(V), mbits, static_cast<float*>(O), st);
+    return e == hipSuccess ? SEA_OK : fail_hip(e);
+  }
   int32_t* idx = idx_opt ? idx_opt : reinterpret_cast<int32_t*>(w);
   w += align256(rows * static_cast<size_t>(s.L) * sizeof(int32_t));
   int32_t* cnt = cnt_opt ? cnt_opt : reinterpret_cast<int32_t*>(w);

@@ -58,6 +58,10 @@ hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, in
 // Tiled MFMA attention over the column-structured mask (bf16, K | T, power-of-two keys per column)
 bool tile_attn_supported(const Shape& s, sea_dtype dt, int32_t* rlog_out);
 size_t tile_attn_workspace(const Shape& s);
+// fp32 tensors: tiled attention on the fp64 / fp32 matrix cores from per-row column bits
+bool tile_attn_f32_supported(const Shape& s);
+hipError_t launch_tile_attn_f32(const Shape& s, const float* Q, const float* K, const float* V,
+                                const uint32_t* mbits, float* O, hipStream_t st);
 hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
                             const uint32_t* mbits, uint16_t* O, void* ws, hipStream_t st);
 size_t dense_attn_workspace(const Shape& s);

@@ -709,6 +709,248 @@ hipError_t launch_tile_attn(const Shape& s, const uint16_t* Q, const uint16_t* K
   return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------
+// fp32 tensors: the same walk over the compact key list on the fp64 / fp32 matrix cores.
+// Block = 4 waves on the same 16 query rows; wave w takes the 16-key chunks c = w (mod 4) and the
+// four partial results are merged through LDS (log-sum-exp weights).  Per chunk:
+//   S^T (keys x queries) = K_c Q^T with v_mfma_f64_16x16x4_f64 (fp32 inputs widened, fp64 sums: the
+//   precision contract of the fp32 mode), softmax weights in fp32 against a running reference,
+//   O^T (dims x queries) += V_c^T P^T with v_mfma_f32_16x16x4_f32.
+// Layouts: A lane l = A[row l % 16][k l / 16], B lane l = B[k l / 16][col l % 16]; the fp64 result
+// register i is D[row 4 i + l / 16][col l % 16], the fp32 one D[row 4 (l / 16) + i][col l % 16].
+// So a lane is one query (column); its four S^T registers are keys 4 i + g, g = l / 16, exactly the
+// contraction slot (k = g of step i) the second product expects of P^T.  The contraction index of
+// the first product is a free permutation of the 64 dims: step 4 j + e of lane group g is dim
+// 16 j + 4 g + e, so Q and K rows are read as 16-byte pieces.
+// ------------------------------------------------------------------------------------------
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+struct TileF32Args {
+  const float* Q;
+  const float* K;
+  const float* V;
+  const uint32_t* mbits;  // [N][T][KW]
+  float* O;
+  const int32_t* seq_len;
+  int32_t N, H, T, U, KW, rlog, w, causal;
+  double f;  // scale * log2(e)
+};
+
+__device__ __forceinline__ float rows_max_f(float x) {
+  const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  const float y = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float rows_sum_f(float x) {
+  const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  const float y = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+__global__ __launch_bounds__(256, 2) void tile_attn_f32_kernel(TileF32Args a) {
+  __shared__ float m_s[4][16], l_s[4][16];
+  __shared__ float o_s[4][kHeadDim][17];  // [wave][dim][query], padded
+  __shared__ uint32_t mask_s[16 * 33];     // K <= 1024: at most 32 words per row
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int qc = lane & 15, g = lane >> 4;
+  const uint32_t tiles = (a.T + 15) / 16;
+  // longest first: the last row tiles of every head come first
+  const uint32_t tile = tiles - 1 - blockIdx.x / static_cast<uint32_t>(a.N);
+  const int64_t head = blockIdx.x % static_cast<uint32_t>(a.N);
+  const int32_t q0 = static_cast<int32_t>(tile) * 16;
+  const int32_t t = q0 + qc;
+  const int32_t b = static_cast<int32_t>(head / a.H);
+  const int32_t len = a.seq_len ? min(max(a.seq_len[b], 0), a.T) : a.T;
+  const bool row_active = t < len;
+  const int32_t tq = min(t, a.T - 1);
+  const float* Kh = a.K + head * static_cast<int64_t>(a.T) * kHeadDim;
+  const float* Vh = a.V + head * static_cast<int64_t>(a.T) * kHeadDim;
+  // selected-column bits of the tile's 16 rows -> LDS (row stride KW + 1 words)
+  {
+    const uint32_t* msrc = a.mbits + (head * a.T + q0) * a.KW;
+    const int32_t nwords = min(16, a.T - q0) * a.KW;
+    for (int32_t x = tid; x < 16 * a.KW; x += 256) {
+      const int32_t r = x / a.KW, wi = x - r * a.KW;
+      mask_s[r * (a.KW + 1) + wi] = x < nwords ? msrc[x] : 0u;
+    }
+  }
+  __syncthreads();
+  const uint32_t* mrow_s = &mask_s[qc * (a.KW + 1)];
+
+  double qd[16];
+  {
+    const float* Qr = a.Q + (head * a.T + tq) * kHeadDim + 4 * g;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float4 v = *reinterpret_cast<const float4*>(Qr + 16 * j);
+      qd[4 * j] = v.x; qd[4 * j + 1] = v.y; qd[4 * j + 2] = v.z; qd[4 * j + 3] = v.w;
+    }
+  }
+  const int32_t my_jmax = a.causal ? min(t, len - 1) : len - 1;
+  const int32_t t_hi = min(q0 + 15, a.T - 1);
+  const int32_t u_end = compact_count(a.causal ? min(t_hi, len - 1) : len - 1, a.rlog, a.w);
+  const int32_t nchunks = (u_end + 15) / 16;
+
+  double m_run = -INFINITY;
+  float l_run = 0.f;
+  floatx4 o[4];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt) o[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // admissibility of this lane's four entries of chunk cc (keys 16 cc + 4 i + g) and their
+  // positions; false when no row of the tile uses the chunk
+  bool okn[4];
+  int32_t pvn[4];
+  auto probe = [&](int32_t cc) -> bool {
+    bool any = false;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int32_t u = 16 * cc + 4 * i + g, uc = min(u, a.U - 1);
+      const int32_t col = uc >> a.rlog;
+      pvn[i] = pos_of(uc, a.rlog, a.w);
+      okn[i] = row_active && u < a.U && ((mrow_s[col >> 5] >> (col & 31)) & 1u) != 0u && pvn[i] <= my_jmax;
+      any = any || okn[i];
+    }
+    return __ballot(any) != 0ull;
+  };
+  // operands of chunk cc: K row of key 16 cc + qc (16-byte pieces at dims 16 j + 4 g), V entries
+  // at dims 16 dt + qc of this lane's four keys
+  float4 kfn[4];
+  float vfn[4][4];
+  auto request = [&](int32_t cc) {
+    const float* Kr = Kh + static_cast<int64_t>(pos_of(min(16 * cc + qc, a.U - 1), a.rlog, a.w)) * kHeadDim + 4 * g;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) kfn[j] = *reinterpret_cast<const float4*>(Kr + 16 * j);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) vfn[i][dt] = Vh[static_cast<int64_t>(pvn[i]) * kHeadDim + 16 * dt + qc];
+  };
+
+  int32_t c = wid;
+  while (c < nchunks && !probe(c)) c += 4;
+  if (c < nchunks) request(c);
+  while (c < nchunks) {
+    // take over the chunk that is on its way, then look for the next one and request it
+    bool ok[4];
+    float4 kf[4];
+    float vf[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      ok[i] = okn[i];
+      kf[i] = kfn[i];
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) vf[i][dt] = vfn[i][dt];
+    }
+    int32_t cn = c + 4;
+    while (cn < nchunks && !probe(cn)) cn += 4;
+    if (cn < nchunks) request(cn);
+    c = cn;
+
+    // two independent chains halve the latency of the 16 dependent products
+    doublex4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int j = 0; j < 4; j += 2) {
+      acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(kf[j].x), qd[4 * j], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(kf[j + 1].x), qd[4 * j + 4], acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(kf[j].y), qd[4 * j + 1], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(kf[j + 1].y), qd[4 * j + 5], acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(kf[j].z), qd[4 * j + 2], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(kf[j + 1].z), qd[4 * j + 6], acc1, 0, 0, 0);
+      acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(kf[j].w), qd[4 * j + 3], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(static_cast<double>(kf[j + 1].w), qd[4 * j + 7], acc1, 0, 0, 0);
+    }
+    double y[4];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      y[i] = ok[i] ? (acc0[i] + acc1[i]) * a.f : -INFINITY;
+      mx = fmaxf(mx, static_cast<float>(y[i]));
+    }
+    // the reference only has to be common to the row's keys: an fp32 rounding of the maximum does
+    mx = rows_max_f(mx);
+    const double m_new = fmax(m_run, static_cast<double>(mx));
+    if (__ballot(m_new != -INFINITY) == 0ull) continue;
+    const double m_safe = (m_new == -INFINITY) ? 0.0 : m_new;
+    const float corr = (m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(static_cast<float>(m_run - m_safe));
+    m_run = m_new;
+    l_run *= corr;
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) o[dt][i] *= corr;
+    float pw[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      pw[i] = __builtin_amdgcn_exp2f(static_cast<float>(y[i] - m_safe));  // exp2(-inf) = 0 for masked entries
+      l_run += pw[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_16x16x4f32(vf[i][dt], pw[i], o[dt], 0, 0, 0);
+  }
+  // merge the four waves: O = sum_w 2^(m_w - M) O_w / sum_w 2^(m_w - M) l_w.  m_run only ever takes
+  // fp32 values (or -inf), so publishing it as fp32 loses nothing.
+  l_run = rows_sum_f(l_run);
+  if (g == 0) {
+    m_s[wid][qc] = static_cast<float>(m_run);
+    l_s[wid][qc] = l_run;
+  }
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o_s[wid][16 * dt + 4 * g + i][qc] = o[dt][i];
+  __syncthreads();
+  {
+    const int q = tid & 15, dq = tid >> 4;  // query, quad of dims
+    const int32_t tt = q0 + q;
+    float M = fmaxf(fmaxf(m_s[0][q], m_s[1][q]), fmaxf(m_s[2][q], m_s[3][q]));
+    float L = 0.f, acc4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float wgt = (m_s[w][q] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m_s[w][q] - M);
+      L = fmaf(wgt, l_s[w][q], L);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc4[e] = fmaf(wgt, o_s[w][4 * dq + e][q], acc4[e]);
+    }
+    if (tt < a.T) {
+      const float inv = (tt < len && L > 0.f) ? 1.f / L : 0.f;
+      *reinterpret_cast<float4*>(a.O + (head * a.T + tt) * kHeadDim + 4 * dq) =
+          make_float4(acc4[0] * inv, acc4[1] * inv, acc4[2] * inv, acc4[3] * inv);
+    }
+  }
+}
+
+bool tile_attn_f32_supported(const Shape& s) {
+  if (s.geometry != 0 || s.T % s.K != 0 || s.K > 1024) return false;  // the tile's mask words live in LDS
+  const int32_t w = s.T / s.K;
+  const int32_t r = w < s.rep_cap ? w : s.rep_cap;
+  if (r <= 0 || (r & (r - 1)) != 0) return false;
+  if (static_cast<int64_t>(w) * r > (int64_t(1) << 30)) return false;
+  return true;
+}
+
+hipError_t launch_tile_attn_f32(const Shape& s, const float* Q, const float* K, const float* V,
+                                const uint32_t* mbits, float* O, hipStream_t st) {
+  if (!tile_attn_f32_supported(s)) return hipErrorNotSupported;
+  const int32_t w = s.T / s.K, r = w < s.rep_cap ? w : s.rep_cap;
+  int32_t rlog = 0;
+  while ((1 << rlog) < r) ++rlog;
+  StageScope scope(SEA_STAGE_SPARSE, st);
+  TileF32Args a{};
+  a.Q = Q; a.K = K; a.V = V; a.mbits = mbits; a.O = O; a.seq_len = s.seq_len;
+  a.N = s.N; a.H = s.H; a.T = s.T; a.U = s.K * r; a.KW = (s.K + 31) / 32; a.rlog = rlog; a.w = w; a.causal = s.causal;
+  a.f = static_cast<double>(s.scale) * 1.4426950408889634;
+  const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 15) / 16));
+  hipLaunchKernelGGL(tile_attn_f32_kernel, grid, dim3(256), 0, st, a);
+  return hipGetLastError();
+}
+
 size_t dense_attn_workspace(const Shape&) { return 0; }
 
 hipError_t launch_dense_attn(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* V,
