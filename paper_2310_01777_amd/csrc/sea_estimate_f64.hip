@@ -180,9 +180,30 @@ __global__ __launch_bounds__(256) void contract_f64_kernel(Shape s, const double
     act[i] = t < len;
     tcol[i] = act[i] ? bucket_of(t, s.T, s.K) : -1;
   }
+  // Operands are requested a block of contraction steps ahead of the products that use them (two
+  // register sets in turn): with one wave per SIMD nothing else hides the memory latency.
   if (s.causal) {
+    constexpr int DS = 8;  // steps per block; m is a multiple of 32 = 8 steps
     doublex4 dg = {0.0, 0.0, 0.0, 0.0};
-    for (int32_t f = 0; f < s.m; f += 4) dg = mfma_f64(qrow[f], prow[f], dg);
+    double qa[DS], pa[DS], qb[DS], pb[DS];
+    auto ld = [&](int32_t f0, double (&q)[DS], double (&p)[DS]) {
+#pragma unroll
+      for (int e = 0; e < DS; ++e) { q[e] = qrow[f0 + 4 * e]; p[e] = prow[f0 + 4 * e]; }
+    };
+    auto mm = [&](const double (&q)[DS], const double (&p)[DS]) {
+#pragma unroll
+      for (int e = 0; e < DS; ++e) dg = mfma_f64(q[e], p[e], dg);
+    };
+    ld(0, qa, pa);
+    for (int32_t f0 = 0; f0 < s.m; f0 += 8 * DS) {
+      const bool more = f0 + 4 * DS < s.m;
+      if (more) ld(f0 + 4 * DS, qb, pb);
+      mm(qa, pa);
+      if (more) {
+        if (f0 + 8 * DS < s.m) ld(f0 + 8 * DS, qa, pa);
+        mm(qb, pb);
+      }
+    }
     // the diagonal entry of token u sits in lane (lr = u, lg = u % 4), register u / 4
 #pragma unroll
     for (int i = 0; i < 4; ++i) diag[i] = __shfl(dg[i], 16 * lg + 4 * i + lg, kWave);
@@ -190,16 +211,37 @@ __global__ __launch_bounds__(256) void contract_f64_kernel(Shape s, const double
   doublex4 acc[NCT];
   auto group = [&](int32_t g) {
     const int32_t c0 = 16 * NCT * g;
+    constexpr int FS = NCT >= 16 ? 2 : 4;  // contraction steps per block
 #pragma unroll
     for (int ct = 0; ct < NCT; ++ct) acc[ct] = doublex4{0.0, 0.0, 0.0, 0.0};
-    for (int32_t f = 0; f < s.m; f += 4) {
-      const double a = qrow[f];
+    int32_t ccol[NCT];
 #pragma unroll
-      for (int ct = 0; ct < NCT; ++ct) {
-        if (c0 + 16 * ct < ncols) {
-          const int32_t c = min(c0 + 16 * ct + lr, s.K - 1);
-          acc[ct] = mfma_f64(a, st[static_cast<int64_t>(f + lg) * s.K + c], acc[ct]);
-        }
+    for (int ct = 0; ct < NCT; ++ct) ccol[ct] = min(c0 + 16 * ct + lr, s.K - 1);
+    double aa[FS], ab[FS], ba[NCT][FS], bb[NCT][FS];
+    auto ld = [&](int32_t f0, double (&qa)[FS], double (&bs)[NCT][FS]) {
+#pragma unroll
+      for (int e = 0; e < FS; ++e) {
+        qa[e] = qrow[f0 + 4 * e];
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct)
+          if (c0 + 16 * ct < ncols) bs[ct][e] = st[static_cast<int64_t>(f0 + 4 * e + lg) * s.K + ccol[ct]];
+      }
+    };
+    auto mm = [&](const double (&qa)[FS], const double (&bs)[NCT][FS]) {
+#pragma unroll
+      for (int e = 0; e < FS; ++e)
+#pragma unroll
+        for (int ct = 0; ct < NCT; ++ct)
+          if (c0 + 16 * ct < ncols) acc[ct] = mfma_f64(qa[e], bs[ct][e], acc[ct]);
+    };
+    ld(0, aa, ba);
+    for (int32_t f0 = 0; f0 < s.m; f0 += 8 * FS) {
+      const bool more = f0 + 4 * FS < s.m;
+      if (more) ld(f0 + 4 * FS, ab, bb);
+      mm(aa, ba);
+      if (more) {
+        if (f0 + 8 * FS < s.m) ld(f0 + 8 * FS, aa, ba);
+        mm(ab, bb);
       }
     }
 #pragma unroll
