@@ -50,6 +50,10 @@ __device__ __forceinline__ double exp_f64(double x) {
 // phi for 16 rows per wave.  which = 0: queries (row-max shifted, any shift cancels in the
 // normaliser), 1: keys (no shift; zero beyond seq_len).  D[row = token 4 i + lg][col = feature lr];
 // contraction slot (step s, lane group lg) stands for dimension 16 lg + s.
+// NFT > 0: the exponent arguments of the (at most NFT) feature tiles stay in registers between the
+// projection and the exponential, and the unrolled tile loop lets the loads of W run ahead;
+// NFT = 0: any m, the arguments take a round trip through the output buffer.
+template <int NFT>
 __global__ __launch_bounds__(256) void features_f64_kernel(Shape s, const float* __restrict__ Q,
                                                            const float* __restrict__ K, const float* __restrict__ W,
                                                            double* __restrict__ phiQ, double* __restrict__ phiK) {
@@ -84,41 +88,77 @@ __global__ __launch_bounds__(256) void features_f64_kernel(Shape s, const float*
   for (int i = 0; i < 4; ++i) half_n[i] = 0.5 * __shfl(nx, 4 * i + lg, kWave);
   double* out = (which ? phiK : phiQ) + (head * s.T) * s.m;
   double amax[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-  for (int ft = 0; ft < s.m / 16; ++ft) {
+  const int ntiles = s.m / 16;
+  auto project = [&](int ft) {
     const float* w = W + static_cast<int64_t>(ft * 16 + lr) * kHeadDim + 16 * lg;
+    float4 wv[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) wv[q] = *reinterpret_cast<const float4*>(w + 4 * q);
     doublex4 acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const float4 v = *reinterpret_cast<const float4*>(w + 4 * q);
-      acc = mfma_f64(xa[4 * q], static_cast<double>(v.x), acc);
-      acc = mfma_f64(xa[4 * q + 1], static_cast<double>(v.y), acc);
-      acc = mfma_f64(xa[4 * q + 2], static_cast<double>(v.z), acc);
-      acc = mfma_f64(xa[4 * q + 3], static_cast<double>(v.w), acc);
+      acc = mfma_f64(xa[4 * q], static_cast<double>(wv[q].x), acc);
+      acc = mfma_f64(xa[4 * q + 1], static_cast<double>(wv[q].y), acc);
+      acc = mfma_f64(xa[4 * q + 2], static_cast<double>(wv[q].z), acc);
+      acc = mfma_f64(xa[4 * q + 3], static_cast<double>(wv[q].w), acc);
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int32_t t = r0 + 4 * i + lg;
-      const double a = acc[i] - half_n[i];
-      amax[i] = fmax(amax[i], a);
-      if (t < s.T) out[static_cast<int64_t>(t) * s.m + ft * 16 + lr] = a;  // exponent argument for now
-    }
-  }
+    return acc;
+  };
   double shift[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    double mx = amax[i];
-#pragma unroll
-    for (int mask = 1; mask < 16; mask <<= 1) mx = fmax(mx, __shfl_xor(mx, mask, kWave));
-    shift[i] = which ? 0.0 : mx;
-  }
-  // second pass over the lane's own values
-  for (int ft = 0; ft < s.m / 16; ++ft) {
+  auto row_shift = [&]() {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int32_t t = r0 + 4 * i + lg;
-      if (t >= s.T) continue;
-      double* o = out + static_cast<int64_t>(t) * s.m + ft * 16 + lr;
-      *o = t < len ? exp_f64(*o - shift[i]) : 0.0;
+      double mx = amax[i];
+#pragma unroll
+      for (int mask = 1; mask < 16; mask <<= 1) mx = fmax(mx, __shfl_xor(mx, mask, kWave));
+      shift[i] = which ? 0.0 : mx;
+    }
+  };
+  if constexpr (NFT > 0) {
+    double arg[NFT][4];
+#pragma unroll
+    for (int ft = 0; ft < NFT; ++ft) {
+      if (ft < ntiles) {
+        const doublex4 acc = project(ft);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          arg[ft][i] = acc[i] - half_n[i];
+          amax[i] = fmax(amax[i], arg[ft][i]);
+        }
+      }
+    }
+    row_shift();
+#pragma unroll
+    for (int ft = 0; ft < NFT; ++ft) {
+      if (ft < ntiles) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int32_t t = r0 + 4 * i + lg;
+          if (t < s.T) out[static_cast<int64_t>(t) * s.m + ft * 16 + lr] = t < len ? exp_f64(arg[ft][i] - shift[i]) : 0.0;
+        }
+      }
+    }
+  } else {
+    for (int ft = 0; ft < ntiles; ++ft) {
+      const doublex4 acc = project(ft);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int32_t t = r0 + 4 * i + lg;
+        const double a = acc[i] - half_n[i];
+        amax[i] = fmax(amax[i], a);
+        if (t < s.T) out[static_cast<int64_t>(t) * s.m + ft * 16 + lr] = a;  // exponent argument for now
+      }
+    }
+    row_shift();
+    // second pass over the lane's own values
+    for (int ft = 0; ft < ntiles; ++ft) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int32_t t = r0 + 4 * i + lg;
+        if (t >= s.T) continue;
+        double* o = out + static_cast<int64_t>(t) * s.m + ft * 16 + lr;
+        *o = t < len ? exp_f64(*o - shift[i]) : 0.0;
+      }
     }
   }
 }
@@ -330,8 +370,13 @@ hipError_t launch_estimate_f64(const Shape& s, const float* Q, const float* K, c
   {
     StageScope scope(SEA_STAGE_FEATURES, st);
     const int64_t waves = 2 * static_cast<int64_t>(s.N) * ((s.T + 15) / 16);
-    hipLaunchKernelGGL(features_f64_kernel, dim3(static_cast<uint32_t>((waves + 3) / 4)), dim3(256), 0, st, s, Q, K, W,
-                       phiQ, phiK);
+    const dim3 grid(static_cast<uint32_t>((waves + 3) / 4));
+    if (s.m <= 128)
+      hipLaunchKernelGGL(features_f64_kernel<8>, grid, dim3(256), 0, st, s, Q, K, W, phiQ, phiK);
+    else if (s.m <= 256)
+      hipLaunchKernelGGL(features_f64_kernel<16>, grid, dim3(256), 0, st, s, Q, K, W, phiQ, phiK);
+    else
+      hipLaunchKernelGGL(features_f64_kernel<0>, grid, dim3(256), 0, st, s, Q, K, W, phiQ, phiK);
   }
   {
     StageScope scope(SEA_STAGE_STATE, st);
