@@ -201,7 +201,7 @@ template <int MC, int WLOG>
 __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
     Shape s, const uint16_t* __restrict__ K, const uint16_t* __restrict__ W, uint16_t* __restrict__ state,
     uint16_t* __restrict__ pref, float* __restrict__ bsum_u, float* __restrict__ bsum_r, float c_dot,
-    float c_norm) {
+    float c_norm, int32_t iters) {
   constexpr int m = 32 * MC;
   constexpr int w = 1 << WLOG;
   constexpr int kWaves = w > 64 ? w / 16 : 4;  // waves per block
@@ -214,10 +214,11 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
   const int tid = threadIdx.x, lane = tid & 63;
   const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lr = lane & 15, lg = lane >> 4;
+  // a block takes `iters` consecutive key tiles of one head, so W is parked once for all of them
   const uint32_t tiles = (s.T + kRows - 1) / kRows;
-  const int64_t head = blockIdx.x / tiles;
-  const int32_t blk_r0 = static_cast<int32_t>(blockIdx.x % tiles) * kRows;
-  const int32_t r0 = blk_r0 + wid * 16;
+  const uint32_t bph = (tiles + iters - 1) / iters;  // blocks per head
+  const int64_t head = blockIdx.x / bph;
+  const uint32_t tile_first = (blockIdx.x % bph) * iters;
   for (int x = tid; x < m * 8; x += 64 * kWaves) {
     const int r = x >> 3, part8 = x & 7;
     *reinterpret_cast<uint4*>(&Ws[r * kWRow + part8 * 8]) =
@@ -226,6 +227,10 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
   __syncthreads();
   const int32_t b = static_cast<int32_t>(head / s.H);
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
+  for (uint32_t tile = tile_first; tile < min(tile_first + static_cast<uint32_t>(iters), tiles); ++tile) {
+  if (tile != tile_first) __syncthreads();  // the sums of the previous tile have left LDS
+  const int32_t blk_r0 = static_cast<int32_t>(tile) * kRows;
+  const int32_t r0 = blk_r0 + wid * 16;
   // operand rows: key r0 + lr; accumulator rows: keys r0 + 4 lg + i
   const uint16_t* X = K + (head * s.T + min(r0 + lr, s.T - 1)) * kHeadDim;
   const bf16x8 x0 = *reinterpret_cast<const bf16x8*>(X + 8 * lg);
@@ -282,7 +287,7 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
       }
     }
   }
-  if (w < 4) return;
+  if (w < 4) continue;
   __syncthreads();
   if (w <= 16) {
     // each LDS vector is one finished column: columns blk_r0 / w + 0 .. kSlots - 1
@@ -297,7 +302,7 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
     // column spans several waves of this block
     constexpr int wpc = w / 16;            // waves per column
     constexpr int cols = kRows / w;        // columns per block
-    const int32_t col0 = static_cast<int32_t>(blockIdx.x % tiles) * cols;
+    const int32_t col0 = static_cast<int32_t>(tile) * cols;
     for (int x = tid; x < cols * m; x += 64 * kWaves) {
       const int cl = x / m, p = x - cl * m;
       float acc = 0.f;
@@ -306,7 +311,7 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
       if (WLOG == 7 && bsum_u) {
         // columns wider than this block: leave the block's sums (and, causal, the sums of the
         // rounded features) for the kernel that walks each column's blocks
-        const int64_t blk = head * tiles + blockIdx.x % tiles;
+        const int64_t blk = head * tiles + tile;
         bsum_u[blk * m + p] = acc;
         if (bsum_r) {
           float racc = 0.f;
@@ -322,7 +327,7 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
       // exclusive prefix over the column's tiles, as bf16 planes hi + lo + lo2 (each difference is
       // exact in fp32, so the three planes carry the leading 24 bits of the sum)
       const int64_t ntile = s.T >> 4;
-      const int64_t tile0 = static_cast<int64_t>(blockIdx.x % tiles) * kWaves;
+      const int64_t tile0 = static_cast<int64_t>(tile) * kWaves;
       for (int x = tid; x < kWaves * m; x += 64 * kWaves) {
         const int q = x / m, p = x - q * m, qc = q & (wpc - 1);
         if (qc == 0 || tile0 + q >= ntile) continue;  // a column's first tile has nothing before it
@@ -339,6 +344,7 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
       }
     }
   }
+  }  // tiles of this block
 }
 
 // Columns of 256 keys or more: one block per (head, column) adds up the column's 128-key blocks.
@@ -871,8 +877,12 @@ void launch_key(const Shape& s, const uint16_t* K, const uint16_t* W, const Fuse
                 float c_norm, hipStream_t st) {
   constexpr int kKeyWaves = (1 << WLOG) > 64 ? (1 << WLOG) / 16 : 4;
   const uint32_t ktiles = (s.T + 16 * kKeyWaves - 1) / (16 * kKeyWaves);
-  hipLaunchKernelGGL((key_state_kernel<MC, WLOG>), dim3(static_cast<uint32_t>(s.N) * ktiles),
-                     dim3(64 * kKeyWaves), 0, st, s, K, W, f.state, f.pref, f.bsum_u, f.bsum_r, c_dot, c_norm);
+  // tiles per block: as many as leave about eight blocks per CU
+  int32_t iters = static_cast<int32_t>((static_cast<int64_t>(s.N) * ktiles) / 2048);
+  iters = iters < 1 ? 1 : (iters > 8 ? 8 : iters);
+  const uint32_t bph = (ktiles + iters - 1) / iters;
+  hipLaunchKernelGGL((key_state_kernel<MC, WLOG>), dim3(static_cast<uint32_t>(s.N) * bph), dim3(64 * kKeyWaves), 0, st,
+                     s, K, W, f.state, f.pref, f.bsum_u, f.bsum_r, c_dot, c_norm, iters);
 }
 
 template <int MC, int WLOG>
