@@ -667,8 +667,9 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   // Bits 29..16 are searched on the keys' high halves, two keys per register: both halves of
   // hp - trial (16-bit wrap-around differences; candidates and trial lie in [0x8000, 0xc000),
   // non-candidates are 0x4000) have bit 15 set exactly for keys below the trial, and those bits are
-  // counted four differences at a time.  The trial's low half is zero in that phase, so the counts
-  // are those of the full keys.  Bits 15..0 then compare whole keys.
+  // counted four differences at a time (a byte permute spreads each sign over a byte).  The trial's
+  // low half is zero in that phase, so the counts are those of the full keys.  Bits 15..0 then
+  // compare whole keys.
 #define SEA_SEARCH_STEP(COUNT_BODY_)                                                             \
     /* done when every row's count of keys >= tau equals its quota */                            \
     const bool pend = (cge != nsel) && (nsel != 0u);                                             \
@@ -695,11 +696,10 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
         _Pragma("unroll") for (int pr = 0; pr < 2 * (NT_); pr += 2) {                             \
           const uint32_t d0 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr] - th2)); \
           const uint32_t d1 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr + 1] - th2)); \
-          /* the four sign bytes of two differences */                                           \
-          const uint32_t sb = __builtin_amdgcn_perm(d1, d0, 0x07050301u) & 0x80808080u;          \
-          below += static_cast<uint32_t>(__popc(sb));                                            \
+          /* byte selectors 8..11 give 0x00 / 0xff by the sign of bytes 1, 3, 5, 7: eight bits a key */ \
+          below += static_cast<uint32_t>(__popc(__builtin_amdgcn_perm(d1, d0, 0x0b0a0908u)));    \
         }                                                                                        \
-        cnt = 4u * static_cast<uint32_t>(NT_) - below;)                                          \
+        cnt = 4u * static_cast<uint32_t>(NT_) - (below >> 3);)                                   \
     }                                                                                            \
   }                                                                                              \
   _Pragma("unroll 1") for (int bit = 15; bit >= 0; --bit) {                                       \

@@ -303,9 +303,10 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
       for (int pr = 0; pr < VPT / 2; pr += 2) {
         const uint32_t d0 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr] - th2));
         const uint32_t d1 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr + 1] - th2));
-        below += static_cast<uint32_t>(__popc(__builtin_amdgcn_perm(d1, d0, 0x07050301u) & 0x80808080u));
+        // byte selectors 8..11 give 0x00 / 0xff by the sign of bytes 1, 3, 5, 7: eight bits a key
+        below += static_cast<uint32_t>(__popc(__builtin_amdgcn_perm(d1, d0, 0x0b0a0908u)));
       }
-      const uint32_t c = wave_sum_u32(static_cast<uint32_t>(VPT) - below);
+      const uint32_t c = wave_sum_u32(static_cast<uint32_t>(VPT) - (below >> 3));
       if (lane == 0) red[bit & 1][wid] = c;
       __syncthreads();  // the buffers alternate, so one barrier per step is enough
       const uint32_t ct = red[bit & 1][0] + red[bit & 1][1] + red[bit & 1][2] + red[bit & 1][3];
