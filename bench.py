@@ -29,8 +29,8 @@ SWEEP = ("c1", "c2", "c3", "c4_T4096", "c4_T8192", "c4_T16384", "c5")
 # HBM bytes per launch (fetched, written) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # script, scaled by the copy-kernel factors; they cannot be read inside this process, so they are
 # quoted from the committed summary and only for the workload and kernel that summary covers.
-TRAFFIC_FROM_PROFILES = {("c4_T32768", "sparse"): (190.2e6, 134.2e6), ("c4_T32768", "contract"): (361.7e6, 33.6e6),
-                         ("c4_T32768", "state"): (134.6e6, 92.3e6)}
+TRAFFIC_FROM_PROFILES = {("c4_T32768", "sparse"): (190.8e6, 134.2e6), ("c4_T32768", "contract"): (361.7e6, 33.6e6),
+                         ("c4_T32768", "state"): (135.1e6, 92.3e6)}
 TRAFFIC_SOURCE = "profiles/sea_forward_c4_T32768.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, not measured in this run)"
 
 
@@ -243,6 +243,14 @@ def measure(torch, sea, synth, wl, steps, warmup, detail):
                              "issued_tflops": issued / (sparse_ms * 1e-3) / 1e12, "pairs": pairs,
                              "note": "achieved counts the selected (query, key) pairs only, 4 d flops each; issued "
                                      "counts every pair of the 32 x 32 tiles the kernel visits"}
+    elif sparse_ms > 0 and sea.sea_attention_path(p) == 2:
+        # fp32 tensors: q.k on the fp64 matrix cores (2 d flops per pair), P V on the fp32 ones (2 d)
+        ach = 2.0 * wl.d * pairs / (sparse_ms * 1e-3) / 1e12
+        kernels["sparse"] = {"kernel": "tile_attn_f32_kernel", "bound": "mfma", "achieved": ach, "peak": FP64_PEAK_TFLOPS,
+                             "unit": "TFLOP/s", "frac": ach / FP64_PEAK_TFLOPS, "avg_kernel_ms": sparse_ms,
+                             "algorithmic_flops": 2.0 * wl.d * pairs, "pairs": pairs,
+                             "note": "fp64 products of the selected (query, key) pairs only, against the fp64 matrix "
+                                     "peak; the fp32 products of P V (as many again) run beside them"}
     elif sparse_ms > 0:
         # per-row list kernel: the bytes that must cross HBM once are Q, K, V, O and the lists; the
         # repeated K / V row gathers of the pairs are served by the caches

@@ -630,7 +630,9 @@ int sea_attention_path(const sea_params* p) {
   int rc = check_common(p);
   if (rc == SEA_OK) rc = check_mask_params(p);
   if (rc != SEA_OK) return rc;
-  return tile_attn_supported(make_shape(p, true), p->dtype, nullptr) ? 1 : 0;
+  const Shape s = make_shape(p, true);
+  if (tile_attn_supported(s, p->dtype, nullptr)) return 1;
+  return (p->dtype == SEA_F32 && tile_attn_f32_supported(s)) ? 2 : 0;
 }
 
 const char* sea_version(void) { return "sea-hip 0.1 (gfx950)"; }

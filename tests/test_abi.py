@@ -102,7 +102,8 @@ def test_argument_validation_returns_codes_not_crashes(sea):
     assert sea.sea_version().startswith("sea-hip")
     # which attention kernel a forward call takes: tiles need bf16, K | T and a power-of-two r
     assert sea.sea_attention_path(P(1, 2, 2048, 64, 128, 128, 64)) == 1
-    assert sea.sea_attention_path(P(1, 2, 2048, 64, 128, 128, 64, dtype="f32")) == 0
+    assert sea.sea_attention_path(P(1, 2, 2048, 64, 128, 128, 64, dtype="f32")) == 2
+    assert sea.sea_attention_path(P(1, 2, 300, 64, 96, 17, 5, dtype="f32")) == 0
     assert sea.sea_attention_path(P(1, 2, 300, 64, 96, 17, 5)) == 0            # K does not divide T
     assert sea.sea_attention_path(P(1, 2, 768, 64, 64, 64, 8, k_budget=24)) == 0   # r = 3
     assert sea.sea_attention_path(P(1, 1, 64, 64, 32, 16, 17)) == sea.SEA_EINVAL
