@@ -752,8 +752,218 @@ DecWs dec_layout(const Shape& s) {
   return w;
 }
 
+// ------------------------------------------------------------------------------------------
+// 3x3 convolutions with the input window in LDS.  A block of eight waves computes a tile of output
+// pixels (each wave 64 of them: RW rows x CW columns, RW CW = 64) for a slab of up to 16 NT output
+// channels.  The tile's input halo -- every (virtual, i.e. resized) pixel any of its taps touches,
+// zeros outside the image -- and the slab's weights are parked in LDS once per channel chunk, the
+// weights in operand-fragment order, the pixels with an odd number of 16-byte units per pixel so
+// that the 16 pixels of an operand tile hit different banks.  Each input pixel is then read from
+// memory once per tile instead of once per tap.  The contraction runs over (tap, channel) of the
+// chunk flattened in units of 8 channels, one unit per lane group and step; a lane advances its own
+// (tap, unit) position without divisions.
+// ------------------------------------------------------------------------------------------
+struct Conv3Args {
+  ConvArgs a;
+  int32_t t_shift, x_shift;      // log2 of the nearest-resize ratios (virtual / stored size)
+  int32_t CK, nchunk, P, pp_log; // channels per chunk, chunks, 16-byte units per pixel and chunk, log2 of P rounded up
+  int32_t ksteps;                // contraction steps per chunk
+  int32_t cw_log;                // log2 of the columns a wave covers (4..6); rows per wave = 64 >> cw_log
+  int32_t rows_out, cols_out, halo_rows, halo_cols, px_units;  // tile geometry; px_units odd
+  int32_t tiles_t, tiles_x;
+};
+constexpr int kConv3Waves = 8;
+
+template <int NT>
+__global__ __launch_bounds__(64 * kConv3Waves) void dec_conv3_kernel(Conv3Args g) {
+  extern __shared__ __attribute__((aligned(16))) uint4 lds3[];
+  const ConvArgs& a = g.a;
+  uint4* halo = lds3;                                                        // [halo_rows][halo_cols][px_units]
+  uint4* wts = lds3 + static_cast<int64_t>(g.halo_rows) * g.halo_cols * g.px_units;  // [kstep][NT][64]
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lr = lane & 15, lg = lane >> 4;
+  uint32_t bid = blockIdx.x;
+  const int32_t tx = static_cast<int32_t>(bid % static_cast<uint32_t>(g.tiles_x)); bid /= static_cast<uint32_t>(g.tiles_x);
+  const int32_t tt = static_cast<int32_t>(bid % static_cast<uint32_t>(g.tiles_t));
+  const int64_t b = bid / static_cast<uint32_t>(g.tiles_t);
+  const int32_t t0 = tt * g.rows_out, x0 = tx * g.cols_out;     // first output pixel of the tile
+  const int32_t tv0 = t0 * a.stride_t - a.pad_top, xv0 = x0 - 1;  // first virtual input pixel of the halo
+  const int32_t cout0 = blockIdx.y * (16 * NT);
+  const int32_t ktot = 9 * a.Cin;
+  const uint16_t* img = a.in + b * a.Tin * a.Xin * a.Cin;
+
+  floatx4 acc[NT][4];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) acc[nt][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  // this lane's pixel in each of the wave's four operand tiles: row and column inside the output tile
+  const int rw = 64 >> g.cw_log, ctiles = (1 << g.cw_log) >> 4;  // rows per wave, 16-pixel tiles per row
+  int32_t prow[4], pcol[4];
+#pragma unroll
+  for (int mt = 0; mt < 4; ++mt) {
+    prow[mt] = wid * rw + mt / ctiles;
+    pcol[mt] = (mt % ctiles) * 16 + lr;
+  }
+
+  for (int32_t ch = 0; ch < g.nchunk; ++ch) {
+    if (ch > 0) __syncthreads();  // the previous chunk is no longer read
+    const int32_t cbase = ch * g.CK;
+    // halo: thread = (pixel, 16-byte unit); units past P idle
+    {
+      const int32_t unit = tid & ((1 << g.pp_log) - 1);
+      const int32_t npx = g.halo_rows * g.halo_cols;
+      for (int32_t px = tid >> g.pp_log; px < npx; px += (64 * kConv3Waves) >> g.pp_log) {
+        if (unit >= g.P) continue;
+        const int32_t hr = px / g.halo_cols, hc = px - hr * g.halo_cols;
+        const int32_t tv = tv0 + hr, xv = xv0 + hc;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (static_cast<uint32_t>(tv) < static_cast<uint32_t>(a.Tv) && static_cast<uint32_t>(xv) < static_cast<uint32_t>(a.Xv)) {
+          const int32_t ts = tv >> g.t_shift, xs = xv >> g.x_shift;
+          v = *reinterpret_cast<const uint4*>(img + (static_cast<int64_t>(ts) * a.Xin + xs) * a.Cin + cbase + 8 * unit);
+        }
+        halo[static_cast<int64_t>(px) * g.px_units + unit] = v;
+      }
+    }
+    // weights of the chunk: fragment (step, tile, lane) = channels cbase + 8 cu .. + 7 of tap `tap` for
+    // output channel cout0 + 16 nt + lane % 16, with (tap, cu) = unit 4 step + lane / 16 of the chunk
+    for (int32_t id = tid; id < g.ksteps * NT * 64; id += 64 * kConv3Waves) {
+      const int32_t fl = id & 63, q = id >> 6, nt = q % NT, ks = q / NT;
+      const int32_t u = 4 * ks + (fl >> 4), tap = u / g.P, cu = u - tap * g.P;
+      const int32_t co = cout0 + 16 * nt + (fl & 15);
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);
+      if (tap < 9 && co < a.Cout)
+        v = *reinterpret_cast<const uint4*>(a.w + static_cast<int64_t>(co) * ktot + tap * a.Cin + cbase + 8 * cu);
+      wts[id] = v;
+    }
+    __syncthreads();
+    int32_t tap = 0, cu = lg;
+    while (cu >= g.P) { cu -= g.P; ++tap; }
+    for (int32_t ks = 0; ks < g.ksteps; ++ks) {
+      const bool valid = tap < 9;
+      const int32_t ky = (tap * 11) >> 5, kx = tap - 3 * ky;  // tap / 3 and tap % 3 for tap <= 8
+      bf16x8 xf[4];
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt) {
+        const int32_t hr = prow[mt] * a.stride_t + ky, hc = pcol[mt] + kx;
+        const uint4 v = halo[valid ? (static_cast<int64_t>(hr) * g.halo_cols + hc) * g.px_units + cu : 0];
+        xf[mt] = valid ? __builtin_bit_cast(bf16x8, v) : zero8();
+      }
+      const uint4* wk = wts + (static_cast<int64_t>(ks) * NT) * 64 + lane;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const bf16x8 wf = __builtin_bit_cast(bf16x8, wk[nt * 64]);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) acc[nt][mt] = mfma16(wf, xf[mt], acc[nt][mt]);
+      }
+      cu += 4;
+      while (cu >= g.P) { cu -= g.P; ++tap; }
+    }
+  }
+  // epilogue: tile (nt, mt): rows = output channels cout0 + 16 nt + 4 lg + i, column = this lane's pixel of tile mt
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    const int32_t co = cout0 + 16 * nt + 4 * lg;
+    if (co >= a.Cout) continue;
+    float bv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bv[i] = co + i < a.Cout ? a.bias[co + i] : 0.f;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+      const int32_t t = t0 + prow[mt], x = x0 + pcol[mt];
+      if (prow[mt] >= g.rows_out || pcol[mt] >= g.cols_out || t >= a.Tout || x >= a.Xout) continue;
+      float v[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        v[i] = acc[nt][mt][i] + bv[i];
+        if (a.relu) v[i] = fmaxf(v[i], 0.f);
+      }
+      if (a.mode == 0) {
+        const uint2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) + ((b * a.Tout + t) * a.Xout + x) * a.Cout + co) = pk;
+      } else {
+        float* o = static_cast<float*>(a.out);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (co + i < a.Cout) o[((b * a.Cout + co + i) * a.Tout + t) * a.Xout + x] = v[i];
+      }
+    }
+  }
+}
+
+// log2 of virtual / stored size when that ratio is a power of two, else -1
+int32_t resize_shift(int32_t vsize, int32_t size) {
+  for (int32_t sh = 0; sh < 16; ++sh)
+    if ((static_cast<int64_t>(size) << sh) == vsize) return sh;
+  return -1;
+}
+
+// Geometry of the LDS-window kernel for one layer; false when the layer does not fit it (then the
+// direct kernels run).  The channel chunk is the largest divisor of Cin (in units of 8 channels)
+// whose halo and weights fit the LDS budget.
+constexpr size_t kConv3LdsBudget = 72 << 10;  // two blocks per CU overlap one block's staging with the other's products
+bool conv3_plan(const ConvArgs& a, Conv3Args* g, int32_t* nt_out, size_t* lds_out) {
+  if (a.taps != 9 || a.Cin % 8 != 0 || (a.mode != 0 && a.mode != 2)) return false;
+  if (a.mode == 0 && a.Cout % 4 != 0) return false;
+  const int32_t ts = resize_shift(a.Tv, a.Tin), xs = resize_shift(a.Xv, a.Xin);
+  if (ts < 0 || xs < 0) return false;
+  const int32_t slab = a.Cout < 128 ? a.Cout : 128;
+  const int32_t nt = (slab + 15) / 16;
+  int32_t cw_log = 6;
+  while (cw_log > 4 && (1 << (cw_log - 1)) >= a.Xout) --cw_log;
+  const int32_t rows_out = kConv3Waves * (64 >> cw_log), cols_out = 1 << cw_log;
+  const int32_t halo_rows = (rows_out - 1) * a.stride_t + 3, halo_cols = cols_out + 2;
+  const int32_t units = a.Cin / 8;
+  for (int32_t nchunk = 1; nchunk <= units; ++nchunk) {
+    if (units % nchunk != 0) continue;
+    const int32_t P = units / nchunk;
+    const int32_t px_units = P | 1;
+    const int32_t ksteps = (9 * P + 3) / 4;
+    const size_t lds = (static_cast<size_t>(halo_rows) * halo_cols * px_units + static_cast<size_t>(ksteps) * nt * 64) * 16;
+    if (lds > kConv3LdsBudget) continue;
+    int32_t pp_log = 0;
+    while ((1 << pp_log) < P) ++pp_log;
+    g->a = a; g->t_shift = ts; g->x_shift = xs; g->CK = 8 * P; g->nchunk = nchunk; g->P = P; g->pp_log = pp_log;
+    g->ksteps = ksteps; g->cw_log = cw_log; g->rows_out = rows_out; g->cols_out = cols_out;
+    g->halo_rows = halo_rows; g->halo_cols = halo_cols; g->px_units = px_units;
+    g->tiles_t = (a.Tout + rows_out - 1) / rows_out; g->tiles_x = (a.Xout + cols_out - 1) / cols_out;
+    *nt_out = nt; *lds_out = lds;
+    return true;
+  }
+  return false;
+}
+
+// a failed attribute call stays the runtime's last error, which the caller reports
+template <int NT>
+void launch_conv3(const Conv3Args& g, uint32_t slabs, size_t lds, hipStream_t st) {
+  if (lds > (64u << 10) &&
+      hipFuncSetAttribute(reinterpret_cast<const void*>(&dec_conv3_kernel<NT>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds)) != hipSuccess)
+    return;
+  const uint32_t blocks = static_cast<uint32_t>(g.a.B) * g.tiles_t * g.tiles_x;
+  hipLaunchKernelGGL(dec_conv3_kernel<NT>, dim3(blocks, slabs), dim3(64 * kConv3Waves), lds, st, g);
+}
+
 void launch_conv(const ConvArgs& a, hipStream_t st) {
   const int64_t npix = static_cast<int64_t>(a.B) * a.Tout * a.Xout;
+  Conv3Args g{};
+  int32_t nt = 0;
+  size_t lds = 0;
+  if (conv3_plan(a, &g, &nt, &lds)) {
+    const uint32_t slabs3 = static_cast<uint32_t>((a.Cout + 16 * nt - 1) / (16 * nt));
+    switch (nt) {
+      case 1: launch_conv3<1>(g, slabs3, lds, st); break;
+      case 2: launch_conv3<2>(g, slabs3, lds, st); break;
+      case 3: launch_conv3<3>(g, slabs3, lds, st); break;
+      case 4: launch_conv3<4>(g, slabs3, lds, st); break;
+      case 5: launch_conv3<5>(g, slabs3, lds, st); break;
+      case 6: launch_conv3<6>(g, slabs3, lds, st); break;
+      case 7: launch_conv3<7>(g, slabs3, lds, st); break;
+      default: launch_conv3<8>(g, slabs3, lds, st); break;
+    }
+    return;
+  }
   const uint32_t slabs = static_cast<uint32_t>((a.Cout + 127) / 128);
   if (a.Cout >= 96 && a.taps * a.Cin >= 512) {
     hipLaunchKernelGGL(dec_conv_lds_kernel, dim3(static_cast<uint32_t>((npix + 255) / 256), slabs), dim3(256), 0, st, a);
