@@ -892,6 +892,110 @@ __global__ __launch_bounds__(64 * kConv3Waves) void dec_conv3_kernel(Conv3Args g
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Linear layers (one tap) on rows of at most 256 inputs: the block parks the weights of its slab of
+// up to 128 output channels in LDS (operand-fragment order) and walks tiles of 32 rows; a wave
+// requests the operand fragments of its next tile (every step of the contraction) before it
+// multiplies the current one, so the row reads, which bound these layers, overlap the products.
+// ------------------------------------------------------------------------------------------
+constexpr int kLinSteps = 8;  // contraction steps of 32 a row may have (Cin <= 256)
+
+__global__ __launch_bounds__(256) void dec_linear_kernel(ConvArgs a, int32_t tiles_per_wave) {
+  extern __shared__ __attribute__((aligned(16))) uint4 wlin[];  // [kstep][8][64]
+  const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int64_t nrows = static_cast<int64_t>(a.B) * a.Tout * a.Xout;
+  const int32_t cout0 = blockIdx.y * 128;
+  const int32_t ntiles_c = min(8, (a.Cout - cout0 + 15) / 16);
+  const int32_t ksteps = (a.Cin + 31) / 32;
+  for (int32_t id = tid; id < ksteps * 8 * 64; id += 256) {
+    const int32_t fl = id & 63, nt = (id >> 6) & 7, ks = id >> 9;
+    const int32_t co = cout0 + 16 * nt + (fl & 15), k0 = 32 * ks + 8 * (fl >> 4);
+    uint4 v = make_uint4(0u, 0u, 0u, 0u);
+    if (co < a.Cout && k0 < a.Cin) v = *reinterpret_cast<const uint4*>(a.w + static_cast<int64_t>(co) * a.Cin + k0);
+    wlin[id] = v;
+  }
+  __syncthreads();
+  const int64_t ntile = (nrows + 31) / 32;
+  const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + wid;
+  int64_t tile = wave * tiles_per_wave;
+  const int64_t tile_end = min(ntile, tile + tiles_per_wave);
+  bf16x8 nx[kLinSteps][2];
+  auto request = [&](int64_t tl) {
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+      int64_t r = min(tl * 32 + 16 * mt + lr, nrows - 1);
+      if (a.mode == 1) {
+        // walk the rows (b h, t) as (b, t, h), heads fastest: the lanes of a wave then write next to
+        // each other in the channels-last image
+        const int64_t q = r / a.H, h = r - q * a.H, b = q / a.T, t = q - b * a.T;
+        r = (b * a.H + h) * a.T + t;
+      }
+      const uint16_t* row = a.in + r * a.Cin + 8 * lg;
+#pragma unroll
+      for (int ks = 0; ks < kLinSteps; ++ks)
+        if (ks < ksteps) nx[ks][mt] = (32 * ks + 8 * lg < a.Cin) ? load8(row + 32 * ks) : zero8();
+    }
+  };
+  if (tile < tile_end) request(tile);
+  for (; tile < tile_end; ++tile) {
+    bf16x8 xf[kLinSteps][2];
+#pragma unroll
+    for (int ks = 0; ks < kLinSteps; ++ks) { xf[ks][0] = nx[ks][0]; xf[ks][1] = nx[ks][1]; }
+    if (tile + 1 < tile_end) request(tile + 1);
+    floatx4 acc[8][2];
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) acc[nt][0] = acc[nt][1] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ks = 0; ks < kLinSteps; ++ks) {
+      if (ks < ksteps) {
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt) {
+          if (nt < ntiles_c) {
+            const bf16x8 wf = __builtin_bit_cast(bf16x8, wlin[(ks * 8 + nt) * 64 + lane]);
+            acc[nt][0] = mfma16(wf, xf[ks][0], acc[nt][0]);
+            acc[nt][1] = mfma16(wf, xf[ks][1], acc[nt][1]);
+          }
+        }
+      }
+    }
+    // epilogue: tile (nt, mt): rows = output channels cout0 + 16 nt + 4 lg + i, column = row lr of tile mt
+#pragma unroll
+    for (int nt = 0; nt < 8; ++nt) {
+      if (nt >= ntiles_c) continue;
+      const int32_t co = cout0 + 16 * nt + 4 * lg;
+      if (co >= a.Cout) continue;
+      float bv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) bv[i] = co + i < a.Cout ? a.bias[co + i] : 0.f;
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        const int64_t pp = tile * 32 + 16 * mt + lr;
+        if (pp >= nrows) continue;
+        float v[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          v[i] = acc[nt][mt][i] + bv[i];
+          if (a.relu) v[i] = fmaxf(v[i], 0.f);
+        }
+        uint2 pk = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        if (a.mode == 0) {
+          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) + pp * a.Cout + co) = pk;
+        } else {
+          // row pp = (b, t, h); outputs co .. co + 3 = compressed column co / 4, extra channels 0..3
+          const int64_t q = pp / a.H;
+          const int32_t h = static_cast<int32_t>(pp - q * a.H);
+          const int32_t b = static_cast<int32_t>(q / a.T), t = static_cast<int32_t>(q - static_cast<int64_t>(b) * a.T);
+          const int32_t len = a.seq_len ? min(max(a.seq_len[b], 0), a.T) : a.T;
+          if (t >= len) pk = make_uint2(0u, 0u);
+          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) +
+                                    ((static_cast<int64_t>(b) * a.T + t) * a.Wd + (co >> 2)) * a.C + h * kCh) = pk;
+        }
+      }
+    }
+  }
+}
+
 // log2 of virtual / stored size when that ratio is a power of two, else -1
 int32_t resize_shift(int32_t vsize, int32_t size) {
   for (int32_t sh = 0; sh < 16; ++sh)
@@ -947,6 +1051,16 @@ void launch_conv3(const Conv3Args& g, uint32_t slabs, size_t lds, hipStream_t st
 
 void launch_conv(const ConvArgs& a, hipStream_t st) {
   const int64_t npix = static_cast<int64_t>(a.B) * a.Tout * a.Xout;
+  if (a.taps == 1 && a.Cin % 8 == 0 && a.Cin <= 32 * kLinSteps && a.Cout % 4 == 0 && (a.mode == 0 || a.mode == 1)) {
+    // tiles per wave: whole numbers, about eight waves per CU
+    const int64_t ntile = (npix + 31) / 32;
+    const int32_t per_wave = static_cast<int32_t>((ntile + 2047) / 2048);
+    const int64_t waves = (ntile + per_wave - 1) / per_wave;
+    const size_t lds = static_cast<size_t>((a.Cin + 31) / 32) * 8 * 1024;
+    hipLaunchKernelGGL(dec_linear_kernel, dim3(static_cast<uint32_t>((waves + 3) / 4), static_cast<uint32_t>((a.Cout + 127) / 128)),
+                       dim3(256), lds, st, a, per_wave);
+    return;
+  }
   Conv3Args g{};
   int32_t nt = 0;
   size_t lds = 0;
