@@ -33,6 +33,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kCs = 2;       // width reduction of the CNN's hidden image (c_s)
 constexpr int kCh = 4;       // channel expansion (c_h)
+constexpr int kTRow = 72;      // halfwords per LDS row of the transposed 64-token tile (16-byte aligned rows)
 constexpr int kValCols = 144;  // [V_I (64); V (64); 1; 15 unused]: nine 16-column slices
 
 __device__ __forceinline__ floatx4 mfma16(bf16x8 a, bf16x8 b, floatx4 c) {
@@ -130,9 +131,11 @@ __global__ __launch_bounds__(256) void dec_features_kernel(Shape s, int32_t Tp, 
     return;
   }
   // keys: natural and transposed copies; positions past the sequence end (and the padding up to Tp)
-  // hold zeros, so they drop out of every sum over keys
+  // hold zeros, so they drop out of every sum over keys.  The transposed copies (phi(K)^T and V^T,
+  // 64 tokens = 128 bytes per row and block) are gathered in LDS and leave as whole lines.
+  __shared__ __attribute__((aligned(16))) uint16_t tT[(256 + kHeadDim) * kTRow];
+  const int tcol = wid * 16 + lr;  // this lane's token inside the block's 64
   uint16_t* out = phiK + (head * s.T + tc) * s.m;
-  uint16_t* outT = phiKT + head * static_cast<int64_t>(s.m) * Tp + t;
   for (int ft = 0; ft < ftiles; ++ft) {
     const uint16_t* w = W + (ft * 16 + lr) * kHeadDim;
     floatx4 acc = {0.f, 0.f, 0.f, 0.f};
@@ -148,19 +151,28 @@ __global__ __launch_bounds__(256) void dec_features_kernel(Shape s, int32_t Tp, 
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const uint32_t word = i < 2 ? pk.x : pk.y;
-      outT[static_cast<int64_t>(ft * 16 + 4 * lg + i) * Tp] = static_cast<uint16_t>((i & 1) ? (word >> 16) : (word & 0xffffu));
+      tT[(ft * 16 + 4 * lg + i) * kTRow + tcol] = static_cast<uint16_t>((i & 1) ? (word >> 16) : (word & 0xffffu));
     }
   }
   // V^T: this lane moves dims 16 lg .. + 15 of row t
   const uint16_t* vrow = V + (head * s.T + tc) * kHeadDim + 16 * lg;
   const uint4 va = *reinterpret_cast<const uint4*>(vrow), vb = *reinterpret_cast<const uint4*>(vrow + 8);
   const uint32_t words[8] = {va.x, va.y, va.z, va.w, vb.x, vb.y, vb.z, vb.w};
-  uint16_t* vt = Vt + (head * kHeadDim + 16 * lg) * static_cast<int64_t>(Tp) + t;
 #pragma unroll
   for (int e = 0; e < 16; ++e) {
     const uint32_t word = words[e >> 1];
     const uint16_t val = static_cast<uint16_t>((e & 1) ? (word >> 16) : (word & 0xffffu));
-    vt[static_cast<int64_t>(e) * Tp] = t < s.T ? val : static_cast<uint16_t>(0);
+    tT[(s.m + 16 * lg + e) * kTRow + tcol] = t < s.T ? val : static_cast<uint16_t>(0);
+  }
+  __syncthreads();
+  const int32_t blk_t0 = static_cast<int32_t>(bid % tiles) * 64;
+  uint16_t* kt_base = phiKT + head * static_cast<int64_t>(s.m) * Tp + blk_t0;
+  uint16_t* vt_base = Vt + head * static_cast<int64_t>(kHeadDim) * Tp + blk_t0;
+  for (int x = threadIdx.x; x < (s.m + kHeadDim) * 8; x += 256) {
+    const int row = x >> 3, piece = x & 7;
+    const uint4 v = *reinterpret_cast<const uint4*>(&tT[row * kTRow + 8 * piece]);
+    uint16_t* dst = row < s.m ? kt_base + static_cast<int64_t>(row) * Tp : vt_base + static_cast<int64_t>(row - s.m) * Tp;
+    *reinterpret_cast<uint4*>(dst + 8 * piece) = v;
   }
 }
 
