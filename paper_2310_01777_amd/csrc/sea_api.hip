@@ -124,6 +124,12 @@ bool scores_stay_on_chip(const sea_params* p, const Shape& s) {
 // Scratch of the whole forward pass: estimator scratch, A_hat, then either the tiled path's mask
 // bits and bucket tables or the row-list path's idx + cnt.  `lean`: the caller keeps no
 // intermediate, so the A_hat part is dropped where the scores stay on chip.
+// per-row width geometry, bf16, sequences short enough for a block's per-key mask words to fit LDS:
+// the selection is expanded to one bit per key and the tiled attention kernel runs on those
+bool keybit_path(const Shape& s, sea_dtype dt) {
+  return s.geometry == 1 && keybits_supported(s) && tile_attn_keybits_supported(s, dt);
+}
+
 size_t forward_ws(const sea_params* p, bool lean) {
   const size_t rows = static_cast<size_t>(p->B) * p->H * p->T;
   const Shape s = make_shape(p, true);
@@ -134,6 +140,9 @@ size_t forward_ws(const sea_params* p, bool lean) {
     bytes += align256(tile_attn_workspace(s));
   } else if (p->dtype == SEA_F32 && tile_attn_f32_supported(s)) {
     bytes += align256(rows * ((p->K + 31) / 32) * sizeof(uint32_t));
+  } else if (keybit_path(s, p->dtype)) {
+    bytes += align256(rows * ((p->K + 31) / 32) * sizeof(uint32_t));
+    bytes += align256(keybits_bytes(s));
   } else {
     bytes += align256(rows * static_cast<size_t>(row_stride_of(p)) * sizeof(int32_t));
     bytes += align256(rows * sizeof(int32_t));
@@ -384,6 +393,18 @@ int forward_stages(const sea_params* p, const void* Q, const void* K, const void
     if (e != hipSuccess) return fail_hip(e);
     e = launch_tile_attn_f32(s, static_cast<const float*>(Q), static_cast<const float*>(K),
                              static_cast<const float*>(V), mbits, static_cast<float*>(O), st);
+    return e == hipSuccess ? SEA_OK : fail_hip(e);
+  }
+  if (keybit_path(s, p->dtype)) {
+    uint32_t* mbits = mhat_opt ? mhat_opt : reinterpret_cast<uint32_t*>(w);
+    w += align256(rows * ((s.K + 31) / 32) * sizeof(uint32_t));
+    uint32_t* kb = reinterpret_cast<uint32_t*>(w);
+    e = launch_topk_mask(s, A_hat, sel_opt, idx_opt, cnt_opt, mbits, st);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_keybits(s, mbits, kb, st);
+    if (e != hipSuccess) return fail_hip(e);
+    e = launch_tile_attn_keybits(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                                 static_cast<const uint16_t*>(V), kb, static_cast<uint16_t*>(O), st);
     return e == hipSuccess ? SEA_OK : fail_hip(e);
   }
   int32_t* idx = idx_opt ? idx_opt : reinterpret_cast<int32_t*>(w);

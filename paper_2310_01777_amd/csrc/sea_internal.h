@@ -58,6 +58,14 @@ hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, in
 // Tiled MFMA attention over the column-structured mask (bf16, K | T, power-of-two keys per column)
 bool tile_attn_supported(const Shape& s, sea_dtype dt, int32_t* rlog_out);
 size_t tile_attn_workspace(const Shape& s);
+// a row's selection expanded to one bit per key ([N][T][ceil(T / 32)] words), for masks whose
+// columns differ from row to row; the tiled attention then runs with keys as "columns"
+bool keybits_supported(const Shape& s);
+size_t keybits_bytes(const Shape& s);
+hipError_t launch_keybits(const Shape& s, const uint32_t* mbits, uint32_t* kb, hipStream_t st);
+bool tile_attn_keybits_supported(const Shape& s, sea_dtype dt);
+hipError_t launch_tile_attn_keybits(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
+                                    const uint32_t* kb, uint16_t* O, hipStream_t st);
 // fp32 tensors: tiled attention on the fp64 / fp32 matrix cores from per-row column bits
 bool tile_attn_f32_supported(const Shape& s);
 hipError_t launch_tile_attn_f32(const Shape& s, const float* Q, const float* K, const float* V,

@@ -951,6 +951,34 @@ hipError_t launch_tile_attn_f32(const Shape& s, const float* Q, const float* K, 
   return hipGetLastError();
 }
 
+// Masks without column structure shared by the rows (per-row width geometry): the selection
+// arrives as one bit per (row, key), and the same kernel runs with every key its own "column"
+// (one key per column, column width 1) -- the walk of the dense kernel with per-key mask bits.
+// The block's mask words (128 rows x ceil(T / 32)) must fit LDS beside the staging buffers.
+bool tile_attn_keybits_supported(const Shape& s, sea_dtype dt) {
+  return dt == SEA_BF16 && s.T <= 4096 && s.T <= (1 << 24);
+}
+
+hipError_t launch_tile_attn_keybits(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
+                                    const uint32_t* kb, uint16_t* O, hipStream_t st) {
+  if (!tile_attn_keybits_supported(s, SEA_BF16)) return hipErrorNotSupported;
+  StageScope scope(SEA_STAGE_SPARSE, st);
+  TileArgs a{};
+  a.Q = Q; a.K = K; a.V = V; a.mbits = kb; a.O = O; a.seq_len = s.seq_len;
+  a.N = s.N; a.H = s.H; a.T = s.T; a.U = s.T; a.KW = (s.T + 31) / 32; a.rlog = 0; a.w = 1; a.causal = s.causal;
+  a.group_heads = group_heads_for(s.N, s.T);
+  a.c = s.scale * kLog2e;
+  const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 127) / 128)), block(256);
+  const size_t shm = static_cast<size_t>(128) * (a.KW + 1) * sizeof(uint32_t);
+  if (shm > (64u << 10)) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tile_attn_kernel<0, 0>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shm));
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL((tile_attn_kernel<0, 0>), grid, block, shm, st, a);
+  return hipGetLastError();
+}
+
 size_t dense_attn_workspace(const Shape&) { return 0; }
 
 hipError_t launch_dense_attn(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* V,

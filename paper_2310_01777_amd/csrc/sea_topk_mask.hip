@@ -446,7 +446,74 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// The selection of a row, expanded to one bit per key (Sec. 3.1 "Linear Sparse Attention Mask
+// Generation", with App. A.4's per-row widths when geometry = 1; App. A.5.3 for the replication
+// cap): bit j of row t is set iff key j belongs to a selected column of that row and is one of the
+// r = min(w, cap) keys start + floor(i w / r) the column emits, j <= t (causal) and j < seq_len.
+// One wavefront per row: lanes walk the K column bits, a selected column ORs its keys into the
+// row's words in LDS, the words leave as one coalesced run.  kb: [N][T][KWk], KWk = ceil(T / 32).
+// ------------------------------------------------------------------------------------------
+constexpr int kKeyBitWordsMax = 128;  // T <= 4096
+
+__global__ __launch_bounds__(kWavesPerBlock* kWave) void keybits_kernel(Shape s, const uint32_t* __restrict__ mbits,
+                                                                       uint32_t* __restrict__ kb, int32_t KWk) {
+  __shared__ uint32_t words[kWavesPerBlock][kKeyBitWordsMax];
+  const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t row = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wid;
+  const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
+  if (row >= nrows) return;  // whole wave leaves; only wave-level barriers below
+  const int32_t t = static_cast<int32_t>(row % s.T);
+  const int32_t b = static_cast<int32_t>((row / s.T) / s.H);
+  const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
+  const int32_t kw = (s.K + 31) / 32;
+  for (int32_t x = lane; x < KWk; x += kWave) words[wid][x] = 0u;
+  __builtin_amdgcn_wave_barrier();
+  if (t < len) {
+    const int32_t jmax = (s.causal && t < len - 1) ? t : len - 1;
+    const int32_t Tw = s.geometry == 1 ? t + 1 : s.T;
+    const uint32_t* mrow = mbits + row * kw;
+    for (int32_t c = lane; c < s.K; c += kWave) {
+      if (((mrow[c >> 5] >> (c & 31)) & 1u) == 0u) continue;
+      const int32_t s0 = block_start(c, Tw, s.K);
+      const int32_t w = block_start(c + 1, Tw, s.K) - s0;
+      if (w <= 0) continue;
+      const int32_t r = min(w, s.rep_cap);
+      if (r == w) {
+        // the whole column: keys s0 .. min(s0 + w - 1, jmax)
+        const int32_t j1 = min(s0 + w - 1, jmax);
+        if (s0 > j1) continue;
+        for (int32_t wd = s0 >> 5; wd <= (j1 >> 5); ++wd) {
+          const int32_t lo = max(s0, wd << 5) & 31, hi = min(j1, (wd << 5) + 31) & 31;
+          const uint32_t m = (hi == 31 ? 0xffffffffu : ((1u << (hi + 1)) - 1u)) & ~((1u << lo) - 1u);
+          atomicOr(&words[wid][wd], m);
+        }
+      } else {
+        for (int32_t i = 0; i < r; ++i) {
+          const int32_t j = s0 + static_cast<int32_t>((static_cast<int64_t>(i) * w) / r);
+          if (j <= jmax) atomicOr(&words[wid][j >> 5], 1u << (j & 31));
+        }
+      }
+    }
+  }
+  __builtin_amdgcn_wave_barrier();
+  for (int32_t x = lane; x < KWk; x += kWave) kb[row * KWk + x] = words[wid][x];
+}
+
 }  // namespace
+
+bool keybits_supported(const Shape& s) { return (s.T + 31) / 32 <= kKeyBitWordsMax; }
+size_t keybits_bytes(const Shape& s) {
+  return static_cast<size_t>(s.N) * s.T * static_cast<size_t>((s.T + 31) / 32) * sizeof(uint32_t);
+}
+hipError_t launch_keybits(const Shape& s, const uint32_t* mbits, uint32_t* kb, hipStream_t st) {
+  if (!keybits_supported(s)) return hipErrorNotSupported;
+  const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
+  const uint32_t grid = static_cast<uint32_t>((nrows + kWavesPerBlock - 1) / kWavesPerBlock);
+  StageScope scope(SEA_STAGE_TOPK_MASK, st);
+  hipLaunchKernelGGL(keybits_kernel, dim3(grid), dim3(kWavesPerBlock * kWave), 0, st, s, mbits, kb, (s.T + 31) / 32);
+  return hipGetLastError();
+}
 
 hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, int32_t* idx,
                             int32_t* cnt, uint32_t* mbits, hipStream_t st) {
