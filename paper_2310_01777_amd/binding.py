@@ -401,7 +401,7 @@ def sea_profile_collect():
 
 
 def sea_attention_path(p: "SeaParams") -> int:
-    """1 = tiled matrix-core attention (bf16), 2 = its fp32 counterpart, 0 = per-row index lists, negative = rejected parameters."""
+    """1 = tiled matrix-core attention (bf16), 2 = its fp32 counterpart, 3 = tiled on per-key bits (row-width geometry), 0 = per-row index lists, negative = rejected parameters."""
     cp = p.c()
     return int(_lib.sea_attention_path(ctypes.byref(cp)))
 

@@ -653,7 +653,8 @@ int sea_attention_path(const sea_params* p) {
   if (rc != SEA_OK) return rc;
   const Shape s = make_shape(p, true);
   if (tile_attn_supported(s, p->dtype, nullptr)) return 1;
-  return (p->dtype == SEA_F32 && tile_attn_f32_supported(s)) ? 2 : 0;
+  if (p->dtype == SEA_F32 && tile_attn_f32_supported(s)) return 2;
+  return keybit_path(s, p->dtype) ? 3 : 0;
 }
 
 const char* sea_version(void) { return "sea-hip 0.1 (gfx950)"; }
