@@ -148,6 +148,18 @@ int sea_sparse_attn(const sea_params* p, const void* Q, const void* K, const voi
                     void* hip_stream);
 
 /*
+ * Sec. 3.1 "Linear Sparse Attention Mask Generation" (App. A.4 for geometry = 1, App. A.5.3 for the
+ * replication cap): the expanded mask M* as one bit per (row, key), from the compressed binary mask
+ * M^ (mhat: [B][H][T][ceil(K / 32)] device words, bit c % 32 of word c / 32 = column c, as
+ * sea_forward writes to mhat_opt).  Bit j % 32 of word j / 32 of row t of key_bits
+ * ([B][H][T][ceil(T / 32)] device words) is set iff key j is one of the r = min(w, cap) keys
+ * start + floor(i w / r) of a selected column of that row, j <= t when causal, j < seq_len; rows
+ * t >= seq_len are zero.  This is the mask sea_forward's attention stage consumes when
+ * sea_attention_path(p) == 3.  Needs T <= 4096 (SEA_ENOTSUP otherwise); no workspace.
+ */
+int sea_key_mask(const sea_params* p, const uint32_t* mhat, uint32_t* key_bits, void* hip_stream);
+
+/*
  * Sec. 3.1.1 "FlatCSR" and App. A.5 "FlatCSR: Modified CSR Format To Handle Grouped Mask": the
  * expanded mask M* [B][H][T][T] with the head and query axes exchanged and (head, key) flattened
  * into one column axis, stored as CSR, so that one time step -- the group of the causal-per-batch

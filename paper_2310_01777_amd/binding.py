@@ -85,6 +85,7 @@ def _load() -> ctypes.CDLL:
     lib.sea_flatcsr.restype = ctypes.c_int
     lib.sea_flatcsr.argtypes = [P, vp, vp, ctypes.c_int32, vp, vp, ctypes.c_int64, vp, sz, vp]
     lib.sea_flatcsr_attn.restype, lib.sea_flatcsr_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, vp, vp]
+    lib.sea_key_mask.restype, lib.sea_key_mask.argtypes = ctypes.c_int, [P, vp, vp, vp]
     lib.sea_mask_attn_workspace_bytes.restype, lib.sea_mask_attn_workspace_bytes.argtypes = sz, [P]
     lib.sea_mask_attn.restype, lib.sea_mask_attn.argtypes = ctypes.c_int, [P, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.sea_version.restype, lib.sea_version.argtypes = ctypes.c_char_p, []
@@ -237,6 +238,15 @@ def sea_flatcsr_attn(p: SeaParams, Q, K, V, crow, col, O, stream=None):
                                  _ptr(col, torch.int32, None, "col"),
                                  _ptr(O, p.torch_dtype, n * p.d, "O"), _stream(stream)),
            "sea_flatcsr_attn")
+
+
+def sea_key_mask(p: SeaParams, mhat, key_bits, stream=None):
+    """mhat [B, H, T, ceil(K/32)] int32 -> key_bits [B, H, T, ceil(T/32)] int32 (one bit per key)."""
+    n = p.B * p.H * p.T
+    cp = p.c()
+    _check(_lib.sea_key_mask(ctypes.byref(cp), _ptr(mhat, torch.int32, n * ((p.K + 31) // 32), "mhat"),
+                             _ptr(key_bits, torch.int32, n * ((p.T + 31) // 32), "key_bits"), _stream(stream)),
+           "sea_key_mask")
 
 
 def sea_mask_attn_workspace_bytes(p: SeaParams) -> int:

@@ -299,6 +299,17 @@ int sea_flatcsr(const sea_params* p, const int32_t* idx, const int32_t* cnt, int
   return e == hipSuccess ? SEA_OK : fail_hip(e);
 }
 
+int sea_key_mask(const sea_params* p, const uint32_t* mhat, uint32_t* key_bits, void* hip_stream) {
+  int rc = check_common(p);
+  if (rc == SEA_OK) rc = check_mask_params(p);
+  if (rc != SEA_OK) return rc;
+  if (!mhat || !key_bits) return SEA_EINVAL;
+  const Shape s = make_shape(p, true);
+  if (!keybits_supported(s)) return SEA_ENOTSUP;
+  const hipError_t e = launch_keybits(s, mhat, key_bits, static_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SEA_OK : fail_hip(e);
+}
+
 int sea_flatcsr_attn(const sea_params* p, const void* Q, const void* K, const void* V, const int64_t* crow,
                      const int32_t* col, void* O, void* hip_stream) {
   const int rc = check_common(p);

@@ -642,6 +642,46 @@ def test_row_width_geometry(sea, wl):
     print(f"    rows differing at near-ties: {(~same).sum()} / {same.size}", flush=True)
 
 
+KEY_MASK_CASES = [w for w in ROW_WIDTH_CASES[:13] if w.T <= 1200] + [
+    _wl("km_fixed_budget", 2, 2, 512, 64, 32, 5, k_budget=12),                 # fixed buckets, 2 of 16 keys a column
+    _wl("km_fixed_ragged_pad", 1, 3, 300, 64, 17, 4, causal=False, pad_frac=0.3),
+    _wl("km_words_edge", 1, 1, 4096, 64, 128, 9, geometry=1),                  # the longest supported rows
+]
+
+
+@pytest.mark.parametrize("wl", KEY_MASK_CASES, ids=lambda w: w.name)
+def test_key_mask_bits(sea, wl):
+    """Sec. 3.1 "Linear Sparse Attention Mask Generation": the per-(row, key) bits sea_key_mask expands
+    from the selection a forward pass made are exactly the keys the oracle's expansion lists for
+    that selection (both geometries, replication cap, padding, rows shorter than K)."""
+    x = synth.make_inputs(wl)
+    p, xd, g = _gpu_forward(sea, wl, x)
+    kwk = (wl.T + 31) // 32
+    kb = torch.empty(wl.B, wl.H, wl.T, kwk, dtype=torch.int32, device="cuda")
+    sea.sea_key_mask(p, g["mhat"].cuda(), kb)
+    torch.cuda.synchronize()
+    bits = _unpack_mhat(kb.cpu().numpy(), wl.T)                                   # [B, H, T, T] bool
+    po = oracle_params(wl)
+    sl = None if x["seq_len"] is None else x["seq_len"].numpy()
+    A_g = g["A_hat"].numpy().astype(np.float64)
+    sel_s, idx_s, cnt_s = oracle.topk_mask(po, A_g, seq_len=sl)
+    assert np.array_equal(g["sel"].numpy(), sel_s)                               # same selection first
+    want = np.zeros(bits.shape[:-1] + (wl.T + 1,), dtype=bool)
+    np.put_along_axis(want, np.where(idx_s >= 0, idx_s, wl.T), True, axis=-1)
+    want = want[..., :wl.T]
+    assert want.sum() == cnt_s.sum()
+    assert np.array_equal(bits, want)
+
+
+def test_key_mask_rejects_long_rows(sea):
+    p = sea.SeaParams(B=1, H=1, T=8192, d=64, m=64, K=64, k_hat=4, causal=True, scale=0.125, dtype="bf16", geometry=1)
+    mh = torch.zeros(1, 1, 8192, 2, dtype=torch.int32, device="cuda")
+    kb = torch.zeros(1, 1, 8192, 256, dtype=torch.int32, device="cuda")
+    with pytest.raises(sea.SeaError) as e:
+        sea.sea_key_mask(p, mh, kb)
+    assert e.value.status == sea.SEA_ENOTSUP
+
+
 @pytest.mark.parametrize("case", [(2, 3, 300, 17, 5, 0, True, "bf16", 0), (2, 4, 512, 32, 3, 12, True, "bf16", 1),
                                   (1, 2, 130, 24, 24, 0, False, "f32", 0), (3, 5, 1030, 64, 2, 16, True, "f32", 1),
                                   (1, 12, 2048, 128, 4, 64, True, "bf16", 1)])
