@@ -53,9 +53,16 @@ __device__ __forceinline__ double exp_f64(double x) {
 // NFT > 0: the exponent arguments of the (at most NFT) feature tiles stay in registers between the
 // projection and the exponential, and the unrolled tile loop lets the loads of W run ahead;
 // NFT = 0: any m, the arguments take a round trip through the output buffer.
-template <int NFT>
-__global__ __launch_bounds__(256) void features_f64_kernel(Shape s, const float* __restrict__ Q,
-                                                           const float* __restrict__ K, const float* __restrict__ W,
+// four consecutive elements of an fp32 or bf16 tensor
+__device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 load4(const uint16_t* p) {
+  const uint2 u = *reinterpret_cast<const uint2*>(p);
+  return make_float4(bf16lo_to_f32(u.x), bf16hi_to_f32(u.x), bf16lo_to_f32(u.y), bf16hi_to_f32(u.y));
+}
+
+template <int NFT, typename TI>
+__global__ __launch_bounds__(256) void features_f64_kernel(Shape s, const TI* __restrict__ Q,
+                                                           const TI* __restrict__ K, const TI* __restrict__ W,
                                                            double* __restrict__ phiQ, double* __restrict__ phiK) {
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int lr = lane & 15, lg = lane >> 4;
@@ -69,13 +76,13 @@ __global__ __launch_bounds__(256) void features_f64_kernel(Shape s, const float*
   const int32_t r0 = static_cast<int32_t>(wv % tiles) * 16;
   const int32_t b = static_cast<int32_t>(head / s.H);
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
-  const float* X = (which ? K : Q) + (head * s.T + min(r0 + lr, s.T - 1)) * kHeadDim + 16 * lg;
+  const TI* X = (which ? K : Q) + (head * s.T + min(r0 + lr, s.T - 1)) * kHeadDim + 16 * lg;
   const double rs = sqrt(static_cast<double>(s.scale));
   double xa[16];
   double nx = 0.0;
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
-    const float4 v = *reinterpret_cast<const float4*>(X + 4 * q);
+    const float4 v = load4(X + 4 * q);
     xa[4 * q] = rs * v.x; xa[4 * q + 1] = rs * v.y; xa[4 * q + 2] = rs * v.z; xa[4 * q + 3] = rs * v.w;
   }
 #pragma unroll
@@ -90,10 +97,10 @@ __global__ __launch_bounds__(256) void features_f64_kernel(Shape s, const float*
   double amax[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
   const int ntiles = s.m / 16;
   auto project = [&](int ft) {
-    const float* w = W + static_cast<int64_t>(ft * 16 + lr) * kHeadDim + 16 * lg;
+    const TI* w = W + static_cast<int64_t>(ft * 16 + lr) * kHeadDim + 16 * lg;
     float4 wv[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) wv[q] = *reinterpret_cast<const float4*>(w + 4 * q);
+    for (int q = 0; q < 4; ++q) wv[q] = load4(w + 4 * q);
     doublex4 acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -353,7 +360,33 @@ __global__ __launch_bounds__(256) void contract_f64_kernel(Shape s, const double
   }
 }
 
+template <typename TI>
+void launch_features_f64_t(const Shape& s, const TI* Q, const TI* K, const TI* W, double* phiQ, double* phiK,
+                           hipStream_t st) {
+  const int64_t waves = 2 * static_cast<int64_t>(s.N) * ((s.T + 15) / 16);
+  const dim3 grid(static_cast<uint32_t>((waves + 3) / 4));
+  if (s.m <= 128)
+    hipLaunchKernelGGL((features_f64_kernel<8, TI>), grid, dim3(256), 0, st, s, Q, K, W, phiQ, phiK);
+  else if (s.m <= 256)
+    hipLaunchKernelGGL((features_f64_kernel<16, TI>), grid, dim3(256), 0, st, s, Q, K, W, phiQ, phiK);
+  else
+    hipLaunchKernelGGL((features_f64_kernel<0, TI>), grid, dim3(256), 0, st, s, Q, K, W, phiQ, phiK);
+}
+
 }  // namespace
+
+// phi(Q) (row-shifted) and phi(K) (zero past seq_len) in fp64, [N][T][m] each, from fp32 or bf16 tensors
+hipError_t launch_features_f64(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* W,
+                               double* phiQ, double* phiK, hipStream_t st) {
+  if (s.m % 16 != 0) return hipErrorNotSupported;
+  if (dt == SEA_BF16)
+    launch_features_f64_t(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                          static_cast<const uint16_t*>(W), phiQ, phiK, st);
+  else
+    launch_features_f64_t(s, static_cast<const float*>(Q), static_cast<const float*>(K),
+                          static_cast<const float*>(W), phiQ, phiK, st);
+  return hipGetLastError();
+}
 
 size_t estimate_f64_workspace(const Shape& s) {
   const size_t ntm = static_cast<size_t>(s.N) * s.T * s.m;
@@ -369,14 +402,7 @@ hipError_t launch_estimate_f64(const Shape& s, const float* Q, const float* K, c
   double* stateT = phiK + ntm;
   {
     StageScope scope(SEA_STAGE_FEATURES, st);
-    const int64_t waves = 2 * static_cast<int64_t>(s.N) * ((s.T + 15) / 16);
-    const dim3 grid(static_cast<uint32_t>((waves + 3) / 4));
-    if (s.m <= 128)
-      hipLaunchKernelGGL(features_f64_kernel<8>, grid, dim3(256), 0, st, s, Q, K, W, phiQ, phiK);
-    else if (s.m <= 256)
-      hipLaunchKernelGGL(features_f64_kernel<16>, grid, dim3(256), 0, st, s, Q, K, W, phiQ, phiK);
-    else
-      hipLaunchKernelGGL(features_f64_kernel<0>, grid, dim3(256), 0, st, s, Q, K, W, phiQ, phiK);
+    launch_features_f64_t(s, Q, K, W, phiQ, phiK, st);
   }
   {
     StageScope scope(SEA_STAGE_STATE, st);

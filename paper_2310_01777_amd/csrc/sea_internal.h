@@ -33,6 +33,8 @@ struct Shape {
 hipError_t launch_estimate_f64(const Shape& s, const float* Q, const float* K, const float* W,
                                float* A_hat, void* ws, hipStream_t st);
 size_t estimate_f64_workspace(const Shape& s);
+hipError_t launch_features_f64(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* W,
+                               double* phiQ, double* phiK, hipStream_t st);
 
 hipError_t launch_estimate_bf16(const Shape& s, const uint16_t* Q, const uint16_t* K,
                                 const uint16_t* W, float* A_hat, void* ws, hipStream_t st);

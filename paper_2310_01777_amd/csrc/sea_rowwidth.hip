@@ -285,6 +285,112 @@ __global__ __launch_bounds__(kRowWaves* kWave) void rows_kernel(Shape s, const T
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// The same estimate without prefixes: A^[t][c] is the sum of a_tj = phi(q_t) . phi(k_j) over the keys
+// j of row t's column c, and the a_tj of 16 rows x 16 keys are one tile of phi(K) phi(Q)^T on the
+// fp64 matrix cores (v_mfma_f64_16x16x4_f64; lane l supplies A[row l % 16][k l / 16] and
+// B[k l / 16][col l % 16], result register i is D[row 4 i + l / 16][col l % 16]).  One wavefront
+// per (head, 16-row tile) walks the causal key chunks; the operand rows are permuted so that a lane
+// ends up with four consecutive keys of its query, adds each product to the bin of its column
+// floor(j K / (t + 1)) in LDS ([16 rows][K] fp64), and the bins leave normalised by their row sum
+// (= phi(q_t) . sum_{j <= t} phi(k_j)).  Nothing is differenced, so there is no cancellation, and
+// the key features are read T / 16 times per head from the L2 instead of K + 1 prefix vectors per row.
+// The contraction index is a free permutation of the features: step s of lane group g is feature
+// 8 (s / 2) + 2 g + s % 2, which makes every operand load a 16-byte piece.
+// ------------------------------------------------------------------------------------------
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+
+template <int MQ>  // m / 4: contraction steps
+__global__ __launch_bounds__(64) void rw_tiles_kernel(Shape s, const double* __restrict__ phiQ,
+                                                      const double* __restrict__ phiK, float* __restrict__ A_hat) {
+  extern __shared__ __align__(16) double bins[];  // [16][K + 1]
+  __shared__ double tot_s[16][4];
+  const int lane = threadIdx.x, qc = lane & 15, g = lane >> 4;
+  const int32_t m = 4 * MQ;
+  const uint32_t tiles = (s.T + 15) / 16;
+  // longest first: the last row tiles of every head come first
+  const uint32_t tile = tiles - 1 - blockIdx.x / static_cast<uint32_t>(s.N);
+  const int64_t head = blockIdx.x % static_cast<uint32_t>(s.N);
+  const int32_t r0 = static_cast<int32_t>(tile) * 16;
+  const int32_t t = r0 + qc;
+  const int32_t b = static_cast<int32_t>(head / s.H);
+  const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
+  const bool active = t < len;
+  const int32_t tq = min(t, s.T - 1);
+  const int32_t bstride = s.K + 1;
+  for (int32_t x = lane; x < 16 * bstride; x += 64) bins[x] = 0.0;
+  double qd[MQ];
+  {
+    const double* qr = phiQ + (head * s.T + tq) * m + 2 * g;
+#pragma unroll
+    for (int j = 0; j < MQ / 2; ++j) {
+      const double2 v = *reinterpret_cast<const double2*>(qr + 8 * j);
+      qd[2 * j] = v.x;
+      qd[2 * j + 1] = v.y;
+    }
+  }
+  const double inv_w = 1.0 / static_cast<double>(t + 1);
+  const double* Kh = phiK + head * static_cast<int64_t>(s.T) * m;
+  const int32_t last_key = min(min(r0 + 15, s.T - 1), len - 1);  // keys past it reach no row of the tile
+  const int32_t nchunks = last_key < 0 ? 0 : last_key / 16 + 1;
+  // operand row lr stands for key 4 (lr % 4) + lr / 4 of the chunk: result register i of lane group g is key 4 g + i
+  const int32_t krow = 4 * (qc & 3) + (qc >> 2);
+  double kn[MQ];
+  auto request = [&](int32_t c) {
+    const double* kr = Kh + static_cast<int64_t>(min(16 * c + krow, s.T - 1)) * m + 2 * g;
+#pragma unroll
+    for (int j = 0; j < MQ / 2; ++j) {
+      const double2 v = *reinterpret_cast<const double2*>(kr + 8 * j);
+      kn[2 * j] = v.x;
+      kn[2 * j + 1] = v.y;
+    }
+  };
+  __syncthreads();
+  if (nchunks > 0) request(0);
+  for (int32_t c = 0; c < nchunks; ++c) {
+    double kd[MQ];
+#pragma unroll
+    for (int x = 0; x < MQ; ++x) kd[x] = kn[x];
+    if (c + 1 < nchunks) request(c + 1);
+    doublex4 acc0 = {0.0, 0.0, 0.0, 0.0}, acc1 = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int x = 0; x < MQ; x += 2) {
+      acc0 = __builtin_amdgcn_mfma_f64_16x16x4f64(kd[x], qd[x], acc0, 0, 0, 0);
+      acc1 = __builtin_amdgcn_mfma_f64_16x16x4f64(kd[x + 1], qd[x + 1], acc1, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int32_t j = 16 * c + 4 * g + i;
+      if (active && j <= t && j < len) {
+        // column of key j in row t: floor(j K / (t + 1)), exact in fp64 (the half step keeps the
+        // product away from integers by 0.5 / (t + 1), far more than its rounding error)
+        const int32_t col = static_cast<int32_t>((static_cast<double>(static_cast<int64_t>(j) * s.K) + 0.5) * inv_w);
+        atomicAdd(&bins[qc * bstride + col], acc0[i] + acc1[i]);
+      }
+    }
+  }
+  __syncthreads();
+  // row sums: lane (qc, g) adds the columns c = g (mod 4), the four parts meet in LDS
+  {
+    double part = 0.0;
+    for (int32_t c = g; c < s.K; c += 4) part += bins[qc * bstride + c];
+    tot_s[qc][g] = part;
+  }
+  __syncthreads();
+  for (int32_t x = lane; x < 16 * s.K; x += 64) {
+    const int32_t q = x / s.K, c = x - q * s.K;
+    const int32_t tt = r0 + q;
+    if (tt >= s.T) continue;
+    const double total = (tot_s[q][0] + tot_s[q][1]) + (tot_s[q][2] + tot_s[q][3]);
+    const double inv = (tt < len && total > 0.0) ? 1.0 / total : 0.0;
+    A_hat[(head * s.T + tt) * s.K + c] = static_cast<float>(bins[q * bstride + c] * inv);
+  }
+}
+
+// the tile form needs the bins of 16 rows in LDS and, for now, the contraction operands of a
+// chunk in registers twice over (m <= 128)
+bool tiles_supported(const Shape& s) { return (s.m == 64 || s.m == 128) && s.K <= 1024; }
+
 struct Layout {
   size_t ctot, cbase, P, total;
   int32_t nch;
@@ -299,6 +405,11 @@ Layout layout(const Shape& s, sea_dtype dt) {
   l.P = 2 * tab;
   const size_t el = dt == SEA_BF16 ? sizeof(PrefixOfBf16) : sizeof(double);
   l.total = l.P + ((static_cast<size_t>(s.N) * (static_cast<size_t>(s.T) + 1) * s.m * el + 255) & ~size_t(255));
+  if (tiles_supported(s)) {
+    // tile form: phi(Q) and phi(K) in fp64, [N][T][m] each
+    const size_t one = (static_cast<size_t>(s.N) * s.T * s.m * sizeof(double) + 255) & ~size_t(255);
+    l.total = 2 * one;
+  }
   return l;
 }
 
@@ -360,6 +471,30 @@ size_t estimate_rowwidth_workspace(const Shape& s, sea_dtype dt) { return layout
 
 hipError_t launch_estimate_rowwidth(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* W,
                                     float* A_hat, void* ws, hipStream_t st) {
+  if (tiles_supported(s)) {
+    const size_t one = (static_cast<size_t>(s.N) * s.T * s.m * sizeof(double) + 255) & ~size_t(255);
+    double* phiQ = static_cast<double*>(ws);
+    double* phiK = reinterpret_cast<double*>(static_cast<char*>(ws) + one);
+    {
+      StageScope scope(SEA_STAGE_FEATURES, st);
+      const hipError_t e = launch_features_f64(s, dt, Q, K, W, phiQ, phiK, st);
+      if (e != hipSuccess) return e;
+    }
+    StageScope scope(SEA_STAGE_CONTRACT, st);
+    const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 15) / 16));
+    const size_t lds = static_cast<size_t>(16) * (s.K + 1) * sizeof(double);
+    if (lds > (64u << 10)) {
+      const void* fn = s.m == 64 ? reinterpret_cast<const void*>(&rw_tiles_kernel<16>)
+                                 : reinterpret_cast<const void*>(&rw_tiles_kernel<32>);
+      const hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+      if (e != hipSuccess) return e;
+    }
+    if (s.m == 64)
+      hipLaunchKernelGGL(rw_tiles_kernel<16>, grid, dim3(64), lds, st, s, phiQ, phiK, A_hat);
+    else
+      hipLaunchKernelGGL(rw_tiles_kernel<32>, grid, dim3(64), lds, st, s, phiQ, phiK, A_hat);
+    return hipGetLastError();
+  }
   return dt == SEA_BF16 ? launch_all<PrefixOfBf16, uint16_t>(s, dt, Q, K, W, A_hat, ws, st)
                         : launch_all<double, float>(s, dt, Q, K, W, A_hat, ws, st);
 }
