@@ -282,10 +282,17 @@ def measure(torch, sea, synth, wl, steps, warmup, detail):
            "useful_flops": est_flops - (0.5 * contr * (1.0 - 1.0 / wl.K) if wl.causal else 0.0),
            "includes_topk": "topk_mask" not in avg}
     if wl.geometry == 1:
-        gbytes = float(nrows) * (wl.K + 1) * wl.m * 8
         cms = avg.get("contract", 0.0)
-        est.update({"rows_kernel_ms": cms, "gathered_bytes": gbytes,
-                    "gather_TBps": gbytes / (cms * 1e-3) / 1e12 if cms > 0 else 0.0})
+        if wl.m <= 128:
+            # tile form: phi(K) phi(Q)^T below the diagonal on the fp64 matrix cores, 2 m flops per (row, key) pair
+            fl = float(N) * wl.T * (wl.T + 1) / 2 * 2 * wl.m
+            est.update({"rows_kernel_ms": cms, "fp64_flops": fl,
+                        "fp64_tflops": fl / (cms * 1e-3) / 1e12 if cms > 0 else 0.0,
+                        "frac_of_fp64_matrix_peak": fl / (cms * 1e-3) / 1e12 / FP64_PEAK_TFLOPS if cms > 0 else 0.0})
+        else:
+            gbytes = float(nrows) * (wl.K + 1) * wl.m * 8
+            est.update({"rows_kernel_ms": cms, "gathered_bytes": gbytes,
+                        "gather_TBps": gbytes / (cms * 1e-3) / 1e12 if cms > 0 else 0.0})
     dominant = max(kernels, key=lambda k: kernels[k]["avg_kernel_ms"]) if kernels else None
     if dominant is None and avg:
         # correctness paths (general shapes, fp32): report the estimator against its arithmetic peak

@@ -13,7 +13,8 @@
 //   rows_kernel              one wavefront per two or four consecutive rows: phi(q_t), the K gathers of
 //                            neighbouring prefix rows, their differences, row norm
 // Features, prefixes and dot products are fp64 for both tensor types (see PrefixOfBf16); nothing is
-// rounded to bf16 here.
+// rounded to bf16 here.  For m <= 128 the prefix form above is replaced by rw_tiles_kernel (further
+// down): the same sums taken from tiles of phi(K) phi(Q)^T on the fp64 matrix cores.
 #include "sea_internal.h"
 
 namespace sea {
