@@ -211,6 +211,8 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
                                                          uint32_t* __restrict__ mbits) {
   __shared__ uint32_t red[2][4];
   __shared__ uint32_t scan[4];
+  __shared__ uint32_t hist[2048];
+  __shared__ uint32_t found[3];
   extern __shared__ uint8_t flags[];  // [H * K] selected?
   const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
   const int32_t t = static_cast<int32_t>(blockIdx.x % s.T);
@@ -267,52 +269,70 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
       }
     }
   }
-  // n-th largest key by bitwise search; block-wide counts: wave ballots, then 4 partial sums in LDS
-  // Counts are kept on the vector units (per-thread compare-and-add, DPP row sums, two
-  // cross-row exchanges, four partial sums through LDS): the scalar unit, shared by the four
-  // SIMDs of a CU, would otherwise be the bottleneck.  The search stops as soon as exactly n
-  // keys are >= tau.
+  // n-th largest key of the slab.  Estimates take the radix selection below; the general bitwise
+  // search keeps its counts on the vector units (per-thread compare-and-add, DPP row sums, two
+  // cross-row exchanges, four partial sums through LDS).  Either stops as soon as exactly n keys
+  // are >= tau.
   uint32_t tau = 0, c_ge = static_cast<uint32_t>(256 * VPT);
   // Scores of an estimate lie in [0, 2): their keys are 0x80000000 + (less than 2^30), so bits 31
-  // and 30 of the threshold are known and bits 29..16 can be searched on the keys' high halves, two
-  // keys per register (16-bit wrap-around differences against the trial have bit 15 set exactly
-  // for keys below it once non-candidates are given 0x4000; the sign bytes of two registers are
-  // gathered by one byte permute and counted).  Any other input takes the general 32-bit search.
+  // and 30 of the threshold are known.  The n-th largest of up to 16 K keys is then found by radix
+  // selection in three passes (11 + 11 + 8 bits): a histogram of the pass's digit over the keys that
+  // still match the prefix (LDS atomics), a suffix count over the bins, the bin that holds the n-th
+  // largest.  A pass ends the search early when the keys at or above its bin are exactly n.  Any
+  // other input takes the general 32-bit bitwise search.
   bool in_range = true;
 #pragma unroll
   for (int v = 0; v < VPT; ++v) in_range &= (key[v] == 0u) || ((key[v] >> 30) == 2u);
   const bool fast = __syncthreads_and(in_range ? 1 : 0) != 0;
   int bit = 31;
-  if (n > 0 && fast && VPT <= 32) {  // the largest slabs have no registers to spare for the packed copy
-    typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
-    ushort2v hp[VPT / 2];
-#pragma unroll
-    for (int pr = 0; pr < VPT / 2; ++pr) {
-      const uint32_t k0 = key[2 * pr] ? key[2 * pr] : 0x40000000u, k1 = key[2 * pr + 1] ? key[2 * pr + 1] : 0x40000000u;
-      hp[pr] = __builtin_bit_cast(ushort2v, __builtin_amdgcn_perm(k1, k0, 0x07060302u));
-    }
+  if (n > 0 && fast) {
     tau = 0x80000000u;
-    c_ge = static_cast<uint32_t>(total);  // every candidate's key is >= 0x80000000
+    uint32_t pmask = 0xc0000000u, need = n, above = 0;  // keys above the prefix region so far
+    c_ge = static_cast<uint32_t>(total);
+    const int shifts[3] = {19, 8, 0}, widths[3] = {11, 11, 8};
 #pragma unroll 1
-    for (bit = 29; bit >= 16 && c_ge != n; --bit) {
-      const uint32_t trial = tau | (1u << bit);
-      const uint32_t th = trial >> 16;
-      const ushort2v th2 = __builtin_bit_cast(ushort2v, th | (th << 16));
-      uint32_t below = 0;
+    for (int pass = 0; pass < 3 && c_ge != n; ++pass) {
+      const int shift = shifts[pass];
+      const uint32_t nb = 1u << widths[pass];
+      for (uint32_t x = tid; x < nb; x += 256) hist[x] = 0u;
+      __syncthreads();
 #pragma unroll
-      for (int pr = 0; pr < VPT / 2; pr += 2) {
-        const uint32_t d0 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr] - th2));
-        const uint32_t d1 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr + 1] - th2));
-        // byte selectors 8..11 give 0x00 / 0xff by the sign of bytes 1, 3, 5, 7: eight bits a key
-        below += static_cast<uint32_t>(__popc(__builtin_amdgcn_perm(d1, d0, 0x0b0a0908u)));
+      for (int v = 0; v < VPT; ++v)
+        if (key[v] != 0u && (key[v] & pmask) == tau) atomicAdd(&hist[(key[v] >> shift) & (nb - 1u)], 1u);
+      __syncthreads();
+      // thread tid owns `per` consecutive bins; keys in higher bins = total - inclusive prefix
+      const uint32_t per = nb >> 8;  // 8, 8, 1
+      uint32_t mine = 0;
+      for (uint32_t q = 0; q < per; ++q) mine += hist[tid * per + q];
+      uint32_t incl = mine;
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) {
+        const uint32_t o = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += o;
       }
-      const uint32_t c = wave_sum_u32(static_cast<uint32_t>(VPT) - (below >> 3));
-      if (lane == 0) red[bit & 1][wid] = c;
-      __syncthreads();  // the buffers alternate, so one barrier per step is enough
-      const uint32_t ct = red[bit & 1][0] + red[bit & 1][1] + red[bit & 1][2] + red[bit & 1][3];
-      if (ct >= n) { tau = trial; c_ge = ct; }
+      if (lane == kWave - 1) scan[wid] = incl;
+      __syncthreads();
+      uint32_t all = scan[0] + scan[1] + scan[2] + scan[3];
+      for (int q = 0; q < wid; ++q) incl += scan[q];
+      uint32_t g = all - incl;  // keys of the pass in bins above this thread's
+      for (int32_t q = static_cast<int32_t>(per) - 1; q >= 0; --q) {
+        const uint32_t c = hist[tid * per + q];
+        if (g < need && g + c >= need) {
+          found[0] = tid * per + q;
+          found[1] = g;
+          found[2] = c;
+        }
+        g += c;
+      }
+      __syncthreads();
+      const uint32_t digit = found[0], gt = found[1], at = found[2];
+      tau |= digit << shift;
+      pmask |= (nb - 1u) << shift;
+      c_ge = above + gt + at;  // keys >= the new prefix
+      above += gt;
+      need -= gt;
     }
-    bit = 15;
+    bit = -1;
   }
   if (n > 0) {
 #pragma unroll 1
