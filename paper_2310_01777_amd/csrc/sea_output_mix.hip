@@ -156,18 +156,40 @@ template <typename T>
 __global__ __launch_bounds__(256) void pool_kernel(Shape s, const T* __restrict__ V,
                                                    const float* __restrict__ A_hat,
                                                    float* __restrict__ pooled) {
-  extern __shared__ double sh[];  // ihat[K], then red[4][65]
+  extern __shared__ double sh[];  // ihat[K], then red[4][65], then part[256]
   double* ihat = sh;
   double* red = sh + s.K;
+  double* part = red + 4 * 65;
   const int64_t head = blockIdx.x;
   const int32_t b = static_cast<int32_t>(head / s.H);
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
-  for (int32_t c = threadIdx.x; c < s.K; c += 256) {
-    double acc = 0.0;
-    for (int32_t t = 0; t < len; ++t) acc += A_hat[(head * s.T + t) * s.K + c];
-    ihat[c] = len > 0 ? acc / len : 0.0;
+  // column means over the active rows: with K < 256 the block splits the rows into 256 / K parts
+  // (thread = (part, column)), each thread keeps four sums going, the parts meet in LDS
+  const int32_t P = s.K < 256 ? 256 / s.K : 1;
+  for (int32_t c0 = 0; c0 < s.K; c0 += 256) {
+    const int32_t c = c0 + static_cast<int32_t>(threadIdx.x) % min(s.K, 256);
+    const int32_t pt = static_cast<int32_t>(threadIdx.x) / min(s.K, 256);
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    if (pt < P && c < s.K) {
+      const float* col = A_hat + head * s.T * s.K + c;
+      int32_t t = pt;
+      for (; t + 3 * P < len; t += 4 * P) {
+        a0 += col[static_cast<int64_t>(t) * s.K];
+        a1 += col[static_cast<int64_t>(t + P) * s.K];
+        a2 += col[static_cast<int64_t>(t + 2 * P) * s.K];
+        a3 += col[static_cast<int64_t>(t + 3 * P) * s.K];
+      }
+      for (; t < len; t += P) a0 += col[static_cast<int64_t>(t) * s.K];
+    }
+    part[threadIdx.x] = (a0 + a1) + (a2 + a3);
+    __syncthreads();
+    if (pt == 0 && c < s.K) {
+      double acc = 0.0;
+      for (int32_t q = 0; q < P; ++q) acc += part[q * min(s.K, 256) + static_cast<int32_t>(threadIdx.x)];
+      ihat[c] = len > 0 ? acc / len : 0.0;
+    }
+    __syncthreads();
   }
-  __syncthreads();
   const int d = threadIdx.x & 63, q = threadIdx.x >> 6;
   double acc = 0.0, wsum = 0.0;
   for (int32_t j = q; j < len; j += 4) {
@@ -218,7 +240,7 @@ hipError_t run(const Shape& s, const T* C, const T* V, const float* A_hat, const
     hipLaunchKernelGGL(mix_causal_kernel<T>, grid, dim3(256), 0, st_, s, C, V, part, s_prob, s_mix, O);
   } else {
     float* pooled = static_cast<float*>(ws);
-    const size_t shm = (static_cast<size_t>(s.K) + 4 * 65) * sizeof(double);
+    const size_t shm = (static_cast<size_t>(s.K) + 4 * 65 + 256) * sizeof(double);
     hipLaunchKernelGGL(pool_kernel<T>, dim3(s.N), dim3(256), shm, st_, s, V, A_hat, pooled);
     const int64_t total = static_cast<int64_t>(s.N) * s.T * kHeadDim;
     hipLaunchKernelGGL(mix_pooled_kernel<T>, dim3(static_cast<uint32_t>((total + 255) / 256)), dim3(256), 0,
