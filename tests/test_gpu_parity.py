@@ -78,6 +78,11 @@ SMALL_CASES = [
     _wl("f32_bidir_pad", 2, 2, 192, 32, 16, 5, causal=False, dtype="f32", pad_frac=0.3),
     _wl("f32_ragged_cols", 1, 2, 150, 64, 13, 4, dtype="f32"),
     _wl("f32_budget", 1, 2, 256, 32, 8, 2, k_budget=10, dtype="f32"),
+    # fp32 tensors on the tiled matrix-core attention (K | T, power-of-two keys per column)
+    _wl("f32_tile_bidir_pad", 2, 2, 256, 32, 16, 5, causal=False, dtype="f32", pad_frac=0.3),
+    _wl("f32_tile_budget", 1, 2, 512, 32, 16, 3, k_budget=12, dtype="f32"),
+    _wl("f32_tile_one_key_columns", 1, 2, 96, 32, 96, 7, dtype="f32"),
+    _wl("f32_tile_tail_rows", 1, 3, 1000, 64, 125, 9, dtype="f32"),
     _wl("bf16_causal", 2, 3, 320, 128, 40, 9),
     _wl("bf16_tail", 1, 2, 203, 64, 29, 7),
     _wl("bf16_bidir_pad", 3, 2, 256, 128, 32, 8, causal=False, pad_frac=0.3),
