@@ -341,7 +341,7 @@ int sea_last_hip_error(void);
  * number of keys per selected column, fixed key buckets), 2 = its fp32 counterpart (same shapes,
  * fp32 tensors: logits on the fp64 matrix cores, weights and P V in fp32; sea_forward only),
  * 3 = the same tiled kernel on a per-(row, key) bit mask expanded from the selection (per-row width
- * geometry, bf16, T <= 4096; sea_forward only), 0 = the per-row index-list kernel.
+ * geometry, T <= 4096, either tensor type; sea_forward only), 0 = the per-row index-list kernel.
  * Negative: the sea_status the parameters would be rejected with.  Pure host computation.
  */
 int sea_attention_path(const sea_params* p);

@@ -124,7 +124,7 @@ bool scores_stay_on_chip(const sea_params* p, const Shape& s) {
 // Scratch of the whole forward pass: estimator scratch, A_hat, then either the tiled path's mask
 // bits and bucket tables or the row-list path's idx + cnt.  `lean`: the caller keeps no
 // intermediate, so the A_hat part is dropped where the scores stay on chip.
-// per-row width geometry, bf16, sequences short enough for a block's per-key mask words to fit LDS:
+// per-row width geometry, sequences short enough for a block's per-key mask words to fit LDS:
 // the selection is expanded to one bit per key and the tiled attention kernel runs on those
 bool keybit_path(const Shape& s, sea_dtype dt) {
   return s.geometry == 1 && keybits_supported(s) && tile_attn_keybits_supported(s, dt);
@@ -414,8 +414,12 @@ int forward_stages(const sea_params* p, const void* Q, const void* K, const void
     if (e != hipSuccess) return fail_hip(e);
     e = launch_keybits(s, mbits, kb, st);
     if (e != hipSuccess) return fail_hip(e);
-    e = launch_tile_attn_keybits(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
-                                 static_cast<const uint16_t*>(V), kb, static_cast<uint16_t*>(O), st);
+    if (p->dtype == SEA_BF16)
+      e = launch_tile_attn_keybits(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                                   static_cast<const uint16_t*>(V), kb, static_cast<uint16_t*>(O), st);
+    else
+      e = launch_tile_attn_f32_keybits(s, static_cast<const float*>(Q), static_cast<const float*>(K),
+                                       static_cast<const float*>(V), kb, static_cast<float*>(O), st);
     return e == hipSuccess ? SEA_OK : fail_hip(e);
   }
   int32_t* idx = idx_opt ? idx_opt : reinterpret_cast<int32_t*>(w);

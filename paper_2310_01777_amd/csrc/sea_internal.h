@@ -68,6 +68,8 @@ hipError_t launch_keybits(const Shape& s, const uint32_t* mbits, uint32_t* kb, h
 bool tile_attn_keybits_supported(const Shape& s, sea_dtype dt);
 hipError_t launch_tile_attn_keybits(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* V,
                                     const uint32_t* kb, uint16_t* O, hipStream_t st);
+hipError_t launch_tile_attn_f32_keybits(const Shape& s, const float* Q, const float* K, const float* V,
+                                        const uint32_t* kb, float* O, hipStream_t st);
 // fp32 tensors: tiled attention on the fp64 / fp32 matrix cores from per-row column bits
 bool tile_attn_f32_supported(const Shape& s);
 hipError_t launch_tile_attn_f32(const Shape& s, const float* Q, const float* K, const float* V,

@@ -753,7 +753,7 @@ __device__ __forceinline__ float rows_sum_f(float x) {
 __global__ __launch_bounds__(256, 2) void tile_attn_f32_kernel(TileF32Args a) {
   __shared__ float m_s[4][16], l_s[4][16];
   __shared__ float o_s[4][kHeadDim][17];  // [wave][dim][query], padded
-  __shared__ uint32_t mask_s[16 * 33];     // K <= 1024: at most 32 words per row
+  __shared__ uint32_t mask_s[16 * 129];    // at most 128 mask words per row (K <= 1024 columns, or T <= 4096 keys)
   const int tid = threadIdx.x, lane = tid & 63;
   const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int qc = lane & 15, g = lane >> 4;
@@ -955,8 +955,20 @@ hipError_t launch_tile_attn_f32(const Shape& s, const float* Q, const float* K, 
 // arrives as one bit per (row, key), and the same kernel runs with every key its own "column"
 // (one key per column, column width 1) -- the walk of the dense kernel with per-key mask bits.
 // The block's mask words (128 rows x ceil(T / 32)) must fit LDS beside the staging buffers.
-bool tile_attn_keybits_supported(const Shape& s, sea_dtype dt) {
-  return dt == SEA_BF16 && s.T <= 4096 && s.T <= (1 << 24);
+bool tile_attn_keybits_supported(const Shape& s, sea_dtype) { return s.T <= 4096; }
+
+// the same for fp32 tensors
+hipError_t launch_tile_attn_f32_keybits(const Shape& s, const float* Q, const float* K, const float* V,
+                                        const uint32_t* kb, float* O, hipStream_t st) {
+  if (s.T > 4096) return hipErrorNotSupported;
+  StageScope scope(SEA_STAGE_SPARSE, st);
+  TileF32Args a{};
+  a.Q = Q; a.K = K; a.V = V; a.mbits = kb; a.O = O; a.seq_len = s.seq_len;
+  a.N = s.N; a.H = s.H; a.T = s.T; a.U = s.T; a.KW = (s.T + 31) / 32; a.rlog = 0; a.w = 1; a.causal = s.causal;
+  a.f = static_cast<double>(s.scale) * 1.4426950408889634;
+  const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 15) / 16));
+  hipLaunchKernelGGL(tile_attn_f32_kernel, grid, dim3(256), 0, st, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_tile_attn_keybits(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* V,

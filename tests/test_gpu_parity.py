@@ -601,8 +601,8 @@ def test_row_width_geometry(sea, wl):
     attention within tolerance, end to end identical lists except at near-ties."""
     x = synth.make_inputs(wl)
     p, xd, g = _gpu_forward(sea, wl, x)
-    # bf16: tiled attention on per-(row, key) bits; fp32: per-row key lists
-    assert sea.sea_attention_path(p) == (3 if wl.dtype == "bf16" and wl.T <= 4096 else 0)
+    # tiled attention on per-(row, key) bits while a block's mask words fit LDS, else per-row key lists
+    assert sea.sea_attention_path(p) == (3 if wl.T <= 4096 else 0)
     rows = None if wl.T <= 1024 else sorted(set(range(0, 140)) | set(range(wl.T - 40, wl.T))
                                             | set(range(1000, wl.T, 97)))
     po = oracle_params(wl)
