@@ -36,7 +36,9 @@
  *     process): a causal row t is resized to its own width, so its column c
  *     holds the keys [ceil(c (t+1) / K), ceil((c+1)(t+1) / K)) -- the whole
  *     method for that row is the bidirectional one on a sequence of t + 1 keys;
- *     no reduced-precision rounding points apply in this geometry;
+ *     in reduced-precision mode every column of such a row is summed key by
+ *     key, as a fixed-bucket row's own column is: phi(q_t) and each phi(k_j)
+ *     are rounded, nothing else;
  *   - masked-out keys are excluded from the softmax (not given logit zero);
  *   - right padding: keys and rows >= seq_len[b] are inactive;
  *   - ties in the selection go to the lower column; a column with no admissible
@@ -195,7 +197,11 @@ int ref_estimate(const ref_params* p, const double* Q, const double* K,
           /* the row's own width: FAVOR+ with V_I the (t+1) x K stretch of the identity */
           for (int64_t j = 0; j <= t; ++j) {
             double dotp = 0.0;
-            for (int64_t i = 0; i < m; ++i) dotp += phiQ[i] * phiK[j * m + i];
+            for (int64_t i = 0; i < m; ++i) {
+              /* key by key, as in the own column above: each phi(k_j) is rounded before its product */
+              const double f = phiK[j * m + i];
+              dotp += phiQ[i] * (p->round8 ? ref_round8(f) : f);
+            }
             Arow[bucket_of(j, t + 1, KK)] += dotp;
             rowsum += dotp;
           }

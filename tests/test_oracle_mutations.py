@@ -35,6 +35,7 @@ MUTATIONS = [
     ("r8_state_not_rounded", "state[x] = ref_round8(state[x]);", "state[x] = state[x];"),
     ("r8_query_features_not_rounded", "if (p->round8) phiQ[i] = ref_round8(phiQ[i]);", ";"),
     ("r8_own_column_keys_not_rounded", "acc += phiQ[i] * (p->round8 ? ref_round8(f) : f);", "acc += phiQ[i] * f;"),
+    ("r8_row_width_keys_not_rounded", "dotp += phiQ[i] * (p->round8 ? ref_round8(f) : f);", "dotp += phiQ[i] * f;"),
     ("r8_state_rounded_per_key", "state[c * m + i] += phiK[j * m + i];",
      "state[c * m + i] += p->round8 ? ref_round8(phiK[j * m + i]) : phiK[j * m + i];"),
     ("r8_query_rounded_before_shift_to_7_bits", "double s = ldexp(f, 8);           /* |s| in [128, 256) */\n  double r = nearbyint(s);          /* default mode: ties to even */\n  return ldexp(r, e - 8);",
@@ -57,6 +58,7 @@ PINS = [
     (pins.test_estimate_literal_favor_with_stretched_identity, {}),
     (pins.test_reduced_precision_points_hand_built_case, {}),
     (pins.test_reduced_precision_points_with_library_casts, {}),
+    (pins.test_row_width_reduced_precision_points_with_library_casts, {}),
     (pins.test_output_mix_limits_and_closed_forms, {}),
     (pins.test_estimate_converges_to_exact_softmax_buckets, {"causal": True}),
 ]

@@ -787,6 +787,38 @@ def test_row_width_row_equals_bidirectional_run_on_the_prefix(kb):
         np.testing.assert_allclose(a["O"][:, :, t], b["O"][:, :, 0], rtol=1e-11, atol=1e-14)
 
 
+def test_row_width_reduced_precision_points_with_library_casts():
+    """Reduced-precision mode in the per-row width geometry (Sec. 3 "Performer (FAVOR+)", App. A.4,
+    read for bf16 tensors): phi(q_t) and every phi(k_j) are rounded, the products are summed key
+    by key into the row's own columns, nothing else is rounded.  Rebuilt here through the T x T
+    matrix of rounded feature products with the library's bf16 cast and an integer scatter; the
+    unrounded variants (no cast on the keys, no cast on the queries) are told apart."""
+    B, H, T, d, m, Kc = 1, 2, 53, 6, 16, 7
+    Q, K, _ = _rand_qkv(B, H, T, d, seed=23, std=0.8)
+    W = synth.gaussian_orthogonal(m, d, 3).numpy().astype(np.float64)
+    scale = 0.4
+    cast = lambda a: torch.from_numpy(a.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    p = oracle.Params(B=B, H=H, T=T, d=d, m=m, K=Kc, k_hat=2, causal=True, scale=scale, round8=True,
+                      geometry=1)
+    A = oracle.estimate(p, Q, K, W)
+    for h in range(H):
+        x, y = np.sqrt(scale) * Q[0, h], np.sqrt(scale) * K[0, h]
+        aq = x @ W.T - 0.5 * (x * x).sum(-1, keepdims=True)
+        fq = np.exp(aq - np.ceil(aq.max(-1, keepdims=True) / np.log(2.0)) * np.log(2.0))
+        fk = np.exp(y @ W.T - 0.5 * (y * y).sum(-1, keepdims=True))
+
+        def rows(fq_, fk_):
+            S = fq_ @ fk_.T
+            out = np.zeros((T, Kc))
+            for t in range(T):
+                np.add.at(out[t], (np.arange(t + 1) * Kc) // (t + 1), S[t, :t + 1])
+            return out / out.sum(-1, keepdims=True)
+
+        np.testing.assert_allclose(A[0, h], rows(cast(fq), cast(fk)), rtol=1e-9, atol=1e-15)
+        assert np.abs(A[0, h] - rows(cast(fq), fk)).max() > 1e-5
+        assert np.abs(A[0, h] - rows(fq, cast(fk))).max() > 1e-5
+
+
 def test_row_width_mask_is_the_library_resize_of_each_row():
     """k_budget = 0: row t of M* is the nearest-neighbour resize of row t of M^ (K wide) to t + 1
     pixels, also when t + 1 < K (columns without a pixel are never selected).  The library resize
