@@ -53,6 +53,12 @@ size_t estimate_rowwidth_workspace(const Shape& s, sea_dtype dt);
 hipError_t launch_estimate_rowwidth(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* W,
                                     float* A_hat, void* ws, hipStream_t st);
 
+// the same estimate for bf16 tensors on the bf16 matrix cores (features rounded to bf16, per-key products binned in LDS)
+bool rowwidth_mfma_supported(const Shape& s, sea_dtype dt);
+size_t rowwidth_mfma_workspace(const Shape& s);
+hipError_t launch_rowwidth_mfma(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W,
+                                float* A_hat, void* ws, hipStream_t st);
+
 // sel, idx, cnt, mbits may each be nullptr; mbits is [N][T][ceil(K/32)] selected-column bits
 hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, int32_t* idx,
                             int32_t* cnt, uint32_t* mbits, hipStream_t st);

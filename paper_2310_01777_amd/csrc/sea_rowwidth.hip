@@ -309,9 +309,12 @@ __global__ __launch_bounds__(64) void rw_tiles_kernel(Shape s, const double* __r
   const int lane = threadIdx.x, qc = lane & 15, g = lane >> 4;
   const int32_t m = 4 * MQ;
   const uint32_t tiles = (s.T + 15) / 16;
-  // longest first: the last row tiles of every head come first
-  const uint32_t tile = tiles - 1 - blockIdx.x / static_cast<uint32_t>(s.N);
-  const int64_t head = blockIdx.x % static_cast<uint32_t>(s.N);
+  // Head-major, each XCD on a contiguous range of blocks: the row tiles of a head run close together
+  // on one XCD, whose L2 then serves all but the first read of the head's key features.  Within a
+  // head the longest (last) row tiles come first.
+  const uint32_t lb = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int64_t head = lb / tiles;
+  const uint32_t tile = tiles - 1 - lb % tiles;
   const int32_t r0 = static_cast<int32_t>(tile) * 16;
   const int32_t t = r0 + qc;
   const int32_t b = static_cast<int32_t>(head / s.H);
@@ -468,10 +471,15 @@ hipError_t launch_all(const Shape& s, sea_dtype dt, const void* Qv, const void* 
 
 bool estimate_rowwidth_supported(const Shape& s) { return s.causal && (s.m == 64 || s.m == 128 || s.m == 256); }
 
-size_t estimate_rowwidth_workspace(const Shape& s, sea_dtype dt) { return layout(s, dt).total; }
+size_t estimate_rowwidth_workspace(const Shape& s, sea_dtype dt) {
+  return rowwidth_mfma_supported(s, dt) ? rowwidth_mfma_workspace(s) : layout(s, dt).total;
+}
 
 hipError_t launch_estimate_rowwidth(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* W,
                                     float* A_hat, void* ws, hipStream_t st) {
+  if (rowwidth_mfma_supported(s, dt))
+    return launch_rowwidth_mfma(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+                                static_cast<const uint16_t*>(W), A_hat, ws, st);
   if (tiles_supported(s)) {
     const size_t one = (static_cast<size_t>(s.N) * s.T * s.m * sizeof(double) + 255) & ~size_t(255);
     double* phiQ = static_cast<double*>(ws);

@@ -139,6 +139,9 @@ def test_workspace_sizes_closed_forms(sea):
     assert sea.sea_mask_attn_workspace_bytes(P(1, 2, 2048, 64, 128, 128, 64)) == 0
     assert sea.sea_mask_attn_workspace_bytes(P(1, 2, 1024, 64, 64, 32, 1, k_budget=16)) > 0
     assert sea.sea_mask_attn_workspace_bytes(P(1, 2, 2048, 64, 128, 128, 64, geometry=1)) == 0   # not offered
-    # per-row width geometry: prefix table (T + 1) m fp64 per head dominates the estimator scratch
-    p1 = P(2, 3, 512, 64, 128, 32, 4, geometry=1)
-    assert sea.sea_workspace_bytes(p1) >= 2 * 3 * 513 * 128 * 8
+    # per-row width geometry: both feature tensors dominate the estimator scratch -- bf16 for bf16
+    # tensors (T rounded up to whole 32-token chunks), fp64 for fp32 tensors
+    p1 = P(2, 3, 500, 64, 128, 32, 4, geometry=1)
+    assert sea.sea_workspace_bytes(p1) >= 2 * (2 * 3 * 512 * 128 * 2)
+    p2 = P(2, 3, 500, 64, 128, 32, 4, geometry=1, dtype="f32")
+    assert sea.sea_workspace_bytes(p2) >= 2 * (2 * 3 * 500 * 128 * 8)

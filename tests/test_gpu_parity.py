@@ -561,7 +561,8 @@ ROW_WIDTH_CASES = [
     _wl("rw_bf16_three_slots", 1, 2, 777, 256, 192, 8, geometry=1),
     _wl("rw_bf16_one_column", 1, 2, 256, 64, 8, 1, k_budget=4, geometry=1),
     _wl("rw_bf16_long", 1, 1, 8192, 128, 128, 4, k_budget=32, geometry=1),
-    _wl("rw_max_K", 1, 1, 1200, 64, 1024, 50, geometry=1),                     # sixteen column slots per lane
+    _wl("rw_max_K", 1, 1, 1200, 64, 1024, 50, geometry=1),                     # bf16: eight column parts, two passes of four waves
+    _wl("rw_bf16_wide_index", 1, 1, 8400, 64, 256, 8, k_budget=64, geometry=1),  # K T > 2^21: column arithmetic in fp64
     replace(synth.get_workload("c2"), name="c2+row_width", geometry=1),      # full size, sampled rows
     # the paper's own setting: causal-per-batch selection in this geometry
     _wl("rw_grouped", 2, 4, 300, 64, 16, 3, grouping=1, geometry=1),

@@ -22,8 +22,7 @@ def to_np64(t: torch.Tensor) -> np.ndarray:
 def oracle_params(wl_or_p, round8=None) -> oracle.Params:
     p = wl_or_p
     geometry = int(getattr(p, "geometry", 0))
-    # the per-row width geometry has no reduced-precision rounding points
-    r8 = (p.dtype == "bf16" and geometry == 0) if round8 is None else round8
+    r8 = (p.dtype == "bf16") if round8 is None else round8
     return oracle.Params(B=p.B, H=p.H, T=p.T, d=p.d, m=p.m, K=p.K, k_hat=p.k_hat,
                          k_budget=p.k_budget, causal=bool(p.causal), scale=float(p.scale), round8=r8,
                          grouping=int(getattr(p, "grouping", 0)), geometry=geometry)
