@@ -74,7 +74,7 @@ def cpu_baseline(wl, x, budget_s):
     nheads = wl.B * wl.H
     p = oracle.Params(B=wl.B, H=wl.H, T=wl.T, d=wl.d, m=wl.m, K=wl.K, k_hat=wl.k_hat,
                       k_budget=wl.k_budget, causal=wl.causal, scale=wl.scale,
-                      round8=wl.dtype == "bf16" and wl.geometry == 0, grouping=wl.grouping, geometry=wl.geometry)
+                      round8=wl.dtype == "bf16", grouping=wl.grouping, geometry=wl.geometry)
     Q, K, V, W = f64(x["Q"]), f64(x["K"]), f64(x["V"]), f64(x["W"])
     sl = None if x["seq_len"] is None else x["seq_len"].numpy()
     unit = wl.H if wl.grouping else 1          # heads that must be computed together
@@ -283,7 +283,15 @@ def measure(torch, sea, synth, wl, steps, warmup, detail):
            "includes_topk": "topk_mask" not in avg}
     if wl.geometry == 1:
         cms = avg.get("contract", 0.0)
-        if wl.m <= 128:
+        if wl.dtype == "bf16":
+            # phi~(K) phi~(Q)^T below the diagonal on the bf16 matrix cores, 2 m flops per (row, key) pair,
+            # every product then binned in LDS (the time includes the binning)
+            fl = float(N) * wl.T * (wl.T + 1) / 2 * 2 * wl.m
+            est.update({"tiles_kernel_ms": cms, "pair_flops": fl,
+                        "pair_tflops": fl / (cms * 1e-3) / 1e12 if cms > 0 else 0.0,
+                        "frac_of_bf16_mfma_peak": fl / (cms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS if cms > 0 else 0.0,
+                        "binned_pairs_per_s": float(N) * wl.T * (wl.T + 1) / 2 / (cms * 1e-3) if cms > 0 else 0.0})
+        elif wl.m <= 128:
             # tile form: phi(K) phi(Q)^T below the diagonal on the fp64 matrix cores, 2 m flops per (row, key) pair
             fl = float(N) * wl.T * (wl.T + 1) / 2 * 2 * wl.m
             est.update({"rows_kernel_ms": cms, "fp64_flops": fl,

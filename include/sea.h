@@ -107,8 +107,11 @@ size_t sea_workspace_bytes(const sea_params* p);
  * phi(K)^T V_I are rounded to bfloat16 and contracted on the matrix cores with fp32
  * accumulation; a causal row's own column is summed key by key over j <= t from phi(k_j) rounded
  * to bfloat16 (no prefix state is rounded).  dtype = SEA_F32: all products accumulate in fp64.
- * geometry = 1: V_I of row t is the (t+1) x K stretch, A_hat[t][c] = phi(q_t) . sum of phi(k_j)
- * over the keys of the row's own column c, normalised per row; all of it in fp64, either dtype.
+ * geometry = 1: V_I of row t is the (t+1) x K stretch, A_hat[t][c] = sum of phi(q_t) . phi(k_j)
+ * over the keys of the row's own column c, normalised per row.  dtype = SEA_BF16: phi(q_t) (after
+ * a power-of-two row scale) and every phi(k_j) are rounded to bfloat16, the per-key products are
+ * taken on the matrix cores with fp32 accumulation and summed per column without further
+ * rounding; dtype = SEA_F32: all of it in fp64.
  * The feature exponent is not stabilised on the key side (a data-dependent key stabiliser would
  * make causal results depend on future keys).  Two bounds follow for dtype = SEA_BF16, where the
  * features are fp32: above, log2(e) |w_i|^2 / 2 must stay inside the fp32 exponent range (true for

@@ -53,12 +53,8 @@ __device__ __forceinline__ double exp_f64(double x) {
 // NFT > 0: the exponent arguments of the (at most NFT) feature tiles stay in registers between the
 // projection and the exponential, and the unrolled tile loop lets the loads of W run ahead;
 // NFT = 0: any m, the arguments take a round trip through the output buffer.
-// four consecutive elements of an fp32 or bf16 tensor
+// four consecutive elements of an fp32 tensor
 __device__ __forceinline__ float4 load4(const float* p) { return *reinterpret_cast<const float4*>(p); }
-__device__ __forceinline__ float4 load4(const uint16_t* p) {
-  const uint2 u = *reinterpret_cast<const uint2*>(p);
-  return make_float4(bf16lo_to_f32(u.x), bf16hi_to_f32(u.x), bf16lo_to_f32(u.y), bf16hi_to_f32(u.y));
-}
 
 template <int NFT, typename TI>
 __global__ __launch_bounds__(256) void features_f64_kernel(Shape s, const TI* __restrict__ Q,
@@ -375,16 +371,11 @@ void launch_features_f64_t(const Shape& s, const TI* Q, const TI* K, const TI* W
 
 }  // namespace
 
-// phi(Q) (row-shifted) and phi(K) (zero past seq_len) in fp64, [N][T][m] each, from fp32 or bf16 tensors
-hipError_t launch_features_f64(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* W,
-                               double* phiQ, double* phiK, hipStream_t st) {
+// phi(Q) (row-shifted) and phi(K) (zero past seq_len) in fp64, [N][T][m] each
+hipError_t launch_features_f64(const Shape& s, const float* Q, const float* K, const float* W, double* phiQ,
+                               double* phiK, hipStream_t st) {
   if (s.m % 16 != 0) return hipErrorNotSupported;
-  if (dt == SEA_BF16)
-    launch_features_f64_t(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
-                          static_cast<const uint16_t*>(W), phiQ, phiK, st);
-  else
-    launch_features_f64_t(s, static_cast<const float*>(Q), static_cast<const float*>(K),
-                          static_cast<const float*>(W), phiQ, phiK, st);
+  launch_features_f64_t(s, Q, K, W, phiQ, phiK, st);
   return hipGetLastError();
 }
 

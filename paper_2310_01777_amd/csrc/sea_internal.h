@@ -33,8 +33,8 @@ struct Shape {
 hipError_t launch_estimate_f64(const Shape& s, const float* Q, const float* K, const float* W,
                                float* A_hat, void* ws, hipStream_t st);
 size_t estimate_f64_workspace(const Shape& s);
-hipError_t launch_features_f64(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* W,
-                               double* phiQ, double* phiK, hipStream_t st);
+hipError_t launch_features_f64(const Shape& s, const float* Q, const float* K, const float* W, double* phiQ,
+                               double* phiK, hipStream_t st);
 
 hipError_t launch_estimate_bf16(const Shape& s, const uint16_t* Q, const uint16_t* K,
                                 const uint16_t* W, float* A_hat, void* ws, hipStream_t st);
@@ -47,7 +47,8 @@ size_t estimate_fused_workspace(const Shape& s);
 hipError_t launch_estimate_fused(const Shape& s, const uint16_t* Q, const uint16_t* K, const uint16_t* W,
                                  float* A_hat, uint32_t* mbits, void* ws, hipStream_t st);
 
-// per-row width geometry (causal, m in {64,128,256}): prefix table of phi(K), K + 1 gathered dot products per row
+// per-row width geometry (causal, m in {64,128,256}); fp32 tensors: fp64 features, tiles on the fp64 matrix
+// cores or a prefix table of phi(K); bf16 tensors: the bf16 matrix-core form below
 bool estimate_rowwidth_supported(const Shape& s);
 size_t estimate_rowwidth_workspace(const Shape& s, sea_dtype dt);
 hipError_t launch_estimate_rowwidth(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* W,

@@ -1,4 +1,4 @@
-// Estimate in the per-row width geometry (App. A.4, figure of the masking process: in causal
+// Estimate in the per-row width geometry for fp32 tensors (App. A.4, figure of the masking process: in causal
 // attention every row of A^ and M^ is resized to its own width).  Row t spreads its K columns
 // over its own t + 1 keys: column c holds the keys [b_c, b_{c+1}), b_c = ceil(c (t+1) / K), so
 //   A^[t][c] = phi(q_t) . (P[b_{c+1}] - P[b_c]) / (phi(q_t) . P[t+1]),
@@ -12,9 +12,11 @@
 //   prefix_kernel<.., true>  same walk again, writes P = chunk base + running sum
 //   rows_kernel              one wavefront per two or four consecutive rows: phi(q_t), the K gathers of
 //                            neighbouring prefix rows, their differences, row norm
-// Features, prefixes and dot products are fp64 for both tensor types (see PrefixOfBf16); nothing is
-// rounded to bf16 here.  For m <= 128 the prefix form above is replaced by rw_tiles_kernel (further
-// down): the same sums taken from tiles of phi(K) phi(Q)^T on the fp64 matrix cores.
+// Features, prefixes and dot products are fp64; a difference of fp32 prefixes could not resolve
+// scores below ~1e-6 of the row, and with k^ = K / 2 such scores sit at the selection boundary of
+// many rows.  For m <= 128 the prefix form above is replaced by rw_tiles_kernel (further down): the
+// same sums taken from tiles of phi(K) phi(Q)^T on the fp64 matrix cores.  bf16 tensors take the
+// bf16 matrix-core form in its own file.
 #include "sea_internal.h"
 
 namespace sea {
@@ -23,16 +25,8 @@ namespace {
 constexpr int kStage = 64;        // keys staged in LDS at a time
 constexpr int kMaxChunks = 64;    // chunks per head
 constexpr int kRowWaves = 4;
-// Arithmetic and prefix element type for bf16 tensors.  float makes the rows kernel 1.7x faster
-// (half the gathered bytes) but a difference of fp32 prefixes cannot resolve scores below ~1e-6 of
-// the row, and with k^ = K / 2 such scores sit at the selection boundary of many rows.
-using PrefixOfBf16 = double;
 
-// element i of a bf16 (uint16_t) or fp32 tensor, converted to the arithmetic type F
-template <typename F>
-__device__ __forceinline__ F elem(const uint16_t* p, int64_t i) {
-  return static_cast<F>(bf16_to_f32(p[i]));
-}
+// element i of an fp32 tensor, converted to the arithmetic type F
 template <typename F>
 __device__ __forceinline__ F elem(const float* p, int64_t i) {
   return static_cast<F>(p[i]);
@@ -399,7 +393,7 @@ struct Layout {
   size_t ctot, cbase, P, total;
   int32_t nch;
 };
-Layout layout(const Shape& s, sea_dtype dt) {
+Layout layout(const Shape& s) {
   Layout l{};
   const int32_t CH = chunk_len(s.T);
   l.nch = (s.T + CH - 1) / CH;
@@ -407,8 +401,7 @@ Layout layout(const Shape& s, sea_dtype dt) {
   l.ctot = 0;
   l.cbase = tab;
   l.P = 2 * tab;
-  const size_t el = dt == SEA_BF16 ? sizeof(PrefixOfBf16) : sizeof(double);
-  l.total = l.P + ((static_cast<size_t>(s.N) * (static_cast<size_t>(s.T) + 1) * s.m * el + 255) & ~size_t(255));
+  l.total = l.P + ((static_cast<size_t>(s.N) * (static_cast<size_t>(s.T) + 1) * s.m * sizeof(double) + 255) & ~size_t(255));
   if (tiles_supported(s)) {
     // tile form: phi(Q) and phi(K) in fp64, [N][T][m] each
     const size_t one = (static_cast<size_t>(s.N) * s.T * s.m * sizeof(double) + 255) & ~size_t(255);
@@ -440,12 +433,12 @@ hipError_t launch_rows(const Shape& s, const TI* Q, const TI* W, const F* P,
 }
 
 template <typename F, typename TI>
-hipError_t launch_all(const Shape& s, sea_dtype dt, const void* Qv, const void* Kv, const void* Wv, float* A_hat,
+hipError_t launch_all(const Shape& s, const void* Qv, const void* Kv, const void* Wv, float* A_hat,
                       void* ws, hipStream_t st) {
   const TI* Q = static_cast<const TI*>(Qv);
   const TI* K = static_cast<const TI*>(Kv);
   const TI* W = static_cast<const TI*>(Wv);
-  const Layout l = layout(s, dt);
+  const Layout l = layout(s);
   char* base = static_cast<char*>(ws);
   double* ctot = reinterpret_cast<double*>(base + l.ctot);
   double* cbase = reinterpret_cast<double*>(base + l.cbase);
@@ -472,7 +465,7 @@ hipError_t launch_all(const Shape& s, sea_dtype dt, const void* Qv, const void* 
 bool estimate_rowwidth_supported(const Shape& s) { return s.causal && (s.m == 64 || s.m == 128 || s.m == 256); }
 
 size_t estimate_rowwidth_workspace(const Shape& s, sea_dtype dt) {
-  return rowwidth_mfma_supported(s, dt) ? rowwidth_mfma_workspace(s) : layout(s, dt).total;
+  return rowwidth_mfma_supported(s, dt) ? rowwidth_mfma_workspace(s) : layout(s).total;
 }
 
 hipError_t launch_estimate_rowwidth(const Shape& s, sea_dtype dt, const void* Q, const void* K, const void* W,
@@ -480,13 +473,15 @@ hipError_t launch_estimate_rowwidth(const Shape& s, sea_dtype dt, const void* Q,
   if (rowwidth_mfma_supported(s, dt))
     return launch_rowwidth_mfma(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
                                 static_cast<const uint16_t*>(W), A_hat, ws, st);
+  if (dt != SEA_F32) return hipErrorNotSupported;
   if (tiles_supported(s)) {
     const size_t one = (static_cast<size_t>(s.N) * s.T * s.m * sizeof(double) + 255) & ~size_t(255);
     double* phiQ = static_cast<double*>(ws);
     double* phiK = reinterpret_cast<double*>(static_cast<char*>(ws) + one);
     {
       StageScope scope(SEA_STAGE_FEATURES, st);
-      const hipError_t e = launch_features_f64(s, dt, Q, K, W, phiQ, phiK, st);
+      const hipError_t e = launch_features_f64(s, static_cast<const float*>(Q), static_cast<const float*>(K),
+                                               static_cast<const float*>(W), phiQ, phiK, st);
       if (e != hipSuccess) return e;
     }
     StageScope scope(SEA_STAGE_CONTRACT, st);
@@ -504,8 +499,7 @@ hipError_t launch_estimate_rowwidth(const Shape& s, sea_dtype dt, const void* Q,
       hipLaunchKernelGGL(rw_tiles_kernel<32>, grid, dim3(64), lds, st, s, phiQ, phiK, A_hat);
     return hipGetLastError();
   }
-  return dt == SEA_BF16 ? launch_all<PrefixOfBf16, uint16_t>(s, dt, Q, K, W, A_hat, ws, st)
-                        : launch_all<double, float>(s, dt, Q, K, W, A_hat, ws, st);
+  return launch_all<double, float>(s, Q, K, W, A_hat, ws, st);
 }
 
 }  // namespace sea

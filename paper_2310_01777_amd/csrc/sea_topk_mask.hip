@@ -79,7 +79,8 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
     for (int q = 0; q < SLOTS; ++q) {
       const int32_t c = q * kWave + lane;
       bool cand = c < ncand;  // c < ncand <= K
-      if (ROWW) cand = cand && block_start(c + 1, Tw, s.K) > block_start(c, Tw, s.K);
+      // a row at least K keys wide has a key in every column (the row is wave-uniform)
+      if (ROWW && Tw < s.K) cand = cand && block_start(c + 1, Tw, s.K) > block_start(c, Tw, s.K);
       key[q] = cand ? ordered_key(A_hat[row * s.K + c]) : 0u;
     }
     // largest tau with #{key >= tau} >= n  ==  the n-th largest key
@@ -91,6 +92,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
   #pragma unroll
       for (int q = 0; q < SLOTS; ++q) c_ge += popc64(__ballot(key[q] >= trial));
       if (c_ge >= n) tau = trial;
+      if (c_ge == n) break;  // the keys >= tau are exactly the n to take (one row per wave: uniform)
     }
     int c_gt = 0;
   #pragma unroll
