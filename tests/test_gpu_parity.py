@@ -636,8 +636,8 @@ def test_row_width_geometry(sea, wl):
             a = o["A_hat"][b, :, r]
             lo, hi = min(a[h, c] for h, c in theirs), max(a[h, c] for h, c in mine - theirs)
             # near-tie: relative gap below the dtype's bound, or both scores (shares of a row that
-            # sums to 1, taken from differences of fp64 prefix sums of the whole row) below what
-            # fp64 can tell apart: m * 2^-53 < 1e-13 of the row
+            # sums to 1; fp32 tensors with m = 256 take them from differences of fp64 prefix sums
+            # of the whole row) below what fp64 can tell apart: m * 2^-53 < 1e-13 of the row
             assert (lo - hi) / lo < GAP[wl.dtype] or lo - hi < 1e-12, (b, grp, r, lo, hi)
     assert (~same).mean() <= 0.02
     assert np.array_equal(gi[same], o["idx"][same]) and np.array_equal(gc[same], o["cnt"][same])
