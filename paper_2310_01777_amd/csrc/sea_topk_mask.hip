@@ -8,6 +8,7 @@
 // population counts only; ties at the threshold go to the lower column.  Selected columns
 // are compacted in ascending order with ballot prefix counts, then expanded.
 #include "sea_internal.h"
+#include "sea_rowlanes.h"
 
 namespace sea {
 namespace {
@@ -186,6 +187,126 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
     total = kept;
   }
   if (cnt && lane == 0) cnt[row] = total;
+}
+
+// ------------------------------------------------------------------------------------------
+// The same per-query selection when only the selected-column bits are wanted (the forward paths
+// that run the attention on bits), for K <= 64 with 4 | K.  One wavefront owns 16 rows: row
+// l % 16 lives in the four lanes l % 16 + 16 q, lane group lg = l / 16 holds the columns
+// 16 ct + 4 lg + i of every 16-column tile ct, so a row's K scores are NCT float4 loads per lane and
+// every count over a row is NCT x 4 compares in the lane plus two row-swap steps.  Same order-
+// preserving keys, same bitwise search (it ends as soon as every row's threshold separates exactly
+// its quota), same tie rule (lowest columns first) as the kernel above.
+// ------------------------------------------------------------------------------------------
+template <int NCT, bool ROWW>
+__global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_bits_kernel(Shape s, const float* __restrict__ A_hat,
+                                                                         uint32_t* __restrict__ mbits) {
+  const int lane = threadIdx.x & 63, lr = lane & 15, lg = lane >> 4;
+  const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
+  const int64_t row0 = (static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6)) * 16;
+  if (row0 >= nrows) return;  // whole wave leaves; no block-wide barrier is used below
+  const int64_t row = min(row0 + lr, nrows - 1);
+  const int32_t t = static_cast<int32_t>(row % s.T);
+  const int32_t b = static_cast<int32_t>((row / s.T) / s.H);
+  const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
+  const bool active = row0 + lr < nrows && t < len;
+  const int32_t jmax = (s.causal && t < len - 1) ? t : len - 1;  // last admissible key
+  const int32_t Tw = ROWW ? t + 1 : s.T;                         // width the K columns are spread over
+  const int32_t ncand = active ? bucket_of(jmax, Tw, s.K) + 1 : 0;
+  const uint32_t nsel = active ? static_cast<uint32_t>(min(s.k_hat, ROWW ? min(s.K, Tw) : ncand)) : 0u;
+  // rows narrower than K have columns without a key (wave-uniform: does the wave hold such a row)
+  const bool sparse_cols = ROWW && __ballot(active && Tw < s.K) != 0ull;
+
+  uint32_t key[NCT][4];
+  const float* arow = A_hat + row * s.K;
+#pragma unroll
+  for (int ct = 0; ct < NCT; ++ct) {
+    const int32_t c0 = 16 * ct + 4 * lg;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c0 < s.K) v = *reinterpret_cast<const float4*>(arow + c0);
+    const float a[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int32_t c = c0 + i;
+      bool cand = c < ncand;  // ncand <= K
+      if (sparse_cols && cand && Tw < s.K) cand = block_start(c + 1, Tw, s.K) > block_start(c, Tw, s.K);
+      key[ct][i] = cand ? ordered_key(a[i]) : 0u;
+    }
+  }
+  // largest tau with #{key >= tau} >= nsel, or any tau whose count is exactly nsel
+  uint32_t tau = 0u, cge = 16u * NCT;  // every key is >= 0
+#pragma unroll 1
+  for (int bit = 31; bit >= 0; --bit) {
+    const bool pend = cge != nsel && nsel != 0u;
+    if (__ballot(pend) == 0ull) break;
+    const uint32_t trial = tau | (1u << bit);
+    uint32_t cnt = 0;
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) cnt += key[ct][i] >= trial ? 1u : 0u;
+    cnt = rows_sum_u(cnt);
+    const bool take = pend && cnt >= nsel;
+    tau = take ? trial : tau;
+    cge = take ? cnt : cge;
+  }
+  // nib[ct]: bit i set iff column 16 ct + 4 lg + i of this lane's row is selected
+  uint32_t nib[NCT];
+  const bool excess = cge != nsel && nsel != 0u;  // more keys than the quota tie at tau
+  if (__ballot(excess) == 0ull) {
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+      uint32_t bits = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) bits |= (nsel != 0u && key[ct][i] >= tau) ? (1u << i) : 0u;
+      nib[ct] = bits;
+    }
+  } else {
+    uint32_t cgt = 0;
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) cgt += key[ct][i] > tau ? 1u : 0u;
+    cgt = rows_sum_u(cgt);
+    // rows without excess: every key >= tau is taken (cge == nsel, so need_eq covers all ties)
+    int32_t need_eq = static_cast<int32_t>(nsel) - static_cast<int32_t>(cgt);
+#pragma unroll
+    for (int ct = 0; ct < NCT; ++ct) {
+      uint32_t eqm = 0, gtm = 0;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        eqm |= (key[ct][i] == tau && nsel != 0u) ? (1u << i) : 0u;
+        gtm |= (key[ct][i] > tau && nsel != 0u) ? (1u << i) : 0u;
+      }
+      // columns ascend with (ct, lg, i): ties in lower lane groups of this tile come first
+      uint32_t below;
+      const uint32_t total = rows_sum_prefix_u(static_cast<uint32_t>(__popc(eqm)), lg, &below);
+      uint32_t bits = gtm;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int32_t rank = static_cast<int32_t>(below) + __popc(eqm & ((1u << i) - 1u));
+        if (((eqm >> i) & 1u) && rank < need_eq) bits |= 1u << i;
+      }
+      nib[ct] = bits;
+      need_eq -= min(need_eq, static_cast<int32_t>(total));
+    }
+  }
+  // word j holds columns 32 j .. 32 j + 31 = tiles 2 j (low half) and 2 j + 1; the four lanes of a
+  // row combine their parts and lane group 0 stores them
+  const int32_t kw = (s.K + 31) >> 5;
+  constexpr int kWords = (NCT + 1) / 2;
+  uint32_t words[kWords];
+#pragma unroll
+  for (int j = 0; j < kWords; ++j) {
+    uint32_t part = nib[2 * j] << (4 * lg);
+    if (2 * j + 1 < NCT) part |= nib[2 * j + 1] << (16 + 4 * lg);
+    words[j] = rows_or_u(part);
+  }
+  if (lg != 0 || row0 + lr >= nrows) return;
+  uint32_t* mrow = mbits + row * kw;
+#pragma unroll
+  for (int j = 0; j < kWords; ++j)
+    if (j < kw) mrow[j] = words[j];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -544,6 +665,22 @@ hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, in
   const dim3 block(kWavesPerBlock * kWave);
   const int slots = (s.K + kWave - 1) / kWave;
   StageScope scope(SEA_STAGE_TOPK_MASK, st);
+  if (s.grouping == 0 && mbits && !sel && !idx && !cnt && s.K <= 64 && s.K % 4 == 0) {
+    // Only the bits are wanted and a row is short: 16 rows per wavefront.  (Measured against the
+    // one-row-per-wavefront kernel below, which counts with ballots on the scalar unit: 0.033 against
+    // 0.072 ms on 196 608 rows of K = 64, but no gain at K = 128 and 256, where the 2 K vector
+    // compare-and-adds a step cost here weigh as much as its scalar counts.)
+    const dim3 bgrid(static_cast<uint32_t>((nrows + 16 * kWavesPerBlock - 1) / (16 * kWavesPerBlock)));
+#define SEA_TOPK_BITS(NCT_)                                                                          \
+  do {                                                                                               \
+    if (s.geometry == 1) hipLaunchKernelGGL((topk_bits_kernel<NCT_, true>), bgrid, block, 0, st, s, A_hat, mbits);  \
+    else hipLaunchKernelGGL((topk_bits_kernel<NCT_, false>), bgrid, block, 0, st, s, A_hat, mbits);  \
+  } while (0)
+    if (s.K <= 32) SEA_TOPK_BITS(2);
+    else SEA_TOPK_BITS(4);
+#undef SEA_TOPK_BITS
+    return hipGetLastError();
+  }
   bool from_bits = false;
   if (s.grouping == 1) {
     // With a mask buffer at hand the slab kernel only selects; the lists are then written by the

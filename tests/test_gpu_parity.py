@@ -344,6 +344,48 @@ def test_exact_ties_take_the_lowest_columns(sea, case):
                 assert got[got >= 0].tolist() == want, (b, t, got, want)
 
 
+BITS_ONLY_CASES = [
+    # forward paths that ask the selection for bits only when no list is requested: fp32 tensors on
+    # the tiled attention, the per-row width geometry on key bits, bf16 shapes outside the fused estimator
+    (_wl("bits_f32_tile", 2, 2, 256, 32, 16, 5, causal=False, dtype="f32", pad_frac=0.3), False),
+    (_wl("bits_f32_tile_causal", 1, 3, 512, 64, 64, 9, dtype="f32"), False),
+    (_wl("bits_rw_bf16", 2, 3, 300, 64, 16, 3, geometry=1), False),
+    (_wl("bits_rw_bf16_narrow_rows", 1, 2, 777, 256, 192, 8, pad_frac=0.3, geometry=1), False),
+    (_wl("bits_rw_f32", 1, 2, 200, 64, 24, 5, dtype="f32", geometry=1), False),
+    (_wl("bits_bf16_m32", 1, 2, 512, 32, 64, 6), False),
+    (_wl("bits_bf16_K12", 2, 2, 384, 64, 12, 3, causal=False, pad_frac=0.3), False),
+    # exact ties (Q = K = 0: whole columns score the same), which the tie rule must order
+    (_wl("bits_ties_f32", 1, 2, 512, 64, 64, 9, dtype="f32"), True),
+    (_wl("bits_ties_rw", 1, 2, 512, 64, 64, 9, geometry=1), True),
+    (_wl("bits_ties_bidir", 2, 2, 512, 32, 32, 5, causal=False, pad_frac=0.3), True),
+]
+
+
+@pytest.mark.parametrize("wl,ties", BITS_ONLY_CASES, ids=lambda v: v.name if hasattr(v, "name") else str(v))
+def test_bits_only_selection_equals_the_list_selection(sea, wl, ties):
+    """Sec. 3.1 "Grouped Top-k^ Selection": when sea_forward is asked for no lists, the selection runs
+    in a kernel that leaves only the column bits (16 rows per wavefront).  Its bits must equal, word
+    for word, those of the call that also writes the lists (one wavefront per row), the oracle's
+    selection applied to the GPU's own scores, and the attention output must be the same."""
+    x = synth.make_inputs(wl)
+    if ties:
+        x["Q"] = torch.zeros_like(x["Q"])
+        x["K"] = torch.zeros_like(x["K"])
+    p, xd, g = _gpu_forward(sea, wl, x)
+    out = sea.alloc_outputs(p)
+    ws = sea.alloc_workspace(p)
+    sea.sea_forward(p, xd["Q"], xd["K"], xd["V"], xd["W"], out["O"], out["A_hat"], None, None, None, ws,
+                    mhat=out["mhat"])
+    torch.cuda.synchronize()
+    assert torch.equal(out["A_hat"].cpu(), g["A_hat"])
+    assert torch.equal(out["mhat"].cpu(), g["mhat"]), "bits-only selection differs from the list selection"
+    po = oracle_params(wl)
+    sl = None if x["seq_len"] is None else x["seq_len"].numpy()
+    sel_s, _, _ = oracle.topk_mask(po, g["A_hat"].numpy().astype(np.float64), seq_len=sl)
+    assert np.array_equal(_unpack_mhat(out["mhat"].cpu().numpy(), wl.K), _sel_to_mask(sel_s, wl.K))
+    assert torch.equal(out["O"].cpu(), g["O"])
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("causal", [False, True])
 def test_full_selection_reduces_to_dense_attention(sea, dtype, causal):
