@@ -410,9 +410,14 @@ int forward_stages(const sea_params* p, const void* Q, const void* K, const void
     uint32_t* mbits = mhat_opt ? mhat_opt : reinterpret_cast<uint32_t*>(w);
     w += align256(rows * ((s.K + 31) / 32) * sizeof(uint32_t));
     uint32_t* kb = reinterpret_cast<uint32_t*>(w);
-    e = launch_topk_mask(s, A_hat, sel_opt, idx_opt, cnt_opt, mbits, st);
-    if (e != hipSuccess) return fail_hip(e);
-    e = launch_keybits(s, mbits, kb, st);
+    if (s.grouping == 0) {
+      // per-query selection: the kernel that selects a row also expands it to its key bits
+      e = launch_topk_mask(s, A_hat, sel_opt, idx_opt, cnt_opt, mbits, st, kb);
+    } else {
+      e = launch_topk_mask(s, A_hat, sel_opt, idx_opt, cnt_opt, mbits, st);
+      if (e != hipSuccess) return fail_hip(e);
+      e = launch_keybits(s, mbits, kb, st);
+    }
     if (e != hipSuccess) return fail_hip(e);
     if (p->dtype == SEA_BF16)
       e = launch_tile_attn_keybits(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),

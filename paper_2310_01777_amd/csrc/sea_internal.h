@@ -61,8 +61,9 @@ hipError_t launch_rowwidth_mfma(const Shape& s, const uint16_t* Q, const uint16_
                                 float* A_hat, void* ws, hipStream_t st);
 
 // sel, idx, cnt, mbits may each be nullptr; mbits is [N][T][ceil(K/32)] selected-column bits
+// kb (per-query grouping, keybits_supported shapes only): also the selection expanded to one bit per key
 hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, int32_t* idx,
-                            int32_t* cnt, uint32_t* mbits, hipStream_t st);
+                            int32_t* cnt, uint32_t* mbits, hipStream_t st, uint32_t* kb = nullptr);
 
 // Tiled MFMA attention over the column-structured mask (bf16, K | T, power-of-two keys per column)
 bool tile_attn_supported(const Shape& s, sea_dtype dt, int32_t* rlog_out);

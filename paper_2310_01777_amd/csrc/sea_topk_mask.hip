@@ -14,6 +14,7 @@ namespace sea {
 namespace {
 
 constexpr int kWavesPerBlock = 4;
+constexpr int kKeyBitWordsMax = 128;  // key-bit rows of at most 128 words: T <= 4096
 
 __device__ __forceinline__ uint32_t ordered_key(float a) {
   a += 0.0f;  // -0 -> +0
@@ -26,6 +27,32 @@ __device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
   return __popcll(mask & ((1ull << lane) - 1ull));
 }
 
+// The keys a selected column c of a row emits (App. A.5.3: r = min(w, cap) keys start + floor(i w / r),
+// kept while <= jmax), ORed into the row's key-bit words in LDS.  Tw: the width the row's K columns
+// are spread over.
+__device__ __forceinline__ void or_column_keys(uint32_t* words, int32_t c, int32_t Tw, int32_t K, int32_t rep_cap,
+                                               int32_t jmax) {
+  const int32_t s0 = block_start(c, Tw, K);
+  const int32_t w = block_start(c + 1, Tw, K) - s0;
+  if (w <= 0) return;
+  const int32_t r = min(w, rep_cap);
+  if (r == w) {
+    // the whole column: keys s0 .. min(s0 + w - 1, jmax)
+    const int32_t j1 = min(s0 + w - 1, jmax);
+    if (s0 > j1) return;
+    for (int32_t wd = s0 >> 5; wd <= (j1 >> 5); ++wd) {
+      const int32_t lo = max(s0, wd << 5) & 31, hi = min(j1, (wd << 5) + 31) & 31;
+      const uint32_t m = (hi == 31 ? 0xffffffffu : ((1u << (hi + 1)) - 1u)) & ~((1u << lo) - 1u);
+      atomicOr(&words[wd], m);
+    }
+  } else {
+    for (int32_t i = 0; i < r; ++i) {
+      const int32_t j = s0 + static_cast<int32_t>((static_cast<int64_t>(i) * w) / r);
+      if (j <= jmax) atomicOr(&words[j >> 5], 1u << (j & 31));
+    }
+  }
+}
+
 // ROWW: per-row width geometry -- a causal row t spreads its K columns over its own t + 1 keys
 // (column c = keys [ceil(c (t+1) / K), ceil((c+1)(t+1) / K)); empty columns are no candidates).
 // FROMBITS: the selection was already made (mbits holds it, A_hat is not read); only the lists
@@ -33,9 +60,10 @@ __device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
 template <int SLOTS, bool ROWW, bool FROMBITS>
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
     Shape s, const float* __restrict__ A_hat, int32_t* __restrict__ sel, int32_t* __restrict__ idx,
-    int32_t* __restrict__ cnt, uint32_t* __restrict__ mbits) {
+    int32_t* __restrict__ cnt, uint32_t* __restrict__ mbits, uint32_t* __restrict__ kb, int32_t KWk) {
   __shared__ int32_t sh_sel[kWavesPerBlock][SLOTS * kWave];
   __shared__ int32_t sh_off[kWavesPerBlock][SLOTS * kWave + 1];
+  __shared__ uint32_t sh_kb[kWavesPerBlock][kKeyBitWordsMax];  // the row's key bits (kb != nullptr)
   const int wid = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
   const int64_t row = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wid;
@@ -56,6 +84,8 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
       for (int32_t x = lane; x < s.sel_stride; x += kWave) srow[x] = -1;
     if (mrow && !FROMBITS)
       for (int32_t x = lane; x < kw; x += kWave) mrow[x] = 0u;
+    if (kb)
+      for (int32_t x = lane; x < KWk; x += kWave) kb[row * KWk + x] = 0u;
     if (cnt && lane == 0) cnt[row] = 0;
     return;
   }
@@ -120,6 +150,15 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
   __builtin_amdgcn_wave_barrier();
   if (srow)
     for (int32_t x = lane; x < s.sel_stride; x += kWave) srow[x] = (x < n_sel) ? sh_sel[wid][x] : -1;
+  if (kb) {
+    // one bit per key of the row (what keybits_kernel writes from the column bits), straight from
+    // the compacted selection: every lane expands one selected column
+    for (int32_t x = lane; x < KWk; x += kWave) sh_kb[wid][x] = 0u;
+    __builtin_amdgcn_wave_barrier();
+    for (int32_t x = lane; x < n_sel; x += kWave) or_column_keys(sh_kb[wid], sh_sel[wid][x], Tw, s.K, s.rep_cap, jmax);
+    __builtin_amdgcn_wave_barrier();
+    for (int32_t x = lane; x < KWk; x += kWave) kb[row * KWk + x] = sh_kb[wid][x];
+  }
 
   if (!irow && !cnt) return;
   // expansion: selected column c emits r keys start + floor(i w / r), i < r
@@ -597,8 +636,6 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
 // One wavefront per row: lanes walk the K column bits, a selected column ORs its keys into the
 // row's words in LDS, the words leave as one coalesced run.  kb: [N][T][KWk], KWk = ceil(T / 32).
 // ------------------------------------------------------------------------------------------
-constexpr int kKeyBitWordsMax = 128;  // T <= 4096
-
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void keybits_kernel(Shape s, const uint32_t* __restrict__ mbits,
                                                                        uint32_t* __restrict__ kb, int32_t KWk) {
   __shared__ uint32_t words[kWavesPerBlock][kKeyBitWordsMax];
@@ -618,25 +655,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void keybits_kernel(Shape s,
     const uint32_t* mrow = mbits + row * kw;
     for (int32_t c = lane; c < s.K; c += kWave) {
       if (((mrow[c >> 5] >> (c & 31)) & 1u) == 0u) continue;
-      const int32_t s0 = block_start(c, Tw, s.K);
-      const int32_t w = block_start(c + 1, Tw, s.K) - s0;
-      if (w <= 0) continue;
-      const int32_t r = min(w, s.rep_cap);
-      if (r == w) {
-        // the whole column: keys s0 .. min(s0 + w - 1, jmax)
-        const int32_t j1 = min(s0 + w - 1, jmax);
-        if (s0 > j1) continue;
-        for (int32_t wd = s0 >> 5; wd <= (j1 >> 5); ++wd) {
-          const int32_t lo = max(s0, wd << 5) & 31, hi = min(j1, (wd << 5) + 31) & 31;
-          const uint32_t m = (hi == 31 ? 0xffffffffu : ((1u << (hi + 1)) - 1u)) & ~((1u << lo) - 1u);
-          atomicOr(&words[wid][wd], m);
-        }
-      } else {
-        for (int32_t i = 0; i < r; ++i) {
-          const int32_t j = s0 + static_cast<int32_t>((static_cast<int64_t>(i) * w) / r);
-          if (j <= jmax) atomicOr(&words[wid][j >> 5], 1u << (j & 31));
-        }
-      }
+      or_column_keys(words[wid], c, Tw, s.K, s.rep_cap, jmax);
     }
   }
   __builtin_amdgcn_wave_barrier();
@@ -659,13 +678,15 @@ hipError_t launch_keybits(const Shape& s, const uint32_t* mbits, uint32_t* kb, h
 }
 
 hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, int32_t* idx,
-                            int32_t* cnt, uint32_t* mbits, hipStream_t st) {
+                            int32_t* cnt, uint32_t* mbits, hipStream_t st, uint32_t* kb) {
+  if (kb && (!keybits_supported(s) || s.grouping != 0)) return hipErrorNotSupported;
+  const int32_t KWk = (s.T + 31) / 32;
   const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
   const uint32_t grid = static_cast<uint32_t>((nrows + kWavesPerBlock - 1) / kWavesPerBlock);
   const dim3 block(kWavesPerBlock * kWave);
   const int slots = (s.K + kWave - 1) / kWave;
   StageScope scope(SEA_STAGE_TOPK_MASK, st);
-  if (s.grouping == 0 && mbits && !sel && !idx && !cnt && s.K <= 64 && s.K % 4 == 0) {
+  if (s.grouping == 0 && mbits && !sel && !idx && !cnt && !kb && s.K <= 64 && s.K % 4 == 0) {
     // Only the bits are wanted and a row is short: 16 rows per wavefront.  (Measured against the
     // one-row-per-wavefront kernel below, which counts with ballots on the scalar unit: 0.033 against
     // 0.072 ms on 196 608 rows of K = 64, but no gain at K = 128 and 256, where the 2 K vector
@@ -706,16 +727,16 @@ hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, in
   do {                                                                                                             \
     if (from_bits && s.geometry == 1)                                                                              \
       hipLaunchKernelGGL((topk_mask_kernel<SL, true, true>), dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt,    \
-                         mbits);                                                                                   \
+                         mbits, kb, KWk);                                                                                   \
     else if (from_bits)                                                                                            \
       hipLaunchKernelGGL((topk_mask_kernel<SL, false, true>), dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt,   \
-                         mbits);                                                                                   \
+                         mbits, kb, KWk);                                                                                   \
     else if (s.geometry == 1)                                                                                      \
       hipLaunchKernelGGL((topk_mask_kernel<SL, true, false>), dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt,   \
-                         mbits);                                                                                   \
+                         mbits, kb, KWk);                                                                                   \
     else                                                                                                           \
       hipLaunchKernelGGL((topk_mask_kernel<SL, false, false>), dim3(grid), block, 0, st, s, A_hat, sel, idx, cnt,  \
-                         mbits);                                                                                   \
+                         mbits, kb, KWk);                                                                                   \
   } while (0)
   if (slots <= 1) SEA_TOPK(1);
   else if (slots <= 2) SEA_TOPK(2);
