@@ -90,6 +90,7 @@ __global__ __launch_bounds__(256) void mix_causal_kernel(Shape s, const T* __res
                                                          const float* __restrict__ s_mix, T* __restrict__ O) {
   __shared__ float red[32][kHeadDim + 1];
   __shared__ double offs[33][kHeadDim];  // exclusive prefix of the 32 slots (row 32: unused total)
+  __shared__ double before[4][kHeadDim];  // partial sums over the head's earlier chunks
   const int slot = threadIdx.x >> 3, dg = threadIdx.x & 7;
   const uint32_t chunks = (s.T + kChunkRows - 1) / kChunkRows;
   const int64_t head = blockIdx.x / chunks;
@@ -113,11 +114,24 @@ __global__ __launch_bounds__(256) void mix_causal_kernel(Shape s, const T* __res
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) red[slot][dg * 8 + i] = acc[i];
+  {
+    // sum of the earlier chunks of the head: the block's four waves take every fourth chunk each,
+    // two sums in flight per thread, so that the loads of a long sequence do not queue behind one another
+    const int d = threadIdx.x & 63, pt = threadIdx.x >> 6;
+    const double* ph = part + head * chunks * kHeadDim + d;
+    double a0 = 0.0, a1 = 0.0;
+    uint32_t c = static_cast<uint32_t>(pt);
+    for (; c + 4 < chunk; c += 8) {
+      a0 += ph[static_cast<size_t>(c) * kHeadDim];
+      a1 += ph[static_cast<size_t>(c + 4) * kHeadDim];
+    }
+    if (c < chunk) a0 += ph[static_cast<size_t>(c) * kHeadDim];
+    before[pt][d] = a0 + a1;
+  }
   __syncthreads();
   if (threadIdx.x < kHeadDim) {
     const int d = threadIdx.x;
-    double run = 0.0;
-    for (uint32_t c = 0; c < chunk; ++c) run += part[(head * chunks + c) * kHeadDim + d];
+    double run = (before[0][d] + before[1][d]) + (before[2][d] + before[3][d]);
     for (int q = 0; q < 32; ++q) {
       offs[q][d] = run;
       run += red[q][d];

@@ -466,6 +466,26 @@ def test_output_mix_matches_oracle(sea, dtype, causal):
     assert_close(to_np64(C_dev), want, TOL[dtype], "C_sea in place")
 
 
+@pytest.mark.parametrize("dtype,T", [("f32", 5000), ("bf16", 9300)])
+def test_output_mix_causal_long_sequence(sea, dtype, T):
+    """Sec. 3.1.1 "Output Calculation", causal: C_avg[t] is the running mean of V.  Long rows: the sum
+    over the earlier 256-row chunks of a head (20 and 37 chunks here) is split over the block's waves."""
+    wl = _wl("mix_long", 1, 2, T, 64, 50, 5, dtype=dtype, pad_frac=0.1)
+    x = synth.make_inputs(wl)
+    xd = _dev(x)
+    p = _params(sea, wl, xd["seq_len"])
+    gen = torch.Generator().manual_seed(3)
+    C = torch.randn(wl.B, wl.H, wl.T, wl.d, generator=gen).to(x["V"].dtype)
+    s_mix = torch.rand(wl.B, wl.H, wl.T, generator=gen)
+    ws = torch.empty(sea.sea_output_mix_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    O = torch.empty_like(xd["V"])
+    sea.sea_output_mix(p, C.cuda(), xd["V"], s_mix.cuda(), O, ws)
+    torch.cuda.synchronize()
+    want = oracle.output_mix(oracle_params(wl), to_np64(C), to_np64(x["V"]), s_mix.numpy(),
+                             seq_len=x["seq_len"].numpy())
+    assert_close(to_np64(O), want, TOL[dtype], "C_sea")
+
+
 def test_grouped_topk_mask_exact_on_planted_ties(sea):
     """Causal-per-batch grouping: the H x K slab of a time step is ranked as one list; equal scores
     go to the lower flattened index h K + c.  Bit-exact against the oracle with planted duplicates
