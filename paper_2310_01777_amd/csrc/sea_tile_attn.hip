@@ -111,8 +111,11 @@ constexpr int kVRow = 64;    // halfwords per staged V row: no padding; the 64-b
 // column, so every visited tile is fully used no matter how scattered the choices are.
 template <int RLOG, int MODE>
 __global__ __launch_bounds__(256, 4) void tile_attn_kernel(TileArgs a) {
-  constexpr bool DENSE = MODE != 0;   // no per-column bits to look up
+  constexpr bool DENSE = MODE == 1 || MODE == 2;  // no per-column bits to look up
   constexpr bool BUCKET = MODE == 2;
+  // MODE 3: one bit per (row, key) in HBM ([N][T][KW] words); a lane reads its row's two words of a
+  // step straight from memory one step ahead, nothing of the mask is parked in LDS
+  constexpr bool STREAM = MODE == 3;
   __shared__ __attribute__((aligned(16))) uint16_t Ks[2][kChunk * kKRow];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[2][kChunk * kVRow];
   // selected-column bits of the 128 rows, (KW + 1) words per row (K <= 1024: at most 16.5 KB)
@@ -167,7 +170,7 @@ __global__ __launch_bounds__(256, 4) void tile_attn_kernel(TileArgs a) {
   const uint16_t* Vh = a.V + head * static_cast<int64_t>(a.T) * kHeadDim;
   // mask words of the block's rows -> LDS (row stride KW + 1 words: conflict-free per-row reads)
   const int mstride = a.KW + 1;
-  if (!DENSE) {
+  if (!DENSE && !STREAM) {
     const int32_t row0 = wg_tile * 128;
     const uint32_t* msrc = a.mbits + (head * a.T + row0) * a.KW;
     const int32_t nwords = min(128, a.T - row0) * a.KW;
@@ -176,7 +179,14 @@ __global__ __launch_bounds__(256, 4) void tile_attn_kernel(TileArgs a) {
       Ms[r * mstride + wi] = x < nwords ? msrc[x] : 0u;
     }
   }
-  const uint32_t* mrow = DENSE ? nullptr : &Ms[(32 * wid + ql) * mstride];
+  const uint32_t* mrow = (DENSE || STREAM) ? nullptr : &Ms[(32 * wid + ql) * mstride];
+  const uint32_t* krow = STREAM ? a.mbits + (head * a.T + tq) * a.KW : nullptr;
+  uint32_t mw0 = 0u, mw1 = 0u, mn0 = 0u, mn1 = 0u;  // the row's words of this step and of the next
+  auto fetch_words = [&](int32_t step_, uint32_t& w0, uint32_t& w1) {
+    const int32_t wi = 2 * step_;
+    w0 = (row_active && wi < a.KW) ? krow[wi] : 0u;
+    w1 = (row_active && wi + 1 < a.KW) ? krow[wi + 1] : 0u;
+  };
 
   // keys the block / this wave can see: position <= min(last row, len - 1) when causal
   int32_t u_end_wg, u_end, j_free;
@@ -253,11 +263,17 @@ __global__ __launch_bounds__(256, 4) void tile_attn_kernel(TileArgs a) {
   if (nsteps > 0) {
     SEA_FETCH(0);
     SEA_PARK(0);
+    if (STREAM) fetch_words(0, mn0, mn1);
   }
   __syncthreads();
   for (int32_t step = 0; step < nsteps; ++step) {
     const int stage = step & 1;
     if (step + 1 < nsteps) SEA_FETCH(step + 1);
+    if (STREAM) {
+      mw0 = mn0;
+      mw1 = mn1;
+      if (step + 1 < nsteps) fetch_words(step + 1, mn0, mn1);
+    }
 #pragma unroll
     for (int sc = 0; sc < 2; ++sc) {
       const int32_t u0 = ubase + step * kChunk + 32 * sc;
@@ -266,7 +282,7 @@ __global__ __launch_bounds__(256, 4) void tile_attn_kernel(TileArgs a) {
       uint32_t bits = 0xffffffffu;
       if (!DENSE) {
         const int32_t col0 = u0 >> (RLOG < 5 ? RLOG : a.rlog);  // first column of the sub-chunk
-        const uint32_t word = row_active ? mrow[col0 >> 5] : 0u;
+        const uint32_t word = STREAM ? (sc == 0 ? mw0 : mw1) : (row_active ? mrow[col0 >> 5] : 0u);
         bits = word >> (col0 & 31);
         constexpr uint32_t ncol = RLOG >= 5 ? 1u : (32u >> RLOG);
         constexpr uint32_t cmask = ncol >= 32 ? 0xffffffffu : ((1u << ncol) - 1u);
@@ -953,8 +969,9 @@ hipError_t launch_tile_attn_f32(const Shape& s, const float* Q, const float* K, 
 
 // Masks without column structure shared by the rows (per-row width geometry): the selection
 // arrives as one bit per (row, key), and the same kernel runs with every key its own "column"
-// (one key per column, column width 1) -- the walk of the dense kernel with per-key mask bits.
-// The block's mask words (128 rows x ceil(T / 32)) must fit LDS beside the staging buffers.
+// (one key per column, column width 1) -- the walk of the dense kernel with per-key mask bits,
+// which every lane reads for its own row one step ahead (no mask words in LDS: four blocks per CU
+// as in the other modes).  T <= 4096 is the limit of the kernels that write the bits.
 bool tile_attn_keybits_supported(const Shape& s, sea_dtype) { return s.T <= 4096; }
 
 // the same for fp32 tensors
@@ -981,13 +998,7 @@ hipError_t launch_tile_attn_keybits(const Shape& s, const uint16_t* Q, const uin
   a.group_heads = group_heads_for(s.N, s.T);
   a.c = s.scale * kLog2e;
   const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 127) / 128)), block(256);
-  const size_t shm = static_cast<size_t>(128) * (a.KW + 1) * sizeof(uint32_t);
-  if (shm > (64u << 10)) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&tile_attn_kernel<0, 0>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(shm));
-    if (e != hipSuccess) return e;
-  }
-  hipLaunchKernelGGL((tile_attn_kernel<0, 0>), grid, block, shm, st, a);
+  hipLaunchKernelGGL((tile_attn_kernel<0, 3>), grid, block, 0, st, a);
   return hipGetLastError();
 }
 

@@ -672,7 +672,7 @@ def test_row_width_geometry(sea, wl):
     attention within tolerance, end to end identical lists except at near-ties."""
     x = synth.make_inputs(wl)
     p, xd, g = _gpu_forward(sea, wl, x)
-    # tiled attention on per-(row, key) bits while a block's mask words fit LDS, else per-row key lists
+    # tiled attention on per-(row, key) bits for T <= 4096 (the kernels that write the bits keep a row in LDS), else per-row key lists
     assert sea.sea_attention_path(p) == (3 if wl.T <= 4096 else 0)
     rows = None if wl.T <= 1024 else sorted(set(range(0, 140)) | set(range(wl.T - 40, wl.T))
                                             | set(range(1000, wl.T, 97)))
