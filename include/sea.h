@@ -158,7 +158,7 @@ int sea_sparse_attn(const sea_params* p, const void* Q, const void* K, const voi
  * ([B][H][T][ceil(T / 32)] device words) is set iff key j is one of the r = min(w, cap) keys
  * start + floor(i w / r) of a selected column of that row, j <= t when causal, j < seq_len; rows
  * t >= seq_len are zero.  This is the mask sea_forward's attention stage consumes when
- * sea_attention_path(p) == 3.  Needs T <= 4096 (SEA_ENOTSUP otherwise); no workspace.
+ * sea_attention_path(p) == 3.  Needs T <= 8192 (SEA_ENOTSUP otherwise); no workspace.
  */
 int sea_key_mask(const sea_params* p, const uint32_t* mhat, uint32_t* key_bits, void* hip_stream);
 
@@ -344,7 +344,8 @@ int sea_last_hip_error(void);
  * number of keys per selected column, fixed key buckets), 2 = its fp32 counterpart (same shapes,
  * fp32 tensors: logits on the fp64 matrix cores, weights and P V in fp32; sea_forward only),
  * 3 = the same tiled kernel on a per-(row, key) bit mask expanded from the selection (per-row width
- * geometry, T <= 4096, either tensor type; sea_forward only), 0 = the per-row index-list kernel.
+ * geometry, T <= 8192 for bf16 and T <= 4096 for fp32 tensors; sea_forward only), 0 = the per-row
+ * index-list kernel.
  * Negative: the sea_status the parameters would be rejected with.  Pure host computation.
  */
 int sea_attention_path(const sea_params* p);

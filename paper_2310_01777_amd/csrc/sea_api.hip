@@ -124,7 +124,7 @@ bool scores_stay_on_chip(const sea_params* p, const Shape& s) {
 // Scratch of the whole forward pass: estimator scratch, A_hat, then either the tiled path's mask
 // bits and bucket tables or the row-list path's idx + cnt.  `lean`: the caller keeps no
 // intermediate, so the A_hat part is dropped where the scores stay on chip.
-// per-row width geometry, sequences short enough for a block's per-key mask words to fit LDS:
+// per-row width geometry, sequences of at most 8192 (bf16) or 4096 (fp32) keys:
 // the selection is expanded to one bit per key and the tiled attention kernel runs on those
 bool keybit_path(const Shape& s, sea_dtype dt) {
   return s.geometry == 1 && keybits_supported(s) && tile_attn_keybits_supported(s, dt);

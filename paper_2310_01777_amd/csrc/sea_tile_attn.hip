@@ -971,8 +971,10 @@ hipError_t launch_tile_attn_f32(const Shape& s, const float* Q, const float* K, 
 // arrives as one bit per (row, key), and the same kernel runs with every key its own "column"
 // (one key per column, column width 1) -- the walk of the dense kernel with per-key mask bits,
 // which every lane reads for its own row one step ahead (no mask words in LDS: four blocks per CU
-// as in the other modes).  T <= 4096 is the limit of the kernels that write the bits.
-bool tile_attn_keybits_supported(const Shape& s, sea_dtype) { return s.T <= 4096; }
+// as in the other modes).  T <= 8192 is the limit of the kernels that write the bits (beyond it the
+// quadratic walk also loses to per-row lists for the budgets in use); the fp32 kernel keeps the mask
+// words of its 16 rows in LDS, 128 per row.
+bool tile_attn_keybits_supported(const Shape& s, sea_dtype dt) { return s.T <= (dt == SEA_BF16 ? 8192 : 4096); }
 
 // the same for fp32 tensors
 hipError_t launch_tile_attn_f32_keybits(const Shape& s, const float* Q, const float* K, const float* V,

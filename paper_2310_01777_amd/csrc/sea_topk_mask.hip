@@ -14,7 +14,7 @@ namespace sea {
 namespace {
 
 constexpr int kWavesPerBlock = 4;
-constexpr int kKeyBitWordsMax = 128;  // key-bit rows of at most 128 words: T <= 4096
+constexpr int kKeyBitWordsMax = 256;  // key-bit rows of at most 256 words: T <= 8192
 
 __device__ __forceinline__ uint32_t ordered_key(float a) {
   a += 0.0f;  // -0 -> +0

@@ -109,7 +109,9 @@ def test_argument_validation_returns_codes_not_crashes(sea):
     assert sea.sea_attention_path(P(1, 1, 64, 64, 32, 16, 17)) == sea.SEA_EINVAL
     # per-row width geometry: causal only, key lists for the attention
     assert sea.sea_attention_path(P(1, 2, 2048, 64, 128, 128, 64, geometry=1)) == 3
-    assert sea.sea_attention_path(P(1, 2, 8192, 64, 128, 128, 64, geometry=1)) == 0
+    assert sea.sea_attention_path(P(1, 2, 8192, 64, 128, 128, 64, geometry=1)) == 3
+    assert sea.sea_attention_path(P(1, 2, 8192, 64, 128, 128, 64, geometry=1, dtype="f32")) == 0
+    assert sea.sea_attention_path(P(1, 2, 16384, 64, 128, 128, 64, geometry=1)) == 0
     for bad, code in ((P(1, 2, 256, 64, 64, 16, 4, causal=False, geometry=1), sea.SEA_EINVAL),
                       (P(1, 2, 256, 64, 64, 16, 4, geometry=2), sea.SEA_EINVAL)):
         with pytest.raises(sea.SeaError) as e:

@@ -672,8 +672,8 @@ def test_row_width_geometry(sea, wl):
     attention within tolerance, end to end identical lists except at near-ties."""
     x = synth.make_inputs(wl)
     p, xd, g = _gpu_forward(sea, wl, x)
-    # tiled attention on per-(row, key) bits for T <= 4096 (the kernels that write the bits keep a row in LDS), else per-row key lists
-    assert sea.sea_attention_path(p) == (3 if wl.T <= 4096 else 0)
+    # tiled attention on per-(row, key) bits for T <= 8192 (fp32 tensors: 4096), else per-row key lists
+    assert sea.sea_attention_path(p) == (3 if wl.T <= (8192 if wl.dtype == "bf16" else 4096) else 0)
     rows = None if wl.T <= 1024 else sorted(set(range(0, 140)) | set(range(wl.T - 40, wl.T))
                                             | set(range(1000, wl.T, 97)))
     po = oracle_params(wl)
@@ -721,7 +721,7 @@ def test_row_width_geometry(sea, wl):
 KEY_MASK_CASES = [w for w in ROW_WIDTH_CASES[:13] if w.T <= 1200] + [
     _wl("km_fixed_budget", 2, 2, 512, 64, 32, 5, k_budget=12),                 # fixed buckets, 2 of 16 keys a column
     _wl("km_fixed_ragged_pad", 1, 3, 300, 64, 17, 4, causal=False, pad_frac=0.3),
-    _wl("km_words_edge", 1, 1, 4096, 64, 128, 9, geometry=1),                  # the longest supported rows
+    _wl("km_words_edge", 1, 1, 8192, 64, 128, 9, geometry=1),                  # the longest supported rows
 ]
 
 
@@ -750,9 +750,9 @@ def test_key_mask_bits(sea, wl):
 
 
 def test_key_mask_rejects_long_rows(sea):
-    p = sea.SeaParams(B=1, H=1, T=8192, d=64, m=64, K=64, k_hat=4, causal=True, scale=0.125, dtype="bf16", geometry=1)
-    mh = torch.zeros(1, 1, 8192, 2, dtype=torch.int32, device="cuda")
-    kb = torch.zeros(1, 1, 8192, 256, dtype=torch.int32, device="cuda")
+    p = sea.SeaParams(B=1, H=1, T=8224, d=64, m=64, K=64, k_hat=4, causal=True, scale=0.125, dtype="bf16", geometry=1)
+    mh = torch.zeros(1, 1, 8224, 2, dtype=torch.int32, device="cuda")
+    kb = torch.zeros(1, 1, 8224, 257, dtype=torch.int32, device="cuda")
     with pytest.raises(sea.SeaError) as e:
         sea.sea_key_mask(p, mh, kb)
     assert e.value.status == sea.SEA_ENOTSUP
