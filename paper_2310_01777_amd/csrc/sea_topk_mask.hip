@@ -22,6 +22,13 @@ __device__ __forceinline__ uint32_t ordered_key(float a) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Blocks are dealt per head: blocks_per_head(T, rows a block takes) of them each, so that the head
+// and the time step of a row come from 32-bit divisions of the block index rather than from a
+// 64-bit row index divided by T and H.
+__host__ __device__ __forceinline__ uint32_t blocks_per_head(int32_t T, int32_t rows_per_block) {
+  return static_cast<uint32_t>((T + rows_per_block - 1) / rows_per_block);
+}
+
 __device__ __forceinline__ int popc64(uint64_t x) { return __popcll(x); }
 __device__ __forceinline__ int lanes_below(uint64_t mask, int lane) {
   return __popcll(mask & ((1ull << lane) - 1ull));
@@ -66,11 +73,12 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
   __shared__ uint32_t sh_kb[kWavesPerBlock][kKeyBitWordsMax];  // the row's key bits (kb != nullptr)
   const int wid = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
-  const int64_t row = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wid;
-  const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
-  if (row >= nrows) return;  // whole wave leaves; no block-wide barrier is used below
-  const int32_t t = static_cast<int32_t>(row % s.T);
-  const int32_t b = static_cast<int32_t>((row / s.T) / s.H);
+  const uint32_t bph = blocks_per_head(s.T, kWavesPerBlock);
+  const uint32_t head = blockIdx.x / bph;
+  const int32_t t = static_cast<int32_t>(blockIdx.x - head * bph) * kWavesPerBlock + wid;
+  if (t >= s.T) return;  // whole wave leaves; no block-wide barrier is used below
+  const int64_t row = static_cast<int64_t>(head) * s.T + t;
+  const int32_t b = static_cast<int32_t>(head / static_cast<uint32_t>(s.H));
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
   int32_t* irow = idx ? idx + row * s.L : nullptr;
   int32_t* srow = sel ? sel + row * s.sel_stride : nullptr;
@@ -241,14 +249,16 @@ template <int NCT, bool ROWW>
 __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_bits_kernel(Shape s, const float* __restrict__ A_hat,
                                                                          uint32_t* __restrict__ mbits) {
   const int lane = threadIdx.x & 63, lr = lane & 15, lg = lane >> 4;
-  const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
-  const int64_t row0 = (static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6)) * 16;
-  if (row0 >= nrows) return;  // whole wave leaves; no block-wide barrier is used below
-  const int64_t row = min(row0 + lr, nrows - 1);
-  const int32_t t = static_cast<int32_t>(row % s.T);
-  const int32_t b = static_cast<int32_t>((row / s.T) / s.H);
+  const uint32_t bph = blocks_per_head(s.T, 16 * kWavesPerBlock);
+  const uint32_t head = blockIdx.x / bph;
+  const int32_t t0 = (static_cast<int32_t>(blockIdx.x - head * bph) * kWavesPerBlock + static_cast<int32_t>(threadIdx.x >> 6)) * 16;
+  if (t0 >= s.T) return;  // whole wave leaves; no block-wide barrier is used below
+  const bool in_head = t0 + lr < s.T;
+  const int32_t t = min(t0 + lr, s.T - 1);
+  const int64_t row = static_cast<int64_t>(head) * s.T + t;
+  const int32_t b = static_cast<int32_t>(head / static_cast<uint32_t>(s.H));
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
-  const bool active = row0 + lr < nrows && t < len;
+  const bool active = in_head && t < len;
   const int32_t jmax = (s.causal && t < len - 1) ? t : len - 1;  // last admissible key
   const int32_t Tw = ROWW ? t + 1 : s.T;                         // width the K columns are spread over
   const int32_t ncand = active ? bucket_of(jmax, Tw, s.K) + 1 : 0;
@@ -341,7 +351,7 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_bits_kernel(Shape 
     if (2 * j + 1 < NCT) part |= nib[2 * j + 1] << (16 + 4 * lg);
     words[j] = rows_or_u(part);
   }
-  if (lg != 0 || row0 + lr >= nrows) return;
+  if (lg != 0 || !in_head) return;
   uint32_t* mrow = mbits + row * kw;
 #pragma unroll
   for (int j = 0; j < kWords; ++j)
@@ -640,11 +650,12 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void keybits_kernel(Shape s,
                                                                        uint32_t* __restrict__ kb, int32_t KWk) {
   __shared__ uint32_t words[kWavesPerBlock][kKeyBitWordsMax];
   const int wid = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int64_t row = static_cast<int64_t>(blockIdx.x) * kWavesPerBlock + wid;
-  const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
-  if (row >= nrows) return;  // whole wave leaves; only wave-level barriers below
-  const int32_t t = static_cast<int32_t>(row % s.T);
-  const int32_t b = static_cast<int32_t>((row / s.T) / s.H);
+  const uint32_t bph = blocks_per_head(s.T, kWavesPerBlock);
+  const uint32_t head = blockIdx.x / bph;
+  const int32_t t = static_cast<int32_t>(blockIdx.x - head * bph) * kWavesPerBlock + wid;
+  if (t >= s.T) return;  // whole wave leaves; only wave-level barriers below
+  const int64_t row = static_cast<int64_t>(head) * s.T + t;
+  const int32_t b = static_cast<int32_t>(head / static_cast<uint32_t>(s.H));
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
   const int32_t kw = (s.K + 31) / 32;
   for (int32_t x = lane; x < KWk; x += kWave) words[wid][x] = 0u;
@@ -670,8 +681,7 @@ size_t keybits_bytes(const Shape& s) {
 }
 hipError_t launch_keybits(const Shape& s, const uint32_t* mbits, uint32_t* kb, hipStream_t st) {
   if (!keybits_supported(s)) return hipErrorNotSupported;
-  const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
-  const uint32_t grid = static_cast<uint32_t>((nrows + kWavesPerBlock - 1) / kWavesPerBlock);
+  const uint32_t grid = static_cast<uint32_t>(s.N) * blocks_per_head(s.T, kWavesPerBlock);
   StageScope scope(SEA_STAGE_TOPK_MASK, st);
   hipLaunchKernelGGL(keybits_kernel, dim3(grid), dim3(kWavesPerBlock * kWave), 0, st, s, mbits, kb, (s.T + 31) / 32);
   return hipGetLastError();
@@ -681,8 +691,7 @@ hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, in
                             int32_t* cnt, uint32_t* mbits, hipStream_t st, uint32_t* kb) {
   if (kb && (!keybits_supported(s) || s.grouping != 0)) return hipErrorNotSupported;
   const int32_t KWk = (s.T + 31) / 32;
-  const int64_t nrows = static_cast<int64_t>(s.N) * s.T;
-  const uint32_t grid = static_cast<uint32_t>((nrows + kWavesPerBlock - 1) / kWavesPerBlock);
+  const uint32_t grid = static_cast<uint32_t>(s.N) * blocks_per_head(s.T, kWavesPerBlock);
   const dim3 block(kWavesPerBlock * kWave);
   const int slots = (s.K + kWave - 1) / kWave;
   StageScope scope(SEA_STAGE_TOPK_MASK, st);
@@ -691,7 +700,7 @@ hipError_t launch_topk_mask(const Shape& s, const float* A_hat, int32_t* sel, in
     // one-row-per-wavefront kernel below, which counts with ballots on the scalar unit: 0.033 against
     // 0.072 ms on 196 608 rows of K = 64, but no gain at K = 128 and 256, where the 2 K vector
     // compare-and-adds a step cost here weigh as much as its scalar counts.)
-    const dim3 bgrid(static_cast<uint32_t>((nrows + 16 * kWavesPerBlock - 1) / (16 * kWavesPerBlock)));
+    const dim3 bgrid(static_cast<uint32_t>(s.N) * blocks_per_head(s.T, 16 * kWavesPerBlock));
 #define SEA_TOPK_BITS(NCT_)                                                                          \
   do {                                                                                               \
     if (s.geometry == 1) hipLaunchKernelGGL((topk_bits_kernel<NCT_, true>), bgrid, block, 0, st, s, A_hat, mbits);  \
