@@ -654,18 +654,36 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
       hp[2 * ct] = __builtin_bit_cast(ushort2v, __builtin_amdgcn_perm(key[ct][1], key[ct][0], 0x07060302u)); \
       hp[2 * ct + 1] = __builtin_bit_cast(ushort2v, __builtin_amdgcn_perm(key[ct][3], key[ct][2], 0x07060302u)); \
     }                                                                                            \
-    _Pragma("unroll 1") for (int bit = 29; bit >= 16; --bit) {                                    \
-      SEA_SEARCH_STEP(                                                                           \
-        const uint32_t th = trial >> 16;                                                         \
-        const ushort2v th2 = __builtin_bit_cast(ushort2v, th | (th << 16));                      \
-        uint32_t below = 0;                                                                      \
-        _Pragma("unroll") for (int pr = 0; pr < 2 * (NT_); pr += 2) {                             \
-          const uint32_t d0 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr] - th2)); \
-          const uint32_t d1 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr + 1] - th2)); \
-          /* byte selectors 8..11 give 0x00 / 0xff by the sign of bytes 1, 3, 5, 7: eight bits a key */ \
-          below += static_cast<uint32_t>(__popc(__builtin_amdgcn_perm(d1, d0, 0x0b0a0908u)));    \
-        }                                                                                        \
-        cnt = 4u * static_cast<uint32_t>(NT_) - (below >> 3);)                                   \
+    /* Count of this lane's keys at or above a trial whose low half is zero. */                  \
+    auto count_high = [&](uint32_t trial_) {                                                     \
+      const uint32_t th = trial_ >> 16;                                                          \
+      const ushort2v th2 = __builtin_bit_cast(ushort2v, th | (th << 16));                        \
+      uint32_t below = 0;                                                                        \
+      _Pragma("unroll") for (int pr = 0; pr < 2 * (NT_); pr += 2) {                               \
+        const uint32_t d0 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr] - th2));   \
+        const uint32_t d1 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr + 1] - th2)); \
+        /* byte selectors 8..11 give 0x00 / 0xff by the sign of bytes 1, 3, 5, 7: eight bits a key */ \
+        below += static_cast<uint32_t>(__popc(__builtin_amdgcn_perm(d1, d0, 0x0b0a0908u)));      \
+      }                                                                                          \
+      return 4u * static_cast<uint32_t>(NT_) - (below >> 3);                                     \
+    };                                                                                           \
+    /* Bits 29..27 at once: a row whose quota of scores lies at or above 2^-15 (rows sum to 1    \
+       over at most 256 columns, so nearly every row) would take all three bits, because the     \
+       count only grows as the trial falls; one count then stands for three steps.  A wave with  \
+       a row that fails the test searches from bit 29 as before. */                              \
+    int bit_top = 29;                                                                            \
+    {                                                                                            \
+      const bool pend = (cge != nsel) && (nsel != 0u);                                           \
+      const uint32_t trial = 0xb8000000u;                                                        \
+      const uint32_t cnt = rows_sum_u(count_high(trial));                                        \
+      if (__ballot(pend && cnt < nsel) == 0ull) {                                                \
+        tau = pend ? trial : tau;                                                                \
+        cge = pend ? cnt : cge;                                                                  \
+        bit_top = 26;                                                                            \
+      }                                                                                          \
+    }                                                                                            \
+    _Pragma("unroll 1") for (int bit = bit_top; bit >= 16; --bit) {                               \
+      SEA_SEARCH_STEP(cnt = count_high(trial);)                                                  \
     }                                                                                            \
   }                                                                                              \
   _Pragma("unroll 1") for (int bit = 15; bit >= 0; --bit) {                                       \
