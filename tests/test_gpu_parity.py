@@ -277,6 +277,36 @@ GROUPED_CASES = [
 ]
 
 
+def _random_grouped_cases(n, seed):
+    """Seeded draw of valid small shapes for causal-per-batch selection: slabs of H K entries from a
+    few dozen to the limit of 16384, K that does and does not divide T, both directions, padding."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        K = int(rng.choice([3, 8, 16, 24, 32, 64, 100, 128, 256]))
+        H = int(rng.choice([1, 2, 3, 4, 8, 12, 32]))
+        if H * K > 16384:
+            continue
+        T = K * int(rng.choice([1, 2, 4, 8, 16, 3])) if rng.random() < 0.7 else int(rng.integers(K, 600))
+        if T < 16 or T > 1024:
+            continue
+        m = int(rng.choice([32, 64, 128, 256]))
+        k_hat = int(min(K, rng.choice([1, 2, 3, 5, 8, 13, 32])))
+        k_budget = int(rng.choice([0, 0, 8, 33, 64]))
+        causal = bool(rng.random() < 0.7)
+        pad = float(rng.choice([0.0, 0.3]))
+        dtype = "f32" if rng.random() < 0.2 else "bf16"
+        out.append(_wl(f"grp_rnd{len(out)}_H{H}_T{T}_K{K}_m{m}_kh{k_hat}_kb{k_budget}_c{int(causal)}_p{int(pad > 0)}_{dtype}",
+                       int(rng.integers(1, 3)), H, T, m, K, k_hat, k_budget=k_budget, causal=causal,
+                       pad_frac=pad, dtype=dtype, grouping=1))
+    return out
+
+
+# SEA_GRP_RANDOM_CASES / SEA_GRP_RANDOM_SEED widen or move this draw for a one-off sweep
+GROUPED_CASES += _random_grouped_cases(int(os.environ.get("SEA_GRP_RANDOM_CASES", "12")),
+                                       int(os.environ.get("SEA_GRP_RANDOM_SEED", "4242")))
+
+
 @pytest.mark.parametrize("wl", GROUPED_CASES, ids=lambda w: w.name)
 def test_causal_per_batch_grouping(sea, wl):
     """Sec. 3.1 causal-per-batch selection: the H rows of a time step share a quota of H k^."""
