@@ -109,8 +109,13 @@ constexpr int kVRow = 64;    // halfwords per staged V row: no padding; the 64-b
 // bits).  MODE 2: "bucket" form for k^ = 1 -- every row selected exactly one column, rows are
 // grouped by that column, and a block takes 128 rows of one bucket against the r keys of its
 // column, so every visited tile is fully used no matter how scattered the choices are.
-template <int RLOG, int MODE>
-__global__ __launch_bounds__(256, 4) void tile_attn_kernel(TileArgs a) {
+template <int RLOG, int MODE, int NW = 4>
+__global__ __launch_bounds__(64 * NW, 16 / NW) void tile_attn_kernel(TileArgs a) {
+  // NW = waves per block: 4 (128 query rows) or 8 (256 rows sharing every staged key step, which
+  // halves the bytes a head's keys and values travel from the L2s to LDS; two blocks per CU)
+  static_assert(NW == 4 || NW == 8, "four or eight waves per block");
+  static_assert(MODE != 2 || NW == 4, "bucket chunks are 128 rows");
+  constexpr int kRows = 32 * NW, kThreads = 64 * NW;
   constexpr bool DENSE = MODE == 1 || MODE == 2;  // no per-column bits to look up
   constexpr bool BUCKET = MODE == 2;
   // MODE 3: one bit per (row, key) in HBM ([N][T][KW] words); a lane reads its row's two words of a
@@ -123,7 +128,7 @@ __global__ __launch_bounds__(256, 4) void tile_attn_kernel(TileArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, keep it scalar
   const int ql = lane & 31, g = lane >> 5;
-  const uint32_t wgs = (a.T + 127) / 128;  // blocks per head
+  const uint32_t wgs = (a.T + kRows - 1) / kRows;  // blocks per head
   int64_t head;
   int32_t wg_tile = 0, q0 = 0, t, eslot = 0;
   int32_t ubase = 0, ulim = a.U;  // compact keys this block may touch: [ubase, ulim)
@@ -149,7 +154,7 @@ __global__ __launch_bounds__(256, 4) void tile_attn_kernel(TileArgs a) {
     const uint32_t nh = min(static_cast<uint32_t>(a.group_heads), static_cast<uint32_t>(a.N) - grp * a.group_heads);
     head = static_cast<int64_t>(grp) * a.group_heads + rem % nh;
     wg_tile = static_cast<int32_t>(wgs - 1 - rem / nh);
-    q0 = wg_tile * 128 + 32 * wid;  // first row of this wave
+    q0 = wg_tile * kRows + 32 * wid;  // first row of this wave
     t = q0 + ql;
   }
   const int32_t b = static_cast<int32_t>(head / a.H);
@@ -171,10 +176,10 @@ __global__ __launch_bounds__(256, 4) void tile_attn_kernel(TileArgs a) {
   // mask words of the block's rows -> LDS (row stride KW + 1 words: conflict-free per-row reads)
   const int mstride = a.KW + 1;
   if (!DENSE && !STREAM) {
-    const int32_t row0 = wg_tile * 128;
+    const int32_t row0 = wg_tile * kRows;
     const uint32_t* msrc = a.mbits + (head * a.T + row0) * a.KW;
-    const int32_t nwords = min(128, a.T - row0) * a.KW;
-    for (int32_t x = tid; x < 128 * a.KW; x += 256) {
+    const int32_t nwords = min(kRows, a.T - row0) * a.KW;
+    for (int32_t x = tid; x < kRows * a.KW; x += kThreads) {
       const int32_t r = x / a.KW, wi = x - r * a.KW;
       Ms[r * mstride + wi] = x < nwords ? msrc[x] : 0u;
     }
@@ -199,7 +204,7 @@ __global__ __launch_bounds__(256, 4) void tile_attn_kernel(TileArgs a) {
     for (int off = 32; off >= 1; off >>= 1) jm = min(jm, __shfl_xor(jm, off, 64));
     j_free = jm;
   } else {
-    const int32_t wg_hi = min(wg_tile * 128 + 127, a.T - 1);
+    const int32_t wg_hi = min(wg_tile * kRows + kRows - 1, a.T - 1);
     u_end_wg = compact_count(a.causal ? min(wg_hi, len - 1) : len - 1, a.rlog, a.w);
     const int32_t t_hi = min(q0 + 31, a.T - 1);
     u_end = q0 < a.T ? compact_count(a.causal ? min(t_hi, len - 1) : len - 1, a.rlog, a.w) : 0;
@@ -209,12 +214,12 @@ __global__ __launch_bounds__(256, 4) void tile_attn_kernel(TileArgs a) {
   const int32_t my_jmax = a.causal ? min(t, len - 1) : len - 1;
   const int32_t nsteps = (u_end_wg - ubase + kChunk - 1) / kChunk;
 
-  // staging roles: 16-byte part tid & 7 of the K and V rows (tid >> 3) and (tid >> 3) + 32 of the
-  // step.  V is parked as it lies in memory; the product reads it through the LDS transpose read.
+  // staging roles: 16-byte part tid & 7 of the K and V rows (tid >> 3) and, with four waves,
+  // (tid >> 3) + 32 of the step (eight waves cover the 64 rows in one go).  V is parked as it lies in memory; the product reads it through the LDS transpose read.
   // Slots past the list re-read its last key; their scores are masked.
   const int srow = tid >> 3, spart = tid & 7;
   const int vpart = spart ^ (((srow >> 1) & 1) << 2);  // V rows 2, 3 (mod 4): halves exchanged
-  uint4 kreg0, kreg1, vreg0, vreg1;
+  uint4 kreg0, kreg1 = {0u, 0u, 0u, 0u}, vreg0, vreg1 = {0u, 0u, 0u, 0u};
   // With at most 64 keys per column a step of 64 compact keys advances every slot's position by
   // the same amount, so the four row offsets (bytes inside the head, 32 bits) just step by a
   // constant; they are clamped to the last row, since slots past the list only need an address
@@ -233,20 +238,20 @@ __global__ __launch_bounds__(256, 4) void tile_attn_kernel(TileArgs a) {
   do {                                                                                               \
     if (!linear) {                                                                                   \
       offa = SEA_SLOT_OFF(srow, step_);                                                              \
-      offb = SEA_SLOT_OFF(srow + 32, step_);                                                         \
+      if (NW == 4) offb = SEA_SLOT_OFF(srow + 32, step_);                                            \
     }                                                                                                \
     kreg0 = *reinterpret_cast<const uint4*>(Kb + min(offa, off_max));                                \
-    kreg1 = *reinterpret_cast<const uint4*>(Kb + min(offb, off_max));                                \
+    if (NW == 4) kreg1 = *reinterpret_cast<const uint4*>(Kb + min(offb, off_max));                   \
     vreg0 = *reinterpret_cast<const uint4*>(Vb + min(offa, off_max));                                \
-    vreg1 = *reinterpret_cast<const uint4*>(Vb + min(offb, off_max));                                \
+    if (NW == 4) vreg1 = *reinterpret_cast<const uint4*>(Vb + min(offb, off_max));                   \
     offa += off_step; offb += off_step;                                                              \
   } while (0)
 #define SEA_PARK(stage_)                                                                             \
   do {                                                                                               \
     *reinterpret_cast<uint4*>(&Ks[stage_][srow * kKRow + spart * 8]) = kreg0;                         \
-    *reinterpret_cast<uint4*>(&Ks[stage_][(srow + 32) * kKRow + spart * 8]) = kreg1;                  \
+    if (NW == 4) *reinterpret_cast<uint4*>(&Ks[stage_][(srow + 32) * kKRow + spart * 8]) = kreg1;     \
     *reinterpret_cast<uint4*>(&Vs[stage_][srow * kVRow + vpart * 8]) = vreg0;                         \
-    *reinterpret_cast<uint4*>(&Vs[stage_][(srow + 32) * kVRow + vpart * 8]) = vreg1;                  \
+    if (NW == 4) *reinterpret_cast<uint4*>(&Vs[stage_][(srow + 32) * kVRow + vpart * 8]) = vreg1;     \
   } while (0)
 
   floatx16 oacc[2];
@@ -602,6 +607,17 @@ int32_t group_heads_for(int32_t N, int64_t U) {
   if (per_xcd < 1) per_xcd = 1;
   const int64_t g = 8 * per_xcd;
   return static_cast<int32_t>(g < N ? g : N);
+}
+
+#ifndef SEA_NW8_MIN_BLOCKS
+#define SEA_NW8_MIN_BLOCKS 1024
+#endif
+// Dense baseline: eight-wave blocks (256 rows) when even those are at least two per block slot of
+// the chip (2 per CU x 256 CUs); every staged key step then serves twice the rows (3-6 % at
+// T = 32768).  The masked kernels keep four-wave blocks: interleaved on one box the wide form
+// was within 1 % at T = 32768 and 4 % slower at T = 2048.
+static bool wide_blocks(const Shape& s) {
+  return static_cast<int64_t>(s.N) * ((s.T + 255) / 256) >= SEA_NW8_MIN_BLOCKS;
 }
 
 bool tile_attn_supported(const Shape& s, sea_dtype dt, int32_t* rlog_out) {
@@ -1018,6 +1034,11 @@ hipError_t launch_dense_attn(const Shape& s, sea_dtype dt, const void* Q, const 
   a.N = s.N; a.H = s.H; a.T = s.T; a.U = s.T; a.KW = 0; a.rlog = 0; a.w = 1;
   a.causal = s.causal; a.c = s.scale * kLog2e;
   a.group_heads = group_heads_for(s.N, s.T);
+  if (wide_blocks(s)) {
+    const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 255) / 256)), block(512);
+    hipLaunchKernelGGL((tile_attn_kernel<0, 1, 8>), grid, block, 0, st, a);
+    return hipGetLastError();
+  }
   const dim3 grid(static_cast<uint32_t>(s.N) * ((s.T + 127) / 128)), block(256);
   hipLaunchKernelGGL((tile_attn_kernel<0, 1>), grid, block, 0, st, a);
   return hipGetLastError();
