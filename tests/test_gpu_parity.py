@@ -468,6 +468,37 @@ def test_dense_baseline_matches_library_softmax(sea, causal, pad, T):
     assert_close(to_np64(O), want, TOL["bf16"], "dense O")
 
 
+@pytest.mark.parametrize("causal,pad", [(True, 0.0), (False, 0.3), (True, 0.3)])
+def test_dense_baseline_large_launch(sea, causal, pad):
+    """A launch large enough for the baseline's 256-row blocks (256 heads x 4 blocks, the last one
+    ragged: 1000 = 3 x 256 + 232 rows), against torch.softmax in fp64 on sampled heads."""
+    wl = _wl("dense_wide", 16, 16, 1000, 32, 8, 2, causal=causal, pad_frac=pad)
+    x = synth.make_inputs(wl)
+    xd = _dev(x)
+    p = _params(sea, wl, xd["seq_len"])
+    O = torch.empty_like(xd["Q"])
+    ws = torch.empty(sea.sea_dense_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    print(f"[case] dense large launch causal{int(causal)} pad{pad}", flush=True)
+    sea.sea_dense_attn(p, xd["Q"], xd["K"], xd["V"], O, ws)
+    torch.cuda.synchronize()
+    Oc = O.cpu()
+    T = wl.T
+    sl = x["seq_len"] if x["seq_len"] is not None else torch.full((wl.B,), T, dtype=torch.int32)
+    rng = np.random.default_rng(3)
+    for bh in sorted(set([0, wl.B * wl.H - 1] + rng.choice(wl.B * wl.H, 8, replace=False).tolist())):
+        b, h = divmod(bh, wl.H)
+        Q, K, V = (x[k][b, h].to(torch.float64) for k in "QKV")
+        S = wl.scale * Q @ K.T
+        valid = torch.arange(T) < int(sl[b])
+        keep = valid[None, :].expand(T, T).clone()
+        if causal:
+            keep &= torch.tril(torch.ones(T, T, dtype=torch.bool))
+        keep[:, 0] |= ~keep.any(-1)   # rows with no admissible key: any finite row, zeroed below
+        want = torch.softmax(S.masked_fill(~keep, float("-inf")), -1) @ V
+        want = (want * valid[:, None]).numpy()
+        assert_close(to_np64(Oc[b, h])[None, None], want[None, None], TOL["bf16"], f"dense O head {bh}")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("causal", [True, False])
 def test_output_mix_matches_oracle(sea, dtype, causal):
