@@ -28,6 +28,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
 
 constexpr int kWRow = 72;  // halfwords per staged W row (128 B + 16 B pad): conflict-free b128 reads
@@ -636,14 +637,14 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   // counted four differences at a time (a byte permute spreads each sign over a byte).  The trial's
   // low half is zero in that phase, so the counts are those of the full keys.  Bits 15..0 then
   // compare whole keys.
-#define SEA_SEARCH_STEP(COUNT_BODY_)                                                             \
+#define SEA_SEARCH_STEP(COUNT_BODY_, REDUCE_)                                                    \
     /* done when every row's count of keys >= tau equals its quota */                            \
     const bool pend = (cge != nsel) && (nsel != 0u);                                             \
     if (__ballot(pend) == 0ull) break;                                                           \
     const uint32_t trial = tau | (1u << bit);                                                    \
     uint32_t cnt = 0;                                                                            \
     COUNT_BODY_                                                                                  \
-    cnt = rows_sum_u(cnt);                                                                       \
+    REDUCE_                                                                                      \
     const bool take = pend && cnt >= nsel;                                                       \
     tau = take ? trial : tau;                                                                    \
     cge = take ? cnt : cge;
@@ -654,18 +655,31 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
       hp[2 * ct] = __builtin_bit_cast(ushort2v, __builtin_amdgcn_perm(key[ct][1], key[ct][0], 0x07060302u)); \
       hp[2 * ct + 1] = __builtin_bit_cast(ushort2v, __builtin_amdgcn_perm(key[ct][3], key[ct][2], 0x07060302u)); \
     }                                                                                            \
-    /* Count of this lane's keys at or above a trial whose low half is zero. */                  \
+    /* Count of the ROW's keys at or above a trial whose low half is zero.  A byte permute turns  \
+       the signs of four differences into four bytes 0x00 / 0xff (selectors 8..11 take the sign \
+       of bytes 1, 3, 5, 7), i.e. 0 / -1 as 8-bit integers; sixteen of them are one operand of  \
+       the 8-bit matrix product, whose column is the query row (lane % 16) and whose           \
+       contraction runs over the lane's sixteen keys and the row's four lanes: against an      \
+       all -1 operand every result row is the number of the row's keys BELOW the trial, summed \
+       over the four lanes, so the counting and the cross-lane sum leave the vector pipe. */    \
     auto count_high = [&](uint32_t trial_) {                                                     \
       const uint32_t th = trial_ >> 16;                                                          \
       const ushort2v th2 = __builtin_bit_cast(ushort2v, th | (th << 16));                        \
-      uint32_t below = 0;                                                                        \
-      _Pragma("unroll") for (int pr = 0; pr < 2 * (NT_); pr += 2) {                               \
-        const uint32_t d0 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr] - th2));   \
-        const uint32_t d1 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr + 1] - th2)); \
-        /* byte selectors 8..11 give 0x00 / 0xff by the sign of bytes 1, 3, 5, 7: eight bits a key */ \
-        below += static_cast<uint32_t>(__popc(__builtin_amdgcn_perm(d1, d0, 0x0b0a0908u)));      \
+      const intx4 neg1 = {-1, -1, -1, -1};                                                       \
+      intx4 below = {0, 0, 0, 0};                                                                \
+      _Pragma("unroll") for (int q4 = 0; q4 < ((NT_) + 3) / 4; ++q4) {                            \
+        intx4 fl = {0, 0, 0, 0};                                                                 \
+        _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                           \
+          if (4 * q4 + j < (NT_)) {                                                              \
+            const int pr = 2 * (4 * q4 + j);                                                     \
+            const uint32_t d0 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr] - th2)); \
+            const uint32_t d1 = __builtin_bit_cast(uint32_t, static_cast<ushort2v>(hp[pr + 1] - th2)); \
+            fl[j] = static_cast<int>(__builtin_amdgcn_perm(d1, d0, 0x0b0a0908u));                \
+          }                                                                                      \
+        }                                                                                        \
+        below = __builtin_amdgcn_mfma_i32_16x16x64_i8(neg1, fl, below, 0, 0, 0);                 \
       }                                                                                          \
-      return 4u * static_cast<uint32_t>(NT_) - (below >> 3);                                     \
+      return 16u * static_cast<uint32_t>(NT_) - static_cast<uint32_t>(below[0]);                 \
     };                                                                                           \
     /* Bits 29..27 at once: a row whose quota of scores lies at or above 2^-15 (rows sum to 1    \
        over at most 256 columns, so nearly every row) would take all three bits, because the     \
@@ -675,7 +689,7 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     {                                                                                            \
       const bool pend = (cge != nsel) && (nsel != 0u);                                           \
       const uint32_t trial = 0xb8000000u;                                                        \
-      const uint32_t cnt = rows_sum_u(count_high(trial));                                        \
+      const uint32_t cnt = count_high(trial);                                                    \
       if (__ballot(pend && cnt < nsel) == 0ull) {                                                \
         tau = pend ? trial : tau;                                                                \
         cge = pend ? cnt : cge;                                                                  \
@@ -683,13 +697,14 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
       }                                                                                          \
     }                                                                                            \
     _Pragma("unroll 1") for (int bit = bit_top; bit >= 16; --bit) {                               \
-      SEA_SEARCH_STEP(cnt = count_high(trial);)                                                  \
+      SEA_SEARCH_STEP(cnt = count_high(trial);, )                                                \
     }                                                                                            \
   }                                                                                              \
   _Pragma("unroll 1") for (int bit = 15; bit >= 0; --bit) {                                       \
     SEA_SEARCH_STEP(                                                                             \
       _Pragma("unroll") for (int ct = 0; ct < (NT_); ++ct)                                        \
-        _Pragma("unroll") for (int i = 0; i < 4; ++i) cnt += (key[ct][i] >= trial) ? 1u : 0u;)   \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i) cnt += (key[ct][i] >= trial) ? 1u : 0u;,   \
+      cnt = rows_sum_u(cnt);)                                                                    \
   }
   const int32_t nct_wave = CAUSAL ? min(NCT, (ncols_wave + 15) >> 4) : NCT;
   if (s.k_hat == 1) {
