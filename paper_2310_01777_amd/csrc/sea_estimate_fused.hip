@@ -29,6 +29,7 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef unsigned short ushort2v __attribute__((ext_vector_type(2)));
 
 constexpr int kWRow = 72;  // halfwords per staged W row (128 B + 16 B pad): conflict-free b128 reads
@@ -246,10 +247,11 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
         // the matrix pipe: the four keys of this lane, rounded, are contraction slots 0..3 of an
         // operand whose column is the feature; against an all-ones operand every result row is the
         // sum over the wave's 16 keys, accumulated in fp32.
-        uint4 u = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), 0u, 0u};
-        const uint4 one = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
-        const floatx4 rs = mfma16(__builtin_bit_cast(bf16x8, one), __builtin_bit_cast(bf16x8, u),
-                                  floatx4{0.f, 0.f, 0.f, 0.f});
+        // (the four-slot product: exactly the lane's four keys, no zero padding of the operand)
+        const uint2 u = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        const uint2 one = {0x3f803f80u, 0x3f803f80u};
+        const floatx4 rs = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
+            __builtin_bit_cast(shortx4, one), __builtin_bit_cast(shortx4, u), floatx4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
         if (lg == 0) tpart[wid * m + slot] = rs[0];
       }
     }
