@@ -602,24 +602,26 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   }
   {
     const float r = rows_sum(rsum);
-    const float inv = r > 0.f ? 1.f / r : 0.f;
+    // The normalised scores are kept NEGATED from here on: the bit pattern of -x (x >= +0) is
+    // 0x80000000 | bits(x), which is the selection key itself, so the keys cost no instruction.
+    const float ninv = r > 0.f ? -1.f / r : -0.f;
 #pragma unroll
     for (int ct = 0; ct < NCT; ++ct)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) acc[ct][i] *= inv;
+      for (int i = 0; i < 4; ++i) acc[ct][i] *= ninv;
     if (A_hat && trow < s.T) {
       float* out = A_hat + (head * s.T + trow) * s.K;
       if ((s.K & 3) == 0) {
 #pragma unroll
         for (int ct = 0; ct < NCT; ++ct)
           if (ct * 16 + 4 * lg < s.K)
-            *reinterpret_cast<float4*>(out + ct * 16 + 4 * lg) = make_float4(acc[ct][0], acc[ct][1], acc[ct][2], acc[ct][3]);
+            *reinterpret_cast<float4*>(out + ct * 16 + 4 * lg) = make_float4(-acc[ct][0], -acc[ct][1], -acc[ct][2], -acc[ct][3]);
       } else {
 #pragma unroll
         for (int ct = 0; ct < NCT; ++ct)
 #pragma unroll
           for (int i = 0; i < 4; ++i)
-            if (ct * 16 + 4 * lg + i < s.K) out[ct * 16 + 4 * lg + i] = acc[ct][i];
+            if (ct * 16 + 4 * lg + i < s.K) out[ct * 16 + 4 * lg + i] = -acc[ct][i];
       }
     }
   }
@@ -637,11 +639,11 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   for (int ct = 0; ct < NCT; ++ct) {
     if (ct < ct_free) {  // every column of the tile is a candidate of every row
 #pragma unroll
-      for (int i = 0; i < 4; ++i) key[ct][i] = __float_as_uint(acc[ct][i] + 0.0f) | 0x80000000u;
+      for (int i = 0; i < 4; ++i) key[ct][i] = __float_as_uint(acc[ct][i]);
     } else {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        key[ct][i] = ct * 16 + i <= e ? (__float_as_uint(acc[ct][i] + 0.0f) | 0x80000000u) : 0x40000000u;
+        key[ct][i] = ct * 16 + i <= e ? __float_as_uint(acc[ct][i]) : 0x40000000u;
     }
   }
   // The compare-and-count loop runs over the tiles that hold candidates of this wave's rows only
