@@ -447,12 +447,42 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
 
   // ---- phi(Q) of this wave's 16 rows, as contraction fragments ----
   bf16x8 afrag[MC];
+  // causal: phi(K) of the same 16 rows (the keys of the rows' own column inside the wave), taken in
+  // the same pass over W's fragments, so that each is read from LDS once for both projections; a
+  // key's features need no row shift and are rounded and packed tile by tile
+  bf16x8 kfrag[CAUSAL ? MC : 1];
   {
     float nx = sumsq8(x0) + sumsq8(x1);
     nx += __shfl_xor(nx, 16, kWave);
     nx += __shfl_xor(nx, 32, kWave);
     floatx4 dots[2 * MC];
-    project_dots<MC>(Ws, x0, x1, lr, lg, dots);
+    if (CAUSAL) {
+      float ny = sumsq8(y0) + sumsq8(y1);
+      ny += __shfl_xor(ny, 16, kWave);
+      ny += __shfl_xor(ny, 32, kWave);
+      const float kbias = c_norm * ny;
+#pragma unroll
+      for (int kc = 0; kc < MC; ++kc) {
+        float lo[4], hi[4];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int ft = 2 * kc + h;
+          const uint16_t* w = &Ws[(ft * 16 + lr) * kWRow + 8 * lg];
+          const bf16x8 w0 = *reinterpret_cast<const bf16x8*>(w), w1 = *reinterpret_cast<const bf16x8*>(w + 32);
+          floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+          acc = mfma16(w0, x0, acc);
+          dots[ft] = mfma16(w1, x1, acc);
+          floatx4 ka = {0.f, 0.f, 0.f, 0.f};
+          ka = mfma16(w0, y0, ka);
+          ka = mfma16(w1, y1, ka);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) (h == 0 ? lo : hi)[i] = __builtin_amdgcn_exp2f(fmaf(c_dot, ka[i], -kbias));
+        }
+        kfrag[kc] = pack8(lo, hi);
+      }
+    } else {
+      project_dots<MC>(Ws, x0, x1, lr, lg, dots);
+    }
     float dmax = -INFINITY;
 #pragma unroll
     for (int ft = 0; ft < 2 * MC; ++ft)
@@ -477,7 +507,6 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
       afrag[kc] = pack8(lo, hi);
     }
   }
-  __builtin_amdgcn_sched_barrier(0);  // keep the two projections' temporaries from overlapping
   // From here on every product is taken with the query rows as accumulator COLUMNS: lane l % 16 is
   // the query row, so a row of A_hat lives in the four lanes l % 16 + 16 q (16 values each per 64
   // columns) and every per-row reduction is two row-swap steps.
@@ -486,22 +515,9 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     // the row's own column: sum over keys j <= t of that column of phi(q_t) . phi(k_j).  Those
     // keys are the wave's own 16 rows (S = phi(Q) phi(K_own)^T with a lower-triangular, same-column
     // mask) and, for columns wider than 16, the 16-key tiles of the column before the wave.
-    float ny = sumsq8(y0) + sumsq8(y1);
-    ny += __shfl_xor(ny, 16, kWave);
-    ny += __shfl_xor(ny, 32, kWave);
-    floatx4 arg[2 * MC];
-    project<MC>(Ws, y0, y1, lr, lg, c_dot, c_norm * ny, arg);
     floatx4 sd = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kc = 0; kc < MC; ++kc) {
-      float lo[4], hi[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        lo[i] = __builtin_amdgcn_exp2f(arg[2 * kc][i]);
-        hi[i] = __builtin_amdgcn_exp2f(arg[2 * kc + 1][i]);
-      }
-      sd = mfma16(pack8(lo, hi), afrag[kc], sd);  // rows = keys 4 lg + i, col = query lr
-    }
+    for (int kc = 0; kc < MC; ++kc) sd = mfma16(kfrag[kc], afrag[kc], sd);  // rows = keys 4 lg + i, col = query lr
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int rk = 4 * lg + i;  // key row within the wave; the query row within the wave is lr
