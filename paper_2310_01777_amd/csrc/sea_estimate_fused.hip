@@ -215,44 +215,72 @@ __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
     bias[i] = act[i] ? c_norm * __shfl(nx, (lane & 48) | (4 * lg + i), kWave) : INFINITY;
   }
   uint16_t* sh = state + head * static_cast<int64_t>(s.K) * m;
+  // Feature tiles are taken four at a time, so that the cross-lane part of the column sums can be
+  // shared: a row swap of two tiles' sums leaves, after one addition, tile a's pair sums in the even
+  // lane groups and tile b's in the odd ones; a half swap of two such registers and one more addition
+  // leave the full sums of the four tiles in lane groups 0..3 -- three swaps and three additions for
+  // four tiles, the same order of additions as summing each tile on its own, and one LDS store.
+  static_assert((2 * MC) % 4 == 0, "feature tiles in groups of four");
+  // slot of this lane's feature in a fragment-ordered row, for the tile its lane group ends up with
+  const int slot_lane = 8 * (lr >> 2) + (lr & 3);
 #pragma unroll
-  for (int ft = 0; ft < 2 * MC; ++ft) {
-    const uint16_t* wr = &Ws[(ft * 16 + lr) * kWRow + 8 * lg];
-    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-    acc = mfma16(x0, *reinterpret_cast<const bf16x8*>(wr), acc);
-    acc = mfma16(x1, *reinterpret_cast<const bf16x8*>(wr + 32), acc);
-    float v[4];
+  for (int ft0 = 0; ft0 < 2 * MC; ft0 += 4) {
+    float sum4[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int i = 0; i < 4; ++i) v[i] = __builtin_amdgcn_exp2f(fmaf(c_dot, acc[i], -bias[i]));
-    // where feature 16 ft + lr sits in a fragment-ordered row
-    const int slot = 32 * (ft >> 1) + 8 * (lr >> 2) + 4 * (ft & 1) + (lr & 3);
-    if (w == 1) {
+    for (int q = 0; q < 4; ++q) {
+      const int ft = ft0 + q;
+      const uint16_t* wr = &Ws[(ft * 16 + lr) * kWRow + 8 * lg];
+      floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+      acc = mfma16(x0, *reinterpret_cast<const bf16x8*>(wr), acc);
+      acc = mfma16(x1, *reinterpret_cast<const bf16x8*>(wr + 32), acc);
+      float v[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (r0 + 4 * lg + i < s.T) sh[static_cast<int64_t>(r0 + 4 * lg + i) * m + slot] = f32_to_bf16(v[i]);
-    } else if (w == 2) {
+      for (int i = 0; i < 4; ++i) v[i] = __builtin_amdgcn_exp2f(fmaf(c_dot, acc[i], -bias[i]));
+      // where feature 16 ft + lr sits in a fragment-ordered row
+      const int slot = 32 * (ft >> 1) + 4 * (ft & 1) + slot_lane;
+      if (w == 1) {
 #pragma unroll
-      for (int i = 0; i < 4; i += 2)
-        if (r0 + 4 * lg + i < s.T)
-          sh[static_cast<int64_t>((r0 + 4 * lg + i) >> 1) * m + slot] = f32_to_bf16(v[i] + v[i + 1]);
-    } else {
-      float sum = (v[0] + v[1]) + (v[2] + v[3]);  // the four keys share a column
-      if (w >= 8) sum = xor16_sum(sum);
-      if (w >= 16) sum = xor32_sum(sum);
-      const bool writer = w == 4 ? true : (w == 8 ? (lg & 1) == 0 : lg == 0);
-      const int pw = w == 4 ? lg : (w == 8 ? lg >> 1 : 0);
-      if (writer) part[(wid * kPartsWave + pw) * m + slot] = sum;
-      if (w > 16 && pref) {
-        // The same tile sum over the ROUNDED features (what a causal row's own-column term uses), on
-        // the matrix pipe: the four keys of this lane, rounded, are contraction slots 0..3 of an
-        // operand whose column is the feature; against an all-ones operand every result row is the
-        // sum over the wave's 16 keys, accumulated in fp32.
-        // (the four-slot product: exactly the lane's four keys, no zero padding of the operand)
-        const uint2 u = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-        const uint2 one = {0x3f803f80u, 0x3f803f80u};
-        const floatx4 rs = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
-            __builtin_bit_cast(shortx4, one), __builtin_bit_cast(shortx4, u), floatx4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-        if (lg == 0) tpart[wid * m + slot] = rs[0];
+        for (int i = 0; i < 4; ++i)
+          if (r0 + 4 * lg + i < s.T) sh[static_cast<int64_t>(r0 + 4 * lg + i) * m + slot] = f32_to_bf16(v[i]);
+      } else if (w == 2) {
+#pragma unroll
+        for (int i = 0; i < 4; i += 2)
+          if (r0 + 4 * lg + i < s.T)
+            sh[static_cast<int64_t>((r0 + 4 * lg + i) >> 1) * m + slot] = f32_to_bf16(v[i] + v[i + 1]);
+      } else {
+        sum4[q] = (v[0] + v[1]) + (v[2] + v[3]);  // the four keys share a column
+        if (w == 4) part[(wid * kPartsWave + lg) * m + slot] = sum4[q];
+        if (w > 16 && pref) {
+          // The same tile sum over the ROUNDED features (what a causal row's own-column term uses), on
+          // the matrix pipe: the four keys of this lane, rounded, are the contraction slots of an
+          // operand whose column is the feature; against an all-ones operand every result row is the
+          // sum over the wave's 16 keys, accumulated in fp32.
+          // (the four-slot product: exactly the lane's four keys, no zero padding of the operand)
+          const uint2 u = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+          const uint2 one = {0x3f803f80u, 0x3f803f80u};
+          const floatx4 rs = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(
+              __builtin_bit_cast(shortx4, one), __builtin_bit_cast(shortx4, u), floatx4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+          if (lg == 0) tpart[wid * m + slot] = rs[0];
+        }
+      }
+    }
+    if (w >= 8) {
+      // lane groups (0, 1, 2, 3) after the row swaps: pair sums of tiles (a, b, a, b) for keys
+      // 0-7 in groups 0, 1 and keys 8-15 in groups 2, 3
+      const auto ab = __builtin_amdgcn_permlane16_swap(__float_as_uint(sum4[0]), __float_as_uint(sum4[1]), false, false);
+      const auto cd = __builtin_amdgcn_permlane16_swap(__float_as_uint(sum4[2]), __float_as_uint(sum4[3]), false, false);
+      const float s_ab = __uint_as_float(ab[0]) + __uint_as_float(ab[1]);
+      const float s_cd = __uint_as_float(cd[0]) + __uint_as_float(cd[1]);
+      if (w == 8) {
+        // two column parts per wave: group lg holds tile (lg & 1) of its pair, keys 8 (lg >> 1) ..
+        const int tq = lg & 1, pw = lg >> 1;
+        part[(wid * kPartsWave + pw) * m + 32 * (ft0 >> 1) + 4 * tq + slot_lane] = s_ab;
+        part[(wid * kPartsWave + pw) * m + 32 * ((ft0 + 2) >> 1) + 4 * tq + slot_lane] = s_cd;
+      } else {
+        // full sums: lane group lg ends up with tile ft0 + lg
+        const auto t = __builtin_amdgcn_permlane32_swap(__float_as_uint(s_ab), __float_as_uint(s_cd), false, false);
+        const float tot = __uint_as_float(t[0]) + __uint_as_float(t[1]);
+        part[wid * kPartsWave * m + 32 * ((ft0 + lg) >> 1) + 4 * (lg & 1) + slot_lane] = tot;
       }
     }
   }
