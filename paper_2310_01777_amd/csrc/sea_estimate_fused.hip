@@ -846,24 +846,36 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   // combine their parts; the lane of the first row stores them as vectors.
   const int32_t kw = (s.K + 31) >> 5;
   constexpr int kWords = NCT / 2;
-  uint32_t words[kWords];
+  if constexpr (kWords % 4 == 0) {
+    // Four words at a time: a row swap of two words' parts and an OR leave word a's halves in the
+    // even lane groups and word b's in the odd ones; a half swap of two such registers and an OR
+    // leave the four finished words in lane groups 0..3 (three swaps for four words instead of
+    // eight), and every lane stores the word of its group.
+    uint32_t* mrow = mbits + (head * s.T + min(trow, s.T - 1)) * kw;
 #pragma unroll
-  for (int j = 0; j < kWords; ++j)
-    words[j] = rows_or_u((nib[2 * j] << (4 * lg)) | (nib[2 * j + 1] << (16 + 4 * lg)));
-  if (trow >= s.T || lg != 0) return;
-  uint32_t* mrow = mbits + (head * s.T + trow) * kw;
-  if (kw == kWords) {
-    if constexpr (kWords == 2) {
+    for (int j = 0; j < kWords; j += 4) {
+      uint32_t pw[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) pw[q] = (nib[2 * (j + q)] << (4 * lg)) | (nib[2 * (j + q) + 1] << (16 + 4 * lg));
+      const auto ab = __builtin_amdgcn_permlane16_swap(pw[0], pw[1], false, false);
+      const auto cd = __builtin_amdgcn_permlane16_swap(pw[2], pw[3], false, false);
+      const auto t = __builtin_amdgcn_permlane32_swap(ab[0] | ab[1], cd[0] | cd[1], false, false);
+      if (trow < s.T && j + lg < kw) mrow[j + lg] = t[0] | t[1];
+    }
+  } else {
+    uint32_t words[kWords];
+#pragma unroll
+    for (int j = 0; j < kWords; ++j)
+      words[j] = rows_or_u((nib[2 * j] << (4 * lg)) | (nib[2 * j + 1] << (16 + 4 * lg)));
+    if (trow >= s.T || lg != 0) return;
+    uint32_t* mrow = mbits + (head * s.T + trow) * kw;
+    if (kw == kWords) {
       *reinterpret_cast<uint2*>(mrow) = make_uint2(words[0], words[1]);
     } else {
 #pragma unroll
-      for (int j = 0; j < kWords; j += 4)
-        *reinterpret_cast<uint4*>(mrow + j) = make_uint4(words[j], words[j + 1], words[j + 2], words[j + 3]);
+      for (int j = 0; j < kWords; ++j)
+        if (j < kw) mrow[j] = words[j];
     }
-  } else {
-#pragma unroll
-    for (int j = 0; j < kWords; ++j)
-      if (j < kw) mrow[j] = words[j];
   }
 }
 
