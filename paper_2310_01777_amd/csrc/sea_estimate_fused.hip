@@ -673,9 +673,10 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
 
   // ---- per-row top-k^ on the normalised scores, in registers (Sec. 3.1 "Grouped Top-k^
   // Selection", per-query grouping).  A row lives in four lanes, 4 NCT scores each.  The k^-th
-  // largest score is found by a bitwise search on order-preserving integer keys; every lane counts
-  // its own scores and the four counts meet in two row-swap steps.  Scores are in [0, 1], so the
-  // key's two top bits are known and the search starts below them.
+  // largest score is found by a bitwise search on order-preserving integer keys (the bit patterns
+  // of the negated scores); the counts of a step are taken over the whole row by an 8-bit integer
+  // matrix product (high halves) or per lane with two row-swap steps (low halves).  Scores are in
+  // [0, 1], so the key's two top bits are known and the search starts below them.
   const uint32_t nsel = static_cast<uint32_t>(min(s.k_hat, ncnd));
   uint32_t tau = 0x80000000u, cge = static_cast<uint32_t>(ncnd);
   uint32_t key[NCT][4];
@@ -694,8 +695,9 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   // (causal: the leading ones), in even steps so that a handful of loop bodies covers all cases.
   // Bits 29..16 are searched on the keys' high halves, two keys per register: both halves of
   // hp - trial (16-bit wrap-around differences; candidates and trial lie in [0x8000, 0xc000),
-  // non-candidates are 0x4000) have bit 15 set exactly for keys below the trial, and those bits are
-  // counted four differences at a time (a byte permute spreads each sign over a byte).  The trial's
+  // non-candidates are 0x4000) have bit 15 set exactly for keys below the trial; a byte permute
+  // spreads each sign over a byte, four differences at a time, and the matrix product adds the bytes
+  // up.  The trial's
   // low half is zero in that phase, so the counts are those of the full keys.  Bits 15..0 then
   // compare whole keys.
 #define SEA_SEARCH_STEP(COUNT_BODY_, REDUCE_)                                                    \
