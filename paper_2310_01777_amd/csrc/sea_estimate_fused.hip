@@ -151,20 +151,10 @@ __device__ __forceinline__ void project(const uint16_t* Ws, bf16x8 x0, bf16x8 x1
 //
 // Here the projection is taken with the keys as accumulator rows, C[key][feature] = X W^T: a lane
 // then holds, per 16-feature tile, feature 16 ft + lr of the four keys 4 lg + i, so a column sum
-// is three adds in the lane plus at most two cross-lane steps per tile, and no feature array is
-// kept in registers.  Sums meet in LDS (one m-vector per wave and column part) and leave as
+// is three adds in the lane plus at most two cross-lane steps, which four tiles share (three swaps
+// and three additions for four tiles), and no feature array is kept in registers.  Sums meet in LDS (one m-vector per wave and column part) and leave as
 // coalesced bf16 rows.
 // ------------------------------------------------------------------------------------------
-__device__ __forceinline__ float xor32_sum(float x) {
-  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-// x + the value of the lane 16 further (or back) in the same half of the wave
-__device__ __forceinline__ float xor16_sum(float x) {
-  const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
 template <int MC, int WLOG>
 __global__ __launch_bounds__(WLOG > 6 ? 512 : 256) void key_state_kernel(
     Shape s, const uint16_t* __restrict__ K, const uint16_t* __restrict__ W, uint16_t* __restrict__ state,
