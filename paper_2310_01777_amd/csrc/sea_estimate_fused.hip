@@ -401,6 +401,9 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
   constexpr int kStageHalfwords = kColStage * kSRow;
   constexpr int kSmemHalfwords = m * kWRow > 2 * kStageHalfwords ? m * kWRow : 2 * kStageHalfwords;
   __shared__ __attribute__((aligned(16))) uint16_t smem[kSmemHalfwords];
+  // causal, columns wider than 16 keys: the three prefix planes of each wave's tile (requested with
+  // the wave's rows, parked here, read as operand rows once phi(Q) is ready)
+  __shared__ __attribute__((aligned(16))) uint16_t planes_s[(CAUSAL && WLOG >= 5) ? 4 * 3 * m : 8];
   uint16_t* const Ws = smem;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -459,7 +462,27 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     y0 = *reinterpret_cast<const bf16x8*>(Xk + 8 * lg);
     y1 = *reinterpret_cast<const bf16x8*>(Xk + 32 + 8 * lg);
   }
+  // Prefix planes of the wave's tile inside its 128-key block (its column, if narrower): 3 m
+  // halfwords, contiguous; lane l takes 16-byte pieces l and l + 64.
+  bool tile_planes = false;
+  if (CAUSAL && WLOG >= 5) {
+    const int tl = min(wl, 7) - 4;  // log2(tiles per prefix group)
+    tile_planes = r0 < s.T && ((r0 >> 4) & ((1 << tl) - 1)) != 0;  // wave-uniform
+  }
+  uint4 preg0 = {0u, 0u, 0u, 0u}, preg1 = preg0;
+  if (tile_planes) {
+    const uint4* psrc = reinterpret_cast<const uint4*>(pref + (head * (s.T >> 4) + (r0 >> 4)) * 3 * m);
+    constexpr int kPieces = 3 * m / 8;
+    if (lane < kPieces) preg0 = psrc[lane];
+    if (lane + 64 < kPieces) preg1 = psrc[lane + 64];
+  }
   stage_w(W, Ws, m, tid);
+  if (tile_planes) {
+    constexpr int kPieces = 3 * m / 8;
+    uint4* pdst = reinterpret_cast<uint4*>(&planes_s[wid * 3 * m]);
+    if (lane < kPieces) pdst[lane] = preg0;
+    if (lane + 64 < kPieces) pdst[lane + 64] = preg1;
+  }
   if (nstages > 0) { SEA_SFETCH(0); }  // parked in LDS after the projections
   __syncthreads();
 
@@ -548,9 +571,8 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     // in-wave ones.  Two levels: tiles before this one inside its 128-key block (its column, if
     // narrower), and, for columns wider than that, the column's blocks before this one.
     if (WLOG >= 5 && r0 < s.T) {
-      const int tl = min(wl, 7) - 4;  // log2(tiles per prefix group)
-      if (((r0 >> 4) & ((1 << tl) - 1)) != 0) {
-        const uint16_t* src = pref + ((head * (s.T >> 4) + (r0 >> 4)) * 3 + min(lr, 2)) * m + 8 * lg;
+      if (tile_planes) {
+        const uint16_t* src = &planes_s[(wid * 3 + min(lr, 2)) * m + 8 * lg];
 #pragma unroll
         for (int kc = 0; kc < MC; ++kc) {
           uint4 f = *reinterpret_cast<const uint4*>(src + 32 * kc);
