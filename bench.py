@@ -251,6 +251,21 @@ def measure(torch, sea, synth, wl, steps, warmup, detail):
                              "algorithmic_flops": 2.0 * wl.d * pairs, "pairs": pairs,
                              "note": "fp64 products of the selected (query, key) pairs only, against the fp64 matrix "
                                      "peak; the fp32 products of P V (as many again) run beside them"}
+    elif sparse_ms > 0 and sea.sea_attention_path(p) == 3:
+        # the tiled kernel on one mask bit per (row, key) (per-row width geometry): the walk of the dense
+        # causal kernel, every 32 x 32 tile at or below the diagonal issued
+        fp32 = wl.dtype != "bf16"
+        peak3 = FP64_PEAK_TFLOPS if fp32 else MFMA_BF16_PEAK_TFLOPS
+        fl3 = (2.0 if fp32 else 4.0) * wl.d * pairs
+        tiles_row = (wl.T + 31) // 32
+        issued_pairs = float(N) * 1024.0 * tiles_row * (tiles_row + 1) / 2
+        ach = fl3 / (sparse_ms * 1e-3) / 1e12
+        kernels["sparse"] = {"kernel": ("tile_attn_f32_kernel" if fp32 else "tile_attn_kernel") + " (one mask bit per (row, key))",
+                             "bound": "mfma", "achieved": ach, "peak": peak3, "unit": "TFLOP/s", "frac": ach / peak3,
+                             "avg_kernel_ms": sparse_ms, "algorithmic_flops": fl3, "pairs": pairs,
+                             "issued_flops_upper_bound": (2.0 if fp32 else 4.0) * wl.d * issued_pairs,
+                             "note": "achieved counts the selected (query, key) pairs only; the upper bound of the issued "
+                                     "flops counts every 32 x 32 tile at or below the diagonal (padding ignored)"}
     elif sparse_ms > 0:
         # per-row list kernel: the bytes that must cross HBM once are Q, K, V, O and the lists; the
         # repeated K / V row gathers of the pairs are served by the caches
@@ -291,12 +306,26 @@ def measure(torch, sea, synth, wl, steps, warmup, detail):
                         "pair_tflops": fl / (cms * 1e-3) / 1e12 if cms > 0 else 0.0,
                         "frac_of_bf16_mfma_peak": fl / (cms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS if cms > 0 else 0.0,
                         "binned_pairs_per_s": float(N) * wl.T * (wl.T + 1) / 2 / (cms * 1e-3) if cms > 0 else 0.0})
+            if cms > 0:
+                kernels["contract"] = {"kernel": "rw_tiles_mfma_kernel", "bound": "mfma", "achieved": fl / (cms * 1e-3) / 1e12,
+                                       "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                       "frac": fl / (cms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "avg_kernel_ms": cms,
+                                       "algorithmic_flops": fl,
+                                       "note": "2 m flops per (row, key) pair at or below the diagonal; the time includes "
+                                               "binning every product into its column in LDS"}
         elif wl.m <= 128:
             # tile form: phi(K) phi(Q)^T below the diagonal on the fp64 matrix cores, 2 m flops per (row, key) pair
             fl = float(N) * wl.T * (wl.T + 1) / 2 * 2 * wl.m
             est.update({"rows_kernel_ms": cms, "fp64_flops": fl,
                         "fp64_tflops": fl / (cms * 1e-3) / 1e12 if cms > 0 else 0.0,
                         "frac_of_fp64_matrix_peak": fl / (cms * 1e-3) / 1e12 / FP64_PEAK_TFLOPS if cms > 0 else 0.0})
+            if cms > 0:
+                kernels["contract"] = {"kernel": "rw_tiles_kernel", "bound": "mfma", "achieved": fl / (cms * 1e-3) / 1e12,
+                                       "peak": FP64_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                       "frac": fl / (cms * 1e-3) / 1e12 / FP64_PEAK_TFLOPS, "avg_kernel_ms": cms,
+                                       "algorithmic_flops": fl,
+                                       "note": "2 m flops per (row, key) pair at or below the diagonal on the fp64 matrix "
+                                               "cores; the time includes binning every product into its column in LDS"}
         else:
             gbytes = float(nrows) * (wl.K + 1) * wl.m * 8
             est.update({"rows_kernel_ms": cms, "gathered_bytes": gbytes,
