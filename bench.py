@@ -228,7 +228,7 @@ def measure(torch, sea, synth, wl, steps, warmup, detail):
     N = wl.B * wl.H
     tiled = sea.sea_attention_path(p) == 1
     wcol = wl.T // wl.K
-    fused = tiled and wl.grouping == 0 and wl.m in (64, 128, 256) and wl.K <= 256 and (wcol & (wcol - 1)) == 0
+    fused = tiled and wl.m in (64, 128, 256) and wl.K <= 256 and (wcol & (wcol - 1)) == 0
     kernels = {}
     # sparse attention: 4 d flops per selected (query, key) pair
     sparse_ms = avg.get("sparse", 0.0)
@@ -287,6 +287,14 @@ def measure(torch, sea, synth, wl, steps, warmup, detail):
                                  "algorithmic_flops": fl,
                                  "note": "dense count; about half of a causal contraction lies above the diagonal "
                                          "and is skipped" if name == "contract" and wl.causal else "dense count"}
+    if wl.grouping == 1 and wl.geometry == 0 and avg.get("topk_mask", 0.0) > 0:
+        # causal-per-batch selection: every time step's H x K slab of fp32 scores is read once, mask bits written
+        gms = avg["topk_mask"]
+        gbytes = float(nrows) * wl.K * 4 + float(nrows) * ((wl.K + 31) // 32) * 4
+        kernels["topk_mask"] = {"kernel": "topk_group_kernel", "bound": "hbm", "achieved": gbytes / (gms * 1e-3) / 1e9,
+                                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbytes / (gms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                                "avg_kernel_ms": gms, "algorithmic_bytes": gbytes,
+                                "note": "reads A_hat (fp32) once and writes the mask bits"}
     est_ms = sum(avg.get(k, 0.0) for k in ("features", "state", "contract"))
     est_flops = 2.0 * proj + contr
     peak = MFMA_BF16_PEAK_TFLOPS if wl.dtype == "bf16" else FP64_PEAK_TFLOPS
