@@ -222,6 +222,7 @@ PLAIN_CASES = [
     (synth.get_workload("c2"), (0, 4)),          # full size, all rows of the first heads
     (synth.get_workload("c5"), (0, 8)),
     (synth.get_workload("c3"), (0, 2)),
+    (synth.get_workload("c4_T32768"), (0, 1)),   # the headline workload: 128-key columns, key budget
     # per-row width geometry: phi(q) and every phi(k_j) are rounded once, the same bound applies
     (_wl("plain_row_width", 2, 3, 320, 128, 40, 9, geometry=1), None),
     (_wl("plain_row_width_m256_pad", 1, 2, 700, 256, 96, 12, k_budget=48, pad_frac=0.3, geometry=1), None),
@@ -256,7 +257,10 @@ def test_bf16_forward_against_the_plain_definition(sea, wl, heads):
     bad = ~same & ~(gaps < PLAIN_GAP)
     assert not bad.any(), f"{bad.sum()} rows differ with a plain-oracle gap >= 2^-6 (largest {gaps[~same].max():.3g})"
     frac = float((~same).mean())
-    assert frac <= 0.02, f"{wl.name}: {(~same).sum()} of {same.size} rows select differently from the plain oracle"
+    # c4 at T = 32768 (columns of 128 keys, scores closer together): the oracle's own two modes select
+    # differently on 762 of the 32768 rows of head 0 (2.33 %), the GPU on 763; everywhere else <= 1.7 %
+    cap = 0.03 if wl.name == "c4_T32768" else 0.02
+    assert frac <= cap, f"{wl.name}: {(~same).sum()} of {same.size} rows select differently from the plain oracle"
     assert np.array_equal(pick(g["idx"].numpy())[same], pick(o["idx"])[same])
     Og, Oo = pick(to_np64(g["O"])).copy(), pick(o["O"]).copy()
     Og[~same] = 0.0
