@@ -140,6 +140,12 @@ def _ptr(t: Optional[torch.Tensor], dtype=None, numel=None, name="tensor"):
     return t.data_ptr()
 
 
+def _nbytes(t: Optional[torch.Tensor]) -> int:
+    """Size of a workspace tensor; no tensor = 0 bytes, which the library answers with SEA_EWORKSPACE
+    wherever it needs any."""
+    return 0 if t is None else t.numel() * t.element_size()
+
+
 def _stream(stream) -> int:
     if stream is None:
         return torch.cuda.current_stream().cuda_stream
@@ -184,7 +190,7 @@ def sea_estimate(p: SeaParams, Q, K, W, A_hat, workspace, stream=None):
                              _ptr(W, p.torch_dtype, p.m * p.d, "W"),
                              _ptr(A_hat, torch.float32, n * p.K, "A_hat"),
                              _ptr(workspace, None, None, "workspace"),
-                             workspace.numel() * workspace.element_size(), _stream(stream)),
+                             _nbytes(workspace), _stream(stream)),
            "sea_estimate")
 
 
@@ -224,7 +230,7 @@ def sea_flatcsr(p: SeaParams, idx, cnt, row_stride, crow, col, workspace, stream
                             _ptr(crow, torch.int64, p.B * p.T + 1, "crow"),
                             _ptr(col, torch.int32, None, "col"), col.numel(),
                             _ptr(workspace, None, None, "workspace"),
-                            workspace.numel() * workspace.element_size(), _stream(stream)),
+                            _nbytes(workspace), _stream(stream)),
            "sea_flatcsr")
 
 
@@ -263,7 +269,7 @@ def sea_mask_attn(p: SeaParams, Q, K, V, mhat, O, workspace=None, stream=None):
                               _ptr(mhat, torch.int32, n * ((p.K + 31) // 32), "mhat"),
                               _ptr(O, p.torch_dtype, n * p.d, "O"),
                               _ptr(workspace, None, None, "workspace"),
-                              0 if workspace is None else workspace.numel() * workspace.element_size(),
+                              _nbytes(workspace),
                               _stream(stream)),
            "sea_mask_attn")
 
@@ -284,7 +290,7 @@ def sea_forward(p: SeaParams, Q, K, V, W, O, A_hat=None, sel=None, idx=None, cnt
                             _ptr(cnt, torch.int32, n, "cnt"),
                             _ptr(mhat, torch.int32, n * ((p.K + 31) // 32), "mhat"),
                             _ptr(workspace, None, None, "workspace"),
-                            0 if workspace is None else workspace.numel() * workspace.element_size(),
+                            _nbytes(workspace),
                             _stream(stream)),
            "sea_forward")
 
@@ -336,7 +342,7 @@ def sea_decoder_estimate(p: SeaParams, weights: dict, Q, K, V, W, A_hat, workspa
                                      _ptr(A_hat, torch.float32, n * p.K, "A_hat"),
                                      _ptr(s_mix, torch.float32, n, "s_mix"), _ptr(s_prob, torch.float32, n, "s_prob"),
                                      _ptr(workspace, None, None, "workspace"),
-                                     0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                     _nbytes(workspace),
                                      _stream(stream)),
            "sea_decoder_estimate")
 
@@ -349,7 +355,7 @@ def sea_decoder_forward(p: SeaParams, weights: dict, Q, K, V, W, O, workspace, A
                                     _ptr(W, p.torch_dtype, p.m * p.d, "W"), _ptr(O, p.torch_dtype, n * p.d, "O"),
                                     _ptr(A_hat, torch.float32, n * p.K, "A_hat"),
                                     _ptr(workspace, None, None, "workspace"),
-                                    0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                    _nbytes(workspace),
                                     _stream(stream)),
            "sea_decoder_forward")
 
@@ -367,7 +373,7 @@ def sea_dense_attn(p: SeaParams, Q, K, V, O, workspace=None, stream=None):
                                _ptr(V, p.torch_dtype, n * p.d, "V"),
                                _ptr(O, p.torch_dtype, n * p.d, "O"),
                                _ptr(workspace, None, None, "workspace"),
-                               0 if workspace is None else workspace.numel() * workspace.element_size(),
+                               _nbytes(workspace),
                                _stream(stream)),
            "sea_dense_attn")
 
@@ -387,7 +393,7 @@ def sea_output_mix(p: SeaParams, C, V, s_mix, O, workspace, s_prob=None, A_hat=N
                                _ptr(s_mix, torch.float32, n, "s_mix"),
                                _ptr(O, p.torch_dtype, n * p.d, "O"),
                                _ptr(workspace, None, None, "workspace"),
-                               workspace.numel() * workspace.element_size(), _stream(stream)),
+                               _nbytes(workspace), _stream(stream)),
            "sea_output_mix")
 
 
