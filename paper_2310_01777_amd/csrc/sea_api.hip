@@ -378,7 +378,11 @@ int forward_stages(const sea_params* p, const void* Q, const void* K, const void
       if (e != hipSuccess) return fail_hip(e);
       if (need_lists) e = launch_topk_mask(s, A_hat, sel_opt, idx_opt, cnt_opt, nullptr, st);
     } else {
-      e = launch_estimate_bf16(s, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
+      // causal-per-batch selection reads a row's scores only up to its last candidate column: when
+      // the scores go to scratch and nothing else reads them, the estimator writes no further
+      Shape se = s;
+      se.cand_only = (s.grouping == 1 && !A_hat_opt && !need_lists) ? 1 : 0;
+      e = launch_estimate_bf16(se, static_cast<const uint16_t*>(Q), static_cast<const uint16_t*>(K),
                                static_cast<const uint16_t*>(W), A_hat, est_ws, st);
       if (e != hipSuccess) return fail_hip(e);
       e = launch_topk_mask(s, A_hat, sel_opt, idx_opt, cnt_opt, mbits, st);

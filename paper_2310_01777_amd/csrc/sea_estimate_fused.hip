@@ -668,9 +668,11 @@ __global__ __launch_bounds__(256, 3) void estimate_rows_kernel(Shape s, const ui
     if (A_hat && trow < s.T) {
       float* out = A_hat + (head * s.T + trow) * s.K;
       if ((s.K & 3) == 0) {
+        // a scratch A_hat read only by the grouped selection needs no zeros past a row's candidates
+        const int32_t cend = s.cand_only ? min(s.K, ncnd) : s.K;
 #pragma unroll
         for (int ct = 0; ct < NCT; ++ct)
-          if (ct * 16 + 4 * lg < s.K)
+          if (ct * 16 + 4 * lg < cend)
             *reinterpret_cast<float4*>(out + ct * 16 + 4 * lg) = make_float4(-acc[ct][0], -acc[ct][1], -acc[ct][2], -acc[ct][3]);
       } else {
 #pragma unroll

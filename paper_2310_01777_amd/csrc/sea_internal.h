@@ -25,6 +25,8 @@ struct Shape {
   int32_t grouping;    // 0 per-query top-k^, 1 causal-per-batch
   int32_t sel_stride;  // columns one row can select: k_hat, or min(K, H k_hat) when grouped
   int32_t geometry;    // 0 fixed key buckets, 1 a causal row spreads its K columns over its own t + 1 keys
+  int32_t cand_only;   // fused estimator: store A_hat only where a row has candidate columns (scratch A_hat
+                       // that only the causal-per-batch selection reads); the rest stays unwritten
   float scale;
   const int32_t* seq_len;  // device [B] or nullptr
 };

@@ -413,22 +413,40 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
   // head and column of the thread's first entry; a group further on is 1024 entries further on
   const int32_t adv_h = 1024 / s.K, adv_c = 1024 - adv_h * s.K;  // block-uniform
   int32_t gh = (tid * 4) / s.K, gc = tid * 4 - gh * s.K;
+  if ((s.K & 3) == 0) {
+    // the four entries of a group lie in one head: one 128-bit load.  All loads of the thread are
+    // issued before the first is used: a group with nothing to read (past the slab, or past the
+    // step's last candidate column) reads the first entries of the slab instead (always inside the
+    // buffer), and its values are discarded, so no load sits behind a branch and none waits for
+    // another.
+    const float* slab = A_hat + (static_cast<int64_t>(b) * s.H * s.T + t) * s.K;  // head 0 of the step
+    const int64_t hstride = static_cast<int64_t>(s.T) * s.K;
+    // element offset of the thread's group inside the slab, stepped from group to group (one
+    // 64-bit multiplication per thread instead of one per group)
+    int64_t off = gh * hstride + gc;
+    const int64_t adv_off = adv_h * hstride + adv_c, wrap_off = hstride - s.K;  // block-uniform
+    float4 f[VPT / 4];
+    int32_t c0s[VPT / 4];
 #pragma unroll
-  for (int gi = 0; gi < VPT / 4; ++gi) {
-    const int32_t e0 = (gi * 256 + tid) * 4;
-    if ((s.K & 3) == 0) {
-      // the four entries lie in one head: one 128-bit load
-      const int32_t h = gh, c0 = gc;
-      gh += adv_h;
+    for (int gi = 0; gi < VPT / 4; ++gi) {
+      const int32_t e0 = (gi * 256 + tid) * 4;
+      const bool ld = e0 < HK && gc < ncand;
+      c0s[gi] = ld ? gc : s.K;  // s.K: no candidate in this group
+      f[gi] = *reinterpret_cast<const float4*>(slab + (ld ? off : 0));
       gc += adv_c;
-      if (gc >= s.K) { gc -= s.K; ++gh; }
-      float4 f = {0.f, 0.f, 0.f, 0.f};
-      if (e0 < HK && c0 < ncand)
-        f = *reinterpret_cast<const float4*>(A_hat + ((static_cast<int64_t>(b) * s.H + h) * s.T + t) * s.K + c0);
-      const float fv[4] = {f.x, f.y, f.z, f.w};
+      off += adv_off;
+      if (gc >= s.K) { gc -= s.K; off += wrap_off; }
+    }
 #pragma unroll
-      for (int q = 0; q < 4; ++q) key[4 * gi + q] = (e0 < HK && is_cand(c0 + q)) ? ordered_key(fv[q]) : 0u;
-    } else {
+    for (int gi = 0; gi < VPT / 4; ++gi) {
+      const float fv[4] = {f[gi].x, f[gi].y, f[gi].z, f[gi].w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q) key[4 * gi + q] = is_cand(c0s[gi] + q) ? ordered_key(fv[q]) : 0u;
+    }
+  } else {
+#pragma unroll
+    for (int gi = 0; gi < VPT / 4; ++gi) {
+      const int32_t e0 = (gi * 256 + tid) * 4;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int32_t e = e0 + q;
@@ -470,7 +488,8 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
       __syncthreads();
 #pragma unroll
       for (int v = 0; v < VPT; ++v)
-        if (key[v] != 0u && (key[v] & pmask) == tau) atomicAdd(&hist[(key[v] >> shift) & (nb - 1u)], 1u);
+        // (a non-candidate's key is 0 and tau carries bit 31, so it never matches the prefix)
+        if ((key[v] & pmask) == tau) atomicAdd(&hist[(key[v] >> shift) & (nb - 1u)], 1u);
       __syncthreads();
       // thread tid owns `per` consecutive bins; keys in higher bins = total - inclusive prefix
       const uint32_t per = nb >> 8;  // 8, 8, 1
@@ -547,6 +566,12 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
       }
     }
     if (words_from_regs) {
+      // head and column of the thread's groups, stepped as when they were read
+      // (32 | K and H K <= 16384, so a head's H T K / 32 words index with 32 bits)
+      int32_t oh = (tid * 4) / s.K, oc = tid * 4 - oh * s.K;
+      const int32_t hwords = s.T * kw;  // mask words of one head
+      int32_t ow = oh * hwords;         // first word of the thread's head, inside the batch element
+      uint32_t* mstep = mbits + (static_cast<int64_t>(b) * s.H * s.T + t) * kw;  // head 0, this step
 #pragma unroll
       for (int gi = 0; gi < VPT / 4; ++gi) {
         const int32_t e0 = (gi * 256 + tid) * 4;
@@ -557,10 +582,10 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
         word |= static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(word), 0xB1, 0xf, 0xf, false));
         word |= static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(word), 0x4E, 0xf, 0xf, false));
         word |= static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(word), 0x141, 0xf, 0xf, false));
-        if ((lane & 7) == 0 && e0 < HK) {
-          const int32_t h = e0 / s.K, c0 = e0 - h * s.K;
-          mbits[((static_cast<int64_t>(b) * s.H + h) * s.T + t) * kw + (c0 >> 5)] = word;
-        }
+        if ((lane & 7) == 0 && e0 < HK) mstep[ow + (oc >> 5)] = word;
+        ow += adv_h * hwords;
+        oc += adv_c;
+        if (oc >= s.K) { oc -= s.K; ow += hwords; }
       }
     }
   } else {

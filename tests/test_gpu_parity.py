@@ -346,6 +346,16 @@ def test_causal_per_batch_grouping(sea, wl):
     Oo[~keep] = 0.0
     assert_close(Og, Oo, tol, "O (end to end)")
     print(f"    steps differing at near-ties: {(~same).sum()} / {same.size}", flush=True)
+    # the call that asks for O and the packed mask only (scores in scratch, written up to each row's
+    # last candidate column and nowhere else): same bits, same output, on a workspace full of NaN
+    ws = sea.alloc_workspace(p)
+    ws.view(torch.uint8).fill_(0xff)
+    O2 = torch.empty_like(xd["Q"])
+    mh = torch.empty_like(g["mhat"], device="cuda")
+    sea.sea_forward(p, xd["Q"], xd["K"], xd["V"], xd["W"], O2, None, None, None, None, ws, mhat=mh)
+    torch.cuda.synchronize()
+    assert torch.equal(mh.cpu(), g["mhat"])
+    assert torch.equal(O2.cpu(), g["O"])
 
 
 @pytest.mark.parametrize("case", [(1, 2, 512, 64, 64, 9, 0, True), (2, 2, 512, 128, 32, 5, 0, False),
