@@ -62,14 +62,16 @@ __global__ __launch_bounds__(256) void chunk_sums_kernel(Shape s, const T* __res
   const int32_t b = static_cast<int32_t>(head / s.H);
   const int32_t len = s.seq_len ? min(max(s.seq_len[b], 0), s.T) : s.T;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // All eight rows are requested before the first is added: a row past the sequence reads the last
+  // row of the head instead and is not added, so no load sits behind a branch.
+  float v[8][8];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) load8(V + (head * s.T + min(r0 + r, s.T - 1)) * kHeadDim + dg * 8, v[r]);
 #pragma unroll
   for (int r = 0; r < 8; ++r) {
-    if (r0 + r < len) {
-      float v[8];
-      load8(V + (head * s.T + r0 + r) * kHeadDim + dg * 8, v);
+    const bool keep = r0 + r < len;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) acc[i] += v[i];
-    }
+    for (int i = 0; i < 8; ++i) acc[i] += keep ? v[r][i] : 0.f;
   }
 #pragma unroll
   for (int i = 0; i < 8; ++i) red[slot][dg * 8 + i] = acc[i];
@@ -101,11 +103,13 @@ __global__ __launch_bounds__(256) void mix_causal_kernel(Shape s, const T* __res
   // the thread's 8 rows x 8 dimensions of V, kept for the second sweep
   float v[8][8];
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  // all eight rows requested before the first is used (rows past the sequence read the head's last
+  // row and are cleared afterwards)
+#pragma unroll
+  for (int r = 0; r < 8; ++r) load8(V + (head * s.T + min(r0 + r, s.T - 1)) * kHeadDim + dg * 8, v[r]);
 #pragma unroll
   for (int r = 0; r < 8; ++r) {
-    if (r0 + r < len) {
-      load8(V + (head * s.T + r0 + r) * kHeadDim + dg * 8, v[r]);
-    } else {
+    if (r0 + r >= len) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) v[r][i] = 0.f;
     }
@@ -141,27 +145,35 @@ __global__ __launch_bounds__(256) void mix_causal_kernel(Shape s, const T* __res
   double run[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) run[i] = offs[slot][dg * 8 + i];
+  // four rows at a time: their C rows and scalers are requested together (clamped to the head's
+  // last row where the chunk overruns it), then mixed and stored
 #pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    const int32_t t = r0 + r;
-    if (t >= s.T) break;
-    const int64_t e = (head * s.T + t) * kHeadDim + dg * 8;
-    float o[8];
-    if (t >= len) {
+  for (int r4 = 0; r4 < 8; r4 += 4) {
+    float c[4][8], sm[4], sp[4];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) o[i] = 0.f;
-    } else {
-      float c[8];
-      load8(C + e, c);
-      const float sm = s_mix[head * s.T + t], sp = s_prob ? s_prob[head * s.T + t] : 1.f;
-      const double inv = 1.0 / static_cast<double>(t + 1);
+    for (int r = 0; r < 4; ++r) {
+      const int64_t rowc = head * s.T + min(r0 + r4 + r, s.T - 1);
+      load8(C + rowc * kHeadDim + dg * 8, c[r]);
+      sm[r] = s_mix[rowc];
+      sp[r] = s_prob ? s_prob[rowc] : 1.f;
+    }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        run[i] += v[r][i];
-        o[i] = static_cast<float>(static_cast<double>(sm) * sp * c[i] + (1.0 - sm) * (run[i] * inv));
+    for (int r = 0; r < 4; ++r) {
+      const int32_t t = r0 + r4 + r;
+      if (t < s.T) {
+        const int64_t e = (head * s.T + t) * kHeadDim + dg * 8;
+        float o[8];
+        const bool live = t < len;
+        const double inv = 1.0 / static_cast<double>(t + 1);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          run[i] += v[r4 + r][i];
+          const float x = static_cast<float>(static_cast<double>(sm[r]) * sp[r] * c[r][i] + (1.0 - sm[r]) * (run[i] * inv));
+          o[i] = live ? x : 0.f;
+        }
+        store8(O + e, o);
       }
     }
-    store8(O + e, o);
   }
 }
 

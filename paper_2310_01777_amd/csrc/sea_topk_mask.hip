@@ -104,23 +104,36 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_mask_kernel(
 
   int n_sel = 0;
   if (FROMBITS) {
+    // the row's mask words, all requested before the first is used (a slot past K re-reads the
+    // last word; its bit is not looked at)
+    uint32_t mw[SLOTS];
+#pragma unroll
+    for (int q = 0; q < SLOTS; ++q) mw[q] = mrow[min(q * kWave + lane, s.K - 1) >> 5];
 #pragma unroll
     for (int q = 0; q < SLOTS; ++q) {
       const int32_t c = q * kWave + lane;
-      const bool take = c < s.K && ((mrow[c >> 5] >> (c & 31)) & 1u);
+      const bool take = c < s.K && ((mw[q] >> (c & 31)) & 1u);
       const uint64_t tk = __ballot(take);
       if (take) sh_sel[wid][n_sel + lanes_below(tk, lane)] = c;
       n_sel += popc64(tk);
     }
   } else {
     uint32_t key[SLOTS];
+    // every slot's score is requested before the first is used: a slot past the candidates reads
+    // column 0 instead (its value is discarded), so no load sits behind a branch
+    float a[SLOTS];
+  #pragma unroll
+    for (int q = 0; q < SLOTS; ++q) {
+      const int32_t c = q * kWave + lane;
+      a[q] = A_hat[row * s.K + (c < ncand ? c : 0)];
+    }
   #pragma unroll
     for (int q = 0; q < SLOTS; ++q) {
       const int32_t c = q * kWave + lane;
       bool cand = c < ncand;  // c < ncand <= K
       // a row at least K keys wide has a key in every column (the row is wave-uniform)
       if (ROWW && Tw < s.K) cand = cand && block_start(c + 1, Tw, s.K) > block_start(c, Tw, s.K);
-      key[q] = cand ? ordered_key(A_hat[row * s.K + c]) : 0u;
+      key[q] = cand ? ordered_key(a[q]) : 0u;
     }
     // largest tau with #{key >= tau} >= n  ==  the n-th largest key
     uint32_t tau = 0;
@@ -268,12 +281,18 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void topk_bits_kernel(Shape 
 
   uint32_t key[NCT][4];
   const float* arow = A_hat + row * s.K;
+  // all tiles of the row are requested before the first is used (a tile past K re-reads the row's
+  // first columns; its values are discarded), so no load sits behind a branch
+  float4 vt[NCT];
 #pragma unroll
   for (int ct = 0; ct < NCT; ++ct) {
     const int32_t c0 = 16 * ct + 4 * lg;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (c0 < s.K) v = *reinterpret_cast<const float4*>(arow + c0);
-    const float a[4] = {v.x, v.y, v.z, v.w};
+    vt[ct] = *reinterpret_cast<const float4*>(arow + (c0 < s.K ? c0 : 0));
+  }
+#pragma unroll
+  for (int ct = 0; ct < NCT; ++ct) {
+    const int32_t c0 = 16 * ct + 4 * lg;
+    const float a[4] = {vt[ct].x, vt[ct].y, vt[ct].z, vt[ct].w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int32_t c = c0 + i;
