@@ -264,8 +264,10 @@ __global__ __launch_bounds__(64 * kLinWaves) void dec_linattn_kernel(Shape s, in
   auto fetch = [&](int32_t t0, bool want_q, bool want_k, bool want_kt) {
 #pragma unroll
     for (int r = 0; r < kPer; ++r) {
-      const int id = tid + r * kThreads;
-      if (id >= 3 * kFrags) break;
+      // a slot with nothing to fetch (past the last fragment, or a tile this pass does not use)
+      // reads the head's first 16 bytes instead: every load is unconditional, so all of a thread's
+      // loads are in flight together
+      const int id = min(tid + r * kThreads, 3 * kFrags - 1);
       const int which = id / kFrags, fid = id % kFrags;
       const int x = fid >> 6, fl = fid & 63, flr = fl & 15, flg = fl >> 4;
       const uint16_t* src;
@@ -280,7 +282,7 @@ __global__ __launch_bounds__(64 * kLinWaves) void dec_linattn_kernel(Shape s, in
         src = KTh + static_cast<int64_t>(f) * Tp + t0 + 8 * flg;
         want = want_kt;
       }
-      if (want) held[r] = *reinterpret_cast<const uint4*>(src);
+      held[r] = *reinterpret_cast<const uint4*>(want ? src : Qh);
     }
   };
   auto park = [&]() {
@@ -923,9 +925,9 @@ __global__ __launch_bounds__(256) void dec_linear_kernel(ConvArgs a, int32_t til
   for (int32_t id = tid; id < ksteps * 8 * 64; id += 256) {
     const int32_t fl = id & 63, nt = (id >> 6) & 7, ks = id >> 9;
     const int32_t co = cout0 + 16 * nt + (fl & 15), k0 = 32 * ks + 8 * (fl >> 4);
-    uint4 v = make_uint4(0u, 0u, 0u, 0u);
-    if (co < a.Cout && k0 < a.Cin) v = *reinterpret_cast<const uint4*>(a.w + static_cast<int64_t>(co) * a.Cin + k0);
-    wlin[id] = v;
+    // unconditional load from a clamped address, cleared where the slab overruns the matrix
+    const uint4 v = *reinterpret_cast<const uint4*>(a.w + static_cast<int64_t>(min(co, a.Cout - 1)) * a.Cin + min(k0, a.Cin - 8));
+    wlin[id] = (co < a.Cout && k0 < a.Cin) ? v : make_uint4(0u, 0u, 0u, 0u);
   }
   __syncthreads();
   const int64_t ntile = (nrows + 31) / 32;
@@ -943,10 +945,17 @@ __global__ __launch_bounds__(256) void dec_linear_kernel(ConvArgs a, int32_t til
         const int64_t q = r / a.H, h = r - q * a.H, b = q / a.T, t = q - b * a.T;
         r = (b * a.H + h) * a.T + t;
       }
-      const uint16_t* row = a.in + r * a.Cin + 8 * lg;
+      // a lane whose piece lies past the row's channels reads the row's last piece instead and
+      // clears it, so no load sits behind a per-lane branch and all of a tile's loads are in flight
+      // together
+      const uint16_t* row = a.in + r * a.Cin;
 #pragma unroll
       for (int ks = 0; ks < kLinSteps; ++ks)
-        if (ks < ksteps) nx[ks][mt] = (32 * ks + 8 * lg < a.Cin) ? load8(row + 32 * ks) : zero8();
+        if (ks < ksteps) {
+          const int32_t k0 = 32 * ks + 8 * lg;
+          const bf16x8 x = load8(row + min(k0, a.Cin - 8));
+          nx[ks][mt] = k0 < a.Cin ? x : zero8();
+        }
     }
   };
   if (tile < tile_end) request(tile);
@@ -969,6 +978,23 @@ __global__ __launch_bounds__(256) void dec_linear_kernel(ConvArgs a, int32_t til
             acc[nt][1] = mfma16(wf, xf[ks][1], acc[nt][1]);
           }
         }
+      }
+    }
+    // mode 1: where the lane's two rows (b, t, h) land in the channels-last image, and whether they
+    // lie inside their sequence -- once per tile, not once per channel tile (two 64-bit divisions
+    // and a load each)
+    int64_t orow[2] = {0, 0};
+    bool live[2] = {true, true};
+    if (a.mode != 0) {
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt) {
+        const int64_t pp = min(tile * 32 + 16 * mt + lr, nrows - 1);
+        const int64_t q = pp / a.H;
+        const int32_t h = static_cast<int32_t>(pp - q * a.H);
+        const int32_t b = static_cast<int32_t>(q / a.T), t = static_cast<int32_t>(q - static_cast<int64_t>(b) * a.T);
+        const int32_t len = a.seq_len ? min(max(a.seq_len[b], 0), a.T) : a.T;
+        live[mt] = t < len;
+        orow[mt] = (static_cast<int64_t>(b) * a.T + t) * a.Wd * a.C + h * kCh;
       }
     }
     // epilogue: tile (nt, mt): rows = output channels cout0 + 16 nt + 4 lg + i, column = row lr of tile mt
@@ -995,13 +1021,8 @@ __global__ __launch_bounds__(256) void dec_linear_kernel(ConvArgs a, int32_t til
           *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) + pp * a.Cout + co) = pk;
         } else {
           // row pp = (b, t, h); outputs co .. co + 3 = compressed column co / 4, extra channels 0..3
-          const int64_t q = pp / a.H;
-          const int32_t h = static_cast<int32_t>(pp - q * a.H);
-          const int32_t b = static_cast<int32_t>(q / a.T), t = static_cast<int32_t>(q - static_cast<int64_t>(b) * a.T);
-          const int32_t len = a.seq_len ? min(max(a.seq_len[b], 0), a.T) : a.T;
-          if (t >= len) pk = make_uint2(0u, 0u);
-          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) +
-                                    ((static_cast<int64_t>(b) * a.T + t) * a.Wd + (co >> 2)) * a.C + h * kCh) = pk;
+          if (!live[mt]) pk = make_uint2(0u, 0u);
+          *reinterpret_cast<uint2*>(static_cast<uint16_t*>(a.out) + orow[mt] + static_cast<int64_t>(co >> 2) * a.C) = pk;
         }
       }
     }
