@@ -444,23 +444,28 @@ __global__ __launch_bounds__(256) void topk_group_kernel(Shape s, const float* _
     // 64-bit multiplication per thread instead of one per group)
     int64_t off = gh * hstride + gc;
     const int64_t adv_off = adv_h * hstride + adv_c, wrap_off = hstride - s.K;  // block-uniform
-    float4 f[VPT / 4];
-    int32_t c0s[VPT / 4];
+    // at most eight loads (32 registers) in flight: the largest slabs take two rounds
+    constexpr int kBatch = VPT / 4 < 8 ? VPT / 4 : 8;
 #pragma unroll
-    for (int gi = 0; gi < VPT / 4; ++gi) {
-      const int32_t e0 = (gi * 256 + tid) * 4;
-      const bool ld = e0 < HK && gc < ncand;
-      c0s[gi] = ld ? gc : s.K;  // s.K: no candidate in this group
-      f[gi] = *reinterpret_cast<const float4*>(slab + (ld ? off : 0));
-      gc += adv_c;
-      off += adv_off;
-      if (gc >= s.K) { gc -= s.K; off += wrap_off; }
-    }
+    for (int g0 = 0; g0 < VPT / 4; g0 += kBatch) {
+      float4 f[kBatch];
+      int32_t c0s[kBatch];
 #pragma unroll
-    for (int gi = 0; gi < VPT / 4; ++gi) {
-      const float fv[4] = {f[gi].x, f[gi].y, f[gi].z, f[gi].w};
+      for (int gj = 0; gj < kBatch; ++gj) {
+        const int32_t e0 = ((g0 + gj) * 256 + tid) * 4;
+        const bool ld = e0 < HK && gc < ncand;
+        c0s[gj] = ld ? gc : s.K;  // s.K: no candidate in this group
+        f[gj] = *reinterpret_cast<const float4*>(slab + (ld ? off : 0));
+        gc += adv_c;
+        off += adv_off;
+        if (gc >= s.K) { gc -= s.K; off += wrap_off; }
+      }
 #pragma unroll
-      for (int q = 0; q < 4; ++q) key[4 * gi + q] = is_cand(c0s[gi] + q) ? ordered_key(fv[q]) : 0u;
+      for (int gj = 0; gj < kBatch; ++gj) {
+        const float fv[4] = {f[gj].x, f[gj].y, f[gj].z, f[gj].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) key[4 * (g0 + gj) + q] = is_cand(c0s[gj] + q) ? ordered_key(fv[q]) : 0u;
+      }
     }
   } else {
 #pragma unroll
