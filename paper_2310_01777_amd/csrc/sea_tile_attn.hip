@@ -447,14 +447,21 @@ __global__ __launch_bounds__(kBucketRows) void bucket_count_kernel(const uint32_
   if (row < T) {
     const uint32_t* mw = mbits + (head * T + row) * KW;
     int n = 0;  // a row has at most `slots` entries: further bits of a foreign mask are ignored
-    for (int32_t j = 0; j < KW; ++j) {
-      uint32_t word = mw[j];
+    auto take = [&](uint32_t word, int32_t j) {
       while (word != 0u && n < slots) {
         const int bit = __ffs(static_cast<int>(word)) - 1;
         word &= word - 1u;
         atomicAdd(&hist[32 * j + bit], 1);
         ++n;
       }
+    };
+    if ((KW & 3) == 0 && (reinterpret_cast<uintptr_t>(mbits) & 15) == 0) {  // rows of whole, aligned 16-byte pieces: one load per four words
+      for (int32_t j = 0; j < KW; j += 4) {
+        const uint4 w4 = *reinterpret_cast<const uint4*>(mw + j);
+        take(w4.x, j); take(w4.y, j + 1); take(w4.z, j + 2); take(w4.w, j + 3);
+      }
+    } else {
+      for (int32_t j = 0; j < KW; ++j) take(mw[j], j);
     }
   }
   __syncthreads();
@@ -520,8 +527,7 @@ __global__ __launch_bounds__(kBucketRows) void bucket_scatter_kernel(const uint3
   int n = 0;
   if (row < T) {
     const uint32_t* mw = mbits + (head * T + row) * KW;
-    for (int32_t j = 0; j < KW; ++j) {
-      uint32_t word = mw[j];
+    auto take = [&](uint32_t word, int32_t j) {
       while (word != 0u && n < slots) {
         const int bit = __ffs(static_cast<int>(word)) - 1;
         word &= word - 1u;
@@ -532,6 +538,14 @@ __global__ __launch_bounds__(kBucketRows) void bucket_scatter_kernel(const uint3
           if (q == n) { cols[q] = col; ranks[q] = rank; }
         ++n;
       }
+    };
+    if ((KW & 3) == 0 && (reinterpret_cast<uintptr_t>(mbits) & 15) == 0) {  // rows of whole, aligned 16-byte pieces: one load per four words
+      for (int32_t j = 0; j < KW; j += 4) {
+        const uint4 w4 = *reinterpret_cast<const uint4*>(mw + j);
+        take(w4.x, j); take(w4.y, j + 1); take(w4.z, j + 2); take(w4.w, j + 3);
+      }
+    } else {
+      for (int32_t j = 0; j < KW; ++j) take(mw[j], j);
     }
   }
   __syncthreads();
