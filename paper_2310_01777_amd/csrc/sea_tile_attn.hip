@@ -279,6 +279,15 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void tile_attn_kernel(TileArgs a)
       mw1 = mn1;
       if (step + 1 < nsteps) fetch_words(step + 1, mn0, mn1);
     }
+    // With two or more keys per column the (at most 32) columns of a 64-key step lie in one mask
+    // word: it is read once per step, unconditionally (every row of the block has its words in
+    // LDS), ahead of both sub-chunks instead of in front of each one's first fragment read.
+    constexpr bool kStepWord = !DENSE && !STREAM && RLOG >= 1;
+    uint32_t wstep = 0u;
+    if (kStepWord) {
+      wstep = mrow[((step * kChunk) >> (RLOG < 5 ? RLOG : a.rlog)) >> 5];
+      wstep = row_active ? wstep : 0u;
+    }
 #pragma unroll
     for (int sc = 0; sc < 2; ++sc) {
       const int32_t u0 = ubase + step * kChunk + 32 * sc;
@@ -287,7 +296,7 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void tile_attn_kernel(TileArgs a)
       uint32_t bits = 0xffffffffu;
       if (!DENSE) {
         const int32_t col0 = u0 >> (RLOG < 5 ? RLOG : a.rlog);  // first column of the sub-chunk
-        const uint32_t word = STREAM ? (sc == 0 ? mw0 : mw1) : (row_active ? mrow[col0 >> 5] : 0u);
+        const uint32_t word = STREAM ? (sc == 0 ? mw0 : mw1) : (kStepWord ? wstep : (row_active ? mrow[col0 >> 5] : 0u));
         bits = word >> (col0 & 31);
         constexpr uint32_t ncol = RLOG >= 5 ? 1u : (32u >> RLOG);
         constexpr uint32_t cmask = ncol >= 32 ? 0xffffffffu : ((1u << ncol) - 1u);
