@@ -347,6 +347,30 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void tile_attn_kernel(TileArgs a)
           y[i] = okb ? fmaf(sv[i], a.c, -m_ref) : -INFINITY;
         }
       }
+      // The V^T fragments of the sub-chunk are requested here, into the registers the raw scores
+      // just left, so that their LDS latency lies under the softmax arithmetic below instead of in
+      // front of the products that use them.  The LDS transpose read hands lane i of a 16-lane
+      // group element i % 4 of the 8 bytes that lanes 4 e + i / 4 (e = 0..3) of the group point at:
+      // with lane r pointing at dims 4 (r % 4) .. + 3 of key r / 4, lane i receives dim i of keys
+      // 0..3 -- four consecutive keys of one dimension.  Lanes 8..15 of a group point at rows 2, 3
+      // (mod 4), whose halves are stored exchanged.
+      // (With the per-key mask words of MODE 3 in registers as well there is no room for that:
+      // there the fragments are requested just before their products.)
+      bf16x8 av[2][2];
+      auto request_v = [&]() {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+          const uint16_t* Vr = &Vs[stage][(32 * sc + 4 * g + ((ql & 15) >> 2)) * kVRow +
+                                          32 * (mt ^ ((ql >> 3) & 1)) + (ql & 16) + 4 * (ql & 3)];
+#pragma unroll
+          for (int c2 = 0; c2 < 2; ++c2) {
+            const bf16x4 lo = lds_transpose4(Vr + (16 * c2) * kVRow);
+            const bf16x4 hi = lds_transpose4(Vr + (16 * c2 + 8) * kVRow);
+            av[mt][c2] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          }
+        }
+      };
+      if (!STREAM) request_v();
       float ymax = fmaxf(fmaxf(y[0], y[1]), y[2]);
 #pragma unroll
       for (int i = 3; i < 15; i += 2) ymax = fmaxf(fmaxf(ymax, y[i]), y[i + 1]);
@@ -386,23 +410,13 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void tile_attn_kernel(TileArgs a)
         const bf16x4 hi = __builtin_shufflevector(h[4 * c2 + 2], h[4 * c2 + 3], 0, 1, 2, 3);
         bp[c2] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       }
-      // O^T += V^T P^T; V^T fragments in the key order of the P registers.  The LDS transpose
-      // read hands lane i of a 16-lane group element i % 4 of the 8 bytes that lanes 4 e + i / 4
-      // (e = 0..3) of the group point at: with lane r pointing at dims 4 (r % 4) .. + 3 of key
-      // r / 4, lane i receives dim i of keys 0..3 -- four consecutive keys of one dimension.
-      // Lanes 8..15 of a group point at rows 2, 3 (mod 4), whose halves are stored exchanged.
+      // O^T += V^T P^T; V^T fragments in the key order of the P registers
+      if (STREAM) request_v();
 #pragma unroll
-      for (int mt = 0; mt < 2; ++mt) {
-        const uint16_t* Vr = &Vs[stage][(32 * sc + 4 * g + ((ql & 15) >> 2)) * kVRow +
-                                        32 * (mt ^ ((ql >> 3) & 1)) + (ql & 16) + 4 * (ql & 3)];
+      for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int c2 = 0; c2 < 2; ++c2) {
-          const bf16x4 lo = lds_transpose4(Vr + (16 * c2) * kVRow);
-          const bf16x4 hi = lds_transpose4(Vr + (16 * c2 + 8) * kVRow);
-          const bf16x8 av = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bp[c2], oacc[mt], 0, 0, 0);
-        }
-      }
+        for (int c2 = 0; c2 < 2; ++c2)
+          oacc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[mt][c2], bp[c2], oacc[mt], 0, 0, 0);
     }
     if (step + 1 < nsteps) SEA_PARK(stage ^ 1);
     __syncthreads();
