@@ -91,7 +91,10 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void sparse_attn_bf16_kernel
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const int32_t p = k0 + u * 8 + g;
-      int32_t j = (p < n) ? irow[p] - kl.base : -1;
+      // the index is read unconditionally (a slot past the list re-reads its last entry and is
+      // then discarded): a load behind `p < n` would be waited for before the next slot's is issued
+      int32_t j = irow[min(p, n - 1)] - kl.base;
+      j = (p < n) ? j : -1;
       ok[u] = static_cast<uint32_t>(j) < static_cast<uint32_t>(s.T);
       j = ok[u] ? j : 0;
       kv[u] = *reinterpret_cast<const uint4*>(Kh + static_cast<int64_t>(j) * kHeadDim + c8 * 8);
@@ -187,7 +190,10 @@ __global__ __launch_bounds__(kWavesPerBlock* kWave) void sparse_attn_f32_kernel(
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const int32_t p = k0 + u * 4 + g;
-      int32_t j = (p < n) ? irow[p] - kl.base : -1;
+      // the index is read unconditionally (a slot past the list re-reads its last entry and is
+      // then discarded): a load behind `p < n` would be waited for before the next slot's is issued
+      int32_t j = irow[min(p, n - 1)] - kl.base;
+      j = (p < n) ? j : -1;
       ok[u] = static_cast<uint32_t>(j) < static_cast<uint32_t>(s.T);
       j = ok[u] ? j : 0;
       kv[u] = *reinterpret_cast<const float4*>(Kh + static_cast<int64_t>(j) * kHeadDim + c16 * 4);
