@@ -212,6 +212,8 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void tile_attn_kernel(TileArgs a)
     j_free = a.causal ? min(q0, len - 1) : len - 1;
   }
   const int32_t my_jmax = a.causal ? min(t, len - 1) : len - 1;
+  // compact keys this row may attend: those of the block's range whose position is <= my_jmax
+  const int32_t my_ucount = min(ulim, compact_count(row_active ? my_jmax : -1, a.rlog, a.w));
   const int32_t nsteps = (u_end_wg - ubase + kChunk - 1) / kChunk;
 
   // staging roles: 16-byte part tid & 7 of the K and V rows (tid >> 3) and, with four waves,
@@ -339,10 +341,18 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void tile_attn_kernel(TileArgs a)
         for (int i = 0; i < 16; ++i) {
           const int32_t slot = 8 * (i >> 2) + 4 * g + (i & 3);
           uint32_t okb = DENSE ? (row_active ? 1u : 0u) : ((bits >> (RLOG >= 5 ? 0 : (slot >> RLOG))) & 1u);
+          // positions ascend with the compact index, so "position <= the row's last admissible
+          // key" is "index below the row's count of such keys", taken once per row.  The variants
+          // with one key per column walk this per-element path in every sub-chunk and have no
+          // register left for that count: they compare positions.
           if (boundary) {
-            const int32_t u = u0 + slot;
-            const int32_t pu = pos_of(min(u, a.U - 1), a.rlog, a.w);
-            okb &= (u < ulim ? 1u : 0u) & (pu <= my_jmax ? 1u : 0u);
+            if (kGroup > 1) {
+              okb &= (u0 + slot < my_ucount) ? 1u : 0u;
+            } else {
+              const int32_t u = u0 + slot;
+              const int32_t pu = pos_of(min(u, a.U - 1), a.rlog, a.w);
+              okb &= (u < ulim ? 1u : 0u) & (pu <= my_jmax ? 1u : 0u);
+            }
           }
           y[i] = okb ? fmaf(sv[i], a.c, -m_ref) : -INFINITY;
         }
