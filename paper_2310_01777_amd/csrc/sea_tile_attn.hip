@@ -93,6 +93,14 @@ __device__ __forceinline__ int32_t compact_count(int32_t jmax, int32_t rlog, int
   return col * r + inside;
 }
 
+// raw buffer resource, word 3: 32-bit data format, no swizzle; loads past num_records return zero
+constexpr int kBufferFlags = 0x00020000;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, static_cast<int>(byte_off), 0, 0);
+  return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
 constexpr int kChunk = 64;   // keys staged in LDS per step (two 32-key MFMA sub-chunks)
 constexpr int kKRow = 72;    // halfwords per staged K row: 128 B + 16 B pad, conflict-free b128 reads
 constexpr int kVRow = 64;    // halfwords per staged V row: no padding; the 64-byte halves of rows 2, 3 (mod 4)
@@ -232,8 +240,11 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void tile_attn_kernel(TileArgs a)
   const uint32_t off_step = linear ? static_cast<uint32_t>((kChunk >> a.rlog) * a.w) * row_bytes : 0u;
   uint32_t offa = static_cast<uint32_t>(pos_of(ubase + srow, a.rlog, a.w)) * row_bytes + part_bytes;
   uint32_t offb = static_cast<uint32_t>(pos_of(ubase + srow + 32, a.rlog, a.w)) * row_bytes + part_bytes;
-  const char* Kb = reinterpret_cast<const char*>(Kh);
-  const char* Vb = reinterpret_cast<const char*>(Vh);
+  // The head's keys and values as buffer resources (base in scalar registers, 32-bit byte offset
+  // per lane): a staging load then needs no 64-bit address arithmetic on the vector pipe.
+  const uint32_t head_bytes = static_cast<uint32_t>(a.T) * row_bytes;
+  const __amdgpu_buffer_rsrc_t Kres = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(Kh), 0, head_bytes, kBufferFlags);
+  const __amdgpu_buffer_rsrc_t Vres = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(Vh), 0, head_bytes, kBufferFlags);
 #define SEA_SLOT_OFF(slot_, step_)                                                                   \
   (static_cast<uint32_t>(pos_of(min(ubase + (step_) * kChunk + (slot_), a.U - 1), a.rlog, a.w)) * row_bytes + part_bytes)
 #define SEA_FETCH(step_)                                                                             \
@@ -242,10 +253,10 @@ __global__ __launch_bounds__(64 * NW, 16 / NW) void tile_attn_kernel(TileArgs a)
       offa = SEA_SLOT_OFF(srow, step_);                                                              \
       if (NW == 4) offb = SEA_SLOT_OFF(srow + 32, step_);                                            \
     }                                                                                                \
-    kreg0 = *reinterpret_cast<const uint4*>(Kb + min(offa, off_max));                                \
-    if (NW == 4) kreg1 = *reinterpret_cast<const uint4*>(Kb + min(offb, off_max));                   \
-    vreg0 = *reinterpret_cast<const uint4*>(Vb + min(offa, off_max));                                \
-    if (NW == 4) vreg1 = *reinterpret_cast<const uint4*>(Vb + min(offb, off_max));                   \
+    kreg0 = buffer_load16(Kres, min(offa, off_max));                                                 \
+    if (NW == 4) kreg1 = buffer_load16(Kres, min(offb, off_max));                                    \
+    vreg0 = buffer_load16(Vres, min(offa, off_max));                                                 \
+    if (NW == 4) vreg1 = buffer_load16(Vres, min(offb, off_max));                                    \
     offa += off_step; offb += off_step;                                                              \
   } while (0)
 #define SEA_PARK(stage_)                                                                             \
